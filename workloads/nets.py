@@ -1,0 +1,297 @@
+"""Layer lists of the five synthetic early-exit networks and their random weights.
+
+The architectures are the public ResNet-18 / ResNet-50 / MobileNetV2 layer
+shapes (plus a three-stage toy net); weights are seeded random numbers.  The
+result of `build_net` is a blob (see blob.py) whose calibration fields (shift,
+res_shift, gap_shift, frac_bits, logit_scale, thr) still hold placeholder
+values; they are filled in later from a calibration record.
+"""
+import math
+import numpy as np
+
+from . import rng
+from .blob import (HEADER_DT, STAGE_DT, OP_DT, EXIT_DT, MAGIC, DT_I8, DT_BF16, OP_CONV, OP_DWCONV,
+                   OP_MAXPOOL, Blob, f32_to_bf16_bits)
+
+BASE_SEED = 0x220913443000
+RELU6_Q = 96  # int8 stand-in for the ReLU6 ceiling (per-tensor power-of-two scales carry no absolute unit)
+
+
+class _Net:
+    def __init__(self, dtype, in_h, in_w, in_c, n_classes):
+        self.dtype, self.in_shape, self.n_classes = dtype, (in_h, in_w, in_c), n_classes
+        self.stages = []   # list of dict(ops=[...], shapes={id: (h,w,c)}, out=id)
+        self._cur = None
+
+    # -- stage construction -------------------------------------------------
+    def begin_stage(self):
+        prev = self.stages[-1] if self.stages else None
+        shape0 = self.in_shape if prev is None else prev["shapes"][prev["out"]]
+        self._cur = dict(ops=[], shapes={0: shape0}, out=None)
+        return 0
+
+    def end_stage(self, out):
+        self._cur["out"] = out
+        self.stages.append(self._cur)
+        self._cur = None
+
+    def _new(self, shape):
+        tid = len(self._cur["shapes"])
+        self._cur["shapes"][tid] = shape
+        return tid
+
+    def _act(self, act):
+        if act == "relu":
+            return 0, 127, 0.0, math.inf
+        if act == "relu6":
+            return 0, RELU6_Q, 0.0, 6.0
+        return -128, 127, -math.inf, math.inf
+
+    def conv(self, src, co, k, stride, pad, act="relu", res=-1):
+        h, w, ci = self._cur["shapes"][src]
+        ho, wo = (h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1
+        dst = self._new((ho, wo, co))
+        lo, hi, flo, fhi = self._act(act)
+        self._cur["ops"].append(dict(kind=OP_CONV, src=src, dst=dst, res=res, h_in=h, w_in=w, c_in=ci,
+                                     h_out=ho, w_out=wo, c_out=co, kh=k, kw=k, stride=stride, pad=pad,
+                                     lo=lo, hi=hi, f_lo=flo, f_hi=fhi))
+        return dst
+
+    def dwconv(self, src, k, stride, pad, act="relu6"):
+        h, w, c = self._cur["shapes"][src]
+        ho, wo = (h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1
+        dst = self._new((ho, wo, c))
+        lo, hi, flo, fhi = self._act(act)
+        self._cur["ops"].append(dict(kind=OP_DWCONV, src=src, dst=dst, res=-1, h_in=h, w_in=w, c_in=c,
+                                     h_out=ho, w_out=wo, c_out=c, kh=k, kw=k, stride=stride, pad=pad,
+                                     lo=lo, hi=hi, f_lo=flo, f_hi=fhi))
+        return dst
+
+    def maxpool(self, src, k, stride, pad):
+        h, w, c = self._cur["shapes"][src]
+        ho, wo = (h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1
+        dst = self._new((ho, wo, c))
+        self._cur["ops"].append(dict(kind=OP_MAXPOOL, src=src, dst=dst, res=-1, h_in=h, w_in=w, c_in=c,
+                                     h_out=ho, w_out=wo, c_out=c, kh=k, kw=k, stride=stride, pad=pad,
+                                     lo=-128, hi=127, f_lo=-math.inf, f_hi=math.inf))
+        return dst
+
+
+# ---------------------------------------------------------------------------
+# architectures
+# ---------------------------------------------------------------------------
+def _tiny(dtype):
+    net = _Net(dtype, 32, 32, 3, 10)
+    for ch in (16, 32, 64):
+        t = net.begin_stage()
+        t = net.conv(t, ch, 3, 2, 1)
+        t = net.conv(t, ch, 3, 1, 1)
+        net.end_stage(t)
+    return net
+
+
+def _resnet_stem(net):
+    t = net.begin_stage()
+    t = net.conv(t, 64, 7, 2, 3)
+    return net.maxpool(t, 3, 2, 1)
+
+
+def _resnet18(dtype, in_hw=224, n_classes=1000):
+    net = _Net(dtype, in_hw, in_hw, 3, n_classes)
+    cin = 64
+    for s, (ch, nblk) in enumerate(zip((64, 128, 256, 512), (2, 2, 2, 2))):
+        t = _resnet_stem(net) if s == 0 else net.begin_stage()
+        for b in range(nblk):
+            stride = 2 if (b == 0 and s > 0) else 1
+            short = t
+            if stride != 1 or cin != ch:
+                short = net.conv(t, ch, 1, stride, 0, act="linear")
+            u = net.conv(t, ch, 3, stride, 1)
+            t = net.conv(u, ch, 3, 1, 1, res=short)
+            cin = ch
+        net.end_stage(t)
+    return net
+
+
+def _resnet50(dtype, in_hw=224, n_classes=1000, blocks=(3, 4, 6, 3)):
+    net = _Net(dtype, in_hw, in_hw, 3, n_classes)
+    cin = 64
+    for s, (mid, nblk) in enumerate(zip((64, 128, 256, 512), blocks)):
+        t = _resnet_stem(net) if s == 0 else net.begin_stage()
+        for b in range(nblk):
+            stride = 2 if (b == 0 and s > 0) else 1
+            short = t
+            if b == 0:
+                short = net.conv(t, 4 * mid, 1, stride, 0, act="linear")
+            u = net.conv(t, mid, 1, 1, 0)
+            u = net.conv(u, mid, 3, stride, 1)
+            t = net.conv(u, 4 * mid, 1, 1, 0, res=short)
+            cin = 4 * mid
+        net.end_stage(t)
+    return net
+
+
+def _mobilenetv2(dtype, in_hw=224, n_classes=1000):
+    net = _Net(dtype, in_hw, in_hw, 3, n_classes)
+    cfg = [(1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2), (6, 96, 3, 1), (6, 160, 3, 2), (6, 320, 1, 1)]
+    exits_after = (6, 13, 17)
+    t = net.begin_stage()
+    t = net.conv(t, 32, 3, 2, 1, act="relu6")
+    cin, blk = 32, 0
+    for (e, c, n, s) in cfg:
+        for i in range(n):
+            stride = s if i == 0 else 1
+            u = t
+            if e != 1:
+                u = net.conv(u, cin * e, 1, 1, 0, act="relu6")
+            u = net.dwconv(u, 3, stride, 1, act="relu6")
+            use_res = (stride == 1 and cin == c)
+            t = net.conv(u, c, 1, 1, 0, act="linear", res=t if use_res else -1)
+            cin = c
+            blk += 1
+            if blk in exits_after:
+                if blk == exits_after[-1]:
+                    t = net.conv(t, 1280, 1, 1, 0, act="relu6")   # final head's 1x1 expansion
+                    net.end_stage(t)
+                else:
+                    net.end_stage(t)
+                    t = net.begin_stage()
+    return net
+
+
+CONFIGS = {
+    # name: (architecture, dtype, seed offset)
+    "tiny_i8": (_tiny, DT_I8, 1),
+    "resnet18_i8": (_resnet18, DT_I8, 2),
+    "mobilenetv2_i8": (_mobilenetv2, DT_I8, 3),
+    "resnet50_i8": (_resnet50, DT_I8, 4),
+    "resnet50_bf16": (_resnet50, DT_BF16, 5),
+    # reduced-size variants for fast tests (same layer types, smaller images / fewer classes)
+    "tiny_bf16": (_tiny, DT_BF16, 11),
+    "resnet18_small_i8": (lambda dt: _resnet18(dt, 64, 100), DT_I8, 12),
+    "resnet50_small_i8": (lambda dt: _resnet50(dt, 64, 100, (1, 2, 2, 1)), DT_I8, 14),
+    "resnet50_small_bf16": (lambda dt: _resnet50(dt, 64, 100, (1, 2, 2, 1)), DT_BF16, 15),
+    "mobilenetv2_small_i8": (lambda dt: _mobilenetv2(dt, 64, 100), DT_I8, 13),
+}
+
+
+# ---------------------------------------------------------------------------
+# blob assembly
+# ---------------------------------------------------------------------------
+def _align(n, a=64):
+    return (n + a - 1) // a * a
+
+
+def _int8_weights(seed, stream, count):
+    """int8 uniform over [-127, 127]."""
+    raw = rng.uniform_bytes(seed, stream, 2 * count).view("<u2")
+    return (raw % np.uint16(255)).astype(np.int16).__sub__(127).astype(np.int8)
+
+
+def _int32_bias(seed, stream, count, bits):
+    raw = rng.raw_u64(seed, stream, count)
+    span = np.uint64((1 << (bits + 1)) + 1)
+    return ((raw >> np.uint64(16)) % span).astype(np.int64).__sub__(1 << bits).astype(np.int32)
+
+
+def build_net(name):
+    """Assemble the un-calibrated blob of configuration `name` (a key of CONFIGS)."""
+    arch, dtype, off = CONFIGS[name]
+    seed = BASE_SEED + off
+    net = arch(dtype)
+    n_stages = len(net.stages)
+    n_ops = sum(len(s["ops"]) for s in net.stages)
+    stages = np.zeros(n_stages, STAGE_DT)
+    ops = np.zeros(n_ops, OP_DT)
+    exits = np.zeros(n_stages, EXIT_DT)
+    stages_off = 128
+    ops_off = stages_off + stages.nbytes
+    exits_off = ops_off + ops.nbytes
+    data_off = _align(exits_off + exits.nbytes)
+    chunks, cursor, stream = [], data_off, 1
+
+    def put(arr):
+        nonlocal cursor
+        off0 = cursor
+        b = np.ascontiguousarray(arr).view(np.uint8).ravel()
+        pad = _align(b.size) - b.size
+        chunks.append(b)
+        if pad:
+            chunks.append(np.zeros(pad, np.uint8))
+        cursor += b.size + pad
+        return off0
+
+    def weights(count, fan_in):
+        nonlocal stream
+        stream += 1
+        if dtype == DT_I8:
+            return _int8_weights(seed, stream, count)
+        w = rng.normal_f64(seed, stream, count) * math.sqrt(2.0 / fan_in)
+        return f32_to_bf16_bits(w.astype(np.float32))
+
+    def bias(count, k_red):
+        nonlocal stream
+        stream += 1
+        if dtype == DT_I8:
+            return _int32_bias(seed, stream, count, 10 + int(math.ceil(0.5 * math.log2(k_red))))
+        return np.zeros(count, np.float32)
+
+    oi = 0
+    for s, st in enumerate(net.stages):
+        oh, ow, oc = st["shapes"][st["out"]]
+        stages[s] = (oi, len(st["ops"]), len(st["shapes"]), st["out"], oh, ow, oc, 0)
+        for op in st["ops"]:
+            rec = ops[oi]
+            for k, v in op.items():
+                rec[k] = v
+            rec["shift"], rec["res_shift"] = 0, 0
+            if op["kind"] == OP_CONV:
+                kred = op["kh"] * op["kw"] * op["c_in"]
+                rec["w_off"] = put(weights(op["c_out"] * kred, kred))
+                rec["b_off"] = put(bias(op["c_out"], kred))
+            elif op["kind"] == OP_DWCONV:
+                kred = op["kh"] * op["kw"]
+                rec["w_off"] = put(weights(op["c_out"] * kred, kred))
+                rec["b_off"] = put(bias(op["c_out"], kred))
+            oi += 1
+        e = exits[s]
+        e["h"], e["w"], e["c"], e["n_cls"] = oh, ow, oc, net.n_classes
+        e["gap_shift"] = int(math.ceil(math.log2(oh * ow))) if oh * ow > 1 else 0
+        e["frac_bits"], e["logit_scale"], e["thr"] = 8, 1.0, 2.0
+        e["w_off"] = put(weights(net.n_classes * oc, oc))
+        e["b_off"] = put(bias(net.n_classes, oc))
+
+    header = np.zeros(1, HEADER_DT)
+    header[0]["magic"] = MAGIC
+    header[0]["version"], header[0]["dtype"] = 1, dtype
+    header[0]["n_stages"], header[0]["n_ops"] = n_stages, n_ops
+    header[0]["in_h"], header[0]["in_w"], header[0]["in_c"] = net.in_shape
+    header[0]["n_classes"] = net.n_classes
+    header[0]["stages_off"], header[0]["ops_off"] = stages_off, ops_off
+    header[0]["exits_off"], header[0]["data_off"] = exits_off, data_off
+    header[0]["total_bytes"] = cursor
+    head = np.concatenate([header.view(np.uint8), stages.view(np.uint8), ops.view(np.uint8), exits.view(np.uint8)])
+    head = np.concatenate([head, np.zeros(data_off - head.size, np.uint8)])
+    return Blob(np.concatenate([head] + chunks).tobytes())
+
+
+def apply_calibration(blob, rec):
+    """Write a calibration record (per-layer shifts, logit scaling, exit thresholds) into a blob."""
+    assert len(rec["ops"]) == len(blob.ops) and len(rec["exits"]) == blob.n_stages
+    for op, r in zip(blob.ops, rec["ops"]):
+        op["shift"], op["res_shift"] = r["shift"], r["res_shift"]
+    for e, r in zip(blob.exits, rec["exits"]):
+        e["gap_shift"], e["frac_bits"] = r["gap_shift"], r["frac_bits"]
+        e["logit_scale"] = np.uint32(r["logit_scale_bits"]).view(np.float32)
+        e["thr"] = np.uint32(r["thr_bits"]).view(np.float32)
+    return blob
+
+
+def load_net(name):
+    """The calibrated blob of configuration `name` (needs workloads/calib/<name>.json)."""
+    import json
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "calib", f"{name}.json")
+    with open(path) as f:
+        rec = json.load(f)
+    return apply_calibration(build_net(name), rec)
