@@ -122,20 +122,20 @@ def test_refill_raises_mean_batch_of_deep_segments(orc):
 
 
 def test_slo_criterion_by_hand(orc):
-    """Two samples start at t=0, one exits at E1 (t=100); four more are queued.  Eq. 4:
-    T_overhead = T1[4] + T2[5] = 130 + 250 = 380.  Eq. 3: T_slack = T_SLO - 100."""
+    """Two samples start at t=0, one exits at E1 (t = T1[2] = 110); four more are queued.  Eq. 4:
+    T_overhead = T1[4] + T2[5] = 130 + 250 = 380.  Eq. 3: T_slack = T_SLO - 110."""
     lut = np.array([[100, 110, 120, 130, 140, 150, 160, 170], [210, 220, 230, 240, 250, 260, 270, 280]], np.int64)
     arrivals = np.array([0, 0, 1, 2, 3, 4], np.int64)
     forced = np.array([1, 0, 1, 1, 1, 1], np.int32)
-    for slo, accept in ((480, False), (481, True)):
+    for slo, accept in ((490, False), (491, True)):
         res, st, ev = orc.serve_stream(None, arrivals, None, 8, lut, t_slo_ns=slo, forced_exit=forced, n_stages=2, max_events=50)
         crit = ev[ev["kind"] == 4][0]
-        assert crit["t_ns"] == 100 and crit["b"] == 4 and crit["aux"] == int(accept)
+        assert crit["t_ns"] == 110 and crit["b"] == 4 and crit["aux"] == int(accept)
         if accept:
             # upper bound of Eq. 4 holds: the preempted sample still meets its SLO
-            assert res["latency_ns"][0] == 100 + 130 + 250 and res["latency_ns"][0] <= slo
+            assert res["latency_ns"][0] == 110 + 130 + 250 and res["latency_ns"][0] <= slo
         else:
-            assert res["latency_ns"][0] == 100 + 210
+            assert res["latency_ns"][0] == 110 + 210
 
 
 def test_min_incr_and_errors(orc):
