@@ -1,0 +1,159 @@
+/*
+ * ee.h -- C ABI of the MI355X (gfx950) early-exit serving library.
+ *
+ * The library runs the data-parallel hot path of exit-aware batched serving of early-exit
+ * CNNs: a backbone segment over a batch of in-flight samples, the exit head after it, the
+ * compaction of survivors with refill of the freed batch slots, and the stream driver that
+ * strings them together with the paper's exit-aware preemptive scheduler.
+ *
+ * Conventions for every call
+ *   - returns EE_OK (0) or a negative ee_status; never throws, never aborts;
+ *   - "device" pointers are GPU global memory owned by the caller (16-byte aligned); "host"
+ *     pointers are ordinary process memory; "device-visible" means either device memory or
+ *     pinned host memory;
+ *   - device work is enqueued on the HIP stream given to ee_create and is asynchronous unless
+ *     stated otherwise: device outputs are valid once the caller has synchronised that stream;
+ *   - nothing is allocated after ee_create: activation workspaces are sized for b_max at
+ *     creation, as the paper pre-allocates its buffers for the largest activation matrix at
+ *     B_max (Sec. III-B, "Overhead");
+ *   - activations are NHWC, dense [slot][H][W][C], slot-major; int8 networks use int8
+ *     activations, bf16 networks raw bfloat16 (uint16_t);
+ *   - a ctx must not be used from two threads at once.
+ */
+#ifndef EE_H
+#define EE_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ee_ctx ee_ctx;
+
+typedef enum {
+    EE_OK = 0,
+    EE_ERR_ARG = -1,          /* NULL pointer, index or batch size out of range, misaligned pointer */
+    EE_ERR_SHAPE = -2,        /* blob whose tensor shapes do not chain */
+    EE_ERR_UNSUPPORTED = -3,  /* dtype or layer kind this build does not carry */
+    EE_ERR_DEVICE = -4,       /* HIP error (no device, allocation or launch failure) */
+    EE_ERR_OVERFLOW = -5      /* a size does not fit the library's limits */
+} ee_status;
+
+typedef enum { EE_I8 = 0, EE_BF16 = 1 } ee_dtype;
+
+const char* ee_strerror(int status);
+
+/* Host-only validation of a network blob (layout: the header comment of csrc/net.cpp).
+ * Needs no GPU.  EE_ERR_SHAPE if the layer shapes do not chain. */
+int ee_blob_check(const void* model_blob, size_t blob_bytes);
+
+/* Parse the blob, repack the weights for the matrix cores into device memory and size the
+ * workspace for b_max slots (1..1024).  `dtype` must match the blob.  `hip_stream` is a
+ * hipStream_t (NULL = the default stream).  The blob may be freed after the call. */
+int ee_create(const void* model_blob, size_t blob_bytes, int b_max, int dtype, void* hip_stream, ee_ctx** out);
+int ee_destroy(ee_ctx* ctx);
+
+/* Number of segments and per-sample byte sizes entering / leaving each (arrays of >= 8). */
+int ee_query(const ee_ctx* ctx, int* n_stages, int64_t* stage_in_bytes, int64_t* stage_out_bytes);
+
+/* ProcUntilExit of Algorithm 1, backbone part: all layers of segment `stage` (0-based) on slots
+ * [0, b_act).  Every CONV layer is the GEMM  R x P . P x C  of Sec. II-C with the batch appended
+ * along the row dimension (R-batching, Sec. III-A).
+ *   act_in   device, [b_act][Hi][Wi][Ci]   (read only)
+ *   act_out  device, [b_act][Ho][Wo][Co]   (written); must not alias act_in
+ * b_act == 0 is a no-op.  EE_ERR_ARG for stage / b_act out of range or NULL / misaligned pointers. */
+int ee_stage_forward(ee_ctx* ctx, int stage, int b_act, const void* act_in, void* act_out);
+
+/* Exit head of segment `stage` on act[b_act][H][W][C]: global average pool, FC, softmax top-1
+ * confidence compared with `thr` (Sec. IV "Benchmarks": softmax top-1 as confidence; a sample
+ * leaves at the first exit whose confidence reaches the threshold).  At the last exit every
+ * sample leaves and `thr` is ignored.  Per-slot device outputs:
+ *   label[b_act] int32, conf[b_act] float, score[b_act] int64, exit_flag[b_act] uint8 (1 = leaves).
+ * int8 networks: score is the integer softmax denominator S (confidence = 2^30 / S) and the
+ * decision is S <= floor(2^30 / thr); bf16 networks: score is 0 and the decision conf >= thr. */
+int ee_exit_head(ee_ctx* ctx, int stage, int b_act, const void* act, float thr,
+                 int32_t* label, float* conf, int64_t* score, uint8_t* exit_flag);
+
+/* The logits the most recent ee_exit_head call computed, [b_act][n_cls] int32 (int8 networks) or
+ * float (bf16 networks), copied to host memory.  Synchronous; for verification. */
+int ee_last_logits(ee_ctx* ctx, int b_act, void* host_out);
+
+/* B_rem = B_act - B_exit and B_merged = B_rem + B_incr of Algorithm 1: stable compaction of the
+ * survivors (exit_flag == 0) of act_src[b_act] into act_dst[0, B_rem), then the b_incr samples of
+ * refill_act appended at act_dst[B_rem, B_rem + b_incr); ids travel the same way.  All tensors
+ * have the per-sample shape of segment `stage`'s output.  act_dst must hold b_act + b_incr
+ * (<= b_max) samples and must not alias act_src / refill_act.
+ *   exit_flag, act_src, ids_src, refill_act, refill_ids   device (read only)
+ *   act_dst, ids_dst                                       device (written)
+ *   b_rem_out, b_merged_out                                device-visible int (written), may be NULL */
+int ee_compact_refill(ee_ctx* ctx, int stage, int b_act, const uint8_t* exit_flag,
+                      const void* act_src, void* act_dst, const int32_t* ids_src, int32_t* ids_dst,
+                      const void* refill_act, const int32_t* refill_ids, int b_incr,
+                      int* b_rem_out, int* b_merged_out);
+
+/* ---- stream serving: Algorithm 1 with the criterion of Eq. (3) / Eq. (4) ------------------- */
+typedef struct { int64_t n; const int64_t* arrival_ns; /* host, non-decreasing */ } ee_trace;
+
+typedef struct {
+    int32_t b_max;          /* <= the ctx's b_max */
+    int32_t clock;          /* 0: wall clock (latencies are measurements); 1: virtual clock driven by lut_ns */
+    int64_t t_slo_ns;       /* latency SLO T_SLO; < 0 = none (infinite slack) */
+    const int64_t* lut_ns;  /* host, [n_stages][b_max]: time of segment s (with its exit head) entered with
+                               B = column + 1 samples (Sec. III-B, "Exit-Level Latency Prediction") */
+    int32_t min_incr;       /* smallest B_incr worth a preemption; 1 = Algorithm 1 as printed */
+    int32_t refill;         /* 0: model-level batching (no preemption); 1: Algorithm 1 */
+} ee_serve_opts;
+
+typedef struct { int32_t exit_idx; int32_t label; float conf; int32_t pad_; int64_t score; int64_t latency_ns; } ee_result;
+
+typedef struct { int64_t t_ns; int32_t kind; int32_t stage; int32_t b; int32_t aux; } ee_event;
+enum { EE_EV_ROUND = 1, EE_EV_PROC = 2, EE_EV_PROC_CATCHUP = 3, EE_EV_CRITERION = 4, EE_EV_MERGE = 5 };
+
+typedef struct {
+    int64_t rounds, criterion_evals, preemptions, end_time_ns;
+    int64_t seg_runs[8], seg_samples[8];   /* per segment: runs (main + catch-up) and samples entered */
+    int64_t n_events;
+} ee_serve_stats;
+
+/* Synchronous.  Serves trace->n requests; request k is row k of input_pool (device,
+ * [n][H][W][C], resident before the call) and its result is results[k] (host): results are
+ * stored by sample id, not in completion order (Sec. III-B, "Overhead").  stats and events
+ * may be NULL.  EE_ERR_ARG for decreasing arrival times or b_max out of range. */
+int ee_serve_stream(ee_ctx* ctx, const ee_trace* trace, const void* input_pool, const ee_serve_opts* opts,
+                    ee_result* results, ee_serve_stats* stats, ee_event* events, int64_t max_events);
+
+/* The same scheduler with the network replaced by a table: forced_exit[k] (host) is the 0-based
+ * exit at which request k leaves.  Touches no GPU; opts->clock must be 1. */
+int ee_schedule_sim(int n_stages, const ee_trace* trace, const int32_t* forced_exit, const ee_serve_opts* opts,
+                    ee_result* results, ee_serve_stats* stats, ee_event* events, int64_t max_events);
+
+/* Design-time latency table (Sec. III-B, "Exit-Level Latency Prediction"): runs segment s with its
+ * exit head for every B = 1..b_max, `reps` times each, and stores the mean time in
+ * lut_ns[s * b_max + B - 1] (host).  Synchronous; activations are whatever the workspace holds. */
+int ee_measure_lut(ee_ctx* ctx, int reps, int64_t* lut_ns);
+
+/* ---- kernel timing (HIP events on the library's stream) ------------------------------------ */
+enum { EE_K_CONV_MFMA = 0, EE_K_CONV_FIRST = 1, EE_K_CONV_DIRECT = 2, EE_K_DEPTHWISE = 3, EE_K_MAXPOOL = 4,
+       EE_K_PAD_INPUT = 5, EE_K_GAP = 6, EE_K_FC = 7, EE_K_SOFTMAX = 8, EE_K_COMPACT = 9, EE_K_ADMIT = 10,
+       EE_K_COUNT = 11 };
+typedef struct { int64_t launches; double ms; double ops; double bytes; } ee_kernel_stat;
+/* enable = 1 brackets every kernel launch with a pair of HIP events; ee_profile_read synchronises,
+ * adds the elapsed times up per kernel class into stats[EE_K_COUNT] (host) and resets the counters.
+ * ops = 2 * MACs of the launches, bytes = their algorithmic HBM traffic (each operand once). */
+int ee_profile_enable(ee_ctx* ctx, int enable);
+int ee_profile_read(ee_ctx* ctx, ee_kernel_stat* stats);
+const char* ee_kernel_name(int kernel_class);
+
+/* Tuning / test control of the convolution tiling, process-wide: 0 = chosen per layer and active
+ * batch size (default), 1 = 128x128, 2 = 256x64, 3 = 64x64 (output pixels x output channels per
+ * workgroup).  Results never depend on it.  Returns the previous setting, EE_ERR_ARG if out of range. */
+int ee_tune_conv_tile(int tile);
+
+/* Host copy of the 256-entry table round(2^30 * 2^(-i/256)) used by the integer softmax. */
+const uint32_t* ee_exp2_table(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,479 @@
+// C ABI entry points: context creation (weight packing, workspace planning), one backbone
+// segment, one exit head, compaction / refill, latency-table measurement and kernel timing.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+#include "ee_ctx.hpp"
+
+namespace ee {
+const uint32_t* exp2_table_host();
+int set_conv_tile(int tile);
+}
+
+using namespace ee;
+
+namespace {
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+template <typename T>
+int dev_alloc(ee_ctx* ctx, T** out, size_t bytes)
+{
+    void* p = nullptr;
+    if (bytes == 0) bytes = 16;
+    if (hipMalloc(&p, bytes) != hipSuccess) return EE_ERR_DEVICE;
+    if (hipMemset(p, 0, bytes) != hipSuccess) { hipFree(p); return EE_ERR_DEVICE; }
+    ctx->owned.push_back(p);
+    *out = static_cast<T*>(p);
+    return EE_OK;
+}
+
+int upload(ee_ctx* ctx, void** out, const std::vector<unsigned char>& host)
+{
+    unsigned char* p = nullptr;
+    int rc = dev_alloc(ctx, &p, host.size());
+    if (rc) return rc;
+    if (!host.empty() && hipMemcpy(p, host.data(), host.size(), hipMemcpyHostToDevice) != hipSuccess) return EE_ERR_DEVICE;
+    *out = p;
+    return EE_OK;
+}
+
+// Packs one layer's weights for its kernel and uploads them with the (padded) bias.
+int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
+{
+    const OpDesc& d = p.d;
+    const int es = ctx->net.elem_bytes();
+    if (d.kind == OP_MAXPOOL) {
+        if ((d.c_in * es) % 16 != 0) return EE_ERR_UNSUPPORTED;
+        p.impl = IMPL_POOL;
+        return EE_OK;
+    }
+    const unsigned char* w = blob + d.w_off;
+    const unsigned char* b = blob + d.b_off;
+    if (d.kind == OP_DWCONV) {
+        if ((d.c_in * es) % 16 != 0 || d.kh != d.kw) return EE_ERR_UNSUPPORTED;
+        p.impl = IMPL_DW;
+        const int taps = d.kh * d.kw, C = d.c_in;
+        std::vector<unsigned char> wp((size_t)taps * C * es);
+        for (int c = 0; c < C; ++c)                       // [C][k][k] -> [k*k][C]
+            for (int t = 0; t < taps; ++t) std::memcpy(&wp[((size_t)t * C + c) * es], w + ((size_t)c * taps + t) * es, es);
+        std::vector<unsigned char> bp(b, b + 4 * (size_t)C);
+        int rc = upload(ctx, &p.w_dev, wp);
+        if (!rc) rc = upload(ctx, &p.b_dev, bp);
+        p.weight_bytes = (double)wp.size() + bp.size();
+        return rc;
+    }
+    const int Co = d.c_out, Ci = d.c_in, Co_pad = round_up(Co, 128);
+    std::vector<unsigned char> bp(4 * (size_t)Co_pad, 0);
+    std::memcpy(bp.data(), b, 4 * (size_t)Co);
+    std::vector<unsigned char> wp;
+    if ((Ci * es) % 16 == 0 && Co % 4 == 0) {
+        p.impl = IMPL_MFMA;
+        const int K = d.kh * d.kw * Ci;
+        p.Kp = round_up(K * es, 64) / es;
+        wp.assign((size_t)Co_pad * p.Kp * es, 0);
+        for (int o = 0; o < Co; ++o) std::memcpy(&wp[(size_t)o * p.Kp * es], w + (size_t)o * K * es, (size_t)K * es);
+    } else if (Ci <= 4 && Co % 4 == 0) {
+        // first layer: the input is copied into a zero-padded 4-channel image, a kernel row of kwp taps is
+        // then kwp*4 contiguous elements; k index = (r * kwp + s) * 4 + c
+        p.impl = IMPL_MFMA_C4;
+        p.kwp = round_up(d.kw, 16 / (4 * es));
+        p.Kp = round_up(d.kh * p.kwp * 4 * es, 64) / es;
+        p.Hp = d.h_in + 2 * d.pad;
+        p.Wp = round_up(std::max(d.w_in + 2 * d.pad, (d.w_out - 1) * d.stride + p.kwp), 4);
+        wp.assign((size_t)Co_pad * p.Kp * es, 0);
+        for (int o = 0; o < Co; ++o)
+            for (int r = 0; r < d.kh; ++r)
+                for (int s = 0; s < d.kw; ++s)
+                    for (int c = 0; c < Ci; ++c)
+                        std::memcpy(&wp[((size_t)o * p.Kp + (size_t)(r * p.kwp + s) * 4 + c) * es],
+                                    w + ((((size_t)o * d.kh + r) * d.kw + s) * Ci + c) * es, es);
+    } else {
+        p.impl = IMPL_DIRECT;
+        wp.assign(w, w + (size_t)Co * d.kh * d.kw * Ci * es);
+    }
+    int rc = upload(ctx, &p.w_dev, wp);
+    if (!rc) rc = upload(ctx, &p.b_dev, bp);
+    p.weight_bytes = (double)Co * d.kh * d.kw * Ci * es + 4.0 * Co;
+    return rc;
+}
+
+// Assigns the intermediate tensors of every segment to a small pool of reusable buffers
+// (greedy by liveness); the segment input and output stay with the caller.
+void plan_buffers(ee_ctx* ctx)
+{
+    const int es = ctx->net.elem_bytes();
+    for (const StageDesc& st : ctx->net.stages) {
+        std::vector<int> last_use(st.n_tensors, -1), buf(st.n_tensors, -3);
+        for (int k = 0; k < st.n_ops; ++k) {
+            const OpDesc& d = ctx->plans[st.first_op + k].d;
+            last_use[d.src] = k;
+            if (d.res >= 0) last_use[d.res] = k;
+        }
+        buf[0] = BUF_EXT_IN;
+        buf[st.out_tensor] = BUF_EXT_OUT;
+        std::vector<int> free_list;
+        std::vector<char> in_use(ctx->pool_sample_bytes.size(), 0);
+        for (int k = 0; k < st.n_ops; ++k) {
+            OpPlan& p = ctx->plans[st.first_op + k];
+            const OpDesc& d = p.d;
+            if (buf[d.dst] == -3) {
+                const size_t need = (size_t)d.h_out * d.w_out * d.c_out * es;
+                int pick = -1;
+                for (size_t i = 0; i < in_use.size(); ++i)
+                    if (!in_use[i]) { pick = (int)i; break; }
+                if (pick < 0) {
+                    pick = (int)ctx->pool_sample_bytes.size();
+                    ctx->pool_sample_bytes.push_back(0);
+                    in_use.push_back(0);
+                }
+                in_use[pick] = 1;
+                ctx->pool_sample_bytes[pick] = std::max(ctx->pool_sample_bytes[pick], need);
+                buf[d.dst] = pick;
+            }
+            p.src_buf = buf[d.src];
+            p.dst_buf = buf[d.dst];
+            p.res_buf = d.res >= 0 ? buf[d.res] : -3;
+            // release tensors whose last reader was this op (the destination is never released here)
+            for (int t : {d.src, d.res})
+                if (t > 0 && buf[t] >= 0 && last_use[t] == k) in_use[buf[t]] = 0;
+        }
+    }
+}
+
+void* resolve(ee_ctx* ctx, int buf, const void* ext_in, void* ext_out)
+{
+    if (buf == BUF_EXT_IN) return const_cast<void*>(ext_in);
+    if (buf == BUF_EXT_OUT) return ext_out;
+    return buf >= 0 ? ctx->pool[buf] : nullptr;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+extern "C" const char* ee_strerror(int status)
+{
+    switch (status) {
+        case EE_OK: return "ok";
+        case EE_ERR_ARG: return "invalid argument";
+        case EE_ERR_SHAPE: return "tensor shapes of the network do not chain";
+        case EE_ERR_UNSUPPORTED: return "unsupported dtype or layer";
+        case EE_ERR_DEVICE: return "HIP device error";
+        case EE_ERR_OVERFLOW: return "size exceeds the library's limits";
+        default: return "unknown status";
+    }
+}
+
+extern "C" const char* ee_kernel_name(int k)
+{
+    static const char* names[EE_K_COUNT] = {"conv_mfma", "conv_first", "conv_direct", "depthwise", "maxpool", "pad_input",
+                                            "gap", "fc", "softmax", "compact", "admit"};
+    return k >= 0 && k < EE_K_COUNT ? names[k] : "?";
+}
+
+extern "C" const uint32_t* ee_exp2_table(void) { return exp2_table_host(); }
+
+extern "C" int ee_tune_conv_tile(int tile) { return tile < 0 || tile > 3 ? EE_ERR_ARG : set_conv_tile(tile); }
+
+extern "C" int ee_blob_check(const void* blob, size_t bytes) { return parse_blob(blob, bytes, nullptr); }
+
+extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, void* hip_stream, ee_ctx** out)
+{
+    if (!out) return EE_ERR_ARG;
+    *out = nullptr;
+    if (b_max < 1 || b_max > 1024) return EE_ERR_ARG;
+    NetDesc net;
+    int rc = parse_blob(blob, bytes, &net);
+    if (rc) return rc;
+    if (dtype != net.dtype) return EE_ERR_UNSUPPORTED;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return EE_ERR_DEVICE;
+    ee_ctx* ctx = new (std::nothrow) ee_ctx();
+    if (!ctx) return EE_ERR_DEVICE;
+    ctx->net = std::move(net);
+    ctx->b_max = b_max;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    const int es = ctx->net.elem_bytes();
+    const unsigned char* base = static_cast<const unsigned char*>(blob);
+    auto fail = [&](int code) { ee_destroy(ctx); return code; };
+
+    ctx->plans.resize(ctx->net.ops.size());
+    for (size_t i = 0; i < ctx->plans.size(); ++i) {
+        OpPlan& p = ctx->plans[i];
+        p.d = ctx->net.ops[i];
+        if ((rc = pack_op(ctx, base, p))) return fail(rc);
+        const OpDesc& d = p.d;
+        const double out_e = (double)d.h_out * d.w_out * d.c_out, in_e = (double)d.h_in * d.w_in * d.c_in;
+        const double kred = d.kind == OP_CONV ? (double)d.kh * d.kw * d.c_in : (double)d.kh * d.kw;
+        p.ops_per_sample = d.kind == OP_MAXPOOL ? 0.0 : 2.0 * out_e * kred;
+        p.bytes_per_sample = (in_e + out_e + (d.res >= 0 ? out_e : 0.0)) * es;
+        if (p.impl == IMPL_MFMA_C4) {
+            void* pb = nullptr;
+            if ((rc = dev_alloc(ctx, &pb, (size_t)b_max * p.Hp * p.Wp * 4 * es + 256))) return fail(rc);
+            p.pad_buf = (int)ctx->pad_bufs.size();
+            ctx->pad_bufs.push_back(pb);
+        }
+    }
+    plan_buffers(ctx);
+    ctx->pool.resize(ctx->pool_sample_bytes.size(), nullptr);
+    for (size_t i = 0; i < ctx->pool.size(); ++i)
+        if ((rc = dev_alloc(ctx, &ctx->pool[i], ctx->pool_sample_bytes[i] * (size_t)b_max))) return fail(rc);
+
+    // exit heads
+    int c_max = 0;
+    const int n_st = (int)ctx->net.stages.size();
+    ctx->wfc_dev.resize(n_st);
+    ctx->bfc_dev.resize(n_st);
+    for (int s = 0; s < n_st; ++s) {
+        const ExitDesc& e = ctx->net.exits[s];
+        if ((e.c * es) % 16 != 0 || e.c * es / 16 > 256) return fail(EE_ERR_UNSUPPORTED);
+        c_max = std::max(c_max, e.c);
+        std::vector<unsigned char> w(base + e.w_off, base + e.w_off + (size_t)e.n_cls * e.c * es);
+        std::vector<unsigned char> b(base + e.b_off, base + e.b_off + 4 * (size_t)e.n_cls);
+        if ((rc = upload(ctx, &ctx->wfc_dev[s], w)) || (rc = upload(ctx, &ctx->bfc_dev[s], b))) return fail(rc);
+        if (ctx->stage_out_bytes(s) % 16 != 0 || ctx->stage_in_bytes(s) % 16 != 0) return fail(EE_ERR_UNSUPPORTED);
+    }
+    if ((rc = dev_alloc(ctx, &ctx->sums, sizeof(int32_t) * (size_t)b_max * c_max))) return fail(rc);
+    if ((rc = dev_alloc(ctx, &ctx->logits, 4 * (size_t)b_max * ctx->net.n_classes))) return fail(rc);
+    if ((rc = dev_alloc(ctx, &ctx->d_count, 64))) return fail(rc);
+
+    // stream-serving workspace: packed input slots and raw output slots of every segment
+    ctx->in_buf.resize(n_st);
+    ctx->out_buf.resize(n_st);
+    for (int s = 0; s < n_st; ++s) {
+        if ((rc = dev_alloc(ctx, &ctx->in_buf[s], (size_t)ctx->stage_in_bytes(s) * b_max))) return fail(rc);
+        if ((rc = dev_alloc(ctx, &ctx->out_buf[s], (size_t)ctx->stage_out_bytes(s) * b_max))) return fail(rc);
+    }
+    if ((rc = dev_alloc(ctx, &ctx->d_ids, sizeof(int32_t) * (size_t)b_max))) return fail(rc);
+    if ((rc = dev_alloc(ctx, &ctx->d_label, sizeof(int32_t) * (size_t)b_max))) return fail(rc);
+    if ((rc = dev_alloc(ctx, &ctx->d_conf, sizeof(float) * (size_t)b_max))) return fail(rc);
+    if ((rc = dev_alloc(ctx, &ctx->d_score, sizeof(int64_t) * (size_t)b_max))) return fail(rc);
+    if ((rc = dev_alloc(ctx, &ctx->d_flag, (size_t)b_max + 16))) return fail(rc);
+    if (hipHostMalloc(&ctx->h_pinned, 32 * (size_t)b_max + 4096, hipHostMallocDefault) != hipSuccess) return fail(EE_ERR_DEVICE);
+    if (hipDeviceSynchronize() != hipSuccess) return fail(EE_ERR_DEVICE);
+    *out = ctx;
+    return EE_OK;
+}
+
+extern "C" int ee_destroy(ee_ctx* ctx)
+{
+    if (!ctx) return EE_OK;
+    hipDeviceSynchronize();
+    for (void* p : ctx->owned) hipFree(p);
+    if (ctx->h_pinned) hipHostFree(ctx->h_pinned);
+    for (ProfRec& r : ctx->prof) { hipEventDestroy(r.e0); hipEventDestroy(r.e1); }
+    delete ctx;
+    return EE_OK;
+}
+
+extern "C" int ee_query(const ee_ctx* ctx, int* n_stages, int64_t* in_bytes, int64_t* out_bytes)
+{
+    if (!ctx) return EE_ERR_ARG;
+    const int n = (int)ctx->net.stages.size();
+    if (n_stages) *n_stages = n;
+    for (int s = 0; s < n; ++s) {
+        if (in_bytes) in_bytes[s] = ctx->stage_in_bytes(s);
+        if (out_bytes) out_bytes[s] = ctx->stage_out_bytes(s);
+    }
+    return EE_OK;
+}
+
+// ---- one backbone segment ------------------------------------------------------------------------
+int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out)
+{
+    const StageDesc& st = net.stages[stage];
+    const int dt = net.dtype, es = net.elem_bytes();
+    for (int k = 0; k < st.n_ops; ++k) {
+        OpPlan& p = plans[st.first_op + k];
+        const OpDesc& d = p.d;
+        const void* src = resolve(this, p.src_buf, act_in, act_out);
+        void* dst = resolve(this, p.dst_buf, act_in, act_out);
+        const void* res = d.res >= 0 ? resolve(this, p.res_buf, act_in, act_out) : nullptr;
+        const double ops = p.ops_per_sample * b, bytes = p.bytes_per_sample * b + p.weight_bytes;
+        hipError_t e = hipSuccess;
+        if (p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_C4) {
+            ConvArgs a{};
+            a.w = p.w_dev; a.bias = p.b_dev; a.res = res; a.y = dst;
+            a.M = b * d.h_out * d.w_out; a.H = d.h_in; a.W = d.w_in; a.Ci = d.c_in; a.Ho = d.h_out; a.Wo = d.w_out; a.Co = d.c_out;
+            a.kh = d.kh; a.kw = d.kw; a.stride = d.stride; a.pad = d.pad; a.Kp = p.Kp;
+            a.shift = d.shift; a.res_shift = d.res_shift; a.lo = d.lo; a.hi = d.hi; a.f_lo = d.f_lo; a.f_hi = d.f_hi;
+            if (p.impl == IMPL_MFMA_C4) {
+                void* padded = pad_bufs[p.pad_buf];
+                const double pb = (double)b * ((double)d.h_in * d.w_in * d.c_in + (double)p.Hp * p.Wp * 4) * es;
+                e = timed(EE_K_PAD_INPUT, 0.0, pb, [&] { return launch_pad_input(src, padded, b, d.h_in, d.w_in, d.c_in, p.Hp, p.Wp, d.pad, dt, stream); });
+                if (e != hipSuccess) return EE_ERR_DEVICE;
+                a.x = padded; a.mode = 1; a.Hp = p.Hp; a.Wp = p.Wp; a.kwp = p.kwp;
+            } else {
+                a.x = src; a.mode = 0;
+            }
+            const int cls = p.impl == IMPL_MFMA ? EE_K_CONV_MFMA : EE_K_CONV_FIRST;
+            e = timed(cls, ops, bytes, [&] { return dt == EE_I8 ? launch_conv_mfma_i8(a, stream) : launch_conv_mfma_bf16(a, stream); });
+        } else if (p.impl == IMPL_DIRECT) {
+            DirectConvArgs a{src, p.w_dev, p.b_dev, res, dst, b * d.h_out * d.w_out, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.c_out,
+                             d.kh, d.kw, d.stride, d.pad, d.shift, d.res_shift, d.lo, d.hi, d.f_lo, d.f_hi};
+            e = timed(EE_K_CONV_DIRECT, ops, bytes, [&] { return launch_conv_direct(a, dt, stream); });
+        } else {
+            PoolArgs a{src, p.w_dev, p.b_dev, dst, b, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.kh, d.stride, d.pad, d.shift, d.lo, d.hi, d.f_lo, d.f_hi};
+            if (p.impl == IMPL_DW) e = timed(EE_K_DEPTHWISE, ops, bytes, [&] { return launch_depthwise(a, dt, stream); });
+            else e = timed(EE_K_MAXPOOL, 0.0, bytes, [&] { return launch_maxpool(a, dt, stream); });
+        }
+        if (e != hipSuccess) return EE_ERR_DEVICE;
+    }
+    return EE_OK;
+}
+
+extern "C" int ee_stage_forward(ee_ctx* ctx, int stage, int b_act, const void* act_in, void* act_out)
+{
+    if (!ctx || stage < 0 || stage >= (int)ctx->net.stages.size() || b_act < 0 || b_act > ctx->b_max) return EE_ERR_ARG;
+    if (b_act == 0) return EE_OK;
+    if (!act_in || !act_out || act_in == act_out || !aligned16(act_in) || !aligned16(act_out)) return EE_ERR_ARG;
+    return ctx->run_stage(stage, b_act, act_in, act_out);
+}
+
+// ---- one exit head ------------------------------------------------------------------------------------
+int ee_ctx::run_head(int stage, int b, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag)
+{
+    const ExitDesc& e = net.exits[stage];
+    const int dt = net.dtype, es = net.elem_bytes();
+    HeadArgs a{};
+    a.act = act; a.B = b; a.HW = e.h * e.w; a.C = e.c; a.n_cls = e.n_cls;
+    a.gap_shift = e.gap_shift; a.frac_bits = e.frac_bits; a.logit_scale = e.logit_scale;
+    a.wfc = wfc_dev[stage]; a.bfc = bfc_dev[stage]; a.sums = sums; a.logits = logits;
+    a.thr = thr;
+    a.s_thr = !(thr > 0.0f) ? INT64_MAX : (thr > 1.0f ? 0 : (int64_t)std::floor(1073741824.0 / (double)thr));
+    a.last = stage == (int)net.stages.size() - 1;
+    a.label = label; a.conf = conf; a.score = score; a.flag = flag;
+    const double act_bytes = (double)b * a.HW * a.C * es;
+    if (timed(EE_K_GAP, 0.0, act_bytes + 4.0 * b * a.C, [&] { return launch_head_gap(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;
+    if (timed(EE_K_FC, 2.0 * b * a.C * a.n_cls, (double)a.C * a.n_cls * es + 4.0 * b * (a.C + a.n_cls),
+              [&] { return launch_head_fc(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;
+    if (timed(EE_K_SOFTMAX, 0.0, 4.0 * b * a.n_cls + 17.0 * b, [&] { return launch_head_softmax(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;
+    return EE_OK;
+}
+
+extern "C" int ee_exit_head(ee_ctx* ctx, int stage, int b_act, const void* act, float thr,
+                            int32_t* label, float* conf, int64_t* score, uint8_t* exit_flag)
+{
+    if (!ctx || stage < 0 || stage >= (int)ctx->net.stages.size() || b_act < 0 || b_act > ctx->b_max) return EE_ERR_ARG;
+    if (b_act == 0) return EE_OK;
+    if (!act || !label || !conf || !score || !exit_flag || !aligned16(act)) return EE_ERR_ARG;
+    return ctx->run_head(stage, b_act, act, thr, label, conf, score, exit_flag);
+}
+
+extern "C" int ee_last_logits(ee_ctx* ctx, int b_act, void* host_out)
+{
+    if (!ctx || !host_out || b_act < 0 || b_act > ctx->b_max) return EE_ERR_ARG;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return EE_ERR_DEVICE;
+    if (b_act && hipMemcpy(host_out, ctx->logits, 4 * (size_t)b_act * ctx->net.n_classes, hipMemcpyDeviceToHost) != hipSuccess) return EE_ERR_DEVICE;
+    return EE_OK;
+}
+
+// ---- compaction and refill ------------------------------------------------------------------------------
+extern "C" int ee_compact_refill(ee_ctx* ctx, int stage, int b_act, const uint8_t* exit_flag,
+                                 const void* act_src, void* act_dst, const int32_t* ids_src, int32_t* ids_dst,
+                                 const void* refill_act, const int32_t* refill_ids, int b_incr,
+                                 int* b_rem_out, int* b_merged_out)
+{
+    if (!ctx || stage < 0 || stage >= (int)ctx->net.stages.size() || b_act < 0 || b_incr < 0 || b_act + b_incr > ctx->b_max) return EE_ERR_ARG;
+    if (b_act > 0 && (!exit_flag || !act_src || !aligned16(act_src))) return EE_ERR_ARG;
+    if (b_incr > 0 && (!refill_act || !aligned16(refill_act))) return EE_ERR_ARG;
+    if ((b_act > 0 || b_incr > 0) && (!act_dst || !aligned16(act_dst) || act_dst == act_src || act_dst == refill_act)) return EE_ERR_ARG;
+    const int64_t sb = ctx->stage_out_bytes(stage);
+    hipStream_t s = ctx->stream;
+    if (b_act > 0) {
+        const double bytes = 2.0 * sb * b_act;       // upper bound: every slot read and written
+        if (ctx->timed(EE_K_COMPACT, 0.0, bytes, [&] {
+                return launch_compact(exit_flag, act_src, act_dst, ids_src, ids_dst, b_act, sb, 0, ctx->d_count, b_rem_out, s);
+            }) != hipSuccess)
+            return EE_ERR_DEVICE;
+    } else {
+        if (hipMemsetAsync(ctx->d_count, 0, sizeof(int), s) != hipSuccess) return EE_ERR_DEVICE;
+        if (b_rem_out && hipMemsetAsync(b_rem_out, 0, sizeof(int), s) != hipSuccess) return EE_ERR_DEVICE;
+    }
+    if (b_incr > 0) {
+        if (ctx->timed(EE_K_COMPACT, 0.0, 2.0 * sb * b_incr, [&] {
+                return launch_append(refill_act, act_dst, refill_ids, ids_dst, ctx->d_count, 0, b_incr, sb, b_merged_out, s);
+            }) != hipSuccess)
+            return EE_ERR_DEVICE;
+    } else if (b_merged_out) {
+        if (hipMemcpyAsync(b_merged_out, ctx->d_count, sizeof(int), hipMemcpyDefault, s) != hipSuccess) return EE_ERR_DEVICE;
+    }
+    return EE_OK;
+}
+
+// ---- design-time latency table ---------------------------------------------------------------------------
+extern "C" int ee_measure_lut(ee_ctx* ctx, int reps, int64_t* lut_ns)
+{
+    if (!ctx || !lut_ns || reps < 1) return EE_ERR_ARG;
+    const int n_st = (int)ctx->net.stages.size(), bm = ctx->b_max;
+    const bool was = ctx->profiling;
+    ctx->profiling = false;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return EE_ERR_DEVICE;
+    const int step = std::max(1, bm / 64);
+    int rc = EE_OK;
+    for (int s = 0; s < n_st && !rc; ++s) {
+        std::vector<int> measured;
+        for (int b = 1; b <= bm; b += step) measured.push_back(b);
+        if (measured.back() != bm) measured.push_back(bm);
+        std::vector<double> t(measured.size());
+        for (size_t i = 0; i < measured.size() && !rc; ++i) {
+            const int b = measured[i];
+            for (int pass = 0; pass < 2 && !rc; ++pass) {               // pass 0 warms caches and code objects
+                const int n = pass == 0 ? 1 : reps;
+                hipEventRecord(e0, ctx->stream);
+                for (int r = 0; r < n && !rc; ++r) {
+                    rc = ctx->run_stage(s, b, ctx->in_buf[s], ctx->out_buf[s]);
+                    if (!rc) rc = ctx->run_head(s, b, ctx->out_buf[s], 2.0f, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag);
+                }
+                hipEventRecord(e1, ctx->stream);
+                if (hipEventSynchronize(e1) != hipSuccess) rc = EE_ERR_DEVICE;
+                float ms = 0.f;
+                hipEventElapsedTime(&ms, e0, e1);
+                t[i] = (double)ms * 1e6 / n;
+            }
+        }
+        for (int b = 1; b <= bm && !rc; ++b) {                          // linear interpolation between measured sizes
+            size_t hi = 0;
+            while (measured[hi] < b) ++hi;
+            double v = t[hi];
+            if (measured[hi] != b) {
+                const double w = (double)(b - measured[hi - 1]) / (measured[hi] - measured[hi - 1]);
+                v = t[hi - 1] * (1 - w) + t[hi] * w;
+            }
+            lut_ns[(size_t)s * bm + b - 1] = (int64_t)std::llround(v);
+        }
+    }
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    ctx->profiling = was;
+    return rc;
+}
+
+// ---- kernel timing ------------------------------------------------------------------------------------------
+extern "C" int ee_profile_enable(ee_ctx* ctx, int enable)
+{
+    if (!ctx) return EE_ERR_ARG;
+    ctx->profiling = enable != 0;
+    return EE_OK;
+}
+
+extern "C" int ee_profile_read(ee_ctx* ctx, ee_kernel_stat* stats)
+{
+    if (!ctx || !stats) return EE_ERR_ARG;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return EE_ERR_DEVICE;
+    for (int k = 0; k < EE_K_COUNT; ++k) stats[k] = ee_kernel_stat{0, 0.0, 0.0, 0.0};
+    for (size_t i = 0; i < ctx->prof_used; ++i) {
+        const ProfRec& r = ctx->prof[i];
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.e0, r.e1) != hipSuccess) continue;
+        stats[r.cls].launches++;
+        stats[r.cls].ms += ms;
+        stats[r.cls].ops += r.ops;
+        stats[r.cls].bytes += r.bytes;
+    }
+    ctx->prof_used = 0;
+    return EE_OK;
+}

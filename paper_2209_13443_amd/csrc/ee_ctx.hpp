@@ -1,0 +1,85 @@
+// The library context: device copies of the packed weights, the pre-allocated activation
+// workspace and the per-segment launch plans.
+#pragma once
+#include <chrono>
+
+#include "ee_internal.hpp"
+
+namespace ee {
+
+enum Impl { IMPL_MFMA = 0, IMPL_MFMA_C4 = 1, IMPL_DIRECT = 2, IMPL_DW = 3, IMPL_POOL = 4 };
+enum { BUF_EXT_IN = -1, BUF_EXT_OUT = -2 };
+
+struct OpPlan {
+    OpDesc d;
+    int impl = IMPL_DIRECT;
+    void* w_dev = nullptr;      // packed weights
+    void* b_dev = nullptr;      // bias, padded to the weight rows
+    int Kp = 0, kwp = 0, Hp = 0, Wp = 0;
+    int src_buf = 0, dst_buf = 0, res_buf = 0;   // BUF_EXT_* or an index into Ctx::pool
+    int pad_buf = -1;           // zero-padded 4-channel copy of the input (IMPL_MFMA_C4)
+    double ops_per_sample = 0, bytes_per_sample = 0, weight_bytes = 0;
+};
+
+struct ProfRec { int cls; hipEvent_t e0, e1; double ops, bytes; };
+
+}  // namespace ee
+
+struct ee_ctx {
+    ee::NetDesc net;
+    int b_max = 0;
+    hipStream_t stream = nullptr;
+    std::vector<ee::OpPlan> plans;               // same order as net.ops
+    std::vector<void*> pool;                     // intermediate activations, b_max samples each
+    std::vector<size_t> pool_sample_bytes;
+    std::vector<void*> pad_bufs;                 // zero-padded 4-channel input copies (first layers)
+    std::vector<void*> owned;                    // every device allocation, for ee_destroy
+    std::vector<void*> wfc_dev, bfc_dev;         // exit heads
+    int32_t* sums = nullptr;                     // [b_max][C_max]
+    void* logits = nullptr;                      // [b_max][n_cls]
+    int* d_count = nullptr;                      // device int scratch (B_rem)
+    // stream serving workspace
+    std::vector<void*> in_buf, out_buf;          // per segment: packed input slots, raw output slots
+    int32_t* d_ids = nullptr;                    // admission ids
+    int32_t* d_label = nullptr; float* d_conf = nullptr; int64_t* d_score = nullptr; uint8_t* d_flag = nullptr;
+    void* h_pinned = nullptr;                    // pinned host staging (ids ring + head outputs)
+    // kernel timing
+    bool profiling = false;
+    std::vector<ee::ProfRec> prof;
+    size_t prof_used = 0;
+
+    int64_t stage_in_bytes(int s) const
+    {
+        const ee::StageDesc& st = net.stages[s];
+        return (int64_t)st.in_h * st.in_w * st.in_c * net.elem_bytes();
+    }
+    int64_t stage_out_bytes(int s) const
+    {
+        const ee::StageDesc& st = net.stages[s];
+        return (int64_t)st.out_h * st.out_w * st.out_c * net.elem_bytes();
+    }
+
+    // internal entry points shared by the C ABI and the stream driver (no argument checks)
+    int run_stage(int stage, int b_act, const void* act_in, void* act_out);
+    int run_head(int stage, int b_act, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag);
+    // brackets `launch` with a pair of events when profiling
+    template <typename F>
+    hipError_t timed(int cls, double ops, double bytes, F&& launch);
+};
+
+template <typename F>
+hipError_t ee_ctx::timed(int cls, double ops, double bytes, F&& launch)
+{
+    if (!profiling) return launch();
+    if (prof_used == prof.size()) {
+        ee::ProfRec r{};
+        if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return hipErrorOutOfMemory;
+        prof.push_back(r);
+    }
+    ee::ProfRec& r = prof[prof_used++];
+    r.cls = cls; r.ops = ops; r.bytes = bytes;
+    hipEventRecord(r.e0, stream);
+    hipError_t e = launch();
+    hipEventRecord(r.e1, stream);
+    return e;
+}

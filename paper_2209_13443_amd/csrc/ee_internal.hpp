@@ -1,0 +1,103 @@
+// Internal declarations of the early-exit serving library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/ee.h"
+
+namespace ee {
+
+// ---- network description parsed from the blob ------------------------------------------------
+enum OpKind { OP_CONV = 0, OP_DWCONV = 1, OP_MAXPOOL = 2 };
+
+struct OpDesc {
+    int kind, src, dst, res;
+    int h_in, w_in, c_in, h_out, w_out, c_out;
+    int kh, kw, stride, pad;
+    int shift, res_shift, lo, hi;
+    float f_lo, f_hi;
+    int64_t w_off, b_off;
+};
+
+struct ExitDesc {
+    int h, w, c, n_cls, gap_shift, frac_bits;
+    float logit_scale, thr;
+    int64_t w_off, b_off;
+};
+
+struct StageDesc {
+    int first_op, n_ops, n_tensors, out_tensor;
+    int in_h, in_w, in_c, out_h, out_w, out_c;
+};
+
+struct NetDesc {
+    int dtype = 0, n_classes = 0, in_h = 0, in_w = 0, in_c = 0;
+    std::vector<StageDesc> stages;
+    std::vector<OpDesc> ops;
+    std::vector<ExitDesc> exits;
+    int elem_bytes() const { return dtype == EE_I8 ? 1 : 2; }
+};
+
+// Validates and decodes a blob.  Returns an ee_status.
+int parse_blob(const void* blob, size_t bytes, NetDesc* out);
+
+// ---- kernel argument blocks --------------------------------------------------------------------
+// Implicit-GEMM convolution: rows = output pixels m = (n, oy, ox), columns = output channels,
+// reduction over (r, s, c).  Weights are pre-packed [Co_pad][Kp] with the reduction index the
+// loader uses (see pack_weights in ee_api.cpp), zero padded.
+struct ConvArgs {
+    const void* x; const void* w; const void* bias; const void* res; void* y;
+    int M, H, W, Ci, Ho, Wo, Co;
+    int kh, kw, stride, pad;
+    int Kp;              // padded reduction length in elements (multiple of the k-step)
+    int mode;            // 0: Ci % 16 == 0 loader with bounds checks; 1: 4-channel zero-padded input
+    int Hp, Wp, kwp;     // mode 1: padded input dims and padded kernel width
+    int shift, res_shift, lo, hi;
+    float f_lo, f_hi;
+};
+
+struct DirectConvArgs {   // one thread per output element; any shape (correctness fallback)
+    const void* x; const void* w; const void* bias; const void* res; void* y;
+    int M, H, W, Ci, Ho, Wo, Co, kh, kw, stride, pad, shift, res_shift, lo, hi;
+    float f_lo, f_hi;
+};
+
+struct PoolArgs {         // depthwise 3x3 and max-pool share the shape block
+    const void* x; const void* w; const void* bias; void* y;
+    int B, H, W, C, Ho, Wo, k, stride, pad, shift, lo, hi;
+    float f_lo, f_hi;
+};
+
+// ---- launchers (defined in the .hip files) -------------------------------------------------------
+hipError_t launch_conv_mfma_i8(const ConvArgs& a, hipStream_t s);
+hipError_t launch_conv_mfma_bf16(const ConvArgs& a, hipStream_t s);
+hipError_t launch_conv_direct(const DirectConvArgs& a, int dtype, hipStream_t s);
+hipError_t launch_pad_input(const void* x, void* y, int B, int H, int W, int C, int Hp, int Wp, int pad, int dtype, hipStream_t s);
+hipError_t launch_depthwise(const PoolArgs& a, int dtype, hipStream_t s);
+hipError_t launch_maxpool(const PoolArgs& a, int dtype, hipStream_t s);
+
+struct HeadArgs {
+    const void* act; int B, HW, C, n_cls;
+    int gap_shift, frac_bits; float logit_scale;
+    const void* wfc; const void* bfc;
+    int32_t* sums;       // [B][C] int32 (i8) or float (bf16) scratch
+    void* logits;        // [B][n_cls] int32 / float scratch
+    int64_t s_thr; float thr; int last;
+    int32_t* label; float* conf; int64_t* score; uint8_t* flag;
+};
+hipError_t launch_head_gap(const HeadArgs& a, int dtype, hipStream_t s);
+hipError_t launch_head_fc(const HeadArgs& a, int dtype, hipStream_t s);
+hipError_t launch_head_softmax(const HeadArgs& a, int dtype, hipStream_t s);
+
+// Stable compaction + append.  dst_off: first destination slot of the survivors.
+hipError_t launch_compact(const uint8_t* flag, const void* src, void* dst, const int32_t* ids_src, int32_t* ids_dst,
+                          int b_act, int64_t sample_bytes, int dst_off, int* b_rem_out, int* b_rem_out2, hipStream_t s);
+hipError_t launch_append(const void* refill, void* dst, const int32_t* refill_ids, int32_t* ids_dst, const int* b_rem_dev,
+                         int b_rem_host, int b_incr, int64_t sample_bytes, int* b_merged_out, hipStream_t s);
+// Admission: pool rows ids[k] -> slots [0, b)
+hipError_t launch_admit(const void* pool, void* dst, const int32_t* ids, int b, int64_t sample_bytes, hipStream_t s);
+
+}  // namespace ee

@@ -1,0 +1,362 @@
+// Convolution kernels for gfx950 (CDNA4): implicit GEMM on the matrix cores.
+//
+// Every CONV layer is the GEMM  R x P . P x C -> R x C  of the paper's Sec. II-C with the batch
+// appended along R (R-batching, Sec. III-A); here the Toeplitz matrix is never materialised:
+// rows (output pixels) are gathered straight from the NHWC activation tensor while the K loop
+// walks over (r, s, c).
+//
+// Tiling: a workgroup of 4 wavefronts (256 lanes) owns BM output pixels x BN output channels.
+// Per 64-byte k-step both operands are staged in LDS (rows padded to 80 bytes so that the
+// 16-lane phases of a ds_read_b128 hit 64 distinct banks), double buffered with one barrier
+// per k-step; the next step's global loads are issued before the current step's MFMAs.
+// Each wavefront computes WM x WN outputs with v_mfma_i32_32x32x32_i8 (int8) or
+// v_mfma_f32_32x32x16_bf16 (bf16).  The weight fragment is the A operand and the activation
+// fragment the B operand, so that one lane ends up holding 4 consecutive output channels of
+// one pixel per accumulator quad -- a packed store in NHWC.
+//
+// Operand layout assumed for the 32x32 MFMAs (lane l, 16 bytes per lane):
+//   A: row l%32, k-bytes [16*(l/32), 16*(l/32)+16)      B: column l%32, same k-bytes
+//   D: column l%32, rows 8*(v/4) + 4*(l/32) + v%4 for accumulator register v = 0..15
+// (the k order inside an instruction is irrelevant as long as A and B agree).
+#include <type_traits>
+
+#include "ee_internal.hpp"
+
+namespace ee {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+constexpr int kLdsRow = 80;   // 64 data bytes + 16 bytes of padding
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+__device__ __forceinline__ int requant_i8(int t, int shift, int lo, int hi)
+{
+    int q = shift > 0 ? (t + (1 << (shift - 1))) >> shift : t;
+    return min(max(q, lo), hi);
+}
+
+// ES = element size in bytes (1: int8, 2: bf16).  MODE 0: generic NHWC input with C*ES % 16 == 0,
+// bounds-checked taps.  MODE 1: 4-channel input already zero-padded in space ([Hp][Wp][4]); a kernel
+// row of kwp taps is kwp*4*ES contiguous bytes, no bounds checks.
+template <int ES, int BM, int BN, int WM, int WN, int MODE>
+__global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a)
+{
+    constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
+    static_assert(WAVES_M * WAVES_N == 4, "4 wavefronts per workgroup");
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int A_PER_T = BM / 64, B_PER_T = BN / 64;
+    static_assert(A_PER_T >= 1 && B_PER_T >= 1, "tile too small for the loader");
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2][(BM + BN) * kLdsRow];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const int cc = tid & 3, row_base = tid >> 2;
+    const unsigned char* xb = (const unsigned char*)a.x;
+    const unsigned char* wb = (const unsigned char*)a.w;
+    const int nk = a.Kp * ES / 64;
+    const int HoWo = a.Ho * a.Wo;
+
+    // ---- per-thread loader state -------------------------------------------------------------
+    long long a_off[A_PER_T];     // MODE 0: byte offset of pixel (n, 0, 0); MODE 1: byte offset of the patch corner
+    int a_iy0[A_PER_T], a_ix0[A_PER_T];
+#pragma unroll
+    for (int i = 0; i < A_PER_T; ++i) {
+        int m = m0 + row_base + 64 * i;
+        m = m < a.M ? m : a.M - 1;                       // rows past the end repeat the last pixel; never stored
+        const int n = m / HoWo, rem = m - n * HoWo;
+        const int oy = rem / a.Wo, ox = rem - oy * a.Wo;
+        if (MODE == 0) {
+            a_off[i] = (long long)n * a.H * a.W * a.Ci * ES;
+            a_iy0[i] = oy * a.stride - a.pad;
+            a_ix0[i] = ox * a.stride - a.pad;
+        } else {
+            a_off[i] = (((long long)n * a.Hp + oy * a.stride) * a.Wp + ox * a.stride) * 4 * ES;
+            a_iy0[i] = a_ix0[i] = 0;
+        }
+    }
+    const int CiB = a.Ci * ES;                           // bytes per input pixel (MODE 0)
+    int tr, ts, tc;                                      // MODE 0: tap (r, s) and byte offset inside the pixel
+    int prow, ppart;                                     // MODE 1: kernel row and 16-byte part inside it
+    const int cpr = MODE == 1 ? a.kwp * 4 * ES / 16 : 1; // MODE 1: 16-byte chunks per kernel row
+    if (MODE == 0) {
+        const int kb = cc * 16;
+        const int tap = kb / CiB;
+        tc = kb - tap * CiB;
+        tr = tap / a.kw;
+        ts = tap - tr * a.kw;
+        prow = ppart = 0;
+    } else {
+        prow = cc / cpr;
+        ppart = cc - prow * cpr;
+        tr = ts = tc = 0;
+    }
+
+    v4i ra[A_PER_T], rb[B_PER_T];
+    auto load_global = [&](int ks) {
+#pragma unroll
+        for (int i = 0; i < A_PER_T; ++i) {
+            if (MODE == 0) {
+                const int iy = a_iy0[i] + tr, ix = a_ix0[i] + ts;
+                const bool ok = tr < a.kh && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+                v4i v = {0, 0, 0, 0};
+                if (ok) v = *(const v4i*)(xb + a_off[i] + ((long long)iy * a.W + ix) * CiB + tc);
+                ra[i] = v;
+            } else {
+                const int r = prow < a.kh ? prow : a.kh - 1;      // k padding: real bytes times zero weights
+                const unsigned char* p = xb + a_off[i] + (long long)r * a.Wp * 4 * ES + ppart * 16;
+                const int* q = (const int*)p;                     // 4-byte aligned only
+                v4i v = {q[0], q[1], q[2], q[3]};
+                ra[i] = v;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < B_PER_T; ++i)
+            rb[i] = *(const v4i*)(wb + ((long long)(n0 + row_base + 64 * i) * a.Kp * ES) + ks * 64 + cc * 16);
+        // advance the tap state by one k-step (64 bytes)
+        if (MODE == 0) {
+            tc += 64;
+            while (tc >= CiB) {
+                tc -= CiB;
+                if (++ts == a.kw) { ts = 0; ++tr; }
+            }
+        } else {
+            ppart += 4;
+            while (ppart >= cpr) { ppart -= cpr; ++prow; }
+        }
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < A_PER_T; ++i)
+            *(v4i*)(&lds[buf][(row_base + 64 * i) * kLdsRow + cc * 16]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < B_PER_T; ++i)
+            *(v4i*)(&lds[buf][(BM + row_base + 64 * i) * kLdsRow + cc * 16]) = rb[i];
+    };
+
+    using acc_t = typename std::conditional<ES == 1, v16i, v16f>::type;
+    acc_t acc[TN][TM];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][i][v] = 0;
+
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    const int frag_row = lane & 31, frag_k = (lane >> 5) * 16;
+    for (int ks = 0; ks < nk; ++ks) {
+        const int buf = ks & 1;
+        if (ks + 1 < nk) load_global(ks + 1);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            v4i fw[TN], fx[TM];
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                fw[j] = *(const v4i*)(&lds[buf][(BM + wn0 + 32 * j + frag_row) * kLdsRow + half * 32 + frag_k]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fx[i] = *(const v4i*)(&lds[buf][(wm0 + 32 * i + frag_row) * kLdsRow + half * 32 + frag_k]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    if constexpr (ES == 1)
+                        acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[j], fx[i], acc[j][i], 0, 0, 0);
+                    else
+                        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fw[j]),
+                                                                             __builtin_bit_cast(v8bf, fx[i]), acc[j][i], 0, 0, 0);
+                }
+        }
+        if (ks + 1 < nk) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: bias, residual, requantise / clamp, packed NHWC store ------------------------
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = m0 + wm0 + 32 * i + (lane & 31);
+        if (m >= a.M) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int c0 = n0 + wn0 + 32 * j + 8 * g + 4 * (lane >> 5);
+                if (c0 >= a.Co) continue;
+                const long long o = (long long)m * a.Co + c0;
+                if constexpr (ES == 1) {
+                    const v4i bias = *(const v4i*)((const int*)a.bias + c0);
+                    int r4[4] = {0, 0, 0, 0};
+                    if (a.res) {
+                        const int packed = *(const int*)((const signed char*)a.res + o);
+                        r4[0] = (int)(signed char)(packed & 0xFF); r4[1] = (int)(signed char)((packed >> 8) & 0xFF);
+                        r4[2] = (int)(signed char)((packed >> 16) & 0xFF); r4[3] = packed >> 24;
+                    }
+                    unsigned out = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int t = acc[j][i][4 * g + e] + bias[e] + (r4[e] << a.res_shift);
+                        out |= (unsigned)(requant_i8(t, a.shift, a.lo, a.hi) & 0xFF) << (8 * e);
+                    }
+                    *(unsigned*)((signed char*)a.y + o) = out;
+                } else {
+                    const float* bias = (const float*)a.bias + c0;
+                    uint16_t r4[4] = {0, 0, 0, 0};
+                    if (a.res) {
+                        const uint2 packed = *(const uint2*)((const uint16_t*)a.res + o);
+                        r4[0] = packed.x & 0xFFFF; r4[1] = packed.x >> 16; r4[2] = packed.y & 0xFFFF; r4[3] = packed.y >> 16;
+                    }
+                    uint16_t q[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float t = acc[j][i][4 * g + e] + bias[e];
+                        if (a.res) t = t + bf16_to_f32(r4[e]);
+                        t = fminf(fmaxf(t, a.f_lo), a.f_hi);
+                        q[e] = f32_to_bf16_rne(t);
+                    }
+                    uint2 out;
+                    out.x = (unsigned)q[0] | ((unsigned)q[1] << 16);
+                    out.y = (unsigned)q[2] | ((unsigned)q[3] << 16);
+                    *(uint2*)((uint16_t*)a.y + o) = out;
+                }
+            }
+    }
+}
+
+template <int ES, int BM, int BN, int WM, int WN>
+static hipError_t launch_tile(const ConvArgs& a, hipStream_t s)
+{
+    dim3 grid((a.M + BM - 1) / BM, (a.Co + BN - 1) / BN);
+    if (a.mode == 0)
+        hipLaunchKernelGGL((conv_mfma_kernel<ES, BM, BN, WM, WN, 0>), grid, dim3(256), 0, s, a);
+    else
+        hipLaunchKernelGGL((conv_mfma_kernel<ES, BM, BN, WM, WN, 1>), grid, dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// Tile choice: wide tiles when they still give every CU work, narrower ones for few output
+// channels or a small active batch (the GPU face of the paper's per-layer, per-batch-size
+// mapping problem, Sec. III-A).
+static int g_forced_tile = 0;    // 0 = choose by shape; 1: 128x128, 2: 256x64, 3: 64x64 (tuning / test control)
+int set_conv_tile(int tile) { const int old = g_forced_tile; g_forced_tile = tile; return old; }
+
+template <int ES>
+static hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t s)
+{
+    if (a.M <= 0) return hipSuccess;
+    if (g_forced_tile == 1) return launch_tile<ES, 128, 128, 64, 64>(a, s);
+    if (g_forced_tile == 2) return launch_tile<ES, 256, 64, 64, 64>(a, s);
+    if (g_forced_tile == 3) return launch_tile<ES, 64, 64, 32, 32>(a, s);
+    const long long big = (long long)((a.M + 127) / 128) * ((a.Co + 127) / 128);
+    if (a.Co > 64 && big >= 256) return launch_tile<ES, 128, 128, 64, 64>(a, s);
+    if (a.Co <= 64 && (long long)((a.M + 255) / 256) >= 256) return launch_tile<ES, 256, 64, 64, 64>(a, s);
+    return launch_tile<ES, 64, 64, 32, 32>(a, s);
+}
+
+hipError_t launch_conv_mfma_i8(const ConvArgs& a, hipStream_t s) { return launch_conv_mfma<1>(a, s); }
+hipError_t launch_conv_mfma_bf16(const ConvArgs& a, hipStream_t s) { return launch_conv_mfma<2>(a, s); }
+
+// ---- fallback: one thread per output element, any shape ----------------------------------------
+template <int ES>
+__global__ __launch_bounds__(256) void conv_direct_kernel(DirectConvArgs a)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)a.M * a.Co) return;
+    const int co = (int)(idx % a.Co);
+    const int m = (int)(idx / a.Co);
+    const int HoWo = a.Ho * a.Wo;
+    const int n = m / HoWo, rem = m - n * HoWo, oy = rem / a.Wo, ox = rem - oy * a.Wo;
+    if constexpr (ES == 1) {
+        const signed char* x = (const signed char*)a.x;
+        const signed char* w = (const signed char*)a.w + (long long)co * a.kh * a.kw * a.Ci;
+        int acc = ((const int*)a.bias)[co];
+        for (int r = 0; r < a.kh; ++r) {
+            const int iy = oy * a.stride + r - a.pad;
+            if (iy < 0 || iy >= a.H) continue;
+            for (int s = 0; s < a.kw; ++s) {
+                const int ix = ox * a.stride + s - a.pad;
+                if (ix < 0 || ix >= a.W) continue;
+                const signed char* xp = x + (((long long)n * a.H + iy) * a.W + ix) * a.Ci;
+                const signed char* wp = w + (r * a.kw + s) * a.Ci;
+                for (int c = 0; c < a.Ci; ++c) acc += (int)xp[c] * (int)wp[c];
+            }
+        }
+        if (a.res) acc += (int)((const signed char*)a.res)[idx] << a.res_shift;
+        ((signed char*)a.y)[idx] = (signed char)requant_i8(acc, a.shift, a.lo, a.hi);
+    } else {
+        const uint16_t* x = (const uint16_t*)a.x;
+        const uint16_t* w = (const uint16_t*)a.w + (long long)co * a.kh * a.kw * a.Ci;
+        float acc = 0.f;
+        for (int r = 0; r < a.kh; ++r) {
+            const int iy = oy * a.stride + r - a.pad;
+            if (iy < 0 || iy >= a.H) continue;
+            for (int s = 0; s < a.kw; ++s) {
+                const int ix = ox * a.stride + s - a.pad;
+                if (ix < 0 || ix >= a.W) continue;
+                const uint16_t* xp = x + (((long long)n * a.H + iy) * a.W + ix) * a.Ci;
+                const uint16_t* wp = w + (r * a.kw + s) * a.Ci;
+                for (int c = 0; c < a.Ci; ++c) acc = fmaf(bf16_to_f32(xp[c]), bf16_to_f32(wp[c]), acc);
+            }
+        }
+        float t = acc + ((const float*)a.bias)[co];
+        if (a.res) t = t + bf16_to_f32(((const uint16_t*)a.res)[idx]);
+        t = fminf(fmaxf(t, a.f_lo), a.f_hi);
+        ((uint16_t*)a.y)[idx] = f32_to_bf16_rne(t);
+    }
+}
+
+hipError_t launch_conv_direct(const DirectConvArgs& a, int dtype, hipStream_t s)
+{
+    const long long total = (long long)a.M * a.Co;
+    if (total <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    if (dtype == EE_I8) hipLaunchKernelGGL(conv_direct_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(conv_direct_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ---- [B][H][W][C<=4] -> zero-padded [B][Hp][Wp][4] ------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void pad_input_kernel(const T* x, T* y, int B, int H, int W, int C, int Hp, int Wp, int pad)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)B * Hp * Wp) return;
+    const int xp = (int)(idx % Wp);
+    const int yp = (int)((idx / Wp) % Hp);
+    const int n = (int)(idx / ((long long)Wp * Hp));
+    const int iy = yp - pad, ix = xp - pad;
+    T v[4] = {0, 0, 0, 0};
+    if (iy >= 0 && iy < H && ix >= 0 && ix < W) {
+        const T* p = x + (((long long)n * H + iy) * W + ix) * C;
+        for (int c = 0; c < C; ++c) v[c] = p[c];
+    }
+    T* q = y + idx * 4;
+    q[0] = v[0]; q[1] = v[1]; q[2] = v[2]; q[3] = v[3];
+}
+
+hipError_t launch_pad_input(const void* x, void* y, int B, int H, int W, int C, int Hp, int Wp, int pad, int dtype, hipStream_t s)
+{
+    const long long total = (long long)B * Hp * Wp;
+    if (total <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    if (dtype == EE_I8)
+        hipLaunchKernelGGL(pad_input_kernel<signed char>, dim3(blocks), dim3(256), 0, s, (const signed char*)x, (signed char*)y, B, H, W, C, Hp, Wp, pad);
+    else
+        hipLaunchKernelGGL(pad_input_kernel<uint16_t>, dim3(blocks), dim3(256), 0, s, (const uint16_t*)x, (uint16_t*)y, B, H, W, C, Hp, Wp, pad);
+    return hipGetLastError();
+}
+
+}  // namespace ee

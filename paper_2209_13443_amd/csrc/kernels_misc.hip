@@ -1,0 +1,459 @@
+// Bandwidth-bound kernels for gfx950: depthwise 3x3, max-pool, the exit head (global average
+// pool, FC, softmax top-1 and the exit decision), slot compaction / refill and admission.
+// All of them move 16 bytes per lane per access along the channel (NHWC) or sample axis so
+// that a wavefront touches whole cache lines.
+#include "ee_internal.hpp"
+
+namespace ee {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne_m(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32_m(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ int byte_of(int word, int e) { return (int)(signed char)((word >> (8 * e)) & 0xFF); }
+
+// ---- depthwise k x k: one lane = one output pixel x 16 bytes of channels ---------------------------
+// weights repacked [k*k][C]; int8: int32 accumulate + bias, round-shift, clamp; bf16: float accumulate.
+template <int ES>
+__global__ __launch_bounds__(256) void depthwise_kernel(PoolArgs a)
+{
+    const int cchunks = a.C * ES / 16;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)a.B * a.Ho * a.Wo * cchunks) return;
+    const int q = (int)(idx % cchunks);
+    const long long pix = idx / cchunks;
+    const int ox = (int)(pix % a.Wo), oy = (int)((pix / a.Wo) % a.Ho), n = (int)(pix / ((long long)a.Wo * a.Ho));
+    const unsigned char* x = (const unsigned char*)a.x;
+    if constexpr (ES == 1) {
+        int acc[16];
+        const int* bias = (const int*)a.bias + q * 16;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[e] = bias[e];
+        for (int r = 0; r < a.k; ++r) {
+            const int iy = oy * a.stride + r - a.pad;
+            if (iy < 0 || iy >= a.H) continue;
+            for (int s = 0; s < a.k; ++s) {
+                const int ix = ox * a.stride + s - a.pad;
+                if (ix < 0 || ix >= a.W) continue;
+                const v4i xv = *(const v4i*)(x + (((long long)n * a.H + iy) * a.W + ix) * a.C + q * 16);
+                const v4i wv = *(const v4i*)((const unsigned char*)a.w + (long long)(r * a.k + s) * a.C + q * 16);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[e] += byte_of(xv[e >> 2], e & 3) * byte_of(wv[e >> 2], e & 3);
+            }
+        }
+        v4i out = {0, 0, 0, 0};
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            int t = a.shift > 0 ? (acc[e] + (1 << (a.shift - 1))) >> a.shift : acc[e];
+            t = min(max(t, a.lo), a.hi);
+            out[e >> 2] |= (t & 0xFF) << (8 * (e & 3));
+        }
+        *(v4i*)((unsigned char*)a.y + pix * a.C + q * 16) = out;
+    } else {
+        float acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+        for (int r = 0; r < a.k; ++r) {
+            const int iy = oy * a.stride + r - a.pad;
+            if (iy < 0 || iy >= a.H) continue;
+            for (int s = 0; s < a.k; ++s) {
+                const int ix = ox * a.stride + s - a.pad;
+                if (ix < 0 || ix >= a.W) continue;
+                const v4i xv = *(const v4i*)(x + ((((long long)n * a.H + iy) * a.W + ix) * a.C) * 2 + q * 16);
+                const v4i wv = *(const v4i*)((const unsigned char*)a.w + ((long long)(r * a.k + s) * a.C) * 2 + q * 16);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint16_t xe = (uint16_t)((unsigned)xv[e >> 1] >> (16 * (e & 1)));
+                    const uint16_t we = (uint16_t)((unsigned)wv[e >> 1] >> (16 * (e & 1)));
+                    acc[e] = fmaf(bf16_to_f32_m(xe), bf16_to_f32_m(we), acc[e]);
+                }
+            }
+        }
+        const float* bias = (const float*)a.bias + q * 8;
+        v4i out = {0, 0, 0, 0};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float t = fminf(fmaxf(acc[e] + bias[e], a.f_lo), a.f_hi);
+            out[e >> 1] |= (int)((unsigned)f32_to_bf16_rne_m(t) << (16 * (e & 1)));
+        }
+        *(v4i*)((unsigned char*)a.y + (pix * a.C) * 2 + q * 16) = out;
+    }
+}
+
+hipError_t launch_depthwise(const PoolArgs& a, int dtype, hipStream_t s)
+{
+    const int es = dtype == EE_I8 ? 1 : 2;
+    const long long total = (long long)a.B * a.Ho * a.Wo * (a.C * es / 16);
+    if (total <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    if (dtype == EE_I8) hipLaunchKernelGGL(depthwise_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(depthwise_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ---- max-pool k x k over the in-range taps ---------------------------------------------------------
+template <int ES>
+__global__ __launch_bounds__(256) void maxpool_kernel(PoolArgs a)
+{
+    const int cchunks = a.C * ES / 16;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)a.B * a.Ho * a.Wo * cchunks) return;
+    const int q = (int)(idx % cchunks);
+    const long long pix = idx / cchunks;
+    const int ox = (int)(pix % a.Wo), oy = (int)((pix / a.Wo) % a.Ho), n = (int)(pix / ((long long)a.Wo * a.Ho));
+    const unsigned char* x = (const unsigned char*)a.x;
+    constexpr int NE = 16 / ES;
+    float bestf[NE];
+    int besti[NE];
+    bool have = false;
+    v4i bits = {0, 0, 0, 0};
+#pragma unroll
+    for (int e = 0; e < NE; ++e) { besti[e] = -129; bestf[e] = 0.f; }
+    for (int r = 0; r < a.k; ++r) {
+        const int iy = oy * a.stride + r - a.pad;
+        if (iy < 0 || iy >= a.H) continue;
+        for (int s = 0; s < a.k; ++s) {
+            const int ix = ox * a.stride + s - a.pad;
+            if (ix < 0 || ix >= a.W) continue;
+            const v4i xv = *(const v4i*)(x + ((((long long)n * a.H + iy) * a.W + ix) * a.C) * ES + q * 16);
+            if constexpr (ES == 1) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) besti[e] = max(besti[e], byte_of(xv[e >> 2], e & 3));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint16_t xe = (uint16_t)((unsigned)xv[e >> 1] >> (16 * (e & 1)));
+                    const float v = bf16_to_f32_m(xe);
+                    if (!have || v > bestf[e]) {
+                        bestf[e] = v;
+                        bits[e >> 1] = (bits[e >> 1] & ~(0xFFFF << (16 * (e & 1)))) | ((int)xe << (16 * (e & 1)));
+                    }
+                }
+            }
+            have = true;
+        }
+    }
+    if constexpr (ES == 1) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) bits[e >> 2] |= (besti[e] & 0xFF) << (8 * (e & 3));
+    }
+    *(v4i*)((unsigned char*)a.y + (pix * a.C) * ES + q * 16) = bits;
+}
+
+hipError_t launch_maxpool(const PoolArgs& a, int dtype, hipStream_t s)
+{
+    const int es = dtype == EE_I8 ? 1 : 2;
+    const long long total = (long long)a.B * a.Ho * a.Wo * (a.C * es / 16);
+    if (total <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    if (dtype == EE_I8) hipLaunchKernelGGL(maxpool_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(maxpool_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ---- exit head, step 1: global average pool ----------------------------------------------------------
+// grid (pixel splits, B).  Lane = (pixel lane pl, 16-byte channel chunk q); the pixel lanes are reduced
+// through LDS, then one atomic add per channel and workgroup into sums[B][C] (int32: exact in any
+// order).  The bf16 variant runs with a single pixel split, so its float means are plain,
+// deterministic stores.  Needs C * ES / 16 <= 256.
+template <int ES>
+__global__ __launch_bounds__(256) void gap_kernel(HeadArgs a, int pix_per_block)
+{
+    constexpr int NE = 16 / ES;
+    __shared__ int red[256 * NE];
+    const int cchunks = a.C * ES / 16;
+    const int npl = 256 / cchunks;
+    const int b = blockIdx.y;
+    const int q = (int)threadIdx.x % cchunks, pl = (int)threadIdx.x / cchunks;
+    const bool active = pl < npl;
+    const int p0 = blockIdx.x * pix_per_block, p1 = min(a.HW, p0 + pix_per_block);
+    const unsigned char* x = (const unsigned char*)a.act + (long long)b * a.HW * a.C * ES;
+    int acci[NE];
+    float accf[NE];
+#pragma unroll
+    for (int e = 0; e < NE; ++e) { acci[e] = 0; accf[e] = 0.f; }
+    if (active)
+        for (int p = p0 + pl; p < p1; p += npl) {
+            const v4i xv = *(const v4i*)(x + ((long long)p * a.C) * ES + q * 16);
+            if constexpr (ES == 1) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acci[e] += byte_of(xv[e >> 2], e & 3);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) accf[e] += bf16_to_f32_m((uint16_t)((unsigned)xv[e >> 1] >> (16 * (e & 1))));
+            }
+        }
+    if (active) {
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            if constexpr (ES == 1) red[pl * a.C + q * NE + e] = acci[e];
+            else red[pl * a.C + q * NE + e] = __float_as_int(accf[e]);
+        }
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < a.C; c += 256) {
+        if constexpr (ES == 1) {
+            int s = 0;
+            for (int l = 0; l < npl; ++l) s += red[l * a.C + c];
+            atomicAdd(&a.sums[(long long)b * a.C + c], s);
+        } else {
+            float s = 0.f;
+            for (int l = 0; l < npl; ++l) s += __int_as_float(red[l * a.C + c]);
+            ((float*)a.sums)[(long long)b * a.C + c] = s / (float)a.HW;
+        }
+    }
+}
+
+hipError_t launch_head_gap(const HeadArgs& a, int dtype, hipStream_t s)
+{
+    if (a.B <= 0) return hipSuccess;
+    if (dtype == EE_I8) {
+        hipError_t e = hipMemsetAsync(a.sums, 0, sizeof(int32_t) * (size_t)a.B * a.C, s);
+        if (e != hipSuccess) return e;
+        int splits = (1024 + a.B - 1) / a.B;                 // aim at >= 1024 workgroups
+        int ppb = (a.HW + splits - 1) / splits;
+        if (ppb < 16) ppb = a.HW < 16 ? a.HW : 16;
+        splits = (a.HW + ppb - 1) / ppb;
+        hipLaunchKernelGGL(gap_kernel<1>, dim3(splits, a.B), dim3(256), 0, s, a, ppb);
+    } else {
+        hipLaunchKernelGGL(gap_kernel<2>, dim3(1, a.B), dim3(256), 0, s, a, a.HW);
+    }
+    return hipGetLastError();
+}
+
+// ---- exit head, step 2: FC ------------------------------------------------------------------------------
+// grid (class tiles of 16, sample tiles of 16); lane = (class j, sample b).  The reduction over C runs
+// in slabs of 512 channels: the 16 pooled feature rows (requantised on the fly for int8) and the 16
+// weight rows of a slab sit in LDS, rows padded by 16 bytes.
+template <int ES>
+__global__ __launch_bounds__(256) void fc_kernel(HeadArgs a)
+{
+    constexpr int CK = 512;
+    constexpr int ROWG = (ES == 1 ? CK : CK * 4) + 16;       // feature row: int8 (i8) or float (bf16)
+    constexpr int ROWW = CK * ES + 16;
+    __shared__ __attribute__((aligned(16))) unsigned char gs[16 * ROWG];
+    __shared__ __attribute__((aligned(16))) unsigned char ws[16 * ROWW];
+    const int j0 = blockIdx.x * 16, b0 = blockIdx.y * 16;
+    const int jl = threadIdx.x & 15, bl = threadIdx.x >> 4;
+    const int j = j0 + jl, b = b0 + bl;
+    int acci = 0;
+    float accf = 0.f;
+    for (int cbase = 0; cbase < a.C; cbase += CK) {
+        const int cw = min(CK, a.C - cbase);
+        __syncthreads();
+        for (int i = threadIdx.x; i < 16 * cw; i += 256) {
+            const int r = i / cw, c = i - r * cw;
+            const int bb = b0 + r, jj = j0 + r;
+            if constexpr (ES == 1) {
+                int g = 0;
+                if (bb < a.B) {
+                    const int sum = a.sums[(long long)bb * a.C + cbase + c];
+                    g = a.gap_shift > 0 ? (sum + (1 << (a.gap_shift - 1))) >> a.gap_shift : sum;
+                    g = min(max(g, -128), 127);
+                }
+                ((signed char*)(gs + r * ROWG))[c] = (signed char)g;
+                ((signed char*)(ws + r * ROWW))[c] = jj < a.n_cls ? ((const signed char*)a.wfc)[(long long)jj * a.C + cbase + c] : 0;
+            } else {
+                ((float*)(gs + r * ROWG))[c] = bb < a.B ? ((const float*)a.sums)[(long long)bb * a.C + cbase + c] : 0.f;
+                ((uint16_t*)(ws + r * ROWW))[c] = jj < a.n_cls ? ((const uint16_t*)a.wfc)[(long long)jj * a.C + cbase + c] : 0;
+            }
+        }
+        __syncthreads();
+        if constexpr (ES == 1) {
+            const signed char* g = (const signed char*)(gs + bl * ROWG);
+            const signed char* w = (const signed char*)(ws + jl * ROWW);
+            for (int c = 0; c < cw; c += 4) acci = __builtin_amdgcn_sdot4(*(const int*)(g + c), *(const int*)(w + c), acci, false);
+        } else {
+            const float* g = (const float*)(gs + bl * ROWG);
+            const uint16_t* w = (const uint16_t*)(ws + jl * ROWW);
+            for (int c = 0; c < cw; ++c) accf = fmaf(g[c], bf16_to_f32_m(w[c]), accf);
+        }
+    }
+    if (j >= a.n_cls || b >= a.B) return;
+    if constexpr (ES == 1) ((int*)a.logits)[(long long)b * a.n_cls + j] = acci + ((const int*)a.bfc)[j];
+    else ((float*)a.logits)[(long long)b * a.n_cls + j] = a.logit_scale * (accf + ((const float*)a.bfc)[j]);
+}
+
+hipError_t launch_head_fc(const HeadArgs& a, int dtype, hipStream_t s)
+{
+    if (a.B <= 0) return hipSuccess;
+    dim3 grid((a.n_cls + 15) / 16, (a.B + 15) / 16);
+    if (dtype == EE_I8) hipLaunchKernelGGL(fc_kernel<1>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(fc_kernel<2>, grid, dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ---- exit head, step 3: softmax top-1 and the exit decision --------------------------------------------------
+// 2^30 * 2^(-i/256), i = 0..255, rounded to nearest.
+__constant__ uint32_t kExp2[256] = {
+#include "exp2_table.inc"
+};
+static const uint32_t kExp2Host[256] = {
+#include "exp2_table.inc"
+};
+const uint32_t* exp2_table_host() { return kExp2Host; }
+
+template <typename T>
+__device__ __forceinline__ T block_reduce(T v, T* scratch, bool is_max)
+{
+    for (int o = 32; o > 0; o >>= 1) {
+        T other = __shfl_xor(v, o, 64);
+        v = is_max ? (other > v ? other : v) : v + other;
+    }
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch[wave] = v;
+    __syncthreads();
+    T r = scratch[0];
+    for (int w = 1; w < 4; ++w) r = is_max ? (scratch[w] > r ? scratch[w] : r) : r + scratch[w];
+    return r;
+}
+
+// one workgroup per sample.  int8: m = max logit, label = lowest arg-max, S = sum_j T[frac(d_j)] >> (d_j >> f)
+// with d_j = m - a_j (a base-2 softmax denominator in Q30); exits iff S <= s_thr.  bf16: float softmax.
+template <int ES>
+__global__ __launch_bounds__(256) void softmax_kernel(HeadArgs a)
+{
+    __shared__ long long scratch[8];
+    const int b = blockIdx.x;
+    if constexpr (ES == 1) {
+        const int* lg = (const int*)a.logits + (long long)b * a.n_cls;
+        int m = INT32_MIN;
+        for (int j = threadIdx.x; j < a.n_cls; j += 256) m = max(m, lg[j]);
+        m = block_reduce<int>(m, (int*)scratch, true);
+        int arg = INT32_MAX;
+        long long S = 0;
+        const int f = a.frac_bits;
+        for (int j = threadIdx.x; j < a.n_cls; j += 256) {
+            const int v = lg[j];
+            if (v == m) arg = min(arg, j);
+            const long long d = (long long)m - v;
+            const long long q = d >> f;
+            const long long frac = d & ((1ll << f) - 1);
+            const int r = (int)(f >= 8 ? frac >> (f - 8) : frac << (8 - f));
+            S += q >= 31 ? 0 : (long long)(kExp2[r] >> q);
+        }
+        arg = -block_reduce<int>(-arg, (int*)scratch, true);
+        S = block_reduce<long long>(S, scratch, false);
+        if (threadIdx.x == 0) {
+            a.label[b] = arg;
+            a.score[b] = S;
+            a.conf[b] = (float)(1073741824.0 / (double)S);
+            a.flag[b] = (uint8_t)(a.last || S <= a.s_thr);
+        }
+    } else {
+        const float* z = (const float*)a.logits + (long long)b * a.n_cls;
+        float m = -INFINITY;
+        for (int j = threadIdx.x; j < a.n_cls; j += 256) m = fmaxf(m, z[j]);
+        m = block_reduce<float>(m, (float*)scratch, true);
+        int arg = INT32_MAX;
+        float den = 0.f;
+        for (int j = threadIdx.x; j < a.n_cls; j += 256) {
+            if (z[j] == m) arg = min(arg, j);
+            den += expf(z[j] - m);
+        }
+        arg = -block_reduce<int>(-arg, (int*)scratch, true);
+        den = block_reduce<float>(den, (float*)scratch, false);
+        if (threadIdx.x == 0) {
+            const float conf = 1.0f / den;
+            a.label[b] = arg;
+            a.score[b] = 0;
+            a.conf[b] = conf;
+            a.flag[b] = (uint8_t)(a.last || conf >= a.thr);
+        }
+    }
+}
+
+hipError_t launch_head_softmax(const HeadArgs& a, int dtype, hipStream_t s)
+{
+    if (a.B <= 0) return hipSuccess;
+    if (dtype == EE_I8) hipLaunchKernelGGL(softmax_kernel<1>, dim3(a.B), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(softmax_kernel<2>, dim3(a.B), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ---- compaction: survivors keep their order ---------------------------------------------------------------
+// grid (chunks of 16 KiB, b_act).  Every workgroup recomputes its slot's destination = number of
+// survivors in front of it with a ballot-style block count over the (<= 1024) flags, then copies its
+// chunk with 16-byte accesses.
+__global__ __launch_bounds__(256) void compact_kernel(const uint8_t* flag, const unsigned char* src, unsigned char* dst,
+                                                      const int32_t* ids_src, int32_t* ids_dst, int b_act,
+                                                      long long sample_bytes, int dst_off, int* b_rem_out, int* b_rem_out2)
+{
+    const int b = blockIdx.y;
+    int before = 0, total = 0;
+    for (int t0 = 0; t0 < b_act; t0 += 256) {
+        const int t = t0 + threadIdx.x;
+        const int alive = t < b_act && flag[t] == 0;
+        before += __syncthreads_count(alive && t < b);
+        total += __syncthreads_count(alive);
+    }
+    if (blockIdx.x == 0 && b == 0 && threadIdx.x == 0) {
+        if (b_rem_out) *b_rem_out = total;
+        if (b_rem_out2) *b_rem_out2 = total;
+    }
+    if (flag[b]) return;
+    const int d = dst_off + before;
+    if (blockIdx.x == 0 && threadIdx.x == 0 && ids_dst && ids_src) ids_dst[d] = ids_src[b];
+    const long long c0 = (long long)blockIdx.x * 16384;
+    const v4i* s4 = (const v4i*)(src + (long long)b * sample_bytes + c0);
+    v4i* d4 = (v4i*)(dst + (long long)d * sample_bytes + c0);
+    const long long n16 = min((long long)1024, (sample_bytes - c0) / 16);
+    for (long long i = threadIdx.x; i < n16; i += 256) d4[i] = s4[i];
+}
+
+hipError_t launch_compact(const uint8_t* flag, const void* src, void* dst, const int32_t* ids_src, int32_t* ids_dst,
+                          int b_act, int64_t sample_bytes, int dst_off, int* b_rem_out, int* b_rem_out2, hipStream_t s)
+{
+    if (b_act <= 0) return hipSuccess;
+    dim3 grid((unsigned)((sample_bytes + 16383) / 16384), b_act);
+    hipLaunchKernelGGL(compact_kernel, grid, dim3(256), 0, s, flag, (const unsigned char*)src, (unsigned char*)dst,
+                       ids_src, ids_dst, b_act, (long long)sample_bytes, dst_off, b_rem_out, b_rem_out2);
+    return hipGetLastError();
+}
+
+// ---- append / admission: whole samples copied to given slots ---------------------------------------------------
+// src row = ids ? ids[k] : k  (admission gathers pool rows by request id; refill copies rows in order);
+// destination slot = first + k with first = *first_dev when given.
+__global__ __launch_bounds__(256) void copy_rows_kernel(const unsigned char* src, unsigned char* dst, const int32_t* gather_ids,
+                                                        const int32_t* ids_in, int32_t* ids_out, const int* first_dev, int first,
+                                                        int count, long long sample_bytes, int* total_out)
+{
+    const int k = blockIdx.y;
+    const int base = first_dev ? *first_dev : first;
+    if (blockIdx.x == 0 && k == 0 && threadIdx.x == 0 && total_out) *total_out = base + count;
+    if (blockIdx.x == 0 && threadIdx.x == 0 && ids_out && ids_in) ids_out[base + k] = ids_in[k];
+    const long long row = gather_ids ? gather_ids[k] : k;
+    const long long c0 = (long long)blockIdx.x * 16384;
+    const v4i* s4 = (const v4i*)(src + row * sample_bytes + c0);
+    v4i* d4 = (v4i*)(dst + (long long)(base + k) * sample_bytes + c0);
+    const long long n16 = min((long long)1024, (sample_bytes - c0) / 16);
+    for (long long i = threadIdx.x; i < n16; i += 256) d4[i] = s4[i];
+}
+
+hipError_t launch_append(const void* refill, void* dst, const int32_t* refill_ids, int32_t* ids_dst, const int* b_rem_dev,
+                         int b_rem_host, int b_incr, int64_t sample_bytes, int* b_merged_out, hipStream_t s)
+{
+    if (b_incr <= 0) return hipSuccess;
+    dim3 grid((unsigned)((sample_bytes + 16383) / 16384), b_incr);
+    hipLaunchKernelGGL(copy_rows_kernel, grid, dim3(256), 0, s, (const unsigned char*)refill, (unsigned char*)dst,
+                       (const int32_t*)nullptr, refill_ids, ids_dst, b_rem_dev, b_rem_host, b_incr, (long long)sample_bytes, b_merged_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_admit(const void* pool, void* dst, const int32_t* ids, int b, int64_t sample_bytes, hipStream_t s)
+{
+    if (b <= 0) return hipSuccess;
+    dim3 grid((unsigned)((sample_bytes + 16383) / 16384), b);
+    hipLaunchKernelGGL(copy_rows_kernel, grid, dim3(256), 0, s, (const unsigned char*)pool, (unsigned char*)dst, ids,
+                       (const int32_t*)nullptr, (int32_t*)nullptr, (const int*)nullptr, 0, b, (long long)sample_bytes, (int*)nullptr);
+    return hipGetLastError();
+}
+
+}  // namespace ee

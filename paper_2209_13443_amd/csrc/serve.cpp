@@ -1,0 +1,291 @@
+// Stream serving: the exit-aware preemptive scheduler (Algorithm 1) as a plain host-side
+// driver over the three device steps (segment, exit head, compaction / refill).
+//
+// The scheduler is written once against an executor interface; the GPU executor enqueues the
+// kernels and reads the per-slot exit decisions back once per exit boundary (the only
+// device-to-host crossing, as in the paper where B_exit is reported at each exit), the table
+// executor replaces the network by a list of forced exits so that the policy can be tested on
+// its own.
+//
+// Readings of Algorithm 1 where it is silent (kept identical to the documented policy):
+//   - the last segment is processed after the printed loop ends and everyone left exits there;
+//   - B_incr below max(1, min_incr) ends the refill loop; B_rem = 0 ends the round;
+//   - Eq. 4 uses the latency table by segment and entering batch size, with the upper bound
+//     B_rem + B_incr for the merged batch;
+//   - the server idles until the next arrival when the queue is empty; FIFO admission.
+#include <chrono>
+#include <cstring>
+#include <thread>
+
+#include "ee_ctx.hpp"
+
+using namespace ee;
+
+namespace {
+
+struct SlotOutcome { uint8_t flag; int32_t label; float conf; int64_t score; };
+
+// ---- clocks -----------------------------------------------------------------------------------
+struct VirtualClock {
+    const int64_t* lut; int b_max; int64_t t;
+    void start(int64_t t0) { t = t0; }
+    int64_t now() { return t; }
+    void segment_done(int stage, int b) { t += lut[(int64_t)stage * b_max + b - 1]; }
+    void idle_until(int64_t when) { if (when > t) t = when; }
+};
+
+struct WallClock {
+    std::chrono::steady_clock::time_point origin; int64_t t0;
+    void start(int64_t first_arrival) { origin = std::chrono::steady_clock::now(); t0 = first_arrival; }
+    int64_t now() { return t0 + std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - origin).count(); }
+    void segment_done(int, int) {}
+    void idle_until(int64_t when)
+    {
+        while (now() < when) {
+            const int64_t left = when - now();
+            if (left > 200000) std::this_thread::sleep_for(std::chrono::nanoseconds(left - 100000));
+        }
+    }
+};
+
+// ---- executors ------------------------------------------------------------------------------------
+// An executor owns the activations of the two batches Algorithm 1 juggles: the active batch and
+// the catch-up batch.  Slots are implicit: batch slot k of the batch entering segment s lives in
+// row k of that segment's packed input buffer.
+struct TableExec {
+    const int32_t* forced; int n_stages;
+    int admit(const int32_t*, int) { return EE_OK; }
+    int segment(int stage, const int32_t* ids, int b, SlotOutcome* out)
+    {
+        for (int k = 0; k < b; ++k) out[k] = SlotOutcome{(uint8_t)(stage == n_stages - 1 || forced[ids[k]] == stage), -1, 0.f, 0};
+        return EE_OK;
+    }
+    int compact(int, int, int) { return EE_OK; }
+};
+
+struct GpuExec {
+    ee_ctx* ctx; const unsigned char* pool; const float* thr;
+    int32_t* h_ids; int32_t* h_label; float* h_conf; int64_t* h_score; uint8_t* h_flag;
+
+    explicit GpuExec(ee_ctx* c, const void* input_pool) : ctx(c), pool((const unsigned char*)input_pool)
+    {
+        unsigned char* p = (unsigned char*)c->h_pinned;
+        const size_t bm = (size_t)c->b_max;
+        h_score = (int64_t*)p; p += 8 * bm;
+        h_ids = (int32_t*)p; p += 4 * bm;
+        h_label = (int32_t*)p; p += 4 * bm;
+        h_conf = (float*)p; p += 4 * bm;
+        h_flag = (uint8_t*)p;
+    }
+    // A0: copy the queued inputs into slots [0, b) of segment 0's input buffer
+    int admit(const int32_t* ids, int b)
+    {
+        std::memcpy(h_ids, ids, sizeof(int32_t) * (size_t)b);
+        if (hipMemcpyAsync(ctx->d_ids, h_ids, sizeof(int32_t) * (size_t)b, hipMemcpyHostToDevice, ctx->stream) != hipSuccess) return EE_ERR_DEVICE;
+        const int64_t sb = ctx->stage_in_bytes(0);
+        hipError_t e = ctx->timed(EE_K_ADMIT, 0.0, 2.0 * sb * b, [&] { return launch_admit(pool, ctx->in_buf[0], ctx->d_ids, b, sb, ctx->stream); });
+        if (e != hipSuccess) return EE_ERR_DEVICE;
+        // h_ids is reused by the next admission: make sure the copy has been consumed
+        return hipStreamSynchronize(ctx->stream) == hipSuccess ? EE_OK : EE_ERR_DEVICE;
+    }
+    // A1 + A2: segment and exit head on slots [0, b); one read-back of the per-slot outcomes
+    int segment(int stage, const int32_t*, int b, SlotOutcome* out)
+    {
+        int rc = ctx->run_stage(stage, b, ctx->in_buf[stage], ctx->out_buf[stage]);
+        if (!rc) rc = ctx->run_head(stage, b, ctx->out_buf[stage], ctx->net.exits[stage].thr, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag);
+        if (rc) return rc;
+        hipStream_t s = ctx->stream;
+        if (hipMemcpyAsync(h_flag, ctx->d_flag, (size_t)b, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipMemcpyAsync(h_label, ctx->d_label, 4 * (size_t)b, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipMemcpyAsync(h_conf, ctx->d_conf, 4 * (size_t)b, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipMemcpyAsync(h_score, ctx->d_score, 8 * (size_t)b, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess)
+            return EE_ERR_DEVICE;
+        for (int k = 0; k < b; ++k) out[k] = SlotOutcome{h_flag[k], h_label[k], h_conf[k], h_score[k]};
+        return EE_OK;
+    }
+    // A3 / A4: survivors of segment `stage` (flags still on the device) -> next segment's input slots
+    // [dst_off, dst_off + B_rem).  dst_off > 0 merges a catch-up batch behind the parked survivors.
+    int compact(int stage, int b, int dst_off)
+    {
+        if (stage + 1 >= (int)ctx->in_buf.size()) return EE_OK;
+        const int64_t sb = ctx->stage_out_bytes(stage);
+        hipError_t e = ctx->timed(EE_K_COMPACT, 0.0, 2.0 * sb * b, [&] {
+            return launch_compact(ctx->d_flag, ctx->out_buf[stage], ctx->in_buf[stage + 1], nullptr, nullptr, b, sb, dst_off, nullptr, nullptr, ctx->stream);
+        });
+        return e == hipSuccess ? EE_OK : EE_ERR_DEVICE;
+    }
+};
+
+// ---- Algorithm 1 ---------------------------------------------------------------------------------------
+template <class Exec, class Clock>
+class FluidScheduler {
+public:
+    FluidScheduler(Exec& ex, Clock& ck, int n_stages, const ee_trace* tr, const ee_serve_opts* o, ee_result* res,
+                   ee_serve_stats* st, ee_event* ev, int64_t max_ev)
+        : exec(ex), clock(ck), E(n_stages), n(tr->n), arrival(tr->arrival_ns), opts(*o), results(res), stats(st), events(ev), max_events(max_ev),
+          active(o->b_max), fresh(o->b_max), outcome(o->b_max) {}
+
+    int run()
+    {
+        clock.start(arrival[0]);
+        int rc = EE_OK;
+        while (completed < n && !rc) {
+            admit_arrivals();
+            if (queued() == 0) { clock.idle_until(arrival[arrived]); admit_arrivals(); }
+            rc = start_round();
+            for (int i = 0; i < E && !rc && b_act > 0; ++i) {
+                rc = proc_until_exit(active, b_act, i, /*catchup=*/false, /*merge_at=*/0);
+                if (rc || i == E - 1 || b_act == 0) break;
+                if (opts.refill) rc = refill_at_exit(i);
+            }
+        }
+        stats->end_time_ns = clock.now();
+        return rc;
+    }
+
+private:
+    Exec& exec; Clock& clock;
+    const int E; const int64_t n; const int64_t* arrival; const ee_serve_opts opts;
+    ee_result* results; ee_serve_stats* stats; ee_event* events; const int64_t max_events;
+    std::vector<int32_t> active, fresh;      // request ids per slot
+    std::vector<SlotOutcome> outcome;
+    int b_act = 0;
+    int64_t arrived = 0, popped = 0, completed = 0;
+
+    int64_t queued() const { return arrived - popped; }                       // N_Q
+    void admit_arrivals() { const int64_t t = clock.now(); while (arrived < n && arrival[arrived] <= t) ++arrived; }
+    int64_t lut(int s, int b) const { return opts.lut_ns[(int64_t)s * opts.b_max + b - 1]; }
+    void log(int kind, int stage, int b, int aux)
+    {
+        if (events && stats->n_events < max_events) events[stats->n_events] = ee_event{clock.now(), kind, stage, b, aux};
+        stats->n_events++;
+    }
+    void pop(std::vector<int32_t>& ids, int count) { for (int k = 0; k < count; ++k) ids[k] = (int32_t)popped++; }
+
+    int start_round()
+    {
+        b_act = (int)std::min<int64_t>(queued(), opts.b_max);                 // B_act <- min(N_Q, B_max)
+        pop(active, b_act);
+        stats->rounds++;
+        log(EE_EV_ROUND, 0, b_act, 0);
+        return exec.admit(active.data(), b_act);
+    }
+
+    // ProcUntilExit for one segment: run it, book the samples that leave, keep the survivors packed.
+    // `b` is updated to the number of survivors.
+    int proc_until_exit(std::vector<int32_t>& ids, int& b, int stage, bool catchup, int merge_at)
+    {
+        log(catchup ? EE_EV_PROC_CATCHUP : EE_EV_PROC, stage, b, 0);
+        stats->seg_runs[stage]++;
+        stats->seg_samples[stage] += b;
+        int rc = exec.segment(stage, ids.data(), b, outcome.data());
+        if (rc) return rc;
+        clock.segment_done(stage, b);
+        const int64_t t = clock.now();
+        int kept = 0;
+        for (int k = 0; k < b; ++k) {
+            const SlotOutcome& o = outcome[k];
+            if (o.flag) {
+                ee_result& r = results[ids[k]];
+                r.exit_idx = stage; r.label = o.label; r.conf = o.conf; r.pad_ = 0; r.score = o.score;
+                r.latency_ns = t - arrival[ids[k]];
+                ++completed;
+            } else {
+                ids[kept++] = ids[k];
+            }
+        }
+        if (kept > 0) rc = exec.compact(stage, b, merge_at);
+        b = kept;
+        return rc;
+    }
+
+    // The inner loop of Algorithm 1 at exit i: while there is room, take B_incr requests, check the
+    // SLO criterion, let them catch up to exit i and merge them behind the parked survivors.
+    int refill_at_exit(int i)
+    {
+        int b_rem = b_act;
+        const int min_incr = std::max(1, (int)opts.min_incr);
+        while (b_rem < opts.b_max) {
+            admit_arrivals();
+            const int b_slack = opts.b_max - b_rem;
+            const int b_incr = (int)std::min<int64_t>(queued(), b_slack);
+            if (b_incr < min_incr) break;
+            int64_t t_overhead = 0;                                               // Eq. 4
+            for (int s = 0; s <= i; ++s) t_overhead += lut(s, b_incr);
+            for (int s = i + 1; s < E; ++s) t_overhead += lut(s, b_rem + b_incr);
+            bool accept = true;
+            if (opts.t_slo_ns >= 0) {                                             // Eq. 3
+                int64_t oldest = arrival[active[0]];
+                for (int k = 1; k < b_rem; ++k) oldest = std::min(oldest, arrival[active[k]]);
+                const int64_t t_slack = opts.t_slo_ns - (clock.now() - oldest);
+                accept = t_overhead < t_slack;
+            }
+            stats->criterion_evals++;
+            log(EE_EV_CRITERION, i, b_incr, accept ? 1 : 0);
+            if (!accept) break;
+            stats->preemptions++;                                                 // the survivors stay parked in their slots
+            int b_new = b_incr;
+            pop(fresh, b_new);
+            int rc = exec.admit(fresh.data(), b_new);
+            for (int s = 0; s <= i && !rc && b_new > 0; ++s)                      // catch-up run, no nested refill
+                rc = proc_until_exit(fresh, b_new, s, true, s == i ? b_rem : 0);
+            if (rc) return rc;
+            for (int k = 0; k < b_new; ++k) active[b_rem + k] = fresh[k];
+            b_rem += b_new;                                                       // B_merged
+            log(EE_EV_MERGE, i, b_rem, b_new);
+        }
+        b_act = b_rem;
+        return EE_OK;
+    }
+};
+
+int check_serve_args(const ee_trace* tr, const ee_serve_opts* o, const ee_result* res, int n_stages)
+{
+    if (!tr || !o || tr->n < 0 || (tr->n > 0 && (!tr->arrival_ns || !res))) return EE_ERR_ARG;
+    if (o->b_max < 1 || o->b_max > 1024 || !o->lut_ns || n_stages < 1 || n_stages > 8) return EE_ERR_ARG;
+    if (o->clock != 0 && o->clock != 1) return EE_ERR_ARG;
+    if (tr->n > INT32_MAX) return EE_ERR_OVERFLOW;
+    for (int64_t k = 1; k < tr->n; ++k)
+        if (tr->arrival_ns[k] < tr->arrival_ns[k - 1]) return EE_ERR_ARG;
+    return EE_OK;
+}
+
+}  // namespace
+
+extern "C" int ee_serve_stream(ee_ctx* ctx, const ee_trace* trace, const void* input_pool, const ee_serve_opts* opts,
+                               ee_result* results, ee_serve_stats* stats, ee_event* events, int64_t max_events)
+{
+    if (!ctx) return EE_ERR_ARG;
+    const int n_stages = (int)ctx->net.stages.size();
+    int rc = check_serve_args(trace, opts, results, n_stages);
+    if (rc) return rc;
+    if (opts->b_max > ctx->b_max) return EE_ERR_ARG;
+    ee_serve_stats local;
+    if (!stats) stats = &local;
+    std::memset(stats, 0, sizeof *stats);
+    if (trace->n == 0) return EE_OK;
+    if (!input_pool || (reinterpret_cast<uintptr_t>(input_pool) & 15u)) return EE_ERR_ARG;
+    GpuExec exec(ctx, input_pool);
+    if (opts->clock == 1) {
+        VirtualClock ck{opts->lut_ns, opts->b_max, 0};
+        return FluidScheduler<GpuExec, VirtualClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run();
+    }
+    WallClock ck{};
+    return FluidScheduler<GpuExec, WallClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run();
+}
+
+extern "C" int ee_schedule_sim(int n_stages, const ee_trace* trace, const int32_t* forced_exit, const ee_serve_opts* opts,
+                               ee_result* results, ee_serve_stats* stats, ee_event* events, int64_t max_events)
+{
+    int rc = check_serve_args(trace, opts, results, n_stages);
+    if (rc) return rc;
+    if (opts->clock != 1 || (trace->n > 0 && !forced_exit)) return EE_ERR_ARG;
+    ee_serve_stats local;
+    if (!stats) stats = &local;
+    std::memset(stats, 0, sizeof *stats);
+    if (trace->n == 0) return EE_OK;
+    TableExec exec{forced_exit, n_stages};
+    VirtualClock ck{opts->lut_ns, opts->b_max, 0};
+    return FluidScheduler<TableExec, VirtualClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run();
+}

@@ -1,0 +1,287 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element.
+
+int8 networks must match bit for bit (activations, logits, labels, scores, exit flags, compaction
+order, and on the virtual clock the whole schedule).  bf16 networks: logits within 2e-2 of the
+per-sample max-norm, confidences within 1e-3, exit decisions equal unless the oracle's confidence is
+within 1e-3 of the threshold."""
+import sys
+
+import numpy as np
+import pytest
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+@pytest.fixture(scope="module")
+def ee():
+    import paper_2209_13443_amd as ee
+    return ee
+
+
+def dev(torch, a):
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t, like):
+    a = t.cpu().numpy()
+    return a.view(np.uint16) if like.dtype == np.uint16 else a
+
+
+I8_NETS = ["tiny_i8", "zoo_i8", "resnet50_small_i8", "resnet18_small_i8", "mobilenetv2_small_i8"]
+
+
+@pytest.mark.parametrize("name", I8_NETS)
+def test_int8_segments_and_heads_bit_exact(torch, ee, orc, name):
+    blob = W.load_net(name)
+    eng = ee.Engine(blob, 16)
+    x = W.input_pool(blob, 13)
+    for b in (1, 13, 6):                                   # ragged batches, smaller after larger
+        act = x[:b]
+        for s in range(blob.n_stages):
+            say(f"[case] {name} segment {s} b={b}")
+            ref = orc.stage_forward(blob, s, act)
+            got = eng.stage_forward(s, dev(torch, act), ref.shape[1:])
+            torch.cuda.synchronize()
+            got = host(got, ref)
+            assert np.array_equal(got, ref), f"{name} stage {s} b={b}: {np.count_nonzero(got != ref)} of {ref.size} differ"
+            thr = float(blob.exits[s]["thr"])
+            lab, conf, score, flag, logits = orc.exit_head(blob, s, ref, thr, want_logits=True)
+            glab, gconf, gscore, gflag = eng.exit_head(s, dev(torch, ref), thr)
+            glog = eng.last_logits(b, logits.shape[1])
+            assert np.array_equal(glog, logits)
+            assert np.array_equal(glab.cpu().numpy(), lab) and np.array_equal(gscore.cpu().numpy(), score)
+            assert np.array_equal(gflag.cpu().numpy(), flag)
+            assert np.allclose(gconf.cpu().numpy(), conf, rtol=1e-6, atol=0)
+            act = ref
+    eng.close()
+
+
+@pytest.mark.parametrize("tile", [1, 2, 3])
+@pytest.mark.parametrize("name", ["zoo_i8", "resnet50_small_i8"])
+def test_int8_every_conv_tiling_bit_exact(torch, ee, orc, name, tile):
+    blob = W.load_net(name)
+    eng = ee.Engine(blob, 8)
+    x = W.input_pool(blob, 5)
+    old = ee.tune_conv_tile(tile)
+    try:
+        act = x
+        for s in range(blob.n_stages):
+            say(f"[case] {name} tile {tile} segment {s}")
+            ref = orc.stage_forward(blob, s, act)
+            got = host(eng.stage_forward(s, dev(torch, act), ref.shape[1:]), ref)
+            assert np.array_equal(got, ref), f"tile {tile} stage {s}"
+            act = ref
+    finally:
+        ee.tune_conv_tile(old)
+    eng.close()
+
+
+def test_thresholds_zero_and_above_one(torch, ee, orc):
+    blob = W.load_net("tiny_i8")
+    eng = ee.Engine(blob, 8)
+    x = W.input_pool(blob, 8)
+    a0 = eng.stage_forward(0, dev(torch, x), blob.stage_out_shape(0))
+    assert np.all(eng.exit_head(0, a0, 0.0)[3].cpu().numpy() == 1)       # threshold 0: everyone leaves at exit 1
+    assert np.all(eng.exit_head(0, a0, 1.5)[3].cpu().numpy() == 0)       # threshold > 1: nobody leaves early
+    a1 = eng.stage_forward(1, a0, blob.stage_out_shape(1))
+    a2 = eng.stage_forward(2, a1, blob.stage_out_shape(2))
+    assert np.all(eng.exit_head(2, a2, 1.5)[3].cpu().numpy() == 1)       # ... and the last exit takes everybody
+    eng.close()
+
+
+def test_edge_arguments_on_device(torch, ee):
+    blob = W.load_net("tiny_i8")
+    eng = ee.Engine(blob, 4)
+    lib = ee.raw()
+    x = dev(torch, W.input_pool(blob, 4))
+    out = torch.empty((4,) + blob.stage_out_shape(0), dtype=torch.int8, device="cuda")
+    assert lib.ee_stage_forward(eng._h, 0, 0, None, None) == ee.EE_OK           # empty batch is a no-op
+    assert lib.ee_stage_forward(eng._h, 0, 5, x.data_ptr(), out.data_ptr()) == ee.EE_ERR_ARG   # above b_max
+    assert lib.ee_stage_forward(eng._h, 3, 1, x.data_ptr(), out.data_ptr()) == ee.EE_ERR_ARG   # no such segment
+    assert lib.ee_stage_forward(eng._h, 0, 1, x.data_ptr() + 1, out.data_ptr()) == ee.EE_ERR_ARG  # misaligned
+    assert lib.ee_stage_forward(eng._h, 0, 1, x.data_ptr(), x.data_ptr()) == ee.EE_ERR_ARG     # aliasing
+    assert lib.ee_exit_head(eng._h, 0, 0, None, 0.5, None, None, None, None) == ee.EE_OK
+    eng.close()
+
+
+def test_compaction_and_refill(torch, ee, orc):
+    blob = W.load_net("zoo_i8")
+    b_max = 24
+    eng = ee.Engine(blob, b_max)
+    rng = np.random.default_rng(7)
+    shape = blob.stage_out_shape(0)
+    act = rng.integers(-128, 128, size=(16,) + shape).astype(np.int8)
+    refill = rng.integers(-128, 128, size=(5,) + shape).astype(np.int8)
+    ids = rng.permutation(1000)[:16].astype(np.int32)
+    rids = (2000 + np.arange(5)).astype(np.int32)
+    patterns = [np.zeros(16, np.uint8), np.ones(16, np.uint8)] + [rng.integers(0, 2, 16).astype(np.uint8) for _ in range(6)]
+    for k, flags in enumerate(patterns):
+        for with_refill in (False, True):
+            say(f"[case] compaction pattern {k} refill={with_refill}")
+            r_act, r_ids = (refill, rids) if with_refill else (None, None)
+            ref = orc.compact_refill(flags, act, ids, r_act, r_ids)
+            got = eng.compact_refill(0, dev(torch, flags), dev(torch, act), dev(torch, ids),
+                                     None if r_act is None else dev(torch, r_act), None if r_ids is None else dev(torch, r_ids))
+            assert got[2] == ref[2] and got[3] == ref[3]
+            assert np.array_equal(got[0].cpu().numpy(), ref[0]) and np.array_equal(got[1].cpu().numpy(), ref[1])
+    eng.close()
+
+
+def synthetic_lut(n_stages, b_max):
+    return (np.arange(1, n_stages + 1)[:, None] * 1000 + np.arange(b_max)[None, :] * 37).astype(np.int64)
+
+
+SERVE_CASES = [  # name, n, b_max, arrival gap ns, slo, min_incr, refill
+    ("tiny_i8", 64, 8, 0, -1, 1, 1),            # configuration 1: 64 requests, 8 slots, all at t = 0
+    ("tiny_i8", 64, 8, 450, 9000, 1, 1),
+    ("tiny_i8", 50, 5, 300, -1, 2, 1),
+    ("tiny_i8", 40, 8, 0, -1, 1, 0),
+    ("zoo_i8", 48, 8, 700, -1, 1, 1),
+    ("resnet50_small_i8", 40, 8, 900, 30000, 1, 1),
+    ("mobilenetv2_small_i8", 32, 8, 600, -1, 1, 1),
+]
+
+
+@pytest.mark.parametrize("case", SERVE_CASES)
+def test_serve_stream_virtual_clock_matches_oracle(torch, ee, orc, case):
+    name, n, b_max, gap, slo, min_incr, refill = case
+    say(f"[case] serve {case}")
+    blob = W.load_net(name)
+    pool = W.input_pool(blob, n)
+    arrivals = (np.arange(n) * gap).astype(np.int64)
+    lut = synthetic_lut(blob.n_stages, b_max)
+    ref, rst, rev = orc.serve_stream(blob, arrivals, pool, b_max, lut, t_slo_ns=slo, min_incr=min_incr, refill=refill, max_events=5000)
+    eng = ee.Engine(blob, b_max)
+    got, gst, gev = eng.serve_stream(arrivals, dev(torch, pool), lut, clock=1, t_slo_ns=slo, min_incr=min_incr, refill=refill, max_events=5000)
+    for f in ("exit_idx", "label", "score", "latency_ns"):
+        assert np.array_equal(got[f], ref[f]), f
+    assert np.allclose(got["conf"], ref["conf"], rtol=1e-6)
+    assert gst == rst
+    assert np.array_equal(gev, rev)
+    counts = np.bincount(got["exit_idx"], minlength=blob.n_stages)
+    assert counts.sum() == n                                              # everyone leaves exactly once
+    eng.close()
+
+
+def test_serve_stream_wall_clock_invariants(torch, ee, orc):
+    blob = W.load_net("tiny_i8")
+    n, b_max = 64, 8
+    pool = W.input_pool(blob, n)
+    alone = orc.forward_alone(blob, pool)
+    eng = ee.Engine(blob, b_max)
+    lut = eng.measure_lut(reps=2)
+    assert lut.shape == (3, b_max) and np.all(lut > 0)
+    arrivals = (np.arange(n) * 20000).astype(np.int64)
+    got, st, _ = eng.serve_stream(arrivals, dev(torch, pool), lut, clock=0)
+    for f in ("exit_idx", "label", "score"):
+        assert np.array_equal(got[f], alone[f]), f                       # schedule independence
+    assert np.all(got["latency_ns"] > 0)
+    assert st["seg_samples"][0] == n
+    eng.close()
+
+
+# ---- full-size configurations: sampled outputs, in the launch configuration the benchmark uses ----
+FULL = [("resnet18_i8", 128, 32, 0, [0, 17, 31, 64, 100, 127]),
+        ("resnet50_i8", 192, 64, 1, [0, 5, 63, 64, 130, 191]),
+        ("mobilenetv2_i8", 192, 64, 1, [1, 40, 63, 99, 150, 190])]
+
+
+@pytest.mark.parametrize("case", FULL)
+def test_full_size_sampled_parity(torch, ee, orc, case):
+    name, n, b_max, refill, sample_ids = case
+    say(f"[case] full-size {name} n={n} b_max={b_max}")
+    blob = W.load_net(name)
+    pool = W.input_pool(blob, n)
+    eng = ee.Engine(blob, b_max)
+    lut = synthetic_lut(blob.n_stages, b_max)
+    got, st, _ = eng.serve_stream(np.zeros(n, np.int64), dev(torch, pool), lut, clock=1, refill=refill)
+    ref = orc.forward_alone(blob, pool[sample_ids])
+    for f in ("exit_idx", "label", "score"):
+        assert np.array_equal(got[f][sample_ids], ref[f]), f
+    counts = np.bincount(got["exit_idx"], minlength=blob.n_stages)
+    assert counts.sum() == n and np.all(got["exit_idx"] >= 0)
+    say(f"[info] {name} exit counts {counts.tolist()} mean batch {[round(a / max(b, 1), 1) for a, b in zip(st['seg_samples'], st['seg_runs'])]}")
+    # one whole segment at the full batch, element by element on sampled slots
+    act = eng.stage_forward(0, dev(torch, pool[:b_max]), blob.stage_out_shape(0))
+    slots = [0, b_max // 2, b_max - 1]
+    ref0 = orc.stage_forward(blob, 0, pool[:b_max][slots])
+    assert np.array_equal(act.cpu().numpy()[slots], ref0)
+    eng.close()
+
+
+# ---- bf16 ---------------------------------------------------------------------------------------------
+def bf16_to_f32(a):
+    return W.bf16_bits_to_f32(a)
+
+
+@pytest.mark.parametrize("name", ["tiny_bf16", "zoo_bf16", "resnet50_small_bf16"])
+def test_bf16_within_tolerance(torch, ee, orc, name):
+    blob = W.load_net(name)
+    eng = ee.Engine(blob, 16)
+    x = W.input_pool(blob, 12)
+    for tile in (0, 1, 2, 3):
+        ee.tune_conv_tile(tile)
+        act = x
+        for s in range(blob.n_stages):
+            say(f"[case] {name} tile {tile} segment {s}")
+            ref = orc.stage_forward(blob, s, act)
+            got = host(eng.stage_forward(s, dev(torch, act), ref.shape[1:]), ref)
+            r, g = bf16_to_f32(ref).astype(np.float64), bf16_to_f32(got).astype(np.float64)
+            scale = np.abs(r).reshape(r.shape[0], -1).max(axis=1).reshape(-1, 1, 1, 1) + 1e-30
+            assert np.all(np.abs(g - r) <= 2e-2 * scale), f"stage {s}: {np.max(np.abs(g - r) / scale)}"
+            thr = float(blob.exits[s]["thr"])
+            lab, conf, _, flag, logits = orc.exit_head(blob, s, ref, thr, want_logits=True)
+            glab, gconf, _, gflag = eng.exit_head(s, dev(torch, ref), thr)
+            glog = eng.last_logits(ref.shape[0], logits.shape[1])
+            zmax = np.abs(logits).max(axis=1, keepdims=True)
+            assert np.all(np.abs(glog - logits) <= 2e-2 * zmax)
+            assert np.all(np.abs(gconf.cpu().numpy() - conf) <= 1e-3)
+            clear = np.abs(conf - np.float32(thr)) >= 1e-3
+            assert np.array_equal(gflag.cpu().numpy()[clear], flag[clear])
+            top2 = np.sort(logits, axis=1)[:, -2:]
+            sure = (top2[:, 1] - top2[:, 0]) > 4e-2 * zmax[:, 0]
+            assert np.array_equal(glab.cpu().numpy()[sure], lab[sure])
+            act = ref
+    ee.tune_conv_tile(0)
+    eng.close()
+
+
+def test_bf16_serve_stream_decisions(torch, ee, orc):
+    name, n, b_max = "tiny_bf16", 64, 8
+    blob = W.load_net(name)
+    pool = W.input_pool(blob, n)
+    eng = ee.Engine(blob, b_max)
+    lut = synthetic_lut(blob.n_stages, b_max)
+    got, st, _ = eng.serve_stream(np.zeros(n, np.int64), dev(torch, pool), lut, clock=1)
+    # the oracle's view of every sample at every exit it reaches
+    act, alive = pool, np.arange(n)
+    unclear = np.zeros(n, bool)
+    ref_exit = np.full(n, -1)
+    for s in range(blob.n_stages):
+        act = orc.stage_forward(blob, s, act)
+        thr = float(blob.exits[s]["thr"])
+        lab, conf, _, flag = orc.exit_head(blob, s, act, thr)
+        if s < blob.n_stages - 1:
+            unclear[alive[np.abs(conf - np.float32(thr)) < 1e-3]] = True
+        ref_exit[alive[flag == 1]] = s
+        act, alive = act[flag == 0], alive[flag == 0]
+    ok = ~unclear
+    assert np.array_equal(got["exit_idx"][ok], ref_exit[ok])
+    assert np.bincount(got["exit_idx"], minlength=3).sum() == n
+    eng.close()

@@ -1,0 +1,125 @@
+"""Host-side tests of libee.so that need no GPU: the library loads and exports the C ABI,
+argument validation, blob validation, the exp2 table, and the scheduler against the oracle."""
+import ctypes as C
+import os
+import re
+from decimal import Decimal, getcontext
+
+import numpy as np
+import pytest
+
+import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def ee():
+    import paper_2209_13443_amd as ee
+    return ee
+
+
+def test_library_exports_every_declared_symbol(ee):
+    header = open(os.path.join(ROOT, "include", "ee.h")).read()
+    declared = set(re.findall(r"\b(ee_[a-z0-9_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    lib = ee.raw()
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in include/ee.h but not exported"
+    assert set(ee.SYMBOLS) <= declared
+
+
+def test_strerror(ee):
+    assert ee.strerror(0) == "ok"
+    assert "argument" in ee.strerror(ee.EE_ERR_ARG)
+    assert ee.strerror(-99) == "unknown status"
+
+
+def test_blob_check_matches_oracle_verdicts(ee, orc):
+    for name in ("tiny_i8", "resnet50_small_i8", "mobilenetv2_small_i8", "tiny_bf16"):
+        b = W.build_net(name)
+        assert ee.blob_check(b.buffer()) == ee.EE_OK == orc.blob_check(b)
+    b = W.build_net("tiny_i8")
+    b.ops[1]["c_in"] = 17
+    assert ee.blob_check(b.buffer()) == ee.EE_ERR_SHAPE
+    b = W.build_net("tiny_i8")
+    b.ops[2]["res"] = 0            # residual of the wrong shape
+    assert ee.blob_check(b.buffer()) == ee.EE_ERR_SHAPE == orc.blob_check(b)
+    b = W.build_net("tiny_i8")
+    b.header[0]["dtype"] = 5
+    assert ee.blob_check(b.buffer()) == ee.EE_ERR_UNSUPPORTED
+    assert ee.blob_check(np.zeros(64, np.uint8)) == ee.EE_ERR_ARG
+    junk = W.build_net("tiny_i8").buffer().copy()
+    junk[:8] = 0
+    assert ee.blob_check(junk) == ee.EE_ERR_ARG
+
+
+def test_null_and_range_arguments_are_rejected_without_a_gpu(ee):
+    lib = ee.raw()
+    assert lib.ee_stage_forward(None, 0, 1, None, None) == ee.EE_ERR_ARG
+    assert lib.ee_exit_head(None, 0, 1, None, 0.5, None, None, None, None) == ee.EE_ERR_ARG
+    assert lib.ee_compact_refill(None, 0, 1, None, None, None, None, None, None, None, 0, None, None) == ee.EE_ERR_ARG
+    assert lib.ee_serve_stream(None, None, None, None, None, None, None, 0) == ee.EE_ERR_ARG
+    assert lib.ee_query(None, None, None, None) == ee.EE_ERR_ARG
+    assert lib.ee_measure_lut(None, 1, None) == ee.EE_ERR_ARG
+    assert lib.ee_destroy(None) == ee.EE_OK
+    h = C.c_void_p()
+    blob = W.build_net("tiny_i8").buffer()
+    assert lib.ee_create(blob.ctypes.data, blob.size, 0, 0, None, C.byref(h)) == ee.EE_ERR_ARG       # b_max = 0
+    assert lib.ee_create(blob.ctypes.data, blob.size, 8, 1, None, C.byref(h)) == ee.EE_ERR_UNSUPPORTED  # dtype mismatch
+    assert lib.ee_create(blob.ctypes.data, 100, 8, 0, None, C.byref(h)) == ee.EE_ERR_ARG             # truncated
+
+
+def test_exp2_table(ee, orc):
+    getcontext().prec = 60
+    ln2 = Decimal(2).ln()
+    t = ee.exp2_table()
+    for i in range(256):
+        exact = (Decimal(2) ** 30) * (-(Decimal(i) / 256) * ln2).exp()
+        assert int(t[i]) == int(exact.to_integral_value(rounding="ROUND_HALF_EVEN"))
+    assert np.array_equal(t, orc.exp2_table())
+
+
+def _case(seed, n=400, n_stages=4, b_max=8, rate=0.02):
+    rng = np.random.default_rng(seed)
+    arrivals = np.floor(np.cumsum(rng.exponential(1.0 / rate, size=n))).astype(np.int64)
+    forced = rng.integers(0, n_stages, size=n).astype(np.int32)
+    lut = (rng.integers(40, 120, size=(n_stages, 1)) + np.arange(b_max)[None, :] * rng.integers(0, 9, size=(n_stages, 1))).astype(np.int64)
+    return arrivals, forced, lut
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_scheduler_matches_oracle_bit_for_bit(ee, orc, seed):
+    b_max = [8, 8, 3, 64, 1, 16, 8, 8][seed]
+    arrivals, forced, lut = _case(seed, b_max=b_max, rate=[0.02, 0.2, 0.05, 0.5, 0.01, 0.1, 0.02, 0.02][seed])
+    slo = [-1, -1, 700, 2000, -1, 900, 0, 400][seed]
+    min_incr = [1, 1, 1, 4, 1, 2, 1, 1][seed]
+    refill = 0 if seed == 4 else 1
+    a, sa, ea = orc.serve_stream(None, arrivals, None, b_max, lut, t_slo_ns=slo, min_incr=min_incr, refill=refill,
+                                 forced_exit=forced, n_stages=4, max_events=20000)
+    b, sb, eb = ee.schedule_sim(4, arrivals, forced, b_max, lut, t_slo_ns=slo, min_incr=min_incr, refill=refill, max_events=20000)
+    assert sa == sb
+    assert np.array_equal(ea, eb)
+    for f in ("exit_idx", "latency_ns"):
+        assert np.array_equal(a[f], b[f])
+
+
+def test_scheduler_argument_errors(ee):
+    arrivals, forced, lut = _case(0)
+    bad = arrivals.copy()
+    bad[5] = bad[4] - 1
+    with pytest.raises(ee.EEError) as e:
+        ee.schedule_sim(4, bad, forced, 8, lut)
+    assert e.value.code == ee.EE_ERR_ARG
+    res, st, _ = ee.schedule_sim(4, arrivals[:0], forced[:0], 8, lut)
+    assert res.size == 0 and st["rounds"] == 0
+
+
+def test_timeline_example_through_the_library(ee):
+    from test_oracle_sched import read_timeline
+    events, samples = read_timeline()
+    arrivals = np.array([0, 0, 5, 5, 5, 5, 15], np.int64)
+    forced = np.array([s[1] - 1 for s in samples], np.int32)
+    res, st, ev = ee.schedule_sim(2, arrivals, forced, 8, np.full((2, 8), 10, np.int64), t_slo_ns=35, max_events=64)
+    assert [(int(e["t_ns"]), int(e["kind"]), int(e["stage"]), int(e["b"]), int(e["aux"])) for e in ev] == events
+    assert [int(r["latency_ns"] + a) for r, a in zip(res, arrivals)] == [s[2] for s in samples]

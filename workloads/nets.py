@@ -159,6 +159,34 @@ def _mobilenetv2(dtype, in_hw=224, n_classes=1000):
     return net
 
 
+def _zoo(dtype):
+    """Test network: every kernel path and awkward shape (odd image sizes, channel counts that are not
+    multiples of 16, 1x1 / 3x3 / 5x5 / 7x7 kernels, strides, residuals, depthwise, max-pool)."""
+    net = _Net(dtype, 36, 44, 3, 37)
+    t = net.begin_stage()
+    t = net.conv(t, 16, 3, 2, 1)
+    t = net.conv(t, 24, 1, 1, 0)
+    t = net.conv(t, 32, 3, 1, 1)
+    t = net.maxpool(t, 3, 2, 1)
+    net.end_stage(t)
+    t = net.begin_stage()
+    short = net.conv(t, 128, 1, 2, 0, act="linear")
+    u = net.conv(t, 64, 1, 1, 0)
+    u = net.conv(u, 64, 3, 2, 1)
+    t = net.conv(u, 128, 1, 1, 0, res=short)
+    u = net.dwconv(t, 3, 1, 1, act="relu6")
+    u = net.conv(u, 128, 1, 1, 0, act="linear", res=t)
+    u = net.dwconv(u, 3, 2, 1, act="relu6")
+    t = net.conv(u, 48, 1, 1, 0, act="linear")
+    net.end_stage(t)
+    t = net.begin_stage()
+    t = net.conv(t, 64, 5, 1, 2)
+    t = net.conv(t, 80, 7, 2, 3)
+    t = net.conv(t, 256, 1, 1, 0, act="relu6")
+    net.end_stage(t)
+    return net
+
+
 CONFIGS = {
     # name: (architecture, dtype, seed offset)
     "tiny_i8": (_tiny, DT_I8, 1),
@@ -172,6 +200,8 @@ CONFIGS = {
     "resnet50_small_i8": (lambda dt: _resnet50(dt, 64, 100, (1, 2, 2, 1)), DT_I8, 14),
     "resnet50_small_bf16": (lambda dt: _resnet50(dt, 64, 100, (1, 2, 2, 1)), DT_BF16, 15),
     "mobilenetv2_small_i8": (lambda dt: _mobilenetv2(dt, 64, 100), DT_I8, 13),
+    "zoo_i8": (_zoo, DT_I8, 21),
+    "zoo_bf16": (_zoo, DT_BF16, 22),
 }
 
 
