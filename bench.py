@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the early-exit serving hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch of synthetic requests: admission, the
+backbone segments on the matrix cores, the exit heads, compaction and slot refill, driven by the
+exit-aware preemptive scheduler on the wall clock.  The default workload is the ResNet-50-style
+int8 stream: 10,000 requests, Poisson arrivals at 1.2x the static-batch throughput measured in
+the same run, 64 batch slots refilled at the exit boundaries.
+
+Prints ONE JSON line (see the keys below).  `--gpus N` with N > 1 is refused: this path is built
+and measured on one GPU only.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"i8": 5000.0, "bf16": 2500.0}          # dense MFMA peak of MI355X, TOP/s resp. TFLOP/s
+WORKLOADS = {
+    "resnet50_i8_stream": dict(net="resnet50_i8", n=10000, b_max=64, refill=1, load=1.2, spikes=False),
+    "resnet50_bf16_stream": dict(net="resnet50_bf16", n=20000, b_max=256, refill=1, load=0.8, spikes=True),
+    "mobilenetv2_i8_refill": dict(net="mobilenetv2_i8", n=4096, b_max=64, refill=1, load=None, spikes=False),
+    "resnet18_i8_static": dict(net="resnet18_i8", n=1024, b_max=32, refill=0, load=None, spikes=False),
+    "tiny_i8": dict(net="tiny_i8", n=64, b_max=8, refill=1, load=None, spikes=False),
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="resnet50_i8_stream", choices=sorted(WORKLOADS))
+    ap.add_argument("--requests", type=int, default=0, help="override the number of requests (0 = the workload's)")
+    ap.add_argument("--min-incr", type=int, default=0, help="smallest catch-up batch (0 = b_max / 4; 1 = Algorithm 1 as printed)")
+    ap.add_argument("--cpu-samples", type=int, default=0, help="samples timed on the CPU oracle (0 = automatic, -1 = skip)")
+    ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket kernels with HIP events in the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures the path on ONE GPU; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2209_13443_amd as ee
+    import workloads as W
+
+    wl = WORKLOADS[args.workload]
+    n = args.requests or wl["n"]
+    b_max = wl["b_max"]
+    blob = W.load_net(wl["net"])
+    dtype = "i8" if blob.dtype == W.DT_I8 else "bf16"
+    torch.cuda.set_device(0)
+    eng = ee.Engine(blob, b_max)
+
+    # synthetic request pool, resident in HBM before any timed region
+    chunks = []
+    for first in range(0, n, 1000):
+        part = W.input_pool(blob, min(1000, n - first), first=first)
+        chunks.append(torch.from_numpy(part.view(np.int16) if part.dtype == np.uint16 else part).cuda())
+    pool = torch.cat(chunks)
+    del chunks
+    torch.cuda.synchronize()
+
+    lut = eng.measure_lut(reps=3)                      # design-time exit-level latency table
+    min_incr = args.min_incr or max(1, b_max // 4)
+
+    # static-batch throughput (model-level batching, everything queued at t = 0) sets the arrival rate
+    zeros = np.zeros(n, np.int64)
+    eng.serve_stream(zeros, pool, lut, clock=0, refill=0)
+    t0 = time.perf_counter()
+    res_static, st_static, _ = eng.serve_stream(zeros, pool, lut, clock=0, refill=0)
+    static_rate = n / (time.perf_counter() - t0)
+    if wl["load"] is None:
+        arrivals = zeros
+    elif wl["spikes"]:
+        arrivals = W.spiky_trace(n, wl["load"] * static_rate)
+    else:
+        arrivals = W.poisson_trace(n, wl["load"] * static_rate)
+
+    def step():
+        return eng.serve_stream(arrivals, pool, lut, clock=0, refill=wl["refill"], min_incr=min_incr)
+
+    timing = not args.no_kernel_timing
+    eng.profile(timing)
+    for _ in range(max(args.warmup, 1) if timing else args.warmup):
+        step()
+    if timing:                                         # event pairs for the whole timed region, created up front
+        per_step = sum(v["launches"] for v in eng.profile_read().values())
+        eng.profile_reserve(int(per_step * (args.steps + 0.5)) + 1024)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        res, st, _ = step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kstats = eng.profile_read()
+    eng.profile(False)
+    value = args.steps * n / elapsed
+
+    # dominant kernel: the MFMA implicit-GEMM convolution
+    conv = kstats["conv_mfma"]
+    roofline = None
+    if conv["launches"]:
+        achieved = conv["ops"] / (conv["ms"] * 1e-3) / 1e12
+        roofline = dict(bound="mfma", kernel="conv_mfma_kernel", achieved=round(achieved, 2), peak=PEAK[dtype],
+                        unit="TOP/s" if dtype == "i8" else "TFLOP/s", frac=round(achieved / PEAK[dtype], 4), traffic=None,
+                        launches=conv["launches"], avg_launch_us=round(conv["ms"] * 1e3 / conv["launches"], 2),
+                        algorithmic_gops_per_launch=round(conv["ops"] / conv["launches"] / 1e9, 3),
+                        hbm_gbps_algorithmic=round(conv["bytes"] / (conv["ms"] * 1e-3) / 1e9, 1))
+    kernels = {k: dict(launches=v["launches"], ms=round(v["ms"], 3),
+                       gbps=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] > 0 else 0.0,
+                       tops=round(v["ops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] > 0 else 0.0)
+               for k, v in kstats.items() if v["launches"]}
+
+    # the CPU oracle on a bounded sample of the same requests, each sample alone until it exits
+    cpu = None
+    if args.cpu_samples >= 0:
+        import oracle
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        per = {"resnet50_i8": 2 * cores, "resnet50_bf16": cores, "resnet18_i8": 4 * cores, "mobilenetv2_i8": 16 * cores}.get(wl["net"], 64)
+        ns = min(n, args.cpu_samples or per)
+        sample = W.input_pool(blob, ns)
+        t0 = time.perf_counter()
+        ref = oracle.forward_alone(blob, sample)
+        dt = time.perf_counter() - t0
+        agree = bool(np.array_equal(ref["exit_idx"], res["exit_idx"][:ns])) if dtype == "i8" else None
+        cpu = dict(value=round(ns / dt, 3), unit="samples/s", cores=cores, kind="oracle",
+                   sample=f"first {ns} requests of the same pool, each alone through the segments until it exits, OpenMP over samples",
+                   seconds=round(dt, 2), exits_agree_with_gpu=agree)
+
+    lat = res["latency_ns"].astype(np.float64)
+    out = {
+        "metric": "samples/sec early-exit CNN stream (1 GPU)", "value": round(value, 1), "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(elapsed / args.steps * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "requests": n, "b_max": b_max, "refill": wl["refill"], "min_incr": min_incr,
+                   "arrival": "poisson" if wl["load"] else "all_at_t0", "arrival_rate_per_s": round(wl["load"] * static_rate, 1) if wl["load"] else None,
+                   "clock": "wall", "t_slo": None},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "static_batch_samples_per_s": round(static_rate, 1),
+        "exit_counts": np.bincount(res["exit_idx"], minlength=eng.n_stages).tolist(),
+        "mean_batch_per_segment": [round(a / max(b, 1), 2) for a, b in zip(st["seg_samples"], st["seg_runs"])],
+        "mean_batch_per_segment_static": [round(a / max(b, 1), 2) for a, b in zip(st_static["seg_samples"], st_static["seg_runs"])],
+        "preemptions": st["preemptions"], "latency_ms_mean": round(lat.mean() / 1e6, 3), "latency_ms_p99": round(float(np.percentile(lat, 99)) / 1e6, 3),
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -142,6 +142,8 @@ typedef struct { int64_t launches; double ms; double ops; double bytes; } ee_ker
  * adds the elapsed times up per kernel class into stats[EE_K_COUNT] (host) and resets the counters.
  * ops = 2 * MACs of the launches, bytes = their algorithmic HBM traffic (each operand once). */
 int ee_profile_enable(ee_ctx* ctx, int enable);
+/* creates event pairs ahead of time so that a timed region does not pay for their creation */
+int ee_profile_reserve(ee_ctx* ctx, int64_t n_pairs);
 int ee_profile_read(ee_ctx* ctx, ee_kernel_stat* stats);
 const char* ee_kernel_name(int kernel_class);
 

@@ -23,7 +23,7 @@ EVENT_DT = np.dtype([("t_ns", "<i8"), ("kind", "<i4"), ("stage", "<i4"), ("b", "
 
 SYMBOLS = ["ee_strerror", "ee_blob_check", "ee_create", "ee_destroy", "ee_query", "ee_stage_forward", "ee_exit_head",
            "ee_compact_refill", "ee_serve_stream", "ee_schedule_sim", "ee_measure_lut", "ee_profile_enable",
-           "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_last_logits"]
+           "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_last_logits", "ee_profile_reserve"]
 
 
 class Trace(C.Structure):
@@ -66,6 +66,7 @@ _lib.ee_measure_lut.argtypes = [_V, C.c_int, _V]
 _lib.ee_last_logits.argtypes = [_V, C.c_int, _V]
 _lib.ee_profile_enable.argtypes = [_V, C.c_int]
 _lib.ee_profile_read.argtypes = [_V, _V]
+_lib.ee_profile_reserve.argtypes = [_V, C.c_int64]
 
 
 class EEError(RuntimeError):
@@ -219,6 +220,9 @@ class Engine:
 
     def profile(self, enable):
         _chk(_lib.ee_profile_enable(self._h, int(enable)))
+
+    def profile_reserve(self, n_pairs):
+        _chk(_lib.ee_profile_reserve(self._h, int(n_pairs)))
 
     def profile_read(self):
         arr = (KernelStat * len(K_NAMES))()

@@ -460,6 +460,17 @@ extern "C" int ee_profile_enable(ee_ctx* ctx, int enable)
     return EE_OK;
 }
 
+extern "C" int ee_profile_reserve(ee_ctx* ctx, int64_t n_pairs)
+{
+    if (!ctx || n_pairs < 0 || n_pairs > (1 << 22)) return EE_ERR_ARG;
+    while ((int64_t)ctx->prof.size() < n_pairs) {
+        ProfRec r{};
+        if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return EE_ERR_DEVICE;
+        ctx->prof.push_back(r);
+    }
+    return EE_OK;
+}
+
 extern "C" int ee_profile_read(ee_ctx* ctx, ee_kernel_stat* stats)
 {
     if (!ctx || !stats) return EE_ERR_ARG;
