@@ -8,6 +8,7 @@ import ctypes as C
 import os
 
 import numpy as np
+import torch  # noqa: F401  -- first: libee.so must bind to the HIP runtime PyTorch has already loaded
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libee.so")
