@@ -139,12 +139,13 @@ enum { EE_K_CONV_MFMA = 0, EE_K_CONV_FIRST = 1, EE_K_CONV_DIRECT = 2, EE_K_DEPTH
        EE_K_COUNT = 11 };
 typedef struct { int64_t launches; double ms; double ops; double bytes; } ee_kernel_stat;
 /* enable = 1 brackets every kernel launch with a pair of HIP events; ee_profile_read synchronises,
- * adds the elapsed times up per kernel class into stats[EE_K_COUNT] (host) and resets the counters.
+ * adds the elapsed times up per kernel class into stats[EE_K_COUNT] (host) and, when per_layer is not
+ * NULL, per layer of the network into per_layer[number of layers] (host), then resets the counters.
  * ops = 2 * MACs of the launches, bytes = their algorithmic HBM traffic (each operand once). */
 int ee_profile_enable(ee_ctx* ctx, int enable);
 /* creates event pairs ahead of time so that a timed region does not pay for their creation */
 int ee_profile_reserve(ee_ctx* ctx, int64_t n_pairs);
-int ee_profile_read(ee_ctx* ctx, ee_kernel_stat* stats);
+int ee_profile_read(ee_ctx* ctx, ee_kernel_stat* stats, ee_kernel_stat* per_layer);
 const char* ee_kernel_name(int kernel_class);
 
 /* Tuning / test control of the convolution tiling, process-wide: 0 = chosen per layer and active

@@ -66,7 +66,7 @@ _lib.ee_schedule_sim.argtypes = [C.c_int, C.POINTER(Trace), _V, C.POINTER(ServeO
 _lib.ee_measure_lut.argtypes = [_V, C.c_int, _V]
 _lib.ee_last_logits.argtypes = [_V, C.c_int, _V]
 _lib.ee_profile_enable.argtypes = [_V, C.c_int]
-_lib.ee_profile_read.argtypes = [_V, _V]
+_lib.ee_profile_read.argtypes = [_V, _V, _V]
 _lib.ee_profile_reserve.argtypes = [_V, C.c_int64]
 
 
@@ -225,8 +225,12 @@ class Engine:
     def profile_reserve(self, n_pairs):
         _chk(_lib.ee_profile_reserve(self._h, int(n_pairs)))
 
-    def profile_read(self):
+    def profile_read(self, n_layers=0):
         arr = (KernelStat * len(K_NAMES))()
-        _chk(_lib.ee_profile_read(self._h, arr))
-        return {K_NAMES[i]: dict(launches=arr[i].launches, ms=arr[i].ms, ops=arr[i].ops, bytes=arr[i].bytes)
-                for i in range(len(K_NAMES))}
+        lay = (KernelStat * n_layers)() if n_layers else None
+        _chk(_lib.ee_profile_read(self._h, arr, lay))
+        cls = {K_NAMES[i]: dict(launches=arr[i].launches, ms=arr[i].ms, ops=arr[i].ops, bytes=arr[i].bytes)
+               for i in range(len(K_NAMES))}
+        if not n_layers:
+            return cls
+        return cls, [dict(launches=x.launches, ms=x.ms, ops=x.ops, bytes=x.bytes) for x in lay]

@@ -309,15 +309,15 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out)
                 a.x = src; a.mode = 0;
             }
             const int cls = p.impl == IMPL_MFMA ? EE_K_CONV_MFMA : EE_K_CONV_FIRST;
-            e = timed(cls, ops, bytes, [&] { return dt == EE_I8 ? launch_conv_mfma_i8(a, stream) : launch_conv_mfma_bf16(a, stream); });
+            e = timed(cls, ops, bytes, [&] { return dt == EE_I8 ? launch_conv_mfma_i8(a, stream) : launch_conv_mfma_bf16(a, stream); }, st.first_op + k);
         } else if (p.impl == IMPL_DIRECT) {
             DirectConvArgs a{src, p.w_dev, p.b_dev, res, dst, b * d.h_out * d.w_out, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.c_out,
                              d.kh, d.kw, d.stride, d.pad, d.shift, d.res_shift, d.lo, d.hi, d.f_lo, d.f_hi};
-            e = timed(EE_K_CONV_DIRECT, ops, bytes, [&] { return launch_conv_direct(a, dt, stream); });
+            e = timed(EE_K_CONV_DIRECT, ops, bytes, [&] { return launch_conv_direct(a, dt, stream); }, st.first_op + k);
         } else {
             PoolArgs a{src, p.w_dev, p.b_dev, dst, b, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.kh, d.stride, d.pad, d.shift, d.lo, d.hi, d.f_lo, d.f_hi};
-            if (p.impl == IMPL_DW) e = timed(EE_K_DEPTHWISE, ops, bytes, [&] { return launch_depthwise(a, dt, stream); });
-            else e = timed(EE_K_MAXPOOL, 0.0, bytes, [&] { return launch_maxpool(a, dt, stream); });
+            if (p.impl == IMPL_DW) e = timed(EE_K_DEPTHWISE, ops, bytes, [&] { return launch_depthwise(a, dt, stream); }, st.first_op + k);
+            else e = timed(EE_K_MAXPOOL, 0.0, bytes, [&] { return launch_maxpool(a, dt, stream); }, st.first_op + k);
         }
         if (e != hipSuccess) return EE_ERR_DEVICE;
     }
@@ -471,11 +471,13 @@ extern "C" int ee_profile_reserve(ee_ctx* ctx, int64_t n_pairs)
     return EE_OK;
 }
 
-extern "C" int ee_profile_read(ee_ctx* ctx, ee_kernel_stat* stats)
+extern "C" int ee_profile_read(ee_ctx* ctx, ee_kernel_stat* stats, ee_kernel_stat* per_layer)
 {
     if (!ctx || !stats) return EE_ERR_ARG;
     if (hipStreamSynchronize(ctx->stream) != hipSuccess) return EE_ERR_DEVICE;
     for (int k = 0; k < EE_K_COUNT; ++k) stats[k] = ee_kernel_stat{0, 0.0, 0.0, 0.0};
+    if (per_layer)
+        for (size_t k = 0; k < ctx->plans.size(); ++k) per_layer[k] = ee_kernel_stat{0, 0.0, 0.0, 0.0};
     for (size_t i = 0; i < ctx->prof_used; ++i) {
         const ProfRec& r = ctx->prof[i];
         float ms = 0.f;
@@ -484,6 +486,12 @@ extern "C" int ee_profile_read(ee_ctx* ctx, ee_kernel_stat* stats)
         stats[r.cls].ms += ms;
         stats[r.cls].ops += r.ops;
         stats[r.cls].bytes += r.bytes;
+        if (per_layer && r.op >= 0) {
+            per_layer[r.op].launches++;
+            per_layer[r.op].ms += ms;
+            per_layer[r.op].ops += r.ops;
+            per_layer[r.op].bytes += r.bytes;
+        }
     }
     ctx->prof_used = 0;
     return EE_OK;

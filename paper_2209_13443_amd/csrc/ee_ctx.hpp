@@ -21,7 +21,7 @@ struct OpPlan {
     double ops_per_sample = 0, bytes_per_sample = 0, weight_bytes = 0;
 };
 
-struct ProfRec { int cls; hipEvent_t e0, e1; double ops, bytes; };
+struct ProfRec { int cls; int op; hipEvent_t e0, e1; double ops, bytes; };
 
 }  // namespace ee
 
@@ -64,11 +64,11 @@ struct ee_ctx {
     int run_head(int stage, int b_act, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag);
     // brackets `launch` with a pair of events when profiling
     template <typename F>
-    hipError_t timed(int cls, double ops, double bytes, F&& launch);
+    hipError_t timed(int cls, double ops, double bytes, F&& launch, int op = -1);
 };
 
 template <typename F>
-hipError_t ee_ctx::timed(int cls, double ops, double bytes, F&& launch)
+hipError_t ee_ctx::timed(int cls, double ops, double bytes, F&& launch, int op)
 {
     if (!profiling) return launch();
     if (prof_used == prof.size()) {
@@ -77,7 +77,7 @@ hipError_t ee_ctx::timed(int cls, double ops, double bytes, F&& launch)
         prof.push_back(r);
     }
     ee::ProfRec& r = prof[prof_used++];
-    r.cls = cls; r.ops = ops; r.bytes = bytes;
+    r.cls = cls; r.op = op; r.ops = ops; r.bytes = bytes;
     hipEventRecord(r.e0, stream);
     hipError_t e = launch();
     hipEventRecord(r.e1, stream);
