@@ -149,8 +149,8 @@ int ee_profile_read(ee_ctx* ctx, ee_kernel_stat* stats, ee_kernel_stat* per_laye
 const char* ee_kernel_name(int kernel_class);
 
 /* Tuning / test control of the convolution tiling, process-wide: 0 = chosen per layer and active
- * batch size (default), 1 = 128x128, 2 = 256x64, 3 = 64x64 (output pixels x output channels per
- * workgroup).  Results never depend on it.  Returns the previous setting, EE_ERR_ARG if out of range. */
+ * batch size (default), 1 = 128x128, 2 = 128x64, 3 = 64x64, 4 = 64x128 (output pixels x output channels
+ * per workgroup).  Results never depend on it.  Returns the previous setting, EE_ERR_ARG if out of range. */
 int ee_tune_conv_tile(int tile);
 
 /* Host copy of the 256-entry table round(2^30 * 2^(-i/256)) used by the integer softmax. */

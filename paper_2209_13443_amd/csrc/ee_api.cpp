@@ -175,7 +175,7 @@ extern "C" const char* ee_kernel_name(int k)
 
 extern "C" const uint32_t* ee_exp2_table(void) { return exp2_table_host(); }
 
-extern "C" int ee_tune_conv_tile(int tile) { return tile < 0 || tile > 3 ? EE_ERR_ARG : set_conv_tile(tile); }
+extern "C" int ee_tune_conv_tile(int tile) { return tile < 0 || tile > 4 ? EE_ERR_ARG : set_conv_tile(tile); }
 
 extern "C" int ee_blob_check(const void* blob, size_t bytes) { return parse_blob(blob, bytes, nullptr); }
 

@@ -6,9 +6,10 @@
 // walks over (r, s, c).
 //
 // Tiling: a workgroup of 4 wavefronts (256 lanes) owns BM output pixels x BN output channels.
-// Per 64-byte k-step both operands are staged in LDS (rows padded to 80 bytes so that the
-// 16-lane phases of a ds_read_b128 hit 64 distinct banks), double buffered with one barrier
-// per k-step; the next step's global loads are issued before the current step's MFMAs.
+// Per 128-byte k-step both operands are staged in LDS (rows padded to 144 bytes so that the
+// 16-lane phases of a ds_read_b128 hit 64 distinct banks); the next step's global loads are
+// issued into registers before the current step's MFMAs, and several workgroups per CU overlap
+// each other's barriers and memory latency.
 // Each wavefront computes WM x WN outputs with v_mfma_i32_32x32x32_i8 (int8) or
 // v_mfma_f32_32x32x16_bf16 (bf16).  The weight fragment is the A operand and the activation
 // fragment the B operand, so that one lane ends up holding 4 consecutive output channels of
@@ -29,7 +30,8 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
-constexpr int kLdsRow = 80;   // 64 data bytes + 16 bytes of padding
+constexpr int kStep = 128;                 // bytes of the reduction axis staged per barrier
+constexpr int kLdsRow = kStep + 16;        // staged row + 16 bytes of padding (conflict-free ds_read_b128)
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float v)
 {
@@ -49,23 +51,33 @@ __device__ __forceinline__ int requant_i8(int t, int shift, int lo, int hi)
 // ES = element size in bytes (1: int8, 2: bf16).  MODE 0: generic NHWC input with C*ES % 16 == 0,
 // bounds-checked taps.  MODE 1: 4-channel input already zero-padded in space ([Hp][Wp][4]); a kernel
 // row of kwp taps is kwp*4*ES contiguous bytes, no bounds checks.
+//
+// Workgroup -> tile mapping: consecutive workgroup ids go round-robin to the 8 XCDs, each with its
+// own L2.  Tile rows (pixel tiles) are split into 8 contiguous ranges, one per XCD, and all the
+// channel tiles of a pixel tile run back to back on the same XCD, so the activation rows a tile
+// reads (and the halo rows its neighbours share) stay in one L2.
 template <int ES, int BM, int BN, int WM, int WN, int MODE>
-__global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a)
+__global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a, int gm, int gn, int per_xcd)
 {
     constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
     static_assert(WAVES_M * WAVES_N == 4, "4 wavefronts per workgroup");
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int A_PER_T = BM / 64, B_PER_T = BN / 64;
-    static_assert(A_PER_T >= 1 && B_PER_T >= 1, "tile too small for the loader");
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2][(BM + BN) * kLdsRow];
+    constexpr int A_PER_T = BM / 32, B_PER_T = BN / 32;
+    constexpr int OROW = BN * ES + 16;                    // epilogue tile row: BN outputs + padding
+    constexpr int kMainBytes = (BM + BN) * kLdsRow, kEpiBytes = BM * OROW;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[kMainBytes > kEpiBytes ? kMainBytes : kEpiBytes];
 
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int mt = xcd * per_xcd + slot / gn, nt = slot % gn;
+    if (mt >= gm || slot / gn >= per_xcd) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-    const int cc = tid & 3, row_base = tid >> 2;
+    const int m0 = mt * BM, n0 = nt * BN;
+    const int cc = tid & 7, row_base = tid >> 3;
     const unsigned char* xb = (const unsigned char*)a.x;
     const unsigned char* wb = (const unsigned char*)a.w;
-    const int nk = a.Kp * ES / 64;
+    const int KpB = a.Kp * ES;                            // padded reduction length in bytes (multiple of 64)
+    const int nk = (KpB + kStep - 1) / kStep;
     const int HoWo = a.Ho * a.Wo;
 
     // ---- per-thread loader state -------------------------------------------------------------
@@ -73,7 +85,7 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a)
     int a_iy0[A_PER_T], a_ix0[A_PER_T];
 #pragma unroll
     for (int i = 0; i < A_PER_T; ++i) {
-        int m = m0 + row_base + 64 * i;
+        int m = m0 + row_base + 32 * i;
         m = m < a.M ? m : a.M - 1;                       // rows past the end repeat the last pixel; never stored
         const int n = m / HoWo, rem = m - n * HoWo;
         const int oy = rem / a.Wo, ox = rem - oy * a.Wo;
@@ -105,44 +117,44 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a)
 
     v4i ra[A_PER_T], rb[B_PER_T];
     auto load_global = [&](int ks) {
+        const bool k_ok = ks * kStep + cc * 16 < KpB;     // the last step may be half empty
 #pragma unroll
         for (int i = 0; i < A_PER_T; ++i) {
+            v4i v = {0, 0, 0, 0};
             if (MODE == 0) {
                 const int iy = a_iy0[i] + tr, ix = a_ix0[i] + ts;
                 const bool ok = tr < a.kh && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
-                v4i v = {0, 0, 0, 0};
                 if (ok) v = *(const v4i*)(xb + a_off[i] + ((long long)iy * a.W + ix) * CiB + tc);
-                ra[i] = v;
-            } else {
+            } else if (k_ok) {
                 const int r = prow < a.kh ? prow : a.kh - 1;      // k padding: real bytes times zero weights
-                const unsigned char* p = xb + a_off[i] + (long long)r * a.Wp * 4 * ES + ppart * 16;
-                const int* q = (const int*)p;                     // 4-byte aligned only
-                v4i v = {q[0], q[1], q[2], q[3]};
-                ra[i] = v;
+                const int* q = (const int*)(xb + a_off[i] + (long long)r * a.Wp * 4 * ES + ppart * 16);   // 4-byte aligned only
+                v = v4i{q[0], q[1], q[2], q[3]};
             }
+            ra[i] = v;
         }
 #pragma unroll
-        for (int i = 0; i < B_PER_T; ++i)
-            rb[i] = *(const v4i*)(wb + ((long long)(n0 + row_base + 64 * i) * a.Kp * ES) + ks * 64 + cc * 16);
-        // advance the tap state by one k-step (64 bytes)
+        for (int i = 0; i < B_PER_T; ++i) {
+            v4i v = {0, 0, 0, 0};
+            if (k_ok) v = *(const v4i*)(wb + (long long)(n0 + row_base + 32 * i) * KpB + ks * kStep + cc * 16);
+            rb[i] = v;
+        }
+        // advance the tap state by one k-step
         if (MODE == 0) {
-            tc += 64;
+            tc += kStep;
             while (tc >= CiB) {
                 tc -= CiB;
                 if (++ts == a.kw) { ts = 0; ++tr; }
             }
         } else {
-            ppart += 4;
+            ppart += kStep / 16;
             while (ppart >= cpr) { ppart -= cpr; ++prow; }
         }
     };
-    auto store_lds = [&](int buf) {
+    auto store_lds = [&]() {
 #pragma unroll
-        for (int i = 0; i < A_PER_T; ++i)
-            *(v4i*)(&lds[buf][(row_base + 64 * i) * kLdsRow + cc * 16]) = ra[i];
+        for (int i = 0; i < A_PER_T; ++i) *(v4i*)(&lds[(row_base + 32 * i) * kLdsRow + cc * 16]) = ra[i];
 #pragma unroll
-        for (int i = 0; i < B_PER_T; ++i)
-            *(v4i*)(&lds[buf][(BM + row_base + 64 * i) * kLdsRow + cc * 16]) = rb[i];
+        for (int i = 0; i < B_PER_T; ++i) *(v4i*)(&lds[(BM + row_base + 32 * i) * kLdsRow + cc * 16]) = rb[i];
     };
 
     using acc_t = typename std::conditional<ES == 1, v16i, v16f>::type;
@@ -154,22 +166,22 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][i][v] = 0;
 
+    // ---- main loop: registers hold step ks+1 while the matrix cores work on step ks out of LDS ----
     load_global(0);
-    store_lds(0);
-    __syncthreads();
     const int frag_row = lane & 31, frag_k = (lane >> 5) * 16;
     for (int ks = 0; ks < nk; ++ks) {
-        const int buf = ks & 1;
+        store_lds();
+        __syncthreads();
         if (ks + 1 < nk) load_global(ks + 1);
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
+        const int nsub = min(4, (KpB - ks * kStep) / 32);
+        for (int sub = 0; sub < nsub; ++sub) {
             v4i fw[TN], fx[TM];
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                fw[j] = *(const v4i*)(&lds[buf][(BM + wn0 + 32 * j + frag_row) * kLdsRow + half * 32 + frag_k]);
+                fw[j] = *(const v4i*)(&lds[(BM + wn0 + 32 * j + frag_row) * kLdsRow + sub * 32 + frag_k]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                fx[i] = *(const v4i*)(&lds[buf][(wm0 + 32 * i + frag_row) * kLdsRow + half * 32 + frag_k]);
+                fx[i] = *(const v4i*)(&lds[(wm0 + 32 * i + frag_row) * kLdsRow + sub * 32 + frag_k]);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -181,44 +193,56 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a)
                                                                              __builtin_bit_cast(v8bf, fx[i]), acc[j][i], 0, 0, 0);
                 }
         }
-        if (ks + 1 < nk) store_lds(buf ^ 1);
         __syncthreads();
     }
 
-    // ---- epilogue: bias, residual, requantise / clamp, packed NHWC store ------------------------
+    // ---- epilogue: bias, residual, requantise / clamp ---------------------------------------------
+    // Fast path (rows of C_out are 16-byte multiples): the tile goes through LDS so that the residual
+    // is read and the result written with 16 bytes per lane along the channel axis (whole cache
+    // lines); each lane patches its own 4 outputs in place in between.
+    const bool wide = (a.Co * ES) % 16 == 0;
+    constexpr int CPR = BN * ES / 16;                     // 16-byte chunks per tile row
+    if (wide && a.res) {
+        for (int id = tid; id < BM * CPR; id += 256) {
+            const int r = id / CPR, c16 = id - r * CPR;
+            const int m = m0 + r, ch = n0 + c16 * (16 / ES);
+            if (m < a.M && ch < a.Co)
+                *(v4i*)(&lds[r * OROW + c16 * 16]) = *(const v4i*)((const unsigned char*)a.res + ((long long)m * a.Co + ch) * ES);
+        }
+        __syncthreads();
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int m = m0 + wm0 + 32 * i + (lane & 31);
-        if (m >= a.M) continue;
+        const int r = wm0 + 32 * i + (lane & 31);
+        const int m = m0 + r;
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int c0 = n0 + wn0 + 32 * j + 8 * g + 4 * (lane >> 5);
-                if (c0 >= a.Co) continue;
+                const int cl = wn0 + 32 * j + 8 * g + 4 * (lane >> 5);
+                const int c0 = n0 + cl;
+                if (m >= a.M || c0 >= a.Co) continue;
                 const long long o = (long long)m * a.Co + c0;
+                unsigned char* tile = &lds[r * OROW + cl * ES];
                 if constexpr (ES == 1) {
                     const v4i bias = *(const v4i*)((const int*)a.bias + c0);
-                    int r4[4] = {0, 0, 0, 0};
-                    if (a.res) {
-                        const int packed = *(const int*)((const signed char*)a.res + o);
-                        r4[0] = (int)(signed char)(packed & 0xFF); r4[1] = (int)(signed char)((packed >> 8) & 0xFF);
-                        r4[2] = (int)(signed char)((packed >> 16) & 0xFF); r4[3] = packed >> 24;
-                    }
+                    int packed = 0;
+                    if (a.res) packed = wide ? *(const int*)tile : *(const int*)((const signed char*)a.res + o);
                     unsigned out = 0;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const int t = acc[j][i][4 * g + e] + bias[e] + (r4[e] << a.res_shift);
+                        const int rv = (int)(signed char)((packed >> (8 * e)) & 0xFF);
+                        const int t = acc[j][i][4 * g + e] + bias[e] + (rv << a.res_shift);
                         out |= (unsigned)(requant_i8(t, a.shift, a.lo, a.hi) & 0xFF) << (8 * e);
                     }
-                    *(unsigned*)((signed char*)a.y + o) = out;
+                    if (wide) *(unsigned*)tile = out;
+                    else *(unsigned*)((signed char*)a.y + o) = out;
                 } else {
                     const float* bias = (const float*)a.bias + c0;
-                    uint16_t r4[4] = {0, 0, 0, 0};
-                    if (a.res) {
-                        const uint2 packed = *(const uint2*)((const uint16_t*)a.res + o);
-                        r4[0] = packed.x & 0xFFFF; r4[1] = packed.x >> 16; r4[2] = packed.y & 0xFFFF; r4[3] = packed.y >> 16;
-                    }
+                    uint2 packed = {0u, 0u};
+                    if (a.res) packed = wide ? *(const uint2*)tile : *(const uint2*)((const uint16_t*)a.res + o);
+                    const uint16_t r4[4] = {(uint16_t)(packed.x & 0xFFFF), (uint16_t)(packed.x >> 16),
+                                            (uint16_t)(packed.y & 0xFFFF), (uint16_t)(packed.y >> 16)};
                     uint16_t q[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -230,39 +254,54 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a)
                     uint2 out;
                     out.x = (unsigned)q[0] | ((unsigned)q[1] << 16);
                     out.y = (unsigned)q[2] | ((unsigned)q[3] << 16);
-                    *(uint2*)((uint16_t*)a.y + o) = out;
+                    if (wide) *(uint2*)tile = out;
+                    else *(uint2*)((uint16_t*)a.y + o) = out;
                 }
             }
+    }
+    if (wide) {
+        __syncthreads();
+        for (int id = tid; id < BM * CPR; id += 256) {
+            const int r = id / CPR, c16 = id - r * CPR;
+            const int m = m0 + r, ch = n0 + c16 * (16 / ES);
+            if (m < a.M && ch < a.Co)
+                *(v4i*)((unsigned char*)a.y + ((long long)m * a.Co + ch) * ES) = *(const v4i*)(&lds[r * OROW + c16 * 16]);
+        }
     }
 }
 
 template <int ES, int BM, int BN, int WM, int WN>
 static hipError_t launch_tile(const ConvArgs& a, hipStream_t s)
 {
-    dim3 grid((a.M + BM - 1) / BM, (a.Co + BN - 1) / BN);
+    const int gm = (a.M + BM - 1) / BM, gn = (a.Co + BN - 1) / BN, per_xcd = (gm + 7) / 8;
+    dim3 grid((unsigned)(8 * per_xcd * gn));
     if (a.mode == 0)
-        hipLaunchKernelGGL((conv_mfma_kernel<ES, BM, BN, WM, WN, 0>), grid, dim3(256), 0, s, a);
+        hipLaunchKernelGGL((conv_mfma_kernel<ES, BM, BN, WM, WN, 0>), grid, dim3(256), 0, s, a, gm, gn, per_xcd);
     else
-        hipLaunchKernelGGL((conv_mfma_kernel<ES, BM, BN, WM, WN, 1>), grid, dim3(256), 0, s, a);
+        hipLaunchKernelGGL((conv_mfma_kernel<ES, BM, BN, WM, WN, 1>), grid, dim3(256), 0, s, a, gm, gn, per_xcd);
     return hipGetLastError();
 }
 
-// Tile choice: wide tiles when they still give every CU work, narrower ones for few output
-// channels or a small active batch (the GPU face of the paper's per-layer, per-batch-size
-// mapping problem, Sec. III-A).
-static int g_forced_tile = 0;    // 0 = choose by shape; 1: 128x128, 2: 256x64, 3: 64x64 (tuning / test control)
+// Tile choice per layer and active batch size: the widest tile that still gives every CU a few
+// workgroups to overlap (the GPU face of the paper's per-layer, per-batch-size mapping problem,
+// Sec. III-A).  Tiles are output pixels x output channels.
+static int g_forced_tile = 0;    // 0 = by shape; 1: 128x128, 2: 128x64, 3: 64x64, 4: 64x128 (tuning / test control)
 int set_conv_tile(int tile) { const int old = g_forced_tile; g_forced_tile = tile; return old; }
 
 template <int ES>
 static hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t s)
 {
     if (a.M <= 0) return hipSuccess;
-    if (g_forced_tile == 1) return launch_tile<ES, 128, 128, 64, 64>(a, s);
-    if (g_forced_tile == 2) return launch_tile<ES, 256, 64, 64, 64>(a, s);
-    if (g_forced_tile == 3) return launch_tile<ES, 64, 64, 32, 32>(a, s);
-    const long long big = (long long)((a.M + 127) / 128) * ((a.Co + 127) / 128);
-    if (a.Co > 64 && big >= 256) return launch_tile<ES, 128, 128, 64, 64>(a, s);
-    if (a.Co <= 64 && (long long)((a.M + 255) / 256) >= 256) return launch_tile<ES, 256, 64, 64, 64>(a, s);
+    int tile = g_forced_tile;
+    if (tile == 0) {
+        auto blocks = [&](int bm, int bn) { return (long long)((a.M + bm - 1) / bm) * ((a.Co + bn - 1) / bn); };
+        const long long want = 3 * 256;
+        if (a.Co > 64) tile = blocks(128, 128) >= want ? 1 : (blocks(64, 128) >= want ? 4 : 3);
+        else tile = blocks(128, 64) >= want ? 2 : 3;
+    }
+    if (tile == 1) return launch_tile<ES, 128, 128, 64, 64>(a, s);
+    if (tile == 2) return launch_tile<ES, 128, 64, 64, 32>(a, s);
+    if (tile == 4) return launch_tile<ES, 64, 128, 32, 64>(a, s);
     return launch_tile<ES, 64, 64, 32, 32>(a, s);
 }
 

@@ -72,7 +72,7 @@ def test_int8_segments_and_heads_bit_exact(torch, ee, orc, name):
     eng.close()
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4])
 @pytest.mark.parametrize("name", ["zoo_i8", "resnet50_small_i8"])
 def test_int8_every_conv_tiling_bit_exact(torch, ee, orc, name, tile):
     blob = W.load_net(name)
@@ -235,7 +235,7 @@ def test_bf16_within_tolerance(torch, ee, orc, name):
     blob = W.load_net(name)
     eng = ee.Engine(blob, 16)
     x = W.input_pool(blob, 12)
-    for tile in (0, 1, 2, 3):
+    for tile in (0, 1, 2, 3, 4):
         ee.tune_conv_tile(tile)
         act = x
         for s in range(blob.n_stages):
