@@ -66,13 +66,13 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
         return rc;
     }
     const int Co = d.c_out, Ci = d.c_in, Co_pad = round_up(Co, 128);
-    std::vector<unsigned char> bp(4 * (size_t)Co_pad, 0);
+    std::vector<unsigned char> bp(4 * (size_t)(Co_pad + 256), 0);     // the kernels copy 256 entries from the tile's first channel
     std::memcpy(bp.data(), b, 4 * (size_t)Co);
     std::vector<unsigned char> wp;
-    if ((Ci * es) % 16 == 0 && Co % 4 == 0) {
+    if ((Ci * es) % 16 == 0 && Co % 4 == 0 && d.kh * d.kw <= 31) {
         p.impl = IMPL_MFMA;
         const int K = d.kh * d.kw * Ci;
-        p.Kp = round_up(K * es, 64) / es;
+        p.Kp = round_up(K * es, 128) / es;
         wp.assign((size_t)Co_pad * p.Kp * es, 0);
         for (int o = 0; o < Co; ++o) std::memcpy(&wp[(size_t)o * p.Kp * es], w + (size_t)o * K * es, (size_t)K * es);
     } else if (Ci <= 4 && Co % 4 == 0) {
@@ -93,6 +93,16 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
     } else {
         p.impl = IMPL_DIRECT;
         wp.assign(w, w + (size_t)Co * d.kh * d.kw * Ci * es);
+    }
+    if (p.impl == IMPL_MFMA && es == 1 && d.shift > 0) {
+        // that kernel requantises with a bare arithmetic shift: the rounding constant 2^(shift-1) goes
+        // into the bias (the sum fits int32: the network's calibration guarantees t + 2^(shift-1) does)
+        for (int o = 0; o < Co; ++o) {
+            int32_t v;
+            std::memcpy(&v, &bp[4 * (size_t)o], 4);
+            v += 1 << (d.shift - 1);
+            std::memcpy(&bp[4 * (size_t)o], &v, 4);
+        }
     }
     int rc = upload(ctx, &p.w_dev, wp);
     if (!rc) rc = upload(ctx, &p.b_dev, bp);
@@ -238,6 +248,7 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
     if ((rc = dev_alloc(ctx, &ctx->sums, sizeof(int32_t) * (size_t)b_max * c_max))) return fail(rc);
     if ((rc = dev_alloc(ctx, &ctx->logits, 4 * (size_t)b_max * ctx->net.n_classes))) return fail(rc);
     if ((rc = dev_alloc(ctx, &ctx->d_count, 64))) return fail(rc);
+    if ((rc = dev_alloc(ctx, &ctx->zero_page, 256))) return fail(rc);
 
     // stream-serving workspace: packed input slots and raw output slots of every segment
     ctx->in_buf.resize(n_st);
@@ -295,7 +306,9 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out)
         hipError_t e = hipSuccess;
         if (p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_C4) {
             ConvArgs a{};
-            a.w = p.w_dev; a.bias = p.b_dev; a.res = res; a.y = dst;
+            a.w = p.w_dev; a.bias = p.b_dev; a.res = res; a.y = dst; a.zeros = zero_page;
+            a.magic_howo = (unsigned)(0x100000000ull / (unsigned)(d.h_out * d.w_out) - (d.h_out * d.w_out == 1));
+            a.magic_wo = (unsigned)(0x100000000ull / (unsigned)d.w_out - (d.w_out == 1));
             a.M = b * d.h_out * d.w_out; a.H = d.h_in; a.W = d.w_in; a.Ci = d.c_in; a.Ho = d.h_out; a.Wo = d.w_out; a.Co = d.c_out;
             a.kh = d.kh; a.kw = d.kw; a.stride = d.stride; a.pad = d.pad; a.Kp = p.Kp;
             a.shift = d.shift; a.res_shift = d.res_shift; a.lo = d.lo; a.hi = d.hi; a.f_lo = d.f_lo; a.f_hi = d.f_hi;
@@ -309,7 +322,10 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out)
                 a.x = src; a.mode = 0;
             }
             const int cls = p.impl == IMPL_MFMA ? EE_K_CONV_MFMA : EE_K_CONV_FIRST;
-            e = timed(cls, ops, bytes, [&] { return dt == EE_I8 ? launch_conv_mfma_i8(a, stream) : launch_conv_mfma_bf16(a, stream); }, st.first_op + k);
+            e = timed(cls, ops, bytes, [&] {
+                if (p.impl == IMPL_MFMA) return dt == EE_I8 ? launch_conv_igemm<1>(a, forced_conv_tile(), stream) : launch_conv_igemm<2>(a, forced_conv_tile(), stream);
+                return dt == EE_I8 ? launch_conv_mfma_i8(a, stream) : launch_conv_mfma_bf16(a, stream);
+            }, st.first_op + k);
         } else if (p.impl == IMPL_DIRECT) {
             DirectConvArgs a{src, p.w_dev, p.b_dev, res, dst, b * d.h_out * d.w_out, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.c_out,
                              d.kh, d.kw, d.stride, d.pad, d.shift, d.res_shift, d.lo, d.hi, d.f_lo, d.f_hi};

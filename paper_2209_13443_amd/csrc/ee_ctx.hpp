@@ -37,6 +37,7 @@ struct ee_ctx {
     std::vector<void*> wfc_dev, bfc_dev;         // exit heads
     int32_t* sums = nullptr;                     // [b_max][C_max]
     void* logits = nullptr;                      // [b_max][n_cls]
+    void* zero_page = nullptr;                   // zero bytes read in place of padding taps
     int* d_count = nullptr;                      // device int scratch (B_rem)
     // stream serving workspace
     std::vector<void*> in_buf, out_buf;          // per segment: packed input slots, raw output slots

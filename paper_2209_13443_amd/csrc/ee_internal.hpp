@@ -50,9 +50,11 @@ int parse_blob(const void* blob, size_t bytes, NetDesc* out);
 // loader uses (see pack_weights in ee_api.cpp), zero padded.
 struct ConvArgs {
     const void* x; const void* w; const void* bias; const void* res; void* y;
+    const void* zeros;   // >= 16 readable zero bytes: what padding taps and rows past the batch read
     int M, H, W, Ci, Ho, Wo, Co;
     int kh, kw, stride, pad;
-    int Kp;              // padded reduction length in elements (multiple of the k-step)
+    int Kp;              // weight row pitch in elements (reduction length, zero padded)
+    unsigned magic_howo, magic_wo;   // floor(2^32 / (Ho*Wo)), floor(2^32 / Wo): division by multiply-high
     int mode;            // 0: Ci % 16 == 0 loader with bounds checks; 1: 4-channel zero-padded input
     int Hp, Wp, kwp;     // mode 1: padded input dims and padded kernel width
     int shift, res_shift, lo, hi;
@@ -74,6 +76,9 @@ struct PoolArgs {         // depthwise 3x3 and max-pool share the shape block
 // ---- launchers (defined in the .hip files) -------------------------------------------------------
 hipError_t launch_conv_mfma_i8(const ConvArgs& a, hipStream_t s);
 hipError_t launch_conv_mfma_bf16(const ConvArgs& a, hipStream_t s);
+// asynchronous-copy implicit GEMM (ES = element bytes); tile 0 = chosen by shape, 1..4 forced
+template <int ES> hipError_t launch_conv_igemm(const ConvArgs& a, int tile, hipStream_t s);
+int forced_conv_tile();
 hipError_t launch_conv_direct(const DirectConvArgs& a, int dtype, hipStream_t s);
 hipError_t launch_pad_input(const void* x, void* y, int B, int H, int W, int C, int Hp, int Wp, int pad, int dtype, hipStream_t s);
 hipError_t launch_depthwise(const PoolArgs& a, int dtype, hipStream_t s);

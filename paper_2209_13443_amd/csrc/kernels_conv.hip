@@ -287,6 +287,7 @@ static hipError_t launch_tile(const ConvArgs& a, hipStream_t s)
 // Sec. III-A).  Tiles are output pixels x output channels.
 static int g_forced_tile = 0;    // 0 = by shape; 1: 128x128, 2: 128x64, 3: 64x64, 4: 64x128 (tuning / test control)
 int set_conv_tile(int tile) { const int old = g_forced_tile; g_forced_tile = tile; return old; }
+int forced_conv_tile() { return g_forced_tile; }
 
 template <int ES>
 static hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t s)

@@ -1,0 +1,388 @@
+// Implicit-GEMM convolution for gfx950 (CDNA4) with asynchronous global -> LDS staging.
+//
+// Every CONV layer is the GEMM  R x P . P x C -> R x C  of the paper's Sec. II-C with the batch
+// appended along R (R-batching, Sec. III-A).  The Toeplitz matrix is never materialised: the
+// rows (output pixels) are gathered from the NHWC activation tensor while the reduction walks
+// over (r, s, c) in steps of KS bytes.
+//
+// Data movement.  Both operands go from global memory straight into LDS with
+// global_load_lds_dwordx4 (16 bytes per lane, no VGPR staging): lane l of a wavefront names its
+// own source address and its 16 bytes land at  M0 + 16*l, so one instruction fills 1 KiB of LDS.
+// A ring of ns stages keeps ns-1 reduction steps in flight; the wavefronts count their own
+// outstanding copies (s_waitcnt vmcnt) and meet at one barrier per step.  Padding taps and rows
+// past the end of the batch read a small zero page instead of being skipped, so every wavefront
+// issues the same number of copies per step and the counting stays uniform.
+//
+// LDS layout of a stage: BM activation rows then BN weight rows of KS bytes, no padding.  The 16-byte
+// chunk c of row r is stored at chunk position  c ^ swz(r)  (the lane that copies it simply reads
+// a permuted source address), with swz chosen such that the 16-lane phases of a ds_read_b128 of
+// a matrix-core fragment (32 consecutive rows, same c) touch all 64 banks once.
+//
+// Compute.  4 wavefronts as 2 x 2, each owning (BM/2) x (BN/2) outputs in 32x32 accumulators of
+// v_mfma_i32_32x32x32_i8 / v_mfma_f32_32x32x16_bf16 (16 operand bytes per lane and instruction).
+// The weight fragment is the A operand, the activation fragment the B operand, so a lane holds
+// 4 consecutive output channels of one pixel per accumulator quad.
+//   A: row l%32, k-bytes [16*(l/32), +16)      B: column l%32, same k-bytes
+//   D: column l%32, rows 8*(v/4) + 4*(l/32) + v%4 for accumulator register v = 0..15
+//
+// Epilogue.  Bias (copied to LDS at kernel start) and the residual tile (likewise, so that its
+// latency hides behind the main loop) are added in the accumulator layout, the result is
+// requantised / clamped, packed and written into an LDS tile from which the workgroup stores whole
+// 16-byte chunks along the channel axis.
+#include <type_traits>
+
+#include "ee_internal.hpp"
+
+namespace ee {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+namespace {
+
+__device__ __forceinline__ unsigned lds_addr(const void* p)
+{
+    return (unsigned)(size_t)(__attribute__((address_space(3))) const unsigned char*)p;
+}
+
+// 16 bytes per lane, global -> LDS, asynchronous (counted by vmcnt).  lds_base must be wave-uniform.
+__device__ __forceinline__ void dma16(unsigned lds_base, const void* gptr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+__device__ __forceinline__ void dma16(unsigned lds_base, const void* uniform_base, unsigned voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(uniform_base) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_copies_then_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+// bytes of LDS the ring takes: the stages in use, and never less than the output tile that reuses it
+__host__ __device__ constexpr unsigned igemm_ring_bytes(int ns, int nk, int stage_bytes, int tile_o)
+{
+    const int used = (ns < nk ? ns : nk) * stage_bytes;
+    return (unsigned)(used > tile_o ? used : tile_o);
+}
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+__device__ __forceinline__ unsigned fast_div(unsigned m, unsigned d, unsigned magic)   // magic = floor(2^32 / d), d >= 1
+{
+    unsigned q = __umulhi(m, magic);
+    if (m - q * d >= d) ++q;
+    return q;
+}
+
+__device__ __forceinline__ uint16_t to_bf16_rne(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float from_bf16(uint32_t b) { return __uint_as_float(b << 16); }
+
+}  // namespace
+
+// ES: element bytes (1 int8, 2 bf16).  BM x BN: workgroup tile (pixels x channels).  KS: bytes of
+// the reduction axis per stage.  ns (2..4, not above the number of steps + 1): stages in the ring.  PLAIN: 1x1 kernel without padding whose
+// reduction length is a multiple of KS -- the source address of a row then simply advances by KS.
+template <int ES, int BM, int BN, int KS, bool PLAIN>
+__global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int gn, int per_xcd, int ns)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+    constexpr int CPRW = KS / 16;                  // 16-byte chunks per staged row
+    constexpr int RPP = 256 / CPRW;                // rows one copy pass of the workgroup covers
+    constexpr int NA = BM / RPP, NB = BN / RPP, LPT = NA + NB;
+    constexpr int STAGE = (BM + BN) * KS;
+    constexpr int R256 = 256 / KS;                 // staged rows per 256 bytes of LDS
+    constexpr int CR = BN * ES / 16;               // 16-byte chunks per row of the output tile
+    constexpr int OROW = BN * ES, TILE_O = BM * OROW;
+    constexpr int NO = BM * CR / 256;              // output-tile passes of the workgroup
+    constexpr int OSWZ = CR - 1 < 7 ? CR - 1 : 7;
+    static_assert(NA >= 1 && NB >= 1 && NO >= 1, "tile too small for 256 lanes");
+
+    const int xcd = blockIdx.x & 7, wslot = blockIdx.x >> 3;
+    const int mt = xcd * per_xcd + wslot / gn, nt = wslot % gn;
+    if (mt >= gm || wslot / gn >= per_xcd) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
+    const int m0 = mt * BM, n0 = nt * BN;
+    const unsigned char* xb = (const unsigned char*)a.x;
+    const unsigned char* zp = (const unsigned char*)a.zeros;
+    const int KpB = a.Kp * ES;                     // weight row pitch in bytes
+    const int nk = (a.kh * a.kw * a.Ci * ES + KS - 1) / KS;
+    const int CiB = a.Ci * ES;
+    const bool wide = (a.Co * ES) % 16 == 0;
+    const bool has_res = a.res != nullptr;
+    const unsigned lds0 = lds_addr(lds);
+    // LDS map: ring | residual tile (without one the output tile aliases the ring) | bias
+    const unsigned ring = igemm_ring_bytes(ns, nk, STAGE, TILE_O);
+    const unsigned ro_off = has_res && wide ? ring : 0;
+    const unsigned bias_off = has_res && wide ? ring + TILE_O : ring;
+
+    // ---- bias and residual tile: copied first, consumed last --------------------------------------
+    if (wave == 0) dma16(lds0 + bias_off, (const unsigned char*)a.bias + (size_t)n0 * 4 + lane * 16);
+    if (has_res && wide) {
+#pragma unroll
+        for (int j = 0; j < NO; ++j) {
+            const int q = tid + 256 * j, row = q / CR, chunk = (q % CR) ^ (row & OSWZ);
+            const int m = m0 + row, ch = n0 + chunk * (16 / ES);
+            const unsigned char* p = (m < a.M && ch < a.Co) ? (const unsigned char*)a.res + ((size_t)m * a.Co + ch) * ES : zp;
+            dma16(lds0 + ro_off + (256 * j + 64 * wave) * 16, p);
+        }
+    }
+
+    // ---- per-lane copy state ------------------------------------------------------------------------
+    const int lrow = tid / CPRW;
+    const int cchunk = (tid % CPRW) ^ ((lrow / R256) & (CPRW - 1));     // the source chunk this lane copies
+    unsigned voffB[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) voffB[j] = (unsigned)(n0 + lrow + j * RPP) * (unsigned)KpB + cchunk * 16;
+    unsigned voffA[NA];                            // PLAIN: byte offset of the chunk;  else: byte offset of the patch corner
+    unsigned maskA[NA];                            // else: bit (r * kw + s) set iff that tap of the row is inside the image
+    int tap = 0, ts = 0, tc = 0, toff = 0;         // else: this lane's position inside the patch
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+        int m = m0 + lrow + j * RPP;
+        const bool live = m < a.M;
+        m = live ? m : a.M - 1;
+        const unsigned n = fast_div((unsigned)m, (unsigned)(a.Ho * a.Wo), a.magic_howo);
+        const unsigned rem = (unsigned)m - n * (unsigned)(a.Ho * a.Wo);
+        const unsigned oy = fast_div(rem, (unsigned)a.Wo, a.magic_wo), ox = rem - oy * a.Wo;
+        const int iy0 = (int)oy * a.stride - a.pad, ix0 = (int)ox * a.stride - a.pad;
+        voffA[j] = (unsigned)((((int)n * a.H + iy0) * a.W + ix0) * CiB);
+        if (PLAIN) {
+            voffA[j] += cchunk * 16;
+            maskA[j] = 0;
+        } else {
+            unsigned colmask = 0, msk = 0;
+            for (int s = 0; s < a.kw; ++s) colmask |= (unsigned)((unsigned)(ix0 + s) < (unsigned)a.W) << s;
+            for (int r = 0; r < a.kh; ++r)
+                if ((unsigned)(iy0 + r) < (unsigned)a.H) msk |= colmask << (r * a.kw);
+            maskA[j] = live ? msk : 0u;
+        }
+    }
+    if (!PLAIN) {
+        const int kb = cchunk * 16;
+        tap = kb / CiB;
+        tc = kb - tap * CiB;
+        const int tr = tap / a.kw;
+        ts = tap - tr * a.kw;
+        toff = (tr * a.W + ts) * CiB + tc;
+    }
+    const int ntaps = a.kh * a.kw;
+
+    auto issue = [&](int stage) {
+        const unsigned sbase = lds0 + stage * STAGE + wave * 1024;
+        if (PLAIN) {
+#pragma unroll
+            for (int j = 0; j < NA; ++j) {
+                dma16(sbase + j * 4096, xb, voffA[j]);
+                voffA[j] += KS;
+            }
+        } else {
+            const unsigned tapbit = tap < ntaps ? 1u << tap : 0u;
+#pragma unroll
+            for (int j = 0; j < NA; ++j) {
+                const unsigned char* p = (maskA[j] & tapbit) ? xb + (unsigned)(voffA[j] + toff) : zp;
+                dma16(sbase + j * 4096, p);
+            }
+            tc += KS;
+            toff += KS;
+            while (tc >= CiB) {
+                tc -= CiB;
+                ++tap;
+                if (++ts == a.kw) { ts = 0; toff += (a.W - a.kw) * CiB; }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            dma16(sbase + BM * KS + j * 4096, a.w, voffB[j]);
+            voffB[j] += KS;
+        }
+    };
+
+    // ---- fragment addressing ---------------------------------------------------------------------------
+    const int frow = lane & 31, hi = lane >> 5;
+    int fragoff[KS / 32];
+#pragma unroll
+    for (int sub = 0; sub < KS / 32; ++sub) fragoff[sub] = frow * KS + (((2 * sub + hi) ^ ((frow / R256) & (CPRW - 1))) * 16);
+
+    using acc_t = typename std::conditional<ES == 1, v16i, v16f>::type;
+    acc_t acc[TN][TM];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][i][v] = 0;
+
+    auto compute = [&](int stage) {
+        const unsigned char* sa = lds + stage * STAGE + wm0 * KS;
+        const unsigned char* sb = lds + stage * STAGE + (BM + wn0) * KS;
+#pragma unroll
+        for (int sub = 0; sub < KS / 32; ++sub) {
+            v4i fw[TN], fx[TM];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fw[j] = *(const v4i*)(sb + 32 * j * KS + fragoff[sub]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fx[i] = *(const v4i*)(sa + 32 * i * KS + fragoff[sub]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    if constexpr (ES == 1)
+                        acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[j], fx[i], acc[j][i], 0, 0, 0);
+                    else
+                        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fw[j]), __builtin_bit_cast(v8bf, fx[i]),
+                                                                             acc[j][i], 0, 0, 0);
+                }
+        }
+    };
+
+    // ---- main loop: step ks computes out of stage ks % ns while steps ks+1 .. ks+ns-1 are in flight ----
+    for (int s = 0; s < ns - 1; ++s)
+        if (s < nk) issue(s);
+    int st_c = 0, st_i = ns - 1;
+    for (int ks = 0; ks < nk; ++ks) {
+        // steps ks+1 .. ks+ns-2 may still be in flight, each LPT copies of this wavefront
+        if (ks + ns - 2 >= nk || ns == 2) wait_copies_then_barrier<0>();
+        else if (ns == 3) wait_copies_then_barrier<LPT>();
+        else wait_copies_then_barrier<2 * LPT>();
+        if (ks + ns - 1 < nk) issue(st_i);
+        compute(st_c);
+        st_c = st_c + 1 == ns ? 0 : st_c + 1;
+        st_i = st_i + 1 == ns ? 0 : st_i + 1;
+    }
+    lds_barrier();                                  // every wavefront is done with the ring
+
+    // ---- epilogue ------------------------------------------------------------------------------------------
+    unsigned char* ro = lds + ro_off;
+    const int* lbias = (const int*)(lds + bias_off);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int r = wm0 + 32 * i + frow;
+        const int m = m0 + r;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int cl = wn0 + 32 * j + 8 * g + 4 * hi;                         // first of this lane's 4 channels
+                const int byte = cl * ES;
+                unsigned char* cell = ro + r * OROW + (((byte >> 4) ^ (r & OSWZ)) << 4) + (byte & 15);
+                const long long o = (long long)m * a.Co + n0 + cl;
+                const bool inside = m < a.M && n0 + cl < a.Co;
+                const v4i b4 = *(const v4i*)(lbias + cl);
+                if constexpr (ES == 1) {
+                    int packed = 0;
+                    if (has_res) packed = wide ? *(const int*)cell : (inside ? *(const int*)((const signed char*)a.res + o) : 0);
+                    int q[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int rv = (packed << (24 - 8 * e)) >> 24;                // sign-extended byte e
+                        const int t = acc[j][i][4 * g + e] + b4[e] + (rv << a.res_shift);
+                        q[e] = min(max(t >> a.shift, a.lo), a.hi);                   // rounding constant is part of the bias
+                    }
+                    const unsigned out = (unsigned)(q[0] & 0xFF) | ((unsigned)(q[1] & 0xFF) << 8) | ((unsigned)(q[2] & 0xFF) << 16) | ((unsigned)q[3] << 24);
+                    if (wide) *(unsigned*)cell = out;
+                    else if (inside) *(unsigned*)((signed char*)a.y + o) = out;
+                } else {
+                    uint2 packed = {0u, 0u};
+                    if (has_res) packed = wide ? *(const uint2*)cell : (inside ? *(const uint2*)((const uint16_t*)a.res + o) : packed);
+                    const uint32_t r4[4] = {packed.x & 0xFFFFu, packed.x >> 16, packed.y & 0xFFFFu, packed.y >> 16};
+                    uint32_t q[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float t = acc[j][i][4 * g + e] + __int_as_float(b4[e]);
+                        if (has_res) t = t + from_bf16(r4[e]);
+                        t = fminf(fmaxf(t, a.f_lo), a.f_hi);
+                        q[e] = to_bf16_rne(t);
+                    }
+                    uint2 out;
+                    out.x = q[0] | (q[1] << 16);
+                    out.y = q[2] | (q[3] << 16);
+                    if (wide) *(uint2*)cell = out;
+                    else if (inside) *(uint2*)((uint16_t*)a.y + o) = out;
+                }
+            }
+    }
+    if (wide) {
+        lds_barrier();
+#pragma unroll
+        for (int j = 0; j < NO; ++j) {
+            const int q = tid + 256 * j, row = q / CR, chunk = (q % CR) ^ (row & OSWZ);
+            const int m = m0 + row, ch = n0 + chunk * (16 / ES);
+            if (m < a.M && ch < a.Co) *(v4i*)((unsigned char*)a.y + ((size_t)m * a.Co + ch) * ES) = *(const v4i*)(ro + q * 16);
+        }
+    }
+}
+
+// ---- launch ------------------------------------------------------------------------------------------------
+template <int ES, int BM, int BN, int KS>
+static hipError_t launch_igemm_tile(const ConvArgs& a, bool plain, int ns, hipStream_t s)
+{
+    const int gm = (a.M + BM - 1) / BM, gn = (a.Co + BN - 1) / BN, per_xcd = (gm + 7) / 8;
+    const dim3 grid((unsigned)(8 * per_xcd * gn));
+    const bool res_tile = a.res != nullptr && (a.Co * ES) % 16 == 0;
+    const int nk = (a.kh * a.kw * a.Ci * ES + KS - 1) / KS;
+    ns = ns < 2 ? 2 : (ns > 4 ? 4 : ns);
+    const size_t lds_bytes = igemm_ring_bytes(ns, nk, (BM + BN) * KS, BM * BN * ES) + (res_tile ? (size_t)BM * BN * ES : 0) + 1024;
+    // more than 64 KiB of dynamic LDS has to be granted once per kernel
+    static const hipError_t granted = [] {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_igemm_kernel<ES, BM, BN, KS, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_igemm_kernel<ES, BM, BN, KS, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        return e;
+    }();
+    if (granted != hipSuccess) return granted;
+    if (lds_bytes > 160 * 1024) return hipErrorInvalidValue;
+    if (plain)
+        hipLaunchKernelGGL((conv_igemm_kernel<ES, BM, BN, KS, true>), grid, dim3(256), lds_bytes, s, a, gm, gn, per_xcd, ns);
+    else
+        hipLaunchKernelGGL((conv_igemm_kernel<ES, BM, BN, KS, false>), grid, dim3(256), lds_bytes, s, a, gm, gn, per_xcd, ns);
+    return hipGetLastError();
+}
+
+// cfg: bits 0-3 tile (0 = by shape; 1: 128x128, 2: 128x64, 3: 64x64, 4: 64x128), bits 4-7 reduction step
+// (0 = by shape, 1: 64 bytes, 2: 128 bytes), bits 8-11 ring stages (0 = by shape, else 2..4).
+template <int ES>
+hipError_t launch_conv_igemm(const ConvArgs& a, int cfg, hipStream_t s)
+{
+    if (a.M <= 0) return hipSuccess;
+    int tile = cfg & 15, ksel = (cfg >> 4) & 15, ns = (cfg >> 8) & 15;
+    const int kbytes = a.kh * a.kw * a.Ci * ES;
+    if (ksel == 0) ksel = kbytes % 128 == 0 ? 2 : 1;
+    const int ks = ksel == 2 ? 128 : 64;
+    const bool plain = a.kh == 1 && a.kw == 1 && a.pad == 0 && kbytes % ks == 0;
+    if (tile == 0) {
+        auto blocks = [&](int bm, int bn) { return (long long)((a.M + bm - 1) / bm) * ((a.Co + bn - 1) / bn); };
+        const long long want = 2 * 256;
+        if (a.Co > 64) tile = blocks(128, 128) >= want ? 1 : (blocks(64, 128) >= want ? 4 : 3);
+        else tile = blocks(128, 64) >= want ? 2 : 3;
+    }
+    if (ns == 0) ns = 2;     // measured: more workgroups per CU beat a deeper ring at these problem sizes
+    if (ks == 128) {
+        if (tile == 1) return launch_igemm_tile<ES, 128, 128, 128>(a, plain, ns, s);
+        if (tile == 2) return launch_igemm_tile<ES, 128, 64, 128>(a, plain, ns, s);
+        if (tile == 4) return launch_igemm_tile<ES, 64, 128, 128>(a, plain, ns, s);
+        return launch_igemm_tile<ES, 64, 64, 128>(a, plain, ns, s);
+    }
+    if (tile == 1) return launch_igemm_tile<ES, 128, 128, 64>(a, plain, ns, s);
+    if (tile == 2) return launch_igemm_tile<ES, 128, 64, 64>(a, plain, ns, s);
+    if (tile == 4) return launch_igemm_tile<ES, 64, 128, 64>(a, plain, ns, s);
+    return launch_igemm_tile<ES, 64, 64, 64>(a, plain, ns, s);
+}
+
+template hipError_t launch_conv_igemm<1>(const ConvArgs&, int, hipStream_t);
+template hipError_t launch_conv_igemm<2>(const ConvArgs&, int, hipStream_t);
+
+}  // namespace ee
