@@ -151,7 +151,7 @@ class Engine:
         self.esize = 1 if self.dtype == EE_I8 else 2
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _lib is not None:      # module globals are gone at interpreter exit
             _lib.ee_destroy(self._h)
             self._h = None
 

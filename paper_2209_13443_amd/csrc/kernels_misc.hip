@@ -228,56 +228,83 @@ hipError_t launch_head_gap(const HeadArgs& a, int dtype, hipStream_t s)
 }
 
 // ---- exit head, step 2: FC ------------------------------------------------------------------------------
-// grid (class tiles of 16, sample tiles of 16); lane = (class j, sample b).  The reduction over C runs
-// in slabs of 512 channels: the 16 pooled feature rows (requantised on the fly for int8) and the 16
-// weight rows of a slab sit in LDS, rows padded by 16 bytes.
+// logits[b][j] = b_j + sum_c g[b][c] * W[j][c] as a 16 x 16 matrix-core tile per workgroup: rows = 16
+// classes (A operand, weight rows read straight from global memory, 16 bytes per lane), columns = 16
+// samples (B operand, the pooled features: requantised on the fly for int8; split into a bf16 head and
+// a bf16 remainder for bf16 so that the float mean loses nothing that matters).  The 4 wavefronts take
+// every 4th 64-byte step of the reduction and add their partial tiles through LDS.
+//   v_mfma_i32_16x16x64_i8 / v_mfma_f32_16x16x32_bf16, lane l: row l%16, k-bytes [16*(l/16), +16);
+//   D: column l%16, rows 4*(l/16) + v for accumulator register v = 0..3.
+typedef float v4f_m __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf_m __attribute__((ext_vector_type(8)));
+
 template <int ES>
 __global__ __launch_bounds__(256) void fc_kernel(HeadArgs a)
 {
-    constexpr int CK = 512;
-    constexpr int ROWG = (ES == 1 ? CK : CK * 4) + 16;       // feature row: int8 (i8) or float (bf16)
-    constexpr int ROWW = CK * ES + 16;
-    __shared__ __attribute__((aligned(16))) unsigned char gs[16 * ROWG];
-    __shared__ __attribute__((aligned(16))) unsigned char ws[16 * ROWW];
+    __shared__ int part[4][256];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j0 = blockIdx.x * 16, b0 = blockIdx.y * 16;
-    const int jl = threadIdx.x & 15, bl = threadIdx.x >> 4;
-    const int j = j0 + jl, b = b0 + bl;
-    int acci = 0;
-    float accf = 0.f;
-    for (int cbase = 0; cbase < a.C; cbase += CK) {
-        const int cw = min(CK, a.C - cbase);
-        __syncthreads();
-        for (int i = threadIdx.x; i < 16 * cw; i += 256) {
-            const int r = i / cw, c = i - r * cw;
-            const int bb = b0 + r, jj = j0 + r;
+    const int r = lane & 15, kq = lane >> 4;
+    const int j = j0 + r, b = b0 + r;
+    const int CB = a.C * ES;                                   // bytes per weight row (a multiple of 16)
+    const int nsteps = (CB + 63) / 64;
+    const unsigned char* wrow = (const unsigned char*)a.wfc + (long long)min(j, a.n_cls - 1) * CB;
+    const bool jin = j < a.n_cls, bin = b < a.B;
+    const v4i zero4 = {0, 0, 0, 0};
+    v4i acci = zero4;
+    v4f_m accf = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = wave; s0 < nsteps; s0 += 16) {
+        v4i wv[4], gv[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {                           // all loads of 4 steps first
+            const int kb = (s0 + 4 * u) * 64 + kq * 16;
+            const bool kin = kb < CB;
+            wv[u] = kin && jin ? *(const v4i*)(wrow + kb) : zero4;
+            const int* sp = a.sums + (long long)min(b, a.B - 1) * a.C + kb / ES;
+#pragma unroll
+            for (int q = 0; q < (ES == 1 ? 4 : 2); ++q) gv[u][q] = kin && bin ? *(const v4i*)(sp + 4 * q) : zero4;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
             if constexpr (ES == 1) {
-                int g = 0;
-                if (bb < a.B) {
-                    const int sum = a.sums[(long long)bb * a.C + cbase + c];
-                    g = a.gap_shift > 0 ? (sum + (1 << (a.gap_shift - 1))) >> a.gap_shift : sum;
+                v4i g8 = zero4;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int sum = gv[u][e >> 2][e & 3];
+                    int g = a.gap_shift > 0 ? (sum + (1 << (a.gap_shift - 1))) >> a.gap_shift : sum;
                     g = min(max(g, -128), 127);
+                    g8[e >> 2] |= (g & 0xFF) << (8 * (e & 3));
                 }
-                ((signed char*)(gs + r * ROWG))[c] = (signed char)g;
-                ((signed char*)(ws + r * ROWW))[c] = jj < a.n_cls ? ((const signed char*)a.wfc)[(long long)jj * a.C + cbase + c] : 0;
+                acci = __builtin_amdgcn_mfma_i32_16x16x64_i8(wv[u], g8, acci, 0, 0, 0);
             } else {
-                ((float*)(gs + r * ROWG))[c] = bb < a.B ? ((const float*)a.sums)[(long long)bb * a.C + cbase + c] : 0.f;
-                ((uint16_t*)(ws + r * ROWW))[c] = jj < a.n_cls ? ((const uint16_t*)a.wfc)[(long long)jj * a.C + cbase + c] : 0;
+                v4i hi = zero4, lo = zero4;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float g = __int_as_float(gv[u][e >> 2][e & 3]);
+                    const uint16_t h = f32_to_bf16_rne_m(g);
+                    const uint16_t l = f32_to_bf16_rne_m(g - bf16_to_f32_m(h));
+                    hi[e >> 1] |= (int)((unsigned)h << (16 * (e & 1)));
+                    lo[e >> 1] |= (int)((unsigned)l << (16 * (e & 1)));
+                }
+                accf = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf_m, wv[u]), __builtin_bit_cast(v8bf_m, hi), accf, 0, 0, 0);
+                accf = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf_m, wv[u]), __builtin_bit_cast(v8bf_m, lo), accf, 0, 0, 0);
             }
         }
-        __syncthreads();
-        if constexpr (ES == 1) {
-            const signed char* g = (const signed char*)(gs + bl * ROWG);
-            const signed char* w = (const signed char*)(ws + jl * ROWW);
-            for (int c = 0; c < cw; c += 4) acci = __builtin_amdgcn_sdot4(*(const int*)(g + c), *(const int*)(w + c), acci, false);
-        } else {
-            const float* g = (const float*)(gs + bl * ROWG);
-            const uint16_t* w = (const uint16_t*)(ws + jl * ROWW);
-            for (int c = 0; c < cw; ++c) accf = fmaf(g[c], bf16_to_f32_m(w[c]), accf);
-        }
     }
-    if (j >= a.n_cls || b >= a.B) return;
-    if constexpr (ES == 1) ((int*)a.logits)[(long long)b * a.n_cls + j] = acci + ((const int*)a.bfc)[j];
-    else ((float*)a.logits)[(long long)b * a.n_cls + j] = a.logit_scale * (accf + ((const float*)a.bfc)[j]);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) part[wave][v * 64 + lane] = ES == 1 ? acci[v] : __float_as_int(accf[v]);
+    __syncthreads();
+    const int v = threadIdx.x >> 6;                             // this thread finishes element (class 4*kq + v, sample r)
+    const int jj = j0 + 4 * kq + v;
+    if (jj >= a.n_cls || !bin) return;
+    if constexpr (ES == 1) {
+        const int t = part[0][threadIdx.x] + part[1][threadIdx.x] + part[2][threadIdx.x] + part[3][threadIdx.x];
+        ((int*)a.logits)[(long long)b * a.n_cls + jj] = t + ((const int*)a.bfc)[jj];
+    } else {
+        const float t = (__int_as_float(part[0][threadIdx.x]) + __int_as_float(part[1][threadIdx.x])) +
+                        (__int_as_float(part[2][threadIdx.x]) + __int_as_float(part[3][threadIdx.x]));
+        ((float*)a.logits)[(long long)b * a.n_cls + jj] = a.logit_scale * (t + ((const float*)a.bfc)[jj]);
+    }
 }
 
 hipError_t launch_head_fc(const HeadArgs& a, int dtype, hipStream_t s)
