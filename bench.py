@@ -67,6 +67,7 @@ def main():
     del chunks
     torch.cuda.synchronize()
 
+    eng.autotune(reps=5)                               # design-time per-(layer, batch) kernel configuration table
     lut = eng.measure_lut(reps=3)                      # design-time exit-level latency table
     min_incr = args.min_incr or max(1, b_max // 4)
 

@@ -153,6 +153,19 @@ const char* ee_kernel_name(int kernel_class);
  * per workgroup).  Results never depend on it.  Returns the previous setting, EE_ERR_ARG if out of range. */
 int ee_tune_conv_tile(int tile);
 
+/* Kernel-configuration table, one entry per (convolution layer, active-batch bucket 2^k): the GPU
+ * counterpart of the run-time look-up the paper keeps per layer and batch size (Sec. III-A, the
+ * configuration buffer of the Fluid Batching engine).  ee_autotune times the candidate workgroup tiles,
+ * reduction steps and LDS ring depths of every matrix-core convolution on the context's own workspace
+ * (`reps` launches per candidate, synchronous, overwrites the workspace activations) and keeps the
+ * fastest; until it is called the configuration is chosen from the layer shape alone.  Results never
+ * depend on the table.  ee_config_table copies layer `layer`'s entries to cfg_out[0..n) (host) and
+ * returns how many the layer has (0 = not tuned or not a matrix-core convolution); an entry is
+ * tile | step << 4 | stages << 8 with tile 1: 128x128, 2: 128x64, 3: 64x64, 4: 64x128 (pixels x channels),
+ * step 1: 64, 2: 128 bytes of the reduction axis per stage.  EE_ERR_ARG for bad arguments. */
+int ee_autotune(ee_ctx* ctx, int reps);
+int ee_config_table(const ee_ctx* ctx, int layer, int* cfg_out, int n);
+
 /* Host copy of the 256-entry table round(2^30 * 2^(-i/256)) used by the integer softmax. */
 const uint32_t* ee_exp2_table(void);
 

@@ -24,7 +24,7 @@ EVENT_DT = np.dtype([("t_ns", "<i8"), ("kind", "<i4"), ("stage", "<i4"), ("b", "
 
 SYMBOLS = ["ee_strerror", "ee_blob_check", "ee_create", "ee_destroy", "ee_query", "ee_stage_forward", "ee_exit_head",
            "ee_compact_refill", "ee_serve_stream", "ee_schedule_sim", "ee_measure_lut", "ee_profile_enable",
-           "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_last_logits", "ee_profile_reserve"]
+           "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_last_logits", "ee_profile_reserve", "ee_autotune", "ee_config_table"]
 
 
 class Trace(C.Structure):
@@ -65,6 +65,8 @@ _lib.ee_serve_stream.argtypes = [_V, C.POINTER(Trace), _V, C.POINTER(ServeOpts),
 _lib.ee_schedule_sim.argtypes = [C.c_int, C.POINTER(Trace), _V, C.POINTER(ServeOpts), _V, C.POINTER(ServeStats), _V, C.c_int64]
 _lib.ee_measure_lut.argtypes = [_V, C.c_int, _V]
 _lib.ee_last_logits.argtypes = [_V, C.c_int, _V]
+_lib.ee_autotune.argtypes = [_V, C.c_int]
+_lib.ee_config_table.argtypes = [_V, C.c_int, _V, C.c_int]
 _lib.ee_profile_enable.argtypes = [_V, C.c_int]
 _lib.ee_profile_read.argtypes = [_V, _V, _V]
 _lib.ee_profile_reserve.argtypes = [_V, C.c_int64]
@@ -218,6 +220,16 @@ class Engine:
         lut = np.zeros((self.n_stages, self.b_max), np.int64)
         _chk(_lib.ee_measure_lut(self._h, reps, lut.ctypes.data))
         return lut
+
+    def autotune(self, reps=5):
+        _chk(_lib.ee_autotune(self._h, int(reps)))
+
+    def config_table(self, layer):
+        buf = (C.c_int * 16)()
+        n = _lib.ee_config_table(self._h, int(layer), buf, 16)
+        if n < 0:
+            _chk(n)
+        return list(buf)[:n]
 
     def profile(self, enable):
         _chk(_lib.ee_profile_enable(self._h, int(enable)))

@@ -291,6 +291,92 @@ extern "C" int ee_query(const ee_ctx* ctx, int* n_stages, int64_t* in_bytes, int
     return EE_OK;
 }
 
+// ---- one convolution on the matrix cores -----------------------------------------------------------
+hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg)
+{
+    const OpPlan& p = plans[op];
+    const OpDesc& d = p.d;
+    const int dt = net.dtype;
+    ConvArgs a{};
+    a.w = p.w_dev; a.bias = p.b_dev; a.res = res; a.y = dst; a.zeros = zero_page;
+    a.magic_howo = (unsigned)(0x100000000ull / (unsigned)(d.h_out * d.w_out) - (d.h_out * d.w_out == 1));
+    a.magic_wo = (unsigned)(0x100000000ull / (unsigned)d.w_out - (d.w_out == 1));
+    for (int r = 0; r < d.kh && r * d.kw < 32; ++r) a.tap_rows |= 1u << (r * d.kw);
+    a.M = b * d.h_out * d.w_out; a.H = d.h_in; a.W = d.w_in; a.Ci = d.c_in; a.Ho = d.h_out; a.Wo = d.w_out; a.Co = d.c_out;
+    a.kh = d.kh; a.kw = d.kw; a.stride = d.stride; a.pad = d.pad; a.Kp = p.Kp;
+    a.shift = d.shift; a.res_shift = d.res_shift; a.lo = d.lo; a.hi = d.hi; a.f_lo = d.f_lo; a.f_hi = d.f_hi;
+    if (p.impl == IMPL_MFMA_C4) {
+        a.x = pad_bufs[p.pad_buf]; a.mode = 1; a.Hp = p.Hp; a.Wp = p.Wp; a.kwp = p.kwp;
+        return dt == EE_I8 ? launch_conv_mfma_i8(a, stream) : launch_conv_mfma_bf16(a, stream);
+    }
+    a.x = src; a.mode = 0;
+    return dt == EE_I8 ? launch_conv_igemm<1>(a, cfg, stream) : launch_conv_igemm<2>(a, cfg, stream);
+}
+
+// ---- per-(layer, B_act) kernel configuration table ----------------------------------------------------
+// The GPU face of the paper's run-time configuration look-up (Sec. III-A: one entry per layer and active
+// batch size, fetched at run time): for every matrix-core convolution and every batch bucket 2^k the
+// candidate tilings / reduction steps / ring depths are timed on the workspace buffers and the fastest
+// is kept.  Results never depend on the choice.
+extern "C" int ee_autotune(ee_ctx* ctx, int reps)
+{
+    if (!ctx || reps < 1 || reps > 1000) return EE_ERR_ARG;
+    const bool was = ctx->profiling;
+    ctx->profiling = false;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return EE_ERR_DEVICE;
+    const int es = ctx->net.elem_bytes();
+    int rc = EE_OK;
+    std::vector<int> buckets;
+    for (int k = 0; (1 << k) < 2 * ctx->b_max; ++k) buckets.push_back(std::min(1 << k, ctx->b_max));
+    for (size_t s = 0; s < ctx->net.stages.size() && !rc; ++s) {
+        const StageDesc& st = ctx->net.stages[s];
+        for (int k = 0; k < st.n_ops && !rc; ++k) {
+            OpPlan& p = ctx->plans[st.first_op + k];
+            if (p.impl != IMPL_MFMA) continue;
+            const OpDesc& d = p.d;
+            const void* src = resolve(ctx, p.src_buf, ctx->in_buf[s], ctx->out_buf[s]);
+            void* dst = resolve(ctx, p.dst_buf, ctx->in_buf[s], ctx->out_buf[s]);
+            const void* res = d.res >= 0 ? resolve(ctx, p.res_buf, ctx->in_buf[s], ctx->out_buf[s]) : nullptr;
+            const bool k128 = (d.kh * d.kw * d.c_in * es) % 128 == 0;
+            std::vector<int> best(buckets.size(), 0);
+            for (size_t bi = 0; bi < buckets.size() && !rc; ++bi) {
+                float best_ms = 1e30f;
+                for (int tile = 1; tile <= 4; ++tile)
+                    for (int ksel = 1; ksel <= (k128 ? 2 : 1); ++ksel)
+                        for (int ns = 2; ns <= 3; ++ns) {
+                            const int cfg = tile | (ksel << 4) | (ns << 8);
+                            if (ctx->launch_conv(st.first_op + k, buckets[bi], src, dst, res, cfg) != hipSuccess) {
+                                (void)hipGetLastError();                       // this configuration does not fit: skip it
+                                continue;
+                            }
+                            hipEventRecord(e0, ctx->stream);
+                            for (int r = 0; r < reps; ++r) ctx->launch_conv(st.first_op + k, buckets[bi], src, dst, res, cfg);
+                            hipEventRecord(e1, ctx->stream);
+                            if (hipEventSynchronize(e1) != hipSuccess) { rc = EE_ERR_DEVICE; break; }
+                            float ms = 0.f;
+                            hipEventElapsedTime(&ms, e0, e1);
+                            if (ms < best_ms) { best_ms = ms; best[bi] = cfg; }
+                        }
+            }
+            if (!rc) p.cfg = best;
+        }
+    }
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    ctx->profiling = was;
+    return rc;
+}
+
+/* copies the table of layer `op` (one entry per batch bucket 2^k, 0 = not tuned) to cfg_out[n]; returns the entry count */
+extern "C" int ee_config_table(const ee_ctx* ctx, int op, int* cfg_out, int n)
+{
+    if (!ctx || op < 0 || op >= (int)ctx->plans.size() || n < 0 || (n > 0 && !cfg_out)) return EE_ERR_ARG;
+    const std::vector<int>& c = ctx->plans[op].cfg;
+    for (int i = 0; i < n && i < (int)c.size(); ++i) cfg_out[i] = c[i];
+    return (int)c.size();
+}
+
 // ---- one backbone segment ------------------------------------------------------------------------
 int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out)
 {
@@ -305,27 +391,15 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out)
         const double ops = p.ops_per_sample * b, bytes = p.bytes_per_sample * b + p.weight_bytes;
         hipError_t e = hipSuccess;
         if (p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_C4) {
-            ConvArgs a{};
-            a.w = p.w_dev; a.bias = p.b_dev; a.res = res; a.y = dst; a.zeros = zero_page;
-            a.magic_howo = (unsigned)(0x100000000ull / (unsigned)(d.h_out * d.w_out) - (d.h_out * d.w_out == 1));
-            a.magic_wo = (unsigned)(0x100000000ull / (unsigned)d.w_out - (d.w_out == 1));
-            a.M = b * d.h_out * d.w_out; a.H = d.h_in; a.W = d.w_in; a.Ci = d.c_in; a.Ho = d.h_out; a.Wo = d.w_out; a.Co = d.c_out;
-            a.kh = d.kh; a.kw = d.kw; a.stride = d.stride; a.pad = d.pad; a.Kp = p.Kp;
-            a.shift = d.shift; a.res_shift = d.res_shift; a.lo = d.lo; a.hi = d.hi; a.f_lo = d.f_lo; a.f_hi = d.f_hi;
             if (p.impl == IMPL_MFMA_C4) {
-                void* padded = pad_bufs[p.pad_buf];
                 const double pb = (double)b * ((double)d.h_in * d.w_in * d.c_in + (double)p.Hp * p.Wp * 4) * es;
-                e = timed(EE_K_PAD_INPUT, 0.0, pb, [&] { return launch_pad_input(src, padded, b, d.h_in, d.w_in, d.c_in, p.Hp, p.Wp, d.pad, dt, stream); });
+                e = timed(EE_K_PAD_INPUT, 0.0, pb, [&] { return launch_pad_input(src, pad_bufs[p.pad_buf], b, d.h_in, d.w_in, d.c_in, p.Hp, p.Wp, d.pad, dt, stream); });
                 if (e != hipSuccess) return EE_ERR_DEVICE;
-                a.x = padded; a.mode = 1; a.Hp = p.Hp; a.Wp = p.Wp; a.kwp = p.kwp;
-            } else {
-                a.x = src; a.mode = 0;
             }
+            int cfg = forced_conv_tile();
+            if (cfg == 0 && !p.cfg.empty()) cfg = p.cfg[std::min<size_t>(bucket_of(b), p.cfg.size() - 1)];
             const int cls = p.impl == IMPL_MFMA ? EE_K_CONV_MFMA : EE_K_CONV_FIRST;
-            e = timed(cls, ops, bytes, [&] {
-                if (p.impl == IMPL_MFMA) return dt == EE_I8 ? launch_conv_igemm<1>(a, forced_conv_tile(), stream) : launch_conv_igemm<2>(a, forced_conv_tile(), stream);
-                return dt == EE_I8 ? launch_conv_mfma_i8(a, stream) : launch_conv_mfma_bf16(a, stream);
-            }, st.first_op + k);
+            e = timed(cls, ops, bytes, [&] { return launch_conv(st.first_op + k, b, src, dst, res, cfg); }, st.first_op + k);
         } else if (p.impl == IMPL_DIRECT) {
             DirectConvArgs a{src, p.w_dev, p.b_dev, res, dst, b * d.h_out * d.w_out, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.c_out,
                              d.kh, d.kw, d.stride, d.pad, d.shift, d.res_shift, d.lo, d.hi, d.f_lo, d.f_hi};

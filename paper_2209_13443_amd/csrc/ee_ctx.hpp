@@ -18,6 +18,7 @@ struct OpPlan {
     int Kp = 0, kwp = 0, Hp = 0, Wp = 0;
     int src_buf = 0, dst_buf = 0, res_buf = 0;   // BUF_EXT_* or an index into Ctx::pool
     int pad_buf = -1;           // zero-padded 4-channel copy of the input (IMPL_MFMA_C4)
+    std::vector<int> cfg;       // kernel configuration per batch bucket (see ee_autotune); empty = by shape
     double ops_per_sample = 0, bytes_per_sample = 0, weight_bytes = 0;
 };
 
@@ -62,6 +63,9 @@ struct ee_ctx {
 
     // internal entry points shared by the C ABI and the stream driver (no argument checks)
     int run_stage(int stage, int b_act, const void* act_in, void* act_out);
+    // launches layer `op` (an index into plans) on b samples with the given kernel configuration (0 = by shape)
+    hipError_t launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg);
+    static int bucket_of(int b) { int k = 0; while ((1 << k) < b) ++k; return k; }     // smallest k with 2^k >= b
     int run_head(int stage, int b_act, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag);
     // brackets `launch` with a pair of events when profiling
     template <typename F>

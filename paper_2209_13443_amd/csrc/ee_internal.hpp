@@ -55,6 +55,7 @@ struct ConvArgs {
     int kh, kw, stride, pad;
     int Kp;              // weight row pitch in elements (reduction length, zero padded)
     unsigned magic_howo, magic_wo;   // floor(2^32 / (Ho*Wo)), floor(2^32 / Wo): division by multiply-high
+    unsigned tap_rows;   // bit r*kw set for every kernel row r (kh*kw <= 31)
     int mode;            // 0: Ci % 16 == 0 loader with bounds checks; 1: 4-channel zero-padded input
     int Hp, Wp, kwp;     // mode 1: padded input dims and padded kernel width
     int shift, res_shift, lo, hi;

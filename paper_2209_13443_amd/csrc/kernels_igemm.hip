@@ -30,6 +30,7 @@
 // requantised / clamped, packed and written into an LDS tile from which the workgroup stores whole
 // 16-byte chunks along the channel axis.
 #include <type_traits>
+#include <utility>
 
 #include "ee_internal.hpp"
 
@@ -71,6 +72,13 @@ __host__ __device__ constexpr unsigned igemm_ring_bytes(int ns, int nk, int stag
 }
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), unrolled at compile time
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    [&]<int... I>(std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>{}), ...); }(std::make_integer_sequence<int, N>{});
+}
+
 __device__ __forceinline__ unsigned fast_div(unsigned m, unsigned d, unsigned magic)   // magic = floor(2^32 / d), d >= 1
 {
     unsigned q = __umulhi(m, magic);
@@ -78,14 +86,27 @@ __device__ __forceinline__ unsigned fast_div(unsigned m, unsigned d, unsigned ma
     return q;
 }
 
-__device__ __forceinline__ uint16_t to_bf16_rne(float v)
+__device__ __forceinline__ uint32_t to_bf16_rne(float v)
 {
     uint32_t u = __float_as_uint(v);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40;
     u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    return u >> 16;
 }
-__device__ __forceinline__ float from_bf16(uint32_t b) { return __uint_as_float(b << 16); }
+
+__device__ __forceinline__ int clamp_i32(int v, int lo, int hi)       // lo <= hi
+{
+    int r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
+    return r;
+}
+// the low bytes of four ints as one dword, q0 lowest
+__device__ __forceinline__ unsigned pack4_i8(int q0, int q1, int q2, int q3)
+{
+    const unsigned lo = __builtin_amdgcn_perm((unsigned)q1, (unsigned)q0, 0x0c0c0400u);
+    const unsigned hi = __builtin_amdgcn_perm((unsigned)q3, (unsigned)q2, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
 
 }  // namespace
 
@@ -93,7 +114,7 @@ __device__ __forceinline__ float from_bf16(uint32_t b) { return __uint_as_float(
 // the reduction axis per stage.  ns (2..4, not above the number of steps + 1): stages in the ring.  PLAIN: 1x1 kernel without padding whose
 // reduction length is a multiple of KS -- the source address of a row then simply advances by KS.
 template <int ES, int BM, int BN, int KS, bool PLAIN>
-__global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int gn, int per_xcd, int ns)
+__global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int gn, unsigned magic_gn, int per_xcd, int ns)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
@@ -109,8 +130,9 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int
     static_assert(NA >= 1 && NB >= 1 && NO >= 1, "tile too small for 256 lanes");
 
     const int xcd = blockIdx.x & 7, wslot = blockIdx.x >> 3;
-    const int mt = xcd * per_xcd + wslot / gn, nt = wslot % gn;
-    if (mt >= gm || wslot / gn >= per_xcd) return;
+    const int mslot = (int)fast_div((unsigned)wslot, (unsigned)gn, magic_gn);
+    const int mt = xcd * per_xcd + mslot, nt = wslot - mslot * gn;
+    if (mt >= gm || mslot >= per_xcd) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -164,51 +186,46 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int
             voffA[j] += cchunk * 16;
             maskA[j] = 0;
         } else {
-            unsigned colmask = 0, msk = 0;
-            for (int s = 0; s < a.kw; ++s) colmask |= (unsigned)((unsigned)(ix0 + s) < (unsigned)a.W) << s;
-            for (int r = 0; r < a.kh; ++r)
-                if ((unsigned)(iy0 + r) < (unsigned)a.H) msk |= colmask << (r * a.kw);
-            maskA[j] = live ? msk : 0u;
+            // taps s in [s_lo, s_hi) and r in [r_lo, r_hi) fall inside the image; bit r*kw + s of the mask says so
+            const int s_lo = max(0, -ix0), s_hi = min(a.kw, a.W - ix0), r_lo = max(0, -iy0), r_hi = min(a.kh, a.H - iy0);
+            const unsigned colmask = s_hi > s_lo ? ((1u << s_hi) - 1u) & ~((1u << s_lo) - 1u) : 0u;
+            const unsigned rowsel = r_hi > r_lo ? a.tap_rows & ((1u << (r_hi * a.kw)) - 1u) & ~((1u << (r_lo * a.kw)) - 1u) : 0u;
+            maskA[j] = live ? colmask * rowsel : 0u;
         }
-    }
-    if (!PLAIN) {
-        const int kb = cchunk * 16;
-        tap = kb / CiB;
-        tc = kb - tap * CiB;
-        const int tr = tap / a.kw;
-        ts = tap - tr * a.kw;
-        toff = (tr * a.W + ts) * CiB + tc;
     }
     const int ntaps = a.kh * a.kw;
+    auto advance_tap = [&](int bytes) {             // moves this lane's chunk `bytes` further along the (r, s, c) axis
+        tc += bytes;
+        toff += bytes;                              // taps of one kernel row are contiguous in NHWC
+        while (tc >= CiB) {
+            tc -= CiB;
+            ++tap;
+            if (++ts == a.kw) { ts = 0; toff += (a.W - a.kw) * CiB; }
+        }
+    };
+    if (!PLAIN) advance_tap(cchunk * 16);
 
-    auto issue = [&](int stage) {
-        const unsigned sbase = lds0 + stage * STAGE + wave * 1024;
-        if (PLAIN) {
-#pragma unroll
-            for (int j = 0; j < NA; ++j) {
-                dma16(sbase + j * 4096, xb, voffA[j]);
-                voffA[j] += KS;
+    // One piece = one 16-byte-per-lane copy: pieces 0..NA-1 are activation rows, NA..LPT-1 weight rows.
+    auto issue_piece = [&](auto piece, unsigned sbase, unsigned tapbit) {
+        constexpr int P = decltype(piece)::value;
+        if constexpr (P < NA) {
+            if (PLAIN) {
+                dma16(sbase + P * 4096, xb, voffA[P]);
+                voffA[P] += KS;
+            } else {
+                const unsigned char* p = (maskA[P] & tapbit) ? xb + (unsigned)(voffA[P] + toff) : zp;
+                dma16(sbase + P * 4096, p);
             }
         } else {
-            const unsigned tapbit = tap < ntaps ? 1u << tap : 0u;
-#pragma unroll
-            for (int j = 0; j < NA; ++j) {
-                const unsigned char* p = (maskA[j] & tapbit) ? xb + (unsigned)(voffA[j] + toff) : zp;
-                dma16(sbase + j * 4096, p);
-            }
-            tc += KS;
-            toff += KS;
-            while (tc >= CiB) {
-                tc -= CiB;
-                ++tap;
-                if (++ts == a.kw) { ts = 0; toff += (a.W - a.kw) * CiB; }
-            }
+            dma16(sbase + BM * KS + (P - NA) * 4096, a.w, voffB[P - NA]);
+            voffB[P - NA] += KS;
         }
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            dma16(sbase + BM * KS + j * 4096, a.w, voffB[j]);
-            voffB[j] += KS;
-        }
+    };
+    auto issue_all = [&](int stage) {
+        const unsigned sbase = lds0 + stage * STAGE + wave * 1024;
+        const unsigned tapbit = tap < ntaps ? 1u << tap : 0u;
+        static_for<LPT>([&](auto piece) { issue_piece(piece, sbase, tapbit); });
+        if (!PLAIN) advance_tap(KS);
     };
 
     // ---- fragment addressing ---------------------------------------------------------------------------
@@ -226,94 +243,133 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][i][v] = 0;
 
-    auto compute = [&](int stage) {
-        const unsigned char* sa = lds + stage * STAGE + wm0 * KS;
-        const unsigned char* sb = lds + stage * STAGE + (BM + wn0) * KS;
+    // One reduction step out of stage `sc`; with ISSUE the copies of a later step into stage `si` are
+    // spread between the matrix instructions so that the copy queue fills while the matrix cores work.
+    // Fragments of sub-step u+1 are read while sub-step u multiplies.
+    auto step = [&](int sc, int si, auto issue_tag) {
+        constexpr bool ISSUE = decltype(issue_tag)::value;
+        constexpr int NSUB = KS / 32, PPS = (LPT + NSUB - 1) / NSUB;
+        const unsigned char* sa = lds + sc * STAGE + wm0 * KS;
+        const unsigned char* sb = lds + sc * STAGE + (BM + wn0) * KS;
+        const unsigned sbase = lds0 + si * STAGE + wave * 1024;
+        const unsigned tapbit = tap < ntaps ? 1u << tap : 0u;
+        v4i fw[2][TN], fx[2][TM];
+        auto read_frags = [&](int sub, v4i* w, v4i* x) {
 #pragma unroll
-        for (int sub = 0; sub < KS / 32; ++sub) {
-            v4i fw[TN], fx[TM];
+            for (int j = 0; j < TN; ++j) w[j] = *(const v4i*)(sb + 32 * j * KS + fragoff[sub]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) fw[j] = *(const v4i*)(sb + 32 * j * KS + fragoff[sub]);
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fx[i] = *(const v4i*)(sa + 32 * i * KS + fragoff[sub]);
+            for (int i = 0; i < TM; ++i) x[i] = *(const v4i*)(sa + 32 * i * KS + fragoff[sub]);
+        };
+        read_frags(0, fw[0], fx[0]);
+        static_for<NSUB>([&](auto sub_tag) {
+            constexpr int SUB = decltype(sub_tag)::value;
+            // fixed order (the scheduler may not move anything across these fences): next fragments, copies,
+            // then this sub-step's matrix instructions, which only wait for the fragments read one round earlier
+            if constexpr (SUB + 1 < NSUB) read_frags(SUB + 1, fw[(SUB + 1) & 1], fx[(SUB + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (ISSUE)
+                static_for<PPS>([&](auto q_tag) {
+                    constexpr int P = SUB * PPS + decltype(q_tag)::value;
+                    if constexpr (P < LPT) issue_piece(std::integral_constant<int, P>{}, sbase, tapbit);
+                });
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
                     if constexpr (ES == 1)
-                        acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[j], fx[i], acc[j][i], 0, 0, 0);
+                        acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[SUB & 1][j], fx[SUB & 1][i], acc[j][i], 0, 0, 0);
                     else
-                        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fw[j]), __builtin_bit_cast(v8bf, fx[i]),
-                                                                             acc[j][i], 0, 0, 0);
+                        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fw[SUB & 1][j]),
+                                                                             __builtin_bit_cast(v8bf, fx[SUB & 1][i]), acc[j][i], 0, 0, 0);
                 }
-        }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        if (ISSUE && !PLAIN) advance_tap(KS);
     };
 
     // ---- main loop: step ks computes out of stage ks % ns while steps ks+1 .. ks+ns-1 are in flight ----
     for (int s = 0; s < ns - 1; ++s)
-        if (s < nk) issue(s);
-    int st_c = 0, st_i = ns - 1;
-    for (int ks = 0; ks < nk; ++ks) {
+        if (s < nk) issue_all(s);
+    int st_c = 0, st_i = ns - 1, ks = 0;
+    for (; ks + ns - 1 < nk; ++ks) {
         // steps ks+1 .. ks+ns-2 may still be in flight, each LPT copies of this wavefront
-        if (ks + ns - 2 >= nk || ns == 2) wait_copies_then_barrier<0>();
+        if (ns == 2) wait_copies_then_barrier<0>();
         else if (ns == 3) wait_copies_then_barrier<LPT>();
         else wait_copies_then_barrier<2 * LPT>();
-        if (ks + ns - 1 < nk) issue(st_i);
-        compute(st_c);
+        step(st_c, st_i, std::true_type{});
         st_c = st_c + 1 == ns ? 0 : st_c + 1;
         st_i = st_i + 1 == ns ? 0 : st_i + 1;
+    }
+    for (; ks < nk; ++ks) {                         // the last ns-1 steps: nothing left to copy
+        wait_copies_then_barrier<0>();
+        step(st_c, st_c, std::false_type{});
+        st_c = st_c + 1 == ns ? 0 : st_c + 1;
     }
     lds_barrier();                                  // every wavefront is done with the ring
 
     // ---- epilogue ------------------------------------------------------------------------------------------
     unsigned char* ro = lds + ro_off;
     const int* lbias = (const int*)(lds + bias_off);
+    // Cell of (pixel row r, channel cl) in the output tile: chunk (cl*ES/16) ^ (r & OSWZ) of row r.  r & 7 is the
+    // lane's frow & 7 for all of its rows, and the chunk index splits into a wave-uniform part and a
+    // compile-time part, so one XOR and one add per cell remain.
+    const int swz_l = frow & OSWZ;
+    auto finish = [&](auto res_tag, auto wide_tag) {
+        constexpr bool RES = decltype(res_tag)::value, WIDE = decltype(wide_tag)::value;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int r = wm0 + 32 * i + frow;
-        const int m = m0 + r;
+        for (int i = 0; i < TM; ++i) {
+            const int r = wm0 + 32 * i + frow;
+            const int m = m0 + r;
+            unsigned char* rowp = ro + r * OROW + 4 * hi * ES;
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int cl = wn0 + 32 * j + 8 * g + 4 * hi;                         // first of this lane's 4 channels
-                const int byte = cl * ES;
-                unsigned char* cell = ro + r * OROW + (((byte >> 4) ^ (r & OSWZ)) << 4) + (byte & 15);
-                const long long o = (long long)m * a.Co + n0 + cl;
-                const bool inside = m < a.M && n0 + cl < a.Co;
-                const v4i b4 = *(const v4i*)(lbias + cl);
-                if constexpr (ES == 1) {
-                    int packed = 0;
-                    if (has_res) packed = wide ? *(const int*)cell : (inside ? *(const int*)((const signed char*)a.res + o) : 0);
-                    int q[4];
+                for (int g = 0; g < 4; ++g) {
+                    const int cl = wn0 + 32 * j + 8 * g + 4 * hi;                     // first of this lane's 4 channels
+                    const int chunk = (wn0 * ES >> 4) + ((32 * j + 8 * g) * ES >> 4);  // 4*hi*ES stays inside the chunk
+                    unsigned char* cell = rowp + ((chunk ^ swz_l) << 4) + (((32 * j + 8 * g) * ES) & 15);
+                    const long long o = (long long)m * a.Co + n0 + cl;
+                    const bool inside = WIDE || (m < a.M && n0 + cl < a.Co);
+                    const v4i b4 = *(const v4i*)(lbias + cl);
+                    if constexpr (ES == 1) {
+                        int packed = 0;
+                        if (RES) packed = WIDE ? *(const int*)cell : (inside ? *(const int*)((const signed char*)a.res + o) : 0);
+                        int q[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int rv = (packed << (24 - 8 * e)) >> 24;                // sign-extended byte e
-                        const int t = acc[j][i][4 * g + e] + b4[e] + (rv << a.res_shift);
-                        q[e] = min(max(t >> a.shift, a.lo), a.hi);                   // rounding constant is part of the bias
+                        for (int e = 0; e < 4; ++e) {
+                            int t = acc[j][i][4 * g + e] + b4[e];                     // the rounding constant is part of the bias
+                            if (RES) t += __builtin_amdgcn_sbfe(packed, 8 * e, 8) << a.res_shift;
+                            q[e] = clamp_i32(t >> a.shift, a.lo, a.hi);
+                        }
+                        const unsigned out = pack4_i8(q[0], q[1], q[2], q[3]);
+                        if (WIDE) *(unsigned*)cell = out;
+                        else if (inside) *(unsigned*)((signed char*)a.y + o) = out;
+                    } else {
+                        uint2 packed = {0u, 0u};
+                        if (RES) packed = WIDE ? *(const uint2*)cell : (inside ? *(const uint2*)((const uint16_t*)a.res + o) : packed);
+                        const float r0 = __uint_as_float(packed.x << 16), r1 = __uint_as_float(packed.x & 0xFFFF0000u);
+                        const float r2 = __uint_as_float(packed.y << 16), r3 = __uint_as_float(packed.y & 0xFFFF0000u);
+                        float t0 = acc[j][i][4 * g + 0] + __int_as_float(b4[0]), t1 = acc[j][i][4 * g + 1] + __int_as_float(b4[1]);
+                        float t2 = acc[j][i][4 * g + 2] + __int_as_float(b4[2]), t3 = acc[j][i][4 * g + 3] + __int_as_float(b4[3]);
+                        if (RES) { t0 += r0; t1 += r1; t2 += r2; t3 += r3; }
+                        t0 = fminf(fmaxf(t0, a.f_lo), a.f_hi); t1 = fminf(fmaxf(t1, a.f_lo), a.f_hi);
+                        t2 = fminf(fmaxf(t2, a.f_lo), a.f_hi); t3 = fminf(fmaxf(t3, a.f_lo), a.f_hi);
+                        uint2 out;
+                        out.x = to_bf16_rne(t0) | (to_bf16_rne(t1) << 16);
+                        out.y = to_bf16_rne(t2) | (to_bf16_rne(t3) << 16);
+                        if (WIDE) *(uint2*)cell = out;
+                        else if (inside) *(uint2*)((uint16_t*)a.y + o) = out;
                     }
-                    const unsigned out = (unsigned)(q[0] & 0xFF) | ((unsigned)(q[1] & 0xFF) << 8) | ((unsigned)(q[2] & 0xFF) << 16) | ((unsigned)q[3] << 24);
-                    if (wide) *(unsigned*)cell = out;
-                    else if (inside) *(unsigned*)((signed char*)a.y + o) = out;
-                } else {
-                    uint2 packed = {0u, 0u};
-                    if (has_res) packed = wide ? *(const uint2*)cell : (inside ? *(const uint2*)((const uint16_t*)a.res + o) : packed);
-                    const uint32_t r4[4] = {packed.x & 0xFFFFu, packed.x >> 16, packed.y & 0xFFFFu, packed.y >> 16};
-                    uint32_t q[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float t = acc[j][i][4 * g + e] + __int_as_float(b4[e]);
-                        if (has_res) t = t + from_bf16(r4[e]);
-                        t = fminf(fmaxf(t, a.f_lo), a.f_hi);
-                        q[e] = to_bf16_rne(t);
-                    }
-                    uint2 out;
-                    out.x = q[0] | (q[1] << 16);
-                    out.y = q[2] | (q[3] << 16);
-                    if (wide) *(uint2*)cell = out;
-                    else if (inside) *(uint2*)((uint16_t*)a.y + o) = out;
                 }
-            }
+        }
+    };
+    if (wide) {
+        if (has_res) finish(std::true_type{}, std::true_type{});
+        else finish(std::false_type{}, std::true_type{});
+    } else {
+        if (has_res) finish(std::true_type{}, std::false_type{});
+        else finish(std::false_type{}, std::false_type{});
     }
     if (wide) {
         lds_barrier();
@@ -332,6 +388,7 @@ static hipError_t launch_igemm_tile(const ConvArgs& a, bool plain, int ns, hipSt
 {
     const int gm = (a.M + BM - 1) / BM, gn = (a.Co + BN - 1) / BN, per_xcd = (gm + 7) / 8;
     const dim3 grid((unsigned)(8 * per_xcd * gn));
+    const unsigned magic_gn = (unsigned)(0x100000000ull / (unsigned)gn - (gn == 1));
     const bool res_tile = a.res != nullptr && (a.Co * ES) % 16 == 0;
     const int nk = (a.kh * a.kw * a.Ci * ES + KS - 1) / KS;
     ns = ns < 2 ? 2 : (ns > 4 ? 4 : ns);
@@ -346,9 +403,9 @@ static hipError_t launch_igemm_tile(const ConvArgs& a, bool plain, int ns, hipSt
     if (granted != hipSuccess) return granted;
     if (lds_bytes > 160 * 1024) return hipErrorInvalidValue;
     if (plain)
-        hipLaunchKernelGGL((conv_igemm_kernel<ES, BM, BN, KS, true>), grid, dim3(256), lds_bytes, s, a, gm, gn, per_xcd, ns);
+        hipLaunchKernelGGL((conv_igemm_kernel<ES, BM, BN, KS, true>), grid, dim3(256), lds_bytes, s, a, gm, gn, magic_gn, per_xcd, ns);
     else
-        hipLaunchKernelGGL((conv_igemm_kernel<ES, BM, BN, KS, false>), grid, dim3(256), lds_bytes, s, a, gm, gn, per_xcd, ns);
+        hipLaunchKernelGGL((conv_igemm_kernel<ES, BM, BN, KS, false>), grid, dim3(256), lds_bytes, s, a, gm, gn, magic_gn, per_xcd, ns);
     return hipGetLastError();
 }
 

@@ -92,6 +92,29 @@ def test_int8_every_conv_tiling_bit_exact(torch, ee, orc, name, tile):
     eng.close()
 
 
+def test_autotuned_configuration_table_keeps_results(torch, ee, orc):
+    """The per-(layer, batch bucket) kernel configuration table only changes speed, never a byte."""
+    for name in ("resnet50_small_i8", "zoo_i8"):
+        blob = W.load_net(name)
+        eng = ee.Engine(blob, 12)
+        eng.autotune(reps=2)
+        tables = [eng.config_table(k) for k in range(len(blob.ops))]
+        assert any(len(t) > 0 for t in tables)
+        for t in tables:
+            for cfg in t:
+                assert 1 <= (cfg & 15) <= 4 and 1 <= ((cfg >> 4) & 15) <= 2 and 2 <= ((cfg >> 8) & 15) <= 4
+        x = W.input_pool(blob, 11)
+        for b in (11, 3, 1):
+            act = x[:b]
+            for s in range(blob.n_stages):
+                say(f"[case] autotuned {name} segment {s} b={b}")
+                ref = orc.stage_forward(blob, s, act)
+                got = host(eng.stage_forward(s, dev(torch, act), ref.shape[1:]), ref)
+                assert np.array_equal(got, ref)
+                act = ref
+        eng.close()
+
+
 def test_thresholds_zero_and_above_one(torch, ee, orc):
     blob = W.load_net("tiny_i8")
     eng = ee.Engine(blob, 8)
