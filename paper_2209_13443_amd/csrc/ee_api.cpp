@@ -262,7 +262,17 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
     if ((rc = dev_alloc(ctx, &ctx->d_conf, sizeof(float) * (size_t)b_max))) return fail(rc);
     if ((rc = dev_alloc(ctx, &ctx->d_score, sizeof(int64_t) * (size_t)b_max))) return fail(rc);
     if ((rc = dev_alloc(ctx, &ctx->d_flag, (size_t)b_max + 16))) return fail(rc);
-    if (hipHostMalloc(&ctx->h_pinned, 32 * (size_t)b_max + 4096, hipHostMallocDefault) != hipSuccess) return fail(EE_ERR_DEVICE);
+    if ((rc = dev_alloc(ctx, &ctx->d_arrive, 64))) return fail(rc);
+    {
+        const size_t out_bytes = round_up((int)(sizeof(HostOutcome) * (size_t)b_max), 256), ids_bytes = round_up(4 * b_max, 256);
+        if (hipHostMalloc(&ctx->h_pinned, out_bytes + 2 * ids_bytes + 256, hipHostMallocCoherent) != hipSuccess) return fail(EE_ERR_DEVICE);
+        std::memset(ctx->h_pinned, 0, out_bytes + 2 * ids_bytes + 256);
+        unsigned char* hp = static_cast<unsigned char*>(ctx->h_pinned);
+        ctx->h_out = reinterpret_cast<HostOutcome*>(hp);
+        ctx->h_ids[0] = reinterpret_cast<int32_t*>(hp + out_bytes);
+        ctx->h_ids[1] = reinterpret_cast<int32_t*>(hp + out_bytes + ids_bytes);
+        ctx->h_seq = reinterpret_cast<unsigned*>(hp + out_bytes + 2 * ids_bytes);
+    }
     if (hipDeviceSynchronize() != hipSuccess) return fail(EE_ERR_DEVICE);
     *out = ctx;
     return EE_OK;
@@ -423,7 +433,7 @@ extern "C" int ee_stage_forward(ee_ctx* ctx, int stage, int b_act, const void* a
 }
 
 // ---- one exit head ------------------------------------------------------------------------------------
-int ee_ctx::run_head(int stage, int b, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag)
+int ee_ctx::run_head(int stage, int b, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag, bool to_host)
 {
     const ExitDesc& e = net.exits[stage];
     const int dt = net.dtype, es = net.elem_bytes();
@@ -435,6 +445,7 @@ int ee_ctx::run_head(int stage, int b, const void* act, float thr, int32_t* labe
     a.s_thr = !(thr > 0.0f) ? INT64_MAX : (thr > 1.0f ? 0 : (int64_t)std::floor(1073741824.0 / (double)thr));
     a.last = stage == (int)net.stages.size() - 1;
     a.label = label; a.conf = conf; a.score = score; a.flag = flag;
+    if (to_host) { a.host_out = h_out; a.host_seq = h_seq; a.seq_value = ++seq; a.arrive_counter = d_arrive; }
     const double act_bytes = (double)b * a.HW * a.C * es;
     if (timed(EE_K_GAP, 0.0, act_bytes + 4.0 * b * a.C, [&] { return launch_head_gap(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;
     if (timed(EE_K_FC, 2.0 * b * a.C * a.n_cls, (double)a.C * a.n_cls * es + 4.0 * b * (a.C + a.n_cls),

@@ -44,7 +44,13 @@ struct ee_ctx {
     std::vector<void*> in_buf, out_buf;          // per segment: packed input slots, raw output slots
     int32_t* d_ids = nullptr;                    // admission ids
     int32_t* d_label = nullptr; float* d_conf = nullptr; int64_t* d_score = nullptr; uint8_t* d_flag = nullptr;
-    void* h_pinned = nullptr;                    // pinned host staging (ids ring + head outputs)
+    void* h_pinned = nullptr;                    // pinned, device-visible host memory: the three blocks below
+    ee::HostOutcome* h_out = nullptr;            // [b_max] per-slot outcomes written by the exit-head kernel
+    int32_t* h_ids[2] = {nullptr, nullptr};      // admission ids read by the admission kernel, used in turn
+    unsigned* h_seq = nullptr;                   // sequence word stored by the exit head when h_out is complete
+    unsigned seq = 0;                            // last sequence value handed to an exit head
+    unsigned* d_arrive = nullptr;                // device counter of exit-head workgroups that have finished
+    int ids_turn = 0;
     // kernel timing
     bool profiling = false;
     std::vector<ee::ProfRec> prof;
@@ -66,7 +72,9 @@ struct ee_ctx {
     // launches layer `op` (an index into plans) on b samples with the given kernel configuration (0 = by shape)
     hipError_t launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg);
     static int bucket_of(int b) { int k = 0; while ((1 << k) < b) ++k; return k; }     // smallest k with 2^k >= b
-    int run_head(int stage, int b_act, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag);
+    // to_host: also write the outcomes to h_out and store ++seq to h_seq when they are all there
+    int run_head(int stage, int b_act, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag,
+                 bool to_host = false);
     // brackets `launch` with a pair of events when profiling
     template <typename F>
     hipError_t timed(int cls, double ops, double bytes, F&& launch, int op = -1);

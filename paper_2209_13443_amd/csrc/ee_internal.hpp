@@ -93,7 +93,11 @@ struct HeadArgs {
     void* logits;        // [B][n_cls] int32 / float scratch
     int64_t s_thr; float thr; int last;
     int32_t* label; float* conf; int64_t* score; uint8_t* flag;
+    // stream serving: per-slot outcomes written straight into pinned host memory, and a sequence word
+    // the last workgroup stores once every record is visible to the host (all three null otherwise)
+    struct HostOutcome* host_out; unsigned* host_seq; unsigned seq_value; unsigned* arrive_counter;
 };
+struct HostOutcome { int64_t score; int32_t label; float conf; uint32_t flag; uint32_t pad_; };
 hipError_t launch_head_gap(const HeadArgs& a, int dtype, hipStream_t s);
 hipError_t launch_head_fc(const HeadArgs& a, int dtype, hipStream_t s);
 hipError_t launch_head_softmax(const HeadArgs& a, int dtype, hipStream_t s);

@@ -214,8 +214,7 @@ hipError_t launch_head_gap(const HeadArgs& a, int dtype, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
     if (dtype == EE_I8) {
-        hipError_t e = hipMemsetAsync(a.sums, 0, sizeof(int32_t) * (size_t)a.B * a.C, s);
-        if (e != hipSuccess) return e;
+        // a.sums is all zero here: ee_create clears it and the softmax kernel of every head clears what it used
         int splits = (1024 + a.B - 1) / a.B;                 // aim at >= 1024 workgroups
         int ppb = (a.HW + splits - 1) / splits;
         if (ppb < 16) ppb = a.HW < 16 ? a.HW : 16;
@@ -368,11 +367,16 @@ __global__ __launch_bounds__(256) void softmax_kernel(HeadArgs a)
         }
         arg = -block_reduce<int>(-arg, (int*)scratch, true);
         S = block_reduce<long long>(S, scratch, false);
+        // the pooled sums of this sample have been consumed by the FC: leave them zero for the next head
+        for (int c = threadIdx.x; c < a.C; c += 256) a.sums[(long long)b * a.C + c] = 0;
         if (threadIdx.x == 0) {
+            const float conf = (float)(1073741824.0 / (double)S);
+            const uint8_t flag = (uint8_t)(a.last || S <= a.s_thr);
             a.label[b] = arg;
             a.score[b] = S;
-            a.conf[b] = (float)(1073741824.0 / (double)S);
-            a.flag[b] = (uint8_t)(a.last || S <= a.s_thr);
+            a.conf[b] = conf;
+            a.flag[b] = flag;
+            if (a.host_out) a.host_out[b] = HostOutcome{S, arg, conf, flag, 0u};
         }
     } else {
         const float* z = (const float*)a.logits + (long long)b * a.n_cls;
@@ -389,10 +393,21 @@ __global__ __launch_bounds__(256) void softmax_kernel(HeadArgs a)
         den = block_reduce<float>(den, (float*)scratch, false);
         if (threadIdx.x == 0) {
             const float conf = 1.0f / den;
+            const uint8_t flag = (uint8_t)(a.last || conf >= a.thr);
             a.label[b] = arg;
             a.score[b] = 0;
             a.conf[b] = conf;
-            a.flag[b] = (uint8_t)(a.last || conf >= a.thr);
+            a.flag[b] = flag;
+            if (a.host_out) a.host_out[b] = HostOutcome{0, arg, conf, flag, 0u};
+        }
+    }
+    // the workgroup that arrives last tells the host that every record is in place
+    if (a.host_seq && threadIdx.x == 0) {
+        __threadfence_system();
+        if (atomicAdd(a.arrive_counter, 1u) == (unsigned)a.B - 1u) {
+            *a.arrive_counter = 0u;
+            __threadfence_system();
+            __hip_atomic_store(a.host_seq, a.seq_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
 }

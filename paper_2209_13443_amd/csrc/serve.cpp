@@ -55,65 +55,65 @@ struct WallClock {
 struct TableExec {
     const int32_t* forced; int n_stages;
     int admit(const int32_t*, int) { return EE_OK; }
-    int segment(int stage, const int32_t* ids, int b, SlotOutcome* out)
+    int segment(int stage, const int32_t* ids, int b, SlotOutcome* out, int)
     {
         for (int k = 0; k < b; ++k) out[k] = SlotOutcome{(uint8_t)(stage == n_stages - 1 || forced[ids[k]] == stage), -1, 0.f, 0};
         return EE_OK;
     }
-    int compact(int, int, int) { return EE_OK; }
 };
 
 struct GpuExec {
-    ee_ctx* ctx; const unsigned char* pool; const float* thr;
-    int32_t* h_ids; int32_t* h_label; float* h_conf; int64_t* h_score; uint8_t* h_flag;
+    ee_ctx* ctx; const unsigned char* pool;
 
-    explicit GpuExec(ee_ctx* c, const void* input_pool) : ctx(c), pool((const unsigned char*)input_pool)
-    {
-        unsigned char* p = (unsigned char*)c->h_pinned;
-        const size_t bm = (size_t)c->b_max;
-        h_score = (int64_t*)p; p += 8 * bm;
-        h_ids = (int32_t*)p; p += 4 * bm;
-        h_label = (int32_t*)p; p += 4 * bm;
-        h_conf = (float*)p; p += 4 * bm;
-        h_flag = (uint8_t*)p;
-    }
-    // A0: copy the queued inputs into slots [0, b) of segment 0's input buffer
+    explicit GpuExec(ee_ctx* c, const void* input_pool) : ctx(c), pool((const unsigned char*)input_pool) {}
+    // A0: copy the queued inputs into slots [0, b) of segment 0's input buffer.  The kernel reads the
+    // request ids straight from pinned host memory; two id blocks are used in turn, and an exit-head wait
+    // lies between two admissions, so a block is never rewritten while a kernel may still read it.
     int admit(const int32_t* ids, int b)
     {
+        int32_t* h_ids = ctx->h_ids[ctx->ids_turn];
+        ctx->ids_turn ^= 1;
         std::memcpy(h_ids, ids, sizeof(int32_t) * (size_t)b);
-        if (hipMemcpyAsync(ctx->d_ids, h_ids, sizeof(int32_t) * (size_t)b, hipMemcpyHostToDevice, ctx->stream) != hipSuccess) return EE_ERR_DEVICE;
         const int64_t sb = ctx->stage_in_bytes(0);
-        hipError_t e = ctx->timed(EE_K_ADMIT, 0.0, 2.0 * sb * b, [&] { return launch_admit(pool, ctx->in_buf[0], ctx->d_ids, b, sb, ctx->stream); });
-        if (e != hipSuccess) return EE_ERR_DEVICE;
-        // h_ids is reused by the next admission: make sure the copy has been consumed
-        return hipStreamSynchronize(ctx->stream) == hipSuccess ? EE_OK : EE_ERR_DEVICE;
+        hipError_t e = ctx->timed(EE_K_ADMIT, 0.0, 2.0 * sb * b, [&] { return launch_admit(pool, ctx->in_buf[0], h_ids, b, sb, ctx->stream); });
+        return e == hipSuccess ? EE_OK : EE_ERR_DEVICE;
     }
-    // A1 + A2: segment and exit head on slots [0, b); one read-back of the per-slot outcomes
-    int segment(int stage, const int32_t*, int b, SlotOutcome* out)
+    // A1 + A2 (+ A3 / A4): segment and exit head on slots [0, b); the survivors (flags stay on the device)
+    // are packed into the next segment's input slots [dst_off, dst_off + B_rem) right behind the head,
+    // dst_off > 0 merging a catch-up batch behind the parked survivors.  Then the one device-to-host
+    // crossing of the boundary: the head kernel has written the per-slot outcomes into pinned host memory
+    // and stores a sequence word when they are complete; the host polls that word.
+    int segment(int stage, const int32_t*, int b, SlotOutcome* out, int dst_off)
     {
         int rc = ctx->run_stage(stage, b, ctx->in_buf[stage], ctx->out_buf[stage]);
-        if (!rc) rc = ctx->run_head(stage, b, ctx->out_buf[stage], ctx->net.exits[stage].thr, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag);
+        if (!rc) rc = ctx->run_head(stage, b, ctx->out_buf[stage], ctx->net.exits[stage].thr, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag, true);
         if (rc) return rc;
-        hipStream_t s = ctx->stream;
-        if (hipMemcpyAsync(h_flag, ctx->d_flag, (size_t)b, hipMemcpyDeviceToHost, s) != hipSuccess ||
-            hipMemcpyAsync(h_label, ctx->d_label, 4 * (size_t)b, hipMemcpyDeviceToHost, s) != hipSuccess ||
-            hipMemcpyAsync(h_conf, ctx->d_conf, 4 * (size_t)b, hipMemcpyDeviceToHost, s) != hipSuccess ||
-            hipMemcpyAsync(h_score, ctx->d_score, 8 * (size_t)b, hipMemcpyDeviceToHost, s) != hipSuccess ||
-            hipStreamSynchronize(s) != hipSuccess)
-            return EE_ERR_DEVICE;
-        for (int k = 0; k < b; ++k) out[k] = SlotOutcome{h_flag[k], h_label[k], h_conf[k], h_score[k]};
+        if (stage + 1 < (int)ctx->in_buf.size()) {
+            const int64_t sb = ctx->stage_out_bytes(stage);
+            hipError_t e = ctx->timed(EE_K_COMPACT, 0.0, 2.0 * sb * b, [&] {
+                return launch_compact(ctx->d_flag, ctx->out_buf[stage], ctx->in_buf[stage + 1], nullptr, nullptr, b, sb, dst_off, nullptr, nullptr, ctx->stream);
+            });
+            if (e != hipSuccess) return EE_ERR_DEVICE;
+        }
+        if ((rc = wait_outcomes())) return rc;
+        for (int k = 0; k < b; ++k) {
+            const HostOutcome& h = ctx->h_out[k];
+            out[k] = SlotOutcome{(uint8_t)h.flag, h.label, h.conf, h.score};
+        }
         return EE_OK;
     }
-    // A3 / A4: survivors of segment `stage` (flags still on the device) -> next segment's input slots
-    // [dst_off, dst_off + B_rem).  dst_off > 0 merges a catch-up batch behind the parked survivors.
-    int compact(int stage, int b, int dst_off)
+    int wait_outcomes()
     {
-        if (stage + 1 >= (int)ctx->in_buf.size()) return EE_OK;
-        const int64_t sb = ctx->stage_out_bytes(stage);
-        hipError_t e = ctx->timed(EE_K_COMPACT, 0.0, 2.0 * sb * b, [&] {
-            return launch_compact(ctx->d_flag, ctx->out_buf[stage], ctx->in_buf[stage + 1], nullptr, nullptr, b, sb, dst_off, nullptr, nullptr, ctx->stream);
-        });
-        return e == hipSuccess ? EE_OK : EE_ERR_DEVICE;
+        const unsigned want = ctx->seq;
+        const auto t0 = std::chrono::steady_clock::now();
+        for (unsigned spins = 0; __atomic_load_n(ctx->h_seq, __ATOMIC_ACQUIRE) != want; ++spins) {
+            if ((spins & 0xFFFF) == 0xFFFF && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2)) {
+                // no word after two seconds: let the runtime say what happened to the stream
+                if (hipStreamSynchronize(ctx->stream) != hipSuccess) return EE_ERR_DEVICE;
+                return __atomic_load_n(ctx->h_seq, __ATOMIC_ACQUIRE) == want ? EE_OK : EE_ERR_DEVICE;
+            }
+        }
+        return EE_OK;
     }
 };
 
@@ -172,14 +172,15 @@ private:
         return exec.admit(active.data(), b_act);
     }
 
-    // ProcUntilExit for one segment: run it, book the samples that leave, keep the survivors packed.
+    // ProcUntilExit for one segment: run it (the executor also packs the survivors for the next segment),
+    // book the samples that leave, keep the survivors' ids in order.
     // `b` is updated to the number of survivors.
     int proc_until_exit(std::vector<int32_t>& ids, int& b, int stage, bool catchup, int merge_at)
     {
         log(catchup ? EE_EV_PROC_CATCHUP : EE_EV_PROC, stage, b, 0);
         stats->seg_runs[stage]++;
         stats->seg_samples[stage] += b;
-        int rc = exec.segment(stage, ids.data(), b, outcome.data());
+        int rc = exec.segment(stage, ids.data(), b, outcome.data(), merge_at);
         if (rc) return rc;
         clock.segment_done(stage, b);
         const int64_t t = clock.now();
@@ -195,7 +196,6 @@ private:
                 ids[kept++] = ids[k];
             }
         }
-        if (kept > 0) rc = exec.compact(stage, b, merge_at);
         b = kept;
         return rc;
     }
@@ -269,10 +269,13 @@ extern "C" int ee_serve_stream(ee_ctx* ctx, const ee_trace* trace, const void* i
     GpuExec exec(ctx, input_pool);
     if (opts->clock == 1) {
         VirtualClock ck{opts->lut_ns, opts->b_max, 0};
-        return FluidScheduler<GpuExec, VirtualClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run();
+        rc = FluidScheduler<GpuExec, VirtualClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run();
+    } else {
+        WallClock ck{};
+        rc = FluidScheduler<GpuExec, WallClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run();
     }
-    WallClock ck{};
-    return FluidScheduler<GpuExec, WallClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run();
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess && !rc) rc = EE_ERR_DEVICE;    // the call is synchronous
+    return rc;
 }
 
 extern "C" int ee_schedule_sim(int n_stages, const ee_trace* trace, const int32_t* forced_exit, const ee_serve_opts* opts,
