@@ -75,6 +75,17 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
         p.Kp = round_up(K * es, 128) / es;
         wp.assign((size_t)Co_pad * p.Kp * es, 0);
         for (int o = 0; o < Co; ++o) std::memcpy(&wp[(size_t)o * p.Kp * es], w + (size_t)o * K * es, (size_t)K * es);
+    } else if (Ci > 4 && (Ci * es) % 4 == 0 && Co % 4 == 0 && d.kh * d.kw <= 31) {
+        // pixels that are not 16-byte multiples: the layer reads a copy whose channels are zero padded to the
+        // next multiple (made by a small kernel in front of it); the weights get the same per-tap padding
+        p.impl = IMPL_MFMA_CPAD;
+        const int cip = round_up(Ci * es, 16) / es, taps = d.kh * d.kw;
+        p.ci_eff = cip;
+        p.Kp = round_up(taps * cip * es, 128) / es;
+        wp.assign((size_t)Co_pad * p.Kp * es, 0);
+        for (int o = 0; o < Co; ++o)
+            for (int t = 0; t < taps; ++t)
+                std::memcpy(&wp[((size_t)o * p.Kp + (size_t)t * cip) * es], w + ((size_t)o * taps + t) * Ci * es, (size_t)Ci * es);
     } else if (Ci <= 4 && Co % 4 == 0) {
         // first layer: the input is copied into a zero-padded 4-channel image, a kernel row of kwp taps is
         // then kwp*4 contiguous elements; k index = (r * kwp + s) * 4 + c
@@ -94,7 +105,7 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
         p.impl = IMPL_DIRECT;
         wp.assign(w, w + (size_t)Co * d.kh * d.kw * Ci * es);
     }
-    if (p.impl == IMPL_MFMA && es == 1 && d.shift > 0) {
+    if ((p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_CPAD) && es == 1 && d.shift > 0) {
         // that kernel requantises with a bare arithmetic shift: the rounding constant 2^(shift-1) goes
         // into the bias (the sum fits int32: the network's calibration guarantees t + 2^(shift-1) does)
         for (int o = 0; o < Co; ++o) {
@@ -219,12 +230,14 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
         const double kred = d.kind == OP_CONV ? (double)d.kh * d.kw * d.c_in : (double)d.kh * d.kw;
         p.ops_per_sample = d.kind == OP_MAXPOOL ? 0.0 : 2.0 * out_e * kred;
         p.bytes_per_sample = (in_e + out_e + (d.res >= 0 ? out_e : 0.0)) * es;
-        if (p.impl == IMPL_MFMA_C4) {
+        if (p.impl == IMPL_MFMA_C4 || p.impl == IMPL_MFMA_CPAD) {
             void* pb = nullptr;
-            if ((rc = dev_alloc(ctx, &pb, (size_t)b_max * p.Hp * p.Wp * 4 * es + 256))) return fail(rc);
+            const size_t bytes = p.impl == IMPL_MFMA_C4 ? (size_t)b_max * p.Hp * p.Wp * 4 * es : (size_t)b_max * d.h_in * d.w_in * p.ci_eff * es;
+            if ((rc = dev_alloc(ctx, &pb, bytes + 256))) return fail(rc);
             p.pad_buf = (int)ctx->pad_bufs.size();
             ctx->pad_bufs.push_back(pb);
         }
+        if (p.ci_eff == 0) p.ci_eff = d.c_in;
     }
     plan_buffers(ctx);
     ctx->pool.resize(ctx->pool_sample_bytes.size(), nullptr);
@@ -246,6 +259,7 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
         if (ctx->stage_out_bytes(s) % 16 != 0 || ctx->stage_in_bytes(s) % 16 != 0) return fail(EE_ERR_UNSUPPORTED);
     }
     if ((rc = dev_alloc(ctx, &ctx->sums, sizeof(int32_t) * (size_t)b_max * c_max))) return fail(rc);
+    if ((rc = dev_alloc(ctx, &ctx->gap_partial, sizeof(int32_t) * ((size_t)b_max + 1024) * c_max))) return fail(rc);
     if ((rc = dev_alloc(ctx, &ctx->logits, 4 * (size_t)b_max * ctx->net.n_classes))) return fail(rc);
     if ((rc = dev_alloc(ctx, &ctx->d_count, 64))) return fail(rc);
     if ((rc = dev_alloc(ctx, &ctx->zero_page, 256))) return fail(rc);
@@ -312,9 +326,10 @@ hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const 
     a.magic_howo = (unsigned)(0x100000000ull / (unsigned)(d.h_out * d.w_out) - (d.h_out * d.w_out == 1));
     a.magic_wo = (unsigned)(0x100000000ull / (unsigned)d.w_out - (d.w_out == 1));
     for (int r = 0; r < d.kh && r * d.kw < 32; ++r) a.tap_rows |= 1u << (r * d.kw);
-    a.M = b * d.h_out * d.w_out; a.H = d.h_in; a.W = d.w_in; a.Ci = d.c_in; a.Ho = d.h_out; a.Wo = d.w_out; a.Co = d.c_out;
+    a.M = b * d.h_out * d.w_out; a.H = d.h_in; a.W = d.w_in; a.Ci = p.ci_eff; a.Ho = d.h_out; a.Wo = d.w_out; a.Co = d.c_out;
     a.kh = d.kh; a.kw = d.kw; a.stride = d.stride; a.pad = d.pad; a.Kp = p.Kp;
     a.shift = d.shift; a.res_shift = d.res_shift; a.lo = d.lo; a.hi = d.hi; a.f_lo = d.f_lo; a.f_hi = d.f_hi;
+    if (p.impl == IMPL_MFMA_CPAD) src = pad_bufs[p.pad_buf];
     if (p.impl == IMPL_MFMA_C4) {
         a.x = pad_bufs[p.pad_buf]; a.mode = 1; a.Hp = p.Hp; a.Wp = p.Wp; a.kwp = p.kwp;
         return dt == EE_I8 ? launch_conv_mfma_i8(a, stream) : launch_conv_mfma_bf16(a, stream);
@@ -343,12 +358,12 @@ extern "C" int ee_autotune(ee_ctx* ctx, int reps)
         const StageDesc& st = ctx->net.stages[s];
         for (int k = 0; k < st.n_ops && !rc; ++k) {
             OpPlan& p = ctx->plans[st.first_op + k];
-            if (p.impl != IMPL_MFMA) continue;
+            if (p.impl != IMPL_MFMA && p.impl != IMPL_MFMA_CPAD) continue;
             const OpDesc& d = p.d;
             const void* src = resolve(ctx, p.src_buf, ctx->in_buf[s], ctx->out_buf[s]);
             void* dst = resolve(ctx, p.dst_buf, ctx->in_buf[s], ctx->out_buf[s]);
             const void* res = d.res >= 0 ? resolve(ctx, p.res_buf, ctx->in_buf[s], ctx->out_buf[s]) : nullptr;
-            const bool k128 = (d.kh * d.kw * d.c_in * es) % 128 == 0;
+            const bool k128 = (d.kh * d.kw * p.ci_eff * es) % 128 == 0;
             std::vector<int> best(buckets.size(), 0);
             for (size_t bi = 0; bi < buckets.size() && !rc; ++bi) {
                 float best_ms = 1e30f;
@@ -400,7 +415,14 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out)
         const void* res = d.res >= 0 ? resolve(this, p.res_buf, act_in, act_out) : nullptr;
         const double ops = p.ops_per_sample * b, bytes = p.bytes_per_sample * b + p.weight_bytes;
         hipError_t e = hipSuccess;
-        if (p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_C4) {
+        if (p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_C4 || p.impl == IMPL_MFMA_CPAD) {
+            if (p.impl == IMPL_MFMA_CPAD) {
+                const double pb = (double)b * d.h_in * d.w_in * (d.c_in + p.ci_eff) * es;
+                e = timed(EE_K_PAD_INPUT, 0.0, pb, [&] {
+                    return launch_pad_channels(src, pad_bufs[p.pad_buf], (long long)b * d.h_in * d.w_in, d.c_in * es, p.ci_eff * es, stream);
+                });
+                if (e != hipSuccess) return EE_ERR_DEVICE;
+            }
             if (p.impl == IMPL_MFMA_C4) {
                 const double pb = (double)b * ((double)d.h_in * d.w_in * d.c_in + (double)p.Hp * p.Wp * 4) * es;
                 e = timed(EE_K_PAD_INPUT, 0.0, pb, [&] { return launch_pad_input(src, pad_bufs[p.pad_buf], b, d.h_in, d.w_in, d.c_in, p.Hp, p.Wp, d.pad, dt, stream); });
@@ -408,7 +430,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out)
             }
             int cfg = forced_conv_tile();
             if (cfg == 0 && !p.cfg.empty()) cfg = p.cfg[std::min<size_t>(bucket_of(b), p.cfg.size() - 1)];
-            const int cls = p.impl == IMPL_MFMA ? EE_K_CONV_MFMA : EE_K_CONV_FIRST;
+            const int cls = p.impl == IMPL_MFMA_C4 ? EE_K_CONV_FIRST : EE_K_CONV_MFMA;
             e = timed(cls, ops, bytes, [&] { return launch_conv(st.first_op + k, b, src, dst, res, cfg); }, st.first_op + k);
         } else if (p.impl == IMPL_DIRECT) {
             DirectConvArgs a{src, p.w_dev, p.b_dev, res, dst, b * d.h_out * d.w_out, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.c_out,
@@ -440,7 +462,7 @@ int ee_ctx::run_head(int stage, int b, const void* act, float thr, int32_t* labe
     HeadArgs a{};
     a.act = act; a.B = b; a.HW = e.h * e.w; a.C = e.c; a.n_cls = e.n_cls;
     a.gap_shift = e.gap_shift; a.frac_bits = e.frac_bits; a.logit_scale = e.logit_scale;
-    a.wfc = wfc_dev[stage]; a.bfc = bfc_dev[stage]; a.sums = sums; a.logits = logits;
+    a.wfc = wfc_dev[stage]; a.bfc = bfc_dev[stage]; a.sums = sums; a.gap_partial = gap_partial; a.logits = logits;
     a.thr = thr;
     a.s_thr = !(thr > 0.0f) ? INT64_MAX : (thr > 1.0f ? 0 : (int64_t)std::floor(1073741824.0 / (double)thr));
     a.last = stage == (int)net.stages.size() - 1;

@@ -7,7 +7,7 @@
 
 namespace ee {
 
-enum Impl { IMPL_MFMA = 0, IMPL_MFMA_C4 = 1, IMPL_DIRECT = 2, IMPL_DW = 3, IMPL_POOL = 4 };
+enum Impl { IMPL_MFMA = 0, IMPL_MFMA_C4 = 1, IMPL_DIRECT = 2, IMPL_DW = 3, IMPL_POOL = 4, IMPL_MFMA_CPAD = 5 };
 enum { BUF_EXT_IN = -1, BUF_EXT_OUT = -2 };
 
 struct OpPlan {
@@ -17,7 +17,8 @@ struct OpPlan {
     void* b_dev = nullptr;      // bias, padded to the weight rows
     int Kp = 0, kwp = 0, Hp = 0, Wp = 0;
     int src_buf = 0, dst_buf = 0, res_buf = 0;   // BUF_EXT_* or an index into Ctx::pool
-    int pad_buf = -1;           // zero-padded 4-channel copy of the input (IMPL_MFMA_C4)
+    int pad_buf = -1;           // padded copy of the input: 4 channels + spatial border (IMPL_MFMA_C4), channels to 16 bytes (IMPL_MFMA_CPAD)
+    int ci_eff = 0;             // input channels the matrix-core kernel sees (c_in, or c_in padded to a 16-byte multiple)
     std::vector<int> cfg;       // kernel configuration per batch bucket (see ee_autotune); empty = by shape
     double ops_per_sample = 0, bytes_per_sample = 0, weight_bytes = 0;
 };
@@ -37,6 +38,7 @@ struct ee_ctx {
     std::vector<void*> owned;                    // every device allocation, for ee_destroy
     std::vector<void*> wfc_dev, bfc_dev;         // exit heads
     int32_t* sums = nullptr;                     // [b_max][C_max]
+    int32_t* gap_partial = nullptr;              // [(b_max + 1024)][C_max] partial rows of the pooling splits
     void* logits = nullptr;                      // [b_max][n_cls]
     void* zero_page = nullptr;                   // zero bytes read in place of padding taps
     int* d_count = nullptr;                      // device int scratch (B_rem)

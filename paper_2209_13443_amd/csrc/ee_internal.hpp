@@ -82,6 +82,8 @@ template <int ES> hipError_t launch_conv_igemm(const ConvArgs& a, int tile, hipS
 int forced_conv_tile();
 hipError_t launch_conv_direct(const DirectConvArgs& a, int dtype, hipStream_t s);
 hipError_t launch_pad_input(const void* x, void* y, int B, int H, int W, int C, int Hp, int Wp, int pad, int dtype, hipStream_t s);
+// [rows][c_bytes] -> [rows][cp_bytes] (both multiples of 4), the tail of every row zero
+hipError_t launch_pad_channels(const void* x, void* y, long long rows, int c_bytes, int cp_bytes, hipStream_t s);
 hipError_t launch_depthwise(const PoolArgs& a, int dtype, hipStream_t s);
 hipError_t launch_maxpool(const PoolArgs& a, int dtype, hipStream_t s);
 
@@ -89,7 +91,8 @@ struct HeadArgs {
     const void* act; int B, HW, C, n_cls;
     int gap_shift, frac_bits; float logit_scale;
     const void* wfc; const void* bfc;
-    int32_t* sums;       // [B][C] int32 (i8) or float (bf16) scratch
+    int32_t* sums;       // [B][C] int32 sums (i8) or float means (bf16)
+    int32_t* gap_partial;   // bf16: [(B + 1024)][C] partial rows of the pooling splits
     void* logits;        // [B][n_cls] int32 / float scratch
     int64_t s_thr; float thr; int last;
     int32_t* label; float* conf; int64_t* score; uint8_t* flag;

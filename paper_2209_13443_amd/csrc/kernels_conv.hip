@@ -399,4 +399,23 @@ hipError_t launch_pad_input(const void* x, void* y, int B, int H, int W, int C, 
     return hipGetLastError();
 }
 
+// ---- [rows][c_bytes] -> [rows][cp_bytes], zero tail: gives layers whose pixels are not 16-byte multiples
+// the row alignment the matrix-core loader needs ----------------------------------------------------------
+__global__ __launch_bounds__(256) void pad_channels_kernel(const int* x, int* y, long long rows, int c_words, int cp_words)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * cp_words) return;
+    const long long r = idx / cp_words;
+    const int w = (int)(idx - r * cp_words);
+    y[idx] = w < c_words ? x[r * c_words + w] : 0;
+}
+
+hipError_t launch_pad_channels(const void* x, void* y, long long rows, int c_bytes, int cp_bytes, hipStream_t s)
+{
+    const long long total = rows * (cp_bytes / 4);
+    if (total <= 0) return hipSuccess;
+    hipLaunchKernelGGL(pad_channels_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const int*)x, (int*)y, rows, c_bytes / 4, cp_bytes / 4);
+    return hipGetLastError();
+}
+
 }  // namespace ee

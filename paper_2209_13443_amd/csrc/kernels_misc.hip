@@ -158,10 +158,14 @@ hipError_t launch_maxpool(const PoolArgs& a, int dtype, hipStream_t s)
 }
 
 // ---- exit head, step 1: global average pool ----------------------------------------------------------
-// grid (pixel splits, B).  Lane = (pixel lane pl, 16-byte channel chunk q); the pixel lanes are reduced
-// through LDS, then one atomic add per channel and workgroup into sums[B][C] (int32: exact in any
-// order).  The bf16 variant runs with a single pixel split, so its float means are plain,
-// deterministic stores.  Needs C * ES / 16 <= 256.
+// grid (S pixel splits, B).  Lane = (pixel lane pl, 16-byte channel chunk q); the pixel lanes are reduced
+// through LDS into one partial row per workgroup.  int8: the row is added into sums[B][C] with one
+// atomic per channel (int32 addition is exact in any order; the buffer is zero on entry, the softmax
+// kernel of every head clears what it used).  bf16: the S partial rows of a sample are stored and a
+// second small kernel adds them in split order, so the float means never depend on the order in which
+// workgroups ran.  (A last-arriving-workgroup reduction inside one kernel would need a device-scope
+// release per workgroup, which on this chip writes back the whole L2 of its XCD.)
+// Needs C * ES / 16 <= 256.
 template <int ES>
 __global__ __launch_bounds__(256) void gap_kernel(HeadArgs a, int pix_per_block)
 {
@@ -169,7 +173,7 @@ __global__ __launch_bounds__(256) void gap_kernel(HeadArgs a, int pix_per_block)
     __shared__ int red[256 * NE];
     const int cchunks = a.C * ES / 16;
     const int npl = 256 / cchunks;
-    const int b = blockIdx.y;
+    const int b = blockIdx.y, S = gridDim.x;
     const int q = (int)threadIdx.x % cchunks, pl = (int)threadIdx.x / cchunks;
     const bool active = pl < npl;
     const int p0 = blockIdx.x * pix_per_block, p1 = min(a.HW, p0 + pix_per_block);
@@ -178,18 +182,33 @@ __global__ __launch_bounds__(256) void gap_kernel(HeadArgs a, int pix_per_block)
     float accf[NE];
 #pragma unroll
     for (int e = 0; e < NE; ++e) { acci[e] = 0; accf[e] = 0.f; }
-    if (active)
-        for (int p = p0 + pl; p < p1; p += npl) {
+    if (active) {
+        int p = p0 + pl;
+        for (; p + 3 * npl < p1; p += 4 * npl) {           // four rows in flight per lane
+            v4i xv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) xv[u] = *(const v4i*)(x + ((long long)(p + u * npl) * a.C) * ES + q * 16);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if constexpr (ES == 1) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acci[e] += __builtin_amdgcn_sbfe(xv[u][e >> 2], 8 * (e & 3), 8);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) accf[e] += bf16_to_f32_m((uint16_t)((unsigned)xv[u][e >> 1] >> (16 * (e & 1))));
+                }
+            }
+        }
+        for (; p < p1; p += npl) {
             const v4i xv = *(const v4i*)(x + ((long long)p * a.C) * ES + q * 16);
             if constexpr (ES == 1) {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acci[e] += byte_of(xv[e >> 2], e & 3);
+                for (int e = 0; e < 16; ++e) acci[e] += __builtin_amdgcn_sbfe(xv[e >> 2], 8 * (e & 3), 8);
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) accf[e] += bf16_to_f32_m((uint16_t)((unsigned)xv[e >> 1] >> (16 * (e & 1))));
             }
         }
-    if (active) {
 #pragma unroll
         for (int e = 0; e < NE; ++e) {
             if constexpr (ES == 1) red[pl * a.C + q * NE + e] = acci[e];
@@ -205,23 +224,46 @@ __global__ __launch_bounds__(256) void gap_kernel(HeadArgs a, int pix_per_block)
         } else {
             float s = 0.f;
             for (int l = 0; l < npl; ++l) s += __int_as_float(red[l * a.C + c]);
-            ((float*)a.sums)[(long long)b * a.C + c] = s / (float)a.HW;
+            if (S == 1) a.sums[(long long)b * a.C + c] = __float_as_int(s / (float)a.HW);
+            else a.gap_partial[((long long)b * S + blockIdx.x) * a.C + c] = __float_as_int(s);
         }
     }
+}
+
+// bf16: sums[b][c] = (partial[b][0][c] + ... + partial[b][S-1][c]) / HW, 4 channels per lane
+__global__ __launch_bounds__(256) void gap_reduce_kernel(HeadArgs a, int S)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;       // (b, c / 4)
+    const int c4 = a.C / 4;
+    if (idx >= (long long)a.B * c4) return;
+    const long long b = idx / c4;
+    const int c = (int)(idx - b * c4) * 4;
+    const int* rows = a.gap_partial + b * S * a.C + c;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    for (int k = 0; k < S; ++k) {
+        const v4i v = *(const v4i*)(rows + (long long)k * a.C);
+        s0 += __int_as_float(v[0]); s1 += __int_as_float(v[1]); s2 += __int_as_float(v[2]); s3 += __int_as_float(v[3]);
+    }
+    // the same rounding as the single-split path: one division per channel
+    v4i out = {__float_as_int(s0 / (float)a.HW), __float_as_int(s1 / (float)a.HW), __float_as_int(s2 / (float)a.HW), __float_as_int(s3 / (float)a.HW)};
+    *(v4i*)(a.sums + b * a.C + c) = out;
 }
 
 hipError_t launch_head_gap(const HeadArgs& a, int dtype, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
+    int splits = (1024 + a.B - 1) / a.B;                     // aim at >= 1024 workgroups; B * splits <= B + 1024
+    int ppb = (a.HW + splits - 1) / splits;
+    if (ppb < 16) ppb = a.HW < 16 ? a.HW : 16;
+    splits = (a.HW + ppb - 1) / ppb;
     if (dtype == EE_I8) {
-        // a.sums is all zero here: ee_create clears it and the softmax kernel of every head clears what it used
-        int splits = (1024 + a.B - 1) / a.B;                 // aim at >= 1024 workgroups
-        int ppb = (a.HW + splits - 1) / splits;
-        if (ppb < 16) ppb = a.HW < 16 ? a.HW : 16;
-        splits = (a.HW + ppb - 1) / ppb;
         hipLaunchKernelGGL(gap_kernel<1>, dim3(splits, a.B), dim3(256), 0, s, a, ppb);
     } else {
-        hipLaunchKernelGGL(gap_kernel<2>, dim3(1, a.B), dim3(256), 0, s, a, a.HW);
+        hipLaunchKernelGGL(gap_kernel<2>, dim3(splits, a.B), dim3(256), 0, s, a, ppb);
+        if (splits > 1) {
+            const long long total = (long long)a.B * (a.C / 4);
+            hipLaunchKernelGGL(gap_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, splits);
+        }
     }
     return hipGetLastError();
 }
