@@ -72,7 +72,7 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
     if ((Ci * es) % 16 == 0 && Co % 4 == 0 && d.kh * d.kw <= 31) {
         p.impl = IMPL_MFMA;
         const int K = d.kh * d.kw * Ci;
-        p.Kp = round_up(K * es, 128) / es;
+        p.Kp = round_up(K * es, 256) / es;
         wp.assign((size_t)Co_pad * p.Kp * es, 0);
         for (int o = 0; o < Co; ++o) std::memcpy(&wp[(size_t)o * p.Kp * es], w + (size_t)o * K * es, (size_t)K * es);
     } else if (Ci > 4 && (Ci * es) % 4 == 0 && Co % 4 == 0 && d.kh * d.kw <= 31) {
@@ -81,7 +81,7 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
         p.impl = IMPL_MFMA_CPAD;
         const int cip = round_up(Ci * es, 16) / es, taps = d.kh * d.kw;
         p.ci_eff = cip;
-        p.Kp = round_up(taps * cip * es, 128) / es;
+        p.Kp = round_up(taps * cip * es, 256) / es;
         wp.assign((size_t)Co_pad * p.Kp * es, 0);
         for (int o = 0; o < Co; ++o)
             for (int t = 0; t < taps; ++t)
@@ -363,13 +363,14 @@ extern "C" int ee_autotune(ee_ctx* ctx, int reps)
             const void* src = resolve(ctx, p.src_buf, ctx->in_buf[s], ctx->out_buf[s]);
             void* dst = resolve(ctx, p.dst_buf, ctx->in_buf[s], ctx->out_buf[s]);
             const void* res = d.res >= 0 ? resolve(ctx, p.res_buf, ctx->in_buf[s], ctx->out_buf[s]) : nullptr;
-            const bool k128 = (d.kh * d.kw * p.ci_eff * es) % 128 == 0;
+            const int kbytes = d.kh * d.kw * p.ci_eff * es;
             std::vector<int> best(buckets.size(), 0);
             for (size_t bi = 0; bi < buckets.size() && !rc; ++bi) {
                 float best_ms = 1e30f;
                 for (int tile = 1; tile <= 4; ++tile)
-                    for (int ksel = 1; ksel <= (k128 ? 2 : 1); ++ksel)
-                        for (int ns = 2; ns <= 3; ++ns) {
+                    for (int ksel = 1; ksel <= 3; ++ksel)
+                        for (int ns = 2; ns <= 4; ++ns) {
+                            if (ksel > 1 && kbytes <= 64 * (ksel - 1)) continue;        // a longer step than the whole reduction
                             const int cfg = tile | (ksel << 4) | (ns << 8);
                             if (ctx->launch_conv(st.first_op + k, buckets[bi], src, dst, res, cfg) != hipSuccess) {
                                 (void)hipGetLastError();                       // this configuration does not fit: skip it

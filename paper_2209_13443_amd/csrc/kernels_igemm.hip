@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int
     constexpr int RPP = 256 / CPRW;                // rows one copy pass of the workgroup covers
     constexpr int NA = BM / RPP, NB = BN / RPP, LPT = NA + NB;
     constexpr int STAGE = (BM + BN) * KS;
-    constexpr int R256 = 256 / KS;                 // staged rows per 256 bytes of LDS
+    constexpr int R256 = KS >= 256 ? 1 : 256 / KS; // staged rows per 256 bytes of LDS
     constexpr int CR = BN * ES / 16;               // 16-byte chunks per row of the output tile
     constexpr int OROW = BN * ES, TILE_O = BM * OROW;
     constexpr int NO = BM * CR / 256;              // output-tile passes of the workgroup
@@ -410,7 +410,7 @@ static hipError_t launch_igemm_tile(const ConvArgs& a, bool plain, int ns, hipSt
 }
 
 // cfg: bits 0-3 tile (0 = by shape; 1: 128x128, 2: 128x64, 3: 64x64, 4: 64x128), bits 4-7 reduction step
-// (0 = by shape, 1: 64 bytes, 2: 128 bytes), bits 8-11 ring stages (0 = by shape, else 2..4).
+// (0 = by shape, 1: 64, 2: 128, 3: 256 bytes), bits 8-11 ring stages (0 = by shape, else 2..4).
 template <int ES>
 hipError_t launch_conv_igemm(const ConvArgs& a, int cfg, hipStream_t s)
 {
@@ -418,7 +418,7 @@ hipError_t launch_conv_igemm(const ConvArgs& a, int cfg, hipStream_t s)
     int tile = cfg & 15, ksel = (cfg >> 4) & 15, ns = (cfg >> 8) & 15;
     const int kbytes = a.kh * a.kw * a.Ci * ES;
     if (ksel == 0) ksel = kbytes % 128 == 0 ? 2 : 1;
-    const int ks = ksel == 2 ? 128 : 64;
+    const int ks = ksel == 3 ? 256 : (ksel == 2 ? 128 : 64);
     const bool plain = a.kh == 1 && a.kw == 1 && a.pad == 0 && kbytes % ks == 0;
     if (tile == 0) {
         auto blocks = [&](int bm, int bn) { return (long long)((a.M + bm - 1) / bm) * ((a.Co + bn - 1) / bn); };
@@ -427,6 +427,12 @@ hipError_t launch_conv_igemm(const ConvArgs& a, int cfg, hipStream_t s)
         else tile = blocks(128, 64) >= want ? 2 : 3;
     }
     if (ns == 0) ns = 2;     // measured: more workgroups per CU beat a deeper ring at these problem sizes
+    if (ks == 256) {
+        if (tile == 1) return launch_igemm_tile<ES, 128, 128, 256>(a, plain, ns, s);
+        if (tile == 2) return launch_igemm_tile<ES, 128, 64, 256>(a, plain, ns, s);
+        if (tile == 4) return launch_igemm_tile<ES, 64, 128, 256>(a, plain, ns, s);
+        return launch_igemm_tile<ES, 64, 64, 256>(a, plain, ns, s);
+    }
     if (ks == 128) {
         if (tile == 1) return launch_igemm_tile<ES, 128, 128, 128>(a, plain, ns, s);
         if (tile == 2) return launch_igemm_tile<ES, 128, 64, 128>(a, plain, ns, s);
