@@ -86,6 +86,24 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
         for (int o = 0; o < Co; ++o)
             for (int t = 0; t < taps; ++t)
                 std::memcpy(&wp[((size_t)o * p.Kp + (size_t)t * cip) * es], w + ((size_t)o * taps + t) * Ci * es, (size_t)Ci * es);
+    } else if (Ci <= 4 && Co % 4 == 0 && d.stride == 2 && d.kh == d.kw && (d.kh + 1) / 2 * ((d.kh + 1) / 2) <= 31) {
+        // stride-2 first layer: stride-1 convolution with a ceil(k/2)^2 kernel over the padded image folded into
+        // super-pixels (dy, dx, c) of 2 x 2 pixels x 4 channels; weights W'[o][r'][s'][dy][dx][c] = W[o][2r'+dy][2s'+dx][c]
+        p.impl = IMPL_MFMA_S2D;
+        const int k2 = (d.kh + 1) / 2;
+        p.kwp = k2;
+        p.ci_eff = 16;
+        p.Hp = std::max((d.h_in + 2 * d.pad + 1) / 2, d.h_out - 1 + k2);
+        p.Wp = std::max((d.w_in + 2 * d.pad + 1) / 2, d.w_out - 1 + k2);
+        p.Kp = round_up(k2 * k2 * 16 * es, 256) / es;
+        wp.assign((size_t)Co_pad * p.Kp * es, 0);
+        for (int o = 0; o < Co; ++o)
+            for (int r = 0; r < d.kh; ++r)
+                for (int s = 0; s < d.kw; ++s)
+                    for (int ch = 0; ch < Ci; ++ch) {
+                        const size_t kidx = ((size_t)((r >> 1) * k2 + (s >> 1)) * 4 + (r & 1) * 2 + (s & 1)) * 4 + ch;
+                        std::memcpy(&wp[((size_t)o * p.Kp + kidx) * es], w + ((((size_t)o * d.kh + r) * d.kw + s) * Ci + ch) * es, es);
+                    }
     } else if (Ci <= 4 && Co % 4 == 0) {
         // first layer: the input is copied into a zero-padded 4-channel image, a kernel row of kwp taps is
         // then kwp*4 contiguous elements; k index = (r * kwp + s) * 4 + c
@@ -105,7 +123,7 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
         p.impl = IMPL_DIRECT;
         wp.assign(w, w + (size_t)Co * d.kh * d.kw * Ci * es);
     }
-    if ((p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_CPAD) && es == 1 && d.shift > 0) {
+    if ((p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_CPAD || p.impl == IMPL_MFMA_S2D) && es == 1 && d.shift > 0) {
         // that kernel requantises with a bare arithmetic shift: the rounding constant 2^(shift-1) goes
         // into the bias (the sum fits int32: the network's calibration guarantees t + 2^(shift-1) does)
         for (int o = 0; o < Co; ++o) {
@@ -230,9 +248,11 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
         const double kred = d.kind == OP_CONV ? (double)d.kh * d.kw * d.c_in : (double)d.kh * d.kw;
         p.ops_per_sample = d.kind == OP_MAXPOOL ? 0.0 : 2.0 * out_e * kred;
         p.bytes_per_sample = (in_e + out_e + (d.res >= 0 ? out_e : 0.0)) * es;
-        if (p.impl == IMPL_MFMA_C4 || p.impl == IMPL_MFMA_CPAD) {
+        if (p.impl == IMPL_MFMA_C4 || p.impl == IMPL_MFMA_CPAD || p.impl == IMPL_MFMA_S2D) {
             void* pb = nullptr;
-            const size_t bytes = p.impl == IMPL_MFMA_C4 ? (size_t)b_max * p.Hp * p.Wp * 4 * es : (size_t)b_max * d.h_in * d.w_in * p.ci_eff * es;
+            const size_t bytes = p.impl == IMPL_MFMA_C4    ? (size_t)b_max * p.Hp * p.Wp * 4 * es
+                                 : p.impl == IMPL_MFMA_S2D ? (size_t)b_max * p.Hp * p.Wp * 16 * es
+                                                           : (size_t)b_max * d.h_in * d.w_in * p.ci_eff * es;
             if ((rc = dev_alloc(ctx, &pb, bytes + 256))) return fail(rc);
             p.pad_buf = (int)ctx->pad_bufs.size();
             ctx->pad_bufs.push_back(pb);
@@ -325,9 +345,13 @@ hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const 
     a.w = p.w_dev; a.bias = p.b_dev; a.res = res; a.y = dst; a.zeros = zero_page;
     a.magic_howo = (unsigned)(0x100000000ull / (unsigned)(d.h_out * d.w_out) - (d.h_out * d.w_out == 1));
     a.magic_wo = (unsigned)(0x100000000ull / (unsigned)d.w_out - (d.w_out == 1));
-    for (int r = 0; r < d.kh && r * d.kw < 32; ++r) a.tap_rows |= 1u << (r * d.kw);
     a.M = b * d.h_out * d.w_out; a.H = d.h_in; a.W = d.w_in; a.Ci = p.ci_eff; a.Ho = d.h_out; a.Wo = d.w_out; a.Co = d.c_out;
     a.kh = d.kh; a.kw = d.kw; a.stride = d.stride; a.pad = d.pad; a.Kp = p.Kp;
+    if (p.impl == IMPL_MFMA_S2D) {      // the folded tensor: ks2 x ks2 kernel, stride 1, padding already inside
+        src = pad_bufs[p.pad_buf];
+        a.H = p.Hp; a.W = p.Wp; a.kh = a.kw = p.kwp; a.stride = 1; a.pad = 0;
+    }
+    for (int r = 0; r < a.kh && r * a.kw < 32; ++r) a.tap_rows |= 1u << (r * a.kw);
     a.shift = d.shift; a.res_shift = d.res_shift; a.lo = d.lo; a.hi = d.hi; a.f_lo = d.f_lo; a.f_hi = d.f_hi;
     if (p.impl == IMPL_MFMA_CPAD) src = pad_bufs[p.pad_buf];
     if (p.impl == IMPL_MFMA_C4) {
@@ -358,12 +382,12 @@ extern "C" int ee_autotune(ee_ctx* ctx, int reps)
         const StageDesc& st = ctx->net.stages[s];
         for (int k = 0; k < st.n_ops && !rc; ++k) {
             OpPlan& p = ctx->plans[st.first_op + k];
-            if (p.impl != IMPL_MFMA && p.impl != IMPL_MFMA_CPAD) continue;
+            if (p.impl != IMPL_MFMA && p.impl != IMPL_MFMA_CPAD && p.impl != IMPL_MFMA_S2D) continue;
             const OpDesc& d = p.d;
             const void* src = resolve(ctx, p.src_buf, ctx->in_buf[s], ctx->out_buf[s]);
             void* dst = resolve(ctx, p.dst_buf, ctx->in_buf[s], ctx->out_buf[s]);
             const void* res = d.res >= 0 ? resolve(ctx, p.res_buf, ctx->in_buf[s], ctx->out_buf[s]) : nullptr;
-            const int kbytes = d.kh * d.kw * p.ci_eff * es;
+            const int kbytes = (p.impl == IMPL_MFMA_S2D ? p.kwp * p.kwp : d.kh * d.kw) * p.ci_eff * es;
             std::vector<int> best(buckets.size(), 0);
             for (size_t bi = 0; bi < buckets.size() && !rc; ++bi) {
                 float best_ms = 1e30f;
@@ -404,7 +428,7 @@ extern "C" int ee_config_table(const ee_ctx* ctx, int op, int* cfg_out, int n)
 }
 
 // ---- one backbone segment ------------------------------------------------------------------------
-int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out)
+int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool first_packed)
 {
     const StageDesc& st = net.stages[stage];
     const int dt = net.dtype, es = net.elem_bytes();
@@ -416,7 +440,12 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out)
         const void* res = d.res >= 0 ? resolve(this, p.res_buf, act_in, act_out) : nullptr;
         const double ops = p.ops_per_sample * b, bytes = p.bytes_per_sample * b + p.weight_bytes;
         hipError_t e = hipSuccess;
-        if (p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_C4 || p.impl == IMPL_MFMA_CPAD) {
+        if (p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_C4 || p.impl == IMPL_MFMA_CPAD || p.impl == IMPL_MFMA_S2D) {
+            if (p.impl == IMPL_MFMA_S2D && !(first_packed && k == 0)) {
+                const double pb = (double)b * ((double)d.h_in * d.w_in * d.c_in + (double)p.Hp * p.Wp * 16) * es;
+                e = timed(EE_K_PAD_INPUT, 0.0, pb, [&] { return launch_space_to_depth(src, pad_bufs[p.pad_buf], nullptr, b, d.h_in, d.w_in, d.c_in, p.Hp, p.Wp, d.pad, dt, stream); });
+                if (e != hipSuccess) return EE_ERR_DEVICE;
+            }
             if (p.impl == IMPL_MFMA_CPAD) {
                 const double pb = (double)b * d.h_in * d.w_in * (d.c_in + p.ci_eff) * es;
                 e = timed(EE_K_PAD_INPUT, 0.0, pb, [&] {

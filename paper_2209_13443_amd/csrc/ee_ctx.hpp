@@ -7,7 +7,7 @@
 
 namespace ee {
 
-enum Impl { IMPL_MFMA = 0, IMPL_MFMA_C4 = 1, IMPL_DIRECT = 2, IMPL_DW = 3, IMPL_POOL = 4, IMPL_MFMA_CPAD = 5 };
+enum Impl { IMPL_MFMA = 0, IMPL_MFMA_C4 = 1, IMPL_DIRECT = 2, IMPL_DW = 3, IMPL_POOL = 4, IMPL_MFMA_CPAD = 5, IMPL_MFMA_S2D = 6 };
 enum { BUF_EXT_IN = -1, BUF_EXT_OUT = -2 };
 
 struct OpPlan {
@@ -19,6 +19,8 @@ struct OpPlan {
     int src_buf = 0, dst_buf = 0, res_buf = 0;   // BUF_EXT_* or an index into Ctx::pool
     int pad_buf = -1;           // padded copy of the input: 4 channels + spatial border (IMPL_MFMA_C4), channels to 16 bytes (IMPL_MFMA_CPAD)
     int ci_eff = 0;             // input channels the matrix-core kernel sees (c_in, or c_in padded to a 16-byte multiple)
+    // IMPL_MFMA_S2D: stride-2 first layer over <= 4 channels, run as a stride-1 convolution with a ks2 x ks2 kernel over the
+    // zero-padded image folded into Hp x Wp super-pixels of 2 x 2 pixels x 4 channels (Hp, Wp, ks2 reuse the fields above)
     std::vector<int> cfg;       // kernel configuration per batch bucket (see ee_autotune); empty = by shape
     double ops_per_sample = 0, bytes_per_sample = 0, weight_bytes = 0;
 };
@@ -70,7 +72,18 @@ struct ee_ctx {
     }
 
     // internal entry points shared by the C ABI and the stream driver (no argument checks)
-    int run_stage(int stage, int b_act, const void* act_in, void* act_out);
+    // first_packed: the first layer's folded input copy already holds these samples (admission wrote it)
+    int run_stage(int stage, int b_act, const void* act_in, void* act_out, bool first_packed = false);
+    // the plan of segment 0's first layer when that layer reads a folded copy admission can write directly, else null
+    const ee::OpPlan* admission_fold() const
+    {
+        const ee::StageDesc& st = net.stages[0];
+        const ee::OpPlan& p = plans[st.first_op];
+        if (p.impl != ee::IMPL_MFMA_S2D || p.src_buf != ee::BUF_EXT_IN) return nullptr;
+        for (int k = 1; k < st.n_ops; ++k)           // nobody else may read the segment input: it is never written then
+            if (plans[st.first_op + k].src_buf == ee::BUF_EXT_IN || plans[st.first_op + k].res_buf == ee::BUF_EXT_IN) return nullptr;
+        return &p;
+    }
     // launches layer `op` (an index into plans) on b samples with the given kernel configuration (0 = by shape)
     hipError_t launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg);
     static int bucket_of(int b) { int k = 0; while ((1 << k) < b) ++k; return k; }     // smallest k with 2^k >= b

@@ -56,6 +56,7 @@ struct ConvArgs {
     int Kp;              // weight row pitch in elements (reduction length, zero padded)
     unsigned magic_howo, magic_wo;   // floor(2^32 / (Ho*Wo)), floor(2^32 / Wo): division by multiply-high
     unsigned tap_rows;   // bit r*kw set for every kernel row r (kh*kw <= 31)
+    int plain_step;      // set by the launcher: bytes the source of a row advances per reduction step when no tap needs a check
     int mode;            // 0: Ci % 16 == 0 loader with bounds checks; 1: 4-channel zero-padded input
     int Hp, Wp, kwp;     // mode 1: padded input dims and padded kernel width
     int shift, res_shift, lo, hi;
@@ -82,6 +83,9 @@ template <int ES> hipError_t launch_conv_igemm(const ConvArgs& a, int tile, hipS
 int forced_conv_tile();
 hipError_t launch_conv_direct(const DirectConvArgs& a, int dtype, hipStream_t s);
 hipError_t launch_pad_input(const void* x, void* y, int B, int H, int W, int C, int Hp, int Wp, int pad, int dtype, hipStream_t s);
+// [B][H][W][C<=4] -> [B][Hs][Ws][2][2][4]: zero padding `pad`, then 2 x 2 pixel blocks folded into channels;
+// with gather (device-visible) sample n is read from row gather[n] of x
+hipError_t launch_space_to_depth(const void* x, void* y, const int32_t* gather, int B, int H, int W, int C, int Hs, int Ws, int pad, int dtype, hipStream_t s);
 // [rows][c_bytes] -> [rows][cp_bytes] (both multiples of 4), the tail of every row zero
 hipError_t launch_pad_channels(const void* x, void* y, long long rows, int c_bytes, int cp_bytes, hipStream_t s);
 hipError_t launch_depthwise(const PoolArgs& a, int dtype, hipStream_t s);

@@ -399,6 +399,48 @@ hipError_t launch_pad_input(const void* x, void* y, int B, int H, int W, int C, 
     return hipGetLastError();
 }
 
+// ---- [B][H][W][C<=4] -> [B][Hs][Ws][(dy, dx, c)]: the image is zero padded by `pad`, then every 2 x 2 block of
+// pixels becomes one 16-element super-pixel.  A stride-2 k x k convolution of the image is a stride-1
+// ceil(k/2) x ceil(k/2) convolution of the folded tensor whose pixels are whole 16-byte chunks. --------------
+template <typename T>
+__global__ __launch_bounds__(256) void space_to_depth_kernel(const T* x, T* y, const int32_t* gather, int B, int H, int W, int C, int Hs, int Ws, int pad)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)B * Hs * Ws) return;
+    const int xs = (int)(idx % Ws), ys = (int)((idx / Ws) % Hs), n = (int)(idx / ((long long)Ws * Hs));
+    alignas(16) T v[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) v[e] = 0;
+#pragma unroll
+    for (int dy = 0; dy < 2; ++dy)
+#pragma unroll
+        for (int dx = 0; dx < 2; ++dx) {
+            const int iy = 2 * ys + dy - pad, ix = 2 * xs + dx - pad;
+            if (iy >= 0 && iy < H && ix >= 0 && ix < W) {
+                const long long row = gather ? gather[n] : n;              // admission reads request gather[n] of a pool
+                const T* p = x + ((row * H + iy) * W + ix) * C;
+                for (int c = 0; c < C; ++c) v[(dy * 2 + dx) * 4 + c] = p[c];
+            }
+        }
+    typedef int v4i_ __attribute__((ext_vector_type(4)));
+    v4i_* q = (v4i_*)(y + idx * 16);
+    const v4i_* src = (const v4i_*)v;
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(T) * 16 / 16); ++i) q[i] = src[i];
+}
+
+hipError_t launch_space_to_depth(const void* x, void* y, const int32_t* gather, int B, int H, int W, int C, int Hs, int Ws, int pad, int dtype, hipStream_t s)
+{
+    const long long total = (long long)B * Hs * Ws;
+    if (total <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    if (dtype == EE_I8)
+        hipLaunchKernelGGL(space_to_depth_kernel<signed char>, dim3(blocks), dim3(256), 0, s, (const signed char*)x, (signed char*)y, gather, B, H, W, C, Hs, Ws, pad);
+    else
+        hipLaunchKernelGGL(space_to_depth_kernel<uint16_t>, dim3(blocks), dim3(256), 0, s, (const uint16_t*)x, (uint16_t*)y, gather, B, H, W, C, Hs, Ws, pad);
+    return hipGetLastError();
+}
+
 // ---- [rows][c_bytes] -> [rows][cp_bytes], zero tail: gives layers whose pixels are not 16-byte multiples
 // the row alignment the matrix-core loader needs ----------------------------------------------------------
 __global__ __launch_bounds__(256) void pad_channels_kernel(const int* x, int* y, long long rows, int c_words, int cp_words)

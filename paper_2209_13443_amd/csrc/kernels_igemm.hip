@@ -211,7 +211,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int
         if constexpr (P < NA) {
             if (PLAIN) {
                 dma16(sbase + P * 4096, xb, voffA[P]);
-                voffA[P] += KS;
+                voffA[P] += a.plain_step;
             } else {
                 const unsigned char* p = (maskA[P] & tapbit) ? xb + (unsigned)(voffA[P] + toff) : zp;
                 dma16(sbase + P * 4096, p);
@@ -412,14 +412,22 @@ static hipError_t launch_igemm_tile(const ConvArgs& a, bool plain, int ns, hipSt
 // cfg: bits 0-3 tile (0 = by shape; 1: 128x128, 2: 128x64, 3: 64x64, 4: 64x128), bits 4-7 reduction step
 // (0 = by shape, 1: 64, 2: 128, 3: 256 bytes), bits 8-11 ring stages (0 = by shape, else 2..4).
 template <int ES>
-hipError_t launch_conv_igemm(const ConvArgs& a, int cfg, hipStream_t s)
+hipError_t launch_conv_igemm(const ConvArgs& a_in, int cfg, hipStream_t s)
 {
-    if (a.M <= 0) return hipSuccess;
+    if (a_in.M <= 0) return hipSuccess;
+    const ConvArgs& a0 = a_in;
     int tile = cfg & 15, ksel = (cfg >> 4) & 15, ns = (cfg >> 8) & 15;
-    const int kbytes = a.kh * a.kw * a.Ci * ES;
+    const int kbytes = a0.kh * a0.kw * a0.Ci * ES;
     if (ksel == 0) ksel = kbytes % 128 == 0 ? 2 : 1;
     const int ks = ksel == 3 ? 256 : (ksel == 2 ? 128 : 64);
-    const bool plain = a.kh == 1 && a.kw == 1 && a.pad == 0 && kbytes % ks == 0;
+    // PLAIN: every reduction step of a row is one contiguous, always valid run of ks bytes: a 1x1 kernel whose
+    // pixel is a multiple of the step (the address advances by the step), or an unpadded stride-1 kernel whose
+    // kernel row is exactly one step (the address advances by one image row)
+    ConvArgs a = a_in;
+    const bool plain_1x1 = a.kh == 1 && a.kw == 1 && a.pad == 0 && kbytes % ks == 0;
+    const bool plain_rows = !plain_1x1 && a.pad == 0 && a.stride == 1 && a.kw * a.Ci * ES == ks;
+    const bool plain = plain_1x1 || plain_rows;
+    a.plain_step = plain_rows ? a.W * a.Ci * ES : ks;
     if (tile == 0) {
         auto blocks = [&](int bm, int bn) { return (long long)((a.M + bm - 1) / bm) * ((a.Co + bn - 1) / bn); };
         const long long want = 2 * 256;

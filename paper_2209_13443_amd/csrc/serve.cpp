@@ -75,7 +75,17 @@ struct GpuExec {
         ctx->ids_turn ^= 1;
         std::memcpy(h_ids, ids, sizeof(int32_t) * (size_t)b);
         const int64_t sb = ctx->stage_in_bytes(0);
-        hipError_t e = ctx->timed(EE_K_ADMIT, 0.0, 2.0 * sb * b, [&] { return launch_admit(pool, ctx->in_buf[0], h_ids, b, sb, ctx->stream); });
+        hipError_t e;
+        if (const OpPlan* p = ctx->admission_fold()) {
+            // the first layer reads a zero-padded, folded copy of its input: admission writes that copy directly
+            const OpDesc& d = p->d;
+            const int es = ctx->net.elem_bytes();
+            e = ctx->timed(EE_K_ADMIT, 0.0, (double)b * (sb + (double)p->Hp * p->Wp * 16 * es), [&] {
+                return launch_space_to_depth(pool, ctx->pad_bufs[p->pad_buf], h_ids, b, d.h_in, d.w_in, d.c_in, p->Hp, p->Wp, d.pad, ctx->net.dtype, ctx->stream);
+            });
+        } else {
+            e = ctx->timed(EE_K_ADMIT, 0.0, 2.0 * sb * b, [&] { return launch_admit(pool, ctx->in_buf[0], h_ids, b, sb, ctx->stream); });
+        }
         return e == hipSuccess ? EE_OK : EE_ERR_DEVICE;
     }
     // A1 + A2 (+ A3 / A4): segment and exit head on slots [0, b); the survivors (flags stay on the device)
@@ -85,7 +95,7 @@ struct GpuExec {
     // and stores a sequence word when they are complete; the host polls that word.
     int segment(int stage, const int32_t*, int b, SlotOutcome* out, int dst_off)
     {
-        int rc = ctx->run_stage(stage, b, ctx->in_buf[stage], ctx->out_buf[stage]);
+        int rc = ctx->run_stage(stage, b, ctx->in_buf[stage], ctx->out_buf[stage], stage == 0 && ctx->admission_fold() != nullptr);
         if (!rc) rc = ctx->run_head(stage, b, ctx->out_buf[stage], ctx->net.exits[stage].thr, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag, true);
         if (rc) return rc;
         if (stage + 1 < (int)ctx->in_buf.size()) {
