@@ -161,8 +161,9 @@ int ee_tune_conv_tile(int tile);
  * fastest; until it is called the configuration is chosen from the layer shape alone.  Results never
  * depend on the table.  ee_config_table copies layer `layer`'s entries to cfg_out[0..n) (host) and
  * returns how many the layer has (0 = not tuned or not a matrix-core convolution); an entry is
- * tile | step << 4 | stages << 8 with tile 1: 128x128, 2: 128x64, 3: 64x64, 4: 64x128 (pixels x channels),
- * step 1: 64, 2: 128, 3: 256 bytes of the reduction axis per stage.  EE_ERR_ARG for bad arguments. */
+ * tile | step << 4 | stages << 8 | groups << 12 with tile 1: 128x128, 2: 128x64, 3: 64x64, 4: 64x128 (pixels x
+ * channels), step 1: 64, 2: 128, 3: 256 bytes of the reduction axis per stage, groups 0: one group of 4
+ * wavefronts, 2 or 4: that many groups sharing the reduction of a tile.  EE_ERR_ARG for bad arguments. */
 int ee_autotune(ee_ctx* ctx, int reps);
 int ee_config_table(const ee_ctx* ctx, int layer, int* cfg_out, int n);
 

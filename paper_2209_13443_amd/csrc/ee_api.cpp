@@ -393,9 +393,11 @@ extern "C" int ee_autotune(ee_ctx* ctx, int reps)
                 float best_ms = 1e30f;
                 for (int tile = 1; tile <= 4; ++tile)
                     for (int ksel = 1; ksel <= 3; ++ksel)
-                        for (int ns = 2; ns <= 4; ++ns) {
+                        for (int ns = 2; ns <= 4; ++ns)
+                            for (int kspl = 1; kspl <= 4; kspl *= 2) {
                             if (ksel > 1 && kbytes <= 64 * (ksel - 1)) continue;        // a longer step than the whole reduction
-                            const int cfg = tile | (ksel << 4) | (ns << 8);
+                            if (kspl > 1 && (ksel != 3 || tile < 3 || (kspl == 4 && tile != 3) || kbytes < 1024)) continue;   // combinations that exist
+                            const int cfg = tile | (ksel << 4) | (ns << 8) | ((kspl > 1 ? kspl : 0) << 12);
                             if (ctx->launch_conv(st.first_op + k, buckets[bi], src, dst, res, cfg) != hipSuccess) {
                                 (void)hipGetLastError();                       // this configuration does not fit: skip it
                                 continue;

@@ -113,21 +113,30 @@ __device__ __forceinline__ unsigned pack4_i8(int q0, int q1, int q2, int q3)
 // ES: element bytes (1 int8, 2 bf16).  BM x BN: workgroup tile (pixels x channels).  KS: bytes of
 // the reduction axis per stage.  ns (2..4, not above the number of steps + 1): stages in the ring.  PLAIN: 1x1 kernel without padding whose
 // reduction length is a multiple of KS -- the source address of a row then simply advances by KS.
-template <int ES, int BM, int BN, int KS, bool PLAIN>
-__global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int gn, unsigned magic_gn, int per_xcd, int ns)
+// KSPL (1, 2, 4): groups of 4 wavefronts per workgroup.  Every group owns the whole tile but only
+// every KSPL-th part of each stage's sub-steps; the groups' accumulators are added through LDS before
+// the epilogue.  This is the re-shaping the paper does in hardware when the row dimension under-fills
+// the array (Sec. III-A, Eq. 1: samples mapped along P instead of R): with few output pixels the
+// reduction axis supplies the parallelism that keeps a CU's matrix cores and copy queue busy.
+template <int ES, int BM, int BN, int KS, int KSPL, bool PLAIN>
+__global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int gm, int gn, unsigned magic_gn, int per_xcd, int ns)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
     constexpr int CPRW = KS / 16;                  // 16-byte chunks per staged row
-    constexpr int RPP = 256 / CPRW;                // rows one copy pass of the workgroup covers
+    constexpr int NT = 256 * KSPL;                 // lanes per workgroup
+    constexpr int RPP = NT / CPRW;                 // rows one copy pass of the workgroup covers
     constexpr int NA = BM / RPP, NB = BN / RPP, LPT = NA + NB;
     constexpr int STAGE = (BM + BN) * KS;
     constexpr int R256 = KS >= 256 ? 1 : 256 / KS; // staged rows per 256 bytes of LDS
     constexpr int CR = BN * ES / 16;               // 16-byte chunks per row of the output tile
     constexpr int OROW = BN * ES, TILE_O = BM * OROW;
-    constexpr int NO = BM * CR / 256;              // output-tile passes of the workgroup
+    constexpr int NO = (BM * CR + NT - 1) / NT;    // output-tile passes of the workgroup
     constexpr int OSWZ = CR - 1 < 7 ? CR - 1 : 7;
-    static_assert(NA >= 1 && NB >= 1 && NO >= 1, "tile too small for 256 lanes");
+    constexpr int NSUB = KS / 32, SPW = NSUB / KSPL;   // matrix sub-steps per stage, and per wavefront
+    constexpr int PART = TM * TN * 4096;           // bytes of one wavefront's accumulators
+    static_assert(NA >= 1 && NB >= 1 && BM % RPP == 0 && BN % RPP == 0, "tile too small for this many lanes");
+    static_assert(SPW >= 1 && SPW * KSPL == NSUB, "more wavefront groups than sub-steps");
 
     const int xcd = blockIdx.x & 7, wslot = blockIdx.x >> 3;
     const int mslot = (int)fast_div((unsigned)wslot, (unsigned)gn, magic_gn);
@@ -136,7 +145,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
+    const int wm0 = (wave & 1) * WM, wn0 = ((wave >> 1) & 1) * WN, kpart = wave >> 2;
     const int m0 = mt * BM, n0 = nt * BN;
     const unsigned char* xb = (const unsigned char*)a.x;
     const unsigned char* zp = (const unsigned char*)a.zeros;
@@ -147,7 +156,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int
     const bool has_res = a.res != nullptr;
     const unsigned lds0 = lds_addr(lds);
     // LDS map: ring | residual tile (without one the output tile aliases the ring) | bias
-    const unsigned ring = igemm_ring_bytes(ns, nk, STAGE, TILE_O);
+    const unsigned ring = igemm_ring_bytes(ns, nk, STAGE, TILE_O > (KSPL - 1) * 4 * PART ? TILE_O : (KSPL - 1) * 4 * PART);
     const unsigned ro_off = has_res && wide ? ring : 0;
     const unsigned bias_off = has_res && wide ? ring + TILE_O : ring;
 
@@ -156,10 +165,10 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int
     if (has_res && wide) {
 #pragma unroll
         for (int j = 0; j < NO; ++j) {
-            const int q = tid + 256 * j, row = q / CR, chunk = (q % CR) ^ (row & OSWZ);
+            const int q = tid + NT * j, row = q / CR, chunk = (q % CR) ^ (row & OSWZ);
             const int m = m0 + row, ch = n0 + chunk * (16 / ES);
             const unsigned char* p = (m < a.M && ch < a.Co) ? (const unsigned char*)a.res + ((size_t)m * a.Co + ch) * ES : zp;
-            dma16(lds0 + ro_off + (256 * j + 64 * wave) * 16, p);
+            if (NT * j + 64 * wave < BM * CR) dma16(lds0 + ro_off + (NT * j + 64 * wave) * 16, p);      // wave-uniform
         }
     }
 
@@ -210,14 +219,14 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int
         constexpr int P = decltype(piece)::value;
         if constexpr (P < NA) {
             if (PLAIN) {
-                dma16(sbase + P * 4096, xb, voffA[P]);
+                dma16(sbase + P * (NT * 16), xb, voffA[P]);
                 voffA[P] += a.plain_step;
             } else {
                 const unsigned char* p = (maskA[P] & tapbit) ? xb + (unsigned)(voffA[P] + toff) : zp;
-                dma16(sbase + P * 4096, p);
+                dma16(sbase + P * (NT * 16), p);
             }
         } else {
-            dma16(sbase + BM * KS + (P - NA) * 4096, a.w, voffB[P - NA]);
+            dma16(sbase + BM * KS + (P - NA) * (NT * 16), a.w, voffB[P - NA]);
             voffB[P - NA] += KS;
         }
     };
@@ -230,9 +239,9 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int
 
     // ---- fragment addressing ---------------------------------------------------------------------------
     const int frow = lane & 31, hi = lane >> 5;
-    int fragoff[KS / 32];
+    int fragoff[SPW];                              // this wavefront's sub-steps: kpart * SPW + u
 #pragma unroll
-    for (int sub = 0; sub < KS / 32; ++sub) fragoff[sub] = frow * KS + (((2 * sub + hi) ^ ((frow / R256) & (CPRW - 1))) * 16);
+    for (int u = 0; u < SPW; ++u) fragoff[u] = frow * KS + (((2 * (kpart * SPW + u) + hi) ^ ((frow / R256) & (CPRW - 1))) * 16);
 
     using acc_t = typename std::conditional<ES == 1, v16i, v16f>::type;
     acc_t acc[TN][TM];
@@ -248,7 +257,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int
     // Fragments of sub-step u+1 are read while sub-step u multiplies.
     auto step = [&](int sc, int si, auto issue_tag) {
         constexpr bool ISSUE = decltype(issue_tag)::value;
-        constexpr int NSUB = KS / 32, PPS = (LPT + NSUB - 1) / NSUB;
+        constexpr int PPS = (LPT + SPW - 1) / SPW;
         const unsigned char* sa = lds + sc * STAGE + wm0 * KS;
         const unsigned char* sb = lds + sc * STAGE + (BM + wn0) * KS;
         const unsigned sbase = lds0 + si * STAGE + wave * 1024;
@@ -261,11 +270,11 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int
             for (int i = 0; i < TM; ++i) x[i] = *(const v4i*)(sa + 32 * i * KS + fragoff[sub]);
         };
         read_frags(0, fw[0], fx[0]);
-        static_for<NSUB>([&](auto sub_tag) {
+        static_for<SPW>([&](auto sub_tag) {
             constexpr int SUB = decltype(sub_tag)::value;
             // fixed order (the scheduler may not move anything across these fences): next fragments, copies,
             // then this sub-step's matrix instructions, which only wait for the fragments read one round earlier
-            if constexpr (SUB + 1 < NSUB) read_frags(SUB + 1, fw[(SUB + 1) & 1], fx[(SUB + 1) & 1]);
+            if constexpr (SUB + 1 < SPW) read_frags(SUB + 1, fw[(SUB + 1) & 1], fx[(SUB + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (ISSUE)
                 static_for<PPS>([&](auto q_tag) {
@@ -307,6 +316,43 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int
         st_c = st_c + 1 == ns ? 0 : st_c + 1;
     }
     lds_barrier();                                  // every wavefront is done with the ring
+    if constexpr (KSPL > 1) {
+        // groups 1 .. KSPL-1 park their accumulators in LDS (16 bytes per lane and store: conflict free),
+        // group 0 adds them up and alone carries on into the epilogue
+        unsigned char* park = lds + ((kpart - 1) * 4 + (wave & 3)) * PART + lane * 16;
+        if (kpart > 0) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        v4i v;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = ES == 1 ? (int)acc[j][i][4 * g + e] : __float_as_int((float)acc[j][i][4 * g + e]);
+                        *(v4i*)(park + ((j * TM + i) * 4 + g) * 1024) = v;
+                    }
+        }
+        lds_barrier();
+        if (kpart == 0) {
+#pragma unroll
+            for (int kp = 1; kp < KSPL; ++kp)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            const v4i v = *(const v4i*)(lds + ((kp - 1) * 4 + (wave & 3)) * PART + lane * 16 + ((j * TM + i) * 4 + g) * 1024);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                if constexpr (ES == 1) acc[j][i][4 * g + e] += v[e];
+                                else acc[j][i][4 * g + e] += __int_as_float(v[e]);
+                            }
+                        }
+        }
+        lds_barrier();                              // the parking area is free again: the output tile may alias it
+    }
 
     // ---- epilogue ------------------------------------------------------------------------------------------
     unsigned char* ro = lds + ro_off;
@@ -364,26 +410,28 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a, int gm, int
                 }
         }
     };
-    if (wide) {
-        if (has_res) finish(std::true_type{}, std::true_type{});
-        else finish(std::false_type{}, std::true_type{});
-    } else {
-        if (has_res) finish(std::true_type{}, std::false_type{});
-        else finish(std::false_type{}, std::false_type{});
+    if (KSPL == 1 || kpart == 0) {
+        if (wide) {
+            if (has_res) finish(std::true_type{}, std::true_type{});
+            else finish(std::false_type{}, std::true_type{});
+        } else {
+            if (has_res) finish(std::true_type{}, std::false_type{});
+            else finish(std::false_type{}, std::false_type{});
+        }
     }
     if (wide) {
         lds_barrier();
 #pragma unroll
         for (int j = 0; j < NO; ++j) {
-            const int q = tid + 256 * j, row = q / CR, chunk = (q % CR) ^ (row & OSWZ);
+            const int q = tid + NT * j, row = q / CR, chunk = (q % CR) ^ (row & OSWZ);
             const int m = m0 + row, ch = n0 + chunk * (16 / ES);
-            if (m < a.M && ch < a.Co) *(v4i*)((unsigned char*)a.y + ((size_t)m * a.Co + ch) * ES) = *(const v4i*)(ro + q * 16);
+            if (q < BM * CR && m < a.M && ch < a.Co) *(v4i*)((unsigned char*)a.y + ((size_t)m * a.Co + ch) * ES) = *(const v4i*)(ro + q * 16);
         }
     }
 }
 
 // ---- launch ------------------------------------------------------------------------------------------------
-template <int ES, int BM, int BN, int KS>
+template <int ES, int BM, int BN, int KS, int KSPL>
 static hipError_t launch_igemm_tile(const ConvArgs& a, bool plain, int ns, hipStream_t s)
 {
     const int gm = (a.M + BM - 1) / BM, gn = (a.Co + BN - 1) / BN, per_xcd = (gm + 7) / 8;
@@ -392,32 +440,34 @@ static hipError_t launch_igemm_tile(const ConvArgs& a, bool plain, int ns, hipSt
     const bool res_tile = a.res != nullptr && (a.Co * ES) % 16 == 0;
     const int nk = (a.kh * a.kw * a.Ci * ES + KS - 1) / KS;
     ns = ns < 2 ? 2 : (ns > 4 ? 4 : ns);
-    const size_t lds_bytes = igemm_ring_bytes(ns, nk, (BM + BN) * KS, BM * BN * ES) + (res_tile ? (size_t)BM * BN * ES : 0) + 1024;
+    constexpr int TILE_O = BM * BN * ES, PARK = (KSPL - 1) * 4 * (BM / 64) * (BN / 64) * 4096;
+    const size_t lds_bytes = igemm_ring_bytes(ns, nk, (BM + BN) * KS, TILE_O > PARK ? TILE_O : PARK) + (res_tile ? (size_t)TILE_O : 0) + 1024;
     // more than 64 KiB of dynamic LDS has to be granted once per kernel
     static const hipError_t granted = [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_igemm_kernel<ES, BM, BN, KS, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_igemm_kernel<ES, BM, BN, KS, KSPL, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_igemm_kernel<ES, BM, BN, KS, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_igemm_kernel<ES, BM, BN, KS, KSPL, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         return e;
     }();
     if (granted != hipSuccess) return granted;
     if (lds_bytes > 160 * 1024) return hipErrorInvalidValue;
     if (plain)
-        hipLaunchKernelGGL((conv_igemm_kernel<ES, BM, BN, KS, true>), grid, dim3(256), lds_bytes, s, a, gm, gn, magic_gn, per_xcd, ns);
+        hipLaunchKernelGGL((conv_igemm_kernel<ES, BM, BN, KS, KSPL, true>), grid, dim3(256 * KSPL), lds_bytes, s, a, gm, gn, magic_gn, per_xcd, ns);
     else
-        hipLaunchKernelGGL((conv_igemm_kernel<ES, BM, BN, KS, false>), grid, dim3(256), lds_bytes, s, a, gm, gn, magic_gn, per_xcd, ns);
+        hipLaunchKernelGGL((conv_igemm_kernel<ES, BM, BN, KS, KSPL, false>), grid, dim3(256 * KSPL), lds_bytes, s, a, gm, gn, magic_gn, per_xcd, ns);
     return hipGetLastError();
 }
 
 // cfg: bits 0-3 tile (0 = by shape; 1: 128x128, 2: 128x64, 3: 64x64, 4: 64x128), bits 4-7 reduction step
-// (0 = by shape, 1: 64, 2: 128, 3: 256 bytes), bits 8-11 ring stages (0 = by shape, else 2..4).
+// (0 = by shape, 1: 64, 2: 128, 3: 256 bytes), bits 8-11 ring stages (0 = by shape, else 2..4), bits 12-15
+// wavefront groups splitting the reduction inside a workgroup (0 or 1: none, 2, 4).  Not every combination
+// exists: hipErrorInvalidValue for one that does not (or does not fit LDS).
 template <int ES>
 hipError_t launch_conv_igemm(const ConvArgs& a_in, int cfg, hipStream_t s)
 {
     if (a_in.M <= 0) return hipSuccess;
-    const ConvArgs& a0 = a_in;
-    int tile = cfg & 15, ksel = (cfg >> 4) & 15, ns = (cfg >> 8) & 15;
-    const int kbytes = a0.kh * a0.kw * a0.Ci * ES;
+    int tile = cfg & 15, ksel = (cfg >> 4) & 15, ns = (cfg >> 8) & 15, kspl = (cfg >> 12) & 15;
+    const int kbytes = a_in.kh * a_in.kw * a_in.Ci * ES;
     if (ksel == 0) ksel = kbytes % 128 == 0 ? 2 : 1;
     const int ks = ksel == 3 ? 256 : (ksel == 2 ? 128 : 64);
     // PLAIN: every reduction step of a row is one contiguous, always valid run of ks bytes: a 1x1 kernel whose
@@ -435,22 +485,28 @@ hipError_t launch_conv_igemm(const ConvArgs& a_in, int cfg, hipStream_t s)
         else tile = blocks(128, 64) >= want ? 2 : 3;
     }
     if (ns == 0) ns = 2;     // measured: more workgroups per CU beat a deeper ring at these problem sizes
+    if (kspl >= 2) {          // measured to pay only for small tiles with the longest step
+        if (kspl == 2 && ks == 256 && tile == 3) return launch_igemm_tile<ES, 64, 64, 256, 2>(a, plain, ns, s);
+        if (kspl == 2 && ks == 256 && tile == 4) return launch_igemm_tile<ES, 64, 128, 256, 2>(a, plain, ns, s);
+        if (kspl == 4 && ks == 256 && tile == 3) return launch_igemm_tile<ES, 64, 64, 256, 4>(a, plain, ns, s);
+        return hipErrorInvalidValue;
+    }
     if (ks == 256) {
-        if (tile == 1) return launch_igemm_tile<ES, 128, 128, 256>(a, plain, ns, s);
-        if (tile == 2) return launch_igemm_tile<ES, 128, 64, 256>(a, plain, ns, s);
-        if (tile == 4) return launch_igemm_tile<ES, 64, 128, 256>(a, plain, ns, s);
-        return launch_igemm_tile<ES, 64, 64, 256>(a, plain, ns, s);
+        if (tile == 1) return launch_igemm_tile<ES, 128, 128, 256, 1>(a, plain, ns, s);
+        if (tile == 2) return launch_igemm_tile<ES, 128, 64, 256, 1>(a, plain, ns, s);
+        if (tile == 4) return launch_igemm_tile<ES, 64, 128, 256, 1>(a, plain, ns, s);
+        return launch_igemm_tile<ES, 64, 64, 256, 1>(a, plain, ns, s);
     }
     if (ks == 128) {
-        if (tile == 1) return launch_igemm_tile<ES, 128, 128, 128>(a, plain, ns, s);
-        if (tile == 2) return launch_igemm_tile<ES, 128, 64, 128>(a, plain, ns, s);
-        if (tile == 4) return launch_igemm_tile<ES, 64, 128, 128>(a, plain, ns, s);
-        return launch_igemm_tile<ES, 64, 64, 128>(a, plain, ns, s);
+        if (tile == 1) return launch_igemm_tile<ES, 128, 128, 128, 1>(a, plain, ns, s);
+        if (tile == 2) return launch_igemm_tile<ES, 128, 64, 128, 1>(a, plain, ns, s);
+        if (tile == 4) return launch_igemm_tile<ES, 64, 128, 128, 1>(a, plain, ns, s);
+        return launch_igemm_tile<ES, 64, 64, 128, 1>(a, plain, ns, s);
     }
-    if (tile == 1) return launch_igemm_tile<ES, 128, 128, 64>(a, plain, ns, s);
-    if (tile == 2) return launch_igemm_tile<ES, 128, 64, 64>(a, plain, ns, s);
-    if (tile == 4) return launch_igemm_tile<ES, 64, 128, 64>(a, plain, ns, s);
-    return launch_igemm_tile<ES, 64, 64, 64>(a, plain, ns, s);
+    if (tile == 1) return launch_igemm_tile<ES, 128, 128, 64, 1>(a, plain, ns, s);
+    if (tile == 2) return launch_igemm_tile<ES, 128, 64, 64, 1>(a, plain, ns, s);
+    if (tile == 4) return launch_igemm_tile<ES, 64, 128, 64, 1>(a, plain, ns, s);
+    return launch_igemm_tile<ES, 64, 64, 64, 1>(a, plain, ns, s);
 }
 
 template hipError_t launch_conv_igemm<1>(const ConvArgs&, int, hipStream_t);

@@ -102,7 +102,7 @@ def test_autotuned_configuration_table_keeps_results(torch, ee, orc):
         assert any(len(t) > 0 for t in tables)
         for t in tables:
             for cfg in t:
-                assert 1 <= (cfg & 15) <= 4 and 1 <= ((cfg >> 4) & 15) <= 3 and 2 <= ((cfg >> 8) & 15) <= 4
+                assert 1 <= (cfg & 15) <= 4 and 1 <= ((cfg >> 4) & 15) <= 3 and 2 <= ((cfg >> 8) & 15) <= 4 and (cfg >> 12) in (0, 2, 4)
         x = W.input_pool(blob, 11)
         for b in (11, 3, 1):
             act = x[:b]
