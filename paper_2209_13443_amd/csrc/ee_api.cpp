@@ -62,6 +62,14 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
         std::vector<unsigned char> bp(b, b + 4 * (size_t)C);
         int rc = upload(ctx, &p.w_dev, wp);
         if (!rc) rc = upload(ctx, &p.b_dev, bp);
+        if (!rc && es == 1 && d.kh == 3) {            // [C/16][row][4-channel group][channel] dwords (w[r][0], w[r][1], w[r][2], 0)
+            std::vector<unsigned char> w3((size_t)C * 12, 0);
+            for (int ch = 0; ch < C; ++ch)
+                for (int r = 0; r < 3; ++r)
+                    for (int s2 = 0; s2 < 3; ++s2)
+                        w3[((((size_t)(ch / 16) * 3 + r) * 4 + (ch % 16) / 4) * 4 + ch % 4) * 4 + s2] = w[(size_t)ch * 9 + r * 3 + s2];
+            rc = upload(ctx, &p.w3_dev, w3);
+        }
         p.weight_bytes = (double)wp.size() + bp.size();
         return rc;
     }
@@ -469,7 +477,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                              d.kh, d.kw, d.stride, d.pad, d.shift, d.res_shift, d.lo, d.hi, d.f_lo, d.f_hi};
             e = timed(EE_K_CONV_DIRECT, ops, bytes, [&] { return launch_conv_direct(a, dt, stream); }, st.first_op + k);
         } else {
-            PoolArgs a{src, p.w_dev, p.b_dev, dst, b, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.kh, d.stride, d.pad, d.shift, d.lo, d.hi, d.f_lo, d.f_hi};
+            PoolArgs a{src, p.w_dev, p.b_dev, dst, p.w3_dev, b, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.kh, d.stride, d.pad, d.shift, d.lo, d.hi, d.f_lo, d.f_hi};
             if (p.impl == IMPL_DW) e = timed(EE_K_DEPTHWISE, ops, bytes, [&] { return launch_depthwise(a, dt, stream); }, st.first_op + k);
             else e = timed(EE_K_MAXPOOL, 0.0, bytes, [&] { return launch_maxpool(a, dt, stream); }, st.first_op + k);
         }

@@ -15,6 +15,7 @@ struct OpPlan {
     int impl = IMPL_DIRECT;
     void* w_dev = nullptr;      // packed weights
     void* b_dev = nullptr;      // bias, padded to the weight rows
+    void* w3_dev = nullptr;     // int8 3x3 depthwise: weights packed per kernel row for the dot-product kernel
     int Kp = 0, kwp = 0, Hp = 0, Wp = 0;
     int src_buf = 0, dst_buf = 0, res_buf = 0;   // BUF_EXT_* or an index into Ctx::pool
     int pad_buf = -1;           // padded copy of the input: 4 channels + spatial border (IMPL_MFMA_C4), channels to 16 bytes (IMPL_MFMA_CPAD)

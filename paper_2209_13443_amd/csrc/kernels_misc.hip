@@ -86,9 +86,95 @@ __global__ __launch_bounds__(256) void depthwise_kernel(PoolArgs a)
     }
 }
 
+// ---- depthwise 3x3, int8, on the 4-way dot product --------------------------------------------------------
+// One lane = 4 output pixels along x times 16 channels.  v_dot4_i32_i8 wants the 4 bytes of a dword to be 4
+// taps of one channel, NHWC delivers 4 channels of one tap: per kernel row the three tap dwords (and a
+// zero) of a 4-channel group are byte-transposed with 8 v_perm_b32, then 4 dot products add the row to the
+// 4 channels.  Weights are packed per 16-channel chunk as [row][4-channel group][channel] dwords
+// (w[r][0], w[r][1], w[r][2], 0), 192 bytes per chunk, and are loaded once for the lane's 4 pixels, whose
+// windows also share input columns: the kernel is bound by the number of 16-byte accesses per lane, and
+// this halves or thirds them.  Taps outside the image read the row's first in-range pixel and become zero.
+template <int STRIDE>
+__global__ __launch_bounds__(256) void depthwise3x3_i8_kernel(PoolArgs a, int groups_x)
+{
+    constexpr int PX = 4, COLS = (PX - 1) * STRIDE + 3;
+    const int cchunks = a.C / 16;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)a.B * a.Ho * groups_x * cchunks) return;
+    const int q = (int)(idx % cchunks);
+    const long long g = idx / cchunks;
+    const int ox0 = (int)(g % groups_x) * PX, oy = (int)((g / groups_x) % a.Ho), n = (int)(g / ((long long)groups_x * a.Ho));
+    const unsigned char* x = (const unsigned char*)a.x + (long long)n * a.H * a.W * a.C + q * 16;
+    const int iy0 = oy * STRIDE - a.pad, ix0 = ox0 * STRIDE - a.pad;
+    const v4i zero4 = {0, 0, 0, 0};
+    v4i xv[3][COLS];
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int c = 0; c < COLS; ++c) {
+            const int iy = iy0 + r, ix = ix0 + c;
+            const bool ok = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+            const v4i v = *(const v4i*)(x + ((long long)(ok ? iy : min(oy * STRIDE, a.H - 1)) * a.W + (ok ? ix : min(ox0 * STRIDE, a.W - 1))) * a.C);
+            xv[r][c] = ok ? v : zero4;
+        }
+    const v4i* wq = (const v4i*)a.w + q * 12;
+    v4i w4[3][4];
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int cg = 0; cg < 4; ++cg) w4[r][cg] = wq[r * 4 + cg];
+    v4i bias[4];
+#pragma unroll
+    for (int cg = 0; cg < 4; ++cg) bias[cg] = *((const v4i*)a.bias + q * 4 + cg);
+#pragma unroll
+    for (int p = 0; p < PX; ++p) {
+        if (ox0 + p >= a.Wo) break;
+        v4i acc[4] = {bias[0], bias[1], bias[2], bias[3]};
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int cg = 0; cg < 4; ++cg) {
+                const unsigned x0 = (unsigned)xv[r][p * STRIDE][cg], x1 = (unsigned)xv[r][p * STRIDE + 1][cg], x2 = (unsigned)xv[r][p * STRIDE + 2][cg];
+                // bytes (x0.c, x1.c, x2.c, 0) for c = 0..3
+                const unsigned lo01 = __builtin_amdgcn_perm(x1, x0, 0x05010400u), hi01 = __builtin_amdgcn_perm(x1, x0, 0x07030602u);
+                const unsigned lo2 = __builtin_amdgcn_perm(0u, x2, 0x0c010c00u), hi2 = __builtin_amdgcn_perm(0u, x2, 0x0c030c02u);
+                const unsigned t0 = __builtin_amdgcn_perm(lo2, lo01, 0x05040100u), t1 = __builtin_amdgcn_perm(lo2, lo01, 0x07060302u);
+                const unsigned t2 = __builtin_amdgcn_perm(hi2, hi01, 0x05040100u), t3 = __builtin_amdgcn_perm(hi2, hi01, 0x07060302u);
+                acc[cg][0] = __builtin_amdgcn_sdot4((int)t0, w4[r][cg][0], acc[cg][0], false);
+                acc[cg][1] = __builtin_amdgcn_sdot4((int)t1, w4[r][cg][1], acc[cg][1], false);
+                acc[cg][2] = __builtin_amdgcn_sdot4((int)t2, w4[r][cg][2], acc[cg][2], false);
+                acc[cg][3] = __builtin_amdgcn_sdot4((int)t3, w4[r][cg][3], acc[cg][3], false);
+            }
+        v4i out;
+#pragma unroll
+        for (int cg = 0; cg < 4; ++cg) {
+            int t[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int v = a.shift > 0 ? (acc[cg][e] + (1 << (a.shift - 1))) >> a.shift : acc[cg][e];
+                t[e] = min(max(v, a.lo), a.hi);
+            }
+            const unsigned lo = __builtin_amdgcn_perm((unsigned)t[1], (unsigned)t[0], 0x0c0c0400u), hi = __builtin_amdgcn_perm((unsigned)t[3], (unsigned)t[2], 0x0c0c0400u);
+            out[cg] = (int)__builtin_amdgcn_perm(hi, lo, 0x05040100u);
+        }
+        *(v4i*)((unsigned char*)a.y + ((((long long)n * a.Ho + oy) * a.Wo + ox0 + p) * a.C) + q * 16) = out;
+    }
+}
+
 hipError_t launch_depthwise(const PoolArgs& a, int dtype, hipStream_t s)
 {
     const int es = dtype == EE_I8 ? 1 : 2;
+    if (dtype == EE_I8 && a.k == 3 && a.w3 && (a.stride == 1 || a.stride == 2)) {
+        const int groups_x = (a.Wo + 3) / 4;
+        const long long total = (long long)a.B * a.Ho * groups_x * (a.C / 16);
+        if (total <= 0) return hipSuccess;
+        PoolArgs b = a;
+        b.w = a.w3;
+        const dim3 grid((unsigned)((total + 255) / 256));
+        if (a.stride == 1) hipLaunchKernelGGL(depthwise3x3_i8_kernel<1>, grid, dim3(256), 0, s, b, groups_x);
+        else hipLaunchKernelGGL(depthwise3x3_i8_kernel<2>, grid, dim3(256), 0, s, b, groups_x);
+        return hipGetLastError();
+    }
     const long long total = (long long)a.B * a.Ho * a.Wo * (a.C * es / 16);
     if (total <= 0) return hipSuccess;
     const unsigned blocks = (unsigned)((total + 255) / 256);
