@@ -56,7 +56,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="resnet50_i8_stream", choices=sorted(WORKLOADS))
     ap.add_argument("--requests", type=int, default=0, help="override the number of requests (0 = the workload's)")
-    ap.add_argument("--min-incr", type=int, default=0, help="smallest catch-up batch (0 = b_max / 4; 1 = Algorithm 1 as printed)")
+    ap.add_argument("--min-incr", type=int, default=0, help="smallest catch-up batch (0 = b_max / 2; 1 = Algorithm 1 as printed)")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples timed on the CPU oracle (0 = automatic, -1 = skip)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the extra step that brackets every kernel launch with HIP events")
     args = ap.parse_args()
@@ -87,7 +87,7 @@ def main():
 
     eng.autotune(reps=5)                               # design-time per-(layer, batch) kernel configuration table
     lut = eng.measure_lut(reps=3)                      # design-time exit-level latency table
-    min_incr = args.min_incr or max(1, b_max // 4)
+    min_incr = args.min_incr or max(1, b_max // 2)
 
     # static-batch throughput (model-level batching, everything queued at t = 0) sets the arrival rate
     zeros = np.zeros(n, np.int64)

@@ -279,7 +279,7 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
     ctx->bfc_dev.resize(n_st);
     for (int s = 0; s < n_st; ++s) {
         const ExitDesc& e = ctx->net.exits[s];
-        if ((e.c * es) % 16 != 0 || e.c * es / 16 > 256) return fail(EE_ERR_UNSUPPORTED);
+        if ((e.c * es) % 16 != 0 || e.c * es / 16 > 256 || e.n_cls > 2048) return fail(EE_ERR_UNSUPPORTED);
         c_max = std::max(c_max, e.c);
         std::vector<unsigned char> w(base + e.w_off, base + e.w_off + (size_t)e.n_cls * e.c * es);
         std::vector<unsigned char> b(base + e.b_off, base + e.b_off + 4 * (size_t)e.n_cls);

@@ -471,21 +471,35 @@ __device__ __forceinline__ T block_reduce(T v, T* scratch, bool is_max)
 
 // one workgroup per sample.  int8: m = max logit, label = lowest arg-max, S = sum_j T[frac(d_j)] >> (d_j >> f)
 // with d_j = m - a_j (a base-2 softmax denominator in Q30); exits iff S <= s_thr.  bf16: float softmax.
+// The sample's logits are read once into registers (up to 8 per lane: n_cls <= 2048); the arg-max and the
+// denominator travel through one combined reduction.
 template <int ES>
 __global__ __launch_bounds__(256) void softmax_kernel(HeadArgs a)
 {
     __shared__ long long scratch[8];
+    __shared__ int scratch_arg[4];
     const int b = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int PER = 8;
+    int vi[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int j = threadIdx.x + 256 * i;
+        vi[i] = j < a.n_cls ? ((const int*)a.logits)[(long long)b * a.n_cls + j] : (ES == 1 ? INT32_MIN : __float_as_int(-INFINITY));
+    }
     if constexpr (ES == 1) {
-        const int* lg = (const int*)a.logits + (long long)b * a.n_cls;
         int m = INT32_MIN;
-        for (int j = threadIdx.x; j < a.n_cls; j += 256) m = max(m, lg[j]);
+#pragma unroll
+        for (int i = 0; i < PER; ++i) m = max(m, vi[i]);
         m = block_reduce<int>(m, (int*)scratch, true);
         int arg = INT32_MAX;
         long long S = 0;
         const int f = a.frac_bits;
-        for (int j = threadIdx.x; j < a.n_cls; j += 256) {
-            const int v = lg[j];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int j = threadIdx.x + 256 * i;
+            if (j >= a.n_cls) continue;
+            const int v = vi[i];
             if (v == m) arg = min(arg, j);
             const long long d = (long long)m - v;
             const long long q = d >> f;
@@ -493,8 +507,15 @@ __global__ __launch_bounds__(256) void softmax_kernel(HeadArgs a)
             const int r = (int)(f >= 8 ? frac >> (f - 8) : frac << (8 - f));
             S += q >= 31 ? 0 : (long long)(kExp2[r] >> q);
         }
-        arg = -block_reduce<int>(-arg, (int*)scratch, true);
-        S = block_reduce<long long>(S, scratch, false);
+        for (int o = 32; o > 0; o >>= 1) {                  // integer sums and minima: exact in any order
+            S += __shfl_xor(S, o, 64);
+            arg = min(arg, __shfl_xor(arg, o, 64));
+        }
+        __syncthreads();
+        if (lane == 0) { scratch[wave] = S; scratch_arg[wave] = arg; }
+        __syncthreads();
+        S = scratch[0] + scratch[1] + scratch[2] + scratch[3];
+        arg = min(min(scratch_arg[0], scratch_arg[1]), min(scratch_arg[2], scratch_arg[3]));
         // the pooled sums of this sample have been consumed by the FC: leave them zero for the next head
         for (int c = threadIdx.x; c < a.C; c += 256) a.sums[(long long)b * a.C + c] = 0;
         if (threadIdx.x == 0) {
@@ -507,18 +528,29 @@ __global__ __launch_bounds__(256) void softmax_kernel(HeadArgs a)
             if (a.host_out) a.host_out[b] = HostOutcome{S, arg, conf, flag, 0u};
         }
     } else {
-        const float* z = (const float*)a.logits + (long long)b * a.n_cls;
         float m = -INFINITY;
-        for (int j = threadIdx.x; j < a.n_cls; j += 256) m = fmaxf(m, z[j]);
+#pragma unroll
+        for (int i = 0; i < PER; ++i) m = fmaxf(m, __int_as_float(vi[i]));
         m = block_reduce<float>(m, (float*)scratch, true);
         int arg = INT32_MAX;
         float den = 0.f;
-        for (int j = threadIdx.x; j < a.n_cls; j += 256) {
-            if (z[j] == m) arg = min(arg, j);
-            den += expf(z[j] - m);
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int j = threadIdx.x + 256 * i;
+            if (j >= a.n_cls) continue;
+            const float z = __int_as_float(vi[i]);
+            if (z == m) arg = min(arg, j);
+            den += expf(z - m);
         }
-        arg = -block_reduce<int>(-arg, (int*)scratch, true);
-        den = block_reduce<float>(den, (float*)scratch, false);
+        for (int o = 32; o > 0; o >>= 1) {                  // fixed shuffle tree: the float sum is reproducible
+            den += __shfl_xor(den, o, 64);
+            arg = min(arg, __shfl_xor(arg, o, 64));
+        }
+        __syncthreads();
+        if (lane == 0) { ((float*)scratch)[wave] = den; scratch_arg[wave] = arg; }
+        __syncthreads();
+        den = ((((float*)scratch)[0] + ((float*)scratch)[1]) + ((float*)scratch)[2]) + ((float*)scratch)[3];
+        arg = min(min(scratch_arg[0], scratch_arg[1]), min(scratch_arg[2], scratch_arg[3]));
         if (threadIdx.x == 0) {
             const float conf = 1.0f / den;
             const uint8_t flag = (uint8_t)(a.last || conf >= a.thr);
