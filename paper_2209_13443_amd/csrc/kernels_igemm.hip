@@ -132,7 +132,11 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
     constexpr int CR = BN * ES / 16;               // 16-byte chunks per row of the output tile
     constexpr int OROW = BN * ES, TILE_O = BM * OROW;
     constexpr int NO = (BM * CR + NT - 1) / NT;    // output-tile passes of the workgroup
-    constexpr int OSWZ = CR - 1 < 7 ? CR - 1 : 7;
+    // output tile: chunk c of row r sits at c ^ oswz(r), oswz(r) = (r / rows per 256 bytes) & (CR - 1): the 32 rows
+    // a wavefront touches with one 4- or 8-byte access per lane then spread over the banks as evenly as the
+    // row length allows (two rows per bank instead of eight)
+    constexpr int OR256 = OROW >= 256 ? 1 : 256 / OROW;
+    auto oswz = [](int r) { return (r / OR256) & (CR - 1); };
     constexpr int NSUB = KS / 32, SPW = NSUB / KSPL;   // matrix sub-steps per stage, and per wavefront
     constexpr int PART = TM * TN * 4096;           // bytes of one wavefront's accumulators
     static_assert(NA >= 1 && NB >= 1 && BM % RPP == 0 && BN % RPP == 0, "tile too small for this many lanes");
@@ -165,7 +169,7 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
     if (has_res && wide) {
 #pragma unroll
         for (int j = 0; j < NO; ++j) {
-            const int q = tid + NT * j, row = q / CR, chunk = (q % CR) ^ (row & OSWZ);
+            const int q = tid + NT * j, row = q / CR, chunk = (q % CR) ^ oswz(row);
             const int m = m0 + row, ch = n0 + chunk * (16 / ES);
             const unsigned char* p = (m < a.M && ch < a.Co) ? (const unsigned char*)a.res + ((size_t)m * a.Co + ch) * ES : zp;
             if (NT * j + 64 * wave < BM * CR) dma16(lds0 + ro_off + (NT * j + 64 * wave) * 16, p);      // wave-uniform
@@ -357,10 +361,10 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
     // ---- epilogue ------------------------------------------------------------------------------------------
     unsigned char* ro = lds + ro_off;
     const int* lbias = (const int*)(lds + bias_off);
-    // Cell of (pixel row r, channel cl) in the output tile: chunk (cl*ES/16) ^ (r & OSWZ) of row r.  r & 7 is the
-    // lane's frow & 7 for all of its rows, and the chunk index splits into a wave-uniform part and a
-    // compile-time part, so one XOR and one add per cell remain.
-    const int swz_l = frow & OSWZ;
+    // Cell of (pixel row r, channel cl) in the output tile: chunk (cl*ES/16) ^ oswz(r) of row r.  oswz has period
+    // 16, so it is oswz(frow) for all of a lane's rows, and the chunk index splits into a wave-uniform part
+    // and a compile-time part: one XOR and one add per cell remain.
+    const int swz_l = oswz(frow);
     auto finish = [&](auto res_tag, auto wide_tag) {
         constexpr bool RES = decltype(res_tag)::value, WIDE = decltype(wide_tag)::value;
 #pragma unroll
@@ -423,7 +427,7 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
         lds_barrier();
 #pragma unroll
         for (int j = 0; j < NO; ++j) {
-            const int q = tid + NT * j, row = q / CR, chunk = (q % CR) ^ (row & OSWZ);
+            const int q = tid + NT * j, row = q / CR, chunk = (q % CR) ^ oswz(row);
             const int m = m0 + row, ch = n0 + chunk * (16 / ES);
             if (q < BM * CR && m < a.M && ch < a.Co) *(v4i*)((unsigned char*)a.y + ((size_t)m * a.Co + ch) * ES) = *(const v4i*)(ro + q * 16);
         }
