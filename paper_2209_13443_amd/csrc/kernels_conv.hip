@@ -409,17 +409,20 @@ __global__ __launch_bounds__(256) void space_to_depth_kernel(const T* x, T* y, c
     if (idx >= (long long)B * Hs * Ws) return;
     const int xs = (int)(idx % Ws), ys = (int)((idx / Ws) % Hs), n = (int)(idx / ((long long)Ws * Hs));
     alignas(16) T v[16];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) v[e] = 0;
+    const long long row = gather ? gather[n] : n;              // admission reads request gather[n] of a pool
+    const T* img = x + row * H * W * C;
+    // all loads first, from clamped (always valid) addresses; what lies in the padding becomes zero afterwards
 #pragma unroll
     for (int dy = 0; dy < 2; ++dy)
 #pragma unroll
         for (int dx = 0; dx < 2; ++dx) {
             const int iy = 2 * ys + dy - pad, ix = 2 * xs + dx - pad;
-            if (iy >= 0 && iy < H && ix >= 0 && ix < W) {
-                const long long row = gather ? gather[n] : n;              // admission reads request gather[n] of a pool
-                const T* p = x + ((row * H + iy) * W + ix) * C;
-                for (int c = 0; c < C; ++c) v[(dy * 2 + dx) * 4 + c] = p[c];
+            const bool ok = iy >= 0 && iy < H && ix >= 0 && ix < W;
+            const T* p = img + ((long long)min(max(iy, 0), H - 1) * W + min(max(ix, 0), W - 1)) * C;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const T t = c < C ? p[c < C ? c : 0] : (T)0;
+                v[(dy * 2 + dx) * 4 + c] = ok ? t : (T)0;
             }
         }
     typedef int v4i_ __attribute__((ext_vector_type(4)));
