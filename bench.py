@@ -134,7 +134,7 @@ def main():
     roofline = None
     if conv["launches"]:
         achieved = conv["ops"] / (conv["ms"] * 1e-3) / 1e12
-        roofline = dict(bound="mfma", kernel="conv_mfma_kernel", achieved=round(achieved, 2), peak=PEAK[dtype],
+        roofline = dict(bound="mfma", kernel="conv_igemm_kernel", achieved=round(achieved, 2), peak=PEAK[dtype],
                         unit="TOP/s" if dtype == "i8" else "TFLOP/s", frac=round(achieved / PEAK[dtype], 4), traffic=None,
                         launches=conv["launches"], avg_launch_us=round(conv["ms"] * 1e3 / conv["launches"], 2),
                         algorithmic_gops_per_launch=round(conv["ops"] / conv["launches"] / 1e9, 3),
