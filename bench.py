@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--workload", default="resnet50_i8_stream", choices=sorted(WORKLOADS))
     ap.add_argument("--requests", type=int, default=0, help="override the number of requests (0 = the workload's)")
     ap.add_argument("--min-incr", type=int, default=0, help="smallest catch-up batch (0 = b_max / 2; 1 = Algorithm 1 as printed)")
+    ap.add_argument("--t-slo-ms", type=float, default=-1.0, help="latency SLO of Eq. 3 in ms (negative = none: throughput run)")
+    ap.add_argument("--load", type=float, default=0.0, help="arrival rate as a multiple of the static-batch throughput (0 = the workload's)")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples timed on the CPU oracle (0 = automatic, -1 = skip)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the extra step that brackets every kernel launch with HIP events")
     args = ap.parse_args()
@@ -95,15 +97,17 @@ def main():
     t0 = time.perf_counter()
     res_static, st_static, _ = eng.serve_stream(zeros, pool, lut, clock=0, refill=0)
     static_rate = n / (time.perf_counter() - t0)
-    if wl["load"] is None:
+    load = args.load or wl["load"]
+    if load is None:
         arrivals = zeros
     elif wl["spikes"]:
-        arrivals = W.spiky_trace(n, wl["load"] * static_rate)
+        arrivals = W.spiky_trace(n, load * static_rate)
     else:
-        arrivals = W.poisson_trace(n, wl["load"] * static_rate)
+        arrivals = W.poisson_trace(n, load * static_rate)
+    t_slo_ns = int(args.t_slo_ms * 1e6) if args.t_slo_ms >= 0 else -1
 
     def step():
-        return eng.serve_stream(arrivals, pool, lut, clock=0, refill=wl["refill"], min_incr=min_incr)
+        return eng.serve_stream(arrivals, pool, lut, clock=0, refill=wl["refill"], min_incr=min_incr, t_slo_ns=t_slo_ns)
 
     for _ in range(args.warmup):
         step()
@@ -168,14 +172,15 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(elapsed / args.steps * 1e3, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": args.workload, "requests": n, "b_max": b_max, "refill": wl["refill"], "min_incr": min_incr,
-                   "arrival": "poisson" if wl["load"] else "all_at_t0", "arrival_rate_per_s": round(wl["load"] * static_rate, 1) if wl["load"] else None,
-                   "clock": "wall", "t_slo": None},
+                   "arrival": "poisson" if load else "all_at_t0", "arrival_rate_per_s": round(load * static_rate, 1) if load else None,
+                   "clock": "wall", "t_slo_ms": args.t_slo_ms if args.t_slo_ms >= 0 else None},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "static_batch_samples_per_s": round(static_rate, 1),
         "exit_counts": np.bincount(res["exit_idx"], minlength=eng.n_stages).tolist(),
         "mean_batch_per_segment": [round(a / max(b, 1), 2) for a, b in zip(st["seg_samples"], st["seg_runs"])],
         "mean_batch_per_segment_static": [round(a / max(b, 1), 2) for a, b in zip(st_static["seg_samples"], st_static["seg_runs"])],
+        "slo_violation_rate": round(float(np.mean(lat > t_slo_ns)), 4) if t_slo_ns >= 0 else None,
         "preemptions": st["preemptions"], "latency_ms_mean": round(lat.mean() / 1e6, 3), "latency_ms_p99": round(float(np.percentile(lat, 99)) / 1e6, 3),
         "kernels": kernels,
     }
