@@ -63,7 +63,7 @@ def main():
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the extra step that brackets every kernel launch with HIP events")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures the path on ONE GPU; --gpus must be 1", file=sys.stderr)
+        print("bench.py: this program measures the path on ONE GPU; --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
     import torch

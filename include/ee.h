@@ -35,7 +35,7 @@ typedef enum {
     EE_OK = 0,
     EE_ERR_ARG = -1,          /* NULL pointer, index or batch size out of range, misaligned pointer */
     EE_ERR_SHAPE = -2,        /* blob whose tensor shapes do not chain */
-    EE_ERR_UNSUPPORTED = -3,  /* dtype or layer kind this build does not carry */
+    EE_ERR_UNSUPPORTED = -3,  /* dtype or layer kind the library does not carry */
     EE_ERR_DEVICE = -4,       /* HIP error (no device, allocation or launch failure) */
     EE_ERR_OVERFLOW = -5      /* a size does not fit the library's limits */
 } ee_status;

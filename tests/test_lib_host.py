@@ -58,6 +58,8 @@ def test_null_and_range_arguments_are_rejected_without_a_gpu(ee):
     lib = ee.raw()
     assert lib.ee_stage_forward(None, 0, 1, None, None) == ee.EE_ERR_ARG
     assert lib.ee_exit_head(None, 0, 1, None, 0.5, None, None, None, None) == ee.EE_ERR_ARG
+    assert lib.ee_autotune(None, 3) == ee.EE_ERR_ARG
+    assert lib.ee_config_table(None, 0, None, 0) == ee.EE_ERR_ARG
     assert lib.ee_compact_refill(None, 0, 1, None, None, None, None, None, None, None, 0, None, None) == ee.EE_ERR_ARG
     assert lib.ee_serve_stream(None, None, None, None, None, None, None, 0) == ee.EE_ERR_ARG
     assert lib.ee_query(None, None, None, None) == ee.EE_ERR_ARG
