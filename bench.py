@@ -58,6 +58,8 @@ def main():
     ap.add_argument("--requests", type=int, default=0, help="override the number of requests (0 = the workload's)")
     ap.add_argument("--min-incr", type=int, default=0, help="smallest catch-up batch (0 = b_max / 2; 1 = Algorithm 1 as printed)")
     ap.add_argument("--t-slo-ms", type=float, default=-1.0, help="latency SLO of Eq. 3 in ms (negative = none: throughput run)")
+    ap.add_argument("--refill", type=int, default=-1, choices=[-1, 0, 1, 2],
+                    help="serving policy of the timed steps: 0 model-level batching, 1 Algorithm 1, 2 stage pools (-1 = the workload's)")
     ap.add_argument("--load", type=float, default=0.0, help="arrival rate as a multiple of the static-batch throughput (0 = the workload's)")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples timed on the CPU oracle (0 = automatic, -1 = skip)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the extra step that brackets every kernel launch with HIP events")
@@ -106,8 +108,10 @@ def main():
         arrivals = W.poisson_trace(n, load * static_rate)
     t_slo_ns = int(args.t_slo_ms * 1e6) if args.t_slo_ms >= 0 else -1
 
-    def step():
-        return eng.serve_stream(arrivals, pool, lut, clock=0, refill=wl["refill"], min_incr=min_incr, t_slo_ns=t_slo_ns)
+    refill = wl["refill"] if args.refill < 0 else args.refill
+
+    def step(policy=refill):
+        return eng.serve_stream(arrivals, pool, lut, clock=0, refill=policy, min_incr=min_incr, t_slo_ns=t_slo_ns)
 
     for _ in range(args.warmup):
         step()
@@ -122,6 +126,23 @@ def main():
     elapsed = time.perf_counter() - t0
     marker.sin_()
     value = args.steps * n / elapsed
+
+    # the same trace under the stage-pool policy (an extension: survivors wait in front of the next segment
+    # and segments run on full batches), outside the timed region above
+    pools = None
+    if refill == 1:
+        step(2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            res_p, st_p, _ = step(2)
+        torch.cuda.synchronize()
+        lat_p = res_p["latency_ns"].astype(np.float64)
+        pools = dict(samples_per_s=round(args.steps * n / (time.perf_counter() - t0), 1),
+                     mean_batch_per_segment=[round(a / max(b, 1), 2) for a, b in zip(st_p["seg_samples"], st_p["seg_runs"])],
+                     latency_ms_mean=round(lat_p.mean() / 1e6, 3), latency_ms_p99=round(float(np.percentile(lat_p, 99)) / 1e6, 3),
+                     slo_violation_rate=round(float(np.mean(lat_p > t_slo_ns)), 4) if t_slo_ns >= 0 else None,
+                     same_exits=bool(np.array_equal(res_p["exit_idx"], res["exit_idx"])))
 
     # Per-kernel durations: HIP events on the library's stream around every launch of one more step of
     # the same workload.  Bracketing each launch costs the stream its back-to-back dispatch (about a
@@ -171,12 +192,13 @@ def main():
         "metric": "samples/sec early-exit CNN stream (1 GPU)", "value": round(value, 1), "unit": "samples/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(elapsed / args.steps * 1e3, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-        "config": {"workload": args.workload, "requests": n, "b_max": b_max, "refill": wl["refill"], "min_incr": min_incr,
+        "config": {"workload": args.workload, "requests": n, "b_max": b_max, "refill": refill, "min_incr": min_incr,
                    "arrival": "poisson" if load else "all_at_t0", "arrival_rate_per_s": round(load * static_rate, 1) if load else None,
                    "clock": "wall", "t_slo_ms": args.t_slo_ms if args.t_slo_ms >= 0 else None},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "static_batch_samples_per_s": round(static_rate, 1),
+        "stage_pools": pools,
         "exit_counts": np.bincount(res["exit_idx"], minlength=eng.n_stages).tolist(),
         "mean_batch_per_segment": [round(a / max(b, 1), 2) for a, b in zip(st["seg_samples"], st["seg_runs"])],
         "mean_batch_per_segment_static": [round(a / max(b, 1), 2) for a, b in zip(st_static["seg_samples"], st_static["seg_runs"])],

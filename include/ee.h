@@ -102,8 +102,22 @@ typedef struct {
     const int64_t* lut_ns;  /* host, [n_stages][b_max]: time of segment s (with its exit head) entered with
                                B = column + 1 samples (Sec. III-B, "Exit-Level Latency Prediction") */
     int32_t min_incr;       /* smallest B_incr worth a preemption; 1 = Algorithm 1 as printed */
-    int32_t refill;         /* 0: model-level batching (no preemption); 1: Algorithm 1 */
+    int32_t refill;         /* 0: model-level batching (no preemption); 1: Algorithm 1; 2: stage pools (below) */
 } ee_serve_opts;
+
+/* refill = 2, stage pools, is an extension that is not in the paper.  Algorithm 1 keeps one active batch
+ * and lets newcomers catch up with it (Sec. III-B, non-recursive by design); here the survivors of exit i
+ * wait, first in first out, in a pool in front of segment i+1, and every step runs ONE segment on the front
+ * min(n, b_max) samples of one level (level 0 = the arrival queue):
+ *   - preferred: the deepest level holding a full batch of b_max; else the deepest non-empty pool; else the
+ *     queue; else the server idles until the next arrival;
+ *   - with t_slo_ns >= 0 a pool i goes first when its oldest sample still meets the SLO if segments i..|E|
+ *     run now but not if the preferred step runs first: T_rest < T_slack and not T_first + T_rest < T_slack,
+ *     T_slack as in Eq. (3), T_rest and T_first from lut_ns at the entering batch sizes; the deepest such pool
+ *     whose successor pool is not full (its survivors need room there).
+ * A pool never holds more than 2 b_max - 1 samples.  min_incr is not used.  stats: rounds = launches of
+ * segment 0, criterion_evals / preemptions = evaluations of the SLO rule / times it changed the choice;
+ * events: EE_EV_PROC per launch, EE_EV_CRITERION (stage = pool, b = its batch, aux = 1 if it goes first). */
 
 typedef struct { int32_t exit_idx; int32_t label; float conf; int32_t pad_; int64_t score; int64_t latency_ns; } ee_result;
 
@@ -119,7 +133,7 @@ typedef struct {
 /* Synchronous.  Serves trace->n requests; request k is row k of input_pool (device,
  * [n][H][W][C], resident before the call) and its result is results[k] (host): results are
  * stored by sample id, not in completion order (Sec. III-B, "Overhead").  stats and events
- * may be NULL.  EE_ERR_ARG for decreasing arrival times or b_max out of range. */
+ * may be NULL.  EE_ERR_ARG for decreasing arrival times, b_max out of range or refill outside 0..2. */
 int ee_serve_stream(ee_ctx* ctx, const ee_trace* trace, const void* input_pool, const ee_serve_opts* opts,
                     ee_result* results, ee_serve_stats* stats, ee_event* events, int64_t max_events);
 

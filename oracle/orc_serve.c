@@ -16,6 +16,11 @@
  *     the second term = segments i+1..|E| at the upper bound B_rem + B_incr;
  *   - the server idles until the next arrival when the queue is empty;
  *   - requests are taken from the head of the queue (FIFO), results are stored by sample id.
+ *
+ * Second policy (opts->refill == 2), an extension that is NOT in the paper: stage pools.  Where
+ * Algorithm 1 holds one active batch and lets newcomers catch up with it, here the survivors of
+ * exit i wait in a pool in front of segment i+1, and a segment is launched on a full batch of
+ * B_max whenever some pool (or the arrival queue, level 0) holds that many.  See serve_pooled().
  */
 #include "orc.h"
 
@@ -99,6 +104,104 @@ static void proc_until_exit(server* S, batch* bt, int stage, int catchup, char* 
     bt->b = b_rem;
 }
 
+/* ---- stage pools (extension) ---------------------------------------------------------------------
+ * Level 0 is the arrival queue; level i >= 1 holds, in order of arrival at the level, the samples
+ * that survived exit i-1 (with segment i-1's output).  n_i = size of level i, b_i = min(n_i, B_max).
+ * One step at time `now`, after the arrivals up to `now` have joined level 0:
+ *   preferred level P = the deepest level with n_i >= B_max; if there is none, the deepest level
+ *     i >= 1 with n_i > 0; if there is none, level 0 if n_0 > 0; otherwise the server idles until the
+ *     next arrival;
+ *   with an SLO (T_SLO >= 0) a level i >= 1, i != P, n_i > 0, whose successor is not full (n_{i+1} < B_max,
+ *     so that its survivors find room) overrides P when its oldest sample still
+ *     meets the SLO if its remaining segments run now but not if P's step runs first: with
+ *     T_slack = T_SLO - (now - arrival of that sample)   (Eq. 3) and
+ *     T_rest = sum_{s >= i} T[s][b_i]                     (table of Sec. III-B, entering batch size as the bound),
+ *     T_rest < T_slack  and not  T[P][b_P] + T_rest < T_slack; deepest such level first;
+ *   segment L (the level chosen) runs on the b_L samples that have waited longest at level L; the
+ *   clock advances by T[L][b_L]; samples that exit complete now; the survivors join level L+1 in order.
+ */
+static int64_t serve_pooled_rest(const server* S, int level, int b)
+{
+    int64_t t = 0;
+    for (int s = level; s < S->n_stages; ++s) t += lut(S, s, b);
+    return t;
+}
+
+static int serve_pooled(server* S)
+{
+    const int E = S->n_stages, B = S->b_max, cap = 2 * B;
+    int cnt[8] = {0};
+    int32_t* ids[8] = {0}; char* act[8] = {0};
+    batch bt; bt.b = 0;
+    int64_t max_bytes = 1;
+    for (int s = 0; s < E; ++s) {
+        if (S->sample_bytes[s] > max_bytes) max_bytes = S->sample_bytes[s];
+        if (S->out_bytes[s] > max_bytes) max_bytes = S->out_bytes[s];
+    }
+    const size_t buf = S->forced ? 1 : (size_t)max_bytes * (size_t)B;
+    bt.ids = (int32_t*)malloc(sizeof(int32_t) * (size_t)B); bt.act = (char*)malloc(buf);
+    char* scratch = (char*)malloc(buf);
+    int32_t* scratch_ids = (int32_t*)malloc(sizeof(int32_t) * (size_t)B);
+    for (int i = 1; i < E; ++i) {
+        ids[i] = (int32_t*)malloc(sizeof(int32_t) * (size_t)cap);
+        act[i] = (char*)malloc(S->forced ? 1 : (size_t)S->sample_bytes[i] * (size_t)cap);
+    }
+    S->now = S->arrival[0];
+    while (S->done < S->n && !S->err) {
+        admit(S);
+        const int64_t n0 = queue_size(S);
+        int P = -1;
+        for (int i = E - 1; i >= 1 && P < 0; --i) if (cnt[i] >= B) P = i;
+        if (P < 0 && n0 >= B) P = 0;
+        for (int i = E - 1; i >= 1 && P < 0; --i) if (cnt[i] > 0) P = i;
+        if (P < 0 && n0 > 0) P = 0;
+        if (P < 0) { S->now = S->arrival[S->next_arrival]; continue; }       /* idle until the next arrival */
+        int L = P;
+        if (S->opts->t_slo_ns >= 0) {
+            const int64_t np = P ? cnt[P] : n0;
+            const int64_t t_first = lut(S, P, (int)(np < B ? np : B));
+            for (int i = E - 1; i >= 1; --i) {
+                if (i == P || cnt[i] == 0 || (i + 1 < E && cnt[i + 1] >= B)) continue;
+                int64_t oldest = S->arrival[ids[i][0]];
+                for (int k = 1; k < cnt[i]; ++k) if (S->arrival[ids[i][k]] < oldest) oldest = S->arrival[ids[i][k]];
+                const int64_t t_slack = S->opts->t_slo_ns - (S->now - oldest);
+                const int64_t t_rest = serve_pooled_rest(S, i, cnt[i] < B ? cnt[i] : B);
+                const int urgent = t_rest < t_slack && !(t_first + t_rest < t_slack);
+                S->stats->criterion_evals++;
+                log_event(S, ORC_EV_CRITERION, i, cnt[i] < B ? cnt[i] : B, urgent);
+                if (urgent) { L = i; S->stats->preemptions++; break; }
+            }
+        }
+        /* take the batch from the front of level L */
+        if (L == 0) {
+            pop_into(S, &bt, (int)(n0 < B ? n0 : B));
+            S->stats->rounds++;
+        } else {
+            const int b = cnt[L] < B ? cnt[L] : B;
+            const int64_t sb = S->sample_bytes[L];
+            memcpy(bt.ids, ids[L], sizeof(int32_t) * (size_t)b);
+            memmove(ids[L], ids[L] + b, sizeof(int32_t) * (size_t)(cnt[L] - b));
+            if (!S->forced) {
+                memcpy(bt.act, act[L], (size_t)(sb * b));
+                memmove(act[L], act[L] + sb * b, (size_t)(sb * (cnt[L] - b)));
+            }
+            cnt[L] -= b; bt.b = b;
+        }
+        proc_until_exit(S, &bt, L, 0, scratch, scratch_ids);
+        if (S->err) break;
+        if (L + 1 < E && bt.b > 0) {                                         /* survivors wait for segment L+1 */
+            if (cnt[L + 1] + bt.b > cap) { S->err = ORC_ERR_OVERFLOW; break; }    /* cannot happen: a full deeper level runs first */
+            memcpy(ids[L + 1] + cnt[L + 1], bt.ids, sizeof(int32_t) * (size_t)bt.b);
+            if (!S->forced) memcpy(act[L + 1] + S->sample_bytes[L + 1] * cnt[L + 1], bt.act, (size_t)(S->sample_bytes[L + 1] * bt.b));
+            cnt[L + 1] += bt.b;
+        }
+    }
+    S->stats->end_time_ns = S->now;
+    for (int i = 1; i < E; ++i) { free(ids[i]); free(act[i]); }
+    free(bt.ids); free(bt.act); free(scratch); free(scratch_ids);
+    return S->err;
+}
+
 int orc_serve_stream(const void* blob, size_t bytes, int64_t n, const int64_t* arrival_ns, const void* input_pool,
                      const orc_serve_opts* opts, const int32_t* forced_exit, int n_stages_forced,
                      orc_result* results, orc_serve_stats* stats, orc_event* events, int64_t max_events)
@@ -128,6 +231,7 @@ int orc_serve_stream(const void* blob, size_t bytes, int64_t n, const int64_t* a
         }
     }
     if (n == 0) return ORC_OK;
+    if (opts->refill == 2) return serve_pooled(&S);
 
     batch active, fresh;
     const size_t buf = forced_exit ? 1 : (size_t)max_bytes * (size_t)S.b_max;

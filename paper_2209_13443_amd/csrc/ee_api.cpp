@@ -292,11 +292,12 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
     if ((rc = dev_alloc(ctx, &ctx->d_count, 64))) return fail(rc);
     if ((rc = dev_alloc(ctx, &ctx->zero_page, 256))) return fail(rc);
 
-    // stream-serving workspace: packed input slots and raw output slots of every segment
+    // stream-serving workspace: packed input slots and raw output slots of every segment.  Behind the first
+    // segment the input slots are twice b_max: the stage-pool policy keeps up to 2 b_max - 1 waiting samples there.
     ctx->in_buf.resize(n_st);
     ctx->out_buf.resize(n_st);
     for (int s = 0; s < n_st; ++s) {
-        if ((rc = dev_alloc(ctx, &ctx->in_buf[s], (size_t)ctx->stage_in_bytes(s) * b_max))) return fail(rc);
+        if ((rc = dev_alloc(ctx, &ctx->in_buf[s], (size_t)ctx->stage_in_bytes(s) * b_max * (s ? 2 : 1)))) return fail(rc);
         if ((rc = dev_alloc(ctx, &ctx->out_buf[s], (size_t)ctx->stage_out_bytes(s) * b_max))) return fail(rc);
     }
     if ((rc = dev_alloc(ctx, &ctx->d_ids, sizeof(int32_t) * (size_t)b_max))) return fail(rc);
@@ -548,7 +549,7 @@ extern "C" int ee_compact_refill(ee_ctx* ctx, int stage, int b_act, const uint8_
     if (b_act > 0) {
         const double bytes = 2.0 * sb * b_act;       // upper bound: every slot read and written
         if (ctx->timed(EE_K_COMPACT, 0.0, bytes, [&] {
-                return launch_compact(exit_flag, act_src, act_dst, ids_src, ids_dst, b_act, sb, 0, ctx->d_count, b_rem_out, s);
+                return launch_compact(exit_flag, act_src, act_dst, ids_src, ids_dst, b_act, sb, 0, 0, ctx->d_count, b_rem_out, s);
             }) != hipSuccess)
             return EE_ERR_DEVICE;
     } else {

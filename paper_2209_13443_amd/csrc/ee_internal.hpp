@@ -110,9 +110,10 @@ hipError_t launch_head_gap(const HeadArgs& a, int dtype, hipStream_t s);
 hipError_t launch_head_fc(const HeadArgs& a, int dtype, hipStream_t s);
 hipError_t launch_head_softmax(const HeadArgs& a, int dtype, hipStream_t s);
 
-// Stable compaction + append.  dst_off: first destination slot of the survivors.
+// Stable compaction + append.  dst_off: first destination slot of the survivors; ring_rows > 0: dst is a ring of that
+// many slots and destination slots wrap around its end.
 hipError_t launch_compact(const uint8_t* flag, const void* src, void* dst, const int32_t* ids_src, int32_t* ids_dst,
-                          int b_act, int64_t sample_bytes, int dst_off, int* b_rem_out, int* b_rem_out2, hipStream_t s);
+                          int b_act, int64_t sample_bytes, int dst_off, int ring_rows, int* b_rem_out, int* b_rem_out2, hipStream_t s);
 hipError_t launch_append(const void* refill, void* dst, const int32_t* refill_ids, int32_t* ids_dst, const int* b_rem_dev,
                          int b_rem_host, int b_incr, int64_t sample_bytes, int* b_merged_out, hipStream_t s);
 // Admission: pool rows ids[k] -> slots [0, b)

@@ -583,10 +583,11 @@ hipError_t launch_head_softmax(const HeadArgs& a, int dtype, hipStream_t s)
 // ---- compaction: survivors keep their order ---------------------------------------------------------------
 // grid (chunks of 16 KiB, b_act).  Every workgroup recomputes its slot's destination = number of
 // survivors in front of it with a ballot-style block count over the (<= 1024) flags, then copies its
-// chunk with 16-byte accesses.
+// chunk with 16-byte accesses.  ring_rows > 0: dst is a ring of that many sample rows and the
+// destination row wraps around its end.
 __global__ __launch_bounds__(256) void compact_kernel(const uint8_t* flag, const unsigned char* src, unsigned char* dst,
                                                       const int32_t* ids_src, int32_t* ids_dst, int b_act,
-                                                      long long sample_bytes, int dst_off, int* b_rem_out, int* b_rem_out2)
+                                                      long long sample_bytes, int dst_off, int ring_rows, int* b_rem_out, int* b_rem_out2)
 {
     const int b = blockIdx.y;
     int before = 0, total = 0;
@@ -601,7 +602,8 @@ __global__ __launch_bounds__(256) void compact_kernel(const uint8_t* flag, const
         if (b_rem_out2) *b_rem_out2 = total;
     }
     if (flag[b]) return;
-    const int d = dst_off + before;
+    int d = dst_off + before;
+    if (ring_rows > 0 && d >= ring_rows) d -= ring_rows;
     if (blockIdx.x == 0 && threadIdx.x == 0 && ids_dst && ids_src) ids_dst[d] = ids_src[b];
     const long long c0 = (long long)blockIdx.x * 16384;
     const v4i* s4 = (const v4i*)(src + (long long)b * sample_bytes + c0);
@@ -611,12 +613,12 @@ __global__ __launch_bounds__(256) void compact_kernel(const uint8_t* flag, const
 }
 
 hipError_t launch_compact(const uint8_t* flag, const void* src, void* dst, const int32_t* ids_src, int32_t* ids_dst,
-                          int b_act, int64_t sample_bytes, int dst_off, int* b_rem_out, int* b_rem_out2, hipStream_t s)
+                          int b_act, int64_t sample_bytes, int dst_off, int ring_rows, int* b_rem_out, int* b_rem_out2, hipStream_t s)
 {
     if (b_act <= 0) return hipSuccess;
     dim3 grid((unsigned)((sample_bytes + 16383) / 16384), b_act);
     hipLaunchKernelGGL(compact_kernel, grid, dim3(256), 0, s, flag, (const unsigned char*)src, (unsigned char*)dst,
-                       ids_src, ids_dst, b_act, (long long)sample_bytes, dst_off, b_rem_out, b_rem_out2);
+                       ids_src, ids_dst, b_act, (long long)sample_bytes, dst_off, ring_rows, b_rem_out, b_rem_out2);
     return hipGetLastError();
 }
 

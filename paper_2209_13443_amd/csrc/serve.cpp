@@ -13,6 +13,10 @@
 //   - Eq. 4 uses the latency table by segment and entering batch size, with the upper bound
 //     B_rem + B_incr for the merged batch;
 //   - the server idles until the next arrival when the queue is empty; FIFO admission.
+//
+// A second policy, stage pools (refill = 2), is an extension that is not in the paper: the survivors of
+// exit i wait in a pool in front of segment i+1 and a segment is launched on a full batch of B_max
+// whenever a pool (or the arrival queue) holds one.  See PoolScheduler below.
 #include <chrono>
 #include <cstring>
 #include <thread>
@@ -55,7 +59,7 @@ struct WallClock {
 struct TableExec {
     const int32_t* forced; int n_stages;
     int admit(const int32_t*, int) { return EE_OK; }
-    int segment(int stage, const int32_t* ids, int b, SlotOutcome* out, int)
+    int segment(int stage, const int32_t* ids, int b, SlotOutcome* out, int, int, int)
     {
         for (int k = 0; k < b; ++k) out[k] = SlotOutcome{(uint8_t)(stage == n_stages - 1 || forced[ids[k]] == stage), -1, 0.f, 0};
         return EE_OK;
@@ -88,20 +92,22 @@ struct GpuExec {
         }
         return e == hipSuccess ? EE_OK : EE_ERR_DEVICE;
     }
-    // A1 + A2 (+ A3 / A4): segment and exit head on slots [0, b); the survivors (flags stay on the device)
-    // are packed into the next segment's input slots [dst_off, dst_off + B_rem) right behind the head,
-    // dst_off > 0 merging a catch-up batch behind the parked survivors.  Then the one device-to-host
-    // crossing of the boundary: the head kernel has written the per-slot outcomes into pinned host memory
-    // and stores a sequence word when they are complete; the host polls that word.
-    int segment(int stage, const int32_t*, int b, SlotOutcome* out, int dst_off)
+    // A1 + A2 (+ A3 / A4): segment and exit head on the b samples in input slots [src_off, src_off + b); the
+    // survivors (flags stay on the device) are packed into the next segment's input slots
+    // [dst_off, dst_off + B_rem) right behind the head, dst_off > 0 merging a catch-up batch behind the parked
+    // survivors; with ring_rows > 0 those slots form a ring and the destination wraps around its end.
+    // Then the one device-to-host crossing of the boundary: the head kernel has written the per-slot outcomes
+    // into pinned host memory and stores a sequence word when they are complete; the host polls that word.
+    int segment(int stage, const int32_t*, int b, SlotOutcome* out, int src_off, int dst_off, int ring_rows)
     {
-        int rc = ctx->run_stage(stage, b, ctx->in_buf[stage], ctx->out_buf[stage], stage == 0 && ctx->admission_fold() != nullptr);
+        const unsigned char* in = (const unsigned char*)ctx->in_buf[stage] + (int64_t)src_off * ctx->stage_in_bytes(stage);
+        int rc = ctx->run_stage(stage, b, in, ctx->out_buf[stage], stage == 0 && ctx->admission_fold() != nullptr);
         if (!rc) rc = ctx->run_head(stage, b, ctx->out_buf[stage], ctx->net.exits[stage].thr, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag, true);
         if (rc) return rc;
         if (stage + 1 < (int)ctx->in_buf.size()) {
             const int64_t sb = ctx->stage_out_bytes(stage);
             hipError_t e = ctx->timed(EE_K_COMPACT, 0.0, 2.0 * sb * b, [&] {
-                return launch_compact(ctx->d_flag, ctx->out_buf[stage], ctx->in_buf[stage + 1], nullptr, nullptr, b, sb, dst_off, nullptr, nullptr, ctx->stream);
+                return launch_compact(ctx->d_flag, ctx->out_buf[stage], ctx->in_buf[stage + 1], nullptr, nullptr, b, sb, dst_off, ring_rows, nullptr, nullptr, ctx->stream);
             });
             if (e != hipSuccess) return EE_ERR_DEVICE;
         }
@@ -127,40 +133,19 @@ struct GpuExec {
     }
 };
 
-// ---- Algorithm 1 ---------------------------------------------------------------------------------------
+// ---- what both policies share: the arrival queue, the books, one segment run --------------------------
 template <class Exec, class Clock>
-class FluidScheduler {
-public:
-    FluidScheduler(Exec& ex, Clock& ck, int n_stages, const ee_trace* tr, const ee_serve_opts* o, ee_result* res,
-                   ee_serve_stats* st, ee_event* ev, int64_t max_ev)
+class ServeBase {
+protected:
+    ServeBase(Exec& ex, Clock& ck, int n_stages, const ee_trace* tr, const ee_serve_opts* o, ee_result* res,
+              ee_serve_stats* st, ee_event* ev, int64_t max_ev)
         : exec(ex), clock(ck), E(n_stages), n(tr->n), arrival(tr->arrival_ns), opts(*o), results(res), stats(st), events(ev), max_events(max_ev),
-          active(o->b_max), fresh(o->b_max), outcome(o->b_max) {}
+          outcome(o->b_max) {}
 
-    int run()
-    {
-        clock.start(arrival[0]);
-        int rc = EE_OK;
-        while (completed < n && !rc) {
-            admit_arrivals();
-            if (queued() == 0) { clock.idle_until(arrival[arrived]); admit_arrivals(); }
-            rc = start_round();
-            for (int i = 0; i < E && !rc && b_act > 0; ++i) {
-                rc = proc_until_exit(active, b_act, i, /*catchup=*/false, /*merge_at=*/0);
-                if (rc || i == E - 1 || b_act == 0) break;
-                if (opts.refill) rc = refill_at_exit(i);
-            }
-        }
-        stats->end_time_ns = clock.now();
-        return rc;
-    }
-
-private:
     Exec& exec; Clock& clock;
     const int E; const int64_t n; const int64_t* arrival; const ee_serve_opts opts;
     ee_result* results; ee_serve_stats* stats; ee_event* events; const int64_t max_events;
-    std::vector<int32_t> active, fresh;      // request ids per slot
     std::vector<SlotOutcome> outcome;
-    int b_act = 0;
     int64_t arrived = 0, popped = 0, completed = 0;
 
     int64_t queued() const { return arrived - popped; }                       // N_Q
@@ -171,26 +156,17 @@ private:
         if (events && stats->n_events < max_events) events[stats->n_events] = ee_event{clock.now(), kind, stage, b, aux};
         stats->n_events++;
     }
-    void pop(std::vector<int32_t>& ids, int count) { for (int k = 0; k < count; ++k) ids[k] = (int32_t)popped++; }
-
-    int start_round()
-    {
-        b_act = (int)std::min<int64_t>(queued(), opts.b_max);                 // B_act <- min(N_Q, B_max)
-        pop(active, b_act);
-        stats->rounds++;
-        log(EE_EV_ROUND, 0, b_act, 0);
-        return exec.admit(active.data(), b_act);
-    }
+    void pop(int32_t* ids, int count) { for (int k = 0; k < count; ++k) ids[k] = (int32_t)popped++; }
 
     // ProcUntilExit for one segment: run it (the executor also packs the survivors for the next segment),
     // book the samples that leave, keep the survivors' ids in order.
     // `b` is updated to the number of survivors.
-    int proc_until_exit(std::vector<int32_t>& ids, int& b, int stage, bool catchup, int merge_at)
+    int proc_until_exit(int32_t* ids, int& b, int stage, bool catchup, int src_off, int dst_off, int ring_rows)
     {
         log(catchup ? EE_EV_PROC_CATCHUP : EE_EV_PROC, stage, b, 0);
         stats->seg_runs[stage]++;
         stats->seg_samples[stage] += b;
-        int rc = exec.segment(stage, ids.data(), b, outcome.data(), merge_at);
+        int rc = exec.segment(stage, ids, b, outcome.data(), src_off, dst_off, ring_rows);
         if (rc) return rc;
         clock.segment_done(stage, b);
         const int64_t t = clock.now();
@@ -208,6 +184,51 @@ private:
         }
         b = kept;
         return rc;
+    }
+};
+
+// ---- Algorithm 1 ---------------------------------------------------------------------------------------
+template <class Exec, class Clock>
+class FluidScheduler : ServeBase<Exec, Clock> {
+    using Base = ServeBase<Exec, Clock>;
+    using Base::exec; using Base::clock; using Base::E; using Base::n; using Base::arrival; using Base::opts; using Base::stats;
+    using Base::arrived; using Base::completed; using Base::queued; using Base::admit_arrivals; using Base::lut; using Base::log;
+    using Base::pop; using Base::proc_until_exit;
+
+public:
+    FluidScheduler(Exec& ex, Clock& ck, int n_stages, const ee_trace* tr, const ee_serve_opts* o, ee_result* res,
+                   ee_serve_stats* st, ee_event* ev, int64_t max_ev)
+        : Base(ex, ck, n_stages, tr, o, res, st, ev, max_ev), active(o->b_max), fresh(o->b_max) {}
+
+    int run()
+    {
+        clock.start(arrival[0]);
+        int rc = EE_OK;
+        while (completed < n && !rc) {
+            admit_arrivals();
+            if (queued() == 0) { clock.idle_until(arrival[arrived]); admit_arrivals(); }
+            rc = start_round();
+            for (int i = 0; i < E && !rc && b_act > 0; ++i) {
+                rc = proc_until_exit(active.data(), b_act, i, /*catchup=*/false, 0, /*merge_at=*/0, 0);
+                if (rc || i == E - 1 || b_act == 0) break;
+                if (opts.refill) rc = refill_at_exit(i);
+            }
+        }
+        stats->end_time_ns = clock.now();
+        return rc;
+    }
+
+private:
+    std::vector<int32_t> active, fresh;      // request ids per slot
+    int b_act = 0;
+
+    int start_round()
+    {
+        b_act = (int)std::min<int64_t>(queued(), opts.b_max);                 // B_act <- min(N_Q, B_max)
+        pop(active.data(), b_act);
+        stats->rounds++;
+        log(EE_EV_ROUND, 0, b_act, 0);
+        return exec.admit(active.data(), b_act);
     }
 
     // The inner loop of Algorithm 1 at exit i: while there is room, take B_incr requests, check the
@@ -236,10 +257,10 @@ private:
             if (!accept) break;
             stats->preemptions++;                                                 // the survivors stay parked in their slots
             int b_new = b_incr;
-            pop(fresh, b_new);
+            pop(fresh.data(), b_new);
             int rc = exec.admit(fresh.data(), b_new);
             for (int s = 0; s <= i && !rc && b_new > 0; ++s)                      // catch-up run, no nested refill
-                rc = proc_until_exit(fresh, b_new, s, true, s == i ? b_rem : 0);
+                rc = proc_until_exit(fresh.data(), b_new, s, true, 0, s == i ? b_rem : 0, 0);
             if (rc) return rc;
             for (int k = 0; k < b_new; ++k) active[b_rem + k] = fresh[k];
             b_rem += b_new;                                                       // B_merged
@@ -250,11 +271,107 @@ private:
     }
 };
 
+// ---- stage pools (extension) ------------------------------------------------------------------------------
+// Level 0 is the arrival queue; level i >= 1 is a first-in first-out pool of the samples that survived
+// exit i-1, parked in segment i's input slots, which form a ring of 2 B_max rows.  A batch is the front
+// min(n_i, B_max) samples of one level.  Which level runs next:
+//   the preferred level is the deepest one that holds a full batch; failing that the deepest non-empty pool
+//   (samples in flight finish before new ones start); failing that the queue; failing that the server idles;
+//   with an SLO, a pool whose oldest sample still meets it if the pool's remaining segments run now
+//   (T_rest < T_slack, Eq. 3 with the latency table) but not if the preferred step runs first
+//   (not T_first + T_rest < T_slack) goes first instead, the deepest such pool whose successor is not full.
+// A segment never runs while the pool behind it holds a full batch, so a pool never exceeds 2 B_max - 1
+// samples; batches start at ring row 0 or B_max and never wrap (a pool that is emptied restarts at row 0).
+template <class Exec, class Clock>
+class PoolScheduler : ServeBase<Exec, Clock> {
+    using Base = ServeBase<Exec, Clock>;
+    using Base::exec; using Base::clock; using Base::E; using Base::n; using Base::arrival; using Base::opts; using Base::stats;
+    using Base::arrived; using Base::completed; using Base::queued; using Base::admit_arrivals; using Base::lut; using Base::log;
+    using Base::pop; using Base::proc_until_exit;
+
+public:
+    PoolScheduler(Exec& ex, Clock& ck, int n_stages, const ee_trace* tr, const ee_serve_opts* o, ee_result* res,
+                  ee_serve_stats* st, ee_event* ev, int64_t max_ev)
+        : Base(ex, ck, n_stages, tr, o, res, st, ev, max_ev), B(o->b_max), ring(2 * o->b_max), batch(o->b_max)
+    {
+        for (int i = 0; i < E; ++i) { ids[i].assign(i ? ring : 0, -1); head[i] = cnt[i] = 0; }
+    }
+
+    int run()
+    {
+        clock.start(arrival[0]);
+        int rc = EE_OK;
+        while (completed < n && !rc) {
+            admit_arrivals();
+            const int level = choose();
+            if (level < 0) { clock.idle_until(arrival[arrived]); continue; }
+            rc = run_level(level);
+        }
+        stats->end_time_ns = clock.now();
+        return rc;
+    }
+
+private:
+    const int B, ring;
+    std::vector<int32_t> ids[8];             // request ids of the pools, same ring geometry as the activations
+    int head[8], cnt[8];
+    std::vector<int32_t> batch;
+
+    int size_of(int level) const { return level ? cnt[level] : (int)std::min<int64_t>(queued(), INT32_MAX); }
+    int batch_of(int level) const { return std::min(size_of(level), B); }
+
+    int choose()
+    {
+        int pref = -1;
+        for (int i = E - 1; i >= 0 && pref < 0; --i) if (size_of(i) >= B) pref = i;
+        for (int i = E - 1; i >= 1 && pref < 0; --i) if (cnt[i] > 0) pref = i;
+        if (pref < 0 && queued() > 0) pref = 0;
+        if (pref < 0 || opts.t_slo_ns < 0) return pref;
+        const int64_t t_first = lut(pref, batch_of(pref));
+        for (int i = E - 1; i >= 1; --i) {
+            if (i == pref || cnt[i] == 0 || (i + 1 < E && cnt[i + 1] >= B)) continue;
+            const int b = batch_of(i);
+            const int64_t t_slack = opts.t_slo_ns - (clock.now() - arrival[ids[i][head[i]]]);   // the front is the oldest
+            int64_t t_rest = 0;
+            for (int s = i; s < E; ++s) t_rest += lut(s, b);
+            const bool urgent = t_rest < t_slack && !(t_first + t_rest < t_slack);
+            stats->criterion_evals++;
+            log(EE_EV_CRITERION, i, b, urgent ? 1 : 0);
+            if (urgent) { stats->preemptions++; return i; }
+        }
+        return pref;
+    }
+
+    int run_level(int level)
+    {
+        int b = batch_of(level), src = 0, rc = EE_OK;
+        if (level == 0) {
+            pop(batch.data(), b);
+            stats->rounds++;
+            rc = exec.admit(batch.data(), b);
+        } else {
+            src = head[level];
+            for (int k = 0; k < b; ++k) batch[k] = ids[level][src + k];
+            cnt[level] -= b;
+            head[level] = cnt[level] ? (src + b) % ring : 0;
+        }
+        if (rc) return rc;
+        const bool last = level == E - 1;
+        const int tail = last ? 0 : (head[level + 1] + cnt[level + 1]) % ring;
+        rc = proc_until_exit(batch.data(), b, level, false, src, tail, ring);
+        if (rc || last) return rc;
+        if (cnt[level + 1] + b > ring - 1) return EE_ERR_OVERFLOW;                     // cannot happen, see above
+        for (int k = 0; k < b; ++k) ids[level + 1][(tail + k) % ring] = batch[k];
+        cnt[level + 1] += b;
+        return EE_OK;
+    }
+};
+
 int check_serve_args(const ee_trace* tr, const ee_serve_opts* o, const ee_result* res, int n_stages)
 {
     if (!tr || !o || tr->n < 0 || (tr->n > 0 && (!tr->arrival_ns || !res))) return EE_ERR_ARG;
     if (o->b_max < 1 || o->b_max > 1024 || !o->lut_ns || n_stages < 1 || n_stages > 8) return EE_ERR_ARG;
-    if (o->clock != 0 && o->clock != 1) return EE_ERR_ARG;
+    if ((o->clock != 0 && o->clock != 1) || o->refill < 0 || o->refill > 2) return EE_ERR_ARG;
     if (tr->n > INT32_MAX) return EE_ERR_OVERFLOW;
     for (int64_t k = 1; k < tr->n; ++k)
         if (tr->arrival_ns[k] < tr->arrival_ns[k - 1]) return EE_ERR_ARG;
@@ -279,10 +396,12 @@ extern "C" int ee_serve_stream(ee_ctx* ctx, const ee_trace* trace, const void* i
     GpuExec exec(ctx, input_pool);
     if (opts->clock == 1) {
         VirtualClock ck{opts->lut_ns, opts->b_max, 0};
-        rc = FluidScheduler<GpuExec, VirtualClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run();
+        rc = opts->refill == 2 ? PoolScheduler<GpuExec, VirtualClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run()
+                               : FluidScheduler<GpuExec, VirtualClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run();
     } else {
         WallClock ck{};
-        rc = FluidScheduler<GpuExec, WallClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run();
+        rc = opts->refill == 2 ? PoolScheduler<GpuExec, WallClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run()
+                               : FluidScheduler<GpuExec, WallClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run();
     }
     if (hipStreamSynchronize(ctx->stream) != hipSuccess && !rc) rc = EE_ERR_DEVICE;    // the call is synchronous
     return rc;
@@ -300,5 +419,6 @@ extern "C" int ee_schedule_sim(int n_stages, const ee_trace* trace, const int32_
     if (trace->n == 0) return EE_OK;
     TableExec exec{forced_exit, n_stages};
     VirtualClock ck{opts->lut_ns, opts->b_max, 0};
+    if (opts->refill == 2) return PoolScheduler<TableExec, VirtualClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run();
     return FluidScheduler<TableExec, VirtualClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run();
 }

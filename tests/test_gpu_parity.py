@@ -178,6 +178,12 @@ SERVE_CASES = [  # name, n, b_max, arrival gap ns, slo, min_incr, refill
     ("zoo_i8", 48, 8, 700, -1, 1, 1),
     ("resnet50_small_i8", 40, 8, 900, 30000, 1, 1),
     ("mobilenetv2_small_i8", 32, 8, 600, -1, 1, 1),
+    ("tiny_i8", 64, 8, 0, -1, 1, 2),            # stage pools: full batches from the pools in front of the segments
+    ("tiny_i8", 64, 8, 450, 9000, 1, 2),
+    ("tiny_i8", 50, 5, 300, -1, 1, 2),
+    ("zoo_i8", 48, 8, 700, 12000, 1, 2),
+    ("resnet50_small_i8", 60, 8, 200, -1, 1, 2),
+    ("mobilenetv2_small_i8", 40, 8, 100, -1, 1, 2),
 ]
 
 

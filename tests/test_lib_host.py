@@ -106,6 +106,23 @@ def test_scheduler_matches_oracle_bit_for_bit(ee, orc, seed):
         assert np.array_equal(a[f], b[f])
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_stage_pool_scheduler_matches_oracle_bit_for_bit(ee, orc, seed):
+    b_max = [8, 8, 3, 64, 1, 16, 8, 2][seed]
+    arrivals, forced, lut = _case(100 + seed, b_max=b_max, rate=[0.02, 0.2, 0.05, 0.5, 0.01, 0.1, 0.03, 0.02][seed])
+    if seed == 1:
+        arrivals[:] = 0
+    slo = [-1, -1, 700, 2000, -1, 900, 900, 400][seed]
+    a, sa, ea = orc.serve_stream(None, arrivals, None, b_max, lut, t_slo_ns=slo, refill=2, forced_exit=forced, n_stages=4, max_events=20000)
+    b, sb, eb = ee.schedule_sim(4, arrivals, forced, b_max, lut, t_slo_ns=slo, refill=2, max_events=20000)
+    assert sa == sb
+    assert np.array_equal(ea, eb)
+    for f in ("exit_idx", "latency_ns"):
+        assert np.array_equal(a[f], b[f])
+    if slo >= 0:
+        assert sa["preemptions"] > 0                                 # the SLO rule is exercised
+
+
 def test_scheduler_argument_errors(ee):
     arrivals, forced, lut = _case(0)
     bad = arrivals.copy()
@@ -115,6 +132,9 @@ def test_scheduler_argument_errors(ee):
     assert e.value.code == ee.EE_ERR_ARG
     res, st, _ = ee.schedule_sim(4, arrivals[:0], forced[:0], 8, lut)
     assert res.size == 0 and st["rounds"] == 0
+    with pytest.raises(ee.EEError) as e:
+        ee.schedule_sim(4, arrivals, forced, 8, lut, refill=3)
+    assert e.value.code == ee.EE_ERR_ARG
 
 
 def test_timeline_example_through_the_library(ee):
