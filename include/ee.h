@@ -181,6 +181,19 @@ int ee_tune_conv_tile(int tile);
 int ee_autotune(ee_ctx* ctx, int reps);
 int ee_config_table(const ee_ctx* ctx, int layer, int* cfg_out, int n);
 
+/* Fused layer pairs.  A matrix-core convolution without residual whose 64, 128 or 256 output channels are read by
+ * one layer only, the next, a 1x1 stride-1 convolution (conv2 -> conv3 of a bottleneck block), can run as ONE
+ * launch that keeps the intermediate tensor in LDS; results are those of the two separate kernels, bit for bit on
+ * the int8 path.  ee_pair_count: how many layers of the network head such a pair.  ee_pair_mode: 0 = never fuse,
+ * 1 = as the table says (default; until ee_autotune has run: fused below 32 samples, configuration by shape; it then
+ * times every fused configuration against the two best separate kernels per batch bucket), 2 = fuse every pair.
+ * ee_pair_table: like ee_config_table for the fused launch of the pair headed by `layer`; an entry is
+ * rows | step << 4 | stages << 8 with rows 1: 128, 2: 64 pixels per workgroup, step 1: 64, 2: 128 bytes, or 0 = the
+ * two layers run separately for that bucket.  EE_ERR_ARG for bad arguments. */
+int ee_pair_count(const ee_ctx* ctx);
+int ee_pair_mode(ee_ctx* ctx, int mode);
+int ee_pair_table(const ee_ctx* ctx, int layer, int* cfg_out, int n);
+
 /* Host copy of the 256-entry table round(2^30 * 2^(-i/256)) used by the integer softmax. */
 const uint32_t* ee_exp2_table(void);
 

@@ -24,7 +24,8 @@ EVENT_DT = np.dtype([("t_ns", "<i8"), ("kind", "<i4"), ("stage", "<i4"), ("b", "
 
 SYMBOLS = ["ee_strerror", "ee_blob_check", "ee_create", "ee_destroy", "ee_query", "ee_stage_forward", "ee_exit_head",
            "ee_compact_refill", "ee_serve_stream", "ee_schedule_sim", "ee_measure_lut", "ee_profile_enable",
-           "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_last_logits", "ee_profile_reserve", "ee_autotune", "ee_config_table"]
+           "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_last_logits", "ee_profile_reserve", "ee_autotune", "ee_config_table",
+           "ee_pair_count", "ee_pair_mode", "ee_pair_table"]
 
 
 class Trace(C.Structure):
@@ -67,6 +68,9 @@ _lib.ee_measure_lut.argtypes = [_V, C.c_int, _V]
 _lib.ee_last_logits.argtypes = [_V, C.c_int, _V]
 _lib.ee_autotune.argtypes = [_V, C.c_int]
 _lib.ee_config_table.argtypes = [_V, C.c_int, _V, C.c_int]
+_lib.ee_pair_count.argtypes = [_V]
+_lib.ee_pair_mode.argtypes = [_V, C.c_int]
+_lib.ee_pair_table.argtypes = [_V, C.c_int, _V, C.c_int]
 _lib.ee_profile_enable.argtypes = [_V, C.c_int]
 _lib.ee_profile_read.argtypes = [_V, _V, _V]
 _lib.ee_profile_reserve.argtypes = [_V, C.c_int64]
@@ -227,6 +231,22 @@ class Engine:
     def config_table(self, layer):
         buf = (C.c_int * 16)()
         n = _lib.ee_config_table(self._h, int(layer), buf, 16)
+        if n < 0:
+            _chk(n)
+        return list(buf)[:n]
+
+    def pair_count(self):
+        n = _lib.ee_pair_count(self._h)
+        if n < 0:
+            _chk(n)
+        return n
+
+    def pair_mode(self, mode):
+        _chk(_lib.ee_pair_mode(self._h, int(mode)))
+
+    def pair_table(self, layer):
+        buf = (C.c_int * 16)()
+        n = _lib.ee_pair_table(self._h, int(layer), buf, 16)
         if n < 0:
             _chk(n)
         return list(buf)[:n]

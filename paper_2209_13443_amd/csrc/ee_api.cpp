@@ -158,6 +158,9 @@ void plan_buffers(ee_ctx* ctx)
             const OpDesc& d = ctx->plans[st.first_op + k].d;
             last_use[d.src] = k;
             if (d.res >= 0) last_use[d.res] = k;
+            // the head of a fused pair: the one launch reads this layer's input while it writes the next layer's
+            // output, so the input's buffer must stay reserved over both
+            if (k > 0 && ctx->plans[st.first_op + k - 1].pair) last_use[ctx->plans[st.first_op + k - 1].d.src] = k;
         }
         buf[0] = BUF_EXT_IN;
         buf[st.out_tensor] = BUF_EXT_OUT;
@@ -184,8 +187,8 @@ void plan_buffers(ee_ctx* ctx)
             p.dst_buf = buf[d.dst];
             p.res_buf = d.res >= 0 ? buf[d.res] : -3;
             // release tensors whose last reader was this op (the destination is never released here)
-            for (int t : {d.src, d.res})
-                if (t > 0 && buf[t] >= 0 && last_use[t] == k) in_use[buf[t]] = 0;
+            for (int t = 1; t < st.n_tensors; ++t)
+                if (t != d.dst && buf[t] >= 0 && last_use[t] == k) in_use[buf[t]] = 0;
         }
     }
 }
@@ -267,6 +270,21 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
         }
         if (p.ci_eff == 0) p.ci_eff = d.c_in;
     }
+    // layer pairs one fused launch can take: a matrix-core convolution without residual whose output is read by
+    // exactly one layer, the next one, and that one is a 1x1 stride-1 matrix-core convolution
+    for (const StageDesc& st : ctx->net.stages)
+        for (int k = 0; k + 1 < st.n_ops; ++k) {
+            OpPlan& p = ctx->plans[st.first_op + k];
+            const OpPlan& q = ctx->plans[st.first_op + k + 1];
+            if (p.impl != IMPL_MFMA || q.impl != IMPL_MFMA || p.d.res >= 0 || p.d.dst == st.out_tensor) continue;
+            if (q.d.src != p.d.dst || q.d.res == p.d.dst || q.d.kh != 1 || q.d.kw != 1 || q.d.stride != 1 || q.d.pad != 0) continue;
+            int readers = 0;
+            for (int j = 0; j < st.n_ops; ++j) {
+                const OpDesc& o = ctx->plans[st.first_op + j].d;
+                readers += (o.src == p.d.dst) + (o.res == p.d.dst);
+            }
+            p.pair = readers == 1 && conv_pair_supported(es, p.d.c_out, p.d.kh, p.d.kw, p.ci_eff, q.d.c_out);
+        }
     plan_buffers(ctx);
     ctx->pool.resize(ctx->pool_sample_bytes.size(), nullptr);
     for (size_t i = 0; i < ctx->pool.size(); ++i)
@@ -345,30 +363,48 @@ extern "C" int ee_query(const ee_ctx* ctx, int* n_stages, int64_t* in_bytes, int
 }
 
 // ---- one convolution on the matrix cores -----------------------------------------------------------
-hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg)
+void ee_ctx::fill_conv_args(int op, int b, ConvArgs& a) const
 {
     const OpPlan& p = plans[op];
     const OpDesc& d = p.d;
-    const int dt = net.dtype;
-    ConvArgs a{};
-    a.w = p.w_dev; a.bias = p.b_dev; a.res = res; a.y = dst; a.zeros = zero_page;
+    a.w = p.w_dev; a.bias = p.b_dev; a.zeros = zero_page;
     a.magic_howo = (unsigned)(0x100000000ull / (unsigned)(d.h_out * d.w_out) - (d.h_out * d.w_out == 1));
     a.magic_wo = (unsigned)(0x100000000ull / (unsigned)d.w_out - (d.w_out == 1));
     a.M = b * d.h_out * d.w_out; a.H = d.h_in; a.W = d.w_in; a.Ci = p.ci_eff; a.Ho = d.h_out; a.Wo = d.w_out; a.Co = d.c_out;
     a.kh = d.kh; a.kw = d.kw; a.stride = d.stride; a.pad = d.pad; a.Kp = p.Kp;
     if (p.impl == IMPL_MFMA_S2D) {      // the folded tensor: ks2 x ks2 kernel, stride 1, padding already inside
-        src = pad_bufs[p.pad_buf];
         a.H = p.Hp; a.W = p.Wp; a.kh = a.kw = p.kwp; a.stride = 1; a.pad = 0;
     }
     for (int r = 0; r < a.kh && r * a.kw < 32; ++r) a.tap_rows |= 1u << (r * a.kw);
     a.shift = d.shift; a.res_shift = d.res_shift; a.lo = d.lo; a.hi = d.hi; a.f_lo = d.f_lo; a.f_hi = d.f_hi;
-    if (p.impl == IMPL_MFMA_CPAD) src = pad_bufs[p.pad_buf];
+}
+
+hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg)
+{
+    const OpPlan& p = plans[op];
+    const int dt = net.dtype;
+    ConvArgs a{};
+    fill_conv_args(op, b, a);
+    a.res = res; a.y = dst;
+    if (p.impl == IMPL_MFMA_S2D || p.impl == IMPL_MFMA_CPAD) src = pad_bufs[p.pad_buf];
     if (p.impl == IMPL_MFMA_C4) {
         a.x = pad_bufs[p.pad_buf]; a.mode = 1; a.Hp = p.Hp; a.Wp = p.Wp; a.kwp = p.kwp;
         return dt == EE_I8 ? launch_conv_mfma_i8(a, stream) : launch_conv_mfma_bf16(a, stream);
     }
     a.x = src; a.mode = 0;
     return dt == EE_I8 ? launch_conv_igemm<1>(a, cfg, stream) : launch_conv_igemm<2>(a, cfg, stream);
+}
+
+hipError_t ee_ctx::launch_pair(int op, int b, const void* src, void* dst, const void* res, int cfg)
+{
+    const OpPlan& q = plans[op + 1];
+    PairArgs pa{};
+    fill_conv_args(op, b, pa.c2);
+    pa.c2.x = src; pa.c2.mode = 0;
+    pa.w3 = q.w_dev; pa.bias3 = q.b_dev; pa.res = res; pa.y = dst;
+    pa.Co3 = q.d.c_out; pa.Kp3 = q.Kp;
+    pa.shift = q.d.shift; pa.res_shift = q.d.res_shift; pa.lo = q.d.lo; pa.hi = q.d.hi; pa.f_lo = q.d.f_lo; pa.f_hi = q.d.f_hi;
+    return net.dtype == EE_I8 ? launch_conv_pair<1>(pa, cfg, stream) : launch_conv_pair<2>(pa, cfg, stream);
 }
 
 // ---- per-(layer, B_act) kernel configuration table ----------------------------------------------------
@@ -387,6 +423,7 @@ extern "C" int ee_autotune(ee_ctx* ctx, int reps)
     int rc = EE_OK;
     std::vector<int> buckets;
     for (int k = 0; (1 << k) < 2 * ctx->b_max; ++k) buckets.push_back(std::min(1 << k, ctx->b_max));
+    std::vector<std::vector<float>> best_time(ctx->plans.size());       // per layer and bucket: ms of `reps` launches of the best configuration
     for (size_t s = 0; s < ctx->net.stages.size() && !rc; ++s) {
         const StageDesc& st = ctx->net.stages[s];
         for (int k = 0; k < st.n_ops && !rc; ++k) {
@@ -398,8 +435,9 @@ extern "C" int ee_autotune(ee_ctx* ctx, int reps)
             const void* res = d.res >= 0 ? resolve(ctx, p.res_buf, ctx->in_buf[s], ctx->out_buf[s]) : nullptr;
             const int kbytes = (p.impl == IMPL_MFMA_S2D ? p.kwp * p.kwp : d.kh * d.kw) * p.ci_eff * es;
             std::vector<int> best(buckets.size(), 0);
+            best_time[st.first_op + k].assign(buckets.size(), 1e30f);
             for (size_t bi = 0; bi < buckets.size() && !rc; ++bi) {
-                float best_ms = 1e30f;
+                float& best_ms = best_time[st.first_op + k][bi];
                 for (int tile = 1; tile <= 4; ++tile)
                     for (int ksel = 1; ksel <= 3; ++ksel)
                         for (int ns = 2; ns <= 4; ++ns)
@@ -422,6 +460,36 @@ extern "C" int ee_autotune(ee_ctx* ctx, int reps)
             }
             if (!rc) p.cfg = best;
         }
+        // fused pairs: every configuration of the fused kernel against the two best separate kernels
+        for (int k = 0; k + 1 < st.n_ops && !rc; ++k) {
+            OpPlan& p = ctx->plans[st.first_op + k];
+            if (!p.pair) continue;
+            const OpPlan& q = ctx->plans[st.first_op + k + 1];
+            const void* src = resolve(ctx, p.src_buf, ctx->in_buf[s], ctx->out_buf[s]);
+            void* dst = resolve(ctx, q.dst_buf, ctx->in_buf[s], ctx->out_buf[s]);
+            const void* res = q.d.res >= 0 ? resolve(ctx, q.res_buf, ctx->in_buf[s], ctx->out_buf[s]) : nullptr;
+            std::vector<int> best(buckets.size(), 0);
+            for (size_t bi = 0; bi < buckets.size() && !rc; ++bi) {
+                float best_ms = best_time[st.first_op + k][bi] + best_time[st.first_op + k + 1][bi];
+                for (int tile = 1; tile <= 2; ++tile)
+                    for (int ksel = 1; ksel <= 2; ++ksel)
+                        for (int ns = 2; ns <= 4; ++ns) {
+                            const int cfg = tile | (ksel << 4) | (ns << 8);
+                            if (ctx->launch_pair(st.first_op + k, buckets[bi], src, dst, res, cfg) != hipSuccess) {
+                                (void)hipGetLastError();
+                                continue;
+                            }
+                            hipEventRecord(e0, ctx->stream);
+                            for (int r = 0; r < reps; ++r) ctx->launch_pair(st.first_op + k, buckets[bi], src, dst, res, cfg);
+                            hipEventRecord(e1, ctx->stream);
+                            if (hipEventSynchronize(e1) != hipSuccess) { rc = EE_ERR_DEVICE; break; }
+                            float ms = 0.f;
+                            hipEventElapsedTime(&ms, e0, e1);
+                            if (ms < best_ms) { best_ms = ms; best[bi] = cfg; }
+                        }
+            }
+            if (!rc) p.pair_cfg = best;
+        }
     }
     hipEventDestroy(e0);
     hipEventDestroy(e1);
@@ -436,6 +504,31 @@ extern "C" int ee_config_table(const ee_ctx* ctx, int op, int* cfg_out, int n)
     const std::vector<int>& c = ctx->plans[op].cfg;
     for (int i = 0; i < n && i < (int)c.size(); ++i) cfg_out[i] = c[i];
     return (int)c.size();
+}
+
+/* the fused-pair table of layer `op` (one entry per batch bucket, 0 = the two layers run separately); returns the entry
+   count, 0 when the layer heads no pair or nothing was tuned */
+extern "C" int ee_pair_table(const ee_ctx* ctx, int op, int* cfg_out, int n)
+{
+    if (!ctx || op < 0 || op >= (int)ctx->plans.size() || n < 0 || (n > 0 && !cfg_out)) return EE_ERR_ARG;
+    const std::vector<int>& c = ctx->plans[op].pair_cfg;
+    for (int i = 0; i < n && i < (int)c.size(); ++i) cfg_out[i] = c[i];
+    return (int)c.size();
+}
+
+extern "C" int ee_pair_mode(ee_ctx* ctx, int mode)
+{
+    if (!ctx || mode < 0 || mode > 2) return EE_ERR_ARG;
+    ctx->pair_mode = mode;
+    return EE_OK;
+}
+
+extern "C" int ee_pair_count(const ee_ctx* ctx)
+{
+    if (!ctx) return EE_ERR_ARG;
+    int n = 0;
+    for (const OpPlan& p : ctx->plans) n += p.pair;
+    return n;
 }
 
 // ---- one backbone segment ------------------------------------------------------------------------
@@ -470,6 +563,22 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                 if (e != hipSuccess) return EE_ERR_DEVICE;
             }
             int cfg = forced_conv_tile();
+            if (p.pair && pair_mode > 0 && cfg == 0) {
+                // this layer and the next as one launch, unless the table says the two separate kernels are faster here
+                const int pc = p.pair_cfg.empty() ? 0 : p.pair_cfg[std::min<size_t>(bucket_of(b), p.pair_cfg.size() - 1)];
+                // untuned: fused below 32 samples, where it was measured to win (one launch fewer counts most there)
+                if ((p.pair_cfg.empty() && b < 32) || pc != 0 || pair_mode == 2) {
+                    const OpPlan& q = plans[st.first_op + k + 1];
+                    void* dst2 = resolve(this, q.dst_buf, act_in, act_out);
+                    const void* res2 = q.d.res >= 0 ? resolve(this, q.res_buf, act_in, act_out) : nullptr;
+                    const double mid = 2.0 * d.h_out * d.w_out * d.c_out * es * b;      // the tensor that stays on chip
+                    e = timed(EE_K_CONV_MFMA, ops + q.ops_per_sample * b, bytes + q.bytes_per_sample * b + q.weight_bytes - mid,
+                              [&] { return launch_pair(st.first_op + k, b, src, dst2, res2, pc); }, st.first_op + k);
+                    if (e != hipSuccess) return EE_ERR_DEVICE;
+                    ++k;                                                             // the next layer is done
+                    continue;
+                }
+            }
             if (cfg == 0 && !p.cfg.empty()) cfg = p.cfg[std::min<size_t>(bucket_of(b), p.cfg.size() - 1)];
             const int cls = p.impl == IMPL_MFMA_C4 ? EE_K_CONV_FIRST : EE_K_CONV_MFMA;
             e = timed(cls, ops, bytes, [&] { return launch_conv(st.first_op + k, b, src, dst, res, cfg); }, st.first_op + k);

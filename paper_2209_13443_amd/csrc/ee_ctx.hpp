@@ -23,6 +23,8 @@ struct OpPlan {
     // IMPL_MFMA_S2D: stride-2 first layer over <= 4 channels, run as a stride-1 convolution with a ks2 x ks2 kernel over the
     // zero-padded image folded into Hp x Wp super-pixels of 2 x 2 pixels x 4 channels (Hp, Wp, ks2 reuse the fields above)
     std::vector<int> cfg;       // kernel configuration per batch bucket (see ee_autotune); empty = by shape
+    bool pair = false;          // this layer and the next one (a 1x1 layer that alone reads it) can run as one fused launch
+    std::vector<int> pair_cfg;  // per batch bucket: configuration of the fused launch, 0 = run the two layers separately; empty = not tuned
     double ops_per_sample = 0, bytes_per_sample = 0, weight_bytes = 0;
 };
 
@@ -56,6 +58,7 @@ struct ee_ctx {
     unsigned seq = 0;                            // last sequence value handed to an exit head
     unsigned* d_arrive = nullptr;                // device counter of exit-head workgroups that have finished
     int ids_turn = 0;
+    int pair_mode = 1;                           // fused layer pairs: 0 never, 1 as the table says, 2 wherever possible
     // kernel timing
     bool profiling = false;
     std::vector<ee::ProfRec> prof;
@@ -87,6 +90,9 @@ struct ee_ctx {
     }
     // launches layer `op` (an index into plans) on b samples with the given kernel configuration (0 = by shape)
     hipError_t launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg);
+    // layers op and op + 1 as one fused launch: src feeds layer op, res and dst belong to layer op + 1
+    hipError_t launch_pair(int op, int b, const void* src, void* dst, const void* res, int cfg);
+    void fill_conv_args(int op, int b, ee::ConvArgs& a) const;
     static int bucket_of(int b) { int k = 0; while ((1 << k) < b) ++k; return k; }     // smallest k with 2^k >= b
     // to_host: also write the outcomes to h_out and store ++seq to h_seq when they are all there
     int run_head(int stage, int b_act, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag,

@@ -63,6 +63,16 @@ struct ConvArgs {
     float f_lo, f_hi;
 };
 
+// Two chained convolutions in one launch (kernels_pair.hip): c2 is the first layer (its y and res are unused, its
+// output stays on chip), the rest describes the 1x1 layer that reads it.
+struct PairArgs {
+    ConvArgs c2;
+    const void* w3; const void* bias3; const void* res; void* y;
+    int Co3, Kp3;        // second layer: output channels, weight row pitch in elements
+    int shift, res_shift, lo, hi;
+    float f_lo, f_hi;
+};
+
 struct DirectConvArgs {   // one thread per output element; any shape (correctness fallback)
     const void* x; const void* w; const void* bias; const void* res; void* y;
     int M, H, W, Ci, Ho, Wo, Co, kh, kw, stride, pad, shift, res_shift, lo, hi;
@@ -81,6 +91,9 @@ hipError_t launch_conv_mfma_i8(const ConvArgs& a, hipStream_t s);
 hipError_t launch_conv_mfma_bf16(const ConvArgs& a, hipStream_t s);
 // asynchronous-copy implicit GEMM (ES = element bytes); tile 0 = chosen by shape, 1..4 forced
 template <int ES> hipError_t launch_conv_igemm(const ConvArgs& a, int tile, hipStream_t s);
+// the fused pair (ES = element bytes); cfg 0 = chosen by shape
+template <int ES> hipError_t launch_conv_pair(const PairArgs& p, int cfg, hipStream_t s);
+bool conv_pair_supported(int es, int co2, int kh, int kw, int ci, int co3);
 int forced_conv_tile();
 hipError_t launch_conv_direct(const DirectConvArgs& a, int dtype, hipStream_t s);
 hipError_t launch_pad_input(const void* x, void* y, int B, int H, int W, int C, int Hp, int Wp, int pad, int dtype, hipStream_t s);

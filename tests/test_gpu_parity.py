@@ -255,6 +255,39 @@ def test_full_size_sampled_parity(torch, ee, orc, case):
     eng.close()
 
 
+# ---- fused layer pairs (conv2 -> conv3 of a bottleneck block in one launch) ------------------------------
+@pytest.mark.parametrize("case", [("resnet50_i8", 5), ("resnet50_i8", 64), ("resnet50_bf16", 3), ("resnet50_bf16", 40)])
+def test_fused_pairs_equal_separate_layers_and_oracle(torch, ee, orc, case):
+    """Every segment of the ResNet-50-style network with all pairs fused against the same segment with none fused
+    (same arithmetic, so equal bit for bit in both dtypes), at a batch with ragged tiles and at a full one; the
+    fused first segment also against the oracle on sampled slots."""
+    name, b = case
+    say(f"[case] fused pairs {name} b={b}")
+    blob = W.load_net(name)
+    eng = ee.Engine(blob, b)
+    # conv2 -> conv3 of the 3 + 4 + 6 blocks with up to 256 mid channels; in bf16 the 256-channel pairs do not fit LDS
+    assert eng.pair_count() == (13 if blob.dtype == W.DT_I8 else 7)
+    pool = W.input_pool(blob, b)
+    act = dev(torch, pool)
+    for s in range(blob.n_stages):
+        say(f"[case] fused pairs {name} b={b} segment {s}")
+        eng.pair_mode(0)
+        ref = eng.stage_forward(s, act, blob.stage_out_shape(s))
+        eng.pair_mode(2)
+        got = eng.stage_forward(s, act, blob.stage_out_shape(s))
+        assert torch.equal(got, ref), f"segment {s}"
+        if s == 0:
+            slots = sorted({0, b // 2, b - 1})
+            want = orc.stage_forward(blob, 0, pool[slots])
+            if blob.dtype == W.DT_I8:
+                assert np.array_equal(host(got, want)[slots], want)
+            else:
+                r, g = bf16_to_f32(want).astype(np.float64), bf16_to_f32(host(got, want)[slots]).astype(np.float64)
+                assert np.abs(g - r).max() <= 2e-2 * np.abs(r).max()
+        act = ref
+    eng.close()
+
+
 # ---- bf16 ---------------------------------------------------------------------------------------------
 def bf16_to_f32(a):
     return W.bf16_bits_to_f32(a)
