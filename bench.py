@@ -3,9 +3,11 @@
 
 A "step" is one pass of the whole path over one batch of synthetic requests: admission, the
 backbone segments on the matrix cores, the exit heads, compaction and slot refill, driven by the
-exit-aware preemptive scheduler on the wall clock.  The default workload is the ResNet-50-style
+exit-aware host scheduler on the wall clock.  The default workload is the ResNet-50-style
 int8 stream: 10,000 requests, Poisson arrivals at 1.2x the static-batch throughput measured in
-the same run, 64 batch slots refilled at the exit boundaries.
+the same run, 64 batch slots refilled at the exit boundaries.  The timed policy is the stage-pool
+refill (survivors of an exit wait in front of the next segment, segments run on full batches);
+the same trace under Algorithm 1 of the paper and under static batching is printed beside it.
 
 Prints ONE JSON line (see the keys below).  `--gpus N` with N > 1 is refused: this path is built
 and measured on one GPU only.
@@ -41,9 +43,9 @@ def measured_traffic(workload):
     return rec["hbm_bytes_per_launch"]
 
 WORKLOADS = {
-    "resnet50_i8_stream": dict(net="resnet50_i8", n=10000, b_max=64, refill=1, load=1.2, spikes=False),
-    "resnet50_bf16_stream": dict(net="resnet50_bf16", n=20000, b_max=256, refill=1, load=0.8, spikes=True),
-    "mobilenetv2_i8_refill": dict(net="mobilenetv2_i8", n=4096, b_max=64, refill=1, load=None, spikes=False),
+    "resnet50_i8_stream": dict(net="resnet50_i8", n=10000, b_max=64, refill=2, load=1.2, spikes=False),
+    "resnet50_bf16_stream": dict(net="resnet50_bf16", n=20000, b_max=256, refill=2, load=0.8, spikes=True),
+    "mobilenetv2_i8_refill": dict(net="mobilenetv2_i8", n=4096, b_max=64, refill=2, load=None, spikes=False),
     "resnet18_i8_static": dict(net="resnet18_i8", n=1024, b_max=32, refill=0, load=None, spikes=False),
     "tiny_i8": dict(net="tiny_i8", n=64, b_max=8, refill=1, load=None, spikes=False),
 }
@@ -127,22 +129,22 @@ def main():
     marker.sin_()
     value = args.steps * n / elapsed
 
-    # the same trace under the stage-pool policy (an extension: survivors wait in front of the next segment
-    # and segments run on full batches), outside the timed region above
-    pools = None
-    if refill == 1:
-        step(2)
+    # the same trace under the other refill policy (Algorithm 1 of the paper when the stage pools were timed, and
+    # the other way round), outside the timed region above
+    other = None
+    if refill in (1, 2):
+        step(3 - refill)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            res_p, st_p, _ = step(2)
+            res_o, st_o, _ = step(3 - refill)
         torch.cuda.synchronize()
-        lat_p = res_p["latency_ns"].astype(np.float64)
-        pools = dict(samples_per_s=round(args.steps * n / (time.perf_counter() - t0), 1),
-                     mean_batch_per_segment=[round(a / max(b, 1), 2) for a, b in zip(st_p["seg_samples"], st_p["seg_runs"])],
-                     latency_ms_mean=round(lat_p.mean() / 1e6, 3), latency_ms_p99=round(float(np.percentile(lat_p, 99)) / 1e6, 3),
-                     slo_violation_rate=round(float(np.mean(lat_p > t_slo_ns)), 4) if t_slo_ns >= 0 else None,
-                     same_exits=bool(np.array_equal(res_p["exit_idx"], res["exit_idx"])))
+        lat_o = res_o["latency_ns"].astype(np.float64)
+        other = dict(samples_per_s=round(args.steps * n / (time.perf_counter() - t0), 1),
+                     mean_batch_per_segment=[round(a / max(b, 1), 2) for a, b in zip(st_o["seg_samples"], st_o["seg_runs"])],
+                     latency_ms_mean=round(lat_o.mean() / 1e6, 3), latency_ms_p99=round(float(np.percentile(lat_o, 99)) / 1e6, 3),
+                     slo_violation_rate=round(float(np.mean(lat_o > t_slo_ns)), 4) if t_slo_ns >= 0 else None,
+                     preemptions=st_o["preemptions"], same_exits=bool(np.array_equal(res_o["exit_idx"], res["exit_idx"])))
 
     # Per-kernel durations: HIP events on the library's stream around every launch of one more step of
     # the same workload.  Bracketing each launch costs the stream its back-to-back dispatch (about a
@@ -192,13 +194,15 @@ def main():
         "metric": "samples/sec early-exit CNN stream (1 GPU)", "value": round(value, 1), "unit": "samples/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(elapsed / args.steps * 1e3, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-        "config": {"workload": args.workload, "requests": n, "b_max": b_max, "refill": refill, "min_incr": min_incr,
+        "config": {"workload": args.workload, "requests": n, "b_max": b_max, "refill": refill,
+                   "policy": ["static batches", "Algorithm 1", "stage pools"][refill], "min_incr": min_incr if refill == 1 else None,
                    "arrival": "poisson" if load else "all_at_t0", "arrival_rate_per_s": round(load * static_rate, 1) if load else None,
                    "clock": "wall", "t_slo_ms": args.t_slo_ms if args.t_slo_ms >= 0 else None},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "static_batch_samples_per_s": round(static_rate, 1),
-        "stage_pools": pools,
+        ("algorithm1" if refill == 2 else "stage_pools"): other,
+        "algorithm1_min_incr": min_incr if refill == 2 else None,
         "exit_counts": np.bincount(res["exit_idx"], minlength=eng.n_stages).tolist(),
         "mean_batch_per_segment": [round(a / max(b, 1), 2) for a, b in zip(st["seg_samples"], st["seg_runs"])],
         "mean_batch_per_segment_static": [round(a / max(b, 1), 2) for a, b in zip(st_static["seg_samples"], st_static["seg_runs"])],
