@@ -27,20 +27,32 @@ PEAK = {"i8": 5000.0, "bf16": 2500.0}          # dense MFMA peak of MI355X, TOP/
 HBM_PEAK = 8000.0                               # GB/s
 
 
+CONV_SOURCES = ("kernels_igemm.hip", "kernels_pair.hip", "igemm_device.hpp")
+
+
+def conv_sources_digest():
+    """sha256 over the sources of the matrix-core convolution kernels, in the order of CONV_SOURCES"""
+    import hashlib
+    h = hashlib.sha256()
+    for name in CONV_SOURCES:
+        with open(os.path.join(ROOT, "paper_2209_13443_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 def measured_traffic(workload):
     """HBM bytes per launch of the dominant kernel from the committed counter runs (profiles/traffic.json), or
-    None when there is no record for this workload or the kernel source has changed since it was taken."""
-    import hashlib
+    None when there is no record for this workload or the kernel sources have changed since it was taken."""
     try:
         with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
             rec = json.load(f).get(workload)
-        with open(os.path.join(ROOT, "paper_2209_13443_amd", "csrc", "kernels_igemm.hip"), "rb") as f:
-            digest = hashlib.sha256(f.read()).hexdigest()
+        digest = conv_sources_digest()
     except OSError:
         return None
     if not rec or rec.get("kernel_sha256") != digest:
         return None
     return rec["hbm_bytes_per_launch"]
+
 
 WORKLOADS = {
     "resnet50_i8_stream": dict(net="resnet50_i8", n=10000, b_max=64, refill=2, load=1.2, spikes=False),
@@ -64,6 +76,8 @@ def main():
                     help="serving policy of the timed steps: 0 model-level batching, 1 Algorithm 1, 2 stage pools (-1 = the workload's)")
     ap.add_argument("--load", type=float, default=0.0, help="arrival rate as a multiple of the static-batch throughput (0 = the workload's)")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples timed on the CPU oracle (0 = automatic, -1 = skip)")
+    ap.add_argument("--save-tables", default="", help="write the tuned kernel-configuration tables to this JSON file")
+    ap.add_argument("--load-tables", default="", help="load the kernel-configuration tables from this JSON file instead of tuning")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the extra step that brackets every kernel launch with HIP events")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -91,7 +105,14 @@ def main():
     del chunks
     torch.cuda.synchronize()
 
-    eng.autotune(reps=5)                               # design-time per-(layer, batch) kernel configuration table
+    if args.load_tables:                               # design-time per-(layer, batch) kernel configuration table
+        with open(args.load_tables) as f:
+            eng.load_tables(json.load(f))
+    else:
+        eng.autotune(reps=5)
+    if args.save_tables:
+        with open(args.save_tables, "w") as f:
+            json.dump(eng.tables(), f)
     lut = eng.measure_lut(reps=3)                      # design-time exit-level latency table
     min_incr = args.min_incr or max(1, b_max // 2)
 
@@ -165,6 +186,7 @@ def main():
                         unit="TOP/s" if dtype == "i8" else "TFLOP/s", frac=round(achieved / PEAK[dtype], 4), traffic=None,
                         launches=conv["launches"], avg_launch_us=round(conv["ms"] * 1e3 / conv["launches"], 2),
                         algorithmic_gops_per_launch=round(conv["ops"] / conv["launches"] / 1e9, 3),
+                        algorithmic_mb_per_launch=round(conv["bytes"] / conv["launches"] / 1e6, 3),
                         hbm_gbps_algorithmic=round(conv["bytes"] / (conv["ms"] * 1e-3) / 1e9, 1))
         roofline["traffic"] = measured_traffic(args.workload)
     kernels = {k: dict(launches=v["launches"], ms=round(v["ms"], 3),

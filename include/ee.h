@@ -180,6 +180,11 @@ int ee_tune_conv_tile(int tile);
  * wavefronts, 2 or 4: that many groups sharing the reduction of a tile.  EE_ERR_ARG for bad arguments. */
 int ee_autotune(ee_ctx* ctx, int reps);
 int ee_config_table(const ee_ctx* ctx, int layer, int* cfg_out, int n);
+/* Loads a stored table for layer `layer` (n <= 16 entries as ee_config_table returns them; n = 0 clears it):
+ * the table is design-time data, as the paper's look-up tables are.  EE_ERR_ARG for a layer that is not a
+ * matrix-core convolution or an entry outside the encoding; an entry that names a combination the library does
+ * not have makes the launch that would use it fail with EE_ERR_DEVICE. */
+int ee_config_set(ee_ctx* ctx, int layer, const int* cfg, int n);
 
 /* Fused layer pairs.  A matrix-core convolution without residual whose 64, 128 or 256 output channels are read by
  * one layer only, the next, a 1x1 stride-1 convolution (conv2 -> conv3 of a bottleneck block), can run as ONE
@@ -193,6 +198,8 @@ int ee_config_table(const ee_ctx* ctx, int layer, int* cfg_out, int n);
 int ee_pair_count(const ee_ctx* ctx);
 int ee_pair_mode(ee_ctx* ctx, int mode);
 int ee_pair_table(const ee_ctx* ctx, int layer, int* cfg_out, int n);
+/* Loads a stored fused-pair table (as ee_config_set; EE_ERR_ARG when `layer` heads no pair). */
+int ee_pair_set(ee_ctx* ctx, int layer, const int* cfg, int n);
 
 /* Host copy of the 256-entry table round(2^30 * 2^(-i/256)) used by the integer softmax. */
 const uint32_t* ee_exp2_table(void);

@@ -25,7 +25,7 @@ EVENT_DT = np.dtype([("t_ns", "<i8"), ("kind", "<i4"), ("stage", "<i4"), ("b", "
 SYMBOLS = ["ee_strerror", "ee_blob_check", "ee_create", "ee_destroy", "ee_query", "ee_stage_forward", "ee_exit_head",
            "ee_compact_refill", "ee_serve_stream", "ee_schedule_sim", "ee_measure_lut", "ee_profile_enable",
            "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_last_logits", "ee_profile_reserve", "ee_autotune", "ee_config_table",
-           "ee_pair_count", "ee_pair_mode", "ee_pair_table"]
+           "ee_pair_count", "ee_pair_mode", "ee_pair_table", "ee_config_set", "ee_pair_set"]
 
 
 class Trace(C.Structure):
@@ -71,6 +71,8 @@ _lib.ee_config_table.argtypes = [_V, C.c_int, _V, C.c_int]
 _lib.ee_pair_count.argtypes = [_V]
 _lib.ee_pair_mode.argtypes = [_V, C.c_int]
 _lib.ee_pair_table.argtypes = [_V, C.c_int, _V, C.c_int]
+_lib.ee_config_set.argtypes = [_V, C.c_int, _V, C.c_int]
+_lib.ee_pair_set.argtypes = [_V, C.c_int, _V, C.c_int]
 _lib.ee_profile_enable.argtypes = [_V, C.c_int]
 _lib.ee_profile_read.argtypes = [_V, _V, _V]
 _lib.ee_profile_reserve.argtypes = [_V, C.c_int64]
@@ -234,6 +236,28 @@ class Engine:
         if n < 0:
             _chk(n)
         return list(buf)[:n]
+
+    def tables(self):
+        """The tuned tables as plain data: {"config": {layer: [...]}, "pair": {layer: [...]}} (layers that have one)."""
+        out = {"config": {}, "pair": {}}
+        buf = (C.c_int * 16)()
+        layer = 0
+        while True:
+            n = _lib.ee_config_table(self._h, layer, buf, 16)
+            if n < 0:                                   # past the last layer
+                return out
+            if n:
+                out["config"][str(layer)] = list(buf)[:n]
+            n = _lib.ee_pair_table(self._h, layer, buf, 16)
+            if n > 0:
+                out["pair"][str(layer)] = list(buf)[:n]
+            layer += 1
+
+    def load_tables(self, tables):
+        for key, fn in (("config", _lib.ee_config_set), ("pair", _lib.ee_pair_set)):
+            for layer, cfg in tables.get(key, {}).items():
+                buf = (C.c_int * len(cfg))(*cfg)
+                _chk(fn(self._h, int(layer), buf, len(cfg)))
 
     def pair_count(self):
         n = _lib.ee_pair_count(self._h)

@@ -516,6 +516,33 @@ extern "C" int ee_pair_table(const ee_ctx* ctx, int op, int* cfg_out, int n)
     return (int)c.size();
 }
 
+// Loading a stored table (the paper builds its look-up tables once, at design time, and loads them at run time).
+extern "C" int ee_config_set(ee_ctx* ctx, int op, const int* cfg, int n)
+{
+    if (!ctx || op < 0 || op >= (int)ctx->plans.size() || n < 0 || n > 16 || (n > 0 && !cfg)) return EE_ERR_ARG;
+    OpPlan& p = ctx->plans[op];
+    if (p.impl != IMPL_MFMA && p.impl != IMPL_MFMA_CPAD && p.impl != IMPL_MFMA_S2D) return EE_ERR_ARG;
+    for (int i = 0; i < n; ++i) {
+        const int tile = cfg[i] & 15, ksel = (cfg[i] >> 4) & 15, ns = (cfg[i] >> 8) & 15, kspl = (cfg[i] >> 12) & 15;
+        if (cfg[i] < 0 || (cfg[i] >> 16) || tile > 4 || ksel > 3 || (ns != 0 && (ns < 2 || ns > 4)) || (kspl != 0 && kspl != 2 && kspl != 4)) return EE_ERR_ARG;
+    }
+    p.cfg.assign(cfg, cfg + n);
+    return EE_OK;
+}
+
+extern "C" int ee_pair_set(ee_ctx* ctx, int op, const int* cfg, int n)
+{
+    if (!ctx || op < 0 || op >= (int)ctx->plans.size() || n < 0 || n > 16 || (n > 0 && !cfg)) return EE_ERR_ARG;
+    OpPlan& p = ctx->plans[op];
+    if (!p.pair) return EE_ERR_ARG;
+    for (int i = 0; i < n; ++i) {
+        const int tile = cfg[i] & 15, ksel = (cfg[i] >> 4) & 15, ns = (cfg[i] >> 8) & 15;
+        if (cfg[i] < 0 || (cfg[i] >> 12) || tile > 2 || ksel > 2 || (ns != 0 && (ns < 2 || ns > 4))) return EE_ERR_ARG;
+    }
+    p.pair_cfg.assign(cfg, cfg + n);
+    return EE_OK;
+}
+
 extern "C" int ee_pair_mode(ee_ctx* ctx, int mode)
 {
     if (!ctx || mode < 0 || mode > 2) return EE_ERR_ARG;

@@ -112,6 +112,16 @@ def test_autotuned_configuration_table_keeps_results(torch, ee, orc):
                 got = host(eng.stage_forward(s, dev(torch, act), ref.shape[1:]), ref)
                 assert np.array_equal(got, ref)
                 act = ref
+        # the table is plain data: a second engine loads it and runs the same configurations
+        stored = eng.tables()
+        other = ee.Engine(blob, 12)
+        other.load_tables(stored)
+        assert other.tables() == stored
+        ref = orc.stage_forward(blob, 0, x)
+        assert np.array_equal(host(other.stage_forward(0, dev(torch, x), ref.shape[1:]), ref), ref)
+        with pytest.raises(ee.EEError):
+            other.load_tables({"config": {"0": [0x99]}})                    # tile 9 does not exist
+        other.close()
         eng.close()
 
 

@@ -63,6 +63,8 @@ def test_null_and_range_arguments_are_rejected_without_a_gpu(ee):
     assert lib.ee_pair_count(None) == ee.EE_ERR_ARG
     assert lib.ee_pair_mode(None, 1) == ee.EE_ERR_ARG
     assert lib.ee_pair_table(None, 0, None, 0) == ee.EE_ERR_ARG
+    assert lib.ee_config_set(None, 0, None, 0) == ee.EE_ERR_ARG
+    assert lib.ee_pair_set(None, 0, None, 0) == ee.EE_ERR_ARG
     assert lib.ee_compact_refill(None, 0, 1, None, None, None, None, None, None, None, 0, None, None) == ee.EE_ERR_ARG
     assert lib.ee_serve_stream(None, None, None, None, None, None, None, 0) == ee.EE_ERR_ARG
     assert lib.ee_query(None, None, None, None) == ee.EE_ERR_ARG
