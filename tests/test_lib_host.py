@@ -150,3 +150,29 @@ def test_timeline_example_through_the_library(ee):
     res, st, ev = ee.schedule_sim(2, arrivals, forced, 8, np.full((2, 8), 10, np.int64), t_slo_ns=35, max_events=64)
     assert [(int(e["t_ns"]), int(e["kind"]), int(e["stage"]), int(e["b"]), int(e["aux"])) for e in ev] == events
     assert [int(r["latency_ns"] + a) for r, a in zip(res, arrivals)] == [s[2] for s in samples]
+
+
+# ---- both schedulers against the oracle on generated cases ---------------------------------------------------
+from hypothesis import given, settings, strategies as st
+
+
+@settings(max_examples=120, deadline=None)
+@given(seed=st.integers(0, 2**31 - 1), n=st.integers(1, 90), n_stages=st.integers(1, 5), b_max=st.integers(1, 12),
+       refill=st.sampled_from([0, 1, 2]), slo_kind=st.sampled_from(["none", "tight", "loose"]), min_incr=st.integers(1, 6),
+       burst=st.booleans())
+def test_schedulers_match_oracle_on_generated_cases(ee, orc, seed, n, n_stages, b_max, refill, slo_kind, min_incr, burst):
+    """Random traces (Poisson or everything at once), exits, latency tables and SLOs: results, statistics and the whole
+    event log of the library's scheduler equal the oracle's, bit for bit, for all three policies."""
+    rng = np.random.default_rng(seed)
+    arrivals = np.zeros(n, np.int64) if burst else np.floor(np.cumsum(rng.exponential(rng.choice([5.0, 40.0, 300.0]), size=n))).astype(np.int64)
+    forced = rng.integers(0, n_stages, size=n).astype(np.int32)
+    lut = (rng.integers(20, 120, size=(n_stages, 1)) + np.arange(b_max)[None, :] * rng.integers(0, 9, size=(n_stages, 1))).astype(np.int64)
+    total = int(lut[:, -1].sum())
+    slo = {"none": -1, "tight": total // 2, "loose": 3 * total}[slo_kind]
+    a, sa, ea = orc.serve_stream(None, arrivals, None, b_max, lut, t_slo_ns=slo, min_incr=min_incr, refill=refill,
+                                 forced_exit=forced, n_stages=n_stages, max_events=8000)
+    b, sb, eb = ee.schedule_sim(n_stages, arrivals, forced, b_max, lut, t_slo_ns=slo, min_incr=min_incr, refill=refill, max_events=8000)
+    assert sa == sb
+    assert np.array_equal(ea, eb)
+    assert np.array_equal(a["exit_idx"], b["exit_idx"]) and np.array_equal(a["latency_ns"], b["latency_ns"])
+    assert np.array_equal(a["exit_idx"], forced)
