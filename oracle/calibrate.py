@@ -38,10 +38,11 @@ SPLITS = {
     "mobilenetv2_i8": (0.25, 0.25, 0.5), "mobilenetv2_small_i8": (0.25, 0.25, 0.5),
     "resnet50_i8": (0.2, 0.2, 0.3, 0.3), "resnet50_small_i8": (0.2, 0.2, 0.3, 0.3),
     "resnet50_bf16": (0.2, 0.2, 0.3, 0.3), "resnet50_small_bf16": (0.2, 0.2, 0.3, 0.3),
+    "resnet50_eq_i8": (0.2, 0.2, 0.3, 0.3),
     "zoo_i8": (0.35, 0.35, 0.3), "zoo_bf16": (0.35, 0.35, 0.3),
 }
 DEFAULT_N_CAL = {"tiny_i8": 64, "tiny_bf16": 64, "resnet18_i8": 96, "mobilenetv2_i8": 128, "resnet50_i8": 96,
-                 "resnet50_bf16": 64}
+                 "resnet50_bf16": 64, "resnet50_eq_i8": 96}
 CAL_SEED_OFF = 7     # calibration inputs come from their own pool, not from the served one
 N_SHIFT = 16         # samples used for the shift statistics
 

@@ -26,6 +26,20 @@ def test_blob_check_accepts_all_configs_and_rejects_broken_chain(orc):
     assert orc.blob_check(b) == orc.ERR_UNSUPPORTED
 
 
+def test_equidistant_exit_placement(orc):
+    """The variant with exits equidistant in work (Sec. IV, "Benchmarks"): same layers as the ResNet-50-style network,
+    segment ends at the block ends closest to quarters of the total multiply-accumulates."""
+    eq, ref = W.build_net("resnet50_eq_i8"), W.build_net("resnet50_i8")
+    assert orc.blob_check(eq) == orc.OK
+    keys = ("kind", "h_in", "w_in", "c_in", "h_out", "w_out", "c_out", "kh", "kw", "stride", "pad")
+    assert len(eq.ops) == len(ref.ops) and all(int(a[k]) == int(b[k]) for a, b in zip(eq.ops, ref.ops) for k in keys)
+    macs = lambda op: int(op["h_out"]) * int(op["w_out"]) * int(op["c_out"]) * int(op["kh"]) * int(op["kw"]) * int(op["c_in"]) * (int(op["kind"]) == 0)
+    per = [sum(macs(op) for op in eq.ops[int(st["first_op"]):int(st["first_op"]) + int(st["n_ops"])]) for st in eq.stages]
+    cum = np.cumsum(per) / sum(per)
+    assert np.all(np.abs(cum - np.array([0.25, 0.5, 0.75, 1.0])) < 0.04)
+    assert [eq.stage_out_shape(s) for s in range(4)] == [(28, 28, 512), (14, 14, 1024), (14, 14, 1024), (7, 7, 2048)]
+
+
 def test_stage_forward_is_the_composition_of_its_layers(orc, tiny):
     x = W.input_pool(tiny, 5)
     ops = tiny.stage_ops(0)

@@ -131,6 +131,30 @@ def _resnet50(dtype, in_hw=224, n_classes=1000, blocks=(3, 4, 6, 3)):
     return net
 
 
+def _resnet50_eq(dtype, in_hw=224, n_classes=1000, exits_after=(4, 8, 12, 16)):
+    """The same bottleneck backbone with its exits where the cumulative work crosses quarters of the total
+    (Sec. IV "Benchmarks": exits placed equidistantly in FLOPs) instead of at the ends of the four resolution
+    groups: after bottleneck blocks 4, 8, 12 and 16 (28 %, 53 %, 75 %, 100 % of the MACs: the closest block ends)."""
+    net = _Net(dtype, in_hw, in_hw, 3, n_classes)
+    t = _resnet_stem(net)
+    done = 0
+    for g, (mid, nblk) in enumerate(zip((64, 128, 256, 512), (3, 4, 6, 3))):
+        for b in range(nblk):
+            stride = 2 if (b == 0 and g > 0) else 1
+            short = t
+            if b == 0:
+                short = net.conv(t, 4 * mid, 1, stride, 0, act="linear")
+            u = net.conv(t, mid, 1, 1, 0)
+            u = net.conv(u, mid, 3, stride, 1)
+            t = net.conv(u, 4 * mid, 1, 1, 0, res=short)
+            done += 1
+            if done in exits_after:
+                net.end_stage(t)
+                if done != exits_after[-1]:
+                    t = net.begin_stage()
+    return net
+
+
 def _mobilenetv2(dtype, in_hw=224, n_classes=1000):
     net = _Net(dtype, in_hw, in_hw, 3, n_classes)
     cfg = [(1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2), (6, 96, 3, 1), (6, 160, 3, 2), (6, 320, 1, 1)]
@@ -194,6 +218,7 @@ CONFIGS = {
     "mobilenetv2_i8": (_mobilenetv2, DT_I8, 3),
     "resnet50_i8": (_resnet50, DT_I8, 4),
     "resnet50_bf16": (_resnet50, DT_BF16, 5),
+    "resnet50_eq_i8": (_resnet50_eq, DT_I8, 6),          # exits equidistant in work
     # reduced-size variants for fast tests (same layer types, smaller images / fewer classes)
     "tiny_bf16": (_tiny, DT_BF16, 11),
     "resnet18_small_i8": (lambda dt: _resnet18(dt, 64, 100), DT_I8, 12),
