@@ -77,16 +77,18 @@ def out_hw(h, w, k, stride, pad):
 
 
 # ---- int8 primitives ---------------------------------------------------------------
-def conv_acc_i8(x, wt, bias, stride, pad, toeplitz=False):
+def conv_acc_i8(x, wt, bias, stride, pad, toeplitz=False, pad_w=None):
+    """pad: rows of zero padding (top and bottom); pad_w: columns (default: the same)."""
     x, wt = _c(x, np.int8), _c(wt, np.int8)
     n, h, w, ci = x.shape
     co, kh, kw, ci2 = wt.shape
     assert ci == ci2
+    pad_w = pad if pad_w is None else pad_w
     bias = None if bias is None else _c(bias, np.int32)
-    ho, wo = (h + 2 * pad - kh) // stride + 1, (w + 2 * pad - kw) // stride + 1
+    ho, wo = (h + 2 * pad - kh) // stride + 1, (w + 2 * pad_w - kw) // stride + 1
     acc = np.empty((n, max(ho, 0), max(wo, 0), co), np.int32)
-    fn = lib().orc_conv_acc_i8_toeplitz if toeplitz else lib().orc_conv_acc_i8
-    _chk(fn(_p(x), n, h, w, ci, _p(wt), _p(bias), co, kh, kw, stride, pad, _p(acc)))
+    fn = lib().orc_conv_acc_i8_toeplitz_hw if toeplitz else lib().orc_conv_acc_i8_hw
+    _chk(fn(_p(x), n, h, w, ci, _p(wt), _p(bias), co, kh, kw, stride, pad, pad_w, _p(acc)))
     return acc
 
 
@@ -116,6 +118,15 @@ def maxpool_i8(x, k, stride, pad):
     ho, wo = out_hw(h, w, k, stride, pad)
     y = np.empty((n, ho, wo, c), np.int8)
     _chk(lib().orc_maxpool_i8(_p(x), n, h, w, c, k, stride, pad, _p(y)))
+    return y
+
+
+def avgpool_i8(x, k, stride, pad):
+    x = _c(x, np.int8)
+    n, h, w, c = x.shape
+    ho, wo = out_hw(h, w, k, stride, pad)
+    y = np.empty((n, ho, wo, c), np.int8)
+    _chk(lib().orc_avgpool_i8(_p(x), n, h, w, c, k, stride, pad, _p(y)))
     return y
 
 
@@ -154,16 +165,17 @@ def exp2_table():
 
 
 # ---- bf16 primitives -----------------------------------------------------------------
-def conv_bf16(x, wt, bias, stride, pad, res=None, f_lo=-np.inf, f_hi=np.inf):
+def conv_bf16(x, wt, bias, stride, pad, res=None, f_lo=-np.inf, f_hi=np.inf, pad_w=None):
     x, wt = _c(x, np.uint16), _c(wt, np.uint16)
     n, h, w, ci = x.shape
     co, kh, kw, _ = wt.shape
+    pad_w = pad if pad_w is None else pad_w
     bias = None if bias is None else _c(bias, np.float32)
     res = None if res is None else _c(res, np.uint16)
-    ho, wo = out_hw(h, w, kh, stride, pad)
+    ho, wo = (h + 2 * pad - kh) // stride + 1, (w + 2 * pad_w - kw) // stride + 1
     y = np.empty((n, ho, wo, co), np.uint16)
-    _chk(lib().orc_conv_bf16(_p(x), n, h, w, ci, _p(wt), _p(bias), co, kh, kw, stride, pad, _p(res),
-                             C.c_float(f_lo), C.c_float(f_hi), _p(y)))
+    _chk(lib().orc_conv_bf16_hw(_p(x), n, h, w, ci, _p(wt), _p(bias), co, kh, kw, stride, pad, pad_w, _p(res),
+                                C.c_float(f_lo), C.c_float(f_hi), _p(y)))
     return y
 
 
@@ -185,6 +197,15 @@ def maxpool_bf16(x, k, stride, pad):
     ho, wo = out_hw(h, w, k, stride, pad)
     y = np.empty((n, ho, wo, c), np.uint16)
     _chk(lib().orc_maxpool_bf16(_p(x), n, h, w, c, k, stride, pad, _p(y)))
+    return y
+
+
+def avgpool_bf16(x, k, stride, pad):
+    x = _c(x, np.uint16)
+    n, h, w, c = x.shape
+    ho, wo = out_hw(h, w, k, stride, pad)
+    y = np.empty((n, ho, wo, c), np.uint16)
+    _chk(lib().orc_avgpool_bf16(_p(x), n, h, w, c, k, stride, pad, _p(y)))
     return y
 
 

@@ -27,7 +27,7 @@ import numpy as np
 
 import oracle as O
 import workloads as W
-from workloads.blob import OP_CONV, OP_DWCONV, OP_MAXPOOL, DT_I8
+from workloads.blob import OP_CONV, OP_DWCONV, OP_MAXPOOL, OP_AVGPOOL, DT_I8
 
 CALIB_DIR = os.path.join(os.path.dirname(os.path.abspath(W.__file__)), "calib")
 
@@ -39,10 +39,11 @@ SPLITS = {
     "resnet50_i8": (0.2, 0.2, 0.3, 0.3), "resnet50_small_i8": (0.2, 0.2, 0.3, 0.3),
     "resnet50_bf16": (0.2, 0.2, 0.3, 0.3), "resnet50_small_bf16": (0.2, 0.2, 0.3, 0.3),
     "resnet50_eq_i8": (0.2, 0.2, 0.3, 0.3),
+    "inception_i8": (0.2, 0.2, 0.3, 0.3), "inception_small_i8": (0.2, 0.2, 0.3, 0.3), "inception_small_bf16": (0.2, 0.2, 0.3, 0.3),
     "zoo_i8": (0.35, 0.35, 0.3), "zoo_bf16": (0.35, 0.35, 0.3),
 }
 DEFAULT_N_CAL = {"tiny_i8": 64, "tiny_bf16": 64, "resnet18_i8": 96, "mobilenetv2_i8": 128, "resnet50_i8": 96,
-                 "resnet50_bf16": 64, "resnet50_eq_i8": 96}
+                 "resnet50_bf16": 64, "resnet50_eq_i8": 96, "inception_i8": 96}
 CAL_SEED_OFF = 7     # calibration inputs come from their own pool, not from the served one
 N_SHIFT = 16         # samples used for the shift statistics
 
@@ -103,15 +104,17 @@ def calibrate(name, n_cal=None, log=print):
         for op in blob.stage_ops(s):
             kind, src = int(op["kind"]), tens[int(op["src"])]
             res = tens[int(op["res"])] if int(op["res"]) >= 0 else None
-            stride, pad = int(op["stride"]), int(op["pad"])
+            stride, pad, pad_w = int(op["stride"]), int(op["pad"]), int(op["pad_w"])
             co, kh, kw, ci = int(op["c_out"]), int(op["kh"]), int(op["kw"]), int(op["c_in"])
             wt, bias = blob.op_weights(op)
             entry = dict(shift=0, res_shift=0)
             if kind == OP_MAXPOOL:
                 y = O.maxpool_i8(src, kh, stride, pad) if is_i8 else O.maxpool_bf16(src, kh, stride, pad)
+            elif kind == OP_AVGPOOL:
+                y = O.avgpool_i8(src, kh, stride, pad) if is_i8 else O.avgpool_bf16(src, kh, stride, pad)
             elif is_i8:
                 if kind == OP_CONV:
-                    acc = O.conv_acc_i8(src, wt.reshape(co, kh, kw, ci), bias, stride, pad)
+                    acc = O.conv_acc_i8(src, wt.reshape(co, kh, kw, ci), bias, stride, pad, pad_w=pad_w)
                 else:
                     acc = O.dwconv_acc_i8(src, wt.reshape(co, kh, kw), bias, stride, pad)
                 ns = min(N_SHIFT, acc.shape[0])
@@ -128,10 +131,16 @@ def calibrate(name, n_cal=None, log=print):
             else:
                 f_lo, f_hi = float(op["f_lo"]), float(op["f_hi"])
                 if kind == OP_CONV:
-                    y = O.conv_bf16(src, wt.reshape(co, kh, kw, ci), bias, stride, pad, res, f_lo, f_hi)
+                    y = O.conv_bf16(src, wt.reshape(co, kh, kw, ci), bias, stride, pad, res, f_lo, f_hi, pad_w=pad_w)
                 else:
                     y = O.dwconv_bf16(src, wt.reshape(co, kh, kw), bias, stride, pad, f_lo, f_hi)
-            tens[int(op["dst"])] = y
+            dst, c_off, c_tot = int(op["dst"]), int(op["c_off"]), int(op["c_tot"])
+            if c_tot == co:
+                tens[dst] = y
+            else:                                        # a channel slice of a concatenation tensor
+                if dst not in tens:
+                    tens[dst] = np.zeros(y.shape[:3] + (c_tot,), y.dtype)
+                tens[dst][..., c_off:c_off + co] = y
             rec["ops"].append(entry)
         out = tens[int(blob.stages[s]["out_tensor"])]
         e = blob.exits[s]

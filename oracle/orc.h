@@ -39,11 +39,17 @@ int orc_conv_acc_i8(const int8_t* x, int n, int h, int w, int ci, const int8_t* 
                     int co, int kh, int kw, int stride, int pad, int32_t* acc);
 int orc_conv_acc_i8_toeplitz(const int8_t* x, int n, int h, int w, int ci, const int8_t* wt,
                              const int32_t* bias, int co, int kh, int kw, int stride, int pad, int32_t* acc);
+/* the same two with `pad` rows and `pad_w` columns of zero padding (kernels that are not square) */
+int orc_conv_acc_i8_hw(const int8_t* x, int n, int h, int w, int ci, const int8_t* wt, const int32_t* bias,
+                       int co, int kh, int kw, int stride, int pad, int pad_w, int32_t* acc);
+int orc_conv_acc_i8_toeplitz_hw(const int8_t* x, int n, int h, int w, int ci, const int8_t* wt,
+                                const int32_t* bias, int co, int kh, int kw, int stride, int pad, int pad_w, int32_t* acc);
 int orc_dwconv_acc_i8(const int8_t* x, int n, int h, int w, int c, const int8_t* wt, const int32_t* bias,
                       int kh, int kw, int stride, int pad, int32_t* acc);
 int orc_requant_i8(const int32_t* acc, const int8_t* res, int64_t count, int shift, int res_shift,
                    int lo, int hi, int8_t* y);
 int orc_maxpool_i8(const int8_t* x, int n, int h, int w, int c, int k, int stride, int pad, int8_t* y);
+int orc_avgpool_i8(const int8_t* x, int n, int h, int w, int c, int k, int stride, int pad, int8_t* y);
 int orc_gap_i8(const int8_t* x, int n, int h, int w, int c, int gap_shift, int32_t* sums, int8_t* g);
 int orc_fc_i8(const int8_t* g, int n, int c, const int8_t* wfc, const int32_t* bfc, int n_cls, int32_t* a);
 int orc_softmax_top1_i8(const int32_t* a, int n, int n_cls, int frac_bits, int32_t* label, int64_t* score);
@@ -57,6 +63,10 @@ int orc_conv_bf16(const uint16_t* x, int n, int h, int w, int ci, const uint16_t
 int orc_dwconv_bf16(const uint16_t* x, int n, int h, int w, int c, const uint16_t* wt, const float* bias,
                     int kh, int kw, int stride, int pad, float f_lo, float f_hi, uint16_t* y);
 int orc_maxpool_bf16(const uint16_t* x, int n, int h, int w, int c, int k, int stride, int pad, uint16_t* y);
+int orc_avgpool_bf16(const uint16_t* x, int n, int h, int w, int c, int k, int stride, int pad, uint16_t* y);
+int orc_conv_bf16_hw(const uint16_t* x, int n, int h, int w, int ci, const uint16_t* wt, const float* bias,
+                     int co, int kh, int kw, int stride, int pad, int pad_w, const uint16_t* res, float f_lo, float f_hi,
+                     uint16_t* y);
 int orc_head_bf16(const uint16_t* x, int n, int h, int w, int c, const uint16_t* wfc, const float* bfc,
                   int n_cls, float logit_scale, float* logits, int32_t* label, float* conf);
 uint16_t orc_f32_to_bf16(float v);

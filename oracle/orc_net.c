@@ -20,6 +20,7 @@ typedef struct { int32_t first_op, n_ops, n_tensors, out_tensor, out_h, out_w, o
 typedef struct {
     int32_t kind, src, dst, res, h_in, w_in, c_in, h_out, w_out, c_out, kh, kw, stride, pad, shift, res_shift, lo, hi;
     float f_lo, f_hi; int64_t w_off, b_off;
+    int32_t pad_w, c_off, c_tot, reserved;   /* columns of padding; the op writes channels [c_off, c_off + c_out) of a c_tot-channel tensor */
 } blob_op;
 typedef struct {
     int32_t h, w, c, n_cls, gap_shift, frac_bits; float logit_scale, thr; int64_t w_off, b_off; char reserved[16];
@@ -31,14 +32,14 @@ typedef struct {
     const blob_header* hd; const blob_stage* st; const blob_op* op; const blob_exit* ex;
 } net_view;
 
-enum { KIND_CONV = 0, KIND_DWCONV = 1, KIND_MAXPOOL = 2 };
+enum { KIND_CONV = 0, KIND_DWCONV = 1, KIND_MAXPOOL = 2, KIND_AVGPOOL = 3 };
 
 static int view_blob(const void* blob, size_t bytes, net_view* v)
 {
     if (!blob || bytes < sizeof(blob_header)) return ORC_ERR_ARG;
     v->base = (const unsigned char*)blob; v->bytes = bytes;
     v->hd = (const blob_header*)blob;
-    if (memcmp(v->hd->magic, "EENETv1\0", 8) != 0 || v->hd->version != 1) return ORC_ERR_ARG;
+    if (memcmp(v->hd->magic, "EENETv2\0", 8) != 0 || v->hd->version != 2) return ORC_ERR_ARG;
     if (v->hd->dtype != 0 && v->hd->dtype != 1) return ORC_ERR_UNSUPPORTED;
     if ((size_t)v->hd->total_bytes > bytes || v->hd->n_stages <= 0 || v->hd->n_stages > 8 || v->hd->n_ops < 0) return ORC_ERR_ARG;
     v->st = (const blob_stage*)(v->base + v->hd->stages_off);
@@ -53,8 +54,9 @@ static void stage_in_shape(const net_view* v, int s, int* h, int* w, int* c)
     else { *h = v->st[s - 1].out_h; *w = v->st[s - 1].out_w; *c = v->st[s - 1].out_c; }
 }
 
-/* Shapes must chain: every op reads a tensor that exists with the dims it states, writes the
- * next new tensor id, and the stage output has the dims the stage record and exit head state. */
+/* Shapes must chain: every op reads a tensor that has been written with the dims it states and writes either a
+ * new tensor or a channel slice of a concatenation tensor; the stage output has the dims the stage record and
+ * the exit head state. */
 int orc_blob_check(const void* blob, size_t bytes)
 {
     net_view v;
@@ -64,31 +66,46 @@ int orc_blob_check(const void* blob, size_t bytes)
     for (int s = 0; s < v.hd->n_stages; ++s) {
         const blob_stage* st = &v.st[s];
         if (st->n_tensors < 1 || st->n_tensors > 256 || st->first_op < 0 || st->first_op + st->n_ops > v.hd->n_ops) return ORC_ERR_SHAPE;
-        int th[256], tw[256], tc[256];
+        int th[256], tw[256], tc[256], filled[256];    /* filled: channels written so far; 0 = not written yet */
+        static _Thread_local int sl_off[256][32], sl_len[256][32];   /* the slices written so far, per tensor */
+        int n_sl[256];
+        memset(filled, 0, sizeof filled);
+        memset(n_sl, 0, sizeof n_sl);
         stage_in_shape(&v, s, &th[0], &tw[0], &tc[0]);
-        int next = 1;
+        filled[0] = tc[0];
         for (int k = 0; k < st->n_ops; ++k) {
             const blob_op* o = &v.op[st->first_op + k];
-            if (o->src < 0 || o->src >= next || o->dst != next || next >= st->n_tensors) return ORC_ERR_SHAPE;
+            if (o->kind < 0 || o->kind > KIND_AVGPOOL) return ORC_ERR_UNSUPPORTED;
+            if (o->src < 0 || o->src >= st->n_tensors || o->dst < 1 || o->dst >= st->n_tensors || o->dst == o->src) return ORC_ERR_SHAPE;
+            if (filled[o->src] == 0 || filled[o->src] != tc[o->src]) return ORC_ERR_SHAPE;        /* read before it is complete */
             if (o->h_in != th[o->src] || o->w_in != tw[o->src] || o->c_in != tc[o->src]) return ORC_ERR_SHAPE;
-            if (o->stride <= 0 || o->kh <= 0 || o->kw <= 0 || o->pad < 0) return ORC_ERR_SHAPE;
-            if (o->h_out != (o->h_in + 2 * o->pad - o->kh) / o->stride + 1 || o->w_out != (o->w_in + 2 * o->pad - o->kw) / o->stride + 1)
+            if (o->stride <= 0 || o->kh <= 0 || o->kw <= 0 || o->pad < 0 || o->pad_w < 0) return ORC_ERR_SHAPE;
+            if (o->h_out != (o->h_in + 2 * o->pad - o->kh) / o->stride + 1 || o->w_out != (o->w_in + 2 * o->pad_w - o->kw) / o->stride + 1)
                 return ORC_ERR_SHAPE;
             if (o->h_out <= 0 || o->w_out <= 0 || o->c_out <= 0) return ORC_ERR_SHAPE;
-            if (o->kind != KIND_CONV && o->c_out != o->c_in) return ORC_ERR_SHAPE;
-            if (o->kind < 0 || o->kind > KIND_MAXPOOL) return ORC_ERR_UNSUPPORTED;
+            if (o->kind != KIND_CONV && (o->c_out != o->c_in || o->pad != o->pad_w || o->kh != o->kw)) return ORC_ERR_SHAPE;
+            if (o->c_off < 0 || o->c_tot < o->c_off + o->c_out) return ORC_ERR_SHAPE;
+            if (filled[o->dst] == 0) { th[o->dst] = o->h_out; tw[o->dst] = o->w_out; tc[o->dst] = o->c_tot; }
+            else if (th[o->dst] != o->h_out || tw[o->dst] != o->w_out || tc[o->dst] != o->c_tot || o->c_tot == o->c_out) return ORC_ERR_SHAPE;
+            for (int j = 0; j < n_sl[o->dst]; ++j)          /* slices of one tensor must not overlap */
+                if (o->c_off < sl_off[o->dst][j] + sl_len[o->dst][j] && sl_off[o->dst][j] < o->c_off + o->c_out) return ORC_ERR_SHAPE;
+            if (n_sl[o->dst] >= 32) return ORC_ERR_SHAPE;
+            sl_off[o->dst][n_sl[o->dst]] = o->c_off; sl_len[o->dst][n_sl[o->dst]] = o->c_out; n_sl[o->dst]++;
+            filled[o->dst] += o->c_out;
+            if (filled[o->dst] > o->c_tot) return ORC_ERR_SHAPE;
             if (o->res >= 0) {
-                if (o->kind != KIND_CONV || o->res >= next) return ORC_ERR_SHAPE;
+                if (o->kind != KIND_CONV || o->res >= st->n_tensors || o->c_tot != o->c_out || filled[o->res] == 0 || filled[o->res] != tc[o->res]) return ORC_ERR_SHAPE;
                 if (th[o->res] != o->h_out || tw[o->res] != o->w_out || tc[o->res] != o->c_out) return ORC_ERR_SHAPE;
             }
-            if (o->kind != KIND_MAXPOOL) {
+            if (o->kind == KIND_CONV || o->kind == KIND_DWCONV) {
                 const int64_t nw = (int64_t)o->c_out * o->kh * o->kw * (o->kind == KIND_DWCONV ? 1 : o->c_in);
                 if (o->w_off < v.hd->data_off || (size_t)(o->w_off + nw * esz) > bytes) return ORC_ERR_SHAPE;
                 if (o->b_off < v.hd->data_off || (size_t)(o->b_off + 4 * (int64_t)o->c_out) > bytes) return ORC_ERR_SHAPE;
             }
-            th[next] = o->h_out; tw[next] = o->w_out; tc[next] = o->c_out;
-            ++next;
         }
+        const int next = st->n_tensors;
+        for (int t = 0; t < st->n_tensors; ++t)
+            if (filled[t] == 0 || filled[t] != tc[t]) return ORC_ERR_SHAPE;                         /* every tensor is written, and completely */
         if (next != st->n_tensors || st->out_tensor < 0 || st->out_tensor >= next) return ORC_ERR_SHAPE;
         if (th[st->out_tensor] != st->out_h || tw[st->out_tensor] != st->out_w || tc[st->out_tensor] != st->out_c) return ORC_ERR_SHAPE;
         const blob_exit* e = &v.ex[s];
@@ -118,23 +135,30 @@ int orc_stage_forward(const void* blob, size_t bytes, int stage, int b_act, cons
     for (int k = 0; k < st->n_ops && rc == ORC_OK; ++k) {
         const blob_op* o = &v.op[st->first_op + k];
         const int64_t out_elems = (int64_t)b_act * o->h_out * o->w_out * o->c_out;
-        void* dst = (o->dst == st->out_tensor) ? act_out : malloc((size_t)(out_elems * esz));
+        const int64_t rows = (int64_t)b_act * o->h_out * o->w_out;
+        const int sliced = o->c_tot != o->c_out;
+        if (!tens[o->dst]) {                               /* first writer: the whole tensor, c_tot channels per pixel */
+            tens[o->dst] = (o->dst == st->out_tensor) ? act_out : malloc((size_t)(rows * o->c_tot * esz));
+            if (!tens[o->dst]) { rc = ORC_ERR_ARG; break; }
+        }
+        /* a slice is computed densely, then copied into its channels of the concatenation tensor */
+        void* dst = sliced ? malloc((size_t)(out_elems * esz)) : tens[o->dst];
         if (!dst) { rc = ORC_ERR_ARG; break; }
-        tens[o->dst] = dst;
         const void* src = tens[o->src];
         const void* res = o->res >= 0 ? tens[o->res] : NULL;
         const void* wt = v.base + o->w_off;
         const void* bs = v.base + o->b_off;
         if (v.hd->dtype == 0) {
             if (o->kind == KIND_MAXPOOL) {
-                if (o->kh != o->kw) { rc = ORC_ERR_UNSUPPORTED; break; }
                 rc = orc_maxpool_i8((const int8_t*)src, b_act, o->h_in, o->w_in, o->c_in, o->kh, o->stride, o->pad, (int8_t*)dst);
+            } else if (o->kind == KIND_AVGPOOL) {
+                rc = orc_avgpool_i8((const int8_t*)src, b_act, o->h_in, o->w_in, o->c_in, o->kh, o->stride, o->pad, (int8_t*)dst);
             } else {
                 acc = (int32_t*)realloc(acc, sizeof(int32_t) * (size_t)out_elems);
                 if (!acc) { rc = ORC_ERR_ARG; break; }
                 if (o->kind == KIND_CONV)
-                    rc = orc_conv_acc_i8((const int8_t*)src, b_act, o->h_in, o->w_in, o->c_in, (const int8_t*)wt, (const int32_t*)bs,
-                                         o->c_out, o->kh, o->kw, o->stride, o->pad, acc);
+                    rc = orc_conv_acc_i8_hw((const int8_t*)src, b_act, o->h_in, o->w_in, o->c_in, (const int8_t*)wt, (const int32_t*)bs,
+                                            o->c_out, o->kh, o->kw, o->stride, o->pad, o->pad_w, acc);
                 else
                     rc = orc_dwconv_acc_i8((const int8_t*)src, b_act, o->h_in, o->w_in, o->c_in, (const int8_t*)wt, (const int32_t*)bs,
                                            o->kh, o->kw, o->stride, o->pad, acc);
@@ -144,12 +168,20 @@ int orc_stage_forward(const void* blob, size_t bytes, int stage, int b_act, cons
         } else {
             if (o->kind == KIND_MAXPOOL)
                 rc = orc_maxpool_bf16((const uint16_t*)src, b_act, o->h_in, o->w_in, o->c_in, o->kh, o->stride, o->pad, (uint16_t*)dst);
+            else if (o->kind == KIND_AVGPOOL)
+                rc = orc_avgpool_bf16((const uint16_t*)src, b_act, o->h_in, o->w_in, o->c_in, o->kh, o->stride, o->pad, (uint16_t*)dst);
             else if (o->kind == KIND_CONV)
-                rc = orc_conv_bf16((const uint16_t*)src, b_act, o->h_in, o->w_in, o->c_in, (const uint16_t*)wt, (const float*)bs,
-                                   o->c_out, o->kh, o->kw, o->stride, o->pad, (const uint16_t*)res, o->f_lo, o->f_hi, (uint16_t*)dst);
+                rc = orc_conv_bf16_hw((const uint16_t*)src, b_act, o->h_in, o->w_in, o->c_in, (const uint16_t*)wt, (const float*)bs,
+                                      o->c_out, o->kh, o->kw, o->stride, o->pad, o->pad_w, (const uint16_t*)res, o->f_lo, o->f_hi, (uint16_t*)dst);
             else
                 rc = orc_dwconv_bf16((const uint16_t*)src, b_act, o->h_in, o->w_in, o->c_in, (const uint16_t*)wt, (const float*)bs,
                                      o->kh, o->kw, o->stride, o->pad, o->f_lo, o->f_hi, (uint16_t*)dst);
+        }
+        if (sliced) {
+            if (rc == ORC_OK)
+                for (int64_t r = 0; r < rows; ++r)
+                    memcpy((char*)tens[o->dst] + (r * o->c_tot + o->c_off) * esz, (const char*)dst + r * o->c_out * esz, (size_t)(o->c_out * esz));
+            free(dst);
         }
     }
     free(acc);

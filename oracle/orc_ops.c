@@ -17,12 +17,12 @@ static int fits_i32(int64_t v) { return v >= INT32_MIN && v <= INT32_MAX; }
  * matrix, (r,s,c) runs over its P columns, output channel o over the C columns of the
  * weight matrix.  Direct evaluation: the sum over P is written out per output element.
  * ------------------------------------------------------------------------------------- */
-int orc_conv_acc_i8(const int8_t* x, int n, int h, int w, int ci, const int8_t* wt, const int32_t* bias,
-                    int co, int kh, int kw, int stride, int pad, int32_t* acc)
+int orc_conv_acc_i8_hw(const int8_t* x, int n, int h, int w, int ci, const int8_t* wt, const int32_t* bias,
+                       int co, int kh, int kw, int stride, int pad, int pad_w, int32_t* acc)
 {
-    if (!x || !wt || !acc || n < 0 || h <= 0 || w <= 0 || ci <= 0 || co <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0)
+    if (!x || !wt || !acc || n < 0 || h <= 0 || w <= 0 || ci <= 0 || co <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0 || pad_w < 0)
         return ORC_ERR_ARG;
-    const int ho = (h + 2 * pad - kh) / stride + 1, wo = (w + 2 * pad - kw) / stride + 1;
+    const int ho = (h + 2 * pad - kh) / stride + 1, wo = (w + 2 * pad_w - kw) / stride + 1;
     if (ho <= 0 || wo <= 0) return ORC_ERR_SHAPE;
     int overflow = 0;
 #pragma omp parallel for collapse(2) reduction(| : overflow) schedule(static)
@@ -35,7 +35,7 @@ int orc_conv_acc_i8(const int8_t* x, int n, int h, int w, int ci, const int8_t* 
                         const int iy = y * stride + r - pad;
                         if (iy < 0 || iy >= h) continue;
                         for (int s = 0; s < kw; ++s) {
-                            const int ix = xo * stride + s - pad;
+                            const int ix = xo * stride + s - pad_w;
                             if (ix < 0 || ix >= w) continue;
                             const int8_t* xp = x + (((int64_t)b * h + iy) * w + ix) * ci;
                             const int8_t* wp = wt + (((int64_t)o * kh + r) * kw + s) * ci;
@@ -50,13 +50,20 @@ int orc_conv_acc_i8(const int8_t* x, int n, int h, int w, int ci, const int8_t* 
     return overflow ? ORC_ERR_OVERFLOW : ORC_OK;
 }
 
+/* square padding: `pad` rows and `pad` columns on every side */
+int orc_conv_acc_i8(const int8_t* x, int n, int h, int w, int ci, const int8_t* wt, const int32_t* bias,
+                    int co, int kh, int kw, int stride, int pad, int32_t* acc)
+{
+    return orc_conv_acc_i8_hw(x, n, h, w, ci, wt, bias, co, kh, kw, stride, pad, pad, acc);
+}
+
 /* Second, independent formulation: build the R x P Toeplitz (im2col) matrix of each sample
  * and the P x C weight matrix explicitly, then multiply them with a plain triple loop. */
-int orc_conv_acc_i8_toeplitz(const int8_t* x, int n, int h, int w, int ci, const int8_t* wt,
-                             const int32_t* bias, int co, int kh, int kw, int stride, int pad, int32_t* acc)
+int orc_conv_acc_i8_toeplitz_hw(const int8_t* x, int n, int h, int w, int ci, const int8_t* wt,
+                                const int32_t* bias, int co, int kh, int kw, int stride, int pad, int pad_w, int32_t* acc)
 {
     if (!x || !wt || !acc || n < 0) return ORC_ERR_ARG;
-    const int ho = (h + 2 * pad - kh) / stride + 1, wo = (w + 2 * pad - kw) / stride + 1;
+    const int ho = (h + 2 * pad - kh) / stride + 1, wo = (w + 2 * pad_w - kw) / stride + 1;
     if (ho <= 0 || wo <= 0) return ORC_ERR_SHAPE;
     const int64_t R = (int64_t)ho * wo, P = (int64_t)kh * kw * ci, C = co;
     int8_t* X = (int8_t*)malloc((size_t)(R * P));
@@ -70,7 +77,7 @@ int orc_conv_acc_i8_toeplitz(const int8_t* x, int n, int h, int w, int ci, const
             const int y = (int)(row / wo), xo = (int)(row % wo);
             for (int64_t p = 0; p < P; ++p) {
                 const int c = (int)(p % ci), s = (int)((p / ci) % kw), r = (int)(p / ((int64_t)ci * kw));
-                const int iy = y * stride + r - pad, ix = xo * stride + s - pad;
+                const int iy = y * stride + r - pad, ix = xo * stride + s - pad_w;
                 X[row * P + p] = (iy < 0 || iy >= h || ix < 0 || ix >= w) ? 0 : x[(((int64_t)b * h + iy) * w + ix) * ci + c];
             }
         }
@@ -84,6 +91,12 @@ int orc_conv_acc_i8_toeplitz(const int8_t* x, int n, int h, int w, int ci, const
     }
     free(X); free(W);
     return overflow ? ORC_ERR_OVERFLOW : ORC_OK;
+}
+
+int orc_conv_acc_i8_toeplitz(const int8_t* x, int n, int h, int w, int ci, const int8_t* wt,
+                             const int32_t* bias, int co, int kh, int kw, int stride, int pad, int32_t* acc)
+{
+    return orc_conv_acc_i8_toeplitz_hw(x, n, h, w, ci, wt, bias, co, kh, kw, stride, pad, pad, acc);
 }
 
 /* Depthwise: the same sum with output channel == input channel (P = kh*kw). */
@@ -153,6 +166,34 @@ int orc_maxpool_i8(const int8_t* x, int n, int h, int w, int c, int k, int strid
                             if (v > best) best = v;
                         }
                     y[(((int64_t)b * ho + yo) * wo + xo) * c + ch] = (int8_t)best;
+                }
+    return ORC_OK;
+}
+
+/* Average pool k x k: the sum over ALL k*k taps with padding counted as zero, divided by k*k and rounded half up
+ * (the divisor does not shrink at the border):  y = floor((2 * sum + k*k) / (2 * k*k)). */
+int orc_avgpool_i8(const int8_t* x, int n, int h, int w, int c, int k, int stride, int pad, int8_t* y)
+{
+    if (!x || !y || n < 0 || k <= 0 || k > 15 || stride <= 0 || pad < 0 || pad >= k) return ORC_ERR_ARG;
+    const int ho = (h + 2 * pad - k) / stride + 1, wo = (w + 2 * pad - k) / stride + 1;
+    if (ho <= 0 || wo <= 0) return ORC_ERR_SHAPE;
+    const int64_t kk = (int64_t)k * k;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < n; ++b)
+        for (int yo = 0; yo < ho; ++yo)
+            for (int xo = 0; xo < wo; ++xo)
+                for (int ch = 0; ch < c; ++ch) {
+                    int64_t sum = 0;
+                    for (int r = 0; r < k; ++r)
+                        for (int s = 0; s < k; ++s) {
+                            const int iy = yo * stride + r - pad, ix = xo * stride + s - pad;
+                            if (iy < 0 || iy >= h || ix < 0 || ix >= w) continue;
+                            sum += x[(((int64_t)b * h + iy) * w + ix) * c + ch];
+                        }
+                    const int64_t num = 2 * sum + kk, den = 2 * kk;          /* floor division, also for negative num */
+                    int64_t q = num / den;
+                    if (num % den != 0 && num < 0) --q;
+                    y[(((int64_t)b * ho + yo) * wo + xo) * c + ch] = (int8_t)q;  /* |q| <= 128 * ... / kk stays in range */
                 }
     return ORC_OK;
 }
@@ -268,12 +309,12 @@ static uint16_t finish_bf16(double accd, float bias, const uint16_t* res, int64_
     return orc_f32_to_bf16(v);
 }
 
-int orc_conv_bf16(const uint16_t* x, int n, int h, int w, int ci, const uint16_t* wt, const float* bias,
-                  int co, int kh, int kw, int stride, int pad, const uint16_t* res, float f_lo, float f_hi,
-                  uint16_t* y)
+int orc_conv_bf16_hw(const uint16_t* x, int n, int h, int w, int ci, const uint16_t* wt, const float* bias,
+                     int co, int kh, int kw, int stride, int pad, int pad_w, const uint16_t* res, float f_lo, float f_hi,
+                     uint16_t* y)
 {
-    if (!x || !wt || !y || n < 0 || stride <= 0) return ORC_ERR_ARG;
-    const int ho = (h + 2 * pad - kh) / stride + 1, wo = (w + 2 * pad - kw) / stride + 1;
+    if (!x || !wt || !y || n < 0 || stride <= 0 || pad < 0 || pad_w < 0) return ORC_ERR_ARG;
+    const int ho = (h + 2 * pad - kh) / stride + 1, wo = (w + 2 * pad_w - kw) / stride + 1;
     if (ho <= 0 || wo <= 0) return ORC_ERR_SHAPE;
 #pragma omp parallel for collapse(2) schedule(static)
     for (int b = 0; b < n; ++b)
@@ -285,7 +326,7 @@ int orc_conv_bf16(const uint16_t* x, int n, int h, int w, int ci, const uint16_t
                         const int iy = yo * stride + r - pad;
                         if (iy < 0 || iy >= h) continue;
                         for (int s = 0; s < kw; ++s) {
-                            const int ix = xo * stride + s - pad;
+                            const int ix = xo * stride + s - pad_w;
                             if (ix < 0 || ix >= w) continue;
                             const uint16_t* xp = x + (((int64_t)b * h + iy) * w + ix) * ci;
                             const uint16_t* wp = wt + (((int64_t)o * kh + r) * kw + s) * ci;
@@ -296,6 +337,13 @@ int orc_conv_bf16(const uint16_t* x, int n, int h, int w, int ci, const uint16_t
                     y[idx] = finish_bf16(sum, bias ? bias[o] : 0.0f, res, idx, f_lo, f_hi);
                 }
     return ORC_OK;
+}
+
+int orc_conv_bf16(const uint16_t* x, int n, int h, int w, int ci, const uint16_t* wt, const float* bias,
+                  int co, int kh, int kw, int stride, int pad, const uint16_t* res, float f_lo, float f_hi,
+                  uint16_t* y)
+{
+    return orc_conv_bf16_hw(x, n, h, w, ci, wt, bias, co, kh, kw, stride, pad, pad, res, f_lo, f_hi, y);
 }
 
 int orc_dwconv_bf16(const uint16_t* x, int n, int h, int w, int c, const uint16_t* wt, const float* bias,
@@ -344,6 +392,29 @@ int orc_maxpool_bf16(const uint16_t* x, int n, int h, int w, int c, int k, int s
                             if (!have || v > best) { best = v; bits = vb; have = 1; }
                         }
                     y[(((int64_t)b * ho + yo) * wo + xo) * c + ch] = bits;
+                }
+    return ORC_OK;
+}
+
+/* Average pool, float path: the taps are added in double (padding contributes zero), divided by k*k, rounded once to
+ * float and then to bf16. */
+int orc_avgpool_bf16(const uint16_t* x, int n, int h, int w, int c, int k, int stride, int pad, uint16_t* y)
+{
+    if (!x || !y || n < 0 || k <= 0 || stride <= 0 || pad < 0 || pad >= k) return ORC_ERR_ARG;
+    const int ho = (h + 2 * pad - k) / stride + 1, wo = (w + 2 * pad - k) / stride + 1;
+    if (ho <= 0 || wo <= 0) return ORC_ERR_SHAPE;
+    for (int b = 0; b < n; ++b)
+        for (int yo = 0; yo < ho; ++yo)
+            for (int xo = 0; xo < wo; ++xo)
+                for (int ch = 0; ch < c; ++ch) {
+                    double sum = 0.0;
+                    for (int r = 0; r < k; ++r)
+                        for (int s = 0; s < k; ++s) {
+                            const int iy = yo * stride + r - pad, ix = xo * stride + s - pad;
+                            if (iy < 0 || iy >= h || ix < 0 || ix >= w) continue;
+                            sum += (double)orc_bf16_to_f32(x[(((int64_t)b * h + iy) * w + ix) * c + ch]);
+                        }
+                    y[(((int64_t)b * ho + yo) * wo + xo) * c + ch] = orc_f32_to_bf16((float)(sum / (double)(k * k)));
                 }
     return ORC_OK;
 }

@@ -45,15 +45,16 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
 {
     const OpDesc& d = p.d;
     const int es = ctx->net.elem_bytes();
-    if (d.kind == OP_MAXPOOL) {
-        if ((d.c_in * es) % 16 != 0) return EE_ERR_UNSUPPORTED;
-        p.impl = IMPL_POOL;
+    if (d.kind == OP_MAXPOOL || d.kind == OP_AVGPOOL) {
+        // whole 16-byte chunks per pixel, also inside a concatenated output pixel
+        if ((d.c_in * es) % 16 != 0 || (d.c_tot * es) % 16 != 0 || (d.c_off * es) % 16 != 0) return EE_ERR_UNSUPPORTED;
+        p.impl = d.kind == OP_MAXPOOL ? IMPL_POOL : IMPL_AVGPOOL;
         return EE_OK;
     }
     const unsigned char* w = blob + d.w_off;
     const unsigned char* b = blob + d.b_off;
     if (d.kind == OP_DWCONV) {
-        if ((d.c_in * es) % 16 != 0 || d.kh != d.kw) return EE_ERR_UNSUPPORTED;
+        if ((d.c_in * es) % 16 != 0 || d.kh != d.kw || d.c_tot != d.c_out) return EE_ERR_UNSUPPORTED;
         p.impl = IMPL_DW;
         const int taps = d.kh * d.kw, C = d.c_in;
         std::vector<unsigned char> wp((size_t)taps * C * es);
@@ -94,7 +95,7 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
         for (int o = 0; o < Co; ++o)
             for (int t = 0; t < taps; ++t)
                 std::memcpy(&wp[((size_t)o * p.Kp + (size_t)t * cip) * es], w + ((size_t)o * taps + t) * Ci * es, (size_t)Ci * es);
-    } else if (Ci <= 4 && Co % 4 == 0 && d.stride == 2 && d.kh == d.kw && (d.kh + 1) / 2 * ((d.kh + 1) / 2) <= 31) {
+    } else if (Ci <= 4 && Co % 4 == 0 && d.stride == 2 && d.kh == d.kw && d.pad == d.pad_w && d.c_tot == Co && (d.kh + 1) / 2 * ((d.kh + 1) / 2) <= 31) {
         // stride-2 first layer: stride-1 convolution with a ceil(k/2)^2 kernel over the padded image folded into
         // super-pixels (dy, dx, c) of 2 x 2 pixels x 4 channels; weights W'[o][r'][s'][dy][dx][c] = W[o][2r'+dy][2s'+dx][c]
         p.impl = IMPL_MFMA_S2D;
@@ -112,7 +113,7 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
                         const size_t kidx = ((size_t)((r >> 1) * k2 + (s >> 1)) * 4 + (r & 1) * 2 + (s & 1)) * 4 + ch;
                         std::memcpy(&wp[((size_t)o * p.Kp + kidx) * es], w + ((((size_t)o * d.kh + r) * d.kw + s) * Ci + ch) * es, es);
                     }
-    } else if (Ci <= 4 && Co % 4 == 0) {
+    } else if (Ci <= 4 && Co % 4 == 0 && d.pad == d.pad_w && d.c_tot == Co) {
         // first layer: the input is copied into a zero-padded 4-channel image, a kernel row of kwp taps is
         // then kwp*4 contiguous elements; k index = (r * kwp + s) * 4 + c
         p.impl = IMPL_MFMA_C4;
@@ -170,7 +171,7 @@ void plan_buffers(ee_ctx* ctx)
             OpPlan& p = ctx->plans[st.first_op + k];
             const OpDesc& d = p.d;
             if (buf[d.dst] == -3) {
-                const size_t need = (size_t)d.h_out * d.w_out * d.c_out * es;
+                const size_t need = (size_t)d.h_out * d.w_out * d.c_tot * es;      // the whole tensor, also when this op writes a slice of it
                 int pick = -1;
                 for (size_t i = 0; i < in_use.size(); ++i)
                     if (!in_use[i]) { pick = (int)i; break; }
@@ -257,7 +258,7 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
         const OpDesc& d = p.d;
         const double out_e = (double)d.h_out * d.w_out * d.c_out, in_e = (double)d.h_in * d.w_in * d.c_in;
         const double kred = d.kind == OP_CONV ? (double)d.kh * d.kw * d.c_in : (double)d.kh * d.kw;
-        p.ops_per_sample = d.kind == OP_MAXPOOL ? 0.0 : 2.0 * out_e * kred;
+        p.ops_per_sample = d.kind == OP_MAXPOOL || d.kind == OP_AVGPOOL ? 0.0 : 2.0 * out_e * kred;
         p.bytes_per_sample = (in_e + out_e + (d.res >= 0 ? out_e : 0.0)) * es;
         if (p.impl == IMPL_MFMA_C4 || p.impl == IMPL_MFMA_CPAD || p.impl == IMPL_MFMA_S2D) {
             void* pb = nullptr;
@@ -277,6 +278,7 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
             OpPlan& p = ctx->plans[st.first_op + k];
             const OpPlan& q = ctx->plans[st.first_op + k + 1];
             if (p.impl != IMPL_MFMA || q.impl != IMPL_MFMA || p.d.res >= 0 || p.d.dst == st.out_tensor) continue;
+            if (p.d.c_tot != p.d.c_out || q.d.c_tot != q.d.c_out) continue;           // no channel slices
             if (q.d.src != p.d.dst || q.d.res == p.d.dst || q.d.kh != 1 || q.d.kw != 1 || q.d.stride != 1 || q.d.pad != 0) continue;
             int readers = 0;
             for (int j = 0; j < st.n_ops; ++j) {
@@ -371,9 +373,10 @@ void ee_ctx::fill_conv_args(int op, int b, ConvArgs& a) const
     a.magic_howo = (unsigned)(0x100000000ull / (unsigned)(d.h_out * d.w_out) - (d.h_out * d.w_out == 1));
     a.magic_wo = (unsigned)(0x100000000ull / (unsigned)d.w_out - (d.w_out == 1));
     a.M = b * d.h_out * d.w_out; a.H = d.h_in; a.W = d.w_in; a.Ci = p.ci_eff; a.Ho = d.h_out; a.Wo = d.w_out; a.Co = d.c_out;
-    a.kh = d.kh; a.kw = d.kw; a.stride = d.stride; a.pad = d.pad; a.Kp = p.Kp;
+    a.kh = d.kh; a.kw = d.kw; a.stride = d.stride; a.pad = d.pad; a.pad_w = d.pad_w; a.Kp = p.Kp;
+    a.ldc = d.c_tot; a.c_off = d.c_off;
     if (p.impl == IMPL_MFMA_S2D) {      // the folded tensor: ks2 x ks2 kernel, stride 1, padding already inside
-        a.H = p.Hp; a.W = p.Wp; a.kh = a.kw = p.kwp; a.stride = 1; a.pad = 0;
+        a.H = p.Hp; a.W = p.Wp; a.kh = a.kw = p.kwp; a.stride = 1; a.pad = a.pad_w = 0;
     }
     for (int r = 0; r < a.kh && r * a.kw < 32; ++r) a.tap_rows |= 1u << (r * a.kw);
     a.shift = d.shift; a.res_shift = d.res_shift; a.lo = d.lo; a.hi = d.hi; a.f_lo = d.f_lo; a.f_hi = d.f_hi;
@@ -611,11 +614,13 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
             e = timed(cls, ops, bytes, [&] { return launch_conv(st.first_op + k, b, src, dst, res, cfg); }, st.first_op + k);
         } else if (p.impl == IMPL_DIRECT) {
             DirectConvArgs a{src, p.w_dev, p.b_dev, res, dst, b * d.h_out * d.w_out, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.c_out,
-                             d.kh, d.kw, d.stride, d.pad, d.shift, d.res_shift, d.lo, d.hi, d.f_lo, d.f_hi};
+                             d.kh, d.kw, d.stride, d.pad, d.shift, d.res_shift, d.lo, d.hi, d.f_lo, d.f_hi, d.pad_w, d.c_tot, d.c_off};
             e = timed(EE_K_CONV_DIRECT, ops, bytes, [&] { return launch_conv_direct(a, dt, stream); }, st.first_op + k);
         } else {
-            PoolArgs a{src, p.w_dev, p.b_dev, dst, p.w3_dev, b, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.kh, d.stride, d.pad, d.shift, d.lo, d.hi, d.f_lo, d.f_hi};
+            PoolArgs a{src, p.w_dev, p.b_dev, dst, p.w3_dev, b, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.kh, d.stride, d.pad, d.shift, d.lo, d.hi, d.f_lo, d.f_hi,
+                       d.c_tot, d.c_off};
             if (p.impl == IMPL_DW) e = timed(EE_K_DEPTHWISE, ops, bytes, [&] { return launch_depthwise(a, dt, stream); }, st.first_op + k);
+            else if (p.impl == IMPL_AVGPOOL) e = timed(EE_K_MAXPOOL, 0.0, bytes, [&] { return launch_avgpool(a, dt, stream); }, st.first_op + k);   // timed with the pooling class
             else e = timed(EE_K_MAXPOOL, 0.0, bytes, [&] { return launch_maxpool(a, dt, stream); }, st.first_op + k);
         }
         if (e != hipSuccess) return EE_ERR_DEVICE;

@@ -11,15 +11,17 @@
 namespace ee {
 
 // ---- network description parsed from the blob ------------------------------------------------
-enum OpKind { OP_CONV = 0, OP_DWCONV = 1, OP_MAXPOOL = 2 };
+enum OpKind { OP_CONV = 0, OP_DWCONV = 1, OP_MAXPOOL = 2, OP_AVGPOOL = 3 };
 
 struct OpDesc {
     int kind, src, dst, res;
     int h_in, w_in, c_in, h_out, w_out, c_out;
-    int kh, kw, stride, pad;
+    int kh, kw, stride, pad;      // pad: rows of zero padding above and below
     int shift, res_shift, lo, hi;
     float f_lo, f_hi;
     int64_t w_off, b_off;
+    int pad_w;                    // columns of zero padding left and right
+    int c_off, c_tot;             // the op writes channels [c_off, c_off + c_out) of a tensor of c_tot channels (concatenation)
 };
 
 struct ExitDesc {
@@ -52,7 +54,9 @@ struct ConvArgs {
     const void* x; const void* w; const void* bias; const void* res; void* y;
     const void* zeros;   // >= 16 readable zero bytes: what padding taps and rows past the batch read
     int M, H, W, Ci, Ho, Wo, Co;
-    int kh, kw, stride, pad;
+    int kh, kw, stride, pad;   // pad: rows
+    int pad_w;           // columns of padding
+    int ldc, c_off;      // the output pixel has ldc channels, of which this layer writes [c_off, c_off + Co)
     int Kp;              // weight row pitch in elements (reduction length, zero padded)
     unsigned magic_howo, magic_wo;   // floor(2^32 / (Ho*Wo)), floor(2^32 / Wo): division by multiply-high
     unsigned tap_rows;   // bit r*kw set for every kernel row r (kh*kw <= 31)
@@ -77,6 +81,7 @@ struct DirectConvArgs {   // one thread per output element; any shape (correctne
     const void* x; const void* w; const void* bias; const void* res; void* y;
     int M, H, W, Ci, Ho, Wo, Co, kh, kw, stride, pad, shift, res_shift, lo, hi;
     float f_lo, f_hi;
+    int pad_w, ldc, c_off;
 };
 
 struct PoolArgs {         // depthwise 3x3 and max-pool share the shape block
@@ -84,6 +89,7 @@ struct PoolArgs {         // depthwise 3x3 and max-pool share the shape block
     const void* w3;      // int8 3x3 depthwise: weights packed for the dot-product kernel, [C/16][3][4][4] dwords (or null)
     int B, H, W, C, Ho, Wo, k, stride, pad, shift, lo, hi;
     float f_lo, f_hi;
+    int ldc, c_off;      // pooling: the output pixel has ldc channels, of which this layer writes [c_off, c_off + C)
 };
 
 // ---- launchers (defined in the .hip files) -------------------------------------------------------
@@ -104,6 +110,7 @@ hipError_t launch_space_to_depth(const void* x, void* y, const int32_t* gather, 
 hipError_t launch_pad_channels(const void* x, void* y, long long rows, int c_bytes, int cp_bytes, hipStream_t s);
 hipError_t launch_depthwise(const PoolArgs& a, int dtype, hipStream_t s);
 hipError_t launch_maxpool(const PoolArgs& a, int dtype, hipStream_t s);
+hipError_t launch_avgpool(const PoolArgs& a, int dtype, hipStream_t s);
 
 struct HeadArgs {
     const void* act; int B, HW, C, n_cls;

@@ -319,6 +319,7 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(DirectConvArgs a)
     const int m = (int)(idx / a.Co);
     const int HoWo = a.Ho * a.Wo;
     const int n = m / HoWo, rem = m - n * HoWo, oy = rem / a.Wo, ox = rem - oy * a.Wo;
+    const long long odx = (long long)m * a.ldc + a.c_off + co;       // the output may be a channel slice of a wider pixel
     if constexpr (ES == 1) {
         const signed char* x = (const signed char*)a.x;
         const signed char* w = (const signed char*)a.w + (long long)co * a.kh * a.kw * a.Ci;
@@ -327,7 +328,7 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(DirectConvArgs a)
             const int iy = oy * a.stride + r - a.pad;
             if (iy < 0 || iy >= a.H) continue;
             for (int s = 0; s < a.kw; ++s) {
-                const int ix = ox * a.stride + s - a.pad;
+                const int ix = ox * a.stride + s - a.pad_w;
                 if (ix < 0 || ix >= a.W) continue;
                 const signed char* xp = x + (((long long)n * a.H + iy) * a.W + ix) * a.Ci;
                 const signed char* wp = w + (r * a.kw + s) * a.Ci;
@@ -335,7 +336,7 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(DirectConvArgs a)
             }
         }
         if (a.res) acc += (int)((const signed char*)a.res)[idx] << a.res_shift;
-        ((signed char*)a.y)[idx] = (signed char)requant_i8(acc, a.shift, a.lo, a.hi);
+        ((signed char*)a.y)[odx] = (signed char)requant_i8(acc, a.shift, a.lo, a.hi);
     } else {
         const uint16_t* x = (const uint16_t*)a.x;
         const uint16_t* w = (const uint16_t*)a.w + (long long)co * a.kh * a.kw * a.Ci;
@@ -344,7 +345,7 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(DirectConvArgs a)
             const int iy = oy * a.stride + r - a.pad;
             if (iy < 0 || iy >= a.H) continue;
             for (int s = 0; s < a.kw; ++s) {
-                const int ix = ox * a.stride + s - a.pad;
+                const int ix = ox * a.stride + s - a.pad_w;
                 if (ix < 0 || ix >= a.W) continue;
                 const uint16_t* xp = x + (((long long)n * a.H + iy) * a.W + ix) * a.Ci;
                 const uint16_t* wp = w + (r * a.kw + s) * a.Ci;
@@ -354,7 +355,7 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(DirectConvArgs a)
         float t = acc + ((const float*)a.bias)[co];
         if (a.res) t = t + bf16_to_f32(((const uint16_t*)a.res)[idx]);
         t = fminf(fmaxf(t, a.f_lo), a.f_hi);
-        ((uint16_t*)a.y)[idx] = f32_to_bf16_rne(t);
+        ((uint16_t*)a.y)[odx] = f32_to_bf16_rne(t);
     }
 }
 

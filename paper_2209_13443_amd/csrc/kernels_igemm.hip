@@ -84,7 +84,8 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
     const int KpB = a.Kp * ES;                     // weight row pitch in bytes
     const int nk = (a.kh * a.kw * a.Ci * ES + KS - 1) / KS;
     const int CiB = a.Ci * ES;
-    const bool wide = (a.Co * ES) % 16 == 0;
+    // whole 16-byte chunks along the channels, also when the layer writes a slice of a wider (concatenated) pixel
+    const bool wide = (a.Co * ES) % 16 == 0 && (a.ldc * ES) % 16 == 0 && (a.c_off * ES) % 16 == 0;
     const bool has_res = a.res != nullptr;
     const unsigned lds0 = lds_addr(lds);
     // LDS map: ring | residual tile (without one the output tile aliases the ring) | bias
@@ -121,7 +122,7 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
         const unsigned n = fast_div((unsigned)m, (unsigned)(a.Ho * a.Wo), a.magic_howo);
         const unsigned rem = (unsigned)m - n * (unsigned)(a.Ho * a.Wo);
         const unsigned oy = fast_div(rem, (unsigned)a.Wo, a.magic_wo), ox = rem - oy * a.Wo;
-        const int iy0 = (int)oy * a.stride - a.pad, ix0 = (int)ox * a.stride - a.pad;
+        const int iy0 = (int)oy * a.stride - a.pad, ix0 = (int)ox * a.stride - a.pad_w;
         voffA[j] = (unsigned)((((int)n * a.H + iy0) * a.W + ix0) * CiB);
         if (PLAIN) {
             voffA[j] += cchunk * 16;
@@ -307,7 +308,8 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
                     const int cl = wn0 + 32 * j + 8 * g + 4 * hi;                     // first of this lane's 4 channels
                     const int chunk = (wn0 * ES >> 4) + ((32 * j + 8 * g) * ES >> 4);  // 4*hi*ES stays inside the chunk
                     unsigned char* cell = rowp + ((chunk ^ swz_l) << 4) + (((32 * j + 8 * g) * ES) & 15);
-                    const long long o = (long long)m * a.Co + n0 + cl;
+                    const long long o = (long long)m * a.Co + n0 + cl;                  // in the residual (never a slice)
+                    const long long oy_ = (long long)m * a.ldc + a.c_off + n0 + cl;      // in the output
                     const bool inside = WIDE || (m < a.M && n0 + cl < a.Co);
                     const v4i b4 = *(const v4i*)(lbias + cl);
                     if constexpr (ES == 1) {
@@ -322,7 +324,7 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
                         }
                         const unsigned out = pack4_i8(q[0], q[1], q[2], q[3]);
                         if (WIDE) *(unsigned*)cell = out;
-                        else if (inside) *(unsigned*)((signed char*)a.y + o) = out;
+                        else if (inside) *(unsigned*)((signed char*)a.y + oy_) = out;
                     } else {
                         uint2 packed = {0u, 0u};
                         if (RES) packed = WIDE ? *(const uint2*)cell : (inside ? *(const uint2*)((const uint16_t*)a.res + o) : packed);
@@ -337,7 +339,7 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
                         out.x = to_bf16_rne(t0) | (to_bf16_rne(t1) << 16);
                         out.y = to_bf16_rne(t2) | (to_bf16_rne(t3) << 16);
                         if (WIDE) *(uint2*)cell = out;
-                        else if (inside) *(uint2*)((uint16_t*)a.y + o) = out;
+                        else if (inside) *(uint2*)((uint16_t*)a.y + oy_) = out;
                     }
                 }
         }
@@ -357,7 +359,7 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
         for (int j = 0; j < NO; ++j) {
             const int q = tid + NT * j, row = q / CR, chunk = (q % CR) ^ oswz(row);
             const int m = m0 + row, ch = n0 + chunk * (16 / ES);
-            if (q < BM * CR && m < a.M && ch < a.Co) *(v4i*)((unsigned char*)a.y + ((size_t)m * a.Co + ch) * ES) = *(const v4i*)(ro + q * 16);
+            if (q < BM * CR && m < a.M && ch < a.Co) *(v4i*)((unsigned char*)a.y + ((size_t)m * a.ldc + a.c_off + ch) * ES) = *(const v4i*)(ro + q * 16);
         }
     }
 }
@@ -406,8 +408,8 @@ hipError_t launch_conv_igemm(const ConvArgs& a_in, int cfg, hipStream_t s)
     // pixel is a multiple of the step (the address advances by the step), or an unpadded stride-1 kernel whose
     // kernel row is exactly one step (the address advances by one image row)
     ConvArgs a = a_in;
-    const bool plain_1x1 = a.kh == 1 && a.kw == 1 && a.pad == 0 && kbytes % ks == 0;
-    const bool plain_rows = !plain_1x1 && a.pad == 0 && a.stride == 1 && a.kw * a.Ci * ES == ks;
+    const bool plain_1x1 = a.kh == 1 && a.kw == 1 && a.pad == 0 && a.pad_w == 0 && kbytes % ks == 0;
+    const bool plain_rows = !plain_1x1 && a.pad == 0 && a.pad_w == 0 && a.stride == 1 && a.kw * a.Ci * ES == ks;
     const bool plain = plain_1x1 || plain_rows;
     a.plain_step = plain_rows ? a.W * a.Ci * ES : ks;
     if (tile == 0) {

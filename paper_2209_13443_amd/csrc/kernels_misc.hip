@@ -229,7 +229,60 @@ __global__ __launch_bounds__(256) void maxpool_kernel(PoolArgs a)
 #pragma unroll
         for (int e = 0; e < 16; ++e) bits[e >> 2] |= (besti[e] & 0xFF) << (8 * (e & 3));
     }
-    *(v4i*)((unsigned char*)a.y + (pix * a.C) * ES + q * 16) = bits;
+    *(v4i*)((unsigned char*)a.y + (pix * a.ldc + a.c_off) * ES + q * 16) = bits;     // a channel slice when ldc > C
+}
+
+// ---- average pool k x k: all k*k taps, padding counts as zero, divisor k*k ---------------------------------
+// int8: y = floor((2 * sum + k*k) / (2 * k*k)) (round half up); the numerator is made non-negative by adding
+// 128 * k*k to the sum (and 128 is taken off the quotient), the division is a multiply-high with
+// floor(2^32 / (2 k*k)) and one correction step.  bf16: float sum in tap order / (k*k), rounded to bf16.
+template <int ES>
+__global__ __launch_bounds__(256) void avgpool_kernel(PoolArgs a, unsigned magic)
+{
+    const int cchunks = a.C * ES / 16;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)a.B * a.Ho * a.Wo * cchunks) return;
+    const int q = (int)(idx % cchunks);
+    const long long pix = idx / cchunks;
+    const int ox = (int)(pix % a.Wo), oy = (int)((pix / a.Wo) % a.Ho), n = (int)(pix / ((long long)a.Wo * a.Ho));
+    const unsigned char* x = (const unsigned char*)a.x;
+    constexpr int NE = 16 / ES;
+    int sumi[NE];
+    float sumf[NE];
+#pragma unroll
+    for (int e = 0; e < NE; ++e) { sumi[e] = 0; sumf[e] = 0.f; }
+    for (int r = 0; r < a.k; ++r) {
+        const int iy = oy * a.stride + r - a.pad;
+        if (iy < 0 || iy >= a.H) continue;
+        for (int s = 0; s < a.k; ++s) {
+            const int ix = ox * a.stride + s - a.pad;
+            if (ix < 0 || ix >= a.W) continue;
+            const v4i xv = *(const v4i*)(x + ((((long long)n * a.H + iy) * a.W + ix) * a.C) * ES + q * 16);
+            if constexpr (ES == 1) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) sumi[e] += byte_of(xv[e >> 2], e & 3);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sumf[e] += bf16_to_f32_m((uint16_t)((unsigned)xv[e >> 1] >> (16 * (e & 1))));
+            }
+        }
+    }
+    v4i bits = {0, 0, 0, 0};
+    const int kk = a.k * a.k;
+    if constexpr (ES == 1) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const unsigned num = (unsigned)(2 * (sumi[e] + 128 * kk) + kk);        // < 2 * 255 * 225 + 225 < 2^17
+            unsigned qv = __umulhi(num, magic);                                        // floor(num / (2 kk)), corrected below
+            if ((qv + 1) * (unsigned)(2 * kk) <= num) ++qv;
+            if (qv * (unsigned)(2 * kk) > num) --qv;
+            bits[e >> 2] |= (((int)qv - 128) & 0xFF) << (8 * (e & 3));
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bits[e >> 1] |= (int)((unsigned)f32_to_bf16_rne_m(sumf[e] / (float)kk) << (16 * (e & 1)));
+    }
+    *(v4i*)((unsigned char*)a.y + (pix * a.ldc + a.c_off) * ES + q * 16) = bits;
 }
 
 hipError_t launch_maxpool(const PoolArgs& a, int dtype, hipStream_t s)
@@ -240,6 +293,19 @@ hipError_t launch_maxpool(const PoolArgs& a, int dtype, hipStream_t s)
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (dtype == EE_I8) hipLaunchKernelGGL(maxpool_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
     else hipLaunchKernelGGL(maxpool_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_avgpool(const PoolArgs& a, int dtype, hipStream_t s)
+{
+    const int es = dtype == EE_I8 ? 1 : 2;
+    const long long total = (long long)a.B * a.Ho * a.Wo * (a.C * es / 16);
+    if (total <= 0) return hipSuccess;
+    if (a.k < 1 || a.k > 15) return hipErrorInvalidValue;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    const unsigned magic = (unsigned)(0x100000000ull / (unsigned)(2 * a.k * a.k));
+    if (dtype == EE_I8) hipLaunchKernelGGL(avgpool_kernel<1>, dim3(blocks), dim3(256), 0, s, a, magic);
+    else hipLaunchKernelGGL(avgpool_kernel<2>, dim3(blocks), dim3(256), 0, s, a, magic);
     return hipGetLastError();
 }
 

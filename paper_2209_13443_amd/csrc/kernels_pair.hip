@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void conv_pair_kernel(PairArgs p, int gm, int 
         const unsigned n = fast_div((unsigned)m, (unsigned)(a.Ho * a.Wo), a.magic_howo);
         const unsigned rem = (unsigned)m - n * (unsigned)(a.Ho * a.Wo);
         const unsigned oy = fast_div(rem, (unsigned)a.Wo, a.magic_wo), ox = rem - oy * a.Wo;
-        const int iy0 = (int)oy * a.stride - a.pad, ix0 = (int)ox * a.stride - a.pad;
+        const int iy0 = (int)oy * a.stride - a.pad, ix0 = (int)ox * a.stride - a.pad_w;
         voffA[j] = (unsigned)((((int)n * a.H + iy0) * a.W + ix0) * CiB);
         const int s_lo = max(0, -ix0), s_hi = min(a.kw, a.W - ix0), r_lo = max(0, -iy0), r_hi = min(a.kh, a.H - iy0);
         const unsigned colmask = s_hi > s_lo ? ((1u << s_hi) - 1u) & ~((1u << s_lo) - 1u) : 0u;

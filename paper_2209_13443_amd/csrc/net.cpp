@@ -1,9 +1,10 @@
 // Decoding and validation of the network blob (host only).
 //
-// Layout (little endian): 128-byte header, stage records (32 B), op records (96 B), exit records
-// (64 B), then the weight / bias tensors.  Tensor ids are local to a stage: 0 is the stage input and
-// every op defines the next id.
+// Layout (little endian): 128-byte header, stage records (32 B), op records (112 B), exit records
+// (64 B), then the weight / bias tensors.  Tensor ids are local to a stage: 0 is the stage input; an op
+// writes a new tensor, or a channel slice of a concatenation tensor that other ops fill as well.
 #include <cstring>
+#include <utility>
 
 #include "ee_internal.hpp"
 
@@ -24,7 +25,7 @@ int parse_blob(const void* blob, size_t bytes, NetDesc* out)
 {
     if (!blob || bytes < 128) return EE_ERR_ARG;
     const unsigned char* base = static_cast<const unsigned char*>(blob);
-    if (std::memcmp(base, "EENETv1\0", 8) != 0) return EE_ERR_ARG;
+    if (std::memcmp(base, "EENETv2\0", 8) != 0) return EE_ERR_ARG;
     Cursor h{base + 8};
     const int version = h.next<int32_t>();
     NetDesc net;
@@ -34,10 +35,10 @@ int parse_blob(const void* blob, size_t bytes, NetDesc* out)
     net.n_classes = h.next<int32_t>();
     const int64_t stages_off = h.next<int64_t>(), ops_off = h.next<int64_t>(), exits_off = h.next<int64_t>();
     const int64_t data_off = h.next<int64_t>(), total = h.next<int64_t>();
-    if (version != 1) return EE_ERR_ARG;
+    if (version != 2) return EE_ERR_ARG;
     if (net.dtype != EE_I8 && net.dtype != EE_BF16) return EE_ERR_UNSUPPORTED;
     if (n_stages < 1 || n_stages > 8 || n_ops < 0 || n_ops > 4096 || total < 0 || (size_t)total > bytes) return EE_ERR_ARG;
-    if (stages_off < 128 || ops_off < stages_off + 32ll * n_stages || exits_off < ops_off + 96ll * n_ops ||
+    if (stages_off < 128 || ops_off < stages_off + 32ll * n_stages || exits_off < ops_off + 112ll * n_ops ||
         data_off < exits_off + 64ll * n_stages || (size_t)data_off > bytes)
         return EE_ERR_ARG;
     if (net.in_h <= 0 || net.in_w <= 0 || net.in_c <= 0 || net.n_classes <= 0) return EE_ERR_SHAPE;
@@ -45,7 +46,7 @@ int parse_blob(const void* blob, size_t bytes, NetDesc* out)
 
     net.ops.resize(n_ops);
     for (int i = 0; i < n_ops; ++i) {
-        Cursor c{base + ops_off + 96ll * i};
+        Cursor c{base + ops_off + 112ll * i};
         OpDesc& o = net.ops[i];
         o.kind = c.next<int32_t>(); o.src = c.next<int32_t>(); o.dst = c.next<int32_t>(); o.res = c.next<int32_t>();
         o.h_in = c.next<int32_t>(); o.w_in = c.next<int32_t>(); o.c_in = c.next<int32_t>();
@@ -54,6 +55,7 @@ int parse_blob(const void* blob, size_t bytes, NetDesc* out)
         o.shift = c.next<int32_t>(); o.res_shift = c.next<int32_t>(); o.lo = c.next<int32_t>(); o.hi = c.next<int32_t>();
         o.f_lo = c.next<float>(); o.f_hi = c.next<float>();
         o.w_off = c.next<int64_t>(); o.b_off = c.next<int64_t>();
+        o.pad_w = c.next<int32_t>(); o.c_off = c.next<int32_t>(); o.c_tot = c.next<int32_t>();
     }
     net.stages.resize(n_stages);
     net.exits.resize(n_stages);
@@ -67,34 +69,45 @@ int parse_blob(const void* blob, size_t bytes, NetDesc* out)
         st.in_h = prev_h; st.in_w = prev_w; st.in_c = prev_c;
         if (st.first_op < 0 || st.n_ops < 0 || st.first_op + st.n_ops > n_ops || st.n_tensors < 1 || st.n_tensors > 256)
             return EE_ERR_SHAPE;
-        // walk the ops and make sure every tensor shape chains
-        std::vector<int> th(st.n_tensors), tw(st.n_tensors), tc(st.n_tensors);
-        th[0] = prev_h; tw[0] = prev_w; tc[0] = prev_c;
-        int defined = 1;
+        // walk the ops and make sure every tensor shape chains: a tensor is read only after it has been written
+        // completely, and is written once, or slice by slice along its channels
+        std::vector<int> th(st.n_tensors), tw(st.n_tensors), tc(st.n_tensors), filled(st.n_tensors, 0);
+        std::vector<std::vector<std::pair<int, int>>> slices(st.n_tensors);      // (first channel, count) written so far
+        th[0] = prev_h; tw[0] = prev_w; tc[0] = prev_c; filled[0] = prev_c;
         for (int k = 0; k < st.n_ops; ++k) {
             const OpDesc& o = net.ops[st.first_op + k];
-            if (o.kind < OP_CONV || o.kind > OP_MAXPOOL) return EE_ERR_UNSUPPORTED;
-            if (o.src < 0 || o.src >= defined || o.dst != defined || defined >= st.n_tensors) return EE_ERR_SHAPE;
+            if (o.kind < OP_CONV || o.kind > OP_AVGPOOL) return EE_ERR_UNSUPPORTED;
+            if (o.src < 0 || o.src >= st.n_tensors || o.dst < 1 || o.dst >= st.n_tensors || o.dst == o.src) return EE_ERR_SHAPE;
+            if (filled[o.src] == 0 || filled[o.src] != tc[o.src]) return EE_ERR_SHAPE;
             if (o.h_in != th[o.src] || o.w_in != tw[o.src] || o.c_in != tc[o.src]) return EE_ERR_SHAPE;
-            if (o.kh < 1 || o.kw < 1 || o.stride < 1 || o.pad < 0 || o.kh > 15 || o.kw > 15) return EE_ERR_SHAPE;
-            const int ho = (o.h_in + 2 * o.pad - o.kh) / o.stride + 1, wo = (o.w_in + 2 * o.pad - o.kw) / o.stride + 1;
+            if (o.kh < 1 || o.kw < 1 || o.stride < 1 || o.pad < 0 || o.pad_w < 0 || o.kh > 15 || o.kw > 15) return EE_ERR_SHAPE;
+            const int ho = (o.h_in + 2 * o.pad - o.kh) / o.stride + 1, wo = (o.w_in + 2 * o.pad_w - o.kw) / o.stride + 1;
             if (ho < 1 || wo < 1 || o.h_out != ho || o.w_out != wo || o.c_out < 1) return EE_ERR_SHAPE;
-            if (o.kind != OP_CONV && o.c_out != o.c_in) return EE_ERR_SHAPE;
-            if (o.kind == OP_MAXPOOL && (o.kh != o.kw || o.pad >= o.kh)) return EE_ERR_SHAPE;
+            if (o.kind != OP_CONV && (o.c_out != o.c_in || o.pad != o.pad_w || o.kh != o.kw)) return EE_ERR_SHAPE;
+            if ((o.kind == OP_MAXPOOL || o.kind == OP_AVGPOOL) && o.pad >= o.kh) return EE_ERR_SHAPE;
+            if (o.c_off < 0 || o.c_tot < o.c_off + o.c_out) return EE_ERR_SHAPE;
+            if (filled[o.dst] == 0) { th[o.dst] = ho; tw[o.dst] = wo; tc[o.dst] = o.c_tot; }
+            else if (th[o.dst] != ho || tw[o.dst] != wo || tc[o.dst] != o.c_tot || o.c_tot == o.c_out) return EE_ERR_SHAPE;
+            for (const auto& sl : slices[o.dst])                                     // slices of one tensor must not overlap
+                if (o.c_off < sl.first + sl.second && sl.first < o.c_off + o.c_out) return EE_ERR_SHAPE;
+            slices[o.dst].emplace_back(o.c_off, o.c_out);
+            filled[o.dst] += o.c_out;
+            if (filled[o.dst] > o.c_tot) return EE_ERR_SHAPE;
             if (o.res >= 0) {
-                if (o.kind != OP_CONV || o.res >= defined) return EE_ERR_SHAPE;
+                if (o.kind != OP_CONV || o.res >= st.n_tensors || o.c_tot != o.c_out || filled[o.res] == 0 || filled[o.res] != tc[o.res]) return EE_ERR_SHAPE;
                 if (th[o.res] != ho || tw[o.res] != wo || tc[o.res] != o.c_out) return EE_ERR_SHAPE;
             }
             if (net.dtype == EE_I8 && (o.shift < 0 || o.shift > 30 || o.res_shift < 0 || o.res_shift > 23 || o.lo < -128 || o.hi > 127 || o.lo > o.hi))
                 return EE_ERR_SHAPE;
-            if (o.kind != OP_MAXPOOL) {
+            if (o.kind == OP_CONV || o.kind == OP_DWCONV) {
                 const int64_t nw = (int64_t)o.c_out * o.kh * o.kw * (o.kind == OP_DWCONV ? 1 : o.c_in);
                 if (o.w_off < data_off || (size_t)(o.w_off + nw * es) > bytes) return EE_ERR_SHAPE;
                 if (o.b_off < data_off || (size_t)(o.b_off + 4ll * o.c_out) > bytes) return EE_ERR_SHAPE;
             }
-            th[defined] = ho; tw[defined] = wo; tc[defined] = o.c_out;
-            ++defined;
         }
+        const int defined = st.n_tensors;
+        for (int t = 0; t < st.n_tensors; ++t)
+            if (filled[t] == 0 || filled[t] != tc[t]) return EE_ERR_SHAPE;
         if (defined != st.n_tensors || st.out_tensor < 0 || st.out_tensor >= defined) return EE_ERR_SHAPE;
         if (th[st.out_tensor] != st.out_h || tw[st.out_tensor] != st.out_w || tc[st.out_tensor] != st.out_c) return EE_ERR_SHAPE;
         Cursor e{base + exits_off + 64ll * s};

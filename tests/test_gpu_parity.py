@@ -43,7 +43,7 @@ def host(t, like):
     return a.view(np.uint16) if like.dtype == np.uint16 else a
 
 
-I8_NETS = ["tiny_i8", "zoo_i8", "resnet50_small_i8", "resnet18_small_i8", "mobilenetv2_small_i8"]
+I8_NETS = ["tiny_i8", "zoo_i8", "resnet50_small_i8", "resnet18_small_i8", "mobilenetv2_small_i8", "inception_small_i8"]
 
 
 @pytest.mark.parametrize("name", I8_NETS)
@@ -194,6 +194,8 @@ SERVE_CASES = [  # name, n, b_max, arrival gap ns, slo, min_incr, refill
     ("zoo_i8", 48, 8, 700, 12000, 1, 2),
     ("resnet50_small_i8", 60, 8, 200, -1, 1, 2),
     ("mobilenetv2_small_i8", 40, 8, 100, -1, 1, 2),
+    ("inception_small_i8", 40, 8, 300, -1, 1, 2),
+    ("inception_small_i8", 32, 8, 0, -1, 1, 1),
 ]
 
 
@@ -347,7 +349,7 @@ def test_full_size_bf16_sampled_parity(torch, ee, orc):
     eng.close()
 
 
-@pytest.mark.parametrize("name", ["tiny_bf16", "zoo_bf16", "resnet50_small_bf16"])
+@pytest.mark.parametrize("name", ["tiny_bf16", "zoo_bf16", "resnet50_small_bf16", "inception_small_bf16"])
 def test_bf16_within_tolerance(torch, ee, orc, name):
     blob = W.load_net(name)
     eng = ee.Engine(blob, 16)

@@ -13,7 +13,7 @@ def tiny():
 
 
 def test_blob_check_accepts_all_configs_and_rejects_broken_chain(orc):
-    for name in ("tiny_i8", "tiny_bf16", "resnet50_small_i8", "mobilenetv2_small_i8", "resnet18_small_i8"):
+    for name in ("tiny_i8", "tiny_bf16", "resnet50_small_i8", "mobilenetv2_small_i8", "resnet18_small_i8", "inception_small_i8", "inception_small_bf16"):
         assert orc.blob_check(W.build_net(name)) == orc.OK
     b = W.build_net("tiny_i8")
     b.ops[1]["c_in"] = 17
@@ -70,6 +70,42 @@ def test_residual_network_segment_against_layerwise(orc):
     assert np.array_equal(out, tens[int(net.stages[0]["out_tensor"])])
     assert 0 < np.count_nonzero(out) < out.size           # calibrated shifts keep the signal alive
     assert any(int(op["res"]) >= 0 for op in net.stage_ops(0))
+
+
+def test_concatenation_network_segment_against_layerwise(orc):
+    """Inception-style segments: every op computed on its own with the primitives (rectangular kernels with their
+    per-axis padding, average and max pooling) and written into its channel slice by hand equals the segment."""
+    net = W.load_net("inception_small_i8")
+    x = W.input_pool(net, 2)
+    kinds = set()
+    for s in (0, 1):
+        tens = {0: x}
+        for op in net.stage_ops(s):
+            src, kind, k = tens[int(op["src"])], int(op["kind"]), int(op["kh"])
+            kinds.add((kind, int(op["kh"]), int(op["kw"])))
+            if kind == W.OP_MAXPOOL:
+                y = orc.maxpool_i8(src, k, int(op["stride"]), int(op["pad"]))
+            elif kind == W.OP_AVGPOOL:
+                y = orc.avgpool_i8(src, k, int(op["stride"]), int(op["pad"]))
+            else:
+                w, b = net.op_weights(op)
+                acc = orc.conv_acc_i8(src, w.reshape(int(op["c_out"]), int(op["kh"]), int(op["kw"]), int(op["c_in"])), b,
+                                      int(op["stride"]), int(op["pad"]), pad_w=int(op["pad_w"]))
+                y = orc.requant_i8(acc, None, int(op["shift"]), 0, int(op["lo"]), int(op["hi"]))
+            dst, c_off, c_tot, co = int(op["dst"]), int(op["c_off"]), int(op["c_tot"]), int(op["c_out"])
+            if c_tot == co:
+                tens[dst] = y
+            else:
+                tens.setdefault(dst, np.full(y.shape[:3] + (c_tot,), 99, np.int8))[..., c_off:c_off + co] = y
+        out = orc.stage_forward(net, s, x)
+        assert np.array_equal(out, tens[int(net.stages[s]["out_tensor"])])
+        assert 0 < np.count_nonzero(out) < out.size
+        x = out
+    assert {(0, 1, 7), (0, 7, 1), (0, 5, 5), (0, 3, 3), (0, 1, 1), (2, 3, 3), (3, 3, 3)} <= kinds
+    bad = W.load_net("inception_small_i8")
+    op = next(o for o in bad.ops if int(o["c_tot"]) != int(o["c_out"]))
+    op["c_off"] += 16                                       # a slice that overlaps its neighbour / leaves a gap
+    assert orc.blob_check(bad) == orc.ERR_SHAPE
 
 
 def test_thresholds_zero_and_above_one(orc, tiny):

@@ -41,6 +41,65 @@ def test_conv_matches_library_conv_and_toeplitz(orc, case):
     assert np.array_equal(acc, orc.conv_acc_i8(x, wt, bias, stride, pad, toeplitz=True))
 
 
+RECT_CASES = [  # n, h, w, ci, co, kh, kw, stride, pad (rows), pad_w (columns): kernels that are not square
+    (2, 6, 9, 3, 4, 1, 7, 1, 0, 3), (1, 9, 6, 5, 3, 7, 1, 1, 3, 0), (2, 5, 5, 4, 4, 1, 3, 1, 0, 1), (1, 5, 5, 4, 6, 3, 1, 1, 1, 0),
+    (1, 8, 10, 2, 3, 3, 5, 2, 1, 2), (1, 7, 7, 3, 2, 5, 5, 1, 2, 2), (1, 9, 9, 2, 2, 3, 3, 2, 0, 0),
+]
+
+
+@pytest.mark.parametrize("case", RECT_CASES)
+def test_rectangular_kernels_and_per_axis_padding(orc, case):
+    """Against the library convolution, against the second (Toeplitz) formulation, and against the transposed problem:
+    swapping the image axes, the kernel axes and the two paddings must give the transposed result."""
+    n, h, w, ci, co, kh, kw, stride, pad, pad_w = case
+    x, wt = rand_i8(n, h, w, ci), rand_i8(co, kh, kw, ci)
+    bias = RNG.integers(-5000, 5000, size=co).astype(np.int32)
+    acc = orc.conv_acc_i8(x, wt, bias, stride, pad, pad_w=pad_w)
+    ref = torch_conv(x, wt, bias, stride, (pad, pad_w))
+    assert acc.shape == ref.shape and np.array_equal(acc.astype(np.float64), ref)
+    assert np.array_equal(acc, orc.conv_acc_i8(x, wt, bias, stride, pad, toeplitz=True, pad_w=pad_w))
+    swapped = orc.conv_acc_i8(np.ascontiguousarray(x.transpose(0, 2, 1, 3)), np.ascontiguousarray(wt.transpose(0, 2, 1, 3)), bias, stride, pad_w, pad_w=pad)
+    assert np.array_equal(acc, swapped.transpose(0, 2, 1, 3))
+
+
+def test_row_kernel_counts_in_range_taps(orc):
+    """All-ones 1x7 kernel with 3 columns of padding on an all-ones row of 9: 4 5 6 7 7 7 6 5 4 taps are inside; no row padding."""
+    acc = orc.conv_acc_i8(np.ones((1, 2, 9, 1), np.int8), np.ones((1, 1, 7, 1), np.int8), None, 1, 0, pad_w=3)[0, :, :, 0]
+    assert acc.shape == (2, 9) and acc[0].tolist() == [4, 5, 6, 7, 7, 7, 6, 5, 4] and acc[1].tolist() == acc[0].tolist()
+
+
+def test_avgpool_definition_and_closed_forms(orc):
+    """k x k average with padding counted as zero and the divisor fixed at k*k, rounded half up."""
+    from fractions import Fraction
+    import math
+    x = rand_i8(2, 6, 7, 3)
+    y = orc.avgpool_i8(x, 3, 1, 1)
+    assert y.shape == x.shape
+    xp = np.pad(x.astype(np.int64), ((0, 0), (1, 1), (1, 1), (0, 0)))
+    for (b, i, j, c) in [(0, 0, 0, 0), (1, 5, 6, 2), (0, 2, 3, 1), (1, 0, 4, 0), (0, 5, 0, 2)]:
+        exact = Fraction(int(xp[b, i:i + 3, j:j + 3, c].sum()), 9)
+        assert y[b, i, j, c] == math.floor(exact + Fraction(1, 2))
+    ref = F.avg_pool2d(torch.from_numpy(x.astype(np.float64)).permute(0, 3, 1, 2), 3, 1, 1, count_include_pad=True).permute(0, 2, 3, 1).numpy()
+    assert np.array_equal(y.astype(np.float64), np.floor(ref + 0.5))       # sums of 9 int8 over 9: no ties hidden by rounding in double
+    const = np.full((1, 5, 5, 2), 90, np.int8)
+    yc = orc.avgpool_i8(const, 3, 1, 1)
+    assert np.all(yc[0, 1:-1, 1:-1] == 90) and yc[0, 0, 0, 0] == 40 and yc[0, 0, 2, 0] == 60     # 4/9 and 6/9 of 90 at corner and edge
+    neg = np.full((1, 3, 3, 1), -128, np.int8)
+    assert orc.avgpool_i8(neg, 3, 1, 1)[0, 1, 1, 0] == -128 and orc.avgpool_i8(neg, 3, 1, 1)[0, 0, 0, 0] == -57   # -512/9 = -56.9 -> -57
+    half = np.array([1, 0, 0, 0, 0, 0, 0, 0, 0], np.int8).reshape(1, 3, 3, 1) * 0 + 0
+    half[0, 1, 1, 0] = -5                                                   # -5/9 = -0.56 -> -1 ; 4/9 -> 0 ; 5/9 = 0.56 -> 1
+    assert orc.avgpool_i8(half, 3, 1, 1)[0, 1, 1, 0] == -1
+    half[0, 1, 1, 0] = 4
+    assert orc.avgpool_i8(half, 3, 1, 1)[0, 1, 1, 0] == 0
+    half[0, 1, 1, 0] = 5
+    assert orc.avgpool_i8(half, 3, 1, 1)[0, 1, 1, 0] == 1
+    # bf16: exact for small integers
+    from workloads.blob import f32_to_bf16_bits, bf16_bits_to_f32
+    xb = f32_to_bf16_bits(np.arange(25, dtype=np.float32).reshape(1, 5, 5, 1) * 9)
+    yb = bf16_bits_to_f32(orc.avgpool_bf16(xb, 3, 1, 1))
+    assert yb[0, 2, 2, 0] == 12 * 9 and yb[0, 0, 0, 0] == (0 + 9 + 45 + 54) / 9
+
+
 def test_conv_1x1_is_a_gemm(orc):
     x, wt = rand_i8(2, 6, 5, 24), rand_i8(10, 1, 1, 24)
     acc = orc.conv_acc_i8(x, wt, None, 1, 0)

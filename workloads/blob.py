@@ -5,21 +5,23 @@ the GPU library (C++) each carry their own parser of this layout.
 
   header   128 B   HEADER_DT
   stages   n_stages x 32 B   STAGE_DT
-  ops      n_ops    x 96 B   OP_DT   (ops of stage s are contiguous)
+  ops      n_ops    x 112 B  OP_DT   (ops of stage s are contiguous)
   exits    n_stages x 64 B   EXIT_DT (exit head s sits on the output of stage s)
   data     weights and biases, each tensor 64-byte aligned
 
 Tensor numbering is local to a stage: id 0 is the stage input, every op
-writes a new id (1, 2, ...).  Activations are NHWC.  Convolution weights are
+writes a new id (1, 2, ...), except that several ops may each write a channel
+slice [c_off, c_off + c_out) of one tensor of c_tot channels (concatenation).
+`pad` pads rows (top and bottom), `pad_w` columns.  Activations are NHWC.  Convolution weights are
 [C_out][kh][kw][C_in], depthwise weights [C][kh][kw], FC weights [n_cls][C].
 int8 networks carry int8 weights / int32 biases; bf16 networks carry bf16
 weights (raw uint16) / float32 biases.
 """
 import numpy as np
 
-MAGIC = b"EENETv1\0"
+MAGIC = b"EENETv2\0"
 DT_I8, DT_BF16 = 0, 1
-OP_CONV, OP_DWCONV, OP_MAXPOOL = 0, 1, 2
+OP_CONV, OP_DWCONV, OP_MAXPOOL, OP_AVGPOOL = 0, 1, 2, 3
 
 HEADER_DT = np.dtype([
     ("magic", "S8"), ("version", "<i4"), ("dtype", "<i4"), ("n_stages", "<i4"), ("n_ops", "<i4"),
@@ -43,8 +45,9 @@ OP_DT = np.dtype([
     ("shift", "<i4"), ("res_shift", "<i4"), ("lo", "<i4"), ("hi", "<i4"),
     ("f_lo", "<f4"), ("f_hi", "<f4"),
     ("w_off", "<i8"), ("b_off", "<i8"),
+    ("pad_w", "<i4"), ("c_off", "<i4"), ("c_tot", "<i4"), ("reserved", "<i4"),
 ])
-assert OP_DT.itemsize == 96
+assert OP_DT.itemsize == 112
 
 EXIT_DT = np.dtype([
     ("h", "<i4"), ("w", "<i4"), ("c", "<i4"), ("n_cls", "<i4"),
@@ -78,7 +81,7 @@ class Blob:
         ns, no = int(h["n_stages"]), int(h["n_ops"])
         so, oo, eo = int(h["stages_off"]), int(h["ops_off"]), int(h["exits_off"])
         self.stages = self.raw[so:so + 32 * ns].view(STAGE_DT)
-        self.ops = self.raw[oo:oo + 96 * no].view(OP_DT)
+        self.ops = self.raw[oo:oo + OP_DT.itemsize * no].view(OP_DT)
         self.exits = self.raw[eo:eo + 64 * ns].view(EXIT_DT)
 
     # -- convenience -------------------------------------------------------
@@ -115,7 +118,7 @@ class Blob:
     def op_weights(self, op):
         """Weight and bias arrays (views) of one op record, or (None, None) for max-pool."""
         kind = int(op["kind"])
-        if kind == OP_MAXPOOL:
+        if kind in (OP_MAXPOOL, OP_AVGPOOL):
             return None, None
         co, kh, kw, ci = int(op["c_out"]), int(op["kh"]), int(op["kw"]), int(op["c_in"])
         nw = co * kh * kw * (1 if kind == OP_DWCONV else ci)

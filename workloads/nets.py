@@ -11,7 +11,7 @@ import numpy as np
 
 from . import rng
 from .blob import (HEADER_DT, STAGE_DT, OP_DT, EXIT_DT, MAGIC, DT_I8, DT_BF16, OP_CONV, OP_DWCONV,
-                   OP_MAXPOOL, Blob, f32_to_bf16_bits)
+                   OP_MAXPOOL, OP_AVGPOOL, Blob, f32_to_bf16_bits)
 
 BASE_SEED = 0x220913443000
 RELU6_Q = 96  # int8 stand-in for the ReLU6 ceiling (per-tensor power-of-two scales carry no absolute unit)
@@ -47,14 +47,30 @@ class _Net:
             return 0, RELU6_Q, 0.0, 6.0
         return -128, 127, -math.inf, math.inf
 
-    def conv(self, src, co, k, stride, pad, act="relu", res=-1):
+    def new_concat(self, h, w, c_tot):
+        """A tensor that several ops fill slice by slice along the channels (`into=(tensor, c_off)`)."""
+        return self._new((h, w, c_tot))
+
+    def _dst(self, shape, into):
+        """Destination tensor id, channel offset and total channels of an op producing `shape`."""
+        if into is None:
+            return self._new(shape), 0, shape[2]
+        tid, c_off = into
+        h, w, c_tot = self._cur["shapes"][tid]
+        assert (h, w) == shape[:2] and 0 <= c_off and c_off + shape[2] <= c_tot
+        return tid, c_off, c_tot
+
+    def conv(self, src, co, k, stride, pad, act="relu", res=-1, into=None):
+        """k and pad are ints (square kernel) or (rows, columns) pairs."""
         h, w, ci = self._cur["shapes"][src]
-        ho, wo = (h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1
-        dst = self._new((ho, wo, co))
+        kh, kw = (k, k) if isinstance(k, int) else k
+        ph, pw = (pad, pad) if isinstance(pad, int) else pad
+        ho, wo = (h + 2 * ph - kh) // stride + 1, (w + 2 * pw - kw) // stride + 1
+        dst, c_off, c_tot = self._dst((ho, wo, co), into)
         lo, hi, flo, fhi = self._act(act)
         self._cur["ops"].append(dict(kind=OP_CONV, src=src, dst=dst, res=res, h_in=h, w_in=w, c_in=ci,
-                                     h_out=ho, w_out=wo, c_out=co, kh=k, kw=k, stride=stride, pad=pad,
-                                     lo=lo, hi=hi, f_lo=flo, f_hi=fhi))
+                                     h_out=ho, w_out=wo, c_out=co, kh=kh, kw=kw, stride=stride, pad=ph, pad_w=pw,
+                                     c_off=c_off, c_tot=c_tot, lo=lo, hi=hi, f_lo=flo, f_hi=fhi))
         return dst
 
     def dwconv(self, src, k, stride, pad, act="relu6"):
@@ -63,18 +79,24 @@ class _Net:
         dst = self._new((ho, wo, c))
         lo, hi, flo, fhi = self._act(act)
         self._cur["ops"].append(dict(kind=OP_DWCONV, src=src, dst=dst, res=-1, h_in=h, w_in=w, c_in=c,
-                                     h_out=ho, w_out=wo, c_out=c, kh=k, kw=k, stride=stride, pad=pad,
-                                     lo=lo, hi=hi, f_lo=flo, f_hi=fhi))
+                                     h_out=ho, w_out=wo, c_out=c, kh=k, kw=k, stride=stride, pad=pad, pad_w=pad,
+                                     c_off=0, c_tot=c, lo=lo, hi=hi, f_lo=flo, f_hi=fhi))
         return dst
 
-    def maxpool(self, src, k, stride, pad):
+    def _pool(self, kind, src, k, stride, pad, into):
         h, w, c = self._cur["shapes"][src]
         ho, wo = (h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1
-        dst = self._new((ho, wo, c))
-        self._cur["ops"].append(dict(kind=OP_MAXPOOL, src=src, dst=dst, res=-1, h_in=h, w_in=w, c_in=c,
-                                     h_out=ho, w_out=wo, c_out=c, kh=k, kw=k, stride=stride, pad=pad,
-                                     lo=-128, hi=127, f_lo=-math.inf, f_hi=math.inf))
+        dst, c_off, c_tot = self._dst((ho, wo, c), into)
+        self._cur["ops"].append(dict(kind=kind, src=src, dst=dst, res=-1, h_in=h, w_in=w, c_in=c,
+                                     h_out=ho, w_out=wo, c_out=c, kh=k, kw=k, stride=stride, pad=pad, pad_w=pad,
+                                     c_off=c_off, c_tot=c_tot, lo=-128, hi=127, f_lo=-math.inf, f_hi=math.inf))
         return dst
+
+    def maxpool(self, src, k, stride, pad, into=None):
+        return self._pool(OP_MAXPOOL, src, k, stride, pad, into)
+
+    def avgpool(self, src, k, stride, pad, into=None):
+        return self._pool(OP_AVGPOOL, src, k, stride, pad, into)
 
 
 # ---------------------------------------------------------------------------
@@ -155,6 +177,110 @@ def _resnet50_eq(dtype, in_hw=224, n_classes=1000, exits_after=(4, 8, 12, 16)):
     return net
 
 
+def _inception(dtype, in_hw=304, n_classes=1000):
+    """Inception-v3-style network with four exits (the paper's second benchmark, Sec. IV): the public layer shapes
+    -- factorised 1x7 / 7x1 and 1x3 / 3x1 convolutions, 5x5 convolutions, average-pool branches, channel concatenation --
+    with exits after the 35x35 group, in the middle and at the end of the 17x17 group, and at the end.  The input is
+    304 x 304 instead of 299 x 299 (a sample is then a whole number of 16-byte chunks); the grids stay 35, 17 and 8."""
+    net = _Net(dtype, in_hw, in_hw, 3, n_classes)
+    shape = lambda t: net._cur["shapes"][t]
+
+    def block_a(t, pool_ch):
+        h, w, _ = shape(t)
+        cat = net.new_concat(h, w, 64 + 64 + 96 + pool_ch)
+        net.conv(t, 64, 1, 1, 0, into=(cat, 0))
+        u = net.conv(t, 48, 1, 1, 0)
+        net.conv(u, 64, 5, 1, 2, into=(cat, 64))
+        u = net.conv(t, 64, 1, 1, 0)
+        u = net.conv(u, 96, 3, 1, 1)
+        net.conv(u, 96, 3, 1, 1, into=(cat, 128))
+        u = net.avgpool(t, 3, 1, 1)
+        net.conv(u, pool_ch, 1, 1, 0, into=(cat, 224))
+        return cat
+
+    def reduce_a(t):
+        h, w, c = shape(t)
+        ho, wo = (h - 3) // 2 + 1, (w - 3) // 2 + 1
+        cat = net.new_concat(ho, wo, 384 + 96 + c)
+        net.conv(t, 384, 3, 2, 0, into=(cat, 0))
+        u = net.conv(t, 64, 1, 1, 0)
+        u = net.conv(u, 96, 3, 1, 1)
+        net.conv(u, 96, 3, 2, 0, into=(cat, 384))
+        net.maxpool(t, 3, 2, 0, into=(cat, 480))
+        return cat
+
+    def block_b(t, c7):
+        h, w, _ = shape(t)
+        cat = net.new_concat(h, w, 768)
+        net.conv(t, 192, 1, 1, 0, into=(cat, 0))
+        u = net.conv(t, c7, 1, 1, 0)
+        u = net.conv(u, c7, (1, 7), 1, (0, 3))
+        net.conv(u, 192, (7, 1), 1, (3, 0), into=(cat, 192))
+        u = net.conv(t, c7, 1, 1, 0)
+        u = net.conv(u, c7, (7, 1), 1, (3, 0))
+        u = net.conv(u, c7, (1, 7), 1, (0, 3))
+        u = net.conv(u, c7, (7, 1), 1, (3, 0))
+        net.conv(u, 192, (1, 7), 1, (0, 3), into=(cat, 384))
+        u = net.avgpool(t, 3, 1, 1)
+        net.conv(u, 192, 1, 1, 0, into=(cat, 576))
+        return cat
+
+    def reduce_b(t):
+        h, w, c = shape(t)
+        ho, wo = (h - 3) // 2 + 1, (w - 3) // 2 + 1
+        cat = net.new_concat(ho, wo, 320 + 192 + c)
+        u = net.conv(t, 192, 1, 1, 0)
+        net.conv(u, 320, 3, 2, 0, into=(cat, 0))
+        u = net.conv(t, 192, 1, 1, 0)
+        u = net.conv(u, 192, (1, 7), 1, (0, 3))
+        u = net.conv(u, 192, (7, 1), 1, (3, 0))
+        net.conv(u, 192, 3, 2, 0, into=(cat, 320))
+        net.maxpool(t, 3, 2, 0, into=(cat, 512))
+        return cat
+
+    def block_c(t):
+        h, w, _ = shape(t)
+        cat = net.new_concat(h, w, 2048)
+        net.conv(t, 320, 1, 1, 0, into=(cat, 0))
+        u = net.conv(t, 384, 1, 1, 0)
+        net.conv(u, 384, (1, 3), 1, (0, 1), into=(cat, 320))
+        net.conv(u, 384, (3, 1), 1, (1, 0), into=(cat, 704))
+        u = net.conv(t, 448, 1, 1, 0)
+        u = net.conv(u, 384, 3, 1, 1)
+        net.conv(u, 384, (1, 3), 1, (0, 1), into=(cat, 1088))
+        net.conv(u, 384, (3, 1), 1, (1, 0), into=(cat, 1472))
+        u = net.avgpool(t, 3, 1, 1)
+        net.conv(u, 192, 1, 1, 0, into=(cat, 1856))
+        return cat
+
+    t = net.begin_stage()
+    t = net.conv(t, 32, 3, 2, 0)
+    t = net.conv(t, 32, 3, 1, 0)
+    t = net.conv(t, 64, 3, 1, 1)
+    t = net.maxpool(t, 3, 2, 0)
+    t = net.conv(t, 80, 1, 1, 0)
+    t = net.conv(t, 192, 3, 1, 0)
+    t = net.maxpool(t, 3, 2, 0)
+    for pool_ch in (32, 64, 64):
+        t = block_a(t, pool_ch)
+    net.end_stage(t)
+    t = net.begin_stage()
+    t = reduce_a(t)
+    for c7 in (128, 160):
+        t = block_b(t, c7)
+    net.end_stage(t)
+    t = net.begin_stage()
+    for c7 in (160, 192):
+        t = block_b(t, c7)
+    net.end_stage(t)
+    t = net.begin_stage()
+    t = reduce_b(t)
+    for _ in range(2):
+        t = block_c(t)
+    net.end_stage(t)
+    return net
+
+
 def _mobilenetv2(dtype, in_hw=224, n_classes=1000):
     net = _Net(dtype, in_hw, in_hw, 3, n_classes)
     cfg = [(1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2), (6, 96, 3, 1), (6, 160, 3, 2), (6, 320, 1, 1)]
@@ -219,6 +345,9 @@ CONFIGS = {
     "resnet50_i8": (_resnet50, DT_I8, 4),
     "resnet50_bf16": (_resnet50, DT_BF16, 5),
     "resnet50_eq_i8": (_resnet50_eq, DT_I8, 6),          # exits equidistant in work
+    "inception_i8": (_inception, DT_I8, 7),
+    "inception_small_i8": (lambda dt: _inception(dt, 80, 100), DT_I8, 16),
+    "inception_small_bf16": (lambda dt: _inception(dt, 80, 100), DT_BF16, 17),
     # reduced-size variants for fast tests (same layer types, smaller images / fewer classes)
     "tiny_bf16": (_tiny, DT_BF16, 11),
     "resnet18_small_i8": (lambda dt: _resnet18(dt, 64, 100), DT_I8, 12),
@@ -318,7 +447,7 @@ def build_net(name):
 
     header = np.zeros(1, HEADER_DT)
     header[0]["magic"] = MAGIC
-    header[0]["version"], header[0]["dtype"] = 1, dtype
+    header[0]["version"], header[0]["dtype"] = 2, dtype
     header[0]["n_stages"], header[0]["n_ops"] = n_stages, n_ops
     header[0]["in_h"], header[0]["in_w"], header[0]["in_c"] = net.in_shape
     header[0]["n_classes"] = net.n_classes
