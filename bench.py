@@ -57,6 +57,7 @@ def measured_traffic(workload):
 WORKLOADS = {
     "resnet50_i8_stream": dict(net="resnet50_i8", n=10000, b_max=64, refill=2, load=1.2, spikes=False),
     "resnet50_eq_i8_stream": dict(net="resnet50_eq_i8", n=10000, b_max=64, refill=2, load=1.2, spikes=False),
+    "inception_i8_stream": dict(net="inception_i8", n=6000, b_max=64, refill=2, load=1.2, spikes=False),
     "resnet50_bf16_stream": dict(net="resnet50_bf16", n=20000, b_max=256, refill=2, load=0.8, spikes=True),
     "mobilenetv2_i8_refill": dict(net="mobilenetv2_i8", n=4096, b_max=64, refill=2, load=None, spikes=False),
     "resnet18_i8_static": dict(net="resnet18_i8", n=1024, b_max=32, refill=0, load=None, spikes=False),
@@ -201,7 +202,7 @@ def main():
     if args.cpu_samples >= 0:
         import oracle
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        per = {"resnet50_i8": 2 * cores, "resnet50_eq_i8": 2 * cores, "resnet50_bf16": cores, "resnet18_i8": 4 * cores, "mobilenetv2_i8": 16 * cores}.get(wl["net"], 64)
+        per = {"resnet50_i8": 2 * cores, "resnet50_eq_i8": 2 * cores, "inception_i8": cores, "resnet50_bf16": cores, "resnet18_i8": 4 * cores, "mobilenetv2_i8": 16 * cores}.get(wl["net"], 64)
         ns = min(n, args.cpu_samples or per)
         sample = W.input_pool(blob, ns)
         t0 = time.perf_counter()

@@ -242,7 +242,8 @@ FULL = [("resnet18_i8", 128, 32, 0, [0, 17, 31, 64, 100, 127]),
         ("resnet50_i8", 192, 64, 1, [0, 5, 63, 64, 130, 191]),
         ("mobilenetv2_i8", 192, 64, 1, [1, 40, 63, 99, 150, 190]),
         ("resnet50_i8", 320, 64, 2, [0, 5, 63, 64, 130, 191, 255, 319]),     # the policy and sizes the benchmark times
-        ("resnet50_eq_i8", 192, 64, 2, [0, 31, 64, 100, 191])]               # exits equidistant in work
+        ("resnet50_eq_i8", 192, 64, 2, [0, 31, 64, 100, 191]),               # exits equidistant in work
+        ("inception_i8", 160, 64, 2, [0, 40, 63, 64, 159])]                  # rectangular kernels, concatenation, average pooling
 
 
 @pytest.mark.parametrize("case", FULL)
