@@ -72,6 +72,44 @@ def test_int8_segments_and_heads_bit_exact(torch, ee, orc, name):
     eng.close()
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_networks_bit_exact(torch, ee, orc, seed):
+    """Generated networks (rectangular kernels, per-axis padding, strides, residuals, depthwise, pooling, concatenated
+    slices at odd offsets, channel counts that are not multiples of 16): every segment and head against the oracle."""
+    blob = W.random_net(seed, W.DT_I8)
+    say(f"[case] random int8 network {seed}: {len(blob.ops)} layers")
+    eng = ee.Engine(blob, 8)
+    x = W.input_pool(blob, 7)
+    for b in (7, 2):
+        act = x[:b]
+        for s in range(blob.n_stages):
+            ref = orc.stage_forward(blob, s, act)
+            got = host(eng.stage_forward(s, dev(torch, act), ref.shape[1:]), ref)
+            assert np.array_equal(got, ref), f"network {seed} segment {s} b={b}: {np.count_nonzero(got != ref)} of {ref.size} differ"
+            lab, conf, score, flag = orc.exit_head(blob, s, ref, 0.5)
+            glab, gconf, gscore, gflag = eng.exit_head(s, dev(torch, ref), 0.5)
+            assert np.array_equal(glab.cpu().numpy(), lab) and np.array_equal(gscore.cpu().numpy(), score) and np.array_equal(gflag.cpu().numpy(), flag)
+            act = ref
+    assert 0 < np.count_nonzero(ref) < ref.size or blob.n_stages == 1
+    eng.close()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_networks_bf16_within_tolerance(torch, ee, orc, seed):
+    blob = W.random_net(seed, W.DT_BF16)
+    say(f"[case] random bf16 network {seed}: {len(blob.ops)} layers")
+    eng = ee.Engine(blob, 8)
+    act = W.input_pool(blob, 5)
+    for s in range(blob.n_stages):
+        ref = orc.stage_forward(blob, s, act)
+        got = host(eng.stage_forward(s, dev(torch, act), ref.shape[1:]), ref)
+        r, g = bf16_to_f32(ref).astype(np.float64), bf16_to_f32(got).astype(np.float64)
+        scale = np.abs(r).reshape(r.shape[0], -1).max(axis=1).reshape(-1, 1, 1, 1) + 1e-30
+        assert np.all(np.abs(g - r) <= 2e-2 * scale), f"network {seed} segment {s}: {np.max(np.abs(g - r) / scale)}"
+        act = ref
+    eng.close()
+
+
 @pytest.mark.parametrize("tile", [1, 2, 3, 4])
 @pytest.mark.parametrize("name", ["zoo_i8", "resnet50_small_i8"])
 def test_int8_every_conv_tiling_bit_exact(torch, ee, orc, name, tile):

@@ -176,3 +176,13 @@ def test_schedulers_match_oracle_on_generated_cases(ee, orc, seed, n, n_stages, 
     assert np.array_equal(ea, eb)
     assert np.array_equal(a["exit_idx"], b["exit_idx"]) and np.array_equal(a["latency_ns"], b["latency_ns"])
     assert np.array_equal(a["exit_idx"], forced)
+
+
+def test_random_networks_pass_both_parsers(ee, orc):
+    """The generated networks of the parity fuzz test are valid for the oracle's parser and for the library's."""
+    lib = ee._lib
+    for dtype in (W.DT_I8, W.DT_BF16):
+        for seed in range(30):
+            blob = W.random_net(seed, dtype)
+            buf = blob.buffer()
+            assert orc.blob_check(blob) == orc.OK and lib.ee_blob_check(buf.ctypes.data, buf.size) == ee.EE_OK, (dtype, seed)

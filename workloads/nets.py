@@ -337,6 +337,68 @@ def _zoo(dtype):
     return net
 
 
+def random_net(seed, dtype):
+    """A small random network for parity fuzzing: one or two segments of randomly chosen layers -- square and
+    rectangular kernels with their own padding per axis, strides, residuals, depthwise, max / average pooling and
+    concatenations whose slices come from convolutions and pooling -- with requantisation shifts guessed from the
+    reduction length, so that outputs are neither all zero nor all saturated.  Data only: no arithmetic of the method."""
+    r = np.random.default_rng(0xFA57 + seed)
+    es = 1 if dtype == DT_I8 else 2
+    pick = lambda seq: seq[int(r.integers(len(seq)))]
+    c0 = pick([3, 4, 8, 16, 32, 48])
+    net = _Net(dtype, int(r.integers(6, 20)), 16 if c0 == 3 else pick([8, 12, 16]), c0, 10)     # a sample is whole 16-byte chunks
+    for _ in range(int(r.integers(1, 3))):
+        t0 = net.begin_stage()
+        shapes = net._cur["shapes"]
+        avail = [t0]
+        for _ in range(int(r.integers(5, 12))):
+            src = pick(avail)
+            h, w, c = shapes[src]
+            kind = pick(["conv"] * 5 + ["pool", "dw", "cat"])
+            chunked = (c * es) % 16 == 0
+            if kind == "conv" or (kind in ("pool", "dw") and not chunked) or (kind == "cat" and min(h, w) < 2):
+                kh, kw = pick([(1, 1), (3, 3), (1, 3), (3, 1), (1, 7), (7, 1), (5, 5), (2, 2), (3, 5)])
+                stride = pick([1, 1, 2])
+                ph, pw = (kh // 2, kw // 2) if r.integers(3) else (0, 0)
+                if (h + 2 * ph - kh) // stride + 1 < 1 or (w + 2 * pw - kw) // stride + 1 < 1:
+                    ph, pw = kh // 2, kw // 2
+                co = pick([4, 8, 12, 16, 24, 32, 40, 64, 80, 136])
+                ho, wo = (h + 2 * ph - kh) // stride + 1, (w + 2 * pw - kw) // stride + 1
+                res = [t for t in avail if shapes[t] == (ho, wo, co)]
+                avail.append(net.conv(src, co, (kh, kw), stride, (ph, pw), act=pick(["relu", "relu", "linear", "relu6"]),
+                                      res=pick(res) if res and r.integers(2) else -1))
+            elif kind == "pool":
+                k, stride, pad = 3, pick([1, 2]), pick([0, 1])
+                if (min(h, w) + 2 * pad - k) // stride + 1 < 1:
+                    pad, stride = 1, 1
+                avail.append((net.maxpool if r.integers(2) else net.avgpool)(src, k, stride, pad))
+            elif kind == "dw":
+                avail.append(net.dwconv(src, 3, pick([1, 2]), 1, act=pick(["relu6", "relu"])))
+            else:                                       # concatenation of 2-3 convolution branches and, maybe, a pooled copy
+                widths = [pick([16, 32, 48]) // es * es for _ in range(int(r.integers(2, 4)))]
+                pooled = chunked and bool(r.integers(2))
+                cat = net.new_concat(h, w, sum(widths) + (c if pooled else 0))
+                off = 0
+                for wd in widths:
+                    kh, kw = pick([(1, 1), (3, 3), (1, 3), (3, 1), (1, 7), (5, 5)])
+                    u = net.conv(src, pick([8, 16, 24]), 1, 1, 0) if r.integers(2) else src
+                    net.conv(u, wd, (kh, kw), 1, (kh // 2, kw // 2), into=(cat, off))
+                    off += wd
+                if pooled:
+                    (net.maxpool if r.integers(2) else net.avgpool)(src, 3, 1, 1, into=(cat, off))
+                avail.append(cat)
+        net.end_stage(net.conv(avail[-1], 32, 1, 1, 0))       # segment outputs (what the exit heads read): 32 channels
+    blob = _assemble(net, dtype, BASE_SEED + 0x5000 + seed)
+    for op in blob.ops:
+        if int(op["kind"]) in (OP_CONV, OP_DWCONV):
+            k_red = int(op["kh"]) * int(op["kw"]) * (int(op["c_in"]) if int(op["kind"]) == OP_CONV else 1)
+            op["shift"] = max(0, int(math.ceil(math.log2(2.0 * 74 * 50 * math.sqrt(k_red) / 127))))
+            op["res_shift"] = min(int(op["shift"]), 6) if int(op["res"]) >= 0 else 0
+    for e in blob.exits:
+        e["frac_bits"], e["thr"] = 10, 0.5
+    return blob
+
+
 CONFIGS = {
     # name: (architecture, dtype, seed offset)
     "tiny_i8": (_tiny, DT_I8, 1),
@@ -381,8 +443,11 @@ def _int32_bias(seed, stream, count, bits):
 def build_net(name):
     """Assemble the un-calibrated blob of configuration `name` (a key of CONFIGS)."""
     arch, dtype, off = CONFIGS[name]
-    seed = BASE_SEED + off
-    net = arch(dtype)
+    return _assemble(arch(dtype), dtype, BASE_SEED + off)
+
+
+def _assemble(net, dtype, seed):
+    """Blob of a layer list: records, seeded random weights and biases."""
     n_stages = len(net.stages)
     n_ops = sum(len(s["ops"]) for s in net.stages)
     stages = np.zeros(n_stages, STAGE_DT)
