@@ -50,7 +50,9 @@ int ee_blob_check(const void* model_blob, size_t blob_bytes);
 
 /* Parse the blob, repack the weights for the matrix cores into device memory and size the
  * workspace for b_max slots (1..1024).  `dtype` must match the blob.  `hip_stream` is a
- * hipStream_t (NULL = the default stream).  The blob may be freed after the call. */
+ * hipStream_t (NULL = the default stream).  The blob may be freed after the call.
+ * EE_ERR_OVERFLOW if b_max samples of some layer's tensor reach 2 GiB (the kernels address a
+ * batch tensor with 32-bit byte offsets). */
 int ee_create(const void* model_blob, size_t blob_bytes, int b_max, int dtype, void* hip_stream, ee_ctx** out);
 int ee_destroy(ee_ctx* ctx);
 

@@ -256,6 +256,9 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
         p.d = ctx->net.ops[i];
         if ((rc = pack_op(ctx, base, p))) return fail(rc);
         const OpDesc& d = p.d;
+        // the kernels address a batch tensor with 32-bit byte offsets
+        const double in_rows = (double)d.h_in * d.w_in * std::max(d.c_in, 16), out_rows = (double)d.h_out * d.w_out * d.c_tot;
+        if (std::max(in_rows, out_rows) * es * b_max >= 2147483648.0) return fail(EE_ERR_OVERFLOW);
         const double out_e = (double)d.h_out * d.w_out * d.c_out, in_e = (double)d.h_in * d.w_in * d.c_in;
         const double kred = d.kind == OP_CONV ? (double)d.kh * d.kw * d.c_in : (double)d.kh * d.kw;
         p.ops_per_sample = d.kind == OP_MAXPOOL || d.kind == OP_AVGPOOL ? 0.0 : 2.0 * out_e * kred;

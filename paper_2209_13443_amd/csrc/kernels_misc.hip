@@ -285,8 +285,120 @@ __global__ __launch_bounds__(256) void avgpool_kernel(PoolArgs a, unsigned magic
     *(v4i*)((unsigned char*)a.y + (pix * a.ldc + a.c_off) * ES + q * 16) = bits;
 }
 
+// ---- int8 3x3 max / average pool on 16-bit halves ---------------------------------------------------------------
+// One lane = 4 output pixels along x times 16 channels; the three rows of every input column are reduced
+// first and shared by the windows that overlap it, so a lane issues 18 (stride 1) or 27 (stride 2) 16-byte
+// loads for 4 outputs instead of 36, and works on two channels per instruction.  Coordinates outside the
+// image are clamped to the nearest pixel inside, so every load is in range and needs no select.
+//  max: the clamped pixel belongs to the window (pad < 3), so it changes nothing.  A 16-bit signed max of the
+//       halves (b1:b0), (b3:b2) of a dword is decided by the high byte: the raw dword yields channels 1 and 3,
+//       the dword shifted left by 8 channels 0 and 2 (the low bytes are don't-cares).
+//  avg: v_perm_b32 sign-extends bytes 1 and 3 of a dword into 16-bit lanes (again of the dword and of the
+//       dword shifted left by 8); a tap outside the image uses the selector that yields zero instead.  The
+//       lanes add with v_pk_add_i16 (|sum| <= 1152).  With S = sum + 1152 >= 0,
+//       floor((2 S + 9) / 18) = ((2 S + 9) * 3641) >> 16 exactly for all S <= 2295 (3641 * 18 = 2^16 + 2 and
+//       4599 * 2 < 2^16); the product stays below 2^24, so the quotient is byte 2 of it, and it carries the
+//       bias 128 = 1152 / 9 that the last xor removes.
+typedef short v2s __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pk_max_i16(unsigned a, unsigned b)
+{
+    return __builtin_bit_cast(unsigned, __builtin_elementwise_max(__builtin_bit_cast(v2s, a), __builtin_bit_cast(v2s, b)));
+}
+__device__ __forceinline__ unsigned pk_add_i16(unsigned a, unsigned b)
+{
+    return __builtin_bit_cast(unsigned, __builtin_bit_cast(v2s, a) + __builtin_bit_cast(v2s, b));
+}
+
+template <int STRIDE, bool AVG>
+__global__ __launch_bounds__(256) void pool3x3_i8_kernel(PoolArgs a, int groups_x)
+{
+    constexpr int PX = 4, COLS = (PX - 1) * STRIDE + 3;
+    const int cchunks = a.C / 16;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)a.B * a.Ho * groups_x * cchunks) return;
+    const int q = (int)(idx % cchunks);
+    const int g = (int)(idx / cchunks);
+    const int ox0 = (g % groups_x) * PX, oy = (g / groups_x) % a.Ho, n = g / (groups_x * a.Ho);
+    const unsigned char* x = (const unsigned char*)a.x;
+    const int iy0 = oy * STRIDE - a.pad, ix0 = ox0 * STRIDE - a.pad;
+    // byte offsets inside the batch tensor fit 32 bits (checked when the context is created)
+    unsigned rowoff[3], coloff[COLS];
+    bool rowok[3], colok[COLS];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        const int iy = iy0 + r;
+        rowok[r] = (unsigned)iy < (unsigned)a.H;
+        rowoff[r] = (unsigned)((n * a.H + min(max(iy, 0), a.H - 1)) * a.W) * (unsigned)a.C + (unsigned)q * 16u;
+    }
+#pragma unroll
+    for (int c = 0; c < COLS; ++c) {
+        const int ix = ix0 + c;
+        colok[c] = (unsigned)ix < (unsigned)a.W;
+        coloff[c] = (unsigned)(min(max(ix, 0), a.W - 1) * a.C);
+    }
+    v4i xv[3][COLS];
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int c = 0; c < COLS; ++c) xv[r][c] = *(const v4i*)(x + (rowoff[r] + coloff[c]));
+    unsigned co[COLS][4], ce[COLS][4];         // per column and dword: channels 1, 3 and channels 0, 2 as 16-bit lanes
+#pragma unroll
+    for (int c = 0; c < COLS; ++c) {
+        unsigned sel[3];                       // avg: bytes (b1, sign b1, b3, sign b3) of the second operand, or four zero bytes
+#pragma unroll
+        for (int r = 0; r < 3; ++r) sel[r] = rowok[r] && colok[c] ? 0x09030801u : 0x0c0c0c0cu;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const unsigned x0 = (unsigned)xv[0][c][d], x1 = (unsigned)xv[1][c][d], x2 = (unsigned)xv[2][c][d];
+            if constexpr (AVG) {
+                co[c][d] = pk_add_i16(pk_add_i16(__builtin_amdgcn_perm(0u, x0, sel[0]), __builtin_amdgcn_perm(0u, x1, sel[1])), __builtin_amdgcn_perm(0u, x2, sel[2]));
+                ce[c][d] = pk_add_i16(pk_add_i16(__builtin_amdgcn_perm(0u, x0 << 8, sel[0]), __builtin_amdgcn_perm(0u, x1 << 8, sel[1])),
+                                      __builtin_amdgcn_perm(0u, x2 << 8, sel[2]));
+            } else {
+                co[c][d] = pk_max_i16(pk_max_i16(x0, x1), x2);
+                ce[c][d] = pk_max_i16(pk_max_i16(x0 << 8, x1 << 8), x2 << 8);
+            }
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < PX; ++p) {
+        if (ox0 + p >= a.Wo) break;
+        v4i out;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const unsigned o0 = co[p * STRIDE][d], o1 = co[p * STRIDE + 1][d], o2 = co[p * STRIDE + 2][d];
+            const unsigned e0 = ce[p * STRIDE][d], e1 = ce[p * STRIDE + 1][d], e2 = ce[p * STRIDE + 2][d];
+            if constexpr (AVG) {
+                const unsigned so = pk_add_i16(pk_add_i16(o0, o1), pk_add_i16(o2, 0x04800480u));
+                const unsigned se = pk_add_i16(pk_add_i16(e0, e1), pk_add_i16(e2, 0x04800480u));
+                const unsigned t0 = (se & 0xFFFFu) * 7282u + 32769u, t2 = (se >> 16) * 7282u + 32769u;
+                const unsigned t1 = (so & 0xFFFFu) * 7282u + 32769u, t3 = (so >> 16) * 7282u + 32769u;
+                const unsigned lo = __builtin_amdgcn_perm(t1, t0, 0x0c0c0602u), hi = __builtin_amdgcn_perm(t3, t2, 0x06020c0cu);
+                out[d] = (int)((lo | hi) ^ 0x80808080u);
+            } else {
+                const unsigned mo = pk_max_i16(pk_max_i16(o0, o1), o2), me = pk_max_i16(pk_max_i16(e0, e1), e2);
+                out[d] = (int)__builtin_amdgcn_perm(mo, me, 0x07030501u);
+            }
+        }
+        *(v4i*)((unsigned char*)a.y + ((((long long)n * a.Ho + oy) * a.Wo + ox0 + p) * a.ldc + a.c_off) + q * 16) = out;
+    }
+}
+
+template <bool AVG>
+static hipError_t launch_pool3x3_i8(const PoolArgs& a, hipStream_t s)
+{
+    const int groups_x = (a.Wo + 3) / 4;
+    const long long total = (long long)a.B * a.Ho * groups_x * (a.C / 16);
+    if (total <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((total + 255) / 256));
+    if (a.stride == 1) hipLaunchKernelGGL((pool3x3_i8_kernel<1, AVG>), grid, dim3(256), 0, s, a, groups_x);
+    else hipLaunchKernelGGL((pool3x3_i8_kernel<2, AVG>), grid, dim3(256), 0, s, a, groups_x);
+    return hipGetLastError();
+}
+
 hipError_t launch_maxpool(const PoolArgs& a, int dtype, hipStream_t s)
 {
+    if (dtype == EE_I8 && a.k == 3 && (a.stride == 1 || a.stride == 2) && a.C % 16 == 0) return launch_pool3x3_i8<false>(a, s);
     const int es = dtype == EE_I8 ? 1 : 2;
     const long long total = (long long)a.B * a.Ho * a.Wo * (a.C * es / 16);
     if (total <= 0) return hipSuccess;
@@ -298,6 +410,7 @@ hipError_t launch_maxpool(const PoolArgs& a, int dtype, hipStream_t s)
 
 hipError_t launch_avgpool(const PoolArgs& a, int dtype, hipStream_t s)
 {
+    if (dtype == EE_I8 && a.k == 3 && (a.stride == 1 || a.stride == 2) && a.C % 16 == 0) return launch_pool3x3_i8<true>(a, s);
     const int es = dtype == EE_I8 ? 1 : 2;
     const long long total = (long long)a.B * a.Ho * a.Wo * (a.C * es / 16);
     if (total <= 0) return hipSuccess;
