@@ -63,12 +63,12 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
         std::vector<unsigned char> bp(b, b + 4 * (size_t)C);
         int rc = upload(ctx, &p.w_dev, wp);
         if (!rc) rc = upload(ctx, &p.b_dev, bp);
-        if (!rc && es == 1 && d.kh == 3) {            // [C/16][row][4-channel group][channel] dwords (w[r][0], w[r][1], w[r][2], 0)
+        if (!rc && es == 1 && d.kh == 3) {            // [C/16][column s][4-channel group][channel] dwords (w[0][s], w[1][s], w[2][s], 0)
             std::vector<unsigned char> w3((size_t)C * 12, 0);
             for (int ch = 0; ch < C; ++ch)
                 for (int r = 0; r < 3; ++r)
                     for (int s2 = 0; s2 < 3; ++s2)
-                        w3[((((size_t)(ch / 16) * 3 + r) * 4 + (ch % 16) / 4) * 4 + ch % 4) * 4 + s2] = w[(size_t)ch * 9 + r * 3 + s2];
+                        w3[((((size_t)(ch / 16) * 3 + s2) * 4 + (ch % 16) / 4) * 4 + ch % 4) * 4 + r] = w[(size_t)ch * 9 + r * 3 + s2];
             rc = upload(ctx, &p.w3_dev, w3);
         }
         p.weight_bytes = (double)wp.size() + bp.size();

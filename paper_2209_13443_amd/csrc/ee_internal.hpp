@@ -86,7 +86,7 @@ struct DirectConvArgs {   // one thread per output element; any shape (correctne
 
 struct PoolArgs {         // depthwise 3x3 and max-pool share the shape block
     const void* x; const void* w; const void* bias; void* y;
-    const void* w3;      // int8 3x3 depthwise: weights packed for the dot-product kernel, [C/16][3][4][4] dwords (or null)
+    const void* w3;      // int8 3x3 depthwise: weights packed for the dot-product kernel, [C/16][column][4-channel group][channel] dwords (or null)
     int B, H, W, C, Ho, Wo, k, stride, pad, shift, lo, hi;
     float f_lo, f_hi;
     int ldc, c_off;      // pooling: the output pixel has ldc channels, of which this layer writes [c_off, c_off + C)

@@ -16,6 +16,12 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne_m(float v)
     return (uint16_t)(u >> 16);
 }
 __device__ __forceinline__ float bf16_to_f32_m(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ int med3_i32(int v, int lo, int hi)       // lo <= hi: v clamped to [lo, hi]
+{
+    int r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
+    return r;
+}
 __device__ __forceinline__ int byte_of(int word, int e) { return (int)(signed char)((word >> (8 * e)) & 0xFF); }
 
 // ---- depthwise k x k: one lane = one output pixel x 16 bytes of channels ---------------------------
@@ -88,12 +94,14 @@ __global__ __launch_bounds__(256) void depthwise_kernel(PoolArgs a)
 
 // ---- depthwise 3x3, int8, on the 4-way dot product --------------------------------------------------------
 // One lane = 4 output pixels along x times 16 channels.  v_dot4_i32_i8 wants the 4 bytes of a dword to be 4
-// taps of one channel, NHWC delivers 4 channels of one tap: per kernel row the three tap dwords (and a
-// zero) of a 4-channel group are byte-transposed with 8 v_perm_b32, then 4 dot products add the row to the
-// 4 channels.  Weights are packed per 16-channel chunk as [row][4-channel group][channel] dwords
-// (w[r][0], w[r][1], w[r][2], 0), 192 bytes per chunk, and are loaded once for the lane's 4 pixels, whose
-// windows also share input columns: the kernel is bound by the number of 16-byte accesses per lane, and
-// this halves or thirds them.  Taps outside the image read the row's first in-range pixel and become zero.
+// taps of one channel, NHWC delivers 4 channels of one tap: per input column the three row dwords (and a
+// zero) of a 4-channel group are byte-transposed with 8 v_perm_b32, and one dot product per channel adds the
+// column to every output pixel whose window holds it.  A column is transposed once for the up to three windows
+// that share it, and the lane loads 18 (stride 1) or 27 (stride 2) times 16 bytes for 4 outputs instead of 36.
+// Weights are packed per 16-channel chunk as [column s][4-channel group][channel] dwords
+// (w[0][s], w[1][s], w[2][s], 0), 192 bytes per chunk.  Coordinates outside the image are clamped, so every
+// load is in range; such taps become zero through the selectors of the first permute level (selector 0x0c
+// yields a zero byte).  The rounding constant of the shift is added to the bias once.
 template <int STRIDE>
 __global__ __launch_bounds__(256) void depthwise3x3_i8_kernel(PoolArgs a, int groups_x)
 {
@@ -102,63 +110,76 @@ __global__ __launch_bounds__(256) void depthwise3x3_i8_kernel(PoolArgs a, int gr
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (long long)a.B * a.Ho * groups_x * cchunks) return;
     const int q = (int)(idx % cchunks);
-    const long long g = idx / cchunks;
-    const int ox0 = (int)(g % groups_x) * PX, oy = (int)((g / groups_x) % a.Ho), n = (int)(g / ((long long)groups_x * a.Ho));
-    const unsigned char* x = (const unsigned char*)a.x + (long long)n * a.H * a.W * a.C + q * 16;
+    const int g = (int)(idx / cchunks);
+    const int ox0 = (g % groups_x) * PX, oy = (g / groups_x) % a.Ho, n = g / (groups_x * a.Ho);
+    const unsigned char* x = (const unsigned char*)a.x;
     const int iy0 = oy * STRIDE - a.pad, ix0 = ox0 * STRIDE - a.pad;
-    const v4i zero4 = {0, 0, 0, 0};
+    // byte offsets inside the batch tensor fit 32 bits (checked when the context is created)
+    unsigned rowoff[3], coloff[COLS];
+    bool rowok[3], colok[COLS];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        const int iy = iy0 + r;
+        rowok[r] = (unsigned)iy < (unsigned)a.H;
+        rowoff[r] = (unsigned)((n * a.H + min(max(iy, 0), a.H - 1)) * a.W) * (unsigned)a.C + (unsigned)q * 16u;
+    }
+#pragma unroll
+    for (int c = 0; c < COLS; ++c) {
+        const int ix = ix0 + c;
+        colok[c] = (unsigned)ix < (unsigned)a.W;
+        coloff[c] = (unsigned)(min(max(ix, 0), a.W - 1) * a.C);
+    }
     v4i xv[3][COLS];
 #pragma unroll
     for (int r = 0; r < 3; ++r)
 #pragma unroll
-        for (int c = 0; c < COLS; ++c) {
-            const int iy = iy0 + r, ix = ix0 + c;
-            const bool ok = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
-            const v4i v = *(const v4i*)(x + ((long long)(ok ? iy : min(oy * STRIDE, a.H - 1)) * a.W + (ok ? ix : min(ox0 * STRIDE, a.W - 1))) * a.C);
-            xv[r][c] = ok ? v : zero4;
-        }
+        for (int c = 0; c < COLS; ++c) xv[r][c] = *(const v4i*)(x + (rowoff[r] + coloff[c]));
+    // first permute level of a column whose three rows are x0, x1, x2:
+    //   (x0.b0, x1.b0, x0.b1, x1.b1), (x0.b2, x1.b2, x0.b3, x1.b3), (x2.b0, 0, x2.b1, 0), (x2.b2, 0, x2.b3, 0)
+    const unsigned s_lo01 = (rowok[0] ? 0x00010000u : 0x000c000cu) | (rowok[1] ? 0x05000400u : 0x0c000c00u);
+    const unsigned s_hi01 = (rowok[0] ? 0x00030002u : 0x000c000cu) | (rowok[1] ? 0x07000600u : 0x0c000c00u);
+    const unsigned s_lo2 = rowok[2] ? 0x0c010c00u : 0x0c0c0c0cu, s_hi2 = rowok[2] ? 0x0c030c02u : 0x0c0c0c0cu;
     const v4i* wq = (const v4i*)a.w + q * 12;
-    v4i w4[3][4];
+    const int rnd = a.shift > 0 ? 1 << (a.shift - 1) : 0;
+    v4i outv[PX];
 #pragma unroll
-    for (int r = 0; r < 3; ++r)
+    for (int cg = 0; cg < 4; ++cg) {
+        const v4i b4 = *((const v4i*)a.bias + q * 4 + cg);
+        v4i w[3];
 #pragma unroll
-        for (int cg = 0; cg < 4; ++cg) w4[r][cg] = wq[r * 4 + cg];
-    v4i bias[4];
+        for (int s = 0; s < 3; ++s) w[s] = wq[s * 4 + cg];
+        int acc[PX][4];
 #pragma unroll
-    for (int cg = 0; cg < 4; ++cg) bias[cg] = *((const v4i*)a.bias + q * 4 + cg);
+        for (int p = 0; p < PX; ++p)
 #pragma unroll
-    for (int p = 0; p < PX; ++p) {
-        if (ox0 + p >= a.Wo) break;
-        v4i acc[4] = {bias[0], bias[1], bias[2], bias[3]};
+            for (int e = 0; e < 4; ++e) acc[p][e] = b4[e] + rnd;
 #pragma unroll
-        for (int r = 0; r < 3; ++r)
+        for (int c = 0; c < COLS; ++c) {
+            const unsigned x0 = (unsigned)xv[0][c][cg], x1 = (unsigned)xv[1][c][cg], x2 = (unsigned)xv[2][c][cg];
+            const unsigned lo01 = __builtin_amdgcn_perm(x1, x0, colok[c] ? s_lo01 : 0x0c0c0c0cu), hi01 = __builtin_amdgcn_perm(x1, x0, colok[c] ? s_hi01 : 0x0c0c0c0cu);
+            const unsigned lo2 = __builtin_amdgcn_perm(0u, x2, colok[c] ? s_lo2 : 0x0c0c0c0cu), hi2 = __builtin_amdgcn_perm(0u, x2, colok[c] ? s_hi2 : 0x0c0c0c0cu);
+            // bytes (x0.c, x1.c, x2.c, 0) for the group's channels c = 0..3
+            const unsigned t[4] = {__builtin_amdgcn_perm(lo2, lo01, 0x05040100u), __builtin_amdgcn_perm(lo2, lo01, 0x07060302u),
+                                   __builtin_amdgcn_perm(hi2, hi01, 0x05040100u), __builtin_amdgcn_perm(hi2, hi01, 0x07060302u)};
 #pragma unroll
-            for (int cg = 0; cg < 4; ++cg) {
-                const unsigned x0 = (unsigned)xv[r][p * STRIDE][cg], x1 = (unsigned)xv[r][p * STRIDE + 1][cg], x2 = (unsigned)xv[r][p * STRIDE + 2][cg];
-                // bytes (x0.c, x1.c, x2.c, 0) for c = 0..3
-                const unsigned lo01 = __builtin_amdgcn_perm(x1, x0, 0x05010400u), hi01 = __builtin_amdgcn_perm(x1, x0, 0x07030602u);
-                const unsigned lo2 = __builtin_amdgcn_perm(0u, x2, 0x0c010c00u), hi2 = __builtin_amdgcn_perm(0u, x2, 0x0c030c02u);
-                const unsigned t0 = __builtin_amdgcn_perm(lo2, lo01, 0x05040100u), t1 = __builtin_amdgcn_perm(lo2, lo01, 0x07060302u);
-                const unsigned t2 = __builtin_amdgcn_perm(hi2, hi01, 0x05040100u), t3 = __builtin_amdgcn_perm(hi2, hi01, 0x07060302u);
-                acc[cg][0] = __builtin_amdgcn_sdot4((int)t0, w4[r][cg][0], acc[cg][0], false);
-                acc[cg][1] = __builtin_amdgcn_sdot4((int)t1, w4[r][cg][1], acc[cg][1], false);
-                acc[cg][2] = __builtin_amdgcn_sdot4((int)t2, w4[r][cg][2], acc[cg][2], false);
-                acc[cg][3] = __builtin_amdgcn_sdot4((int)t3, w4[r][cg][3], acc[cg][3], false);
-            }
-        v4i out;
+            for (int s = 0; s < 3; ++s)
+                if ((c - s) >= 0 && (c - s) % STRIDE == 0 && (c - s) / STRIDE < PX) {
 #pragma unroll
-        for (int cg = 0; cg < 4; ++cg) {
+                    for (int e = 0; e < 4; ++e) acc[(c - s) / STRIDE][e] = __builtin_amdgcn_sdot4((int)t[e], w[s][e], acc[(c - s) / STRIDE][e], false);
+                }
+        }
+#pragma unroll
+        for (int p = 0; p < PX; ++p) {
             int t[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int v = a.shift > 0 ? (acc[cg][e] + (1 << (a.shift - 1))) >> a.shift : acc[cg][e];
-                t[e] = min(max(v, a.lo), a.hi);
-            }
+            for (int e = 0; e < 4; ++e) t[e] = med3_i32(acc[p][e] >> a.shift, a.lo, a.hi);
             const unsigned lo = __builtin_amdgcn_perm((unsigned)t[1], (unsigned)t[0], 0x0c0c0400u), hi = __builtin_amdgcn_perm((unsigned)t[3], (unsigned)t[2], 0x0c0c0400u);
-            out[cg] = (int)__builtin_amdgcn_perm(hi, lo, 0x05040100u);
+            outv[p][cg] = (int)__builtin_amdgcn_perm(hi, lo, 0x05040100u);
         }
-        *(v4i*)((unsigned char*)a.y + ((((long long)n * a.Ho + oy) * a.Wo + ox0 + p) * a.C) + q * 16) = out;
     }
+#pragma unroll
+    for (int p = 0; p < PX; ++p)
+        if (ox0 + p < a.Wo) *(v4i*)((unsigned char*)a.y + ((((long long)n * a.Ho + oy) * a.Wo + ox0 + p) * a.C) + q * 16) = outv[p];
 }
 
 hipError_t launch_depthwise(const PoolArgs& a, int dtype, hipStream_t s)
