@@ -173,10 +173,11 @@ def main():
     # the same workload.  Bracketing each launch costs the stream its back-to-back dispatch (about a
     # quarter of the throughput), so it is kept out of the K timed steps above.
     kstats = {k: dict(launches=0, ms=0.0, ops=0.0, bytes=0.0) for k in ee.K_NAMES}
+    layer_stats = []
     if not args.no_kernel_timing:
         eng.profile(True)
         step()
-        kstats = eng.profile_read()
+        kstats, layer_stats = eng.profile_read(len(blob.ops))
         eng.profile(False)
 
     # dominant kernel: the MFMA implicit-GEMM convolution
@@ -191,6 +192,17 @@ def main():
                         algorithmic_mb_per_launch=round(conv["bytes"] / conv["launches"] / 1e6, 3),
                         hbm_gbps_algorithmic=round(conv["bytes"] / (conv["ms"] * 1e-3) / 1e9, 1))
         roofline["traffic"] = measured_traffic(args.workload)
+        # Layer by layer the convolutions are also capped by their algorithmic bytes: the time the launches of
+        # a layer need at best is max(ops / MFMA peak, bytes / HBM peak); the sum over the layers gives the
+        # rate the stack could reach if every launch sat on its own roofline (ops and bytes of a layer are
+        # proportional to the batch, so the per-layer totals decide the max).
+        conv_layers = [l for op, l in zip(blob.ops, layer_stats) if int(op["kind"]) == W.OP_CONV and l["launches"] and l["ops"] > 0]
+        best_s = sum(max(l["ops"] / (PEAK[dtype] * 1e12), l["bytes"] / (HBM_PEAK * 1e9)) for l in conv_layers)
+        if best_s > 0:
+            capped = sum(l["ops"] for l in conv_layers) / best_s / 1e12
+            roofline["layerwise_cap"] = round(capped, 1)              # same unit as `peak`
+            layers_s = sum(l["ms"] for l in conv_layers) * 1e-3
+            roofline["frac_of_layerwise_cap"] = round(best_s / layers_s, 4)
     kernels = {k: dict(launches=v["launches"], ms=round(v["ms"], 3),
                        gbps=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] > 0 else 0.0,
                        hbm_frac=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9 / HBM_PEAK, 4) if v["ms"] > 0 else 0.0,
