@@ -94,6 +94,33 @@ def test_random_networks_bit_exact(torch, ee, orc, seed):
     eng.close()
 
 
+EDGE_SHAPES = [(1, 1, 16), (2, 5, 16), (3, 3, 48), (7, 7, 32), (9, 13, 16), (4, 17, 144)]
+
+
+@pytest.mark.parametrize("kind", ["maxpool", "avgpool", "dw"])
+def test_int8_3x3_window_layers_edge_shapes_and_values(torch, ee, orc, kind):
+    """The 3x3 pooling and depthwise kernels alone (a segment that is one layer), on shapes around their 4-pixel
+    groups and borders, strides 1 and 2, paddings 0..2, with inputs of extreme values: all -128, all 127, a mix of
+    -128 / 127 / 0 / -1 (negative half-way cases of the average's rounding) and uniform bytes."""
+    r = np.random.default_rng(99)
+    for h, w, c in EDGE_SHAPES:
+        for stride in (1, 2):
+            for pad in (0, 1, 2):
+                if min(h, w) + 2 * pad < 3:
+                    continue
+                blob = W.single_layer_net(kind, h, w, c, 3, stride, pad, W.DT_I8, seed=h * 31 + w)
+                say(f"[case] {kind} {h}x{w}x{c} stride {stride} pad {pad}")
+                x = np.concatenate([np.full((1, h, w, c), -128, np.int8), np.full((1, h, w, c), 127, np.int8),
+                                    r.choice(np.array([-128, 127, 0, -1], np.int8), size=(3, h, w, c)),
+                                    r.integers(-128, 128, size=(2, h, w, c), dtype=np.int8)])
+                eng = ee.Engine(blob, 8)
+                for b in (7, 1):
+                    ref = orc.stage_forward(blob, 0, x[:b])
+                    got = host(eng.stage_forward(0, dev(torch, x[:b]), ref.shape[1:]), ref)
+                    assert np.array_equal(got, ref), f"{kind} {h}x{w}x{c} s{stride} p{pad} b={b}: {np.count_nonzero(got != ref)} of {ref.size} differ"
+                eng.close()
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_random_networks_bf16_within_tolerance(torch, ee, orc, seed):
     blob = W.random_net(seed, W.DT_BF16)

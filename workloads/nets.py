@@ -399,6 +399,25 @@ def random_net(seed, dtype):
     return blob
 
 
+def single_layer_net(kind, h, w, c, k, stride, pad, dtype, seed=0):
+    """One segment that is one layer on the input tensor ("maxpool", "avgpool" or "dw"), so that a test sees
+    the layer's own output: for edge shapes and hand-picked input values.  Data only."""
+    net = _Net(dtype, h, w, c, 10)
+    t0 = net.begin_stage()
+    if kind == "dw":
+        out = net.dwconv(t0, k, stride, pad, act="linear")
+    else:
+        out = (net.maxpool if kind == "maxpool" else net.avgpool)(t0, k, stride, pad)
+    net.end_stage(out)
+    blob = _assemble(net, dtype, BASE_SEED + 0x6000 + seed)
+    for op in blob.ops:
+        if int(op["kind"]) == OP_DWCONV:
+            op["shift"] = 7
+    for e in blob.exits:
+        e["frac_bits"], e["thr"] = 10, 0.5
+    return blob
+
+
 CONFIGS = {
     # name: (architecture, dtype, seed offset)
     "tiny_i8": (_tiny, DT_I8, 1),
