@@ -1,7 +1,7 @@
 """Counter-based random numbers: splitmix64 of (seed, stream, index).
 
 Every tensor is a pure function of (seed, stream id, element index), so any
-slice can be regenerated anywhere (CPU test box, GPU machine) without state.
+slice can be regenerated on any machine without state.
 """
 import numpy as np
 
