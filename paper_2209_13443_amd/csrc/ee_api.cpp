@@ -78,7 +78,12 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
     std::vector<unsigned char> bp(4 * (size_t)(Co_pad + 256), 0);     // the kernels copy 256 entries from the tile's first channel
     std::memcpy(bp.data(), b, 4 * (size_t)Co);
     std::vector<unsigned char> wp;
-    if ((Ci * es) % 16 == 0 && Co % 4 == 0 && d.kh * d.kw <= 31) {
+    if (conv_thin_supported(es, d.kh, d.kw, d.stride, d.pad, d.pad_w, Ci, Co, d.c_tot, d.c_off, d.res >= 0)) {
+        p.impl = IMPL_THIN;                  // weight rows as for IMPL_MFMA: the reduction zero padded to 256 bytes
+        p.Kp = round_up(Ci * es, 256) / es;
+        wp.assign((size_t)Co_pad * p.Kp * es, 0);
+        for (int o = 0; o < Co; ++o) std::memcpy(&wp[(size_t)o * p.Kp * es], w + (size_t)o * Ci * es, (size_t)Ci * es);
+    } else if ((Ci * es) % 16 == 0 && Co % 4 == 0 && d.kh * d.kw <= 31) {
         p.impl = IMPL_MFMA;
         const int K = d.kh * d.kw * Ci;
         p.Kp = round_up(K * es, 256) / es;
@@ -132,7 +137,7 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
         p.impl = IMPL_DIRECT;
         wp.assign(w, w + (size_t)Co * d.kh * d.kw * Ci * es);
     }
-    if ((p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_CPAD || p.impl == IMPL_MFMA_S2D) && es == 1 && d.shift > 0) {
+    if ((p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_CPAD || p.impl == IMPL_MFMA_S2D || p.impl == IMPL_THIN) && es == 1 && d.shift > 0) {
         // that kernel requantises with a bare arithmetic shift: the rounding constant 2^(shift-1) goes
         // into the bias (the sum fits int32: the network's calibration guarantees t + 2^(shift-1) does)
         for (int o = 0; o < Co; ++o) {
@@ -615,6 +620,9 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
             if (cfg == 0 && !p.cfg.empty()) cfg = p.cfg[std::min<size_t>(bucket_of(b), p.cfg.size() - 1)];
             const int cls = p.impl == IMPL_MFMA_C4 ? EE_K_CONV_FIRST : EE_K_CONV_MFMA;
             e = timed(cls, ops, bytes, [&] { return launch_conv(st.first_op + k, b, src, dst, res, cfg); }, st.first_op + k);
+        } else if (p.impl == IMPL_THIN) {
+            ThinConvArgs a{src, p.w_dev, p.b_dev, dst, (long long)b * d.h_out * d.w_out, d.c_in, d.c_out, p.Kp * es, d.c_tot, d.c_off, d.shift, d.lo, d.hi};
+            e = timed(EE_K_CONV_MFMA, ops, bytes, [&] { return launch_conv_thin(a, stream); }, st.first_op + k);
         } else if (p.impl == IMPL_DIRECT) {
             DirectConvArgs a{src, p.w_dev, p.b_dev, res, dst, b * d.h_out * d.w_out, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.c_out,
                              d.kh, d.kw, d.stride, d.pad, d.shift, d.res_shift, d.lo, d.hi, d.f_lo, d.f_hi, d.pad_w, d.c_tot, d.c_off};

@@ -7,7 +7,7 @@
 
 namespace ee {
 
-enum Impl { IMPL_MFMA = 0, IMPL_MFMA_C4 = 1, IMPL_DIRECT = 2, IMPL_DW = 3, IMPL_POOL = 4, IMPL_MFMA_CPAD = 5, IMPL_MFMA_S2D = 6, IMPL_AVGPOOL = 7 };
+enum Impl { IMPL_MFMA = 0, IMPL_MFMA_C4 = 1, IMPL_DIRECT = 2, IMPL_DW = 3, IMPL_POOL = 4, IMPL_MFMA_CPAD = 5, IMPL_MFMA_S2D = 6, IMPL_AVGPOOL = 7, IMPL_THIN = 8 };
 enum { BUF_EXT_IN = -1, BUF_EXT_OUT = -2 };
 
 struct OpPlan {

@@ -100,6 +100,15 @@ template <int ES> hipError_t launch_conv_igemm(const ConvArgs& a, int tile, hipS
 // the fused pair (ES = element bytes); cfg 0 = chosen by shape
 template <int ES> hipError_t launch_conv_pair(const PairArgs& p, int cfg, hipStream_t s);
 bool conv_pair_supported(int es, int co2, int kh, int kw, int ci, int co3);
+// 1x1 int8 layers with at most 32 input channels that are no 16-byte multiple: activations and weights straight from global memory into one
+// matrix instruction per 32 x 32 outputs (w: packed rows of KpB bytes, zero padded; bias with the rounding constant)
+struct ThinConvArgs {
+    const void* x; const void* w; const void* bias; void* y;
+    long long M;                 // output pixels of the batch
+    int Ci, Co, KpB, ldc, c_off, shift, lo, hi;
+};
+hipError_t launch_conv_thin(const ThinConvArgs& a, hipStream_t s);
+bool conv_thin_supported(int es, int kh, int kw, int stride, int pad, int pad_w, int ci, int co, int c_tot, int c_off, bool has_res);
 int forced_conv_tile();
 hipError_t launch_conv_direct(const DirectConvArgs& a, int dtype, hipStream_t s);
 hipError_t launch_pad_input(const void* x, void* y, int B, int H, int W, int C, int Hp, int Wp, int pad, int dtype, hipStream_t s);

@@ -121,6 +121,27 @@ def test_int8_3x3_window_layers_edge_shapes_and_values(torch, ee, orc, kind):
                 eng.close()
 
 
+def test_int8_thin_1x1_layers_bit_exact(torch, ee, orc):
+    """1x1 layers with 4..32 input channels (the kernel that feeds one matrix instruction per 32 x 32 outputs straight
+    from global memory): every channel count, output widths that are and are not multiples of 32, pixel counts that
+    end inside a strip of 32, extreme inputs, relu and linear clamps."""
+    r = np.random.default_rng(7)
+    for ci in (4, 8, 12, 16, 20, 24, 28, 32):
+        for co, act in ((16, "linear"), (48, "relu"), (144, "relu6"), (160, "linear")):
+            h, w = (4, 4) if (ci + co) % 3 else (3, 16)
+            blob = W.single_layer_net("conv", h, w, ci, 1, 1, 0, W.DT_I8, seed=ci * 7 + co, co=co, act=act)
+            say(f"[case] 1x1 conv {ci} -> {co} ({act}) on {h}x{w}")
+            x = np.concatenate([np.full((1, h, w, ci), -128, np.int8), np.full((1, h, w, ci), 127, np.int8),
+                                r.integers(-128, 128, size=(5, h, w, ci), dtype=np.int8)])
+            eng = ee.Engine(blob, 8)
+            for b in (7, 3, 1):
+                ref = orc.stage_forward(blob, 0, x[:b])
+                got = host(eng.stage_forward(0, dev(torch, x[:b]), ref.shape[1:]), ref)
+                assert np.array_equal(got, ref), f"1x1 {ci}->{co} b={b}: {np.count_nonzero(got != ref)} of {ref.size} differ"
+            assert 0 < np.count_nonzero(ref != ref.flat[0])
+            eng.close()
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_random_networks_bf16_within_tolerance(torch, ee, orc, seed):
     blob = W.random_net(seed, W.DT_BF16)

@@ -399,13 +399,15 @@ def random_net(seed, dtype):
     return blob
 
 
-def single_layer_net(kind, h, w, c, k, stride, pad, dtype, seed=0):
-    """One segment that is one layer on the input tensor ("maxpool", "avgpool" or "dw"), so that a test sees
-    the layer's own output: for edge shapes and hand-picked input values.  Data only."""
+def single_layer_net(kind, h, w, c, k, stride, pad, dtype, seed=0, co=None, act="linear"):
+    """One segment that is one layer on the input tensor ("maxpool", "avgpool", "dw", or "conv" with `co` output
+    channels), so that a test sees the layer's own output: for edge shapes and hand-picked input values.  Data only."""
     net = _Net(dtype, h, w, c, 10)
     t0 = net.begin_stage()
     if kind == "dw":
         out = net.dwconv(t0, k, stride, pad, act="linear")
+    elif kind == "conv":
+        out = net.conv(t0, co, k, stride, pad, act=act)
     else:
         out = (net.maxpool if kind == "maxpool" else net.avgpool)(t0, k, stride, pad)
     net.end_stage(out)
@@ -413,6 +415,8 @@ def single_layer_net(kind, h, w, c, k, stride, pad, dtype, seed=0):
     for op in blob.ops:
         if int(op["kind"]) == OP_DWCONV:
             op["shift"] = 7
+        elif int(op["kind"]) == OP_CONV:
+            op["shift"] = max(0, int(math.ceil(math.log2(2.0 * 74 * 74 * math.sqrt(k * k * c) / 127))))
     for e in blob.exits:
         e["frac_bits"], e["thr"] = 10, 0.5
     return blob
