@@ -79,8 +79,8 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
     std::memcpy(bp.data(), b, 4 * (size_t)Co);
     std::vector<unsigned char> wp;
     if (conv_thin_supported(es, d.kh, d.kw, d.stride, d.pad, d.pad_w, Ci, Co, d.c_tot, d.c_off, d.res >= 0)) {
-        p.impl = IMPL_THIN;                  // weight rows as for IMPL_MFMA: the reduction zero padded to 256 bytes
-        p.Kp = round_up(Ci * es, 256) / es;
+        p.impl = IMPL_THIN;                  // weight rows of 32 bytes, zero padded
+        p.Kp = 32;
         wp.assign((size_t)Co_pad * p.Kp * es, 0);
         for (int o = 0; o < Co; ++o) std::memcpy(&wp[(size_t)o * p.Kp * es], w + (size_t)o * Ci * es, (size_t)Ci * es);
     } else if ((Ci * es) % 16 == 0 && Co % 4 == 0 && d.kh * d.kw <= 31) {

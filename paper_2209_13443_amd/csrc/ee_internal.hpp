@@ -100,8 +100,8 @@ template <int ES> hipError_t launch_conv_igemm(const ConvArgs& a, int tile, hipS
 // the fused pair (ES = element bytes); cfg 0 = chosen by shape
 template <int ES> hipError_t launch_conv_pair(const PairArgs& p, int cfg, hipStream_t s);
 bool conv_pair_supported(int es, int co2, int kh, int kw, int ci, int co3);
-// 1x1 int8 layers with at most 32 input channels that are no 16-byte multiple: activations and weights straight from global memory into one
-// matrix instruction per 32 x 32 outputs (w: packed rows of KpB bytes, zero padded; bias with the rounding constant)
+// 1x1 int8 layers with at most 32 input channels: activations and weights straight from global memory into one
+// matrix instruction per 32 x 32 outputs (w: packed rows of 32 bytes, zero padded; bias with the rounding constant)
 struct ThinConvArgs {
     const void* x; const void* w; const void* bias; void* y;
     long long M;                 // output pixels of the batch
