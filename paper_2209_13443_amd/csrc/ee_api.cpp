@@ -621,7 +621,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
             const int cls = p.impl == IMPL_MFMA_C4 ? EE_K_CONV_FIRST : EE_K_CONV_MFMA;
             e = timed(cls, ops, bytes, [&] { return launch_conv(st.first_op + k, b, src, dst, res, cfg); }, st.first_op + k);
         } else if (p.impl == IMPL_THIN) {
-            ThinConvArgs a{src, p.w_dev, p.b_dev, dst, (long long)b * d.h_out * d.w_out, d.c_in, d.c_out, p.Kp * es, d.c_tot, d.c_off, d.shift, d.lo, d.hi};
+            ThinConvArgs a{src, p.w_dev, p.b_dev, dst, (long long)b * d.h_out * d.w_out, d.c_in, d.c_out, d.c_tot, d.c_off, d.shift, d.lo, d.hi};
             e = timed(EE_K_CONV_MFMA, ops, bytes, [&] { return launch_conv_thin(a, stream); }, st.first_op + k);
         } else if (p.impl == IMPL_DIRECT) {
             DirectConvArgs a{src, p.w_dev, p.b_dev, res, dst, b * d.h_out * d.w_out, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.c_out,

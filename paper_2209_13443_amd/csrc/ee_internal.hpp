@@ -105,7 +105,7 @@ bool conv_pair_supported(int es, int co2, int kh, int kw, int ci, int co3);
 struct ThinConvArgs {
     const void* x; const void* w; const void* bias; void* y;
     long long M;                 // output pixels of the batch
-    int Ci, Co, KpB, ldc, c_off, shift, lo, hi;
+    int Ci, Co, ldc, c_off, shift, lo, hi;
 };
 hipError_t launch_conv_thin(const ThinConvArgs& a, hipStream_t s);
 bool conv_thin_supported(int es, int kh, int kw, int stride, int pad, int pad_w, int ci, int co, int c_tot, int c_off, bool has_res);
