@@ -105,10 +105,9 @@ int parse_blob(const void* blob, size_t bytes, NetDesc* out)
                 if (o.b_off < data_off || (size_t)(o.b_off + 4ll * o.c_out) > bytes) return EE_ERR_SHAPE;
             }
         }
-        const int defined = st.n_tensors;
-        for (int t = 0; t < st.n_tensors; ++t)
+        for (int t = 0; t < st.n_tensors; ++t)                       // every tensor of the stage is written completely
             if (filled[t] == 0 || filled[t] != tc[t]) return EE_ERR_SHAPE;
-        if (defined != st.n_tensors || st.out_tensor < 0 || st.out_tensor >= defined) return EE_ERR_SHAPE;
+        if (st.out_tensor < 0 || st.out_tensor >= st.n_tensors) return EE_ERR_SHAPE;
         if (th[st.out_tensor] != st.out_h || tw[st.out_tensor] != st.out_w || tc[st.out_tensor] != st.out_c) return EE_ERR_SHAPE;
         Cursor e{base + exits_off + 64ll * s};
         ExitDesc& ex = net.exits[s];
