@@ -102,13 +102,16 @@ __global__ __launch_bounds__(256) void depthwise_kernel(PoolArgs a)
 // (w[0][s], w[1][s], w[2][s], 0), 192 bytes per chunk.  Coordinates outside the image are clamped, so every
 // load is in range; such taps become zero through the selectors of the first permute level (selector 0x0c
 // yields a zero byte).  The rounding constant of the shift is added to the bias once.
-template <int STRIDE>
+template <int STRIDE, bool TABLE_IN_LDS>
 __global__ __launch_bounds__(256) void depthwise3x3_i8_kernel(PoolArgs a, int groups_x)
 {
     constexpr int PX = 4, COLS = (PX - 1) * STRIDE + 3;
+    extern __shared__ __attribute__((aligned(16))) unsigned char dw_lds_raw[];
+    v4i* dw_lds = (v4i*)dw_lds_raw;                    // per 16-channel chunk: 12 weight quads, then 4 bias quads
     const int cchunks = a.C / 16;
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long long)a.B * a.Ho * groups_x * cchunks) return;
+    const long long total = (long long)a.B * a.Ho * groups_x * cchunks;
+    const long long idx = min((long long)blockIdx.x * 256 + threadIdx.x, total - 1);      // lanes past the end redo the last item
+    const bool active = (long long)blockIdx.x * 256 + threadIdx.x < total;
     const int q = (int)(idx % cchunks);
     const int g = (int)(idx / cchunks);
     const int ox0 = (g % groups_x) * PX, oy = (g / groups_x) % a.Ho, n = g / (groups_x * a.Ho);
@@ -134,20 +137,37 @@ __global__ __launch_bounds__(256) void depthwise3x3_i8_kernel(PoolArgs a, int gr
     for (int r = 0; r < 3; ++r)
 #pragma unroll
         for (int c = 0; c < COLS; ++c) xv[r][c] = *(const v4i*)(x + (rowoff[r] + coloff[c]));
+    // Weights and bias depend on the channel chunk only.  With few channels the workgroup copies the whole table
+    // into LDS once (C * 16 bytes) instead of 16 loads of 16 bytes per lane through the vector memory path (the big
+    // early layers: -10 %); with many channels and few pixels the copy is most of what a workgroup would read
+    // anyway and only adds a step to a short launch, so those layers read the table per lane.
+    if constexpr (TABLE_IN_LDS) {
+        for (int i = threadIdx.x; i < cchunks * 16; i += 256) {
+            const int qq = i >> 4, r = i & 15;
+            dw_lds[i] = r < 12 ? ((const v4i*)a.w)[qq * 12 + r] : ((const v4i*)a.bias)[qq * 4 + (r - 12)];
+        }
+        __syncthreads();
+    }
+    if (!active) return;
     // first permute level of a column whose three rows are x0, x1, x2:
     //   (x0.b0, x1.b0, x0.b1, x1.b1), (x0.b2, x1.b2, x0.b3, x1.b3), (x2.b0, 0, x2.b1, 0), (x2.b2, 0, x2.b3, 0)
     const unsigned s_lo01 = (rowok[0] ? 0x00010000u : 0x000c000cu) | (rowok[1] ? 0x05000400u : 0x0c000c00u);
     const unsigned s_hi01 = (rowok[0] ? 0x00030002u : 0x000c000cu) | (rowok[1] ? 0x07000600u : 0x0c000c00u);
     const unsigned s_lo2 = rowok[2] ? 0x0c010c00u : 0x0c0c0c0cu, s_hi2 = rowok[2] ? 0x0c030c02u : 0x0c0c0c0cu;
-    const v4i* wq = (const v4i*)a.w + q * 12;
     const int rnd = a.shift > 0 ? 1 << (a.shift - 1) : 0;
     v4i outv[PX];
 #pragma unroll
     for (int cg = 0; cg < 4; ++cg) {
-        const v4i b4 = *((const v4i*)a.bias + q * 4 + cg);
-        v4i w[3];
+        v4i b4, w[3];
+        if constexpr (TABLE_IN_LDS) {
+            b4 = dw_lds[q * 16 + 12 + cg];
 #pragma unroll
-        for (int s = 0; s < 3; ++s) w[s] = wq[s * 4 + cg];
+            for (int s = 0; s < 3; ++s) w[s] = dw_lds[q * 16 + s * 4 + cg];
+        } else {
+            b4 = *((const v4i*)a.bias + q * 4 + cg);
+#pragma unroll
+            for (int s = 0; s < 3; ++s) w[s] = *((const v4i*)a.w + q * 12 + s * 4 + cg);
+        }
         int acc[PX][4];
 #pragma unroll
         for (int p = 0; p < PX; ++p)
@@ -192,8 +212,14 @@ hipError_t launch_depthwise(const PoolArgs& a, int dtype, hipStream_t s)
         PoolArgs b = a;
         b.w = a.w3;
         const dim3 grid((unsigned)((total + 255) / 256));
-        if (a.stride == 1) hipLaunchKernelGGL(depthwise3x3_i8_kernel<1>, grid, dim3(256), 0, s, b, groups_x);
-        else hipLaunchKernelGGL(depthwise3x3_i8_kernel<2>, grid, dim3(256), 0, s, b, groups_x);
+        if (a.C <= 192) {                   // the table in LDS: measured to pay up to 192 channels (see the kernel)
+            const size_t lds_bytes = (size_t)a.C * 16;
+            if (a.stride == 1) hipLaunchKernelGGL((depthwise3x3_i8_kernel<1, true>), grid, dim3(256), lds_bytes, s, b, groups_x);
+            else hipLaunchKernelGGL((depthwise3x3_i8_kernel<2, true>), grid, dim3(256), lds_bytes, s, b, groups_x);
+        } else {
+            if (a.stride == 1) hipLaunchKernelGGL((depthwise3x3_i8_kernel<1, false>), grid, dim3(256), 0, s, b, groups_x);
+            else hipLaunchKernelGGL((depthwise3x3_i8_kernel<2, false>), grid, dim3(256), 0, s, b, groups_x);
+        }
         return hipGetLastError();
     }
     const long long total = (long long)a.B * a.Ho * a.Wo * (a.C * es / 16);
