@@ -166,7 +166,9 @@ const char* ee_kernel_name(int kernel_class);
 
 /* Tuning / test control of the convolution tiling, process-wide: 0 = chosen per layer and active
  * batch size (default), 1 = 128x128, 2 = 128x64, 3 = 64x64, 4 = 64x128 (output pixels x output channels
- * per workgroup).  Results never depend on it.  Returns the previous setting, EE_ERR_ARG if out of range. */
+ * per workgroup), 7 = the streaming kernel for the layers it covers (many pixels, a reduction of at most nine
+ * 32-byte blocks, at most 64 output channels; other layers keep the default).  Results never depend on it.
+ * Returns the previous setting, EE_ERR_ARG if out of range. */
 int ee_tune_conv_tile(int tile);
 
 /* Kernel-configuration table, one entry per (convolution layer, active-batch bucket 2^k): the GPU
@@ -179,7 +181,8 @@ int ee_tune_conv_tile(int tile);
  * returns how many the layer has (0 = not tuned or not a matrix-core convolution); an entry is
  * tile | step << 4 | stages << 8 | groups << 12 with tile 1: 128x128, 2: 128x64, 3: 64x64, 4: 64x128 (pixels x
  * channels), step 1: 64, 2: 128, 3: 256 bytes of the reduction axis per stage, groups 0: one group of 4
- * wavefronts, 2 or 4: that many groups sharing the reduction of a tile.  EE_ERR_ARG for bad arguments. */
+ * wavefronts, 2 or 4: that many groups sharing the reduction of a tile; the entry 7 alone selects the streaming
+ * kernel.  EE_ERR_ARG for bad arguments. */
 int ee_autotune(ee_ctx* ctx, int reps);
 int ee_config_table(const ee_ctx* ctx, int layer, int* cfg_out, int n);
 /* Loads a stored table for layer `layer` (n <= 16 entries as ee_config_table returns them; n = 0 clears it):

@@ -231,7 +231,7 @@ extern "C" const char* ee_kernel_name(int k)
 
 extern "C" const uint32_t* ee_exp2_table(void) { return exp2_table_host(); }
 
-extern "C" int ee_tune_conv_tile(int tile) { return tile < 0 || tile > 4 ? EE_ERR_ARG : set_conv_tile(tile); }
+extern "C" int ee_tune_conv_tile(int tile) { return tile < 0 || (tile > 4 && tile != 7) ? EE_ERR_ARG : set_conv_tile(tile); }
 
 extern "C" int ee_blob_check(const void* blob, size_t bytes) { return parse_blob(blob, bytes, nullptr); }
 
@@ -403,6 +403,13 @@ hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const 
         return dt == EE_I8 ? launch_conv_mfma_i8(a, stream) : launch_conv_mfma_bf16(a, stream);
     }
     a.x = src; a.mode = 0;
+    const bool streamable = conv_stream_supported(a, dt == EE_I8 ? 1 : 2);
+    if ((cfg & 15) == 7) {
+        if (streamable) return launch_conv_stream(a, stream);
+        if (forced_conv_tile() != 7) return hipErrorInvalidValue;
+        cfg = 0;                                         // forced for the whole process: layers it does not cover keep the default
+    }
+    if (cfg == 0 && streamable && a.M >= 32768) return launch_conv_stream(a, stream);   // untuned: it wins on every large layer it covers
     return dt == EE_I8 ? launch_conv_igemm<1>(a, cfg, stream) : launch_conv_igemm<2>(a, cfg, stream);
 }
 
@@ -449,13 +456,14 @@ extern "C" int ee_autotune(ee_ctx* ctx, int reps)
             best_time[st.first_op + k].assign(buckets.size(), 1e30f);
             for (size_t bi = 0; bi < buckets.size() && !rc; ++bi) {
                 float& best_ms = best_time[st.first_op + k][bi];
-                for (int tile = 1; tile <= 4; ++tile)
+                for (int tile = 1; tile <= 5; ++tile)
                     for (int ksel = 1; ksel <= 3; ++ksel)
                         for (int ns = 2; ns <= 4; ++ns)
                             for (int kspl = 1; kspl <= 4; kspl *= 2) {
+                            if (tile == 5 && (ksel > 1 || ns > 2 || kspl > 1)) continue;  // the streaming kernel has one configuration
                             if (ksel > 1 && kbytes <= 64 * (ksel - 1)) continue;        // a longer step than the whole reduction
                             if (kspl > 1 && (ksel != 3 || tile < 3 || (kspl == 4 && tile != 3) || kbytes < 1024)) continue;   // combinations that exist
-                            const int cfg = tile | (ksel << 4) | (ns << 8) | ((kspl > 1 ? kspl : 0) << 12);
+                            const int cfg = tile == 5 ? 7 : tile | (ksel << 4) | (ns << 8) | ((kspl > 1 ? kspl : 0) << 12);
                             if (ctx->launch_conv(st.first_op + k, buckets[bi], src, dst, res, cfg) != hipSuccess) {
                                 (void)hipGetLastError();                       // this configuration does not fit: skip it
                                 continue;
@@ -535,6 +543,7 @@ extern "C" int ee_config_set(ee_ctx* ctx, int op, const int* cfg, int n)
     if (p.impl != IMPL_MFMA && p.impl != IMPL_MFMA_CPAD && p.impl != IMPL_MFMA_S2D) return EE_ERR_ARG;
     for (int i = 0; i < n; ++i) {
         const int tile = cfg[i] & 15, ksel = (cfg[i] >> 4) & 15, ns = (cfg[i] >> 8) & 15, kspl = (cfg[i] >> 12) & 15;
+        if (cfg[i] == 7) continue;                                           // the streaming kernel
         if (cfg[i] < 0 || (cfg[i] >> 16) || tile > 4 || ksel > 3 || (ns != 0 && (ns < 2 || ns > 4)) || (kspl != 0 && kspl != 2 && kspl != 4)) return EE_ERR_ARG;
     }
     p.cfg.assign(cfg, cfg + n);

@@ -100,6 +100,9 @@ template <int ES> hipError_t launch_conv_igemm(const ConvArgs& a, int tile, hipS
 // the fused pair (ES = element bytes); cfg 0 = chosen by shape
 template <int ES> hipError_t launch_conv_pair(const PairArgs& p, int cfg, hipStream_t s);
 bool conv_pair_supported(int es, int co2, int kh, int kw, int ci, int co3);
+// streaming kernel for large, thin int8 layers (es = element bytes); hipErrorInvalidValue for a layer it does not cover
+bool conv_stream_supported(const ConvArgs& a, int es);
+hipError_t launch_conv_stream(const ConvArgs& a, hipStream_t s);
 // 1x1 int8 layers with at most 32 input channels: activations and weights straight from global memory into one
 // matrix instruction per 32 x 32 outputs (w: packed rows of 32 bytes, zero padded; bias with the rounding constant)
 struct ThinConvArgs {

@@ -142,6 +142,37 @@ def test_int8_thin_1x1_layers_bit_exact(torch, ee, orc):
             eng.close()
 
 
+STREAM_CASES = [  # (h, w, c, co, k, stride, pad): layers the streaming kernel covers, on shapes around its 32-pixel strips
+    (9, 9, 32, 32, 3, 1, 1), (7, 11, 32, 64, 3, 1, 0), (12, 8, 32, 48, 3, 2, 1), (5, 5, 32, 16, 3, 2, 0), (6, 10, 32, 64, 3, 1, 2),
+    (16, 16, 3, 64, 7, 2, 3), (12, 20, 3, 32, 3, 2, 1), (16, 15, 3, 32, 3, 2, 0), (8, 8, 4, 48, 7, 2, 3), (10, 6, 32, 32, (1, 3), 1, (0, 1)),
+    (10, 6, 32, 64, (3, 1), 1, (1, 0)),
+]
+
+
+@pytest.mark.parametrize("case", STREAM_CASES)
+def test_int8_streaming_kernel_bit_exact(torch, ee, orc, case):
+    """The streaming convolution kernel forced on single-layer segments it covers (folded stride-2 first layers, 3 x 3 /
+    1 x 3 / 3 x 1 layers over 32 channels), extreme inputs included; and the same segments with the default choice."""
+    h, w, c, co, k, stride, pad = case
+    r = np.random.default_rng(11)
+    if (h * w * c) % 16:
+        pytest.skip("a sample must be whole 16-byte chunks")
+    blob = W.single_layer_net("conv", h, w, c, k, stride, pad, W.DT_I8, seed=h * 13 + co, co=co, act="relu" if co % 32 else "linear")
+    x = np.concatenate([np.full((1, h, w, c), -128, np.int8), np.full((1, h, w, c), 127, np.int8), r.integers(-128, 128, size=(6, h, w, c), dtype=np.int8)])
+    for tile in (7, 0):
+        old = ee.tune_conv_tile(tile)
+        try:
+            eng = ee.Engine(blob, 8)
+            for b in (8, 5, 1):
+                ref = orc.stage_forward(blob, 0, x[:b])
+                got = host(eng.stage_forward(0, dev(torch, x[:b]), ref.shape[1:]), ref)
+                assert np.array_equal(got, ref), f"{case} tile {tile} b={b}: {np.count_nonzero(got != ref)} of {ref.size} differ"
+            eng.close()
+        finally:
+            ee.tune_conv_tile(old)
+    assert 0 < np.count_nonzero(ref != ref.flat[0])
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_random_networks_bf16_within_tolerance(torch, ee, orc, seed):
     blob = W.random_net(seed, W.DT_BF16)
@@ -158,7 +189,7 @@ def test_random_networks_bf16_within_tolerance(torch, ee, orc, seed):
     eng.close()
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 7])
 @pytest.mark.parametrize("name", ["zoo_i8", "resnet50_small_i8"])
 def test_int8_every_conv_tiling_bit_exact(torch, ee, orc, name, tile):
     blob = W.load_net(name)
@@ -188,7 +219,7 @@ def test_autotuned_configuration_table_keeps_results(torch, ee, orc):
         assert any(len(t) > 0 for t in tables)
         for t in tables:
             for cfg in t:
-                assert 1 <= (cfg & 15) <= 4 and 1 <= ((cfg >> 4) & 15) <= 3 and 2 <= ((cfg >> 8) & 15) <= 4 and (cfg >> 12) in (0, 2, 4)
+                assert cfg == 7 or (1 <= (cfg & 15) <= 4 and 1 <= ((cfg >> 4) & 15) <= 3 and 2 <= ((cfg >> 8) & 15) <= 4 and (cfg >> 12) in (0, 2, 4))
         x = W.input_pool(blob, 11)
         for b in (11, 3, 1):
             act = x[:b]

@@ -416,7 +416,7 @@ def single_layer_net(kind, h, w, c, k, stride, pad, dtype, seed=0, co=None, act=
         if int(op["kind"]) == OP_DWCONV:
             op["shift"] = 7
         elif int(op["kind"]) == OP_CONV:
-            op["shift"] = max(0, int(math.ceil(math.log2(2.0 * 74 * 74 * math.sqrt(k * k * c) / 127))))
+            op["shift"] = max(0, int(math.ceil(math.log2(2.0 * 74 * 74 * math.sqrt(int(op["kh"]) * int(op["kw"]) * c) / 127))))
     for e in blob.exits:
         e["frac_bits"], e["thr"] = 10, 0.5
     return blob
