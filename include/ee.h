@@ -187,8 +187,9 @@ int ee_autotune(ee_ctx* ctx, int reps);
 int ee_config_table(const ee_ctx* ctx, int layer, int* cfg_out, int n);
 /* Loads a stored table for layer `layer` (n <= 16 entries as ee_config_table returns them; n = 0 clears it):
  * the table is design-time data, as the paper's look-up tables are.  EE_ERR_ARG for a layer that is not a
- * matrix-core convolution or an entry outside the encoding; an entry that names a combination the library does
- * not have makes the launch that would use it fail with EE_ERR_DEVICE. */
+ * matrix-core convolution, an entry outside the encoding, or the entry 7 for a layer the streaming kernel does not
+ * cover; an entry that names a tile combination the library does not have makes the launch that would use it fail
+ * with EE_ERR_DEVICE. */
 int ee_config_set(ee_ctx* ctx, int layer, const int* cfg, int n);
 
 /* Fused layer pairs.  A matrix-core convolution without residual whose 64, 128 or 256 output channels are read by

@@ -543,7 +543,13 @@ extern "C" int ee_config_set(ee_ctx* ctx, int op, const int* cfg, int n)
     if (p.impl != IMPL_MFMA && p.impl != IMPL_MFMA_CPAD && p.impl != IMPL_MFMA_S2D) return EE_ERR_ARG;
     for (int i = 0; i < n; ++i) {
         const int tile = cfg[i] & 15, ksel = (cfg[i] >> 4) & 15, ns = (cfg[i] >> 8) & 15, kspl = (cfg[i] >> 12) & 15;
-        if (cfg[i] == 7) continue;                                           // the streaming kernel
+        if (cfg[i] == 7) {                                                   // the streaming kernel, for the layers it covers
+            ConvArgs a{};
+            ctx->fill_conv_args(op, 1, a);
+            a.res = p.d.res >= 0 ? (const void*)ctx : nullptr;               // only whether there is one matters here
+            if (!conv_stream_supported(a, ctx->net.elem_bytes())) return EE_ERR_ARG;
+            continue;
+        }
         if (cfg[i] < 0 || (cfg[i] >> 16) || tile > 4 || ksel > 3 || (ns != 0 && (ns < 2 || ns > 4)) || (kspl != 0 && kspl != 2 && kspl != 4)) return EE_ERR_ARG;
     }
     p.cfg.assign(cfg, cfg + n);

@@ -238,6 +238,14 @@ def test_autotuned_configuration_table_keeps_results(torch, ee, orc):
         assert np.array_equal(host(other.stage_forward(0, dev(torch, x), ref.shape[1:]), ref), ref)
         with pytest.raises(ee.EEError):
             other.load_tables({"config": {"0": [0x99]}})                    # tile 9 does not exist
+        # the streaming kernel as a stored entry: accepted for the folded first layer it covers (results unchanged),
+        # refused for a layer it does not cover (one with a residual)
+        if name == "resnet50_small_i8":
+            other.load_tables({"config": {"0": [7] * len(stored["config"]["0"])}})
+            assert np.array_equal(host(other.stage_forward(0, dev(torch, x), ref.shape[1:]), ref), ref)
+            with_res = next(k for k, op in enumerate(blob.ops) if int(op["res"]) >= 0 and str(k) in stored["config"])
+            with pytest.raises(ee.EEError):
+                other.load_tables({"config": {str(with_res): [7]}})
         other.close()
         eng.close()
 
