@@ -308,3 +308,94 @@ def test_bf16_head_matches_double_softmax(orc):
     p = torch.softmax(torch.from_numpy(z.astype(np.float64)), dim=1).numpy()
     assert np.array_equal(label, p.argmax(axis=1))
     assert np.allclose(conf, p.max(axis=1), rtol=1e-6)
+
+
+# ---- bf16 pooling and depthwise: library routines on bf16-exact values, closed forms, padding ----------
+def _nchw(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64)).permute(0, 3, 1, 2)
+
+
+def _nhwc(t):
+    return t.permute(0, 2, 3, 1).numpy()
+
+
+@pytest.mark.parametrize("k,stride,pad", [(3, 2, 1), (3, 1, 1), (2, 2, 0), (3, 2, 0), (5, 1, 2)])
+def test_bf16_maxpool_matches_library_and_padding_never_wins(orc, k, stride, pad):
+    """Max over the in-range taps only: the library's max-pool pads with -inf, which is the same statement.
+    Values are small integers and halves, all exact in bf16, negative ones included so that a zero
+    standing in for padding would win somewhere along the border."""
+    x = (RNG.integers(-40, 41, size=(2, 9, 11, 5)) * 0.5).astype(np.float32)
+    y = from_bf16(orc.maxpool_bf16(to_bf16(x), k, stride, pad))
+    ref = _nhwc(F.max_pool2d(_nchw(x), k, stride, pad))
+    assert y.shape == ref.shape and np.array_equal(y.astype(np.float64), ref)
+    neg = np.full((1, 6, 6, 2), -3.0, np.float32)
+    assert np.all(from_bf16(orc.maxpool_bf16(to_bf16(neg), k, stride, pad)) == -3.0)
+    # a single peak is seen by exactly the windows that cover it (catches a transposed or shifted window)
+    peak = np.full((1, 7, 8, 1), -1.0, np.float32)
+    peak[0, 2, 5, 0] = 7.0
+    yp = from_bf16(orc.maxpool_bf16(to_bf16(peak), k, stride, pad))[0, :, :, 0]
+    for yo in range(yp.shape[0]):
+        for xo in range(yp.shape[1]):
+            covers = yo * stride - pad <= 2 < yo * stride - pad + k and xo * stride - pad <= 5 < xo * stride - pad + k
+            assert yp[yo, xo] == (7.0 if covers else -1.0), (yo, xo)
+
+
+def test_bf16_maxpool_returns_the_input_bits(orc):
+    """The result is one of the inputs, bit for bit (-0.0 and denormals included), never a re-rounded float."""
+    x = np.array([0x8000, 0x0001, 0xBF80, 0x8001], np.uint16).reshape(1, 2, 2, 1)       # -0.0, tiny, -1.0, -tiny
+    assert int(orc.maxpool_bf16(x, 2, 2, 0)[0, 0, 0, 0]) == 0x0001
+    x2 = np.array([0xBF80, 0xC000, 0xC040, 0xBFC0], np.uint16).reshape(1, 2, 2, 1)      # -1, -2, -3, -1.5
+    assert int(orc.maxpool_bf16(x2, 2, 2, 0)[0, 0, 0, 0]) == 0xBF80
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_bf16_depthwise_matches_grouped_library_conv_and_dense_block_diagonal(orc, stride):
+    c = 6
+    x = RNG.integers(-8, 9, size=(2, 9, 8, c)).astype(np.float32)
+    w = RNG.integers(-4, 5, size=(c, 3, 3)).astype(np.float32)
+    bias = RNG.integers(-16, 17, size=c).astype(np.float32)
+    y = from_bf16(orc.dwconv_bf16(to_bf16(x), to_bf16(w), bias, stride, 1))
+    # sums stay below 2^8 * 9 * 4: exact in float, and exactly representable in bf16 only after rounding -> round the reference
+    ref = torch_conv(x, w[..., None], bias, stride, 1, groups=c)
+    assert y.shape == ref.shape
+    assert np.array_equal(y.astype(np.float64), from_bf16(to_bf16(ref.astype(np.float32))).astype(np.float64))
+    dense = np.zeros((c, 3, 3, c), np.float32)
+    dense[np.arange(c), :, :, np.arange(c)] = w
+    assert np.array_equal(to_bf16(y), orc.conv_bf16(to_bf16(x), to_bf16(dense), bias, stride, 1))
+    # clamp (ReLU6-style) is applied after the bias
+    yc = from_bf16(orc.dwconv_bf16(to_bf16(x), to_bf16(w), bias, stride, 1, 0.0, 6.0))
+    assert np.array_equal(yc.astype(np.float64), np.clip(from_bf16(to_bf16(ref.astype(np.float32))), 0.0, 6.0).astype(np.float64))
+
+
+def test_bf16_depthwise_tap_counts_and_hand_example(orc):
+    ones = to_bf16(np.ones((1, 4, 5, 2), np.float32))
+    y = from_bf16(orc.dwconv_bf16(ones, to_bf16(np.ones((2, 3, 3), np.float32)), None, 1, 1))[0, :, :, 0]
+    assert y[0, 0] == 4 and y[0, 2] == 6 and y[1, 0] == 6 and y[1, 2] == 9 and y[3, 4] == 4
+    # channel 1 of a 3x3 input with kernel [[0,0,0],[0,0,1],[0,2,0]] (no padding): x[1][2] + 2 x[2][1]
+    x = np.zeros((1, 3, 3, 2), np.float32)
+    x[0, :, :, 1] = np.arange(9).reshape(3, 3)
+    w = np.zeros((2, 3, 3), np.float32)
+    w[1, 1, 2], w[1, 2, 1] = 1.0, 2.0
+    out = from_bf16(orc.dwconv_bf16(to_bf16(x), to_bf16(w), np.array([0.5, 0.25], np.float32), 1, 0))
+    assert out.shape == (1, 1, 1, 2) and out[0, 0, 0].tolist() == [0.5, 5 + 2 * 7 + 0.25]
+
+
+@pytest.mark.parametrize("k,stride,pad", [(3, 1, 1), (3, 2, 1), (2, 2, 0), (5, 1, 2)])
+def test_bf16_avgpool_matches_library_on_exact_values(orc, k, stride, pad):
+    """Padding counts as zero and the divisor is k*k everywhere (the library's count_include_pad).  The inputs are
+    multiples of k*k small enough that every window mean is an integer below 256: exact in bf16, no rounding involved."""
+    x = (RNG.integers(-5, 6, size=(2, 8, 9, 3)) * (k * k)).astype(np.float32)
+    y = from_bf16(orc.avgpool_bf16(to_bf16(x), k, stride, pad))
+    ref = _nhwc(F.avg_pool2d(_nchw(x), k, stride, pad, count_include_pad=True))
+    assert y.shape == ref.shape and np.array_equal(y.astype(np.float64), ref)
+
+
+def test_bf16_avgpool_rounds_once(orc):
+    """General values: the window sum in double divided by k*k, one rounding to float and one to bf16."""
+    x = to_bf16(RNG.normal(size=(1, 6, 7, 4)).astype(np.float32))
+    y = orc.avgpool_bf16(x, 3, 1, 1)
+    ref = _nhwc(F.avg_pool2d(_nchw(from_bf16(x)), 3, 1, 1, count_include_pad=True))       # float64
+    assert np.array_equal(y, to_bf16(ref.astype(np.float32)))
+    corner = to_bf16(np.full((1, 3, 3, 1), 9.0, np.float32))
+    yc = from_bf16(orc.avgpool_bf16(corner, 3, 1, 1))[0, :, :, 0]
+    assert yc[0, 0] == 4.0 and yc[0, 1] == 6.0 and yc[1, 1] == 9.0                        # 4, 6 and 9 taps of 9 over the fixed divisor 9
