@@ -104,18 +104,24 @@ struct GpuExec {
         int rc = ctx->run_stage(stage, b, in, ctx->out_buf[stage], stage == 0 && ctx->admission_fold() != nullptr);
         if (!rc) rc = ctx->run_head(stage, b, ctx->out_buf[stage], ctx->net.exits[stage].thr, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag, true);
         if (rc) return rc;
+        long long compact_rec = -1;                     // index of the compaction launch's timing record, if one is kept
         if (stage + 1 < (int)ctx->in_buf.size()) {
             const int64_t sb = ctx->stage_out_bytes(stage);
+            if (ctx->profiling) compact_rec = (long long)ctx->prof_used;
             hipError_t e = ctx->timed(EE_K_COMPACT, 0.0, 2.0 * sb * b, [&] {
                 return launch_compact(ctx->d_flag, ctx->out_buf[stage], ctx->in_buf[stage + 1], nullptr, nullptr, b, sb, dst_off, ring_rows, nullptr, nullptr, ctx->stream);
             });
             if (e != hipSuccess) return EE_ERR_DEVICE;
         }
         if ((rc = wait_outcomes())) return rc;
+        int kept = 0;
         for (int k = 0; k < b; ++k) {
             const HostOutcome& h = ctx->h_out[k];
             out[k] = SlotOutcome{(uint8_t)h.flag, h.label, h.conf, h.score};
+            kept += h.flag == 0;
         }
+        // the compaction launch was booked before B_rem was known: only the survivors are read and written
+        if (compact_rec >= 0) ctx->prof[(size_t)compact_rec].bytes = 2.0 * (double)ctx->stage_out_bytes(stage) * kept;
         return EE_OK;
     }
     int wait_outcomes()
