@@ -714,7 +714,14 @@ extern "C" int ee_compact_refill(ee_ctx* ctx, int stage, int b_act, const uint8_
     const int64_t sb = ctx->stage_out_bytes(stage);
     hipStream_t s = ctx->stream;
     if (b_act > 0) {
-        const double bytes = 2.0 * sb * b_act;       // upper bound: every slot read and written
+        // only the survivors move: B_rem samples read and written.  The host does not know B_rem here, so a timed run
+        // (and only a timed run) reads the flags back to count them.
+        double bytes = 2.0 * sb * b_act;
+        if (ctx->profiling) {
+            std::vector<uint8_t> hf((size_t)b_act);
+            if (hipStreamSynchronize(s) != hipSuccess || hipMemcpy(hf.data(), exit_flag, (size_t)b_act, hipMemcpyDeviceToHost) != hipSuccess) return EE_ERR_DEVICE;
+            bytes = 2.0 * sb * (double)std::count(hf.begin(), hf.end(), (uint8_t)0);
+        }
         if (ctx->timed(EE_K_COMPACT, 0.0, bytes, [&] {
                 return launch_compact(exit_flag, act_src, act_dst, ids_src, ids_dst, b_act, sb, 0, 0, ctx->d_count, b_rem_out, s);
             }) != hipSuccess)
