@@ -77,6 +77,21 @@ int ee_stage_forward(ee_ctx* ctx, int stage, int b_act, const void* act_in, void
 int ee_exit_head(ee_ctx* ctx, int stage, int b_act, const void* act, float thr,
                  int32_t* label, float* conf, int64_t* score, uint8_t* exit_flag);
 
+/* For callers that cannot allocate device memory or may not trigger an allocation: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The same computation, arguments and outputs
+ * as ee_exit_head, but the head's scratch memory (pooled sums, partial rows of the float pooling, logits) lies
+ * in a fixed array of EE_STATIC_SCRATCH_BYTES that is part of the library image (one copy per GPU, held until
+ * the process ends) instead of the context's workspace; the call allocates nothing, on the host or the device,
+ * and what it clears it clears with a kernel, not a memset node.  EE_ERR_OVERFLOW when
+ *   4 * b_act * (C + n_cls)  (+ 4 * b_act * splits * C for bf16 networks whose pooling is split)
+ * rounded up to 256-byte blocks exceeds the array; EE_ERR_DEVICE when the array's address cannot be found.
+ * All calls on one GPU share the array, from every context: calls that overlap on one GPU (different
+ * streams or threads) race and must be serialised by the caller.  ee_last_logits does not see this call. */
+#define EE_STATIC_SCRATCH_BYTES (4 * 1024 * 1024)
+int ee_exit_head_static(ee_ctx* ctx, int stage, int b_act, const void* act, float thr,
+                        int32_t* label, float* conf, int64_t* score, uint8_t* exit_flag);
+int ee_static_scratch_bytes(void);
+
 /* The logits the most recent ee_exit_head call computed, [b_act][n_cls] int32 (int8 networks) or
  * float (bf16 networks), copied to host memory.  Synchronous; for verification. */
 int ee_last_logits(ee_ctx* ctx, int b_act, void* host_out);

@@ -25,7 +25,8 @@ EVENT_DT = np.dtype([("t_ns", "<i8"), ("kind", "<i4"), ("stage", "<i4"), ("b", "
 SYMBOLS = ["ee_strerror", "ee_blob_check", "ee_create", "ee_destroy", "ee_query", "ee_stage_forward", "ee_exit_head",
            "ee_compact_refill", "ee_serve_stream", "ee_schedule_sim", "ee_measure_lut", "ee_profile_enable",
            "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_last_logits", "ee_profile_reserve", "ee_autotune", "ee_config_table",
-           "ee_pair_count", "ee_pair_mode", "ee_pair_table", "ee_config_set", "ee_pair_set"]
+           "ee_pair_count", "ee_pair_mode", "ee_pair_table", "ee_config_set", "ee_pair_set", "ee_exit_head_static",
+           "ee_static_scratch_bytes"]
 
 
 class Trace(C.Structure):
@@ -61,6 +62,8 @@ _lib.ee_destroy.argtypes = [_V]
 _lib.ee_query.argtypes = [_V, C.POINTER(C.c_int), _V, _V]
 _lib.ee_stage_forward.argtypes = [_V, C.c_int, C.c_int, _V, _V]
 _lib.ee_exit_head.argtypes = [_V, C.c_int, C.c_int, _V, C.c_float, _V, _V, _V, _V]
+_lib.ee_exit_head_static.argtypes = [_V, C.c_int, C.c_int, _V, C.c_float, _V, _V, _V, _V]
+_lib.ee_static_scratch_bytes.argtypes = []
 _lib.ee_compact_refill.argtypes = [_V, C.c_int, C.c_int, _V, _V, _V, _V, _V, _V, _V, C.c_int, _V, _V]
 _lib.ee_serve_stream.argtypes = [_V, C.POINTER(Trace), _V, C.POINTER(ServeOpts), _V, C.POINTER(ServeStats), _V, C.c_int64]
 _lib.ee_schedule_sim.argtypes = [C.c_int, C.POINTER(Trace), _V, C.POINTER(ServeOpts), _V, C.POINTER(ServeStats), _V, C.c_int64]
@@ -184,6 +187,11 @@ class Engine:
         _chk(_lib.ee_exit_head(self._h, stage, b, act.data_ptr(), thr, label.data_ptr(), conf.data_ptr(),
                                score.data_ptr(), flag.data_ptr()))
         return label, conf, score, flag
+
+    def exit_head_static(self, stage, act, thr, label, conf, score, flag):
+        """ee_exit_head_static: the caller brings the four per-slot output tensors; nothing is allocated."""
+        _chk(_lib.ee_exit_head_static(self._h, stage, act.shape[0], act.data_ptr(), thr, label.data_ptr(), conf.data_ptr(),
+                                      score.data_ptr(), flag.data_ptr()))
 
     def last_logits(self, b, n_cls):
         out = np.empty((b, n_cls), np.int32 if self.dtype == EE_I8 else np.float32)

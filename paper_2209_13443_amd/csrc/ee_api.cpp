@@ -663,14 +663,16 @@ extern "C" int ee_stage_forward(ee_ctx* ctx, int stage, int b_act, const void* a
 }
 
 // ---- one exit head ------------------------------------------------------------------------------------
-int ee_ctx::run_head(int stage, int b, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag, bool to_host)
+int ee_ctx::run_head(int stage, int b, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag, bool to_host,
+                     const ee::HeadScratch* own)
 {
     const ExitDesc& e = net.exits[stage];
     const int dt = net.dtype, es = net.elem_bytes();
     HeadArgs a{};
     a.act = act; a.B = b; a.HW = e.h * e.w; a.C = e.c; a.n_cls = e.n_cls;
     a.gap_shift = e.gap_shift; a.frac_bits = e.frac_bits; a.logit_scale = e.logit_scale;
-    a.wfc = wfc_dev[stage]; a.bfc = bfc_dev[stage]; a.sums = sums; a.gap_partial = gap_partial; a.logits = logits;
+    a.wfc = wfc_dev[stage]; a.bfc = bfc_dev[stage];
+    a.sums = own ? own->sums : sums; a.gap_partial = own ? own->gap_partial : gap_partial; a.logits = own ? own->logits : logits;
     a.thr = thr;
     a.s_thr = !(thr > 0.0f) ? INT64_MAX : (thr > 1.0f ? 0 : (int64_t)std::floor(1073741824.0 / (double)thr));
     a.last = stage == (int)net.stages.size() - 1;
@@ -692,6 +694,32 @@ extern "C" int ee_exit_head(ee_ctx* ctx, int stage, int b_act, const void* act, 
     if (!act || !label || !conf || !score || !exit_flag || !aligned16(act)) return EE_ERR_ARG;
     return ctx->run_head(stage, b_act, act, thr, label, conf, score, exit_flag);
 }
+
+// The same head with its scratch memory (pooled sums, partial rows of the float pooling, logits) in the array that is
+// part of the library image instead of the context's workspace: the call allocates nothing.
+extern "C" int ee_exit_head_static(ee_ctx* ctx, int stage, int b_act, const void* act, float thr,
+                                   int32_t* label, float* conf, int64_t* score, uint8_t* exit_flag)
+{
+    if (!ctx || stage < 0 || stage >= (int)ctx->net.stages.size() || b_act < 0 || b_act > ctx->b_max) return EE_ERR_ARG;
+    if (b_act == 0) return EE_OK;
+    if (!act || !label || !conf || !score || !exit_flag || !aligned16(act)) return EE_ERR_ARG;
+    const ExitDesc& e = ctx->net.exits[stage];
+    auto up256 = [](size_t v) { return (v + 255) / 256 * 256; };
+    const size_t sums_bytes = up256(4 * (size_t)b_act * e.c);
+    const size_t logit_bytes = up256(4 * (size_t)b_act * e.n_cls);
+    const int splits = ctx->net.dtype == EE_BF16 ? head_gap_splits(b_act, e.h * e.w) : 0;
+    const size_t partial_bytes = splits > 1 ? up256(4 * (size_t)b_act * splits * e.c) : 0;
+    if (sums_bytes + logit_bytes + partial_bytes > (size_t)EE_STATIC_SCRATCH_BYTES) return EE_ERR_OVERFLOW;
+    void* base = nullptr;
+    if (static_scratch(&base) != hipSuccess) return EE_ERR_DEVICE;
+    unsigned char* p = static_cast<unsigned char*>(base);
+    HeadScratch own{reinterpret_cast<int32_t*>(p), reinterpret_cast<int32_t*>(p + sums_bytes + logit_bytes), p + sums_bytes};
+    // the array keeps what the last call on this GPU left: the integer pooling adds into sums that start at zero
+    if (ctx->net.dtype == EE_I8 && launch_fill_zero(own.sums, sums_bytes, ctx->stream) != hipSuccess) return EE_ERR_DEVICE;
+    return ctx->run_head(stage, b_act, act, thr, label, conf, score, exit_flag, false, &own);
+}
+
+extern "C" int ee_static_scratch_bytes(void) { return EE_STATIC_SCRATCH_BYTES; }
 
 extern "C" int ee_last_logits(ee_ctx* ctx, int b_act, void* host_out)
 {

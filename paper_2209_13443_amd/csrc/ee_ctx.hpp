@@ -28,6 +28,8 @@ struct OpPlan {
     double ops_per_sample = 0, bytes_per_sample = 0, weight_bytes = 0;
 };
 
+struct HeadScratch { int32_t* sums; int32_t* gap_partial; void* logits; };
+
 struct ProfRec { int cls; int op; hipEvent_t e0, e1; double ops, bytes; };
 
 }  // namespace ee
@@ -95,8 +97,9 @@ struct ee_ctx {
     void fill_conv_args(int op, int b, ee::ConvArgs& a) const;
     static int bucket_of(int b) { int k = 0; while ((1 << k) < b) ++k; return k; }     // smallest k with 2^k >= b
     // to_host: also write the outcomes to h_out and store ++seq to h_seq when they are all there
+    // own: scratch memory to use instead of the context's (sums, gap_partial, logits)
     int run_head(int stage, int b_act, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag,
-                 bool to_host = false);
+                 bool to_host = false, const ee::HeadScratch* own = nullptr);
     // brackets `launch` with a pair of events when profiling
     template <typename F>
     hipError_t timed(int cls, double ops, double bytes, F&& launch, int op = -1);

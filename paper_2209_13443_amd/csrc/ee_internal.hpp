@@ -138,6 +138,11 @@ struct HeadArgs {
     struct HostOutcome* host_out; unsigned* host_seq; unsigned seq_value; unsigned* arrive_counter;
 };
 struct HostOutcome { int64_t score; int32_t label; float conf; uint32_t flag; uint32_t pad_; };
+// device address, on the current GPU, of the scratch array that is part of the library image (EE_STATIC_SCRATCH_BYTES bytes)
+hipError_t static_scratch(void** out);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+// workgroups the pooling kernel splits a sample's pixels over (bf16 keeps one partial row per split)
+int head_gap_splits(int B, int HW);
 hipError_t launch_head_gap(const HeadArgs& a, int dtype, hipStream_t s);
 hipError_t launch_head_fc(const HeadArgs& a, int dtype, hipStream_t s);
 hipError_t launch_head_softmax(const HeadArgs& a, int dtype, hipStream_t s);

@@ -561,14 +561,27 @@ __global__ __launch_bounds__(256) void gap_reduce_kernel(HeadArgs a, int S)
     *(v4i*)(a.sums + b * a.C + c) = out;
 }
 
+static int gap_pixels_per_block(int B, int HW)
+{
+    const int splits = (512 + B - 1) / B;                    // aim at >= 512 workgroups (256-512 measured equal; 1024 and more are slower:
+                                                             // every workgroup ends with one atomic per channel); B * splits <= B + 1024
+    int ppb = (HW + splits - 1) / splits;
+    if (ppb < 16) ppb = HW < 16 ? HW : 16;
+    return ppb;
+}
+
+int head_gap_splits(int B, int HW)
+{
+    if (B <= 0 || HW <= 0) return 0;
+    const int ppb = gap_pixels_per_block(B, HW);
+    return (HW + ppb - 1) / ppb;
+}
+
 hipError_t launch_head_gap(const HeadArgs& a, int dtype, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
-    int splits = (512 + a.B - 1) / a.B;                      // aim at >= 512 workgroups (256-512 measured equal; 1024 and more are slower:
-                                                             // every workgroup ends with one atomic per channel); B * splits <= B + 1024
-    int ppb = (a.HW + splits - 1) / splits;
-    if (ppb < 16) ppb = a.HW < 16 ? a.HW : 16;
-    splits = (a.HW + ppb - 1) / ppb;
+    const int ppb = gap_pixels_per_block(a.B, a.HW);
+    const int splits = (a.HW + ppb - 1) / ppb;
     if (dtype == EE_I8) {
         hipLaunchKernelGGL(gap_kernel<1>, dim3(splits, a.B), dim3(256), 0, s, a, ppb);
     } else {
@@ -804,6 +817,48 @@ hipError_t launch_head_softmax(const HeadArgs& a, int dtype, hipStream_t s)
     if (a.B <= 0) return hipSuccess;
     if (dtype == EE_I8) hipLaunchKernelGGL(softmax_kernel<1>, dim3(a.B), dim3(256), 0, s, a);
     else hipLaunchKernelGGL(softmax_kernel<2>, dim3(a.B), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ---- scratch memory that is part of the library image --------------------------------------------------------
+// The exit head needs device memory beyond its inputs and outputs: the pooled sums, the partial rows of the
+// float pooling and the logits.  ee_exit_head takes them from the context's workspace; ee_exit_head_static
+// takes them from this array, so that the call allocates nothing.  Every GPU holds its own copy of the array
+// at its own address: the address is looked up once per device, with that device current, and host code only
+// ever uses the looked-up pointer (the array's name is not a device address on the host side).
+static __device__ __align__(256) unsigned char scratch[EE_STATIC_SCRATCH_BYTES];
+
+hipError_t static_scratch(void** out)
+{
+    static void* ptr_of_device[64] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    void* p = __atomic_load_n(&ptr_of_device[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        __atomic_store_n(&ptr_of_device[dev], p, __ATOMIC_RELEASE);      // the same value from every thread that races here
+    }
+    *out = p;
+    return hipSuccess;
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(v4i* p, long long n16)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    const v4i z = {0, 0, 0, 0};
+    if (i < n16) p[i] = z;
+}
+
+// bytes [0, round-up-to-16(bytes)) of p become zero; a kernel, not a memset node, so that it may be captured
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s)
+{
+    const long long n16 = (long long)((bytes + 15) / 16);
+    if (n16 == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s, (v4i*)p, n16);
     return hipGetLastError();
 }
 
