@@ -65,6 +65,41 @@ WORKLOADS = {
 }
 
 
+def layer_table(args, ee, W, blob, dtype):
+    """Isolated layers: each layer of the network alone on B samples with its tuned configuration, `reps` launches back
+    to back between two HIP events.  One text line per layer on stderr, one JSON line on stdout."""
+    B = args.layers
+    eng = ee.Engine(blob, B)
+    if args.load_tables:
+        with open(args.load_tables) as f:
+            eng.load_tables(json.load(f))
+    else:
+        eng.autotune(reps=5)
+    rows = []
+    for i, op in enumerate(blob.ops):
+        us, ops, byt = eng.time_layer(i, B, 0, reps=30)
+        cfgs = eng.config_table(i)
+        k = int(op["kh"]) * int(op["kw"]) * int(op["c_in"])
+        row = dict(layer=i, kind=int(op["kind"]), h=int(op["h_in"]), w=int(op["w_in"]), ci=int(op["c_in"]), co=int(op["c_out"]), kh=int(op["kh"]),
+                   kw=int(op["kw"]), stride=int(op["stride"]), res=bool(int(op["res"]) >= 0), M=B * int(op["h_out"]) * int(op["w_out"]), K=k,
+                   us=round(us, 2), tops=round(ops / us / 1e6, 1), gbps=round(byt / us / 1e3, 1),
+                   roof_us=round(max(ops / (PEAK[dtype] * 1e6), byt / (HBM_PEAK * 1e3)), 2),
+                   cfg=cfgs[min(len(cfgs) - 1, max(0, (B - 1).bit_length()))] if cfgs else 0)
+        rows.append(row)
+        print("op%3d k%d %3dx%-3d ci%5d co%5d %dx%d s%d res%d M=%7d K=%5d: %8.2f us %8.1f T/s %7.1f GB/s  roof %6.2f us (%4.1f%%) cfg 0x%x" % (
+            i, row["kind"], row["h"], row["w"], row["ci"], row["co"], row["kh"], row["kw"], row["stride"], row["res"], row["M"], row["K"],
+            row["us"], row["tops"], row["gbps"], row["roof_us"], 100 * row["roof_us"] / row["us"], row["cfg"]), file=sys.stderr, flush=True)
+    conv = [r for r in rows if r["kind"] == W.OP_CONV]
+    tot_us = sum(r["us"] for r in rows)
+    conv_us = sum(r["us"] for r in conv)
+    conv_ops = sum(r["tops"] * r["us"] for r in conv)             # T/s * us = Mop
+    out = dict(mode="layers", workload=args.workload, net=WORKLOADS[args.workload]["net"], batch=B, dtype=dtype, total_us=round(tot_us, 1), conv_us=round(conv_us, 1),
+               conv_tops=round(conv_ops / conv_us, 1), conv_frac_of_peak=round(conv_ops / conv_us / PEAK[dtype], 4),
+               roofline_us=round(sum(r["roof_us"] for r in rows), 1), layers=rows)
+    print(json.dumps(out))
+    eng.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -81,6 +116,8 @@ def main():
     ap.add_argument("--save-tables", default="", help="write the tuned kernel-configuration tables to this JSON file")
     ap.add_argument("--load-tables", default="", help="load the kernel-configuration tables from this JSON file instead of tuning")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the extra step that brackets every kernel launch with HIP events")
+    ap.add_argument("--layers", type=int, default=0, metavar="B",
+                    help="instead of the stream: every layer of the workload's network alone on B samples, tuned, launches back to back")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this program measures the path on ONE GPU; --gpus must be 1", file=sys.stderr)
@@ -96,6 +133,8 @@ def main():
     blob = W.load_net(wl["net"])
     dtype = "i8" if blob.dtype == W.DT_I8 else "bf16"
     torch.cuda.set_device(0)
+    if args.layers:
+        return layer_table(args, ee, W, blob, dtype)
     eng = ee.Engine(blob, b_max)
 
     # synthetic request pool, resident in HBM before any timed region

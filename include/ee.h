@@ -164,6 +164,14 @@ int ee_schedule_sim(int n_stages, const ee_trace* trace, const int32_t* forced_e
  * lut_ns[s * b_max + B - 1] (host).  Synchronous; activations are whatever the workspace holds. */
 int ee_measure_lut(ee_ctx* ctx, int reps, int64_t* lut_ns);
 
+/* Design-time measurement of one layer alone (Sec. III-B builds its latency tables the same way, ahead of time): layer
+ * `layer` of the network on `b` samples of the context's workspace, `reps` launches back to back between two HIP events
+ * after two warm-up launches; *us_out = mean microseconds per launch (host), *ops_out = 2 * MACs and *bytes_out = the
+ * algorithmic HBM bytes of one launch (may be NULL).  cfg = 0 uses the layer's table entry, else that kernel
+ * configuration (as in ee_config_set).  Synchronous; overwrites workspace activations.  EE_ERR_DEVICE when the
+ * configuration does not exist for this layer. */
+int ee_time_layer(ee_ctx* ctx, int layer, int b, int cfg, int reps, double* us_out, double* ops_out, double* bytes_out);
+
 /* ---- kernel timing (HIP events on the library's stream) ------------------------------------ */
 enum { EE_K_CONV_MFMA = 0, EE_K_CONV_FIRST = 1, EE_K_CONV_DIRECT = 2, EE_K_DEPTHWISE = 3, EE_K_MAXPOOL = 4,
        EE_K_PAD_INPUT = 5, EE_K_GAP = 6, EE_K_FC = 7, EE_K_SOFTMAX = 8, EE_K_COMPACT = 9, EE_K_ADMIT = 10,

@@ -22,7 +22,7 @@ EVENT_DT = np.dtype([("t_ns", "<i8"), ("kind", "<i4"), ("stage", "<i4"), ("b", "
 
 class ServeOpts(C.Structure):
     _fields_ = [("b_max", C.c_int32), ("clock", C.c_int32), ("t_slo_ns", C.c_int64), ("lut_ns", C.c_void_p),
-                ("min_incr", C.c_int32), ("refill", C.c_int32)]
+                ("min_incr", C.c_int32), ("refill", C.c_int32), ("t_timeout_ns", C.c_int64), ("lanes", C.c_int32), ("pad_", C.c_int32)]
 
 
 class ServeStats(C.Structure):
@@ -278,12 +278,12 @@ def forward_alone(blob, inputs):
 
 
 def serve_stream(blob, arrival_ns, pool, b_max, lut_ns, t_slo_ns=-1, min_incr=1, refill=1,
-                 forced_exit=None, n_stages=None, max_events=0):
+                 forced_exit=None, n_stages=None, max_events=0, t_timeout_ns=0, lanes=1):
     """Algorithm 1 on the virtual clock.  Returns (results, stats dict, events)."""
     arrival_ns = _c(arrival_ns, np.int64)
     n = arrival_ns.size
     lut_ns = _c(lut_ns, np.int64)
-    opts = ServeOpts(b_max, 1, t_slo_ns, lut_ns.ctypes.data, min_incr, refill)
+    opts = ServeOpts(b_max, 1, t_slo_ns, lut_ns.ctypes.data, min_incr, refill, t_timeout_ns, lanes, 0)
     stats = ServeStats()
     res = np.zeros(n, RESULT_DT)
     ev = np.zeros(max_events, EVENT_DT) if max_events else None

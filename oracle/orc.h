@@ -96,6 +96,9 @@ typedef struct {
     const int64_t* lut_ns;  /* [n_stages][b_max]: time of segment s entered with B = col+1 samples */
     int32_t min_incr;    /* smallest catch-up batch worth a preemption; 1 = as in the paper */
     int32_t refill;      /* 0 = model-level batching, 1 = Algorithm 1, 2 = stage pools (an extension, see orc_serve.c) */
+    int64_t t_timeout_ns; /* refill = 0: batch-forming window of adaptive batching (Sec. II-D); <= 0: batches are issued at once */
+    int32_t lanes;       /* refill = 2: steps that may be in flight at once, 1..4 (0 = 1) */
+    int32_t pad_;
 } orc_serve_opts;
 
 typedef struct { int64_t t_ns; int32_t kind; int32_t stage; int32_t b; int32_t aux; } orc_event;

@@ -26,7 +26,7 @@ SYMBOLS = ["ee_strerror", "ee_blob_check", "ee_create", "ee_destroy", "ee_query"
            "ee_compact_refill", "ee_serve_stream", "ee_schedule_sim", "ee_measure_lut", "ee_profile_enable",
            "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_last_logits", "ee_profile_reserve", "ee_autotune", "ee_config_table",
            "ee_pair_count", "ee_pair_mode", "ee_pair_table", "ee_config_set", "ee_pair_set", "ee_exit_head_static",
-           "ee_static_scratch_bytes"]
+           "ee_static_scratch_bytes", "ee_time_layer"]
 
 
 class Trace(C.Structure):
@@ -35,7 +35,7 @@ class Trace(C.Structure):
 
 class ServeOpts(C.Structure):
     _fields_ = [("b_max", C.c_int32), ("clock", C.c_int32), ("t_slo_ns", C.c_int64), ("lut_ns", C.c_void_p),
-                ("min_incr", C.c_int32), ("refill", C.c_int32)]
+                ("min_incr", C.c_int32), ("refill", C.c_int32), ("t_timeout_ns", C.c_int64), ("lanes", C.c_int32), ("pad_", C.c_int32)]
 
 
 class ServeStats(C.Structure):
@@ -64,6 +64,7 @@ _lib.ee_stage_forward.argtypes = [_V, C.c_int, C.c_int, _V, _V]
 _lib.ee_exit_head.argtypes = [_V, C.c_int, C.c_int, _V, C.c_float, _V, _V, _V, _V]
 _lib.ee_exit_head_static.argtypes = [_V, C.c_int, C.c_int, _V, C.c_float, _V, _V, _V, _V]
 _lib.ee_static_scratch_bytes.argtypes = []
+_lib.ee_time_layer.argtypes = [_V, C.c_int, C.c_int, C.c_int, C.c_int, _V, _V, _V]
 _lib.ee_compact_refill.argtypes = [_V, C.c_int, C.c_int, _V, _V, _V, _V, _V, _V, _V, C.c_int, _V, _V]
 _lib.ee_serve_stream.argtypes = [_V, C.POINTER(Trace), _V, C.POINTER(ServeOpts), _V, C.POINTER(ServeStats), _V, C.c_int64]
 _lib.ee_schedule_sim.argtypes = [C.c_int, C.POINTER(Trace), _V, C.POINTER(ServeOpts), _V, C.POINTER(ServeStats), _V, C.c_int64]
@@ -124,14 +125,14 @@ def _stats_dict(st, n_stages):
                 seg_samples=list(st.seg_samples)[:n_stages], n_events=st.n_events)
 
 
-def schedule_sim(n_stages, arrival_ns, forced_exit, b_max, lut_ns, t_slo_ns=-1, min_incr=1, refill=1, max_events=0):
+def schedule_sim(n_stages, arrival_ns, forced_exit, b_max, lut_ns, t_slo_ns=-1, min_incr=1, refill=1, max_events=0, t_timeout_ns=0, lanes=1):
     """ee_schedule_sim: Algorithm 1 on the virtual clock with forced exits (host only)."""
     arrival_ns = np.ascontiguousarray(arrival_ns, np.int64)
     forced_exit = np.ascontiguousarray(forced_exit, np.int32)
     lut_ns = np.ascontiguousarray(lut_ns, np.int64)
     n = arrival_ns.size
     tr = Trace(n, arrival_ns.ctypes.data)
-    opts = ServeOpts(b_max, 1, t_slo_ns, lut_ns.ctypes.data, min_incr, refill)
+    opts = ServeOpts(b_max, 1, t_slo_ns, lut_ns.ctypes.data, min_incr, refill, t_timeout_ns, lanes, 0)
     res = np.zeros(n, RESULT_DT)
     ev = np.zeros(max(max_events, 1), EVENT_DT)
     st = ServeStats()
@@ -215,14 +216,14 @@ class Engine:
         return dst[:b_merged], ids_dst[:b_merged], b_rem, b_merged
 
     # -- stream serving ----------------------------------------------------------------------
-    def serve_stream(self, arrival_ns, pool, lut_ns, b_max=None, clock=0, t_slo_ns=-1, min_incr=1, refill=1, max_events=0):
+    def serve_stream(self, arrival_ns, pool, lut_ns, b_max=None, clock=0, t_slo_ns=-1, min_incr=1, refill=1, max_events=0, t_timeout_ns=0, lanes=1):
         arrival_ns = np.ascontiguousarray(arrival_ns, np.int64)
         lut_ns = np.ascontiguousarray(lut_ns, np.int64)
         b_max = b_max or self.b_max
         assert lut_ns.shape == (self.n_stages, b_max)
         n = arrival_ns.size
         tr = Trace(n, arrival_ns.ctypes.data)
-        opts = ServeOpts(b_max, clock, t_slo_ns, lut_ns.ctypes.data, min_incr, refill)
+        opts = ServeOpts(b_max, clock, t_slo_ns, lut_ns.ctypes.data, min_incr, refill, t_timeout_ns, lanes, 0)
         res = np.zeros(n, RESULT_DT)
         ev = np.zeros(max(max_events, 1), EVENT_DT)
         st = ServeStats()
@@ -234,6 +235,15 @@ class Engine:
         lut = np.zeros((self.n_stages, self.b_max), np.int64)
         _chk(_lib.ee_measure_lut(self._h, reps, lut.ctypes.data))
         return lut
+
+    def time_layer(self, layer, b, cfg=0, reps=20):
+        """(microseconds per launch, 2 * MACs, algorithmic bytes) of one layer alone; None when the configuration does not exist"""
+        us, ops, byt = C.c_double(), C.c_double(), C.c_double()
+        rc = _lib.ee_time_layer(self._h, int(layer), int(b), int(cfg), int(reps), C.byref(us), C.byref(ops), C.byref(byt))
+        if rc == EE_ERR_DEVICE and cfg:
+            return None
+        _chk(rc)
+        return us.value, ops.value, byt.value
 
     def autotune(self, reps=5):
         _chk(_lib.ee_autotune(self._h, int(reps)))

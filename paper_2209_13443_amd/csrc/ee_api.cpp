@@ -585,11 +585,12 @@ extern "C" int ee_pair_count(const ee_ctx* ctx)
 }
 
 // ---- one backbone segment ------------------------------------------------------------------------
-int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool first_packed)
+int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool first_packed, int only_op, int cfg_force)
 {
     const StageDesc& st = net.stages[stage];
     const int dt = net.dtype, es = net.elem_bytes();
     for (int k = 0; k < st.n_ops; ++k) {
+        if (only_op >= 0 && st.first_op + k != only_op) continue;
         OpPlan& p = plans[st.first_op + k];
         const OpDesc& d = p.d;
         const void* src = resolve(this, p.src_buf, act_in, act_out);
@@ -615,8 +616,8 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                 e = timed(EE_K_PAD_INPUT, 0.0, pb, [&] { return launch_pad_input(src, pad_bufs[p.pad_buf], b, d.h_in, d.w_in, d.c_in, p.Hp, p.Wp, d.pad, dt, stream); });
                 if (e != hipSuccess) return EE_ERR_DEVICE;
             }
-            int cfg = forced_conv_tile();
-            if (p.pair && pair_mode > 0 && cfg == 0) {
+            int cfg = cfg_force > 0 ? cfg_force : forced_conv_tile();
+            if (p.pair && pair_mode > 0 && cfg == 0 && only_op < 0) {
                 // this layer and the next as one launch, unless the table says the two separate kernels are faster here
                 const int pc = p.pair_cfg.empty() ? 0 : p.pair_cfg[std::min<size_t>(bucket_of(b), p.pair_cfg.size() - 1)];
                 // untuned: fused below 32 samples, where it was measured to win (one launch fewer counts most there)
@@ -812,6 +813,39 @@ extern "C" int ee_measure_lut(ee_ctx* ctx, int reps, int64_t* lut_ns)
             lut_ns[(size_t)s * bm + b - 1] = (int64_t)std::llround(v);
         }
     }
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    ctx->profiling = was;
+    return rc;
+}
+
+// One layer alone, `reps` launches back to back on the workspace buffers (design-time measurement, like the tables above).
+extern "C" int ee_time_layer(ee_ctx* ctx, int layer, int b, int cfg, int reps, double* us_out, double* ops_out, double* bytes_out)
+{
+    if (!ctx || layer < 0 || layer >= (int)ctx->plans.size() || b < 1 || b > ctx->b_max || reps < 1 || reps > 100000 || cfg < 0 || !us_out) return EE_ERR_ARG;
+    int stage = -1;
+    for (size_t s = 0; s < ctx->net.stages.size(); ++s)
+        if (layer >= ctx->net.stages[s].first_op && layer < ctx->net.stages[s].first_op + ctx->net.stages[s].n_ops) stage = (int)s;
+    if (stage < 0) return EE_ERR_ARG;
+    const bool was = ctx->profiling;
+    ctx->profiling = false;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return EE_ERR_DEVICE;
+    int rc = EE_OK;
+    for (int pass = 0; pass < 2 && !rc; ++pass) {                   // pass 0 warms caches and code objects
+        const int n = pass == 0 ? 2 : reps;
+        hipEventRecord(e0, ctx->stream);
+        for (int r = 0; r < n && !rc; ++r) rc = ctx->run_stage(stage, b, ctx->in_buf[stage], ctx->out_buf[stage], false, layer, cfg);
+        hipEventRecord(e1, ctx->stream);
+        if (hipEventSynchronize(e1) != hipSuccess) rc = EE_ERR_DEVICE;
+        float ms = 0.f;
+        hipEventElapsedTime(&ms, e0, e1);
+        *us_out = (double)ms * 1e3 / n;
+    }
+    (void)hipGetLastError();
+    const OpPlan& p = ctx->plans[layer];
+    if (ops_out) *ops_out = p.ops_per_sample * b;
+    if (bytes_out) *bytes_out = p.bytes_per_sample * b + p.weight_bytes;
     hipEventDestroy(e0);
     hipEventDestroy(e1);
     ctx->profiling = was;

@@ -79,7 +79,9 @@ struct ee_ctx {
 
     // internal entry points shared by the C ABI and the stream driver (no argument checks)
     // first_packed: the first layer's folded input copy already holds these samples (admission wrote it)
-    int run_stage(int stage, int b_act, const void* act_in, void* act_out, bool first_packed = false);
+    // only_op >= 0: just that layer (an index into plans; fused pairs run as separate layers then);
+    // cfg_force > 0: that kernel configuration for every matrix-core layer instead of the table's
+    int run_stage(int stage, int b_act, const void* act_in, void* act_out, bool first_packed = false, int only_op = -1, int cfg_force = 0);
     // the plan of segment 0's first layer when that layer reads a folded copy admission can write directly, else null
     const ee::OpPlan* admission_fold() const
     {

@@ -153,3 +153,88 @@ def test_full_batches_under_overload(orc):
         assert np.count_nonzero(runs["b"] < b_max) <= E
     static, sst, _ = orc.serve_stream(None, zeros, None, b_max, lut, refill=0, forced_exit=forced, n_stages=E)
     assert st["end_time_ns"] < 0.8 * sst["end_time_ns"]
+
+
+# ---- several steps in flight (lanes) ------------------------------------------------------------------
+def serve_lanes(orc, arrivals, forced, b_max, lut, lanes, slo=-1):
+    return orc.serve_stream(None, np.asarray(arrivals, np.int64), None, b_max, np.asarray(lut, np.int64), t_slo_ns=slo, refill=2, lanes=lanes,
+                            forced_exit=np.asarray(forced, np.int32), n_stages=len(lut), max_events=400000)
+
+
+def test_two_lanes_timeline_worked_by_hand(orc):
+    """The six requests of the one-lane timeline above on two lanes (same table: T[s][b] = 10 (s + 1) + b, B_max = 2).
+    t=0    lane 0: segment 1 on {0,1} until 12; lane 1 idle (level 0 is in flight, the pools are empty)
+    t=12   0 leaves.  pool1 = [1].  lane 0: segment 1 on {2,3} until 24; lane 1: pool1 is not full, a step is running -> idle
+    t=24   nobody leaves.  pool1 = [1,2,3].  lane 0: segment 2 on {1,2} until 46; lane 1: segment 1 on {4,5} until 36
+    t=36   5 leaves.  pool1 = [3,4].  lane 1: level 1 is in flight, the queue is empty -> idle
+    t=46   1 leaves.  pool2 = [2].  lane 0: segment 2 on {3,4} until 68; lane 1: pool2 is not full -> idle
+    t=68   4 leaves.  pool2 = [2,3].  lane 0: segment 3 on {2,3} until 100: both leave."""
+    lut = [[10 * (s + 1) + b for b in (1, 2)] for s in range(3)]
+    res, st, ev = serve_lanes(orc, [0] * 6, [0, 1, 2, 2, 1, 0], 2, lut, lanes=2)
+    assert res["latency_ns"].tolist() == [12, 46, 100, 100, 68, 36]
+    assert [(int(e["t_ns"]), int(e["stage"]), int(e["b"]), int(e["aux"])) for e in ev[ev["kind"] == PROC]] == \
+        [(0, 0, 2, 0), (12, 0, 2, 0), (24, 1, 2, 0), (24, 0, 2, 1), (46, 1, 2, 0), (68, 2, 2, 0)]
+    assert st["end_time_ns"] == 100 and st["seg_runs"][:3] == [3, 2, 1]
+
+
+def test_idle_lane_starts_when_an_arrival_fills_a_batch(orc):
+    """B_max = 2, two segments, T[s][b] = 10 (s + 1) + b.  Requests 0, 1 arrive at 0 and leave at the last exit, requests 2, 3
+    arrive at 13 and 15 and leave at the first.  Lane 0 runs segment 1 on {0,1} until 12 and then segment 2 on them until 34.
+    At t = 13 the queue holds one request: not a full batch while a step is running, so lane 1 waits; at t = 15 it holds two and
+    lane 1 runs segment 1 on {2,3} until 27.  (While lane 0 ran segment 1 itself, lane 1 could not have: one step per level.)"""
+    lut = [[11, 12], [21, 22]]
+    res, st, ev = serve_lanes(orc, [0, 0, 13, 15], [1, 1, 0, 0], 2, lut, lanes=2)
+    assert [(int(e["t_ns"]), int(e["stage"]), int(e["b"]), int(e["aux"])) for e in ev[ev["kind"] == PROC]] == [(0, 0, 2, 0), (12, 1, 2, 0), (15, 0, 2, 1)]
+    assert res["latency_ns"].tolist() == [34, 34, 14, 12]
+    # one lane: the second batch waits for the first to finish
+    res1, _, _ = serve_lanes(orc, [0, 0, 13, 15], [1, 1, 0, 0], 2, lut, lanes=1)
+    assert res1["latency_ns"].tolist() == [34, 34, 33, 31]
+    # a single-segment network never overlaps: one step per level
+    res2, _, ev2 = serve_lanes(orc, [0, 0, 3, 5], [0, 0, 0, 0], 2, [[11, 12]], lanes=2)
+    assert [(int(e["t_ns"]), int(e["aux"])) for e in ev2[ev2["kind"] == PROC]] == [(0, 0), (12, 0)]
+
+
+@pytest.mark.parametrize("seed", range(5))
+@pytest.mark.parametrize("lanes", [2, 3, 4])
+def test_lanes_invariants(orc, seed, lanes):
+    b_max, E = 8, 4
+    arrivals, forced, lut = random_case(40 + seed, n=500, b_max=b_max, rate=[0.05, 0.3, 1.0, 0.02, 0.15][seed])
+    res, st, ev = serve_lanes(orc, arrivals, forced, b_max, lut, lanes)
+    assert np.array_equal(res["exit_idx"], forced)
+    proc = ev[ev["kind"] == PROC]
+    t0 = proc["t_ns"].astype(np.int64)
+    t1 = t0 + np.array([lut[int(s)][int(b) - 1] for s, b in zip(proc["stage"], proc["b"])])
+    order = np.argsort(t0, kind="stable")
+    assert np.array_equal(order, np.arange(len(proc)))                       # logged in time order
+    for k in range(len(proc)):
+        live = (t0[:k] <= t0[k]) & (t1[:k] > t0[k])                          # steps still running when step k starts
+        assert np.count_nonzero(live) < lanes
+        assert not np.any(proc["stage"][:k][live] == proc["stage"][k])       # one step per level at a time
+        assert not np.any(proc["aux"][:k][live] == proc["aux"][k])           # a lane runs one step at a time
+        if np.any(live):
+            assert proc["b"][k] == b_max                                     # beside a running step only full batches start
+    # first in, first out at every level: a level's batches take the samples in the order they reached it
+    done_at = res["latency_ns"] + arrivals
+    for s in range(E):
+        runs = proc[proc["stage"] == s]
+        ends = (runs["t_ns"].astype(np.int64) + np.array([lut[s][int(b) - 1] for b in runs["b"]]))
+        leavers = np.nonzero(forced == s)[0]
+        assert set(done_at[leavers].tolist()) <= set(ends.tolist())           # a sample completes when a step of its exit's segment ends
+    assert st["seg_samples"][0] == len(arrivals)
+    for s in range(1, E):
+        assert st["seg_samples"][s] == int(np.count_nonzero(forced >= s))
+    busy = int((t1 - t0).sum())
+    assert st["end_time_ns"] - arrivals[0] >= busy / lanes                    # work conservation
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_one_lane_is_the_plain_policy_and_more_lanes_finish_sooner_under_overload(orc, seed):
+    b_max = 8
+    _, forced, lut = random_case(60 + seed, n=1500, b_max=b_max)
+    zeros = np.zeros(len(forced), np.int64)
+    base = serve(orc, zeros, forced, b_max, lut)
+    one = serve_lanes(orc, zeros, forced, b_max, lut, 1)
+    assert np.array_equal(base[0], one[0]) and base[1] == one[1] and np.array_equal(base[2], one[2])
+    two = serve_lanes(orc, zeros, forced, b_max, lut, 2)
+    assert two[1]["end_time_ns"] < 0.75 * one[1]["end_time_ns"]               # the second lane is busy most of the time
+    assert two[1]["end_time_ns"] >= 0.5 * one[1]["end_time_ns"] - lut.max() * 8  # and cannot more than halve the time (up to the drain)

@@ -147,3 +147,73 @@ def test_min_incr_and_errors(orc):
     bad[10] = bad[9] - 1
     with pytest.raises(orc.OracleError):
         orc.serve_stream(None, bad, None, 8, lut, forced_exit=forced, n_stages=4)
+
+
+# ---- baselines of the evaluation: SERIAL and adaptive batching <B_max, T_timeout> ------------------------
+def test_adaptive_batching_timeline_by_hand(orc):
+    """B_max = 4, two segments of 10 each (any batch size), nobody leaves early, T_timeout = 20.
+    t=0   request 0 queued; window ends at 20; request 1 joins at 3; nothing else by 20 -> {0,1} issued at 20, done at 40
+    t=40  queue empty -> idle until 50; window ends at 70; 51, 52, 53 join: the batch is full at 53 -> issued at 53, done at 73
+    t=73  request 6 (arrived 54) has waited 19 < 20 -> issued at 74, done at 94"""
+    arrivals = np.array([0, 3, 50, 51, 52, 53, 54], np.int64)
+    forced = np.ones(7, np.int32)
+    lut = np.full((2, 4), 10, np.int64)
+    res, st, ev = orc.serve_stream(None, arrivals, None, 4, lut, refill=0, t_timeout_ns=20, forced_exit=forced, n_stages=2, max_events=64)
+    assert res["latency_ns"].tolist() == [40, 37, 23, 22, 21, 20, 40]
+    assert [(int(e["t_ns"]), int(e["b"])) for e in ev[ev["kind"] == KINDS["ROUND"]]] == [(20, 2), (53, 4), (74, 1)]
+    assert st["rounds"] == 3 and st["end_time_ns"] == 94
+    # a request that arrives exactly when the window ends still joins the batch
+    res, st, ev = orc.serve_stream(None, np.array([0, 20], np.int64), None, 4, lut, refill=0, t_timeout_ns=20, forced_exit=np.ones(2, np.int32), n_stages=2, max_events=8)
+    assert [(int(e["t_ns"]), int(e["b"])) for e in ev[ev["kind"] == KINDS["ROUND"]]] == [(20, 2)]
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_adaptive_batching_closed_forms(orc, seed):
+    b_max = 8
+    arrivals, forced, lut = random_case(70 + seed, n=240, b_max=b_max, rate=[0.01, 0.05, 0.3][seed])
+    plain = orc.serve_stream(None, arrivals, None, b_max, lut, refill=0, forced_exit=forced, n_stages=4, max_events=10000)
+    zero = orc.serve_stream(None, arrivals, None, b_max, lut, refill=0, t_timeout_ns=0, forced_exit=forced, n_stages=4, max_events=10000)
+    assert np.array_equal(plain[0], zero[0]) and plain[1] == zero[1]            # no window = model-level batching as it comes
+    # an endless window: every batch is full (240 = 30 * 8) and is issued when its last member has arrived and the server is free
+    res, st, ev = orc.serve_stream(None, arrivals, None, b_max, lut, refill=0, t_timeout_ns=10**15, forced_exit=forced, n_stages=4, max_events=10000)
+    rounds = ev[ev["kind"] == KINDS["ROUND"]]
+    assert len(rounds) == 30 and np.all(rounds["b"] == b_max)
+    free = 0
+    for k in range(30):
+        members = np.arange(8 * k, 8 * k + 8)
+        start = max(free, int(arrivals[members[-1]]))
+        assert int(rounds["t_ns"][k]) == start
+        t, alive = start, members
+        for s in range(4):                                                       # model-level batching: the batch shrinks, nothing joins
+            if len(alive) == 0:
+                break
+            t += int(lut[s][len(alive) - 1])
+            for m in alive[(forced[alive] == s) | (s == 3)]:
+                assert res["latency_ns"][m] == t - arrivals[m]
+            alive = alive[(forced[alive] > s) & (s < 3)]
+        free = t
+    # every window in between: nobody is issued before the window allows, nobody waits for batch forming longer than the window
+    for window in (50, 400, 3000):
+        res, st, ev = orc.serve_stream(None, arrivals, None, b_max, lut, refill=0, t_timeout_ns=window, forced_exit=forced, n_stages=4, max_events=10000)
+        rounds = ev[ev["kind"] == KINDS["ROUND"]]
+        first = 0
+        prev_end = None
+        procs = ev[ev["kind"] == KINDS["PROC"]]
+        for k, r in enumerate(rounds):
+            t, b = int(r["t_ns"]), int(r["b"])
+            oldest = int(arrivals[first])
+            assert b == b_max or t >= oldest + window                            # an incomplete batch only after the window
+            assert b == int(np.count_nonzero(arrivals[first:first + b_max] <= t))   # everyone who had arrived (up to B_max) is in it
+            first += b
+        assert first == len(arrivals)
+
+
+@pytest.mark.parametrize("seed", range(2))
+def test_serial_is_one_request_at_a_time(orc, seed):
+    arrivals, forced, lut = random_case(80 + seed, n=150, b_max=1, rate=0.004)
+    res, st, _ = orc.serve_stream(None, arrivals, None, 1, lut, refill=0, forced_exit=forced, n_stages=4)
+    done = 0
+    for k in range(len(arrivals)):
+        done = max(done, int(arrivals[k])) + int(lut[: forced[k] + 1, 0].sum())
+        assert res["latency_ns"][k] == done - arrivals[k]
+    assert st["rounds"] == len(arrivals)
