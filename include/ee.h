@@ -109,6 +109,10 @@ int ee_compact_refill(ee_ctx* ctx, int stage, int b_act, const uint8_t* exit_fla
                       const void* refill_act, const int32_t* refill_ids, int b_incr,
                       int* b_rem_out, int* b_merged_out);
 
+/* Set-up call for ee_serve_stream with lanes > 1: makes the context hold n lanes (1..4), i.e. allocates the workspace and the
+ * HIP stream (default priority) of the lanes it does not have yet.  Returns the number of lanes or a negative status. */
+int ee_lanes(ee_ctx* ctx, int n);
+
 /* ---- stream serving: Algorithm 1 with the criterion of Eq. (3) / Eq. (4) ------------------- */
 typedef struct { int64_t n; const int64_t* arrival_ns; /* host, non-decreasing */ } ee_trace;
 
@@ -120,6 +124,11 @@ typedef struct {
                                B = column + 1 samples (Sec. III-B, "Exit-Level Latency Prediction") */
     int32_t min_incr;       /* smallest B_incr worth a preemption; 1 = Algorithm 1 as printed */
     int32_t refill;         /* 0: model-level batching (no preemption); 1: Algorithm 1; 2: stage pools (below) */
+    int64_t t_timeout_ns;   /* refill = 0: batch-forming window T_timeout of adaptive batching <B_max, T_timeout> (Sec. II-D):
+                               a full batch is issued at once, an incomplete one when the oldest queued request has waited
+                               this long; <= 0: whatever is queued is issued at once.  B_max = 1 is the SERIAL baseline. */
+    int32_t lanes;          /* refill = 2: steps that may be in flight at once, 1..4 (0 = 1), at most what ee_lanes made */
+    int32_t pad_;
 } ee_serve_opts;
 
 /* refill = 2, stage pools, is an extension that is not in the paper.  Algorithm 1 keeps one active batch
@@ -132,6 +141,9 @@ typedef struct {
  *     run now but not if the preferred step runs first: T_rest < T_slack and not T_first + T_rest < T_slack,
  *     T_slack as in Eq. (3), T_rest and T_first from lut_ns at the entering batch sizes; the deepest such pool
  *     whose successor pool is not full (its survivors need room there).
+ * With lanes > 1 up to that many steps run concurrently on the GPU, each on a stream of its own: at most one step per
+ * level is in flight, a level whose successor pool holds a full batch does not run, and while some step is in flight
+ * an idle lane only starts full batches.  events: aux of EE_EV_PROC is the lane.
  * A pool never holds more than 2 b_max - 1 samples.  min_incr is not used.  stats: rounds = launches of
  * segment 0, criterion_evals / preemptions = evaluations of the SLO rule / times it changed the choice;
  * events: EE_EV_PROC per launch, EE_EV_CRITERION (stage = pool, b = its batch, aux = 1 if it goes first). */

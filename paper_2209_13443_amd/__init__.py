@@ -26,7 +26,7 @@ SYMBOLS = ["ee_strerror", "ee_blob_check", "ee_create", "ee_destroy", "ee_query"
            "ee_compact_refill", "ee_serve_stream", "ee_schedule_sim", "ee_measure_lut", "ee_profile_enable",
            "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_last_logits", "ee_profile_reserve", "ee_autotune", "ee_config_table",
            "ee_pair_count", "ee_pair_mode", "ee_pair_table", "ee_config_set", "ee_pair_set", "ee_exit_head_static",
-           "ee_static_scratch_bytes", "ee_time_layer"]
+           "ee_static_scratch_bytes", "ee_time_layer", "ee_lanes"]
 
 
 class Trace(C.Structure):
@@ -64,6 +64,7 @@ _lib.ee_stage_forward.argtypes = [_V, C.c_int, C.c_int, _V, _V]
 _lib.ee_exit_head.argtypes = [_V, C.c_int, C.c_int, _V, C.c_float, _V, _V, _V, _V]
 _lib.ee_exit_head_static.argtypes = [_V, C.c_int, C.c_int, _V, C.c_float, _V, _V, _V, _V]
 _lib.ee_static_scratch_bytes.argtypes = []
+_lib.ee_lanes.argtypes = [_V, C.c_int]
 _lib.ee_time_layer.argtypes = [_V, C.c_int, C.c_int, C.c_int, C.c_int, _V, _V, _V]
 _lib.ee_compact_refill.argtypes = [_V, C.c_int, C.c_int, _V, _V, _V, _V, _V, _V, _V, C.c_int, _V, _V]
 _lib.ee_serve_stream.argtypes = [_V, C.POINTER(Trace), _V, C.POINTER(ServeOpts), _V, C.POINTER(ServeStats), _V, C.c_int64]
@@ -230,6 +231,13 @@ class Engine:
         _chk(_lib.ee_serve_stream(self._h, C.byref(tr), pool.data_ptr(), C.byref(opts), res.ctypes.data, C.byref(st),
                                   ev.ctypes.data if max_events else None, max_events))
         return res, _stats_dict(st, self.n_stages), ev[:min(st.n_events, max_events)]
+
+    def set_lanes(self, n):
+        """ee_lanes: workspace and streams for n concurrent steps of the stage-pool policy; returns the lane count"""
+        rc = _lib.ee_lanes(self._h, int(n))
+        if rc < 0:
+            _chk(rc)
+        return rc
 
     def measure_lut(self, reps=3):
         lut = np.zeros((self.n_stages, self.b_max), np.int64)

@@ -199,6 +199,47 @@ void plan_buffers(ee_ctx* ctx)
     }
 }
 
+// The per-lane part of the workspace (the lane's stream, intermediate tensors and padded input copies are set by the
+// caller when they exist already).
+int alloc_lane(ee_ctx* ctx, LaneState& L)
+{
+    int rc = EE_OK;
+    const int n_st = (int)ctx->net.stages.size(), b_max = ctx->b_max;
+    if (L.pool.empty()) {
+        L.pool.resize(ctx->pool_sample_bytes.size(), nullptr);
+        for (size_t i = 0; i < L.pool.size(); ++i)
+            if ((rc = dev_alloc(ctx, &L.pool[i], ctx->pool_sample_bytes[i] * (size_t)b_max))) return rc;
+    }
+    if (L.pad_bufs.empty()) {
+        L.pad_bufs.resize(ctx->pad_buf_bytes.size(), nullptr);
+        for (size_t i = 0; i < L.pad_bufs.size(); ++i)
+            if ((rc = dev_alloc(ctx, &L.pad_bufs[i], ctx->pad_buf_bytes[i]))) return rc;
+    }
+    L.out_buf.assign(n_st, nullptr);
+    for (int s = 0; s < n_st; ++s)
+        if ((rc = dev_alloc(ctx, &L.out_buf[s], (size_t)ctx->stage_out_bytes(s) * b_max))) return rc;
+    if ((rc = dev_alloc(ctx, &L.in0, (size_t)ctx->stage_in_bytes(0) * b_max))) return rc;
+    if ((rc = dev_alloc(ctx, &L.sums, sizeof(int32_t) * (size_t)b_max * ctx->c_max))) return rc;
+    if ((rc = dev_alloc(ctx, &L.gap_partial, sizeof(int32_t) * ((size_t)b_max + 1024) * ctx->c_max))) return rc;
+    if ((rc = dev_alloc(ctx, &L.logits, 4 * (size_t)b_max * ctx->net.n_classes))) return rc;
+    if ((rc = dev_alloc(ctx, &L.d_label, sizeof(int32_t) * (size_t)b_max))) return rc;
+    if ((rc = dev_alloc(ctx, &L.d_conf, sizeof(float) * (size_t)b_max))) return rc;
+    if ((rc = dev_alloc(ctx, &L.d_score, sizeof(int64_t) * (size_t)b_max))) return rc;
+    if ((rc = dev_alloc(ctx, &L.d_flag, (size_t)b_max + 16))) return rc;
+    if ((rc = dev_alloc(ctx, &L.d_arrive, 64))) return rc;
+    const size_t out_bytes = round_up((int)(sizeof(HostOutcome) * (size_t)b_max), 256), ids_bytes = round_up(4 * b_max, 256);
+    if (hipHostMalloc(&L.h_pinned, out_bytes + 2 * ids_bytes + 256, hipHostMallocCoherent) != hipSuccess) return EE_ERR_DEVICE;
+    std::memset(L.h_pinned, 0, out_bytes + 2 * ids_bytes + 256);
+    unsigned char* hp = static_cast<unsigned char*>(L.h_pinned);
+    L.h_out = reinterpret_cast<HostOutcome*>(hp);
+    L.h_ids[0] = reinterpret_cast<int32_t*>(hp + out_bytes);
+    L.h_ids[1] = reinterpret_cast<int32_t*>(hp + out_bytes + ids_bytes);
+    L.h_seq = reinterpret_cast<unsigned*>(hp + out_bytes + 2 * ids_bytes);
+    for (int s = 0; s < 8; ++s)
+        if (hipEventCreateWithFlags(&L.packed[s], hipEventDisableTiming) != hipSuccess) return EE_ERR_DEVICE;
+    return EE_OK;
+}
+
 void* resolve(ee_ctx* ctx, int buf, const void* ext_in, void* ext_out)
 {
     if (buf == BUF_EXT_IN) return const_cast<void*>(ext_in);
@@ -276,6 +317,7 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
             if ((rc = dev_alloc(ctx, &pb, bytes + 256))) return fail(rc);
             p.pad_buf = (int)ctx->pad_bufs.size();
             ctx->pad_bufs.push_back(pb);
+            ctx->pad_buf_bytes.push_back(bytes + 256);
         }
         if (p.ci_eff == 0) p.ci_eff = d.c_in;
     }
@@ -314,39 +356,62 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
         if ((rc = upload(ctx, &ctx->wfc_dev[s], w)) || (rc = upload(ctx, &ctx->bfc_dev[s], b))) return fail(rc);
         if (ctx->stage_out_bytes(s) % 16 != 0 || ctx->stage_in_bytes(s) % 16 != 0) return fail(EE_ERR_UNSUPPORTED);
     }
-    if ((rc = dev_alloc(ctx, &ctx->sums, sizeof(int32_t) * (size_t)b_max * c_max))) return fail(rc);
-    if ((rc = dev_alloc(ctx, &ctx->gap_partial, sizeof(int32_t) * ((size_t)b_max + 1024) * c_max))) return fail(rc);
-    if ((rc = dev_alloc(ctx, &ctx->logits, 4 * (size_t)b_max * ctx->net.n_classes))) return fail(rc);
+    ctx->c_max = (size_t)c_max;
     if ((rc = dev_alloc(ctx, &ctx->d_count, 64))) return fail(rc);
     if ((rc = dev_alloc(ctx, &ctx->zero_page, 256))) return fail(rc);
-
-    // stream-serving workspace: packed input slots and raw output slots of every segment.  Behind the first
-    // segment the input slots are twice b_max: the stage-pool policy keeps up to 2 b_max - 1 waiting samples there.
-    ctx->in_buf.resize(n_st);
-    ctx->out_buf.resize(n_st);
-    for (int s = 0; s < n_st; ++s) {
-        if ((rc = dev_alloc(ctx, &ctx->in_buf[s], (size_t)ctx->stage_in_bytes(s) * b_max * (s ? 2 : 1)))) return fail(rc);
-        if ((rc = dev_alloc(ctx, &ctx->out_buf[s], (size_t)ctx->stage_out_bytes(s) * b_max))) return fail(rc);
-    }
     if ((rc = dev_alloc(ctx, &ctx->d_ids, sizeof(int32_t) * (size_t)b_max))) return fail(rc);
-    if ((rc = dev_alloc(ctx, &ctx->d_label, sizeof(int32_t) * (size_t)b_max))) return fail(rc);
-    if ((rc = dev_alloc(ctx, &ctx->d_conf, sizeof(float) * (size_t)b_max))) return fail(rc);
-    if ((rc = dev_alloc(ctx, &ctx->d_score, sizeof(int64_t) * (size_t)b_max))) return fail(rc);
-    if ((rc = dev_alloc(ctx, &ctx->d_flag, (size_t)b_max + 16))) return fail(rc);
-    if ((rc = dev_alloc(ctx, &ctx->d_arrive, 64))) return fail(rc);
+
+    // stream-serving workspace.  Shared by all lanes: the packed input slots of every segment behind the first, a ring of
+    // 3 b_max samples (the stage-pool policy keeps up to 2 b_max - 1 waiting samples there while a batch of up to b_max
+    // is being read).  Per lane: everything alloc_lane makes; lane 0 is made here on the caller's stream.
+    ctx->in_buf.assign(n_st, nullptr);
+    for (int s = 1; s < n_st; ++s)
+        if ((rc = dev_alloc(ctx, &ctx->in_buf[s], (size_t)ctx->stage_in_bytes(s) * b_max * 3))) return fail(rc);
+    ctx->lanes.resize(1);
     {
-        const size_t out_bytes = round_up((int)(sizeof(HostOutcome) * (size_t)b_max), 256), ids_bytes = round_up(4 * b_max, 256);
-        if (hipHostMalloc(&ctx->h_pinned, out_bytes + 2 * ids_bytes + 256, hipHostMallocCoherent) != hipSuccess) return fail(EE_ERR_DEVICE);
-        std::memset(ctx->h_pinned, 0, out_bytes + 2 * ids_bytes + 256);
-        unsigned char* hp = static_cast<unsigned char*>(ctx->h_pinned);
-        ctx->h_out = reinterpret_cast<HostOutcome*>(hp);
-        ctx->h_ids[0] = reinterpret_cast<int32_t*>(hp + out_bytes);
-        ctx->h_ids[1] = reinterpret_cast<int32_t*>(hp + out_bytes + ids_bytes);
-        ctx->h_seq = reinterpret_cast<unsigned*>(hp + out_bytes + 2 * ids_bytes);
+        LaneState& L0 = ctx->lanes[0];
+        L0.stream = ctx->stream;
+        L0.pool = ctx->pool;
+        L0.pad_bufs = ctx->pad_bufs;
+        if ((rc = alloc_lane(ctx, L0))) return fail(rc);
+        ctx->lane = -1;
+        ctx->bind_lane(0);
     }
     if (hipDeviceSynchronize() != hipSuccess) return fail(EE_ERR_DEVICE);
     *out = ctx;
     return EE_OK;
+}
+
+void ee_ctx::bind_lane(int j)
+{
+    if (j == lane) return;
+    if (lane >= 0) {                              // the counters of the lane that was bound travel back
+        lanes[(size_t)lane].seq = seq;
+        lanes[(size_t)lane].ids_turn = ids_turn;
+    }
+    const ee::LaneState& L = lanes[(size_t)j];
+    stream = L.stream; pool = L.pool; pad_bufs = L.pad_bufs; out_buf = L.out_buf; in_buf[0] = L.in0;
+    sums = L.sums; gap_partial = L.gap_partial; logits = L.logits;
+    d_label = L.d_label; d_conf = L.d_conf; d_score = L.d_score; d_flag = L.d_flag; d_arrive = L.d_arrive;
+    h_out = L.h_out; h_ids[0] = L.h_ids[0]; h_ids[1] = L.h_ids[1]; h_seq = L.h_seq; seq = L.seq; ids_turn = L.ids_turn;
+    lane = j;
+}
+
+// Further lanes for the stream driver (a set-up call, like ee_autotune: it allocates their workspace and streams).
+extern "C" int ee_lanes(ee_ctx* ctx, int n)
+{
+    if (!ctx || n < 1 || n > 4) return EE_ERR_ARG;
+    ctx->bind_lane(0);
+    while ((int)ctx->lanes.size() < n) {
+        LaneState L;
+        if (hipStreamCreateWithFlags(&L.stream, hipStreamNonBlocking) != hipSuccess) return EE_ERR_DEVICE;   // default priority
+        L.own_stream = true;
+        const int rc = alloc_lane(ctx, L);
+        ctx->lanes.push_back(L);                  // kept also on failure: ee_destroy releases what it holds
+        if (rc) return rc;
+    }
+    if (hipDeviceSynchronize() != hipSuccess) return EE_ERR_DEVICE;
+    return (int)ctx->lanes.size();
 }
 
 extern "C" int ee_destroy(ee_ctx* ctx)
@@ -354,7 +419,12 @@ extern "C" int ee_destroy(ee_ctx* ctx)
     if (!ctx) return EE_OK;
     hipDeviceSynchronize();
     for (void* p : ctx->owned) hipFree(p);
-    if (ctx->h_pinned) hipHostFree(ctx->h_pinned);
+    for (ee::LaneState& L : ctx->lanes) {
+        if (L.h_pinned) hipHostFree(L.h_pinned);
+        for (int s = 0; s < 8; ++s) if (L.packed[s]) hipEventDestroy(L.packed[s]);
+        if (L.own_stream && L.stream) hipStreamDestroy(L.stream);
+    }
+    ctx->h_pinned = nullptr;
     for (ProfRec& r : ctx->prof) { hipEventDestroy(r.e0); hipEventDestroy(r.e1); }
     delete ctx;
     return EE_OK;
@@ -433,6 +503,7 @@ hipError_t ee_ctx::launch_pair(int op, int b, const void* src, void* dst, const 
 extern "C" int ee_autotune(ee_ctx* ctx, int reps)
 {
     if (!ctx || reps < 1 || reps > 1000) return EE_ERR_ARG;
+    ctx->bind_lane(0);
     const bool was = ctx->profiling;
     ctx->profiling = false;
     hipEvent_t e0, e1;
@@ -658,6 +729,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
 extern "C" int ee_stage_forward(ee_ctx* ctx, int stage, int b_act, const void* act_in, void* act_out)
 {
     if (!ctx || stage < 0 || stage >= (int)ctx->net.stages.size() || b_act < 0 || b_act > ctx->b_max) return EE_ERR_ARG;
+    ctx->bind_lane(0);
     if (b_act == 0) return EE_OK;
     if (!act_in || !act_out || act_in == act_out || !aligned16(act_in) || !aligned16(act_out)) return EE_ERR_ARG;
     return ctx->run_stage(stage, b_act, act_in, act_out);
@@ -691,6 +763,7 @@ extern "C" int ee_exit_head(ee_ctx* ctx, int stage, int b_act, const void* act, 
                             int32_t* label, float* conf, int64_t* score, uint8_t* exit_flag)
 {
     if (!ctx || stage < 0 || stage >= (int)ctx->net.stages.size() || b_act < 0 || b_act > ctx->b_max) return EE_ERR_ARG;
+    ctx->bind_lane(0);
     if (b_act == 0) return EE_OK;
     if (!act || !label || !conf || !score || !exit_flag || !aligned16(act)) return EE_ERR_ARG;
     return ctx->run_head(stage, b_act, act, thr, label, conf, score, exit_flag);
@@ -702,6 +775,7 @@ extern "C" int ee_exit_head_static(ee_ctx* ctx, int stage, int b_act, const void
                                    int32_t* label, float* conf, int64_t* score, uint8_t* exit_flag)
 {
     if (!ctx || stage < 0 || stage >= (int)ctx->net.stages.size() || b_act < 0 || b_act > ctx->b_max) return EE_ERR_ARG;
+    ctx->bind_lane(0);
     if (b_act == 0) return EE_OK;
     if (!act || !label || !conf || !score || !exit_flag || !aligned16(act)) return EE_ERR_ARG;
     const ExitDesc& e = ctx->net.exits[stage];
@@ -725,6 +799,7 @@ extern "C" int ee_static_scratch_bytes(void) { return EE_STATIC_SCRATCH_BYTES; }
 extern "C" int ee_last_logits(ee_ctx* ctx, int b_act, void* host_out)
 {
     if (!ctx || !host_out || b_act < 0 || b_act > ctx->b_max) return EE_ERR_ARG;
+    ctx->bind_lane(0);
     if (hipStreamSynchronize(ctx->stream) != hipSuccess) return EE_ERR_DEVICE;
     if (b_act && hipMemcpy(host_out, ctx->logits, 4 * (size_t)b_act * ctx->net.n_classes, hipMemcpyDeviceToHost) != hipSuccess) return EE_ERR_DEVICE;
     return EE_OK;
@@ -737,6 +812,7 @@ extern "C" int ee_compact_refill(ee_ctx* ctx, int stage, int b_act, const uint8_
                                  int* b_rem_out, int* b_merged_out)
 {
     if (!ctx || stage < 0 || stage >= (int)ctx->net.stages.size() || b_act < 0 || b_incr < 0 || b_act + b_incr > ctx->b_max) return EE_ERR_ARG;
+    ctx->bind_lane(0);
     if (b_act > 0 && (!exit_flag || !act_src || !aligned16(act_src))) return EE_ERR_ARG;
     if (b_incr > 0 && (!refill_act || !aligned16(refill_act))) return EE_ERR_ARG;
     if ((b_act > 0 || b_incr > 0) && (!act_dst || !aligned16(act_dst) || act_dst == act_src || act_dst == refill_act)) return EE_ERR_ARG;
@@ -774,6 +850,7 @@ extern "C" int ee_compact_refill(ee_ctx* ctx, int stage, int b_act, const uint8_
 extern "C" int ee_measure_lut(ee_ctx* ctx, int reps, int64_t* lut_ns)
 {
     if (!ctx || !lut_ns || reps < 1) return EE_ERR_ARG;
+    ctx->bind_lane(0);
     const int n_st = (int)ctx->net.stages.size(), bm = ctx->b_max;
     const bool was = ctx->profiling;
     ctx->profiling = false;
@@ -823,6 +900,7 @@ extern "C" int ee_measure_lut(ee_ctx* ctx, int reps, int64_t* lut_ns)
 extern "C" int ee_time_layer(ee_ctx* ctx, int layer, int b, int cfg, int reps, double* us_out, double* ops_out, double* bytes_out)
 {
     if (!ctx || layer < 0 || layer >= (int)ctx->plans.size() || b < 1 || b > ctx->b_max || reps < 1 || reps > 100000 || cfg < 0 || !us_out) return EE_ERR_ARG;
+    ctx->bind_lane(0);
     int stage = -1;
     for (size_t s = 0; s < ctx->net.stages.size(); ++s)
         if (layer >= ctx->net.stages[s].first_op && layer < ctx->net.stages[s].first_op + ctx->net.stages[s].n_ops) stage = (int)s;
@@ -874,7 +952,8 @@ extern "C" int ee_profile_reserve(ee_ctx* ctx, int64_t n_pairs)
 extern "C" int ee_profile_read(ee_ctx* ctx, ee_kernel_stat* stats, ee_kernel_stat* per_layer)
 {
     if (!ctx || !stats) return EE_ERR_ARG;
-    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return EE_ERR_DEVICE;
+    for (const LaneState& L : ctx->lanes)
+        if (hipStreamSynchronize(L.stream) != hipSuccess) return EE_ERR_DEVICE;
     for (int k = 0; k < EE_K_COUNT; ++k) stats[k] = ee_kernel_stat{0, 0.0, 0.0, 0.0};
     if (per_layer)
         for (size_t k = 0; k < ctx->plans.size(); ++k) per_layer[k] = ee_kernel_stat{0, 0.0, 0.0, 0.0};

@@ -28,6 +28,24 @@ struct OpPlan {
     double ops_per_sample = 0, bytes_per_sample = 0, weight_bytes = 0;
 };
 
+// What one lane of the stream driver owns: a HIP stream, the intermediate tensors of a segment, the raw segment
+// outputs, the exit head's scratch and outputs, and its block of pinned host memory.  Steps on different lanes
+// run concurrently on the GPU; the input rings of the segments behind the first are shared by all lanes.
+struct LaneState {
+    hipStream_t stream = nullptr;
+    bool own_stream = false;
+    std::vector<void*> pool, pad_bufs, out_buf;
+    void* in0 = nullptr;                         // input slots of the first segment
+    int32_t* sums = nullptr; int32_t* gap_partial = nullptr; void* logits = nullptr;
+    int32_t* d_label = nullptr; float* d_conf = nullptr; int64_t* d_score = nullptr; uint8_t* d_flag = nullptr;
+    unsigned* d_arrive = nullptr;
+    void* h_pinned = nullptr; HostOutcome* h_out = nullptr; int32_t* h_ids[2] = {nullptr, nullptr}; unsigned* h_seq = nullptr;
+    unsigned seq = 0;
+    int ids_turn = 0;
+    hipEvent_t packed[8] = {};                   // recorded behind this lane's latest compaction into segment s's input ring
+    bool packed_set[8] = {};
+};
+
 struct HeadScratch { int32_t* sums; int32_t* gap_partial; void* logits; };
 
 struct ProfRec { int cls; int op; hipEvent_t e0, e1; double ops, bytes; };
@@ -61,6 +79,12 @@ struct ee_ctx {
     unsigned* d_arrive = nullptr;                // device counter of exit-head workgroups that have finished
     int ids_turn = 0;
     int pair_mode = 1;                           // fused layer pairs: 0 never, 1 as the table says, 2 wherever possible
+    // lanes of the stream driver: lanes[lane] is a copy of the per-lane members above while that lane is bound
+    std::vector<ee::LaneState> lanes;
+    int lane = 0;
+    std::vector<size_t> pad_buf_bytes;           // size of every padded / folded input copy, for further lanes
+    size_t c_max = 0;                            // widest exit head
+    void bind_lane(int j);                       // makes lane j's stream and buffers the ones the launchers use
     // kernel timing
     bool profiling = false;
     std::vector<ee::ProfRec> prof;

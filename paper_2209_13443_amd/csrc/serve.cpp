@@ -31,6 +31,7 @@ struct SlotOutcome { uint8_t flag; int32_t label; float conf; int64_t score; };
 
 // ---- clocks -----------------------------------------------------------------------------------
 struct VirtualClock {
+    static constexpr bool is_virtual = true;
     const int64_t* lut; int b_max; int64_t t;
     void start(int64_t t0) { t = t0; }
     int64_t now() { return t; }
@@ -39,6 +40,7 @@ struct VirtualClock {
 };
 
 struct WallClock {
+    static constexpr bool is_virtual = false;
     std::chrono::steady_clock::time_point origin; int64_t t0;
     void start(int64_t first_arrival) { origin = std::chrono::steady_clock::now(); t0 = first_arrival; }
     int64_t now() { return t0 + std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - origin).count(); }
@@ -58,12 +60,27 @@ struct WallClock {
 // row k of that segment's packed input buffer.
 struct TableExec {
     const int32_t* forced; int n_stages;
-    int admit(const int32_t*, int) { return EE_OK; }
+    std::vector<SlotOutcome> held[4];            // lanes: the outcomes of the step a lane is running
+    int lanes() const { return 4; }
+    int admit(int, const int32_t*, int) { return EE_OK; }
     int segment(int stage, const int32_t* ids, int b, SlotOutcome* out, int, int, int)
     {
         for (int k = 0; k < b; ++k) out[k] = SlotOutcome{(uint8_t)(stage == n_stages - 1 || forced[ids[k]] == stage), -1, 0.f, 0};
         return EE_OK;
     }
+    int launch(int lane, int stage, const int32_t* ids, int b, int, int, int)
+    {
+        held[lane].resize((size_t)b);
+        return segment(stage, ids, b, held[lane].data(), 0, 0, 0);
+    }
+    bool done(int) { return true; }
+    int collect(int lane, int b, SlotOutcome* out)
+    {
+        for (int k = 0; k < b; ++k) out[k] = held[lane][(size_t)k];
+        return EE_OK;
+    }
+    int pack(int, int, int, int, int, int) { return EE_OK; }
+    void book_pack(int, int, int) {}
 };
 
 struct GpuExec {
@@ -73,8 +90,10 @@ struct GpuExec {
     // A0: copy the queued inputs into slots [0, b) of segment 0's input buffer.  The kernel reads the
     // request ids straight from pinned host memory; two id blocks are used in turn, and an exit-head wait
     // lies between two admissions, so a block is never rewritten while a kernel may still read it.
-    int admit(const int32_t* ids, int b)
+    int lanes() const { return (int)ctx->lanes.size(); }
+    int admit(int lane, const int32_t* ids, int b)
     {
+        ctx->bind_lane(lane);
         int32_t* h_ids = ctx->h_ids[ctx->ids_turn];
         ctx->ids_turn ^= 1;
         std::memcpy(h_ids, ids, sizeof(int32_t) * (size_t)b);
@@ -100,6 +119,7 @@ struct GpuExec {
     // into pinned host memory and stores a sequence word when they are complete; the host polls that word.
     int segment(int stage, const int32_t*, int b, SlotOutcome* out, int src_off, int dst_off, int ring_rows)
     {
+        ctx->bind_lane(0);
         const unsigned char* in = (const unsigned char*)ctx->in_buf[stage] + (int64_t)src_off * ctx->stage_in_bytes(stage);
         int rc = ctx->run_stage(stage, b, in, ctx->out_buf[stage], stage == 0 && ctx->admission_fold() != nullptr);
         if (!rc) rc = ctx->run_head(stage, b, ctx->out_buf[stage], ctx->net.exits[stage].thr, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag, true);
@@ -123,6 +143,66 @@ struct GpuExec {
         // the compaction launch was booked before B_rem was known: only the survivors are read and written
         if (compact_rec >= 0) ctx->prof[(size_t)compact_rec].bytes = 2.0 * (double)ctx->stage_out_bytes(stage) * kept;
         return EE_OK;
+    }
+    // ---- several steps in flight: the same device work in three parts -----------------------------------------
+    // launch: segment and exit head of the b samples in input slots [src_off, src_off + b) on the lane's stream.  Rows that
+    // another lane's compaction kernel wrote are waited for with that lane's event.  eager_dst >= 0: the compaction into
+    // the next segment's ring at that row follows right behind the head (single-lane serving: nothing can change the
+    // ring before this step ends).
+    int launch(int lane, int stage, const int32_t*, int b, int src_off, int eager_dst, int ring_rows)
+    {
+        ctx->bind_lane(lane);
+        if (stage > 0)
+            for (size_t j = 0; j < ctx->lanes.size(); ++j)
+                if ((int)j != lane && ctx->lanes[j].packed_set[stage] && hipStreamWaitEvent(ctx->stream, ctx->lanes[j].packed[stage], 0) != hipSuccess)
+                    return EE_ERR_DEVICE;
+        const unsigned char* in = (const unsigned char*)ctx->in_buf[stage] + (int64_t)src_off * ctx->stage_in_bytes(stage);
+        int rc = ctx->run_stage(stage, b, in, ctx->out_buf[stage], stage == 0 && ctx->admission_fold() != nullptr);
+        if (!rc) rc = ctx->run_head(stage, b, ctx->out_buf[stage], ctx->net.exits[stage].thr, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag, true);
+        if (!rc && eager_dst >= 0) rc = pack(lane, stage, b, -1, eager_dst, ring_rows);
+        return rc;
+    }
+    bool done(int lane)
+    {
+        const LaneState& L = ctx->lanes[(size_t)lane];
+        const unsigned want = lane == ctx->lane ? ctx->seq : L.seq;
+        return __atomic_load_n(L.h_seq, __ATOMIC_ACQUIRE) == want;
+    }
+    int collect(int lane, int b, SlotOutcome* out)
+    {
+        ctx->bind_lane(lane);
+        const int rc = wait_outcomes();
+        if (rc) return rc;
+        for (int k = 0; k < b; ++k) {
+            const HostOutcome& h = ctx->h_out[k];
+            out[k] = SlotOutcome{(uint8_t)h.flag, h.label, h.conf, h.score};
+        }
+        return EE_OK;
+    }
+    // compaction of the lane's step into the next segment's ring at row dst_off; kept: the survivors, when known (timing books)
+    int pack(int lane, int stage, int b, int kept, int dst_off, int ring_rows)
+    {
+        if (stage + 1 >= (int)ctx->in_buf.size()) return EE_OK;
+        ctx->bind_lane(lane);
+        const int64_t sb = ctx->stage_out_bytes(stage);
+        hipError_t e = ctx->timed(EE_K_COMPACT, 0.0, 2.0 * sb * (kept >= 0 ? kept : b), [&] {
+            return launch_compact(ctx->d_flag, ctx->out_buf[stage], ctx->in_buf[stage + 1], nullptr, nullptr, b, sb, dst_off, ring_rows, nullptr, nullptr, ctx->stream);
+        });
+        if (e != hipSuccess) return EE_ERR_DEVICE;
+        pack_rec[lane] = ctx->profiling ? (long long)ctx->prof_used - 1 : -1;
+        LaneState& L = ctx->lanes[(size_t)lane];
+        if (ctx->lanes.size() > 1) {
+            if (hipEventRecord(L.packed[stage + 1], ctx->stream) != hipSuccess) return EE_ERR_DEVICE;
+            L.packed_set[stage + 1] = true;
+        }
+        return EE_OK;
+    }
+    long long pack_rec[4] = {-1, -1, -1, -1};     // timing record of each lane's latest compaction launch
+    // a compaction that was launched before its step's outcome was known is booked with the survivors that really moved
+    void book_pack(int lane, int stage, int kept)
+    {
+        if (pack_rec[lane] >= 0 && ctx->profiling) ctx->prof[(size_t)pack_rec[lane]].bytes = 2.0 * (double)ctx->stage_out_bytes(stage) * kept;
+        pack_rec[lane] = -1;
     }
     int wait_outcomes()
     {
@@ -213,6 +293,7 @@ public:
         while (completed < n && !rc) {
             admit_arrivals();
             if (queued() == 0) { clock.idle_until(arrival[arrived]); admit_arrivals(); }
+            if (opts.refill == 0 && opts.t_timeout_ns > 0) wait_for_batch();
             rc = start_round();
             for (int i = 0; i < E && !rc && b_act > 0; ++i) {
                 rc = proc_until_exit(active.data(), b_act, i, /*catchup=*/false, 0, /*merge_at=*/0, 0);
@@ -228,13 +309,30 @@ private:
     std::vector<int32_t> active, fresh;      // request ids per slot
     int b_act = 0;
 
+    // Adaptive batching <B_max, T_timeout> (Sec. II-D): a full batch is issued at once, an incomplete one when the
+    // batch-forming window, counted from the arrival of the oldest queued request, has passed.
+    void wait_for_batch()
+    {
+        while (queued() < opts.b_max) {
+            const int64_t deadline = arrival[Base::popped] + opts.t_timeout_ns;
+            if (clock.now() >= deadline) break;
+            if (arrived < n && arrival[arrived] <= deadline) {
+                clock.idle_until(arrival[arrived]);
+                admit_arrivals();
+            } else {
+                clock.idle_until(deadline);
+                break;
+            }
+        }
+    }
+
     int start_round()
     {
         b_act = (int)std::min<int64_t>(queued(), opts.b_max);                 // B_act <- min(N_Q, B_max)
         pop(active.data(), b_act);
         stats->rounds++;
         log(EE_EV_ROUND, 0, b_act, 0);
-        return exec.admit(active.data(), b_act);
+        return exec.admit(0, active.data(), b_act);
     }
 
     // The inner loop of Algorithm 1 at exit i: while there is room, take B_incr requests, check the
@@ -264,7 +362,7 @@ private:
             stats->preemptions++;                                                 // the survivors stay parked in their slots
             int b_new = b_incr;
             pop(fresh.data(), b_new);
-            int rc = exec.admit(fresh.data(), b_new);
+            int rc = exec.admit(0, fresh.data(), b_new);
             for (int s = 0; s <= i && !rc && b_new > 0; ++s)                      // catch-up run, no nested refill
                 rc = proc_until_exit(fresh.data(), b_new, s, true, 0, s == i ? b_rem : 0, 0);
             if (rc) return rc;
@@ -279,28 +377,37 @@ private:
 
 // ---- stage pools (extension) ------------------------------------------------------------------------------
 // Level 0 is the arrival queue; level i >= 1 is a first-in first-out pool of the samples that survived
-// exit i-1, parked in segment i's input slots, which form a ring of 2 B_max rows.  A batch is the front
-// min(n_i, B_max) samples of one level.  Which level runs next:
-//   the preferred level is the deepest one that holds a full batch; failing that the deepest non-empty pool
-//   (samples in flight finish before new ones start); failing that the queue; failing that the server idles;
-//   with an SLO, a pool whose oldest sample still meets it if the pool's remaining segments run now
-//   (T_rest < T_slack, Eq. 3 with the latency table) but not if the preferred step runs first
-//   (not T_first + T_rest < T_slack) goes first instead, the deepest such pool whose successor is not full.
-// A segment never runs while the pool behind it holds a full batch, so a pool never exceeds 2 B_max - 1
-// samples; batches start at ring row 0 or B_max and never wrap (a pool that is emptied restarts at row 0).
+// exit i-1, parked in segment i's input slots.  A batch is the front min(n_i, B_max) samples of one level.
+// The server has 1..4 lanes; a lane is idle or runs one step (one segment on one batch), and at most one step
+// per level is in flight.  Whenever the clock reaches an event:
+//   1. the steps that have ended are booked, earliest first: samples that exit complete at the step's end, the
+//      survivors join the next level in slot order;
+//   2. arrivals join the queue;
+//   3. every idle lane, lowest first, may start a step.  A level is eligible when no step of it is in flight, it
+//      is not empty and its successor has room (fewer than B_max waiting); while a step is in flight only full
+//      batches are eligible.  Preferred: the deepest eligible level holding a full batch; failing that the deepest
+//      eligible pool (samples in flight finish before new ones start); failing that the queue; else the lane idles.
+//      With an SLO, a pool whose oldest sample still meets it if the pool's remaining segments run now
+//      (T_rest < T_slack, Eq. 3 with the latency table) but not if the preferred step runs first
+//      (not T_first + T_rest < T_slack) goes first instead, the deepest such pool whose successor has room;
+//   4. the clock moves on to the next end of a step, or to the next arrival when a lane is idle.
+// Memory: segment i's input slots form a ring of three blocks of B_max rows.  A pool's content starts on a block
+// boundary and is shorter than two blocks, a batch never crosses a boundary, and the content always starts in the
+// block behind the batch that was taken last, so the rows a running step still reads are never written.
 template <class Exec, class Clock>
 class PoolScheduler : ServeBase<Exec, Clock> {
     using Base = ServeBase<Exec, Clock>;
     using Base::exec; using Base::clock; using Base::E; using Base::n; using Base::arrival; using Base::opts; using Base::stats;
     using Base::arrived; using Base::completed; using Base::queued; using Base::admit_arrivals; using Base::lut; using Base::log;
-    using Base::pop; using Base::proc_until_exit;
+    using Base::pop; using Base::results; using Base::outcome;
 
 public:
     PoolScheduler(Exec& ex, Clock& ck, int n_stages, const ee_trace* tr, const ee_serve_opts* o, ee_result* res,
                   ee_serve_stats* st, ee_event* ev, int64_t max_ev)
-        : Base(ex, ck, n_stages, tr, o, res, st, ev, max_ev), B(o->b_max), ring(2 * o->b_max), batch(o->b_max)
+        : Base(ex, ck, n_stages, tr, o, res, st, ev, max_ev), B(o->b_max), ring(3 * o->b_max), NL(std::max(1, (int)o->lanes))
     {
-        for (int i = 0; i < E; ++i) { ids[i].assign(i ? ring : 0, -1); head[i] = cnt[i] = 0; }
+        for (int i = 0; i < E; ++i) { ids[i].assign(i ? ring : 0, -1); head[i] = cnt[i] = 0; inflight[i] = false; }
+        for (int j = 0; j < NL; ++j) run_of[j].ids.assign((size_t)B, -1);
     }
 
     int run()
@@ -308,36 +415,77 @@ public:
         clock.start(arrival[0]);
         int rc = EE_OK;
         while (completed < n && !rc) {
+            for (int j; !rc && (j = ended_lane()) >= 0;) rc = finish(j);
+            if (rc || completed >= n) break;
             admit_arrivals();
-            const int level = choose();
-            if (level < 0) { clock.idle_until(arrival[arrived]); continue; }
-            rc = run_level(level);
+            int running = 0;
+            for (int j = 0; j < NL; ++j) running += run_of[j].busy;
+            for (int j = 0; j < NL && !rc; ++j) {
+                if (run_of[j].busy) continue;
+                const int level = choose(running > 0);
+                if (level < 0) continue;
+                rc = start(j, level);
+                ++running;
+            }
+            if (rc) break;
+            if (running == 0) { clock.idle_until(arrival[arrived]); continue; }       // nothing in flight, nothing waiting
+            if constexpr (Clock::is_virtual) {
+                int64_t t_next = INT64_MAX;
+                for (int j = 0; j < NL; ++j) if (run_of[j].busy) t_next = std::min(t_next, run_of[j].t_finish);
+                if (running < NL && arrived < n) t_next = std::min(t_next, arrival[arrived]);
+                clock.idle_until(t_next);
+            }
         }
         stats->end_time_ns = clock.now();
         return rc;
     }
 
 private:
-    const int B, ring;
+    struct Run { bool busy = false; int level = 0, b = 0, tail = 0; int64_t t_finish = 0; std::vector<int32_t> ids; };
+    const int B, ring, NL;
     std::vector<int32_t> ids[8];             // request ids of the pools, same ring geometry as the activations
     int head[8], cnt[8];
-    std::vector<int32_t> batch;
+    bool inflight[8];
+    Run run_of[4];
 
     int size_of(int level) const { return level ? cnt[level] : (int)std::min<int64_t>(queued(), INT32_MAX); }
     int batch_of(int level) const { return std::min(size_of(level), B); }
+    bool has_room_behind(int level) const { return level == E - 1 || cnt[level + 1] < B; }
+    bool eligible(int level, bool full_only) const
+    {
+        return !inflight[level] && size_of(level) > 0 && has_room_behind(level) && (!full_only || size_of(level) >= B);
+    }
 
-    int choose()
+    // the lane whose step has ended: on the virtual clock the earliest finish time that has come (lowest lane first),
+    // on the wall clock the first lane whose exit head has reported
+    int ended_lane()
+    {
+        int best = -1;
+        for (int j = 0; j < NL; ++j) {
+            if (!run_of[j].busy) continue;
+            if constexpr (Clock::is_virtual) {
+                if (run_of[j].t_finish <= clock.now() && (best < 0 || run_of[j].t_finish < run_of[best].t_finish)) best = j;
+            } else {
+                if (exec.done(j)) return j;
+            }
+        }
+        return best;
+    }
+
+    int choose(bool full_only)
     {
         int pref = -1;
-        for (int i = E - 1; i >= 0 && pref < 0; --i) if (size_of(i) >= B) pref = i;
-        for (int i = E - 1; i >= 1 && pref < 0; --i) if (cnt[i] > 0) pref = i;
-        if (pref < 0 && queued() > 0) pref = 0;
+        for (int i = E - 1; i >= 0 && pref < 0; --i) if (eligible(i, full_only) && size_of(i) >= B) pref = i;
+        for (int i = E - 1; i >= 1 && pref < 0; --i) if (eligible(i, full_only)) pref = i;
+        if (pref < 0 && eligible(0, full_only)) pref = 0;
         if (pref < 0 || opts.t_slo_ns < 0) return pref;
         const int64_t t_first = lut(pref, batch_of(pref));
         for (int i = E - 1; i >= 1; --i) {
-            if (i == pref || cnt[i] == 0 || (i + 1 < E && cnt[i + 1] >= B)) continue;
+            if (i == pref || cnt[i] == 0 || inflight[i] || !has_room_behind(i)) continue;
             const int b = batch_of(i);
-            const int64_t t_slack = opts.t_slo_ns - (clock.now() - arrival[ids[i][head[i]]]);   // the front is the oldest
+            int64_t oldest = arrival[ids[i][head[i]]];
+            for (int k = 1; k < cnt[i]; ++k) oldest = std::min(oldest, arrival[ids[i][(head[i] + k) % ring]]);
+            const int64_t t_slack = opts.t_slo_ns - (clock.now() - oldest);
             int64_t t_rest = 0;
             for (int s = i; s < E; ++s) t_rest += lut(s, b);
             const bool urgent = t_rest < t_slack && !(t_first + t_rest < t_slack);
@@ -348,28 +496,67 @@ private:
         return pref;
     }
 
-    int run_level(int level)
+    int start(int j, int level)
     {
-        int b = batch_of(level), src = 0, rc = EE_OK;
+        Run& r = run_of[j];
+        const int b = batch_of(level);
+        int src = 0, rc = EE_OK;
         if (level == 0) {
-            pop(batch.data(), b);
+            pop(r.ids.data(), b);
             stats->rounds++;
-            rc = exec.admit(batch.data(), b);
+            rc = exec.admit(j, r.ids.data(), b);
         } else {
-            src = head[level];
-            for (int k = 0; k < b; ++k) batch[k] = ids[level][src + k];
+            src = head[level];                                        // a block boundary: the batch does not wrap
+            for (int k = 0; k < b; ++k) r.ids[k] = ids[level][src + k];
             cnt[level] -= b;
-            head[level] = cnt[level] ? (src + b) % ring : 0;
+            head[level] = (src / B + 1) * B % ring;                   // what is left, or comes next, starts in the next block
+            if (cnt[level] > 0 && b != B) return EE_ERR_OVERFLOW;     // cannot happen: a partial batch empties its pool
         }
         if (rc) return rc;
-        const bool last = level == E - 1;
-        const int tail = last ? 0 : (head[level + 1] + cnt[level + 1]) % ring;
-        rc = proc_until_exit(batch.data(), b, level, false, src, tail, ring);
-        if (rc || last) return rc;
-        if (cnt[level + 1] + b > ring - 1) return EE_ERR_OVERFLOW;                     // cannot happen, see above
-        for (int k = 0; k < b; ++k) ids[level + 1][(tail + k) % ring] = batch[k];
-        cnt[level + 1] += b;
-        return EE_OK;
+        log(EE_EV_PROC, level, b, j);
+        stats->seg_runs[level]++;
+        stats->seg_samples[level] += b;
+        r.busy = true; r.level = level; r.b = b;
+        r.t_finish = clock.now() + (Clock::is_virtual ? lut(level, b) : 0);
+        inflight[level] = true;
+        // one lane: nothing can touch the next level's ring before this step ends, so its compaction is queued right away
+        r.tail = level + 1 < E ? (head[level + 1] + cnt[level + 1]) % ring : 0;
+        return exec.launch(j, level, r.ids.data(), b, src, NL == 1 && level + 1 < E ? r.tail : -1, ring);
+    }
+
+    int finish(int j)
+    {
+        Run& r = run_of[j];
+        int rc = exec.collect(j, r.b, outcome.data());
+        if (rc) return rc;
+        const int64_t t = Clock::is_virtual ? r.t_finish : clock.now();
+        const int level = r.level;
+        int kept = 0;
+        for (int k = 0; k < r.b; ++k) {
+            const SlotOutcome& o = outcome[k];
+            if (o.flag) {
+                ee_result& out = results[r.ids[k]];
+                out.exit_idx = level; out.label = o.label; out.conf = o.conf; out.pad_ = 0; out.score = o.score;
+                out.latency_ns = t - arrival[r.ids[k]];
+                ++completed;
+            } else {
+                r.ids[kept++] = r.ids[k];
+            }
+        }
+        r.busy = false;
+        inflight[level] = false;
+        if (level == E - 1) return kept == 0 ? EE_OK : EE_ERR_DEVICE;               // the last exit takes everyone
+        if (cnt[level + 1] + kept > 2 * B - 1) return EE_ERR_OVERFLOW;               // cannot happen: the successor had room
+        const int tail = (head[level + 1] + cnt[level + 1]) % ring;
+        if (NL == 1) {
+            if (tail != r.tail) return EE_ERR_DEVICE;                                  // the ring did not move under a single lane
+            exec.book_pack(j, level, kept);
+        } else if (kept > 0) {
+            rc = exec.pack(j, level, r.b, kept, tail, ring);
+        }
+        for (int k = 0; k < kept; ++k) ids[level + 1][(tail + k) % ring] = r.ids[k];
+        cnt[level + 1] += kept;
+        return rc;
     }
 };
 
@@ -377,7 +564,7 @@ int check_serve_args(const ee_trace* tr, const ee_serve_opts* o, const ee_result
 {
     if (!tr || !o || tr->n < 0 || (tr->n > 0 && (!tr->arrival_ns || !res))) return EE_ERR_ARG;
     if (o->b_max < 1 || o->b_max > 1024 || !o->lut_ns || n_stages < 1 || n_stages > 8) return EE_ERR_ARG;
-    if ((o->clock != 0 && o->clock != 1) || o->refill < 0 || o->refill > 2) return EE_ERR_ARG;
+    if ((o->clock != 0 && o->clock != 1) || o->refill < 0 || o->refill > 2 || o->lanes < 0 || o->lanes > 4) return EE_ERR_ARG;
     if (tr->n > INT32_MAX) return EE_ERR_OVERFLOW;
     for (int64_t k = 1; k < tr->n; ++k)
         if (tr->arrival_ns[k] < tr->arrival_ns[k - 1]) return EE_ERR_ARG;
@@ -394,6 +581,7 @@ extern "C" int ee_serve_stream(ee_ctx* ctx, const ee_trace* trace, const void* i
     int rc = check_serve_args(trace, opts, results, n_stages);
     if (rc) return rc;
     if (opts->b_max > ctx->b_max) return EE_ERR_ARG;
+    if (opts->refill == 2 && opts->lanes > (int)ctx->lanes.size()) return EE_ERR_ARG;      // ee_lanes makes them, ahead of time
     ee_serve_stats local;
     if (!stats) stats = &local;
     std::memset(stats, 0, sizeof *stats);
@@ -409,7 +597,9 @@ extern "C" int ee_serve_stream(ee_ctx* ctx, const ee_trace* trace, const void* i
         rc = opts->refill == 2 ? PoolScheduler<GpuExec, WallClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run()
                                : FluidScheduler<GpuExec, WallClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run();
     }
-    if (hipStreamSynchronize(ctx->stream) != hipSuccess && !rc) rc = EE_ERR_DEVICE;    // the call is synchronous
+    for (const LaneState& L : ctx->lanes)                                                  // the call is synchronous
+        if (hipStreamSynchronize(L.stream) != hipSuccess && !rc) rc = EE_ERR_DEVICE;
+    ctx->bind_lane(0);
     return rc;
 }
 

@@ -186,3 +186,49 @@ def test_random_networks_pass_both_parsers(ee, orc):
             blob = W.random_net(seed, dtype)
             buf = blob.buffer()
             assert orc.blob_check(blob) == orc.OK and lib.ee_blob_check(buf.ctypes.data, buf.size) == ee.EE_OK, (dtype, seed)
+
+
+@pytest.mark.parametrize("lanes", [2, 3, 4])
+@pytest.mark.parametrize("seed", range(8))
+def test_stage_pools_with_several_steps_in_flight_match_oracle_bit_for_bit(ee, orc, seed, lanes):
+    b_max = [8, 8, 3, 64, 1, 16, 8, 2][seed]
+    arrivals, forced, lut = _case(200 + seed, b_max=b_max, rate=[0.02, 0.2, 0.05, 0.5, 0.01, 0.1, 0.03, 1.0][seed])
+    if seed == 1:
+        arrivals[:] = 0
+    slo = [-1, -1, 700, 2000, -1, 900, 900, 400][seed]
+    a, sa, ea = orc.serve_stream(None, arrivals, None, b_max, lut, t_slo_ns=slo, refill=2, lanes=lanes, forced_exit=forced, n_stages=4, max_events=20000)
+    b, sb, eb = ee.schedule_sim(4, arrivals, forced, b_max, lut, t_slo_ns=slo, refill=2, lanes=lanes, max_events=20000)
+    assert sa == sb
+    assert np.array_equal(ea, eb)
+    for f in ("exit_idx", "latency_ns"):
+        assert np.array_equal(a[f], b[f])
+    assert np.any(eb["aux"][eb["kind"] == 2] > 0) or b_max == 1 or seed in (0, 4)     # a second lane was used
+
+
+def test_two_lane_timeline_through_the_library(ee):
+    lut = np.array([[10 * (s + 1) + b for b in (1, 2)] for s in range(3)], np.int64)
+    res, st, ev = ee.schedule_sim(3, np.zeros(6, np.int64), np.array([0, 1, 2, 2, 1, 0], np.int32), 2, lut, refill=2, lanes=2, max_events=64)
+    assert res["latency_ns"].tolist() == [12, 46, 100, 100, 68, 36]
+    assert [(int(e["t_ns"]), int(e["stage"]), int(e["b"]), int(e["aux"])) for e in ev[ev["kind"] == 2]] == \
+        [(0, 0, 2, 0), (12, 0, 2, 0), (24, 1, 2, 0), (24, 0, 2, 1), (46, 1, 2, 0), (68, 2, 2, 0)]
+    with pytest.raises(ee.EEError):
+        ee.schedule_sim(3, np.zeros(6, np.int64), np.zeros(6, np.int32), 2, lut, refill=2, lanes=5)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_adaptive_batching_and_serial_match_oracle_bit_for_bit(ee, orc, seed):
+    b_max = [8, 8, 4, 1, 16, 8][seed]
+    arrivals, forced, lut = _case(300 + seed, b_max=b_max, rate=[0.02, 0.2, 0.005, 0.01, 0.1, 0.05][seed])
+    window = [300, 50, 5000, 100, 10**12, 1][seed]
+    a, sa, ea = orc.serve_stream(None, arrivals, None, b_max, lut, refill=0, t_timeout_ns=window, forced_exit=forced, n_stages=4, max_events=20000)
+    b, sb, eb = ee.schedule_sim(4, arrivals, forced, b_max, lut, refill=0, t_timeout_ns=window, max_events=20000)
+    assert sa == sb and np.array_equal(ea, eb)
+    for f in ("exit_idx", "latency_ns"):
+        assert np.array_equal(a[f], b[f])
+
+
+def test_adaptive_batching_timeline_through_the_library(ee):
+    arrivals = np.array([0, 3, 50, 51, 52, 53, 54], np.int64)
+    res, st, ev = ee.schedule_sim(2, arrivals, np.ones(7, np.int32), 4, np.full((2, 4), 10, np.int64), refill=0, t_timeout_ns=20, max_events=64)
+    assert res["latency_ns"].tolist() == [40, 37, 23, 22, 21, 20, 40]
+    assert [(int(e["t_ns"]), int(e["b"])) for e in ev[ev["kind"] == 1]] == [(20, 2), (53, 4), (74, 1)]
