@@ -75,6 +75,9 @@ def layer_table(args, ee, W, blob, dtype):
             eng.load_tables(json.load(f))
     else:
         eng.autotune(reps=5)
+    if args.save_tables:
+        with open(args.save_tables, "w") as f:
+            json.dump(eng.tables(), f)
     rows = []
     for i, op in enumerate(blob.ops):
         us, ops, byt = eng.time_layer(i, B, 0, reps=30)
@@ -100,41 +103,88 @@ def layer_table(args, ee, W, blob, dtype):
     eng.close()
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="resnet50_i8_stream", choices=sorted(WORKLOADS))
-    ap.add_argument("--requests", type=int, default=0, help="override the number of requests (0 = the workload's)")
-    ap.add_argument("--min-incr", type=int, default=0, help="smallest catch-up batch (0 = b_max / 2; 1 = Algorithm 1 as printed)")
-    ap.add_argument("--t-slo-ms", type=float, default=-1.0, help="latency SLO of Eq. 3 in ms (negative = none: throughput run)")
-    ap.add_argument("--refill", type=int, default=-1, choices=[-1, 0, 1, 2],
-                    help="serving policy of the timed steps: 0 model-level batching, 1 Algorithm 1, 2 stage pools (-1 = the workload's)")
-    ap.add_argument("--load", type=float, default=0.0, help="arrival rate as a multiple of the static-batch throughput (0 = the workload's)")
-    ap.add_argument("--cpu-samples", type=int, default=0, help="samples timed on the CPU oracle (0 = automatic, -1 = skip)")
-    ap.add_argument("--save-tables", default="", help="write the tuned kernel-configuration tables to this JSON file")
-    ap.add_argument("--load-tables", default="", help="load the kernel-configuration tables from this JSON file instead of tuning")
-    ap.add_argument("--no-kernel-timing", action="store_true", help="skip the extra step that brackets every kernel launch with HIP events")
-    ap.add_argument("--layers", type=int, default=0, metavar="B",
-                    help="instead of the stream: every layer of the workload's network alone on B samples, tuned, launches back to back")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this program measures the path on ONE GPU; --gpus must be 1", file=sys.stderr)
-        sys.exit(2)
+def policy_sweep(args, ee, W):
+    """The serving policies of the evaluation (Sec. V-A "Baselines", Sec. V-B) on one workload, wall clock: SERIAL, adaptive
+    batching <B_max, T_timeout> with windows of 5 / 45 / 95 % of the SLO (AdaptB-S/M/L), model-level batching without a
+    window, Algorithm 1 as printed and with min_incr = B_max / 2, and the stage pools on one and on two lanes; over arrival
+    rates (multiples of the static-batch throughput) at an SLO of twice the full-batch latency, then over SLOs at 0.8 x.
+    One JSON line: rows of policy, load, slo_ms, samples/s, mean / p99 latency, violation rate, mean batch per segment."""
+    import torch
+    wl = WORKLOADS[args.workload]
+    n = args.requests or min(wl["n"], 4000)
+    b_max = wl["b_max"]
+    blob = W.load_net(wl["net"])
+    eng = ee.Engine(blob, b_max)
+    eng.set_lanes(2)
+    pool = torch.cat([torch.from_numpy((lambda p: p.view(np.int16) if p.dtype == np.uint16 else p)(W.input_pool(blob, min(1000, n - f), first=f))).cuda()
+                      for f in range(0, n, 1000)])
+    if args.load_tables:
+        with open(args.load_tables) as f:
+            eng.load_tables(json.load(f))
+    else:
+        eng.autotune(reps=3)
+    lut = eng.measure_lut(reps=3)
+    zeros = np.zeros(n, np.int64)
+    eng.serve_stream(zeros, pool, lut, clock=0, refill=0)
+    t0 = time.perf_counter()
+    eng.serve_stream(zeros, pool, lut, clock=0, refill=0)
+    static_rate = n / (time.perf_counter() - t0)
+    full_ns = int(lut[:, b_max - 1].sum())                 # latency of a full batch through every segment
+    lut1 = np.ascontiguousarray(lut[:, :1])
+    rows = []
 
+    def run(policy, load, slo_ns):
+        arr = W.poisson_trace(n, load * static_rate)
+        kw = dict(clock=0, t_slo_ns=slo_ns)
+        if policy == "serial":
+            res, st, _ = eng.serve_stream(arr, pool, lut1, b_max=1, refill=0, **kw)
+        elif policy.startswith("adaptb"):
+            frac = {"S": 0.05, "M": 0.45, "L": 0.95}[policy[-1]]
+            res, st, _ = eng.serve_stream(arr, pool, lut, refill=0, t_timeout_ns=max(1, int(frac * slo_ns)), **kw)
+        elif policy == "model_level":
+            res, st, _ = eng.serve_stream(arr, pool, lut, refill=0, **kw)
+        elif policy == "algorithm1_as_printed":
+            res, st, _ = eng.serve_stream(arr, pool, lut, refill=1, min_incr=1, **kw)
+        elif policy == "algorithm1_min_incr":
+            res, st, _ = eng.serve_stream(arr, pool, lut, refill=1, min_incr=max(1, b_max // 2), **kw)
+        else:
+            res, st, _ = eng.serve_stream(arr, pool, lut, refill=2, lanes=int(policy[-1]), **kw)
+        lat = res["latency_ns"].astype(np.float64)
+        span = float(arr[-1] - arr[0] + lat[-1]) if n else 1.0
+        done = (arr + res["latency_ns"]).max() - arr[0]
+        rows.append(dict(policy=policy, load=load, slo_ms=round(slo_ns / 1e6, 3), samples_per_s=round(n / (done * 1e-9), 1),
+                         latency_ms_mean=round(lat.mean() / 1e6, 3), latency_ms_p99=round(float(np.percentile(lat, 99)) / 1e6, 3),
+                         slo_violation_rate=round(float(np.mean(lat > slo_ns)), 4), preemptions=st["preemptions"],
+                         mean_batch_per_segment=[round(a / max(b, 1), 2) for a, b in zip(st["seg_samples"], st["seg_runs"])]))
+        print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
+
+    policies = ["serial", "adaptb_S", "adaptb_M", "adaptb_L", "model_level", "algorithm1_as_printed", "algorithm1_min_incr", "stage_pools_1", "stage_pools_2"]
+    for load in (0.25, 0.5, 0.8, 1.0, 1.2):
+        for pol in policies:
+            if pol == "serial" and load > 0.5:
+                continue                                   # far beyond what one request at a time sustains: the queue only grows
+            run(pol, load, 2 * full_ns)
+    for mult in (1.0, 1.5, 3.0, 4.0):
+        for pol in policies[1:]:
+            run(pol, 0.8, int(mult * full_ns))
+    print(json.dumps(dict(mode="policies", workload=args.workload, requests=n, b_max=b_max, static_batch_samples_per_s=round(static_rate, 1),
+                          full_batch_latency_ms=round(full_ns / 1e6, 3), rows=rows)))
+    eng.close()
+
+
+def run_stream(args, name, steps, warmup, full=True):
+    """One workload: tunes, measures the static-batch rate that sets the arrival rate, times `steps` steps of the stream
+    under the workload's policy, then (full) the same trace under the other policies, the saturated capacity, the per-kernel
+    timing of one more step and the CPU oracle.  Returns the JSON object."""
     import torch
     import paper_2209_13443_amd as ee
     import workloads as W
 
-    wl = WORKLOADS[args.workload]
+    wl = WORKLOADS[name]
     n = args.requests or wl["n"]
     b_max = wl["b_max"]
     blob = W.load_net(wl["net"])
     dtype = "i8" if blob.dtype == W.DT_I8 else "bf16"
-    torch.cuda.set_device(0)
-    if args.layers:
-        return layer_table(args, ee, W, blob, dtype)
     eng = ee.Engine(blob, b_max)
 
     # synthetic request pool, resident in HBM before any timed region
@@ -146,12 +196,12 @@ def main():
     del chunks
     torch.cuda.synchronize()
 
-    if args.load_tables:                               # design-time per-(layer, batch) kernel configuration table
+    if args.load_tables and full:                      # design-time per-(layer, batch) kernel configuration table
         with open(args.load_tables) as f:
             eng.load_tables(json.load(f))
     else:
-        eng.autotune(reps=5)
-    if args.save_tables:
+        eng.autotune(reps=5 if full else 3)
+    if args.save_tables and full:
         with open(args.save_tables, "w") as f:
             json.dump(eng.tables(), f)
     lut = eng.measure_lut(reps=3)                      # design-time exit-level latency table
@@ -163,59 +213,77 @@ def main():
     t0 = time.perf_counter()
     res_static, st_static, _ = eng.serve_stream(zeros, pool, lut, clock=0, refill=0)
     static_rate = n / (time.perf_counter() - t0)
-    load = args.load or wl["load"]
+    load = (args.load if full else 0.0) or wl["load"]
     if load is None:
         arrivals = zeros
     elif wl["spikes"]:
         arrivals = W.spiky_trace(n, load * static_rate)
     else:
         arrivals = W.poisson_trace(n, load * static_rate)
-    t_slo_ns = int(args.t_slo_ms * 1e6) if args.t_slo_ms >= 0 else -1
+    t_slo_ns = int(args.t_slo_ms * 1e6) if args.t_slo_ms >= 0 and full else -1
 
-    refill = wl["refill"] if args.refill < 0 else args.refill
+    refill = wl["refill"] if args.refill < 0 or not full else args.refill
+    lanes = ((args.lanes if full else 0) or wl.get("lanes", 2)) if refill == 2 else 1
+    eng.set_lanes(lanes)
 
-    def step(policy=refill):
-        return eng.serve_stream(arrivals, pool, lut, clock=0, refill=policy, min_incr=min_incr, t_slo_ns=t_slo_ns)
+    def step(policy=refill, arr=None, min_incr_=None, lanes_=None):
+        return eng.serve_stream(arrivals if arr is None else arr, pool, lut, clock=0, refill=policy, min_incr=min_incr_ or min_incr, t_slo_ns=t_slo_ns,
+                                lanes=(lanes_ or lanes) if policy == 2 else 1)
 
-    for _ in range(args.warmup):
+    def timed_steps(k, **kw):
+        step(**kw)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            r, s_, _ = step(**kw)
+        torch.cuda.synchronize()
+        return k * n / (time.perf_counter() - t0), r, s_
+
+    def summary(rate, r, s_):
+        lat_ = r["latency_ns"].astype(np.float64)
+        return dict(samples_per_s=round(rate, 1), mean_batch_per_segment=[round(a / max(b, 1), 2) for a, b in zip(s_["seg_samples"], s_["seg_runs"])],
+                    latency_ms_mean=round(lat_.mean() / 1e6, 3), latency_ms_p99=round(float(np.percentile(lat_, 99)) / 1e6, 3),
+                    slo_violation_rate=round(float(np.mean(lat_ > t_slo_ns)), 4) if t_slo_ns >= 0 else None, preemptions=s_["preemptions"])
+
+    for _ in range(warmup):
         step()
     marker = torch.zeros(64, device="cuda")
     torch.cuda.synchronize()
     marker.cos_()                                      # a kernel trace shows the timed region between a cos and a sin kernel
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         res, st, _ = step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     marker.sin_()
-    value = args.steps * n / elapsed
+    value = steps * n / elapsed
 
-    # the same trace under the other refill policy (Algorithm 1 of the paper when the stage pools were timed, and
-    # the other way round), outside the timed region above
-    other = None
-    if refill in (1, 2):
-        step(3 - refill)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            res_o, st_o, _ = step(3 - refill)
-        torch.cuda.synchronize()
-        lat_o = res_o["latency_ns"].astype(np.float64)
-        other = dict(samples_per_s=round(args.steps * n / (time.perf_counter() - t0), 1),
-                     mean_batch_per_segment=[round(a / max(b, 1), 2) for a, b in zip(st_o["seg_samples"], st_o["seg_runs"])],
-                     latency_ms_mean=round(lat_o.mean() / 1e6, 3), latency_ms_p99=round(float(np.percentile(lat_o, 99)) / 1e6, 3),
-                     slo_violation_rate=round(float(np.mean(lat_o > t_slo_ns)), 4) if t_slo_ns >= 0 else None,
-                     preemptions=st_o["preemptions"], same_exits=bool(np.array_equal(res_o["exit_idx"], res["exit_idx"])))
+    # Outside the timed region: the same trace under the other refill policy (Algorithm 1 of the paper when the stage pools
+    # were timed, and the other way round), Algorithm 1 exactly as printed (min_incr = 1), and the capacity of the timed
+    # policy: every request queued at t = 0, so that the figure is bounded by the path and not by the arrival rate.
+    other = printed = capacity = None
+    k_side = max(1, min(steps, 2))
+    if refill in (1, 2) and full:
+        rate_o, res_o, st_o = timed_steps(k_side, policy=3 - refill)
+        other = summary(rate_o, res_o, st_o)
+        other["same_exits"] = bool(np.array_equal(res_o["exit_idx"], res["exit_idx"]))
+        rate_p, res_p, st_p = timed_steps(1, policy=1, min_incr_=1)
+        printed = summary(rate_p, res_p, st_p)
+    if load is not None and full:
+        rate_c, res_c, st_c = timed_steps(k_side, arr=zeros)
+        capacity = summary(rate_c, res_c, st_c)
+        if refill == 2 and lanes > 1:
+            capacity["one_lane_samples_per_s"] = round(timed_steps(1, arr=zeros, lanes_=1)[0], 1)
 
-    # Per-kernel durations: HIP events on the library's stream around every launch of one more step of
-    # the same workload.  Bracketing each launch costs the stream its back-to-back dispatch (about a
-    # quarter of the throughput), so it is kept out of the K timed steps above.
+    # Per-kernel durations: HIP events on the library's streams around every launch of one more step of the same
+    # workload on one lane (kernels of concurrent steps share the chip, so their durations would say nothing about a
+    # kernel).  Bracketing each launch costs the stream its back-to-back dispatch, so it is kept out of the timed steps.
     kstats = {k: dict(launches=0, ms=0.0, ops=0.0, bytes=0.0) for k in ee.K_NAMES}
     layer_stats = []
     if not args.no_kernel_timing:
         eng.profile(True)
-        step()
+        step(lanes_=1)
         kstats, layer_stats = eng.profile_read(len(blob.ops))
         eng.profile(False)
 
@@ -224,13 +292,15 @@ def main():
     roofline = None
     if conv["launches"]:
         achieved = conv["ops"] / (conv["ms"] * 1e-3) / 1e12
-        roofline = dict(bound="mfma", kernel="conv_igemm_kernel", achieved=round(achieved, 2), peak=PEAK[dtype],
+        roofline = dict(bound="mfma", kernel="conv_igemm_kernel, conv_pair_kernel", achieved=round(achieved, 2), peak=PEAK[dtype],
                         unit="TOP/s" if dtype == "i8" else "TFLOP/s", frac=round(achieved / PEAK[dtype], 4), traffic=None,
                         launches=conv["launches"], avg_launch_us=round(conv["ms"] * 1e3 / conv["launches"], 2),
                         algorithmic_gops_per_launch=round(conv["ops"] / conv["launches"] / 1e9, 3),
                         algorithmic_mb_per_launch=round(conv["bytes"] / conv["launches"] / 1e6, 3),
+                        algorithmic_tops_per_step=round(conv["ops"] / 1e12, 3), algorithmic_gb_per_step=round(conv["bytes"] / 1e9, 3),
+                        kernel_ms_per_step=round(conv["ms"], 3),
                         hbm_gbps_algorithmic=round(conv["bytes"] / (conv["ms"] * 1e-3) / 1e9, 1))
-        roofline["traffic"] = measured_traffic(args.workload)
+        roofline["traffic"] = measured_traffic(name)
         # Layer by layer the convolutions are also capped by their algorithmic bytes: the time the launches of
         # a layer need at best is max(ops / MFMA peak, bytes / HBM peak); the sum over the layers gives the
         # rate the stack could reach if every launch sat on its own roofline (ops and bytes of a layer are
@@ -248,36 +318,45 @@ def main():
                        tops=round(v["ops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] > 0 else 0.0)
                for k, v in kstats.items() if v["launches"]}
 
-    # the CPU oracle on a bounded sample of the same requests, each sample alone until it exits
+    # the CPU oracle on a bounded sample of the same requests, each sample alone until it exits: all cores, then one
     cpu = None
-    if args.cpu_samples >= 0:
+    if args.cpu_samples >= 0 and full:
         import oracle
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        per = {"resnet50_i8": 2 * cores, "resnet50_eq_i8": 2 * cores, "inception_i8": cores, "resnet50_bf16": cores, "resnet18_i8": 4 * cores, "mobilenetv2_i8": 16 * cores}.get(wl["net"], 64)
+        per = {"resnet50_i8": 16 * cores, "resnet50_eq_i8": 16 * cores, "inception_i8": 8 * cores, "resnet50_bf16": 2 * cores, "resnet18_i8": 32 * cores,
+               "mobilenetv2_i8": 128 * cores}.get(wl["net"], 64)
         ns = min(n, args.cpu_samples or per)
         sample = W.input_pool(blob, ns)
         t0 = time.perf_counter()
         ref = oracle.forward_alone(blob, sample)
         dt = time.perf_counter() - t0
         agree = bool(np.array_equal(ref["exit_idx"], res["exit_idx"][:ns])) if dtype == "i8" else None
+        n1 = max(1, min(ns, int(round(ns / dt / cores * 10))))              # about 10 s on one core
+        t0 = time.perf_counter()
+        oracle.forward_alone(blob, sample[:n1], threads=1)
+        dt1 = time.perf_counter() - t0
         cpu = dict(value=round(ns / dt, 3), unit="samples/s", cores=cores, kind="oracle",
                    sample=f"first {ns} requests of the same pool, each alone through the segments until it exits, OpenMP over samples",
-                   seconds=round(dt, 2), exits_agree_with_gpu=agree)
+                   seconds=round(dt, 2), exits_agree_with_gpu=agree,
+                   one_core=dict(value=round(n1 / dt1, 3), unit="samples/s", cores=1, sample=f"first {n1} of them", seconds=round(dt1, 2)))
 
     lat = res["latency_ns"].astype(np.float64)
     out = {
         "metric": "samples/sec early-exit CNN stream (1 GPU)", "value": round(value, 1), "unit": "samples/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(elapsed / args.steps * 1e3, 3),
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-        "config": {"workload": args.workload, "requests": n, "b_max": b_max, "refill": refill,
-                   "policy": ["static batches", "Algorithm 1", "stage pools"][refill], "min_incr": min_incr if refill == 1 else None,
+        "config": {"workload": name, "requests": n, "b_max": b_max, "refill": refill,
+                   "policy": ["static batches", "Algorithm 1", "stage pools"][refill], "lanes": lanes if refill == 2 else None,
+                   "min_incr": min_incr if refill == 1 else None,
                    "arrival": "poisson" if load else "all_at_t0", "arrival_rate_per_s": round(load * static_rate, 1) if load else None,
-                   "clock": "wall", "t_slo_ms": args.t_slo_ms if args.t_slo_ms >= 0 else None},
+                   "clock": "wall", "t_slo_ms": args.t_slo_ms if t_slo_ns >= 0 else None},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "static_batch_samples_per_s": round(static_rate, 1),
+        "capacity": capacity,
         ("algorithm1" if refill == 2 else "stage_pools"): other,
         "algorithm1_min_incr": min_incr if refill == 2 else None,
+        "algorithm1_as_printed": printed,
         "exit_counts": np.bincount(res["exit_idx"], minlength=eng.n_stages).tolist(),
         "mean_batch_per_segment": [round(a / max(b, 1), 2) for a, b in zip(st["seg_samples"], st["seg_runs"])],
         "mean_batch_per_segment_static": [round(a / max(b, 1), 2) for a, b in zip(st_static["seg_samples"], st_static["seg_runs"])],
@@ -285,6 +364,63 @@ def main():
         "preemptions": st["preemptions"], "latency_ms_mean": round(lat.mean() / 1e6, 3), "latency_ms_p99": round(float(np.percentile(lat, 99)) / 1e6, 3),
         "kernels": kernels,
     }
+    eng.close()
+    del pool
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="resnet50_i8_stream", choices=sorted(WORKLOADS))
+    ap.add_argument("--requests", type=int, default=0, help="override the number of requests (0 = the workload's)")
+    ap.add_argument("--min-incr", type=int, default=0, help="smallest catch-up batch (0 = b_max / 2; 1 = Algorithm 1 as printed)")
+    ap.add_argument("--t-slo-ms", type=float, default=-1.0, help="latency SLO of Eq. 3 in ms (negative = none: throughput run)")
+    ap.add_argument("--refill", type=int, default=-1, choices=[-1, 0, 1, 2],
+                    help="serving policy of the timed steps: 0 model-level batching, 1 Algorithm 1, 2 stage pools (-1 = the workload's)")
+    ap.add_argument("--lanes", type=int, default=0, help="stage pools: steps in flight at once (0 = the workload's)")
+    ap.add_argument("--load", type=float, default=0.0, help="arrival rate as a multiple of the static-batch throughput (0 = the workload's)")
+    ap.add_argument("--cpu-samples", type=int, default=0, help="samples timed on the CPU oracle (0 = automatic, -1 = skip)")
+    ap.add_argument("--save-tables", default="", help="write the tuned kernel-configuration tables to this JSON file")
+    ap.add_argument("--load-tables", default="", help="load the kernel-configuration tables from this JSON file instead of tuning")
+    ap.add_argument("--no-kernel-timing", action="store_true", help="skip the extra step that brackets every kernel launch with HIP events")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the short runs of the other stream configurations")
+    ap.add_argument("--layers", type=int, default=0, metavar="B",
+                    help="instead of the stream: every layer of the workload's network alone on B samples, tuned, launches back to back")
+    ap.add_argument("--policies", action="store_true",
+                    help="instead of the one stream: the serving policies of the evaluation over arrival rates and SLOs (see policy_sweep)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this program measures the path on ONE GPU; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2209_13443_amd as ee
+    import workloads as W
+    torch.cuda.set_device(0)
+    if args.layers:
+        blob = W.load_net(WORKLOADS[args.workload]["net"])
+        return layer_table(args, ee, W, blob, "i8" if blob.dtype == W.DT_I8 else "bf16")
+    if args.policies:
+        return policy_sweep(args, ee, W)
+    out = run_stream(args, args.workload, args.steps, args.warmup)
+    if args.workload == "resnet50_i8_stream" and not args.no_other_configs and not args.requests:
+        # the other stream configurations, briefly: one timed step each, their dominant kernel class against its roofline
+        others = {}
+        for name in ("mobilenetv2_i8_refill", "resnet50_bf16_stream"):
+            o = run_stream(args, name, 1, 1, full=False)
+            k = o["kernels"]
+            entry = dict(samples_per_s=o["value"], ms_per_step=o["ms_per_step"], static_batch_samples_per_s=o["static_batch_samples_per_s"],
+                         dtype=o["dtype"], config=o["config"], mean_batch_per_segment=o["mean_batch_per_segment"])
+            if o["roofline"]:
+                entry["conv_mfma"] = {f: o["roofline"][f] for f in ("achieved", "peak", "unit", "frac", "launches", "avg_launch_us")}
+            if "depthwise" in k:
+                entry["depthwise"] = dict(bound="hbm", achieved=k["depthwise"]["gbps"], peak=HBM_PEAK, unit="GB/s", frac=k["depthwise"]["hbm_frac"], launches=k["depthwise"]["launches"])
+            others[name] = entry
+        out["other_configs"] = others
     print(json.dumps(out))
 
 

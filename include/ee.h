@@ -187,7 +187,8 @@ int ee_time_layer(ee_ctx* ctx, int layer, int b, int cfg, int reps, double* us_o
 /* ---- kernel timing (HIP events on the library's stream) ------------------------------------ */
 enum { EE_K_CONV_MFMA = 0, EE_K_CONV_FIRST = 1, EE_K_CONV_DIRECT = 2, EE_K_DEPTHWISE = 3, EE_K_MAXPOOL = 4,
        EE_K_PAD_INPUT = 5, EE_K_GAP = 6, EE_K_FC = 7, EE_K_SOFTMAX = 8, EE_K_COMPACT = 9, EE_K_ADMIT = 10,
-       EE_K_COUNT = 11 };
+       EE_K_CONV_STREAM = 11,   /* matrix-core layers whose operands come straight from global memory (thin and streaming kernels) */
+       EE_K_COUNT = 12 };
 typedef struct { int64_t launches; double ms; double ops; double bytes; } ee_kernel_stat;
 /* enable = 1 brackets every kernel launch with a pair of HIP events; ee_profile_read synchronises,
  * adds the elapsed times up per kernel class into stats[EE_K_COUNT] (host) and, when per_layer is not

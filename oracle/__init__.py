@@ -269,11 +269,18 @@ def compact_refill(flags, act_src, ids_src, refill_act=None, refill_ids=None):
     return dst[:b_merged.value], ids_dst[:b_merged.value], b_rem.value, b_merged.value
 
 
-def forward_alone(blob, inputs):
+def forward_alone(blob, inputs, threads=None):
+    """every request alone through the segments until it exits; threads: worker threads (None = all cores)"""
     inputs = np.ascontiguousarray(inputs)
     n = inputs.shape[0]
     res = np.zeros(n, RESULT_DT)
-    _chk(lib().orc_forward_alone(*_blob_args(blob), C.c_int64(n), _p(inputs), _p(res)))
+    if threads:
+        lib().orc_set_threads(int(threads))
+    try:
+        _chk(lib().orc_forward_alone(*_blob_args(blob), C.c_int64(n), _p(inputs), _p(res)))
+    finally:
+        if threads:
+            lib().orc_set_threads(0)
     return res
 
 

@@ -88,6 +88,9 @@ int orc_compact_refill(int64_t sample_bytes, int b_act, const uint8_t* exit_flag
 /* every sample on its own through the segments until it exits (thresholds from the blob) */
 int orc_forward_alone(const void* blob, size_t bytes, int64_t n, const void* inputs, orc_result* results);
 
+/* worker threads of the parallel loops over samples (timing the oracle on one core); 0 = the default again */
+int orc_set_threads(int n);
+
 /* ---- Algorithm 1 on a virtual clock -------------------------------------------------- */
 typedef struct {
     int32_t b_max;

@@ -316,3 +316,17 @@ int orc_forward_alone(const void* blob, size_t bytes, int64_t n, const void* inp
     }
     return fail;
 }
+
+/* worker threads the parallel loops over samples use (0 = the OpenMP default again) */
+#ifdef _OPENMP
+#include <omp.h>
+static int orc_default_threads = 0;
+int orc_set_threads(int n)
+{
+    if (!orc_default_threads) orc_default_threads = omp_get_max_threads();
+    omp_set_num_threads(n > 0 ? n : orc_default_threads);
+    return omp_get_max_threads();
+}
+#else
+int orc_set_threads(int n) { (void)n; return 1; }
+#endif

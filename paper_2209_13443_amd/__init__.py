@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libee.so")
 EE_OK, EE_ERR_ARG, EE_ERR_SHAPE, EE_ERR_UNSUPPORTED, EE_ERR_DEVICE, EE_ERR_OVERFLOW = 0, -1, -2, -3, -4, -5
 EE_I8, EE_BF16 = 0, 1
 K_NAMES = ["conv_mfma", "conv_first", "conv_direct", "depthwise", "maxpool", "pad_input", "gap", "fc", "softmax",
-           "compact", "admit"]
+           "compact", "admit", "conv_stream"]
 
 RESULT_DT = np.dtype([("exit_idx", "<i4"), ("label", "<i4"), ("conf", "<f4"), ("pad_", "<i4"),
                       ("score", "<i8"), ("latency_ns", "<i8")])

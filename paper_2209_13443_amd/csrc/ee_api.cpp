@@ -266,7 +266,7 @@ extern "C" const char* ee_strerror(int status)
 extern "C" const char* ee_kernel_name(int k)
 {
     static const char* names[EE_K_COUNT] = {"conv_mfma", "conv_first", "conv_direct", "depthwise", "maxpool", "pad_input",
-                                            "gap", "fc", "softmax", "compact", "admit"};
+                                            "gap", "fc", "softmax", "compact", "admit", "conv_stream"};
     return k >= 0 && k < EE_K_COUNT ? names[k] : "?";
 }
 
@@ -705,11 +705,17 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                 }
             }
             if (cfg == 0 && !p.cfg.empty()) cfg = p.cfg[std::min<size_t>(bucket_of(b), p.cfg.size() - 1)];
-            const int cls = p.impl == IMPL_MFMA_C4 ? EE_K_CONV_FIRST : EE_K_CONV_MFMA;
+            int cls = p.impl == IMPL_MFMA_C4 ? EE_K_CONV_FIRST : EE_K_CONV_MFMA;
+            if (p.impl != IMPL_MFMA_C4 && ((cfg & 15) == 7 || cfg == 0)) {             // the streaming kernel is booked in its own class
+                ConvArgs probe{};
+                fill_conv_args(st.first_op + k, b, probe);
+                probe.res = res;
+                if (conv_stream_supported(probe, es) && ((cfg & 15) == 7 || probe.M >= 32768)) cls = EE_K_CONV_STREAM;
+            }
             e = timed(cls, ops, bytes, [&] { return launch_conv(st.first_op + k, b, src, dst, res, cfg); }, st.first_op + k);
         } else if (p.impl == IMPL_THIN) {
             ThinConvArgs a{src, p.w_dev, p.b_dev, dst, (long long)b * d.h_out * d.w_out, d.c_in, d.c_out, d.c_tot, d.c_off, d.shift, d.lo, d.hi};
-            e = timed(EE_K_CONV_MFMA, ops, bytes, [&] { return launch_conv_thin(a, stream); }, st.first_op + k);
+            e = timed(EE_K_CONV_STREAM, ops, bytes, [&] { return launch_conv_thin(a, stream); }, st.first_op + k);
         } else if (p.impl == IMPL_DIRECT) {
             DirectConvArgs a{src, p.w_dev, p.b_dev, res, dst, b * d.h_out * d.w_out, d.h_in, d.w_in, d.c_in, d.h_out, d.w_out, d.c_out,
                              d.kh, d.kw, d.stride, d.pad, d.shift, d.res_shift, d.lo, d.hi, d.f_lo, d.f_hi, d.pad_w, d.c_tot, d.c_off};
