@@ -203,9 +203,11 @@ const char* ee_kernel_name(int kernel_class);
 /* Tuning / test control of the convolution tiling, process-wide: 0 = chosen per layer and active
  * batch size (default), 1 = 128x128, 2 = 128x64, 3 = 64x64, 4 = 64x128 (output pixels x output channels
  * per workgroup), 7 = the streaming kernel for the layers it covers (many pixels, a reduction of at most nine
- * 32-byte blocks, at most 64 output channels; other layers keep the default).  Results never depend on it.
- * Returns the previous setting, EE_ERR_ARG if out of range. */
-int ee_tune_conv_tile(int tile);
+ * 32-byte blocks, at most 64 output channels; other layers keep the default).  A whole configuration word as
+ * in ee_config_set (tile | reduction step << 4 | ring stages << 8 | wavefront groups << 12) forces that one on
+ * every matrix-core layer; a ring deeper than LDS allows runs with the deepest that fits.  Results never depend
+ * on it.  Returns the previous setting, EE_ERR_ARG if out of range. */
+int ee_tune_conv_tile(int cfg);
 
 /* Kernel-configuration table, one entry per (convolution layer, active-batch bucket 2^k): the GPU
  * counterpart of the run-time look-up the paper keeps per layer and batch size (Sec. III-A, the

@@ -272,7 +272,15 @@ extern "C" const char* ee_kernel_name(int k)
 
 extern "C" const uint32_t* ee_exp2_table(void) { return exp2_table_host(); }
 
-extern "C" int ee_tune_conv_tile(int tile) { return tile < 0 || (tile > 4 && tile != 7) ? EE_ERR_ARG : set_conv_tile(tile); }
+extern "C" int ee_tune_conv_tile(int cfg)
+{
+    const int tile = cfg & 15, ksel = (cfg >> 4) & 15, ns = (cfg >> 8) & 15, kspl = (cfg >> 12) & 15;
+    if (cfg < 0 || (cfg >> 17) || ksel > 3 || (ns != 0 && (ns < 2 || ns > 4)) || (kspl != 0 && kspl != 2 && kspl != 4)) return EE_ERR_ARG;
+    if (cfg & EE_CFG_SLAB) {
+        if (tile < 1 || tile > 4 || ksel == 1 || kspl != 0) return EE_ERR_ARG;
+    } else if (tile > 4 && cfg != 7) return EE_ERR_ARG;
+    return set_conv_tile(cfg);
+}
 
 extern "C" int ee_blob_check(const void* blob, size_t bytes) { return parse_blob(blob, bytes, nullptr); }
 
@@ -479,6 +487,13 @@ hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const 
         if (forced_conv_tile() != 7) return hipErrorInvalidValue;
         cfg = 0;                                         // forced for the whole process: layers it does not cover keep the default
     }
+    if (cfg & EE_CFG_SLAB) {
+        hipError_t e = hipErrorInvalidValue;             // a layer that is not of its kind, or a tile whose slab does not fit LDS
+        if (conv_slab_supported(a, dt == EE_I8 ? 1 : 2)) e = dt == EE_I8 ? launch_conv_slab<1>(a, cfg & 0xFFFF, stream) : launch_conv_slab<2>(a, cfg & 0xFFFF, stream);
+        if (e != hipErrorInvalidValue || forced_conv_tile() != cfg) return e;
+        (void)hipGetLastError();
+        cfg = 0;                                         // forced for the whole process: layers it does not cover keep the default
+    }
     if (cfg == 0 && streamable && a.M >= 32768) return launch_conv_stream(a, stream);   // untuned: it wins on every large layer it covers
     return dt == EE_I8 ? launch_conv_igemm<1>(a, cfg, stream) : launch_conv_igemm<2>(a, cfg, stream);
 }
@@ -527,26 +542,32 @@ extern "C" int ee_autotune(ee_ctx* ctx, int reps)
             best_time[st.first_op + k].assign(buckets.size(), 1e30f);
             for (size_t bi = 0; bi < buckets.size() && !rc; ++bi) {
                 float& best_ms = best_time[st.first_op + k][bi];
+                std::vector<int> cands;
                 for (int tile = 1; tile <= 5; ++tile)
                     for (int ksel = 1; ksel <= 3; ++ksel)
                         for (int ns = 2; ns <= 4; ++ns)
                             for (int kspl = 1; kspl <= 4; kspl *= 2) {
-                            if (tile == 5 && (ksel > 1 || ns > 2 || kspl > 1)) continue;  // the streaming kernel has one configuration
-                            if (ksel > 1 && kbytes <= 64 * (ksel - 1)) continue;        // a longer step than the whole reduction
-                            if (kspl > 1 && (ksel != 3 || tile < 3 || (kspl == 4 && tile != 3) || kbytes < 1024)) continue;   // combinations that exist
-                            const int cfg = tile == 5 ? 7 : tile | (ksel << 4) | (ns << 8) | ((kspl > 1 ? kspl : 0) << 12);
-                            if (ctx->launch_conv(st.first_op + k, buckets[bi], src, dst, res, cfg) != hipSuccess) {
-                                (void)hipGetLastError();                       // this configuration does not fit: skip it
-                                continue;
+                                if (tile == 5 && (ksel > 1 || ns > 2 || kspl > 1)) continue;  // the streaming kernel has one configuration
+                                if (ksel > 1 && kbytes <= 64 * (ksel - 1)) continue;        // a longer step than the whole reduction
+                                if (kspl > 1 && (ksel != 3 || tile < 3 || (kspl == 4 && tile != 3) || kbytes < 1024)) continue;   // combinations that exist
+                                cands.push_back(tile == 5 ? 7 : tile | (ksel << 4) | (ns << 8) | ((kspl > 1 ? kspl : 0) << 12));
                             }
-                            hipEventRecord(e0, ctx->stream);
-                            for (int r = 0; r < reps; ++r) ctx->launch_conv(st.first_op + k, buckets[bi], src, dst, res, cfg);
-                            hipEventRecord(e1, ctx->stream);
-                            if (hipEventSynchronize(e1) != hipSuccess) { rc = EE_ERR_DEVICE; break; }
-                            float ms = 0.f;
-                            hipEventElapsedTime(&ms, e0, e1);
-                            if (ms < best_ms) { best_ms = ms; best[bi] = cfg; }
-                        }
+                for (int tile = 1; tile <= 4; ++tile)                                   // the slab kernel, where the layer is of its kind
+                    for (int ksel = 2; ksel <= 3; ++ksel)
+                        for (int ns = 2; ns <= 4; ++ns) cands.push_back(EE_CFG_SLAB | tile | (ksel << 4) | (ns << 8));
+                for (const int cfg : cands) {
+                    if (ctx->launch_conv(st.first_op + k, buckets[bi], src, dst, res, cfg) != hipSuccess) {
+                        (void)hipGetLastError();                       // this configuration does not exist or fit here: skip it
+                        continue;
+                    }
+                    hipEventRecord(e0, ctx->stream);
+                    for (int r = 0; r < reps; ++r) ctx->launch_conv(st.first_op + k, buckets[bi], src, dst, res, cfg);
+                    hipEventRecord(e1, ctx->stream);
+                    if (hipEventSynchronize(e1) != hipSuccess) { rc = EE_ERR_DEVICE; break; }
+                    float ms = 0.f;
+                    hipEventElapsedTime(&ms, e0, e1);
+                    if (ms < best_ms) { best_ms = ms; best[bi] = cfg; }
+                }
             }
             if (!rc) p.cfg = best;
         }
@@ -619,6 +640,13 @@ extern "C" int ee_config_set(ee_ctx* ctx, int op, const int* cfg, int n)
             ctx->fill_conv_args(op, 1, a);
             a.res = p.d.res >= 0 ? (const void*)ctx : nullptr;               // only whether there is one matters here
             if (!conv_stream_supported(a, ctx->net.elem_bytes())) return EE_ERR_ARG;
+            continue;
+        }
+        if (cfg[i] > 0 && (cfg[i] & EE_CFG_SLAB)) {                          // the slab kernel, for the layers it covers
+            ConvArgs a{};
+            ctx->fill_conv_args(op, 1, a);
+            if (p.impl != IMPL_MFMA || !conv_slab_supported(a, ctx->net.elem_bytes())) return EE_ERR_ARG;
+            if ((cfg[i] >> 17) || tile < 1 || tile > 4 || (ksel != 0 && ksel != 2 && ksel != 3) || (ns != 0 && (ns < 2 || ns > 4)) || kspl != 0) return EE_ERR_ARG;
             continue;
         }
         if (cfg[i] < 0 || (cfg[i] >> 16) || tile > 4 || ksel > 3 || (ns != 0 && (ns < 2 || ns > 4)) || (kspl != 0 && kspl != 2 && kspl != 4)) return EE_ERR_ARG;

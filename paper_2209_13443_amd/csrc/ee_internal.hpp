@@ -100,6 +100,10 @@ template <int ES> hipError_t launch_conv_igemm(const ConvArgs& a, int tile, hipS
 // the fused pair (ES = element bytes); cfg 0 = chosen by shape
 template <int ES> hipError_t launch_conv_pair(const PairArgs& p, int cfg, hipStream_t s);
 bool conv_pair_supported(int es, int co2, int kh, int kw, int ci, int co3);
+// stride-1 "same" convolutions with the activation slab of a tile resident in LDS (kernels_slab.hip); cfg as documented there
+bool conv_slab_supported(const ConvArgs& a, int es);
+template <int ES> hipError_t launch_conv_slab(const ConvArgs& a, int cfg, hipStream_t s);
+enum { EE_CFG_SLAB = 0x10000 };     // configuration words with this bit name the slab kernel
 // streaming kernel for large, thin int8 layers (es = element bytes); hipErrorInvalidValue for a layer it does not cover
 bool conv_stream_supported(const ConvArgs& a, int es);
 hipError_t launch_conv_stream(const ConvArgs& a, hipStream_t s);

@@ -37,6 +37,13 @@ __device__ __forceinline__ void wait_copies_then_barrier()
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
+// also waits for this wavefront's own LDS reads
+template <int N>
+__device__ __forceinline__ void wait_all_then_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
 // bytes of LDS the ring takes: the stages in use, and never less than the output tile that reuses it
 __host__ __device__ constexpr unsigned igemm_ring_bytes(int ns, int nk, int stage_bytes, int tile_o)
 {

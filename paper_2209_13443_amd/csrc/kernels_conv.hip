@@ -293,8 +293,8 @@ template <int ES>
 static hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t s)
 {
     if (a.M <= 0) return hipSuccess;
-    int tile = g_forced_tile;
-    if (tile == 0) {
+    int tile = g_forced_tile & 15;
+    if (tile == 0 || tile > 4) {
         auto blocks = [&](int bm, int bn) { return (long long)((a.M + bm - 1) / bm) * ((a.Co + bn - 1) / bn); };
         const long long want = 3 * 256;
         if (a.Co > 64) tile = blocks(128, 128) >= want ? 1 : (blocks(64, 128) >= want ? 4 : 3);

@@ -34,9 +34,13 @@
 
 #include "ee_internal.hpp"
 #include "igemm_device.hpp"
+#include "igemm_epilogue.hpp"
 
 namespace ee {
 
+#ifndef EE_IGEMM_PIPELINED
+#define EE_IGEMM_PIPELINED 1
+#endif
 
 // ES: element bytes (1 int8, 2 bf16).  BM x BN: workgroup tile (pixels x channels).  KS: bytes of
 // the reduction axis per stage.  ns (2..4, not above the number of steps + 1): stages in the ring.  PLAIN: 1x1 kernel without padding whose
@@ -57,14 +61,7 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
     constexpr int NA = BM / RPP, NB = BN / RPP, LPT = NA + NB;
     constexpr int STAGE = (BM + BN) * KS;
     constexpr int R256 = KS >= 256 ? 1 : 256 / KS; // staged rows per 256 bytes of LDS
-    constexpr int CR = BN * ES / 16;               // 16-byte chunks per row of the output tile
-    constexpr int OROW = BN * ES, TILE_O = BM * OROW;
-    constexpr int NO = (BM * CR + NT - 1) / NT;    // output-tile passes of the workgroup
-    // output tile: chunk c of row r sits at c ^ oswz(r), oswz(r) = (r / rows per 256 bytes) & (CR - 1): the 32 rows
-    // a wavefront touches with one 4- or 8-byte access per lane then spread over the banks as evenly as the
-    // row length allows (two rows per bank instead of eight)
-    constexpr int OR256 = OROW >= 256 ? 1 : 256 / OROW;
-    auto oswz = [](int r) { return (r / OR256) & (CR - 1); };
+    constexpr int TILE_O = BM * BN * ES;           // the output tile in LDS (igemm_epilogue.hpp)
     constexpr int NSUB = KS / 32, SPW = NSUB / KSPL;   // matrix sub-steps per stage, and per wavefront
     constexpr int PART = TM * TN * 4096;           // bytes of one wavefront's accumulators
     static_assert(NA >= 1 && NB >= 1 && BM % RPP == 0 && BN % RPP == 0, "tile too small for this many lanes");
@@ -94,16 +91,7 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
     const unsigned bias_off = has_res && wide ? ring + TILE_O : ring;
 
     // ---- bias and residual tile: copied first, consumed last --------------------------------------
-    if (wave == 0) dma16(lds0 + bias_off, (const unsigned char*)a.bias + (size_t)n0 * 4 + lane * 16);
-    if (has_res && wide) {
-#pragma unroll
-        for (int j = 0; j < NO; ++j) {
-            const int q = tid + NT * j, row = q / CR, chunk = (q % CR) ^ oswz(row);
-            const int m = m0 + row, ch = n0 + chunk * (16 / ES);
-            const unsigned char* p = (m < a.M && ch < a.Co) ? (const unsigned char*)a.res + ((size_t)m * a.Co + ch) * ES : zp;
-            if (NT * j + 64 * wave < BM * CR) dma16(lds0 + ro_off + (NT * j + 64 * wave) * 16, p);      // wave-uniform
-        }
-    }
+    igemm_stage_bias_res<ES, BM, BN, NT>(a, lds0, ro_off, bias_off, m0, n0, tid, wave, lane, has_res && wide);
 
     // ---- per-lane copy state ------------------------------------------------------------------------
     const int lrow = tid / CPRW;
@@ -230,10 +218,94 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
         if (ISSUE && !PLAIN) advance_tap(KS);
     };
 
+    // ---- the pipelined form of a step (steps of at least four sub-steps, one wavefront group) -----------------
+    // A wavefront issues in order, so whatever stands between two matrix instructions delays the second one.
+    // Here every matrix instruction is followed by at most one fragment read and one copy, fragments are read
+    // FD sub-steps before they are used (into NFB register sets used in turn), and the wait for the next stage
+    // plus the workgroup barrier sit FD sub-steps before the end of a step, so that the first fragments of the
+    // next step are on their way while this step still multiplies.  Copies of a step are issued in its first
+    // SPW - FD sub-steps, i.e. before that barrier: behind it only the ns - 2 later stages are outstanding.
+    constexpr bool V2 = EE_IGEMM_PIPELINED && KSPL == 1 && SPW >= 4;
+    constexpr int FD = 2, NFB = 4;
+    v4i gw[V2 ? NFB : 1][TN], gx[V2 ? NFB : 1][TM];
+    auto step2 = [&](int sc, int sn, int si, auto issue_tag, auto last_tag) {
+        constexpr bool ISSUE = decltype(issue_tag)::value, LAST = decltype(last_tag)::value;
+        constexpr int NM = TN * TM, NR = TN + TM, ISUBS = SPW > FD ? SPW - FD : 1, PPS = (LPT + ISUBS - 1) / ISUBS;
+        const unsigned char* sa = lds + sc * STAGE + wm0 * KS;
+        const unsigned char* sb = lds + sc * STAGE + (BM + wn0) * KS;
+        const unsigned char* na = lds + sn * STAGE + wm0 * KS;
+        const unsigned char* nb = lds + sn * STAGE + (BM + wn0) * KS;
+        const unsigned sbase = lds0 + si * STAGE + wave * 1024;
+        const unsigned tapbit = tap < ntaps ? 1u << tap : 0u;
+        static_for<SPW>([&](auto sub_tag) {
+            constexpr int SUB = decltype(sub_tag)::value;
+            if constexpr (SUB == SPW - FD && !LAST) {
+                // the next stage has landed for everybody, and everybody has read the last fragments of the stage
+                // before this one (whose slot the next step's copies overwrite)
+                if (!ISSUE || ns == 2) wait_all_then_barrier<0>();
+                else if (ns == 3) wait_all_then_barrier<LPT>();
+                else wait_all_then_barrier<2 * LPT>();
+            }
+            constexpr int TSUB = SUB + FD;                        // the sub-step whose fragments are read now
+            constexpr bool NEXT = TSUB >= SPW;
+            constexpr int RS = NEXT ? TSUB - SPW : TSUB;
+            constexpr bool DO_READ = !(NEXT && LAST);
+            const unsigned char* ra = NEXT ? na : sa;
+            const unsigned char* rb = NEXT ? nb : sb;
+            static_for<NM>([&](auto q_tag) {
+                constexpr int Q = decltype(q_tag)::value, J = Q / TM, I = Q % TM;
+                if constexpr (ES == 1)
+                    acc[J][I] = __builtin_amdgcn_mfma_i32_32x32x32_i8(gw[SUB % NFB][J], gx[SUB % NFB][I], acc[J][I], 0, 0, 0);
+                else
+                    acc[J][I] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, gw[SUB % NFB][J]),
+                                                                         __builtin_bit_cast(v8bf, gx[SUB % NFB][I]), acc[J][I], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                static_for<(NR + NM - 1) / NM>([&](auto r_tag) {
+                    constexpr int R = Q + NM * decltype(r_tag)::value;
+                    if constexpr (DO_READ && R < NR) {
+                        if constexpr (R < TN) gw[TSUB % NFB][R] = *(const v4i*)(rb + 32 * R * KS + fragoff[RS]);
+                        else gx[TSUB % NFB][R - TN] = *(const v4i*)(ra + 32 * (R - TN) * KS + fragoff[RS]);
+                    }
+                });
+                if constexpr (ISSUE && SUB < ISUBS)
+                    static_for<(PPS + NM - 1) / NM>([&](auto d_tag) {
+                        constexpr int D = Q + NM * decltype(d_tag)::value, P = SUB * PPS + D;
+                        if constexpr (D < PPS && P < LPT) issue_piece(std::integral_constant<int, P>{}, sbase, tapbit);
+                    });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+        if (ISSUE && !PLAIN) advance_tap(KS);
+    };
+
     // ---- main loop: step ks computes out of stage ks % ns while steps ks+1 .. ks+ns-1 are in flight ----
     for (int s = 0; s < ns - 1; ++s)
         if (s < nk) issue_all(s);
     int st_c = 0, st_i = ns - 1, ks = 0;
+    if constexpr (V2) {
+        const int ahead = (ns - 1 < nk ? ns - 1 : nk) - 1;      // stages issued behind the first one
+        if (ahead <= 0) wait_copies_then_barrier<0>();
+        else if (ahead == 1) wait_copies_then_barrier<LPT>();
+        else wait_copies_then_barrier<2 * LPT>();
+        static_for<FD>([&](auto u_tag) {                // fragments of the first FD sub-steps
+            constexpr int U = decltype(u_tag)::value;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) gw[U][j] = *(const v4i*)(lds + (BM + wn0) * KS + 32 * j * KS + fragoff[U]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) gx[U][i] = *(const v4i*)(lds + wm0 * KS + 32 * i * KS + fragoff[U]);
+        });
+        auto next_of = [&](int st) { return st + 1 == ns ? 0 : st + 1; };
+        for (; ks + ns - 1 < nk; ++ks) {
+            step2(st_c, next_of(st_c), st_i, std::true_type{}, std::false_type{});
+            st_c = next_of(st_c);
+            st_i = next_of(st_i);
+        }
+        for (; ks + 1 < nk; ++ks) {                     // nothing left to copy
+            step2(st_c, next_of(st_c), st_c, std::false_type{}, std::false_type{});
+            st_c = next_of(st_c);
+        }
+        step2(st_c, st_c, st_c, std::false_type{}, std::true_type{});
+    } else {
     for (; ks + ns - 1 < nk; ++ks) {
         // steps ks+1 .. ks+ns-2 may still be in flight, each LPT copies of this wavefront
         if (ns == 2) wait_copies_then_barrier<0>();
@@ -247,6 +319,7 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
         wait_copies_then_barrier<0>();
         step(st_c, st_c, std::false_type{});
         st_c = st_c + 1 == ns ? 0 : st_c + 1;
+    }
     }
     lds_barrier();                                  // every wavefront is done with the ring
     if constexpr (KSPL > 1) {
@@ -287,81 +360,7 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int 
         lds_barrier();                              // the parking area is free again: the output tile may alias it
     }
 
-    // ---- epilogue ------------------------------------------------------------------------------------------
-    unsigned char* ro = lds + ro_off;
-    const int* lbias = (const int*)(lds + bias_off);
-    // Cell of (pixel row r, channel cl) in the output tile: chunk (cl*ES/16) ^ oswz(r) of row r.  oswz has period
-    // 16, so it is oswz(frow) for all of a lane's rows, and the chunk index splits into a wave-uniform part
-    // and a compile-time part: one XOR and one add per cell remain.
-    const int swz_l = oswz(frow);
-    auto finish = [&](auto res_tag, auto wide_tag) {
-        constexpr bool RES = decltype(res_tag)::value, WIDE = decltype(wide_tag)::value;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int r = wm0 + 32 * i + frow;
-            const int m = m0 + r;
-            unsigned char* rowp = ro + r * OROW + 4 * hi * ES;
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int cl = wn0 + 32 * j + 8 * g + 4 * hi;                     // first of this lane's 4 channels
-                    const int chunk = (wn0 * ES >> 4) + ((32 * j + 8 * g) * ES >> 4);  // 4*hi*ES stays inside the chunk
-                    unsigned char* cell = rowp + ((chunk ^ swz_l) << 4) + (((32 * j + 8 * g) * ES) & 15);
-                    const long long o = (long long)m * a.Co + n0 + cl;                  // in the residual (never a slice)
-                    const long long oy_ = (long long)m * a.ldc + a.c_off + n0 + cl;      // in the output
-                    const bool inside = WIDE || (m < a.M && n0 + cl < a.Co);
-                    const v4i b4 = *(const v4i*)(lbias + cl);
-                    if constexpr (ES == 1) {
-                        int packed = 0;
-                        if (RES) packed = WIDE ? *(const int*)cell : (inside ? *(const int*)((const signed char*)a.res + o) : 0);
-                        int q[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            int t = acc[j][i][4 * g + e] + b4[e];                     // the rounding constant is part of the bias
-                            if (RES) t += __builtin_amdgcn_sbfe(packed, 8 * e, 8) << a.res_shift;
-                            q[e] = clamp_i32(t >> a.shift, a.lo, a.hi);
-                        }
-                        const unsigned out = pack4_i8(q[0], q[1], q[2], q[3]);
-                        if (WIDE) *(unsigned*)cell = out;
-                        else if (inside) *(unsigned*)((signed char*)a.y + oy_) = out;
-                    } else {
-                        uint2 packed = {0u, 0u};
-                        if (RES) packed = WIDE ? *(const uint2*)cell : (inside ? *(const uint2*)((const uint16_t*)a.res + o) : packed);
-                        const float r0 = __uint_as_float(packed.x << 16), r1 = __uint_as_float(packed.x & 0xFFFF0000u);
-                        const float r2 = __uint_as_float(packed.y << 16), r3 = __uint_as_float(packed.y & 0xFFFF0000u);
-                        float t0 = acc[j][i][4 * g + 0] + __int_as_float(b4[0]), t1 = acc[j][i][4 * g + 1] + __int_as_float(b4[1]);
-                        float t2 = acc[j][i][4 * g + 2] + __int_as_float(b4[2]), t3 = acc[j][i][4 * g + 3] + __int_as_float(b4[3]);
-                        if (RES) { t0 += r0; t1 += r1; t2 += r2; t3 += r3; }
-                        t0 = fminf(fmaxf(t0, a.f_lo), a.f_hi); t1 = fminf(fmaxf(t1, a.f_lo), a.f_hi);
-                        t2 = fminf(fmaxf(t2, a.f_lo), a.f_hi); t3 = fminf(fmaxf(t3, a.f_lo), a.f_hi);
-                        uint2 out;
-                        out.x = to_bf16_rne(t0) | (to_bf16_rne(t1) << 16);
-                        out.y = to_bf16_rne(t2) | (to_bf16_rne(t3) << 16);
-                        if (WIDE) *(uint2*)cell = out;
-                        else if (inside) *(uint2*)((uint16_t*)a.y + oy_) = out;
-                    }
-                }
-        }
-    };
-    if (KSPL == 1 || kpart == 0) {
-        if (wide) {
-            if (has_res) finish(std::true_type{}, std::true_type{});
-            else finish(std::false_type{}, std::true_type{});
-        } else {
-            if (has_res) finish(std::true_type{}, std::false_type{});
-            else finish(std::false_type{}, std::false_type{});
-        }
-    }
-    if (wide) {
-        lds_barrier();
-#pragma unroll
-        for (int j = 0; j < NO; ++j) {
-            const int q = tid + NT * j, row = q / CR, chunk = (q % CR) ^ oswz(row);
-            const int m = m0 + row, ch = n0 + chunk * (16 / ES);
-            if (q < BM * CR && m < a.M && ch < a.Co) *(v4i*)((unsigned char*)a.y + ((size_t)m * a.ldc + a.c_off + ch) * ES) = *(const v4i*)(ro + q * 16);
-        }
-    }
+    igemm_epilogue<ES, BM, BN, NT>(a, acc, lds, ro_off, bias_off, m0, n0, wm0, wn0, tid, has_res, wide, KSPL == 1 || kpart == 0);
 }
 
 // ---- launch ------------------------------------------------------------------------------------------------
@@ -375,7 +374,9 @@ static hipError_t launch_igemm_tile(const ConvArgs& a, bool plain, int ns, hipSt
     const int nk = (a.kh * a.kw * a.Ci * ES + KS - 1) / KS;
     ns = ns < 2 ? 2 : (ns > 4 ? 4 : ns);
     constexpr int TILE_O = BM * BN * ES, PARK = (KSPL - 1) * 4 * (BM / 64) * (BN / 64) * 4096;
-    const size_t lds_bytes = igemm_ring_bytes(ns, nk, (BM + BN) * KS, TILE_O > PARK ? TILE_O : PARK) + (res_tile ? (size_t)TILE_O : 0) + 1024;
+    auto lds_need = [&](int stages) { return igemm_ring_bytes(stages, nk, (BM + BN) * KS, TILE_O > PARK ? TILE_O : PARK) + (res_tile ? (size_t)TILE_O : 0) + 1024; };
+    while (ns > 2 && lds_need(ns) > 160 * 1024) --ns;      // the deepest ring that fits
+    const size_t lds_bytes = lds_need(ns);
     // more than 64 KiB of dynamic LDS has to be granted once per kernel
     static const hipError_t granted = [] {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_igemm_kernel<ES, BM, BN, KS, KSPL, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);

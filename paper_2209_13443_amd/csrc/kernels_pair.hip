@@ -21,12 +21,6 @@
 
 namespace ee {
 
-template <int N>
-__device__ __forceinline__ void wait_all_then_barrier()
-{
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
-}
-
 // ES: element bytes.  BM: pixel rows per workgroup.  BN1: output channels of the first layer (all of them).
 // KS: bytes of the first reduction per ring stage.  BN2: output channels of the second layer per chunk.
 template <int ES, int BM, int BN1, int KS, int BN2>

@@ -209,6 +209,32 @@ def test_int8_every_conv_tiling_bit_exact(torch, ee, orc, name, tile):
     eng.close()
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("cfg", [0x0321, 0x0421, 0x0231, 0x0331, 0x0322, 0x0432, 0x0323, 0x0433, 0x0324, 0x0234,
+                                 0x10321, 0x10431, 0x10222, 0x10332, 0x10323, 0x10233, 0x10324, 0x10434])
+def test_int8_pipelined_steps_bit_exact(torch, ee, orc, cfg):
+    """Reduction steps of 128 and 256 bytes run the pipelined form of the inner loop (fragments read two sub-steps ahead,
+    barrier before the end of a step): every tiling of it with rings of 2, 3 and 4 stages, on layers with one, two and
+    many steps and a ragged last tile, against the oracle.  Words with bit 16 name the slab kernel (stride-1 layers whose
+    output is as large as the input; the other layers keep their default kernel): its four tiles, both weight steps."""
+    for name in ("zoo_i8", "resnet50_small_i8") if cfg < 0x10000 else ("resnet50_small_i8", "resnet18_small_i8", "inception_small_i8"):
+        blob = W.load_net(name)
+        eng = ee.Engine(blob, 8)
+        x = W.input_pool(blob, 5)
+        old = ee.tune_conv_tile(cfg)
+        try:
+            act = x
+            for s in range(blob.n_stages):
+                say(f"[case] {name} cfg {cfg:#x} segment {s}")
+                ref = orc.stage_forward(blob, s, act)
+                got = host(eng.stage_forward(s, dev(torch, act), ref.shape[1:]), ref)
+                assert np.array_equal(got, ref), f"cfg {cfg:#x} stage {s}"
+                act = ref
+        finally:
+            ee.tune_conv_tile(old)
+        eng.close()
+
+
 def test_autotuned_configuration_table_keeps_results(torch, ee, orc):
     """The per-(layer, batch bucket) kernel configuration table only changes speed, never a byte."""
     for name in ("resnet50_small_i8", "zoo_i8"):
@@ -580,11 +606,11 @@ def test_bf16_within_tolerance(torch, ee, orc, name):
     blob = W.load_net(name)
     eng = ee.Engine(blob, 16)
     x = W.input_pool(blob, 12)
-    for tile in (0, 1, 2, 3, 4):
+    for tile in (0, 1, 2, 3, 4, 0x0321, 0x0432, 0x10321, 0x10332, 0x10423, 0x10234):     # tiles, pipelined steps, the slab kernel
         ee.tune_conv_tile(tile)
         act = x
         for s in range(blob.n_stages):
-            say(f"[case] {name} tile {tile} segment {s}")
+            say(f"[case] {name} tile {tile:#x} segment {s}")
             ref = orc.stage_forward(blob, s, act)
             got = host(eng.stage_forward(s, dev(torch, act), ref.shape[1:]), ref)
             r, g = bf16_to_f32(ref).astype(np.float64), bf16_to_f32(got).astype(np.float64)
