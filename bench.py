@@ -226,9 +226,12 @@ def run_stream(args, name, steps, warmup, full=True):
     lanes = ((args.lanes if full else 0) or wl.get("lanes", 2)) if refill == 2 else 1
     eng.set_lanes(lanes)
 
-    def step(policy=refill, arr=None, min_incr_=None, lanes_=None):
+    # survivors of an exit stay where they are (zero-copy compaction) wherever the network allows it and two lanes suffice
+    zero_copy = int(eng.zero_copy_supported() and args.zero_copy != 0 and lanes <= 2)
+
+    def step(policy=refill, arr=None, min_incr_=None, lanes_=None, zc=None):
         return eng.serve_stream(arrivals if arr is None else arr, pool, lut, clock=0, refill=policy, min_incr=min_incr_ or min_incr, t_slo_ns=t_slo_ns,
-                                lanes=(lanes_ or lanes) if policy == 2 else 1)
+                                lanes=(lanes_ or lanes) if policy == 2 else 1, zero_copy=zero_copy if zc is None else zc)
 
     def timed_steps(k, **kw):
         step(**kw)
@@ -275,6 +278,8 @@ def run_stream(args, name, steps, warmup, full=True):
         capacity = summary(rate_c, res_c, st_c)
         if refill == 2 and lanes > 1:
             capacity["one_lane_samples_per_s"] = round(timed_steps(1, arr=zeros, lanes_=1)[0], 1)
+        if zero_copy:
+            capacity["copying_compaction_samples_per_s"] = round(timed_steps(k_side, arr=zeros, zc=0)[0], 1)
 
     # Per-kernel durations: HIP events on the library's streams around every launch of one more step of the same
     # workload on one lane (kernels of concurrent steps share the chip, so their durations would say nothing about a
@@ -285,6 +290,9 @@ def run_stream(args, name, steps, warmup, full=True):
         eng.profile(True)
         step(lanes_=1)
         kstats, layer_stats = eng.profile_read(len(blob.ops))
+        if zero_copy:                                  # the compaction kernel only runs in the copying mode: one more step for its line
+            step(lanes_=1, zc=0)
+            kstats["compact"] = eng.profile_read(len(blob.ops))[0]["compact"]
         eng.profile(False)
 
     # dominant kernel: the MFMA implicit-GEMM convolution
@@ -347,6 +355,7 @@ def run_stream(args, name, steps, warmup, full=True):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": name, "requests": n, "b_max": b_max, "refill": refill,
                    "policy": ["static batches", "Algorithm 1", "stage pools"][refill], "lanes": lanes if refill == 2 else None,
+                   "compaction": "zero-copy (slot tables)" if zero_copy else "copy",
                    "min_incr": min_incr if refill == 1 else None,
                    "arrival": "poisson" if load else "all_at_t0", "arrival_rate_per_s": round(load * static_rate, 1) if load else None,
                    "clock": "wall", "t_slo_ms": args.t_slo_ms if t_slo_ns >= 0 else None},
@@ -382,6 +391,7 @@ def main():
     ap.add_argument("--refill", type=int, default=-1, choices=[-1, 0, 1, 2],
                     help="serving policy of the timed steps: 0 model-level batching, 1 Algorithm 1, 2 stage pools (-1 = the workload's)")
     ap.add_argument("--lanes", type=int, default=0, help="stage pools: steps in flight at once (0 = the workload's)")
+    ap.add_argument("--zero-copy", type=int, default=-1, choices=[-1, 0, 1], help="0: always the copying compaction kernel; else zero-copy compaction where the network allows it")
     ap.add_argument("--load", type=float, default=0.0, help="arrival rate as a multiple of the static-batch throughput (0 = the workload's)")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples timed on the CPU oracle (0 = automatic, -1 = skip)")
     ap.add_argument("--save-tables", default="", help="write the tuned kernel-configuration tables to this JSON file")

@@ -128,8 +128,15 @@ typedef struct {
                                a full batch is issued at once, an incomplete one when the oldest queued request has waited
                                this long; <= 0: whatever is queued is issued at once.  B_max = 1 is the SERIAL baseline. */
     int32_t lanes;          /* refill = 2: steps that may be in flight at once, 1..4 (0 = 1), at most what ee_lanes made */
-    int32_t pad_;
+    int32_t zero_copy;      /* 1: survivors of an exit are not moved (Sec. III-A: only the addressing changes): the samples of a batch
+                               stay in the slots the segment wrote and the next segment gathers them through a slot table;
+                               0: the compaction kernel copies them into a dense batch.  Results and schedule are the same.
+                               EE_ERR_UNSUPPORTED unless ee_zero_copy_supported; with refill = 2 at most two lanes. */
 } ee_serve_opts;
+
+/* 1 when the context can serve with zero_copy = 1: b_max <= 256 and every tensor that crosses a segment boundary is read
+ * and written by the general matrix-core convolution kernel only; else 0. */
+int ee_zero_copy_supported(const ee_ctx* ctx);
 
 /* refill = 2, stage pools, is an extension that is not in the paper.  Algorithm 1 keeps one active batch
  * and lets newcomers catch up with it (Sec. III-B, non-recursive by design); here the survivors of exit i

@@ -26,7 +26,7 @@ SYMBOLS = ["ee_strerror", "ee_blob_check", "ee_create", "ee_destroy", "ee_query"
            "ee_compact_refill", "ee_serve_stream", "ee_schedule_sim", "ee_measure_lut", "ee_profile_enable",
            "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_last_logits", "ee_profile_reserve", "ee_autotune", "ee_config_table",
            "ee_pair_count", "ee_pair_mode", "ee_pair_table", "ee_config_set", "ee_pair_set", "ee_exit_head_static",
-           "ee_static_scratch_bytes", "ee_time_layer", "ee_lanes"]
+           "ee_static_scratch_bytes", "ee_time_layer", "ee_lanes", "ee_zero_copy_supported"]
 
 
 class Trace(C.Structure):
@@ -35,7 +35,7 @@ class Trace(C.Structure):
 
 class ServeOpts(C.Structure):
     _fields_ = [("b_max", C.c_int32), ("clock", C.c_int32), ("t_slo_ns", C.c_int64), ("lut_ns", C.c_void_p),
-                ("min_incr", C.c_int32), ("refill", C.c_int32), ("t_timeout_ns", C.c_int64), ("lanes", C.c_int32), ("pad_", C.c_int32)]
+                ("min_incr", C.c_int32), ("refill", C.c_int32), ("t_timeout_ns", C.c_int64), ("lanes", C.c_int32), ("zero_copy", C.c_int32)]
 
 
 class ServeStats(C.Structure):
@@ -74,6 +74,7 @@ _lib.ee_last_logits.argtypes = [_V, C.c_int, _V]
 _lib.ee_autotune.argtypes = [_V, C.c_int]
 _lib.ee_config_table.argtypes = [_V, C.c_int, _V, C.c_int]
 _lib.ee_pair_count.argtypes = [_V]
+_lib.ee_zero_copy_supported.argtypes = [_V]
 _lib.ee_pair_mode.argtypes = [_V, C.c_int]
 _lib.ee_pair_table.argtypes = [_V, C.c_int, _V, C.c_int]
 _lib.ee_config_set.argtypes = [_V, C.c_int, _V, C.c_int]
@@ -217,20 +218,24 @@ class Engine:
         return dst[:b_merged], ids_dst[:b_merged], b_rem, b_merged
 
     # -- stream serving ----------------------------------------------------------------------
-    def serve_stream(self, arrival_ns, pool, lut_ns, b_max=None, clock=0, t_slo_ns=-1, min_incr=1, refill=1, max_events=0, t_timeout_ns=0, lanes=1):
+    def serve_stream(self, arrival_ns, pool, lut_ns, b_max=None, clock=0, t_slo_ns=-1, min_incr=1, refill=1, max_events=0, t_timeout_ns=0, lanes=1,
+                     zero_copy=0):
         arrival_ns = np.ascontiguousarray(arrival_ns, np.int64)
         lut_ns = np.ascontiguousarray(lut_ns, np.int64)
         b_max = b_max or self.b_max
         assert lut_ns.shape == (self.n_stages, b_max)
         n = arrival_ns.size
         tr = Trace(n, arrival_ns.ctypes.data)
-        opts = ServeOpts(b_max, clock, t_slo_ns, lut_ns.ctypes.data, min_incr, refill, t_timeout_ns, lanes, 0)
+        opts = ServeOpts(b_max, clock, t_slo_ns, lut_ns.ctypes.data, min_incr, refill, t_timeout_ns, lanes, int(zero_copy))
         res = np.zeros(n, RESULT_DT)
         ev = np.zeros(max(max_events, 1), EVENT_DT)
         st = ServeStats()
         _chk(_lib.ee_serve_stream(self._h, C.byref(tr), pool.data_ptr(), C.byref(opts), res.ctypes.data, C.byref(st),
                                   ev.ctypes.data if max_events else None, max_events))
         return res, _stats_dict(st, self.n_stages), ev[:min(st.n_events, max_events)]
+
+    def zero_copy_supported(self):
+        return _lib.ee_zero_copy_supported(self._h) == 1
 
     def set_lanes(self, n):
         """ee_lanes: workspace and streams for n concurrent steps of the stage-pool policy; returns the lane count"""

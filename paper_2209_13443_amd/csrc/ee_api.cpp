@@ -372,9 +372,25 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
     // stream-serving workspace.  Shared by all lanes: the packed input slots of every segment behind the first, a ring of
     // 3 b_max samples (the stage-pool policy keeps up to 2 b_max - 1 waiting samples there while a batch of up to b_max
     // is being read).  Per lane: everything alloc_lane makes; lane 0 is made here on the caller's stream.
+    // Zero-copy compaction needs five blocks: up to 2 b_max - 1 waiting samples, the batch that is being read, and the
+    // outputs of two steps in flight.  It is offered when every tensor that crosses a segment boundary is read and
+    // written by the general matrix-core kernel only (the kernel that takes slot tables), b_max fits a table, and the
+    // slots stay below 2 GiB (32-bit byte offsets).
+    ctx->zero_copy_ok = b_max <= EE_ZC_MAX_B && n_st > 1;
+    for (int s = 0; s < n_st && ctx->zero_copy_ok; ++s) {
+        const StageDesc& st = ctx->net.stages[s];
+        for (int k = 0; k < st.n_ops; ++k) {
+            const OpPlan& p = ctx->plans[st.first_op + k];
+            if (s > 0 && (p.src_buf == BUF_EXT_IN || (p.d.res >= 0 && p.res_buf == BUF_EXT_IN)) && (p.impl != IMPL_MFMA || (p.d.res >= 0 && p.res_buf == BUF_EXT_IN))) ctx->zero_copy_ok = false;
+            if (s + 1 < n_st && p.dst_buf == BUF_EXT_OUT && p.impl != IMPL_MFMA) ctx->zero_copy_ok = false;
+            if (p.src_buf == BUF_EXT_OUT || (p.d.res >= 0 && p.res_buf == BUF_EXT_OUT)) ctx->zero_copy_ok = false;   // the scattered output is not read back
+        }
+        if (s > 0 && (double)ctx->stage_in_bytes(s) * b_max * 5 >= 2147483648.0) ctx->zero_copy_ok = false;
+    }
+    ctx->zc_slots = (ctx->zero_copy_ok ? 5 : 3) * b_max;
     ctx->in_buf.assign(n_st, nullptr);
     for (int s = 1; s < n_st; ++s)
-        if ((rc = dev_alloc(ctx, &ctx->in_buf[s], (size_t)ctx->stage_in_bytes(s) * b_max * 3))) return fail(rc);
+        if ((rc = dev_alloc(ctx, &ctx->in_buf[s], (size_t)ctx->stage_in_bytes(s) * ctx->zc_slots))) return fail(rc);
     ctx->lanes.resize(1);
     {
         LaneState& L0 = ctx->lanes[0];
@@ -468,7 +484,7 @@ void ee_ctx::fill_conv_args(int op, int b, ConvArgs& a) const
     a.shift = d.shift; a.res_shift = d.res_shift; a.lo = d.lo; a.hi = d.hi; a.f_lo = d.f_lo; a.f_hi = d.f_hi;
 }
 
-hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg)
+hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg, const SlotTab* xs, const SlotTab* ys)
 {
     const OpPlan& p = plans[op];
     const int dt = net.dtype;
@@ -481,6 +497,12 @@ hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const 
         return dt == EE_I8 ? launch_conv_mfma_i8(a, stream) : launch_conv_mfma_bf16(a, stream);
     }
     a.x = src; a.mode = 0;
+    if (xs || ys) {                                      // slot tables: the general kernel only
+        if (p.impl != IMPL_MFMA || b > EE_ZC_MAX_B) return hipErrorInvalidValue;
+        a.slots = (xs ? EE_GATHER_X : 0) | (ys ? EE_SCATTER_Y : 0);
+        if ((cfg & EE_CFG_SLAB) || (cfg & 15) == 7) cfg = 0;
+        return dt == EE_I8 ? launch_conv_igemm<1>(a, cfg, stream, xs, ys) : launch_conv_igemm<2>(a, cfg, stream, xs, ys);
+    }
     const bool streamable = conv_stream_supported(a, dt == EE_I8 ? 1 : 2);
     if ((cfg & 15) == 7) {
         if (streamable) return launch_conv_stream(a, stream);
@@ -675,6 +697,8 @@ extern "C" int ee_pair_mode(ee_ctx* ctx, int mode)
     return EE_OK;
 }
 
+extern "C" int ee_zero_copy_supported(const ee_ctx* ctx) { return ctx ? (ctx->zero_copy_ok ? 1 : 0) : EE_ERR_ARG; }
+
 extern "C" int ee_pair_count(const ee_ctx* ctx)
 {
     if (!ctx) return EE_ERR_ARG;
@@ -697,6 +721,10 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
         const void* res = d.res >= 0 ? resolve(this, p.res_buf, act_in, act_out) : nullptr;
         const double ops = p.ops_per_sample * b, bytes = p.bytes_per_sample * b + p.weight_bytes;
         hipError_t e = hipSuccess;
+        const SlotTab* xs = p.src_buf == BUF_EXT_IN ? zc_in : nullptr;
+        const SlotTab* ys = p.dst_buf == BUF_EXT_OUT ? zc_out : nullptr;
+        if ((xs || ys) && p.impl != IMPL_MFMA) return EE_ERR_UNSUPPORTED;
+        if (zc_in && d.res >= 0 && p.res_buf == BUF_EXT_IN) return EE_ERR_UNSUPPORTED;
         if (p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_C4 || p.impl == IMPL_MFMA_CPAD || p.impl == IMPL_MFMA_S2D) {
             if (p.impl == IMPL_MFMA_S2D && !(first_packed && k == 0)) {
                 const double pb = (double)b * ((double)d.h_in * d.w_in * d.c_in + (double)p.Hp * p.Wp * 16) * es;
@@ -716,7 +744,8 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                 if (e != hipSuccess) return EE_ERR_DEVICE;
             }
             int cfg = cfg_force > 0 ? cfg_force : forced_conv_tile();
-            if (p.pair && pair_mode > 0 && cfg == 0 && only_op < 0) {
+            const bool q_scatter = zc_out && k + 1 < st.n_ops && plans[st.first_op + k + 1].dst_buf == BUF_EXT_OUT;
+            if (p.pair && pair_mode > 0 && cfg == 0 && only_op < 0 && !xs && !ys && !q_scatter) {
                 // this layer and the next as one launch, unless the table says the two separate kernels are faster here
                 const int pc = p.pair_cfg.empty() ? 0 : p.pair_cfg[std::min<size_t>(bucket_of(b), p.pair_cfg.size() - 1)];
                 // untuned: fused below 32 samples, where it was measured to win (one launch fewer counts most there)
@@ -740,7 +769,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                 probe.res = res;
                 if (conv_stream_supported(probe, es) && ((cfg & 15) == 7 || probe.M >= 32768)) cls = EE_K_CONV_STREAM;
             }
-            e = timed(cls, ops, bytes, [&] { return launch_conv(st.first_op + k, b, src, dst, res, cfg); }, st.first_op + k);
+            e = timed(cls, ops, bytes, [&] { return launch_conv(st.first_op + k, b, src, dst, res, cfg, xs, ys); }, st.first_op + k);
         } else if (p.impl == IMPL_THIN) {
             ThinConvArgs a{src, p.w_dev, p.b_dev, dst, (long long)b * d.h_out * d.w_out, d.c_in, d.c_out, d.c_tot, d.c_off, d.shift, d.lo, d.hi};
             e = timed(EE_K_CONV_STREAM, ops, bytes, [&] { return launch_conv_thin(a, stream); }, st.first_op + k);
@@ -771,7 +800,7 @@ extern "C" int ee_stage_forward(ee_ctx* ctx, int stage, int b_act, const void* a
 
 // ---- one exit head ------------------------------------------------------------------------------------
 int ee_ctx::run_head(int stage, int b, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag, bool to_host,
-                     const ee::HeadScratch* own)
+                     const ee::HeadScratch* own, const ee::SlotTab* slots)
 {
     const ExitDesc& e = net.exits[stage];
     const int dt = net.dtype, es = net.elem_bytes();
@@ -786,7 +815,7 @@ int ee_ctx::run_head(int stage, int b, const void* act, float thr, int32_t* labe
     a.label = label; a.conf = conf; a.score = score; a.flag = flag;
     if (to_host) { a.host_out = h_out; a.host_seq = h_seq; a.seq_value = ++seq; a.arrive_counter = d_arrive; }
     const double act_bytes = (double)b * a.HW * a.C * es;
-    if (timed(EE_K_GAP, 0.0, act_bytes + 4.0 * b * a.C, [&] { return launch_head_gap(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;
+    if (timed(EE_K_GAP, 0.0, act_bytes + 4.0 * b * a.C, [&] { return launch_head_gap(a, dt, stream, slots); }) != hipSuccess) return EE_ERR_DEVICE;
     if (timed(EE_K_FC, 2.0 * b * a.C * a.n_cls, (double)a.C * a.n_cls * es + 4.0 * b * (a.C + a.n_cls),
               [&] { return launch_head_fc(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;
     if (timed(EE_K_SOFTMAX, 0.0, 4.0 * b * a.n_cls + 17.0 * b, [&] { return launch_head_softmax(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;

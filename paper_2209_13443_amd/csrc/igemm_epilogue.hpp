@@ -59,6 +59,12 @@ __device__ __forceinline__ void igemm_epilogue(const ConvArgs& a, ACC& acc, unsi
     // Cell of (pixel row r, channel cl) in the output tile: chunk (cl*ES/16) ^ oswz(r) of row r.  oswz has period
     // 16, so it is oswz(frow) for all of a lane's rows, and the chunk index splits into a wave-uniform part
     // and a compile-time part: one XOR and one add per cell remain.
+    // zero-copy compaction: sample n of the output goes to slot ys[n] of y (second table of the kernel arguments)
+    auto out_row = [&](int m) -> long long {
+        if (!(a.slots & EE_SCATTER_Y) || m >= a.M) return m;
+        const unsigned howo = (unsigned)(a.Ho * a.Wo), n = fast_div((unsigned)m, howo, a.magic_howo);
+        return (long long)slot_tab(1, n) * howo + ((unsigned)m - n * howo);
+    };
     const int swz_l = oswz(frow);
     auto finish = [&](auto res_tag, auto wide_tag) {
         constexpr bool RES = decltype(res_tag)::value, WIDE = decltype(wide_tag)::value;
@@ -75,7 +81,7 @@ __device__ __forceinline__ void igemm_epilogue(const ConvArgs& a, ACC& acc, unsi
                     const int chunk = (wn0 * ES >> 4) + ((32 * j + 8 * g) * ES >> 4);  // 4*hi*ES stays inside the chunk
                     unsigned char* cell = rowp + ((chunk ^ swz_l) << 4) + (((32 * j + 8 * g) * ES) & 15);
                     const long long o = (long long)m * a.Co + n0 + cl;                  // in the residual (never a slice)
-                    const long long oy_ = (long long)m * a.ldc + a.c_off + n0 + cl;      // in the output
+                    const long long oy_ = (WIDE ? 0ll : out_row(m) * a.ldc) + a.c_off + n0 + cl;   // in the output (used by the direct stores only)
                     const bool inside = WIDE || (m < a.M && n0 + cl < a.Co);
                     const v4i b4 = *(const v4i*)(lbias + cl);
                     if constexpr (ES == 1) {
@@ -125,7 +131,7 @@ __device__ __forceinline__ void igemm_epilogue(const ConvArgs& a, ACC& acc, unsi
         for (int j = 0; j < NO; ++j) {
             const int q = tid + NT * j, row = q / CR, chunk = (q % CR) ^ oswz(row);
             const int m = m0 + row, ch = n0 + chunk * (16 / ES);
-            if (q < BM * CR && m < a.M && ch < a.Co) *(v4i*)((unsigned char*)a.y + ((size_t)m * a.ldc + a.c_off + ch) * ES) = *(const v4i*)(ro + q * 16);
+            if (q < BM * CR && m < a.M && ch < a.Co) *(v4i*)((unsigned char*)a.y + ((size_t)out_row(m) * a.ldc + a.c_off + ch) * ES) = *(const v4i*)(ro + q * 16);
         }
     }
 }

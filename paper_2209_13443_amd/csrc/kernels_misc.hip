@@ -479,7 +479,7 @@ hipError_t launch_avgpool(const PoolArgs& a, int dtype, hipStream_t s)
 // release per workgroup, which on this chip writes back the whole L2 of its XCD.)
 // Needs C * ES / 16 <= 256.
 template <int ES>
-__global__ __launch_bounds__(256) void gap_kernel(HeadArgs a, int pix_per_block)
+__global__ __launch_bounds__(256) void gap_kernel(SlotTab, HeadArgs a, int pix_per_block)
 {
     constexpr int NE = 16 / ES;
     __shared__ int red[256 * NE];
@@ -489,7 +489,10 @@ __global__ __launch_bounds__(256) void gap_kernel(HeadArgs a, int pix_per_block)
     const int q = (int)threadIdx.x % cchunks, pl = (int)threadIdx.x / cchunks;
     const bool active = pl < npl;
     const int p0 = blockIdx.x * pix_per_block, p1 = min(a.HW, p0 + pix_per_block);
-    const unsigned char* x = (const unsigned char*)a.act + (long long)b * a.HW * a.C * ES;
+    // zero-copy compaction: sample b of the batch is slot tab[b] of act (the table is the first kernel argument)
+    const __attribute__((address_space(4))) unsigned short* tab = (const __attribute__((address_space(4))) unsigned short*)__builtin_amdgcn_kernarg_segment_ptr();
+    const long long bs = a.gather ? (long long)tab[b] : (long long)b;
+    const unsigned char* x = (const unsigned char*)a.act + bs * a.HW * a.C * ES;
     int acci[NE];
     float accf[NE];
 #pragma unroll
@@ -577,15 +580,20 @@ int head_gap_splits(int B, int HW)
     return (HW + ppb - 1) / ppb;
 }
 
-hipError_t launch_head_gap(const HeadArgs& a, int dtype, hipStream_t s)
+hipError_t launch_head_gap(const HeadArgs& a_in, int dtype, hipStream_t s, const SlotTab* slots)
 {
-    if (a.B <= 0) return hipSuccess;
+    if (a_in.B <= 0) return hipSuccess;
+    static const SlotTab no_slots{};
+    if (slots && a_in.B > EE_ZC_MAX_B) return hipErrorInvalidValue;
+    const SlotTab& tab = slots ? *slots : no_slots;
+    HeadArgs a = a_in;
+    a.gather = slots != nullptr;
     const int ppb = gap_pixels_per_block(a.B, a.HW);
     const int splits = (a.HW + ppb - 1) / ppb;
     if (dtype == EE_I8) {
-        hipLaunchKernelGGL(gap_kernel<1>, dim3(splits, a.B), dim3(256), 0, s, a, ppb);
+        hipLaunchKernelGGL(gap_kernel<1>, dim3(splits, a.B), dim3(256), 0, s, tab, a, ppb);
     } else {
-        hipLaunchKernelGGL(gap_kernel<2>, dim3(splits, a.B), dim3(256), 0, s, a, ppb);
+        hipLaunchKernelGGL(gap_kernel<2>, dim3(splits, a.B), dim3(256), 0, s, tab, a, ppb);
         if (splits > 1) {
             const long long total = (long long)a.B * (a.C / 4);
             hipLaunchKernelGGL(gap_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, splits);

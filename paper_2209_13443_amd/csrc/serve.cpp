@@ -83,10 +83,82 @@ struct TableExec {
     void book_pack(int, int, int) {}
 };
 
+// Zero-copy compaction (zc): a sample that survives an exit stays where the segment wrote it.  Every level behind the
+// first owns a set of sample slots; a step takes free slots of the next level for its outputs, the segment's last layer
+// scatters into them, and "compaction" is the host writing the survivors' slot numbers into the row -> slot map of the
+// next level while the slots of the samples that left, and the input slots the step consumed, return to the free list.
+// The schedulers keep addressing batch rows exactly as with the copying kernel; only this executor translates.
 struct GpuExec {
     ee_ctx* ctx; const unsigned char* pool;
+    bool zc;
+    std::vector<uint16_t> row2slot[8], free_slots[8];
+    struct Step { SlotTab in, out; int b = 0, stage = -1, dst = -1, ring = 0; bool has_out = false; } step_of[4];
 
-    explicit GpuExec(ee_ctx* c, const void* input_pool) : ctx(c), pool((const unsigned char*)input_pool) {}
+    explicit GpuExec(ee_ctx* c, const void* input_pool, bool zero_copy = false) : ctx(c), pool((const unsigned char*)input_pool), zc(zero_copy)
+    {
+        if (!zc) return;
+        for (size_t s = 1; s < ctx->in_buf.size() && s < 8; ++s) {
+            row2slot[s].assign((size_t)ctx->zc_slots, 0);
+            free_slots[s].resize((size_t)ctx->zc_slots);
+            for (int k = 0; k < ctx->zc_slots; ++k) free_slots[s][(size_t)k] = (uint16_t)(ctx->zc_slots - 1 - k);
+        }
+    }
+    // the step's tables: input rows [src_off, src_off + b) of `stage` through the map, fresh slots of the next level
+    int zc_begin(int lane, int stage, int b, int src_off, int ring_rows)
+    {
+        Step& st = step_of[lane];
+        st.b = b; st.stage = stage; st.dst = -1; st.ring = ring_rows;
+        const int E = (int)ctx->in_buf.size();
+        if (stage > 0) {
+            const int rows = (int)row2slot[stage].size();
+            for (int k = 0; k < b; ++k) st.in.s[k] = row2slot[stage][(size_t)((src_off + k) % rows)];
+        }
+        st.has_out = stage + 1 < E;
+        if (st.has_out) {
+            std::vector<uint16_t>& fr = free_slots[stage + 1];
+            if ((int)fr.size() < b) return EE_ERR_OVERFLOW;            // cannot happen: five blocks cover what can be held
+            for (int k = 0; k < b; ++k) { st.out.s[k] = fr.back(); fr.pop_back(); }
+        }
+        ctx->zc_in = stage > 0 ? &st.in : nullptr;
+        ctx->zc_out = st.has_out ? &st.out : nullptr;
+        return EE_OK;
+    }
+    // the step has ended (its exit head has reported): the input slots it read are free again
+    void zc_release_inputs(int lane)
+    {
+        Step& st = step_of[lane];
+        if (st.stage > 0)
+            for (int k = 0; k < st.b; ++k) free_slots[st.stage].push_back(st.in.s[k]);
+    }
+    // "compaction": survivors keep their slots, which become rows dst_off.. of the next level in slot order
+    void zc_pack(int lane, int dst_off, int ring_rows)
+    {
+        Step& st = step_of[lane];
+        if (!st.has_out) return;
+        const HostOutcome* h = ctx->lanes[(size_t)lane].h_out;
+        std::vector<uint16_t>& map = row2slot[st.stage + 1];
+        const int rows = ring_rows > 0 ? ring_rows : (int)map.size();
+        int j = 0;
+        for (int k = 0; k < st.b; ++k) {
+            if (h[k].flag) free_slots[st.stage + 1].push_back(st.out.s[k]);
+            else map[(size_t)((dst_off + j++) % rows)] = st.out.s[k];
+        }
+        st.has_out = false;
+    }
+    // where the step's kernels read and write
+    const void* step_in(int stage, int src_off) const
+    {
+        return (const unsigned char*)ctx->in_buf[stage] + (zc && stage > 0 ? 0 : (int64_t)src_off * ctx->stage_in_bytes(stage));
+    }
+    void* step_out(int stage) const { return zc && stage + 1 < (int)ctx->in_buf.size() ? ctx->in_buf[stage + 1] : ctx->out_buf[stage]; }
+    int run_step(int lane, int stage, int b, int src_off, int ring_rows)
+    {
+        if (zc) { const int rc = zc_begin(lane, stage, b, src_off, ring_rows); if (rc) return rc; }
+        int rc = ctx->run_stage(stage, b, step_in(stage, src_off), step_out(stage), stage == 0 && ctx->admission_fold() != nullptr);
+        if (!rc) rc = ctx->run_head(stage, b, step_out(stage), ctx->net.exits[stage].thr, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag, true, nullptr, ctx->zc_out);
+        ctx->zc_in = ctx->zc_out = nullptr;
+        return rc;
+    }
     // A0: copy the queued inputs into slots [0, b) of segment 0's input buffer.  The kernel reads the
     // request ids straight from pinned host memory; two id blocks are used in turn, and an exit-head wait
     // lies between two admissions, so a block is never rewritten while a kernel may still read it.
@@ -120,12 +192,10 @@ struct GpuExec {
     int segment(int stage, const int32_t*, int b, SlotOutcome* out, int src_off, int dst_off, int ring_rows)
     {
         ctx->bind_lane(0);
-        const unsigned char* in = (const unsigned char*)ctx->in_buf[stage] + (int64_t)src_off * ctx->stage_in_bytes(stage);
-        int rc = ctx->run_stage(stage, b, in, ctx->out_buf[stage], stage == 0 && ctx->admission_fold() != nullptr);
-        if (!rc) rc = ctx->run_head(stage, b, ctx->out_buf[stage], ctx->net.exits[stage].thr, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag, true);
+        int rc = run_step(0, stage, b, src_off, ring_rows);
         if (rc) return rc;
         long long compact_rec = -1;                     // index of the compaction launch's timing record, if one is kept
-        if (stage + 1 < (int)ctx->in_buf.size()) {
+        if (!zc && stage + 1 < (int)ctx->in_buf.size()) {
             const int64_t sb = ctx->stage_out_bytes(stage);
             if (ctx->profiling) compact_rec = (long long)ctx->prof_used;
             hipError_t e = ctx->timed(EE_K_COMPACT, 0.0, 2.0 * sb * b, [&] {
@@ -140,6 +210,7 @@ struct GpuExec {
             out[k] = SlotOutcome{(uint8_t)h.flag, h.label, h.conf, h.score};
             kept += h.flag == 0;
         }
+        if (zc) { zc_release_inputs(0); zc_pack(0, dst_off, ring_rows); }
         // the compaction launch was booked before B_rem was known: only the survivors are read and written
         if (compact_rec >= 0) ctx->prof[(size_t)compact_rec].bytes = 2.0 * (double)ctx->stage_out_bytes(stage) * kept;
         return EE_OK;
@@ -152,14 +223,14 @@ struct GpuExec {
     int launch(int lane, int stage, const int32_t*, int b, int src_off, int eager_dst, int ring_rows)
     {
         ctx->bind_lane(lane);
-        if (stage > 0)
+        // (zero-copy: the rows were written by segment kernels that had ended before the host learned of the survivors)
+        if (stage > 0 && !zc)
             for (size_t j = 0; j < ctx->lanes.size(); ++j)
                 if ((int)j != lane && ctx->lanes[j].packed_set[stage] && hipStreamWaitEvent(ctx->stream, ctx->lanes[j].packed[stage], 0) != hipSuccess)
                     return EE_ERR_DEVICE;
-        const unsigned char* in = (const unsigned char*)ctx->in_buf[stage] + (int64_t)src_off * ctx->stage_in_bytes(stage);
-        int rc = ctx->run_stage(stage, b, in, ctx->out_buf[stage], stage == 0 && ctx->admission_fold() != nullptr);
-        if (!rc) rc = ctx->run_head(stage, b, ctx->out_buf[stage], ctx->net.exits[stage].thr, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag, true);
-        if (!rc && eager_dst >= 0) rc = pack(lane, stage, b, -1, eager_dst, ring_rows);
+        int rc = run_step(lane, stage, b, src_off, ring_rows);
+        if (zc) step_of[lane].dst = eager_dst;
+        else if (!rc && eager_dst >= 0) rc = pack(lane, stage, b, -1, eager_dst, ring_rows);
         return rc;
     }
     bool done(int lane)
@@ -177,12 +248,14 @@ struct GpuExec {
             const HostOutcome& h = ctx->h_out[k];
             out[k] = SlotOutcome{(uint8_t)h.flag, h.label, h.conf, h.score};
         }
+        if (zc) zc_release_inputs(lane);
         return EE_OK;
     }
     // compaction of the lane's step into the next segment's ring at row dst_off; kept: the survivors, when known (timing books)
     int pack(int lane, int stage, int b, int kept, int dst_off, int ring_rows)
     {
         if (stage + 1 >= (int)ctx->in_buf.size()) return EE_OK;
+        if (zc) { zc_pack(lane, dst_off, ring_rows); return EE_OK; }
         ctx->bind_lane(lane);
         const int64_t sb = ctx->stage_out_bytes(stage);
         hipError_t e = ctx->timed(EE_K_COMPACT, 0.0, 2.0 * sb * (kept >= 0 ? kept : b), [&] {
@@ -201,6 +274,7 @@ struct GpuExec {
     // a compaction that was launched before its step's outcome was known is booked with the survivors that really moved
     void book_pack(int lane, int stage, int kept)
     {
+        if (zc) { zc_pack(lane, step_of[lane].dst, step_of[lane].ring); return; }
         if (pack_rec[lane] >= 0 && ctx->profiling) ctx->prof[(size_t)pack_rec[lane]].bytes = 2.0 * (double)ctx->stage_out_bytes(stage) * kept;
         pack_rec[lane] = -1;
     }
@@ -587,7 +661,10 @@ extern "C" int ee_serve_stream(ee_ctx* ctx, const ee_trace* trace, const void* i
     std::memset(stats, 0, sizeof *stats);
     if (trace->n == 0) return EE_OK;
     if (!input_pool || (reinterpret_cast<uintptr_t>(input_pool) & 15u)) return EE_ERR_ARG;
-    GpuExec exec(ctx, input_pool);
+    if (opts->zero_copy != 0 && opts->zero_copy != 1) return EE_ERR_ARG;
+    if (opts->zero_copy && !ctx->zero_copy_ok) return EE_ERR_UNSUPPORTED;
+    if (opts->zero_copy && opts->refill == 2 && opts->lanes > 2) return EE_ERR_ARG;      // the slots cover two steps in flight
+    GpuExec exec(ctx, input_pool, opts->zero_copy != 0);
     if (opts->clock == 1) {
         VirtualClock ck{opts->lut_ns, opts->b_max, 0};
         rc = opts->refill == 2 ? PoolScheduler<GpuExec, VirtualClock>(exec, ck, n_stages, trace, opts, results, stats, events, max_events).run()

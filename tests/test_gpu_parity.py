@@ -428,6 +428,64 @@ def test_serve_stream_lanes_and_baselines_match_oracle(torch, ee, orc, case):
     eng.close()
 
 
+ZC_CASES = [  # name, n, b_max, arrival gap ns, slo, min_incr, refill, lanes
+    ("tiny_i8", 64, 8, 0, -1, 1, 1, 1),              # Algorithm 1: parked survivors, catch-up batches merged behind them
+    ("tiny_i8", 64, 8, 450, 9000, 1, 1, 1),
+    ("tiny_i8", 50, 5, 300, -1, 2, 1, 1),
+    ("tiny_i8", 40, 8, 0, -1, 1, 0, 1),              # model-level batching
+    ("resnet50_small_i8", 40, 8, 900, 30000, 1, 1, 1),
+    ("resnet50_small_i8", 60, 8, 200, -1, 1, 2, 1),  # stage pools, one lane
+    ("resnet50_small_i8", 96, 8, 60, -1, 1, 2, 2),   # stage pools, two steps in flight
+    ("resnet18_small_i8", 64, 8, 100, -1, 1, 2, 2),
+    ("tiny_i8", 64, 8, 0, -1, 1, 2, 2),
+]
+
+
+@pytest.mark.parametrize("case", ZC_CASES)
+def test_serve_stream_zero_copy_matches_oracle_and_copying(torch, ee, orc, case):
+    """Zero-copy compaction (survivors stay where the segment wrote them, the next segment gathers them through a slot
+    table): results, statistics and the whole event list equal the oracle's on the virtual clock, as with the copying kernel."""
+    name, n, b_max, gap, slo, min_incr, refill, lanes = case
+    say(f"[case] zero-copy serve {case}")
+    blob = W.load_net(name)
+    pool = W.input_pool(blob, n)
+    arrivals = (np.arange(n) * gap).astype(np.int64)
+    lut = synthetic_lut(blob.n_stages, b_max)
+    ref, rst, rev = orc.serve_stream(blob, arrivals, pool, b_max, lut, t_slo_ns=slo, min_incr=min_incr, refill=refill, lanes=lanes, max_events=5000)
+    eng = ee.Engine(blob, b_max)
+    assert eng.zero_copy_supported()
+    assert eng.set_lanes(lanes) == lanes
+    dpool = dev(torch, pool)
+    for zc in (1, 0, 1):                                                   # the slots are reused by later calls
+        got, gst, gev = eng.serve_stream(arrivals, dpool, lut, clock=1, t_slo_ns=slo, min_incr=min_incr, refill=refill, lanes=lanes, max_events=5000, zero_copy=zc)
+        for f in ("exit_idx", "label", "score", "latency_ns"):
+            assert np.array_equal(got[f], ref[f]), (f, zc)
+        assert gst == rst and np.array_equal(gev, rev)
+    eng.close()
+
+
+def test_zero_copy_is_refused_where_it_cannot_run(torch, ee, orc):
+    blob = W.load_net("mobilenetv2_small_i8")                               # depthwise / thin layers at the segment boundaries
+    eng = ee.Engine(blob, 8)
+    n = 16
+    dpool = dev(torch, W.input_pool(blob, n))
+    lut = synthetic_lut(blob.n_stages, 8)
+    if not eng.zero_copy_supported():
+        with pytest.raises(ee.EEError):
+            eng.serve_stream(np.zeros(n, np.int64), dpool, lut, clock=1, zero_copy=1)
+    eng.close()
+    blob = W.load_net("tiny_i8")
+    eng = ee.Engine(blob, 8)
+    eng.set_lanes(3)
+    dpool = dev(torch, W.input_pool(blob, n))
+    lut = synthetic_lut(blob.n_stages, 8)
+    with pytest.raises(ee.EEError):
+        eng.serve_stream(np.zeros(n, np.int64), dpool, lut, clock=1, refill=2, lanes=3, zero_copy=1)    # the slots cover two steps in flight
+    with pytest.raises(ee.EEError):
+        eng.serve_stream(np.zeros(n, np.int64), dpool, lut, clock=1, zero_copy=2)
+    eng.close()
+
+
 def test_serve_stream_lanes_wall_clock(torch, ee, orc):
     """On the wall clock the schedule is a measurement; the per-request results are not (schedule independence)."""
     blob = W.load_net("resnet50_small_i8")
@@ -485,9 +543,11 @@ def test_full_size_every_request_against_the_oracle(torch, ee, orc, case):
         assert np.array_equal(got["exit_idx"], g_exit[:n]) and np.array_equal(got["label"], g_label[:n]) and np.array_equal(got["score"], g_score[:n])
         say(f"[info] {name} exit counts {np.bincount(got['exit_idx'], minlength=blob.n_stages).tolist()} "
             f"mean batch {[round(a / max(b, 1), 1) for a, b in zip(st['seg_samples'], st['seg_runs'])]}")
-    # on the wall clock, as the benchmark runs it
-    got, st, _ = eng.serve_stream(np.zeros(n, np.int64), dpool, eng.measure_lut(reps=1), clock=0, refill=policies[0][0], lanes=policies[0][1])
-    assert np.array_equal(got["exit_idx"], g_exit[:n]) and np.array_equal(got["label"], g_label[:n]) and np.array_equal(got["score"], g_score[:n])
+    # on the wall clock, as the benchmark runs it; then with zero-copy compaction where the network allows it
+    for zc in ((0, 1) if eng.zero_copy_supported() else (0,)):
+        say(f"[case] full-size {name} wall clock zero_copy={zc}")
+        got, st, _ = eng.serve_stream(np.zeros(n, np.int64), dpool, eng.measure_lut(reps=1), clock=0, refill=policies[0][0], lanes=policies[0][1], zero_copy=zc)
+        assert np.array_equal(got["exit_idx"], g_exit[:n]) and np.array_equal(got["label"], g_label[:n]) and np.array_equal(got["score"], g_score[:n])
     eng.close()
 
 
