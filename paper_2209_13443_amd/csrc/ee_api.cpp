@@ -13,6 +13,8 @@ int set_conv_tile(int tile);
 
 using namespace ee;
 
+thread_local hipEvent_t ee::g_launch_start = nullptr, ee::g_launch_stop = nullptr;
+
 namespace {
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }

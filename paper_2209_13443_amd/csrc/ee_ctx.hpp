@@ -132,7 +132,7 @@ struct ee_ctx {
     // own: scratch memory to use instead of the context's (sums, gap_partial, logits)
     int run_head(int stage, int b_act, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag,
                  bool to_host = false, const ee::HeadScratch* own = nullptr, const ee::SlotTab* slots = nullptr);
-    // brackets `launch` with a pair of events when profiling
+    // times `launch` with a pair of events attached to its dispatch when profiling
     template <typename F>
     hipError_t timed(int cls, double ops, double bytes, F&& launch, int op = -1);
 };
@@ -148,8 +148,9 @@ hipError_t ee_ctx::timed(int cls, double ops, double bytes, F&& launch, int op)
     }
     ee::ProfRec& r = prof[prof_used++];
     r.cls = cls; r.op = op; r.ops = ops; r.bytes = bytes;
-    hipEventRecord(r.e0, stream);
+    ee::g_launch_start = r.e0;                    // attached to the dispatch (of the last kernel, if `launch` issues several)
+    ee::g_launch_stop = r.e1;
     hipError_t e = launch();
-    hipEventRecord(r.e1, stream);
+    ee::g_launch_start = ee::g_launch_stop = nullptr;
     return e;
 }

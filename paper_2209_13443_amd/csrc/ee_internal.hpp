@@ -1,6 +1,7 @@
 // Internal declarations of the early-exit serving library (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdint>
 #include <string>
@@ -101,6 +102,14 @@ struct PoolArgs {         // depthwise 3x3 and max-pool share the shape block
     float f_lo, f_hi;
     int ldc, c_off;      // pooling: the output pixel has ldc channels, of which this layer writes [c_off, c_off + C)
 };
+
+// ---- kernel launches ---------------------------------------------------------------------------------
+// Every kernel goes out through EE_LAUNCH.  While a launch is being timed, the pair of events named here is attached
+// to the dispatch itself (its own begin and end time stamps, what a kernel trace shows), instead of event records in
+// front of and behind it, which would also count the dispatch latency of a stream whose back-to-back launches they break.
+extern thread_local hipEvent_t g_launch_start, g_launch_stop;     // null: an ordinary launch
+#define EE_LAUNCH(kernel, grid, block, lds_bytes, stream, ...) \
+    hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, ee::g_launch_start, ee::g_launch_stop, 0, __VA_ARGS__)
 
 // ---- launchers (defined in the .hip files) -------------------------------------------------------
 hipError_t launch_conv_mfma_i8(const ConvArgs& a, hipStream_t s);

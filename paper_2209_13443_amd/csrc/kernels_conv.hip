@@ -276,9 +276,9 @@ static hipError_t launch_tile(const ConvArgs& a, hipStream_t s)
     const int gm = (a.M + BM - 1) / BM, gn = (a.Co + BN - 1) / BN, per_xcd = (gm + 7) / 8;
     dim3 grid((unsigned)(8 * per_xcd * gn));
     if (a.mode == 0)
-        hipLaunchKernelGGL((conv_mfma_kernel<ES, BM, BN, WM, WN, 0>), grid, dim3(256), 0, s, a, gm, gn, per_xcd);
+        EE_LAUNCH((conv_mfma_kernel<ES, BM, BN, WM, WN, 0>), grid, dim3(256), 0, s, a, gm, gn, per_xcd);
     else
-        hipLaunchKernelGGL((conv_mfma_kernel<ES, BM, BN, WM, WN, 1>), grid, dim3(256), 0, s, a, gm, gn, per_xcd);
+        EE_LAUNCH((conv_mfma_kernel<ES, BM, BN, WM, WN, 1>), grid, dim3(256), 0, s, a, gm, gn, per_xcd);
     return hipGetLastError();
 }
 
@@ -364,8 +364,8 @@ hipError_t launch_conv_direct(const DirectConvArgs& a, int dtype, hipStream_t s)
     const long long total = (long long)a.M * a.Co;
     if (total <= 0) return hipSuccess;
     const unsigned blocks = (unsigned)((total + 255) / 256);
-    if (dtype == EE_I8) hipLaunchKernelGGL(conv_direct_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(conv_direct_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
+    if (dtype == EE_I8) EE_LAUNCH(conv_direct_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
+    else EE_LAUNCH(conv_direct_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
@@ -394,9 +394,9 @@ hipError_t launch_pad_input(const void* x, void* y, int B, int H, int W, int C, 
     if (total <= 0) return hipSuccess;
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (dtype == EE_I8)
-        hipLaunchKernelGGL(pad_input_kernel<signed char>, dim3(blocks), dim3(256), 0, s, (const signed char*)x, (signed char*)y, B, H, W, C, Hp, Wp, pad);
+        EE_LAUNCH(pad_input_kernel<signed char>, dim3(blocks), dim3(256), 0, s, (const signed char*)x, (signed char*)y, B, H, W, C, Hp, Wp, pad);
     else
-        hipLaunchKernelGGL(pad_input_kernel<uint16_t>, dim3(blocks), dim3(256), 0, s, (const uint16_t*)x, (uint16_t*)y, B, H, W, C, Hp, Wp, pad);
+        EE_LAUNCH(pad_input_kernel<uint16_t>, dim3(blocks), dim3(256), 0, s, (const uint16_t*)x, (uint16_t*)y, B, H, W, C, Hp, Wp, pad);
     return hipGetLastError();
 }
 
@@ -485,16 +485,16 @@ hipError_t launch_space_to_depth(const void* x, void* y, const int32_t* gather, 
     if (row_bytes % 4 == 0 && ((size_t)H * row_bytes) % 4 == 0 && 2 * row_bytes <= 48 * 1024 && B <= 65535) {
         const dim3 grid((unsigned)Hs, (unsigned)B);
         if (dtype == EE_I8)
-            hipLaunchKernelGGL(space_to_depth_rows_kernel<signed char>, grid, dim3(128), 2 * row_bytes, s, (const signed char*)x, (signed char*)y, gather, H, W, C, Hs, Ws, pad);
+            EE_LAUNCH(space_to_depth_rows_kernel<signed char>, grid, dim3(128), 2 * row_bytes, s, (const signed char*)x, (signed char*)y, gather, H, W, C, Hs, Ws, pad);
         else
-            hipLaunchKernelGGL(space_to_depth_rows_kernel<uint16_t>, grid, dim3(128), 2 * row_bytes, s, (const uint16_t*)x, (uint16_t*)y, gather, H, W, C, Hs, Ws, pad);
+            EE_LAUNCH(space_to_depth_rows_kernel<uint16_t>, grid, dim3(128), 2 * row_bytes, s, (const uint16_t*)x, (uint16_t*)y, gather, H, W, C, Hs, Ws, pad);
         return hipGetLastError();
     }
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (dtype == EE_I8)
-        hipLaunchKernelGGL(space_to_depth_kernel<signed char>, dim3(blocks), dim3(256), 0, s, (const signed char*)x, (signed char*)y, gather, B, H, W, C, Hs, Ws, pad);
+        EE_LAUNCH(space_to_depth_kernel<signed char>, dim3(blocks), dim3(256), 0, s, (const signed char*)x, (signed char*)y, gather, B, H, W, C, Hs, Ws, pad);
     else
-        hipLaunchKernelGGL(space_to_depth_kernel<uint16_t>, dim3(blocks), dim3(256), 0, s, (const uint16_t*)x, (uint16_t*)y, gather, B, H, W, C, Hs, Ws, pad);
+        EE_LAUNCH(space_to_depth_kernel<uint16_t>, dim3(blocks), dim3(256), 0, s, (const uint16_t*)x, (uint16_t*)y, gather, B, H, W, C, Hs, Ws, pad);
     return hipGetLastError();
 }
 
@@ -513,7 +513,7 @@ hipError_t launch_pad_channels(const void* x, void* y, long long rows, int c_byt
 {
     const long long total = rows * (cp_bytes / 4);
     if (total <= 0) return hipSuccess;
-    hipLaunchKernelGGL(pad_channels_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const int*)x, (int*)y, rows, c_bytes / 4, cp_bytes / 4);
+    EE_LAUNCH(pad_channels_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const int*)x, (int*)y, rows, c_bytes / 4, cp_bytes / 4);
     return hipGetLastError();
 }
 

@@ -388,9 +388,9 @@ static hipError_t launch_igemm_tile(const ConvArgs& a, bool plain, int ns, hipSt
     if (granted != hipSuccess) return granted;
     if (lds_bytes > 160 * 1024) return hipErrorInvalidValue;
     if (plain)
-        hipLaunchKernelGGL((conv_igemm_kernel<ES, BM, BN, KS, KSPL, true>), grid, dim3(256 * KSPL), lds_bytes, s, xs, ys, a, gm, gn, magic_gn, per_xcd, ns);
+        EE_LAUNCH((conv_igemm_kernel<ES, BM, BN, KS, KSPL, true>), grid, dim3(256 * KSPL), lds_bytes, s, xs, ys, a, gm, gn, magic_gn, per_xcd, ns);
     else
-        hipLaunchKernelGGL((conv_igemm_kernel<ES, BM, BN, KS, KSPL, false>), grid, dim3(256 * KSPL), lds_bytes, s, xs, ys, a, gm, gn, magic_gn, per_xcd, ns);
+        EE_LAUNCH((conv_igemm_kernel<ES, BM, BN, KS, KSPL, false>), grid, dim3(256 * KSPL), lds_bytes, s, xs, ys, a, gm, gn, magic_gn, per_xcd, ns);
     return hipGetLastError();
 }
 

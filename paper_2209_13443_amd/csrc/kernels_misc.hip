@@ -214,19 +214,19 @@ hipError_t launch_depthwise(const PoolArgs& a, int dtype, hipStream_t s)
         const dim3 grid((unsigned)((total + 255) / 256));
         if (a.C <= 192) {                   // the table in LDS: measured to pay up to 192 channels (see the kernel)
             const size_t lds_bytes = (size_t)a.C * 16;
-            if (a.stride == 1) hipLaunchKernelGGL((depthwise3x3_i8_kernel<1, true>), grid, dim3(256), lds_bytes, s, b, groups_x);
-            else hipLaunchKernelGGL((depthwise3x3_i8_kernel<2, true>), grid, dim3(256), lds_bytes, s, b, groups_x);
+            if (a.stride == 1) EE_LAUNCH((depthwise3x3_i8_kernel<1, true>), grid, dim3(256), lds_bytes, s, b, groups_x);
+            else EE_LAUNCH((depthwise3x3_i8_kernel<2, true>), grid, dim3(256), lds_bytes, s, b, groups_x);
         } else {
-            if (a.stride == 1) hipLaunchKernelGGL((depthwise3x3_i8_kernel<1, false>), grid, dim3(256), 0, s, b, groups_x);
-            else hipLaunchKernelGGL((depthwise3x3_i8_kernel<2, false>), grid, dim3(256), 0, s, b, groups_x);
+            if (a.stride == 1) EE_LAUNCH((depthwise3x3_i8_kernel<1, false>), grid, dim3(256), 0, s, b, groups_x);
+            else EE_LAUNCH((depthwise3x3_i8_kernel<2, false>), grid, dim3(256), 0, s, b, groups_x);
         }
         return hipGetLastError();
     }
     const long long total = (long long)a.B * a.Ho * a.Wo * (a.C * es / 16);
     if (total <= 0) return hipSuccess;
     const unsigned blocks = (unsigned)((total + 255) / 256);
-    if (dtype == EE_I8) hipLaunchKernelGGL(depthwise_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(depthwise_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
+    if (dtype == EE_I8) EE_LAUNCH(depthwise_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
+    else EE_LAUNCH(depthwise_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
@@ -438,8 +438,8 @@ static hipError_t launch_pool3x3_i8(const PoolArgs& a, hipStream_t s)
     const long long total = (long long)a.B * a.Ho * groups_x * (a.C / 16);
     if (total <= 0) return hipSuccess;
     const dim3 grid((unsigned)((total + 255) / 256));
-    if (a.stride == 1) hipLaunchKernelGGL((pool3x3_i8_kernel<1, AVG>), grid, dim3(256), 0, s, a, groups_x);
-    else hipLaunchKernelGGL((pool3x3_i8_kernel<2, AVG>), grid, dim3(256), 0, s, a, groups_x);
+    if (a.stride == 1) EE_LAUNCH((pool3x3_i8_kernel<1, AVG>), grid, dim3(256), 0, s, a, groups_x);
+    else EE_LAUNCH((pool3x3_i8_kernel<2, AVG>), grid, dim3(256), 0, s, a, groups_x);
     return hipGetLastError();
 }
 
@@ -450,8 +450,8 @@ hipError_t launch_maxpool(const PoolArgs& a, int dtype, hipStream_t s)
     const long long total = (long long)a.B * a.Ho * a.Wo * (a.C * es / 16);
     if (total <= 0) return hipSuccess;
     const unsigned blocks = (unsigned)((total + 255) / 256);
-    if (dtype == EE_I8) hipLaunchKernelGGL(maxpool_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(maxpool_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
+    if (dtype == EE_I8) EE_LAUNCH(maxpool_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
+    else EE_LAUNCH(maxpool_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
@@ -464,8 +464,8 @@ hipError_t launch_avgpool(const PoolArgs& a, int dtype, hipStream_t s)
     if (a.k < 1 || a.k > 15) return hipErrorInvalidValue;
     const unsigned blocks = (unsigned)((total + 255) / 256);
     const unsigned magic = (unsigned)(0x100000000ull / (unsigned)(2 * a.k * a.k));
-    if (dtype == EE_I8) hipLaunchKernelGGL(avgpool_kernel<1>, dim3(blocks), dim3(256), 0, s, a, magic);
-    else hipLaunchKernelGGL(avgpool_kernel<2>, dim3(blocks), dim3(256), 0, s, a, magic);
+    if (dtype == EE_I8) EE_LAUNCH(avgpool_kernel<1>, dim3(blocks), dim3(256), 0, s, a, magic);
+    else EE_LAUNCH(avgpool_kernel<2>, dim3(blocks), dim3(256), 0, s, a, magic);
     return hipGetLastError();
 }
 
@@ -591,12 +591,18 @@ hipError_t launch_head_gap(const HeadArgs& a_in, int dtype, hipStream_t s, const
     const int ppb = gap_pixels_per_block(a.B, a.HW);
     const int splits = (a.HW + ppb - 1) / ppb;
     if (dtype == EE_I8) {
-        hipLaunchKernelGGL(gap_kernel<1>, dim3(splits, a.B), dim3(256), 0, s, tab, a, ppb);
+        EE_LAUNCH(gap_kernel<1>, dim3(splits, a.B), dim3(256), 0, s, tab, a, ppb);
     } else {
-        hipLaunchKernelGGL(gap_kernel<2>, dim3(splits, a.B), dim3(256), 0, s, tab, a, ppb);
+        // two kernels when the pooling is split: a timed launch takes the first one's begin and the second one's end
+        const hipEvent_t t0 = g_launch_start, t1 = g_launch_stop;
+        if (splits > 1) g_launch_stop = nullptr;
+        EE_LAUNCH(gap_kernel<2>, dim3(splits, a.B), dim3(256), 0, s, tab, a, ppb);
         if (splits > 1) {
             const long long total = (long long)a.B * (a.C / 4);
-            hipLaunchKernelGGL(gap_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, splits);
+            g_launch_start = nullptr;
+            g_launch_stop = t1;
+            EE_LAUNCH(gap_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, splits);
+            g_launch_start = t0;
         }
     }
     return hipGetLastError();
@@ -686,8 +692,8 @@ hipError_t launch_head_fc(const HeadArgs& a, int dtype, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
     dim3 grid((a.n_cls + 15) / 16, (a.B + 15) / 16);
-    if (dtype == EE_I8) hipLaunchKernelGGL(fc_kernel<1>, grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(fc_kernel<2>, grid, dim3(256), 0, s, a);
+    if (dtype == EE_I8) EE_LAUNCH(fc_kernel<1>, grid, dim3(256), 0, s, a);
+    else EE_LAUNCH(fc_kernel<2>, grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
@@ -823,8 +829,8 @@ __global__ __launch_bounds__(256) void softmax_kernel(HeadArgs a)
 hipError_t launch_head_softmax(const HeadArgs& a, int dtype, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
-    if (dtype == EE_I8) hipLaunchKernelGGL(softmax_kernel<1>, dim3(a.B), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(softmax_kernel<2>, dim3(a.B), dim3(256), 0, s, a);
+    if (dtype == EE_I8) EE_LAUNCH(softmax_kernel<1>, dim3(a.B), dim3(256), 0, s, a);
+    else EE_LAUNCH(softmax_kernel<2>, dim3(a.B), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
@@ -866,7 +872,7 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s)
 {
     const long long n16 = (long long)((bytes + 15) / 16);
     if (n16 == 0) return hipSuccess;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s, (v4i*)p, n16);
+    EE_LAUNCH(fill_zero_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s, (v4i*)p, n16);
     return hipGetLastError();
 }
 
@@ -907,7 +913,7 @@ hipError_t launch_compact(const uint8_t* flag, const void* src, void* dst, const
 {
     if (b_act <= 0) return hipSuccess;
     dim3 grid((unsigned)((sample_bytes + 16383) / 16384), b_act);
-    hipLaunchKernelGGL(compact_kernel, grid, dim3(256), 0, s, flag, (const unsigned char*)src, (unsigned char*)dst,
+    EE_LAUNCH(compact_kernel, grid, dim3(256), 0, s, flag, (const unsigned char*)src, (unsigned char*)dst,
                        ids_src, ids_dst, b_act, (long long)sample_bytes, dst_off, ring_rows, b_rem_out, b_rem_out2);
     return hipGetLastError();
 }
@@ -936,7 +942,7 @@ hipError_t launch_append(const void* refill, void* dst, const int32_t* refill_id
 {
     if (b_incr <= 0) return hipSuccess;
     dim3 grid((unsigned)((sample_bytes + 16383) / 16384), b_incr);
-    hipLaunchKernelGGL(copy_rows_kernel, grid, dim3(256), 0, s, (const unsigned char*)refill, (unsigned char*)dst,
+    EE_LAUNCH(copy_rows_kernel, grid, dim3(256), 0, s, (const unsigned char*)refill, (unsigned char*)dst,
                        (const int32_t*)nullptr, refill_ids, ids_dst, b_rem_dev, b_rem_host, b_incr, (long long)sample_bytes, b_merged_out);
     return hipGetLastError();
 }
@@ -945,7 +951,7 @@ hipError_t launch_admit(const void* pool, void* dst, const int32_t* ids, int b, 
 {
     if (b <= 0) return hipSuccess;
     dim3 grid((unsigned)((sample_bytes + 16383) / 16384), b);
-    hipLaunchKernelGGL(copy_rows_kernel, grid, dim3(256), 0, s, (const unsigned char*)pool, (unsigned char*)dst, ids,
+    EE_LAUNCH(copy_rows_kernel, grid, dim3(256), 0, s, (const unsigned char*)pool, (unsigned char*)dst, ids,
                        (const int32_t*)nullptr, (int32_t*)nullptr, (const int*)nullptr, 0, b, (long long)sample_bytes, (int*)nullptr);
     return hipGetLastError();
 }

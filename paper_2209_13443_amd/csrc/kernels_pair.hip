@@ -367,7 +367,7 @@ static hipError_t launch_pair_tile(const PairArgs& p, int ns, hipStream_t s)
                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (granted != hipSuccess) return granted;
     if (lds_bytes > 160 * 1024) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((conv_pair_kernel<ES, BM, BN1, KS, BN2>), dim3((unsigned)(8 * per_xcd)), dim3(256), lds_bytes, s, p, gm, per_xcd, ns);
+    EE_LAUNCH((conv_pair_kernel<ES, BM, BN1, KS, BN2>), dim3((unsigned)(8 * per_xcd)), dim3(256), lds_bytes, s, p, gm, per_xcd, ns);
     return hipGetLastError();
 }
 

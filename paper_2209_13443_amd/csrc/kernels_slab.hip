@@ -298,7 +298,7 @@ static hipError_t launch_slab_tile(const ConvArgs& a, int ns, hipStream_t s)
     static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_slab_kernel<ES, BM, BN, KS>),
                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (granted != hipSuccess) return granted;
-    hipLaunchKernelGGL((conv_slab_kernel<ES, BM, BN, KS>), grid, dim3(256), lds_bytes, s, a, gm, gn, magic_gn, per_xcd, ns, cib_log2);
+    EE_LAUNCH((conv_slab_kernel<ES, BM, BN, KS>), grid, dim3(256), lds_bytes, s, a, gm, gn, magic_gn, per_xcd, ns, cib_log2);
     return hipGetLastError();
 }
 

@@ -152,7 +152,7 @@ static hipError_t launch_stream_inst(const ConvArgs& a, hipStream_t s)
     const long long cap = KH * BPR * NT <= 6 ? 1024 : 512;            // workgroups per CU the registers allow (4 or 2) x 256 CUs; the loop takes the rest
     const unsigned blocks = (unsigned)(want < cap ? want : cap);
     const size_t lds_bytes = (size_t)4 * 32 * (NT * 32 + 16);
-    hipLaunchKernelGGL((conv_stream_i8_kernel<KH, BPR, NT>), dim3(blocks), dim3(256), lds_bytes, s, a, nstrips);
+    EE_LAUNCH((conv_stream_i8_kernel<KH, BPR, NT>), dim3(blocks), dim3(256), lds_bytes, s, a, nstrips);
     return hipGetLastError();
 }
 

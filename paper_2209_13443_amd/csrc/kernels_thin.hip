@@ -84,7 +84,7 @@ hipError_t launch_conv_thin(const ThinConvArgs& a, hipStream_t s)
     static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_thin_i8_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (granted != hipSuccess) return granted;
     const long long strips = (a.M + 31) / 32;
-    hipLaunchKernelGGL(conv_thin_i8_kernel, dim3((unsigned)((strips + 3) / 4)), dim3(256), lds_bytes, s, a, nt, row_pitch);
+    EE_LAUNCH(conv_thin_i8_kernel, dim3((unsigned)((strips + 3) / 4)), dim3(256), lds_bytes, s, a, nt, row_pitch);
     return hipGetLastError();
 }
 
