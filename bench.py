@@ -286,6 +286,7 @@ def run_stream(args, name, steps, warmup, full=True):
     # kernel).  Bracketing each launch costs the stream its back-to-back dispatch, so it is kept out of the timed steps.
     kstats = {k: dict(launches=0, ms=0.0, ops=0.0, bytes=0.0) for k in ee.K_NAMES}
     layer_stats = []
+    at_capacity = None
     if not args.no_kernel_timing:
         eng.profile(True)
         step(lanes_=1)
@@ -293,7 +294,22 @@ def run_stream(args, name, steps, warmup, full=True):
         if zero_copy:                                  # the compaction kernel only runs in the copying mode: one more step for its line
             step(lanes_=1, zc=0)
             kstats["compact"] = eng.profile_read(len(blob.ops))[0]["compact"]
+        if kstats["gap"]["launches"] == 0 and full:    # the serving path pools inside the segment's last layer: the stand-alone
+            for s_ in range(blob.n_stages):            # pooling kernel of ee_exit_head is timed on b_max resident samples per exit
+                ex = blob.exits[s_]
+                act = torch.randint(-100, 100, (b_max, int(ex["h"]), int(ex["w"]), int(ex["c"]) * (1 if dtype == "i8" else 2)), dtype=torch.int8, device="cuda")
+                for _ in range(3):
+                    eng.exit_head(s_, act, 2.0)
+            kstats["gap"] = eng.profile_read(len(blob.ops))[0]["gap"]
         eng.profile(False)
+        if "capacity" in (args.roofline_at or "") and load is not None and full:
+            eng.profile(True)                          # the same per-launch timing with every batch full (all requests at t = 0)
+            step(arr=zeros, lanes_=1)
+            conv_c = eng.profile_read(len(blob.ops))[0]["conv_mfma"]
+            eng.profile(False)
+            at_capacity = dict(achieved=round(conv_c["ops"] / (conv_c["ms"] * 1e-3) / 1e12, 2), launches=conv_c["launches"],
+                               avg_launch_us=round(conv_c["ms"] * 1e3 / conv_c["launches"], 2))
+            at_capacity["frac"] = round(at_capacity["achieved"] / PEAK[dtype], 4)
 
     # dominant kernel: the MFMA implicit-GEMM convolution
     conv = kstats["conv_mfma"]
@@ -309,6 +325,8 @@ def run_stream(args, name, steps, warmup, full=True):
                         kernel_ms_per_step=round(conv["ms"], 3),
                         hbm_gbps_algorithmic=round(conv["bytes"] / (conv["ms"] * 1e-3) / 1e9, 1))
         roofline["traffic"] = measured_traffic(name)
+        if at_capacity:
+            roofline["with_every_batch_full"] = at_capacity
         # Layer by layer the convolutions are also capped by their algorithmic bytes: the time the launches of
         # a layer need at best is max(ops / MFMA peak, bytes / HBM peak); the sum over the layers gives the
         # rate the stack could reach if every launch sat on its own roofline (ops and bytes of a layer are
@@ -391,6 +409,7 @@ def main():
     ap.add_argument("--refill", type=int, default=-1, choices=[-1, 0, 1, 2],
                     help="serving policy of the timed steps: 0 model-level batching, 1 Algorithm 1, 2 stage pools (-1 = the workload's)")
     ap.add_argument("--lanes", type=int, default=0, help="stage pools: steps in flight at once (0 = the workload's)")
+    ap.add_argument("--roofline-at", default="capacity", help="'capacity': also time the convolution launches of a step whose batches are all full")
     ap.add_argument("--zero-copy", type=int, default=-1, choices=[-1, 0, 1], help="0: always the copying compaction kernel; else zero-copy compaction where the network allows it")
     ap.add_argument("--load", type=float, default=0.0, help="arrival rate as a multiple of the static-batch throughput (0 = the workload's)")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples timed on the CPU oracle (0 = automatic, -1 = skip)")

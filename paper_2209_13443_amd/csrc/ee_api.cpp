@@ -374,6 +374,23 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
     // stream-serving workspace.  Shared by all lanes: the packed input slots of every segment behind the first, a ring of
     // 3 b_max samples (the stage-pool policy keeps up to 2 b_max - 1 waiting samples there while a batch of up to b_max
     // is being read).  Per lane: everything alloc_lane makes; lane 0 is made here on the caller's stream.
+    // the layer of each segment that can carry the exit head's pooling in its epilogue: int8, the only writer of the segment's
+    // output, a whole (not sliced) tensor of 16-byte pixels, a general matrix-core layer with a residual (its tile is staged
+    // behind the ring, which the sums then use), and at most 8 samples per 128-row tile
+    ctx->gap_fuse_op.assign((size_t)n_st, -1);
+    for (int s = 0; s < n_st && dtype == EE_I8; ++s) {
+        const StageDesc& st = ctx->net.stages[s];
+        int writer = -1, writers = 0;
+        for (int k = 0; k < st.n_ops; ++k)
+            if (ctx->plans[st.first_op + k].dst_buf == BUF_EXT_OUT) { writer = st.first_op + k; ++writers; }
+        if (writers != 1) continue;
+        const OpPlan& p = ctx->plans[(size_t)writer];
+        const OpDesc& d = p.d;
+        const ExitDesc& e = ctx->net.exits[s];
+        if (p.impl == IMPL_MFMA && d.res >= 0 && d.c_tot == d.c_out && d.c_off == 0 && d.c_out % 16 == 0 && d.c_out == e.c &&
+            d.h_out * d.w_out == e.h * e.w && 127 / (d.h_out * d.w_out) + 2 <= 8)
+            ctx->gap_fuse_op[(size_t)s] = writer;
+    }
     // Zero-copy compaction needs five blocks: up to 2 b_max - 1 waiting samples, the batch that is being read, and the
     // outputs of two steps in flight.  It is offered when every tensor that crosses a segment boundary is read and
     // written by the general matrix-core kernel only (the kernel that takes slot tables), b_max fits a table, and the
@@ -486,7 +503,7 @@ void ee_ctx::fill_conv_args(int op, int b, ConvArgs& a) const
     a.shift = d.shift; a.res_shift = d.res_shift; a.lo = d.lo; a.hi = d.hi; a.f_lo = d.f_lo; a.f_hi = d.f_hi;
 }
 
-hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg, const SlotTab* xs, const SlotTab* ys)
+hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg, const SlotTab* xs, const SlotTab* ys, int32_t* gap_sums)
 {
     const OpPlan& p = plans[op];
     const int dt = net.dtype;
@@ -499,9 +516,10 @@ hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const 
         return dt == EE_I8 ? launch_conv_mfma_i8(a, stream) : launch_conv_mfma_bf16(a, stream);
     }
     a.x = src; a.mode = 0;
-    if (xs || ys) {                                      // slot tables: the general kernel only
-        if (p.impl != IMPL_MFMA || b > EE_ZC_MAX_B) return hipErrorInvalidValue;
+    if (xs || ys || gap_sums) {                          // slot tables, fused pooling: the general kernel only
+        if (p.impl != IMPL_MFMA || ((xs || ys) && b > EE_ZC_MAX_B)) return hipErrorInvalidValue;
         a.slots = (xs ? EE_GATHER_X : 0) | (ys ? EE_SCATTER_Y : 0);
+        a.gap_sums = gap_sums;
         if ((cfg & EE_CFG_SLAB) || (cfg & 15) == 7) cfg = 0;
         return dt == EE_I8 ? launch_conv_igemm<1>(a, cfg, stream, xs, ys) : launch_conv_igemm<2>(a, cfg, stream, xs, ys);
     }
@@ -712,6 +730,7 @@ extern "C" int ee_pair_count(const ee_ctx* ctx)
 // ---- one backbone segment ------------------------------------------------------------------------
 int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool first_packed, int only_op, int cfg_force)
 {
+    gap_fused = false;
     const StageDesc& st = net.stages[stage];
     const int dt = net.dtype, es = net.elem_bytes();
     for (int k = 0; k < st.n_ops; ++k) {
@@ -723,6 +742,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
         const void* res = d.res >= 0 ? resolve(this, p.res_buf, act_in, act_out) : nullptr;
         const double ops = p.ops_per_sample * b, bytes = p.bytes_per_sample * b + p.weight_bytes;
         hipError_t e = hipSuccess;
+        int32_t* gap_dst = gap_fuse_dst && only_op < 0 && st.first_op + k == gap_fuse_op[(size_t)stage] ? gap_fuse_dst : nullptr;
         const SlotTab* xs = p.src_buf == BUF_EXT_IN ? zc_in : nullptr;
         const SlotTab* ys = p.dst_buf == BUF_EXT_OUT ? zc_out : nullptr;
         if ((xs || ys) && p.impl != IMPL_MFMA) return EE_ERR_UNSUPPORTED;
@@ -746,7 +766,8 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                 if (e != hipSuccess) return EE_ERR_DEVICE;
             }
             int cfg = cfg_force > 0 ? cfg_force : forced_conv_tile();
-            const bool q_scatter = zc_out && k + 1 < st.n_ops && plans[st.first_op + k + 1].dst_buf == BUF_EXT_OUT;
+            const bool q_scatter = k + 1 < st.n_ops && ((zc_out && plans[st.first_op + k + 1].dst_buf == BUF_EXT_OUT) ||
+                                                        (gap_fuse_dst && only_op < 0 && st.first_op + k + 1 == gap_fuse_op[(size_t)stage]));
             if (p.pair && pair_mode > 0 && cfg == 0 && only_op < 0 && !xs && !ys && !q_scatter) {
                 // this layer and the next as one launch, unless the table says the two separate kernels are faster here
                 const int pc = p.pair_cfg.empty() ? 0 : p.pair_cfg[std::min<size_t>(bucket_of(b), p.pair_cfg.size() - 1)];
@@ -771,7 +792,8 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                 probe.res = res;
                 if (conv_stream_supported(probe, es) && ((cfg & 15) == 7 || probe.M >= 32768)) cls = EE_K_CONV_STREAM;
             }
-            e = timed(cls, ops, bytes, [&] { return launch_conv(st.first_op + k, b, src, dst, res, cfg, xs, ys); }, st.first_op + k);
+            e = timed(cls, ops, bytes, [&] { return launch_conv(st.first_op + k, b, src, dst, res, cfg, xs, ys, gap_dst); }, st.first_op + k);
+            if (gap_dst && e == hipSuccess) gap_fused = true;
         } else if (p.impl == IMPL_THIN) {
             ThinConvArgs a{src, p.w_dev, p.b_dev, dst, (long long)b * d.h_out * d.w_out, d.c_in, d.c_out, d.c_tot, d.c_off, d.shift, d.lo, d.hi};
             e = timed(EE_K_CONV_STREAM, ops, bytes, [&] { return launch_conv_thin(a, stream); }, st.first_op + k);
@@ -802,7 +824,7 @@ extern "C" int ee_stage_forward(ee_ctx* ctx, int stage, int b_act, const void* a
 
 // ---- one exit head ------------------------------------------------------------------------------------
 int ee_ctx::run_head(int stage, int b, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag, bool to_host,
-                     const ee::HeadScratch* own, const ee::SlotTab* slots)
+                     const ee::HeadScratch* own, const ee::SlotTab* slots, bool pooled)
 {
     const ExitDesc& e = net.exits[stage];
     const int dt = net.dtype, es = net.elem_bytes();
@@ -817,7 +839,7 @@ int ee_ctx::run_head(int stage, int b, const void* act, float thr, int32_t* labe
     a.label = label; a.conf = conf; a.score = score; a.flag = flag;
     if (to_host) { a.host_out = h_out; a.host_seq = h_seq; a.seq_value = ++seq; a.arrive_counter = d_arrive; }
     const double act_bytes = (double)b * a.HW * a.C * es;
-    if (timed(EE_K_GAP, 0.0, act_bytes + 4.0 * b * a.C, [&] { return launch_head_gap(a, dt, stream, slots); }) != hipSuccess) return EE_ERR_DEVICE;
+    if (!pooled && timed(EE_K_GAP, 0.0, act_bytes + 4.0 * b * a.C, [&] { return launch_head_gap(a, dt, stream, slots); }) != hipSuccess) return EE_ERR_DEVICE;
     if (timed(EE_K_FC, 2.0 * b * a.C * a.n_cls, (double)a.C * a.n_cls * es + 4.0 * b * (a.C + a.n_cls),
               [&] { return launch_head_fc(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;
     if (timed(EE_K_SOFTMAX, 0.0, 4.0 * b * a.n_cls + 17.0 * b, [&] { return launch_head_softmax(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;
@@ -912,6 +934,11 @@ extern "C" int ee_compact_refill(ee_ctx* ctx, int stage, int b_act, const uint8_
 }
 
 // ---- design-time latency table ---------------------------------------------------------------------------
+// The design-time exit-level latency table (Sec. III-B, "Exit-Level Latency Prediction").  An entry is what a step of the
+// stream driver costs on the wall clock, measured the way the driver runs it: the segment (the first one reads its input
+// through the admission copy, as when requests are admitted), the exit head writing its outcomes to host memory, the
+// compaction of all b samples behind it (nobody exits: the upper bound), and the host waiting for the head's word.
+// Eq. 4 relies on the table not under-estimating (a preemption it accepts must not cause a violation).
 extern "C" int ee_measure_lut(ee_ctx* ctx, int reps, int64_t* lut_ns)
 {
     if (!ctx || !lut_ns || reps < 1) return EE_ERR_ARG;
@@ -919,29 +946,43 @@ extern "C" int ee_measure_lut(ee_ctx* ctx, int reps, int64_t* lut_ns)
     const int n_st = (int)ctx->net.stages.size(), bm = ctx->b_max;
     const bool was = ctx->profiling;
     ctx->profiling = false;
-    hipEvent_t e0, e1;
-    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return EE_ERR_DEVICE;
     const int step = std::max(1, bm / 64);
     int rc = EE_OK;
+    for (int k = 0; k < bm; ++k) ctx->h_ids[0][k] = ctx->h_ids[1][k] = k;      // admission of rows 0..b-1 of segment 0's own input slots
+    const OpPlan* fold = ctx->admission_fold();
+    auto wait_word = [&]() {
+        const auto t0 = std::chrono::steady_clock::now();
+        for (unsigned spins = 0; __atomic_load_n(ctx->h_seq, __ATOMIC_ACQUIRE) != ctx->seq; ++spins)
+            if ((spins & 0xFFFF) == 0xFFFF && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2))
+                return hipStreamSynchronize(ctx->stream) == hipSuccess && __atomic_load_n(ctx->h_seq, __ATOMIC_ACQUIRE) == ctx->seq ? EE_OK : EE_ERR_DEVICE;
+        return EE_OK;
+    };
     for (int s = 0; s < n_st && !rc; ++s) {
         std::vector<int> measured;
         for (int b = 1; b <= bm; b += step) measured.push_back(b);
         if (measured.back() != bm) measured.push_back(bm);
         std::vector<double> t(measured.size());
+        const int64_t sb_out = ctx->stage_out_bytes(s);
         for (size_t i = 0; i < measured.size() && !rc; ++i) {
             const int b = measured[i];
             for (int pass = 0; pass < 2 && !rc; ++pass) {               // pass 0 warms caches and code objects
                 const int n = pass == 0 ? 1 : reps;
-                hipEventRecord(e0, ctx->stream);
+                if (hipStreamSynchronize(ctx->stream) != hipSuccess) rc = EE_ERR_DEVICE;
+                const auto t0 = std::chrono::steady_clock::now();
                 for (int r = 0; r < n && !rc; ++r) {
-                    rc = ctx->run_stage(s, b, ctx->in_buf[s], ctx->out_buf[s]);
-                    if (!rc) rc = ctx->run_head(s, b, ctx->out_buf[s], 2.0f, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag);
+                    if (s == 0 && fold) {
+                        const OpDesc& d = fold->d;
+                        if (launch_space_to_depth(ctx->in_buf[0], ctx->pad_bufs[fold->pad_buf], ctx->h_ids[0], b, d.h_in, d.w_in, d.c_in, fold->Hp, fold->Wp, d.pad, ctx->net.dtype, ctx->stream, true) != hipSuccess) rc = EE_ERR_DEVICE;
+                    }
+                    ctx->gap_fuse_dst = ctx->sums;
+                    if (!rc) rc = ctx->run_stage(s, b, ctx->in_buf[s], ctx->out_buf[s], s == 0 && fold != nullptr);
+                    ctx->gap_fuse_dst = nullptr;
+                    if (!rc) rc = ctx->run_head(s, b, ctx->out_buf[s], 2.0f, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag, true, nullptr, nullptr, ctx->gap_fused);
+                    if (!rc && s + 1 < n_st && launch_compact(ctx->d_flag, ctx->out_buf[s], ctx->in_buf[s + 1], nullptr, nullptr, b, sb_out, 0, 0, nullptr, nullptr, ctx->stream) != hipSuccess) rc = EE_ERR_DEVICE;
+                    if (!rc) rc = wait_word();
                 }
-                hipEventRecord(e1, ctx->stream);
-                if (hipEventSynchronize(e1) != hipSuccess) rc = EE_ERR_DEVICE;
-                float ms = 0.f;
-                hipEventElapsedTime(&ms, e0, e1);
-                t[i] = (double)ms * 1e6 / n;
+                if (hipStreamSynchronize(ctx->stream) != hipSuccess) rc = EE_ERR_DEVICE;
+                t[i] = std::chrono::duration<double, std::nano>(std::chrono::steady_clock::now() - t0).count() / n;
             }
         }
         for (int b = 1; b <= bm && !rc; ++b) {                          // linear interpolation between measured sizes
@@ -955,8 +996,6 @@ extern "C" int ee_measure_lut(ee_ctx* ctx, int reps, int64_t* lut_ns)
             lut_ns[(size_t)s * bm + b - 1] = (int64_t)std::llround(v);
         }
     }
-    hipEventDestroy(e0);
-    hipEventDestroy(e1);
     ctx->profiling = was;
     return rc;
 }

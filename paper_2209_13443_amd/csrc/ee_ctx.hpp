@@ -80,6 +80,12 @@ struct ee_ctx {
     int ids_turn = 0;
     // zero-copy compaction (stream serving): slot tables of the step being enqueued, or null.  With zc_in, sample n of a
     // segment's input is slot zc_in->s[n] of act_in; with zc_out, sample n of its output goes to slot zc_out->s[n] of act_out.
+    // Exit-head pooling fused into the last layer of a segment (int8): gap_fuse_op[s] is that layer (an index into plans) when
+    // it can carry the pooling, else -1.  run_stage adds the sums into gap_fuse_dst when that is set and says so in gap_fused;
+    // run_head then skips its pooling kernel.
+    std::vector<int> gap_fuse_op;
+    int32_t* gap_fuse_dst = nullptr;
+    bool gap_fused = false;
     const ee::SlotTab* zc_in = nullptr;
     const ee::SlotTab* zc_out = nullptr;
     bool zero_copy_ok = false;                   // every segment boundary can be served that way (set by ee_create)
@@ -123,7 +129,7 @@ struct ee_ctx {
         return &p;
     }
     // launches layer `op` (an index into plans) on b samples with the given kernel configuration (0 = by shape)
-    hipError_t launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg, const ee::SlotTab* xs = nullptr, const ee::SlotTab* ys = nullptr);
+    hipError_t launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg, const ee::SlotTab* xs = nullptr, const ee::SlotTab* ys = nullptr, int32_t* gap_sums = nullptr);
     // layers op and op + 1 as one fused launch: src feeds layer op, res and dst belong to layer op + 1
     hipError_t launch_pair(int op, int b, const void* src, void* dst, const void* res, int cfg);
     void fill_conv_args(int op, int b, ee::ConvArgs& a) const;
@@ -131,7 +137,7 @@ struct ee_ctx {
     // to_host: also write the outcomes to h_out and store ++seq to h_seq when they are all there
     // own: scratch memory to use instead of the context's (sums, gap_partial, logits)
     int run_head(int stage, int b_act, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag,
-                 bool to_host = false, const ee::HeadScratch* own = nullptr, const ee::SlotTab* slots = nullptr);
+                 bool to_host = false, const ee::HeadScratch* own = nullptr, const ee::SlotTab* slots = nullptr, bool pooled = false);
     // times `launch` with a pair of events attached to its dispatch when profiling
     template <typename F>
     hipError_t timed(int cls, double ops, double bytes, F&& launch, int op = -1);

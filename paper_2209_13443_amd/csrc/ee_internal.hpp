@@ -75,6 +75,7 @@ struct ConvArgs {
     int Hp, Wp, kwp;     // mode 1: padded input dims and padded kernel width
     int shift, res_shift, lo, hi;
     float f_lo, f_hi;
+    int* gap_sums;       // not null (int8, conv_igemm_kernel, last layer of a segment): also add the per-sample channel sums of the output into gap_sums[n][Co]
     int slots;           // EE_GATHER_X: sample n of the input is slot xs[n] of x; EE_SCATTER_Y: sample n of the output is slot ys[n] of y (conv_igemm_kernel only)
 };
 
@@ -140,7 +141,9 @@ hipError_t launch_conv_direct(const DirectConvArgs& a, int dtype, hipStream_t s)
 hipError_t launch_pad_input(const void* x, void* y, int B, int H, int W, int C, int Hp, int Wp, int pad, int dtype, hipStream_t s);
 // [B][H][W][C<=4] -> [B][Hs][Ws][2][2][4]: zero padding `pad`, then 2 x 2 pixel blocks folded into channels;
 // with gather (device-visible) sample n is read from row gather[n] of x
-hipError_t launch_space_to_depth(const void* x, void* y, const int32_t* gather, int B, int H, int W, int C, int Hs, int Ws, int pad, int dtype, hipStream_t s);
+// gather_on_host: gather points to host memory the caller may read now (then up to 256 ids travel in the kernel arguments)
+hipError_t launch_space_to_depth(const void* x, void* y, const int32_t* gather, int B, int H, int W, int C, int Hs, int Ws, int pad, int dtype, hipStream_t s,
+                                 bool gather_on_host = false);
 // [rows][c_bytes] -> [rows][cp_bytes] (both multiples of 4), the tail of every row zero
 hipError_t launch_pad_channels(const void* x, void* y, long long rows, int c_bytes, int cp_bytes, hipStream_t s);
 hipError_t launch_depthwise(const PoolArgs& a, int dtype, hipStream_t s);

@@ -56,6 +56,15 @@ __device__ __forceinline__ void igemm_epilogue(const ConvArgs& a, ACC& acc, unsi
     const int lane = tid & 63, frow = lane & 31, hi = lane >> 5;
     unsigned char* ro = lds + ro_off;
     const int* lbias = (const int*)(lds + bias_off);
+    // Exit-head pooling fused into the segment's last layer (int8, a.gap_sums set by the launcher only for a layer with a
+    // staged residual tile, so that the ring in front of the tile is free now): per-sample column sums of the finished
+    // tile are added up in LDS, then one global atomic per (sample, channel) of the tile goes into sums[n][Co].  int32
+    // addition is exact in any order, so the sums are those of the pooling kernel.
+    constexpr int GAP_S = 8;                                  // samples a tile may touch (the launcher checks (BM - 1) / HW + 2 <= GAP_S)
+    int* gacc = (int*)lds;                                    // [GAP_S][BN]
+    const bool fuse_gap = ES == 1 && a.gap_sums != nullptr && wide && has_res && ro_off >= GAP_S * BN * 4;
+    if (fuse_gap)
+        for (int i = tid; i < GAP_S * BN; i += NT) gacc[i] = 0;
     // Cell of (pixel row r, channel cl) in the output tile: chunk (cl*ES/16) ^ oswz(r) of row r.  oswz has period
     // 16, so it is oswz(frow) for all of a lane's rows, and the chunk index splits into a wave-uniform part
     // and a compile-time part: one XOR and one add per cell remain.
@@ -127,11 +136,44 @@ __device__ __forceinline__ void igemm_epilogue(const ConvArgs& a, ACC& acc, unsi
     }
     if (wide) {
         lds_barrier();
+        if (fuse_gap) {
+            constexpr int CG = BN / 4, NRG = NT / CG, RG = (BM + NRG - 1) / NRG;     // dword columns, row groups, rows per group
+            const int cg = tid % CG, rg = tid / CG;
+            const unsigned hw = (unsigned)(a.Ho * a.Wo);
+            const int nfirst = (int)fast_div((unsigned)min(m0, a.M - 1), hw, a.magic_howo);
+            int cur = -1, s0 = 0, s1 = 0, s2 = 0, s3 = 0;
+            auto flush = [&]() {
+                if (cur < 0) return;
+                int* g = gacc + (cur - nfirst) * BN + cg * 4;
+                atomicAdd(g, s0); atomicAdd(g + 1, s1); atomicAdd(g + 2, s2); atomicAdd(g + 3, s3);
+            };
+            for (int r = 0; r < RG; ++r) {
+                const int row = rg * RG + r, m = m0 + row;
+                if (row >= BM || m >= a.M) break;
+                const int n = (int)fast_div((unsigned)m, hw, a.magic_howo);
+                if (n != cur) { flush(); cur = n; s0 = s1 = s2 = s3 = 0; }
+                const int v = *(const int*)(ro + row * OROW + ((((cg * 4) >> 4) ^ oswz(row)) << 4) + ((cg * 4) & 15));
+                s0 += __builtin_amdgcn_sbfe(v, 0, 8); s1 += __builtin_amdgcn_sbfe(v, 8, 8);
+                s2 += __builtin_amdgcn_sbfe(v, 16, 8); s3 += __builtin_amdgcn_sbfe(v, 24, 8);
+            }
+            flush();
+        }
 #pragma unroll
         for (int j = 0; j < NO; ++j) {
             const int q = tid + NT * j, row = q / CR, chunk = (q % CR) ^ oswz(row);
             const int m = m0 + row, ch = n0 + chunk * (16 / ES);
             if (q < BM * CR && m < a.M && ch < a.Co) *(v4i*)((unsigned char*)a.y + ((size_t)out_row(m) * a.ldc + a.c_off + ch) * ES) = *(const v4i*)(ro + q * 16);
+        }
+        if (fuse_gap) {
+            lds_barrier();
+            const unsigned hw = (unsigned)(a.Ho * a.Wo);
+            const int mlast = min(m0 + BM, a.M) - 1;
+            const int nfirst = (int)fast_div((unsigned)min(m0, a.M - 1), hw, a.magic_howo), nlast = (int)fast_div((unsigned)mlast, hw, a.magic_howo);
+            const int cnt = (nlast - nfirst + 1) * BN;
+            for (int i = tid; i < cnt; i += NT) {
+                const int sl = i / BN, c = i - sl * BN;
+                if (n0 + c < a.Co) atomicAdd(a.gap_sums + (long long)(nfirst + sl) * a.Co + n0 + c, gacc[i]);
+            }
         }
     }
 }

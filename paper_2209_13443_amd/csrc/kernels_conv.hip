@@ -21,6 +21,8 @@
 // (the k order inside an instruction is irrelevant as long as A and B agree).
 #include <type_traits>
 
+#include <cstring>
+
 #include "ee_internal.hpp"
 
 namespace ee {
@@ -433,27 +435,34 @@ __global__ __launch_bounds__(256) void space_to_depth_kernel(const T* x, T* y, c
     for (int i = 0; i < (int)(sizeof(T) * 16 / 16); ++i) q[i] = src[i];
 }
 
-// The same folding for image rows that are whole dwords: one workgroup = one row of super-pixels of one sample.
-// The two image rows it folds are copied into LDS with dword loads (a wavefront reads 256 contiguous bytes per
-// instruction), and every lane gathers the 12 scalars of its super-pixel from LDS.  Loading them from global memory
+// The same folding for image rows that are whole dwords: one workgroup = RS rows of super-pixels of one sample.
+// The 2 RS image rows it folds are copied into LDS with dword loads (a wavefront reads 256 contiguous bytes per
+// instruction), and every lane gathers the 12 scalars of a super-pixel from LDS.  Loading them from global memory
 // one byte at a time costs 12 vector-memory instructions per lane for 16 bytes of output.
-template <typename T>
-__global__ __launch_bounds__(128) void space_to_depth_rows_kernel(const T* x, T* y, const int32_t* gather, int H, int W, int C, int Hs, int Ws, int pad)
+// Admission: request ids[n] of a pool is read instead of row n.  For up to 256 samples the ids travel by value as the
+// first kernel argument (IdTab) and are read from the kernel-argument segment; `gather` (device-visible memory, e.g.
+// pinned host memory, where every read crosses the bus) serves larger batches.
+struct IdTab { int32_t id[256]; };
+template <typename T, int RS>
+__global__ __launch_bounds__(256) void space_to_depth_rows_kernel(IdTab, const T* x, T* y, const int32_t* gather, int by_value, int H, int W, int C, int Hs, int Ws, int pad)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char s2d_lds[];
-    const int ys = blockIdx.x, n = blockIdx.y;
-    const long long row = gather ? gather[n] : n;              // admission reads request gather[n] of a pool
+    const int ys0 = blockIdx.x * RS, n = blockIdx.y;
+    const __attribute__((address_space(4))) int* tab = (const __attribute__((address_space(4))) int*)__builtin_amdgcn_kernarg_segment_ptr();
+    const long long row = by_value ? tab[n] : (gather ? gather[n] : n);
     const int row_words = W * C * (int)sizeof(T) / 4;
     const int* img = (const int*)(x + row * H * W * C);
     int* l32 = (int*)s2d_lds;
-    for (int i = threadIdx.x; i < 2 * row_words; i += 128) {
-        const int dy = i >= row_words, w = i - dy * row_words;
-        const int iy = 2 * ys + dy - pad;
+    for (int i = threadIdx.x; i < 2 * RS * row_words; i += 256) {
+        const int r = i / row_words, w = i - r * row_words;
+        const int iy = 2 * ys0 + r - pad;
         l32[i] = (iy >= 0 && iy < H) ? img[(long long)iy * row_words + w] : 0;      // a row in the padding is all zero
     }
     __syncthreads();
     const T* lrow = (const T*)s2d_lds;
-    for (int xs = threadIdx.x; xs < Ws; xs += 128) {
+    for (int o = threadIdx.x; o < RS * Ws; o += 256) {
+        const int rr = o / Ws, xs = o - rr * Ws, ys = ys0 + rr;
+        if (ys >= Hs) break;
         alignas(16) T v[16];
 #pragma unroll
         for (int dy = 0; dy < 2; ++dy)
@@ -461,7 +470,7 @@ __global__ __launch_bounds__(128) void space_to_depth_rows_kernel(const T* x, T*
             for (int dx = 0; dx < 2; ++dx) {
                 const int ix = 2 * xs + dx - pad;
                 const bool ok = ix >= 0 && ix < W;
-                const T* p = lrow + (dy * W + min(max(ix, 0), W - 1)) * C;
+                const T* p = lrow + ((2 * rr + dy) * W + min(max(ix, 0), W - 1)) * C;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const T t = c < C ? p[c < C ? c : 0] : (T)0;
@@ -476,18 +485,22 @@ __global__ __launch_bounds__(128) void space_to_depth_rows_kernel(const T* x, T*
     }
 }
 
-hipError_t launch_space_to_depth(const void* x, void* y, const int32_t* gather, int B, int H, int W, int C, int Hs, int Ws, int pad, int dtype, hipStream_t s)
+hipError_t launch_space_to_depth(const void* x, void* y, const int32_t* gather, int B, int H, int W, int C, int Hs, int Ws, int pad, int dtype, hipStream_t s, bool gather_on_host)
 {
     const long long total = (long long)B * Hs * Ws;
     if (total <= 0) return hipSuccess;
     const int es = dtype == EE_I8 ? 1 : 2;
     const size_t row_bytes = (size_t)W * C * es;
-    if (row_bytes % 4 == 0 && ((size_t)H * row_bytes) % 4 == 0 && 2 * row_bytes <= 48 * 1024 && B <= 65535) {
-        const dim3 grid((unsigned)Hs, (unsigned)B);
+    constexpr int RS = 4;
+    if (row_bytes % 4 == 0 && ((size_t)H * row_bytes) % 4 == 0 && 2 * RS * row_bytes <= 64 * 1024 && B <= 65535) {
+        const dim3 grid((unsigned)((Hs + RS - 1) / RS), (unsigned)B);
+        IdTab tab{};
+        const bool host_ids = gather_on_host && gather && B <= 256;      // ids the host can read: by value
+        if (host_ids) std::memcpy(tab.id, gather, sizeof(int32_t) * (size_t)B);
         if (dtype == EE_I8)
-            EE_LAUNCH(space_to_depth_rows_kernel<signed char>, grid, dim3(128), 2 * row_bytes, s, (const signed char*)x, (signed char*)y, gather, H, W, C, Hs, Ws, pad);
+            EE_LAUNCH((space_to_depth_rows_kernel<signed char, RS>), grid, dim3(256), 2 * RS * row_bytes, s, tab, (const signed char*)x, (signed char*)y, gather, (int)host_ids, H, W, C, Hs, Ws, pad);
         else
-            EE_LAUNCH(space_to_depth_rows_kernel<uint16_t>, grid, dim3(128), 2 * row_bytes, s, (const uint16_t*)x, (uint16_t*)y, gather, H, W, C, Hs, Ws, pad);
+            EE_LAUNCH((space_to_depth_rows_kernel<uint16_t, RS>), grid, dim3(256), 2 * RS * row_bytes, s, tab, (const uint16_t*)x, (uint16_t*)y, gather, (int)host_ids, H, W, C, Hs, Ws, pad);
         return hipGetLastError();
     }
     const unsigned blocks = (unsigned)((total + 255) / 256);

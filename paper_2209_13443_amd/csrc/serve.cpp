@@ -154,8 +154,10 @@ struct GpuExec {
     int run_step(int lane, int stage, int b, int src_off, int ring_rows)
     {
         if (zc) { const int rc = zc_begin(lane, stage, b, src_off, ring_rows); if (rc) return rc; }
+        ctx->gap_fuse_dst = ctx->sums;                   // the segment's last layer pools for the exit head where it can
         int rc = ctx->run_stage(stage, b, step_in(stage, src_off), step_out(stage), stage == 0 && ctx->admission_fold() != nullptr);
-        if (!rc) rc = ctx->run_head(stage, b, step_out(stage), ctx->net.exits[stage].thr, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag, true, nullptr, ctx->zc_out);
+        ctx->gap_fuse_dst = nullptr;
+        if (!rc) rc = ctx->run_head(stage, b, step_out(stage), ctx->net.exits[stage].thr, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag, true, nullptr, ctx->zc_out, ctx->gap_fused);
         ctx->zc_in = ctx->zc_out = nullptr;
         return rc;
     }
@@ -176,7 +178,7 @@ struct GpuExec {
             const OpDesc& d = p->d;
             const int es = ctx->net.elem_bytes();
             e = ctx->timed(EE_K_ADMIT, 0.0, (double)b * (sb + (double)p->Hp * p->Wp * 16 * es), [&] {
-                return launch_space_to_depth(pool, ctx->pad_bufs[p->pad_buf], h_ids, b, d.h_in, d.w_in, d.c_in, p->Hp, p->Wp, d.pad, ctx->net.dtype, ctx->stream);
+                return launch_space_to_depth(pool, ctx->pad_bufs[p->pad_buf], h_ids, b, d.h_in, d.w_in, d.c_in, p->Hp, p->Wp, d.pad, ctx->net.dtype, ctx->stream, true);
             });
         } else {
             e = ctx->timed(EE_K_ADMIT, 0.0, 2.0 * sb * b, [&] { return launch_admit(pool, ctx->in_buf[0], h_ids, b, sb, ctx->stream); });
