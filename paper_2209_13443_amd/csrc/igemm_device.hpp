@@ -7,6 +7,10 @@
 #include <type_traits>
 #include <utility>
 
+#ifndef EE_FRAG_DISTANCE
+#define EE_FRAG_DISTANCE 2      // sub-steps between the read of a fragment and the matrix instructions that use it (pipelined steps)
+#endif
+
 namespace ee {
 
 typedef int v4i __attribute__((ext_vector_type(4)));

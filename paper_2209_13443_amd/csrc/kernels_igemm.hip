@@ -227,7 +227,7 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(SlotTab, SlotTab
     // next step are on their way while this step still multiplies.  Copies of a step are issued in its first
     // SPW - FD sub-steps, i.e. before that barrier: behind it only the ns - 2 later stages are outstanding.
     constexpr bool V2 = EE_IGEMM_PIPELINED && KSPL == 1 && SPW >= 4;
-    constexpr int FD = 2, NFB = 4;
+    constexpr int FD = EE_FRAG_DISTANCE, NFB = 4;
     v4i gw[V2 ? NFB : 1][TN], gx[V2 ? NFB : 1][TM];
     auto step2 = [&](int sc, int sn, int si, auto issue_tag, auto last_tag) {
         constexpr bool ISSUE = decltype(issue_tag)::value, LAST = decltype(last_tag)::value;

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void conv_slab_kernel(ConvArgs a, int gm, int 
     constexpr int R256 = KS >= 256 ? 1 : 256 / KS; // staged weight rows per 256 bytes of LDS
     constexpr int TILE_O = BM * BN * ES;
     constexpr int SPW = KS / 32;                   // matrix sub-steps per stage
-    constexpr int FD = 2, NFB = 4;                 // fragments are read FD sub-steps ahead into NFB register sets used in turn
+    constexpr int FD = EE_FRAG_DISTANCE, NFB = 4;                 // fragments are read FD sub-steps ahead into NFB register sets used in turn
     constexpr int ZERO_BYTES = 1024;               // what taps outside the image read; at least one pixel long
     static_assert(LPT >= 1 && BN % RPP == 0 && SPW >= 4 && SPW % NFB == 0, "tile / step not supported");
 
