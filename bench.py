@@ -27,7 +27,7 @@ PEAK = {"i8": 5000.0, "bf16": 2500.0}          # dense MFMA peak of MI355X, TOP/
 HBM_PEAK = 8000.0                               # GB/s
 
 
-CONV_SOURCES = ("kernels_igemm.hip", "kernels_pair.hip", "igemm_device.hpp")
+CONV_SOURCES = ("kernels_igemm.hip", "kernels_slab.hip", "kernels_pair.hip", "igemm_device.hpp", "igemm_epilogue.hpp")
 
 
 def conv_sources_digest():
@@ -207,11 +207,14 @@ def run_stream(args, name, steps, warmup, full=True):
     lut = eng.measure_lut(reps=3)                      # design-time exit-level latency table
     min_incr = args.min_incr or max(1, b_max // 2)
 
+    # survivors of an exit stay where they are (zero-copy compaction) wherever the network allows it, under every policy
+    zero_copy = int(eng.zero_copy_supported() and args.zero_copy != 0)
+
     # static-batch throughput (model-level batching, everything queued at t = 0) sets the arrival rate
     zeros = np.zeros(n, np.int64)
-    eng.serve_stream(zeros, pool, lut, clock=0, refill=0)
+    eng.serve_stream(zeros, pool, lut, clock=0, refill=0, zero_copy=zero_copy)
     t0 = time.perf_counter()
-    res_static, st_static, _ = eng.serve_stream(zeros, pool, lut, clock=0, refill=0)
+    res_static, st_static, _ = eng.serve_stream(zeros, pool, lut, clock=0, refill=0, zero_copy=zero_copy)
     static_rate = n / (time.perf_counter() - t0)
     load = (args.load if full else 0.0) or wl["load"]
     if load is None:
@@ -226,8 +229,7 @@ def run_stream(args, name, steps, warmup, full=True):
     lanes = ((args.lanes if full else 0) or wl.get("lanes", 2)) if refill == 2 else 1
     eng.set_lanes(lanes)
 
-    # survivors of an exit stay where they are (zero-copy compaction) wherever the network allows it and two lanes suffice
-    zero_copy = int(eng.zero_copy_supported() and args.zero_copy != 0 and lanes <= 2)
+    zero_copy = int(zero_copy and lanes <= 2)          # its slots cover two steps in flight
 
     def step(policy=refill, arr=None, min_incr_=None, lanes_=None, zc=None):
         return eng.serve_stream(arrivals if arr is None else arr, pool, lut, clock=0, refill=policy, min_incr=min_incr_ or min_incr, t_slo_ns=t_slo_ns,
@@ -316,7 +318,7 @@ def run_stream(args, name, steps, warmup, full=True):
     roofline = None
     if conv["launches"]:
         achieved = conv["ops"] / (conv["ms"] * 1e-3) / 1e12
-        roofline = dict(bound="mfma", kernel="conv_igemm_kernel, conv_pair_kernel", achieved=round(achieved, 2), peak=PEAK[dtype],
+        roofline = dict(bound="mfma", kernel="conv_igemm_kernel, conv_slab_kernel, conv_pair_kernel", achieved=round(achieved, 2), peak=PEAK[dtype],
                         unit="TOP/s" if dtype == "i8" else "TFLOP/s", frac=round(achieved / PEAK[dtype], 4), traffic=None,
                         launches=conv["launches"], avg_launch_us=round(conv["ms"] * 1e3 / conv["launches"], 2),
                         algorithmic_gops_per_launch=round(conv["ops"] / conv["launches"] / 1e9, 3),

@@ -229,6 +229,7 @@ int alloc_lane(ee_ctx* ctx, LaneState& L)
     if ((rc = dev_alloc(ctx, &L.d_score, sizeof(int64_t) * (size_t)b_max))) return rc;
     if ((rc = dev_alloc(ctx, &L.d_flag, (size_t)b_max + 16))) return rc;
     if ((rc = dev_alloc(ctx, &L.d_arrive, 64))) return rc;
+    if ((rc = dev_alloc(ctx, &L.d_slots, 2 * sizeof(uint16_t) * EE_ZC_MAX_B))) return rc;
     const size_t out_bytes = round_up((int)(sizeof(HostOutcome) * (size_t)b_max), 256), ids_bytes = round_up(4 * b_max, 256);
     if (hipHostMalloc(&L.h_pinned, out_bytes + 2 * ids_bytes + 256, hipHostMallocCoherent) != hipSuccess) return EE_ERR_DEVICE;
     std::memset(L.h_pinned, 0, out_bytes + 2 * ids_bytes + 256);
@@ -435,7 +436,7 @@ void ee_ctx::bind_lane(int j)
     const ee::LaneState& L = lanes[(size_t)j];
     stream = L.stream; pool = L.pool; pad_bufs = L.pad_bufs; out_buf = L.out_buf; in_buf[0] = L.in0;
     sums = L.sums; gap_partial = L.gap_partial; logits = L.logits;
-    d_label = L.d_label; d_conf = L.d_conf; d_score = L.d_score; d_flag = L.d_flag; d_arrive = L.d_arrive;
+    d_label = L.d_label; d_conf = L.d_conf; d_score = L.d_score; d_flag = L.d_flag; d_arrive = L.d_arrive; d_slots = L.d_slots;
     h_out = L.h_out; h_ids[0] = L.h_ids[0]; h_ids[1] = L.h_ids[1]; h_seq = L.h_seq; seq = L.seq; ids_turn = L.ids_turn;
     lane = j;
 }
@@ -503,7 +504,7 @@ void ee_ctx::fill_conv_args(int op, int b, ConvArgs& a) const
     a.shift = d.shift; a.res_shift = d.res_shift; a.lo = d.lo; a.hi = d.hi; a.f_lo = d.f_lo; a.f_hi = d.f_hi;
 }
 
-hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg, const SlotTab* xs, const SlotTab* ys, int32_t* gap_sums)
+hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg, const uint16_t* xs, const uint16_t* ys, int32_t* gap_sums)
 {
     const OpPlan& p = plans[op];
     const int dt = net.dtype;
@@ -518,10 +519,10 @@ hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const 
     a.x = src; a.mode = 0;
     if (xs || ys || gap_sums) {                          // slot tables, fused pooling: the general kernel only
         if (p.impl != IMPL_MFMA || ((xs || ys) && b > EE_ZC_MAX_B)) return hipErrorInvalidValue;
-        a.slots = (xs ? EE_GATHER_X : 0) | (ys ? EE_SCATTER_Y : 0);
+        a.xs = xs; a.ys = ys;
         a.gap_sums = gap_sums;
         if ((cfg & EE_CFG_SLAB) || (cfg & 15) == 7) cfg = 0;
-        return dt == EE_I8 ? launch_conv_igemm<1>(a, cfg, stream, xs, ys) : launch_conv_igemm<2>(a, cfg, stream, xs, ys);
+        return dt == EE_I8 ? launch_conv_igemm<1>(a, cfg, stream) : launch_conv_igemm<2>(a, cfg, stream);
     }
     const bool streamable = conv_stream_supported(a, dt == EE_I8 ? 1 : 2);
     if ((cfg & 15) == 7) {
@@ -743,8 +744,8 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
         const double ops = p.ops_per_sample * b, bytes = p.bytes_per_sample * b + p.weight_bytes;
         hipError_t e = hipSuccess;
         int32_t* gap_dst = gap_fuse_dst && only_op < 0 && st.first_op + k == gap_fuse_op[(size_t)stage] ? gap_fuse_dst : nullptr;
-        const SlotTab* xs = p.src_buf == BUF_EXT_IN ? zc_in : nullptr;
-        const SlotTab* ys = p.dst_buf == BUF_EXT_OUT ? zc_out : nullptr;
+        const uint16_t* xs = p.src_buf == BUF_EXT_IN ? zc_in : nullptr;
+        const uint16_t* ys = p.dst_buf == BUF_EXT_OUT ? zc_out : nullptr;
         if ((xs || ys) && p.impl != IMPL_MFMA) return EE_ERR_UNSUPPORTED;
         if (zc_in && d.res >= 0 && p.res_buf == BUF_EXT_IN) return EE_ERR_UNSUPPORTED;
         if (p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_C4 || p.impl == IMPL_MFMA_CPAD || p.impl == IMPL_MFMA_S2D) {
@@ -824,7 +825,7 @@ extern "C" int ee_stage_forward(ee_ctx* ctx, int stage, int b_act, const void* a
 
 // ---- one exit head ------------------------------------------------------------------------------------
 int ee_ctx::run_head(int stage, int b, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag, bool to_host,
-                     const ee::HeadScratch* own, const ee::SlotTab* slots, bool pooled)
+                     const ee::HeadScratch* own, const uint16_t* slots, bool pooled)
 {
     const ExitDesc& e = net.exits[stage];
     const int dt = net.dtype, es = net.elem_bytes();
@@ -837,9 +838,10 @@ int ee_ctx::run_head(int stage, int b, const void* act, float thr, int32_t* labe
     a.s_thr = !(thr > 0.0f) ? INT64_MAX : (thr > 1.0f ? 0 : (int64_t)std::floor(1073741824.0 / (double)thr));
     a.last = stage == (int)net.stages.size() - 1;
     a.label = label; a.conf = conf; a.score = score; a.flag = flag;
+    a.slots = slots;
     if (to_host) { a.host_out = h_out; a.host_seq = h_seq; a.seq_value = ++seq; a.arrive_counter = d_arrive; }
     const double act_bytes = (double)b * a.HW * a.C * es;
-    if (!pooled && timed(EE_K_GAP, 0.0, act_bytes + 4.0 * b * a.C, [&] { return launch_head_gap(a, dt, stream, slots); }) != hipSuccess) return EE_ERR_DEVICE;
+    if (!pooled && timed(EE_K_GAP, 0.0, act_bytes + 4.0 * b * a.C, [&] { return launch_head_gap(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;
     if (timed(EE_K_FC, 2.0 * b * a.C * a.n_cls, (double)a.C * a.n_cls * es + 4.0 * b * (a.C + a.n_cls),
               [&] { return launch_head_fc(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;
     if (timed(EE_K_SOFTMAX, 0.0, 4.0 * b * a.n_cls + 17.0 * b, [&] { return launch_head_softmax(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;

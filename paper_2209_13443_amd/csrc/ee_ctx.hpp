@@ -39,6 +39,7 @@ struct LaneState {
     int32_t* sums = nullptr; int32_t* gap_partial = nullptr; void* logits = nullptr;
     int32_t* d_label = nullptr; float* d_conf = nullptr; int64_t* d_score = nullptr; uint8_t* d_flag = nullptr;
     unsigned* d_arrive = nullptr;
+    uint16_t* d_slots = nullptr;                 // the lane's two slot tables (zero-copy compaction)
     void* h_pinned = nullptr; HostOutcome* h_out = nullptr; int32_t* h_ids[2] = {nullptr, nullptr}; unsigned* h_seq = nullptr;
     unsigned seq = 0;
     int ids_turn = 0;
@@ -77,6 +78,7 @@ struct ee_ctx {
     unsigned* h_seq = nullptr;                   // sequence word stored by the exit head when h_out is complete
     unsigned seq = 0;                            // last sequence value handed to an exit head
     unsigned* d_arrive = nullptr;                // device counter of exit-head workgroups that have finished
+    uint16_t* d_slots = nullptr;                 // the bound lane's two slot tables (zero-copy compaction)
     int ids_turn = 0;
     // zero-copy compaction (stream serving): slot tables of the step being enqueued, or null.  With zc_in, sample n of a
     // segment's input is slot zc_in->s[n] of act_in; with zc_out, sample n of its output goes to slot zc_out->s[n] of act_out.
@@ -86,8 +88,8 @@ struct ee_ctx {
     std::vector<int> gap_fuse_op;
     int32_t* gap_fuse_dst = nullptr;
     bool gap_fused = false;
-    const ee::SlotTab* zc_in = nullptr;
-    const ee::SlotTab* zc_out = nullptr;
+    const uint16_t* zc_in = nullptr;             // device memory
+    const uint16_t* zc_out = nullptr;
     bool zero_copy_ok = false;                   // every segment boundary can be served that way (set by ee_create)
     int zc_slots = 0;                            // sample slots in every in_buf behind the first
     int pair_mode = 1;                           // fused layer pairs: 0 never, 1 as the table says, 2 wherever possible
@@ -129,7 +131,7 @@ struct ee_ctx {
         return &p;
     }
     // launches layer `op` (an index into plans) on b samples with the given kernel configuration (0 = by shape)
-    hipError_t launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg, const ee::SlotTab* xs = nullptr, const ee::SlotTab* ys = nullptr, int32_t* gap_sums = nullptr);
+    hipError_t launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg, const uint16_t* xs = nullptr, const uint16_t* ys = nullptr, int32_t* gap_sums = nullptr);
     // layers op and op + 1 as one fused launch: src feeds layer op, res and dst belong to layer op + 1
     hipError_t launch_pair(int op, int b, const void* src, void* dst, const void* res, int cfg);
     void fill_conv_args(int op, int b, ee::ConvArgs& a) const;
@@ -137,7 +139,7 @@ struct ee_ctx {
     // to_host: also write the outcomes to h_out and store ++seq to h_seq when they are all there
     // own: scratch memory to use instead of the context's (sums, gap_partial, logits)
     int run_head(int stage, int b_act, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag,
-                 bool to_host = false, const ee::HeadScratch* own = nullptr, const ee::SlotTab* slots = nullptr, bool pooled = false);
+                 bool to_host = false, const ee::HeadScratch* own = nullptr, const uint16_t* slots = nullptr, bool pooled = false);
     // times `launch` with a pair of events attached to its dispatch when profiling
     template <typename F>
     hipError_t timed(int cls, double ops, double bytes, F&& launch, int op = -1);

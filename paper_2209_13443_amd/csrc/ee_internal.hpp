@@ -50,11 +50,12 @@ int parse_blob(const void* blob, size_t bytes, NetDesc* out);
 // ---- slot tables (zero-copy compaction) ----------------------------------------------------------
 // Survivors of an exit are never moved: the samples of a batch live in arbitrary slots of the next segment's
 // input memory and a table names the slot of every batch row (the GPU analogue of changing only the DMA
-// addressing, Sec. III-A / III-B "Overhead").  The tables travel as the FIRST kernel arguments, by value, and the
-// kernels read them straight out of the kernel-argument segment.
+// addressing, Sec. III-A / III-B "Overhead").  The host hands a step's two tables (input rows, output rows) to one
+// tiny kernel by value, which stores them in device memory; the convolution and pooling kernels read them there.
 enum { EE_ZC_MAX_B = 256 };
 struct SlotTab { uint16_t s[EE_ZC_MAX_B]; };
-enum { EE_GATHER_X = 1, EE_SCATTER_Y = 2 };
+// dst[0..255] = in, dst[256..511] = out
+hipError_t launch_upload_slots(const SlotTab& in, const SlotTab& out, uint16_t* dst, hipStream_t s);
 
 // ---- kernel argument blocks --------------------------------------------------------------------
 // Implicit-GEMM convolution: rows = output pixels m = (n, oy, ox), columns = output channels,
@@ -76,7 +77,8 @@ struct ConvArgs {
     int shift, res_shift, lo, hi;
     float f_lo, f_hi;
     int* gap_sums;       // not null (int8, conv_igemm_kernel, last layer of a segment): also add the per-sample channel sums of the output into gap_sums[n][Co]
-    int slots;           // EE_GATHER_X: sample n of the input is slot xs[n] of x; EE_SCATTER_Y: sample n of the output is slot ys[n] of y (conv_igemm_kernel only)
+    const uint16_t* xs;  // not null: sample n of the input is slot xs[n] of x (device memory; conv_igemm_kernel only)
+    const uint16_t* ys;  // not null: sample n of the output is slot ys[n] of y (device memory; conv_igemm_kernel only)
 };
 
 // Two chained convolutions in one launch (kernels_pair.hip): c2 is the first layer (its y and res are unused, its
@@ -116,7 +118,7 @@ extern thread_local hipEvent_t g_launch_start, g_launch_stop;     // null: an or
 hipError_t launch_conv_mfma_i8(const ConvArgs& a, hipStream_t s);
 hipError_t launch_conv_mfma_bf16(const ConvArgs& a, hipStream_t s);
 // asynchronous-copy implicit GEMM (ES = element bytes); tile 0 = chosen by shape, 1..4 forced
-template <int ES> hipError_t launch_conv_igemm(const ConvArgs& a, int tile, hipStream_t s, const SlotTab* xs = nullptr, const SlotTab* ys = nullptr);
+template <int ES> hipError_t launch_conv_igemm(const ConvArgs& a, int tile, hipStream_t s);
 // the fused pair (ES = element bytes); cfg 0 = chosen by shape
 template <int ES> hipError_t launch_conv_pair(const PairArgs& p, int cfg, hipStream_t s);
 bool conv_pair_supported(int es, int co2, int kh, int kw, int ci, int co3);
@@ -162,7 +164,7 @@ struct HeadArgs {
     // stream serving: per-slot outcomes written straight into pinned host memory, and a sequence word
     // the last workgroup stores once every record is visible to the host (all three null otherwise)
     struct HostOutcome* host_out; unsigned* host_seq; unsigned seq_value; unsigned* arrive_counter;
-    int gather;          // pooling: sample b of the batch is slot tab[b] of act
+    const uint16_t* slots;   // pooling: not null: sample b of the batch is slot slots[b] of act (device memory)
 };
 struct HostOutcome { int64_t score; int32_t label; float conf; uint32_t flag; uint32_t pad_; };
 // device address, on the current GPU, of the scratch array that is part of the library image (EE_STATIC_SCRATCH_BYTES bytes)
@@ -170,7 +172,7 @@ hipError_t static_scratch(void** out);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 // workgroups the pooling kernel splits a sample's pixels over (bf16 keeps one partial row per split)
 int head_gap_splits(int B, int HW);
-hipError_t launch_head_gap(const HeadArgs& a, int dtype, hipStream_t s, const SlotTab* slots = nullptr);
+hipError_t launch_head_gap(const HeadArgs& a, int dtype, hipStream_t s);
 hipError_t launch_head_fc(const HeadArgs& a, int dtype, hipStream_t s);
 hipError_t launch_head_softmax(const HeadArgs& a, int dtype, hipStream_t s);
 

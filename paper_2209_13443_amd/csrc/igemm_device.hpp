@@ -56,13 +56,6 @@ __host__ __device__ constexpr unsigned igemm_ring_bytes(int ns, int nk, int stag
 }
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-// entry `i` of the k-th 512-byte slot table at the front of the kernel-argument segment
-__device__ __forceinline__ unsigned slot_tab(int k, unsigned i)
-{
-    const __attribute__((address_space(4))) unsigned short* t = (const __attribute__((address_space(4))) unsigned short*)__builtin_amdgcn_kernarg_segment_ptr();
-    return t[k * 256 + i];
-}
-
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), unrolled at compile time
 template <int N, typename F>
 __device__ __forceinline__ void static_for(F&& f)

@@ -68,11 +68,11 @@ __device__ __forceinline__ void igemm_epilogue(const ConvArgs& a, ACC& acc, unsi
     // Cell of (pixel row r, channel cl) in the output tile: chunk (cl*ES/16) ^ oswz(r) of row r.  oswz has period
     // 16, so it is oswz(frow) for all of a lane's rows, and the chunk index splits into a wave-uniform part
     // and a compile-time part: one XOR and one add per cell remain.
-    // zero-copy compaction: sample n of the output goes to slot ys[n] of y (second table of the kernel arguments)
+    // zero-copy compaction: sample n of the output goes to slot ys[n] of y
     auto out_row = [&](int m) -> long long {
-        if (!(a.slots & EE_SCATTER_Y) || m >= a.M) return m;
+        if (!a.ys || m >= a.M) return m;
         const unsigned howo = (unsigned)(a.Ho * a.Wo), n = fast_div((unsigned)m, howo, a.magic_howo);
-        return (long long)slot_tab(1, n) * howo + ((unsigned)m - n * howo);
+        return (long long)a.ys[n] * howo + ((unsigned)m - n * howo);
     };
     const int swz_l = oswz(frow);
     auto finish = [&](auto res_tag, auto wide_tag) {

@@ -51,7 +51,7 @@ namespace ee {
 // the array (Sec. III-A, Eq. 1: samples mapped along P instead of R): with few output pixels the
 // reduction axis supplies the parallelism that keeps a CU's matrix cores and copy queue busy.
 template <int ES, int BM, int BN, int KS, int KSPL, bool PLAIN>
-__global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(SlotTab, SlotTab, ConvArgs a, int gm, int gn, unsigned magic_gn, int per_xcd, int ns)
+__global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(ConvArgs a, int gm, int gn, unsigned magic_gn, int per_xcd, int ns)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(SlotTab, SlotTab
         const unsigned rem = (unsigned)m - n * (unsigned)(a.Ho * a.Wo);
         const unsigned oy = fast_div(rem, (unsigned)a.Wo, a.magic_wo), ox = rem - oy * a.Wo;
         const int iy0 = (int)oy * a.stride - a.pad, ix0 = (int)ox * a.stride - a.pad_w;
-        const unsigned nx = (a.slots & EE_GATHER_X) ? slot_tab(0, n) : n;      // zero-copy compaction: sample n is slot xs[n] of x
+        const unsigned nx = a.xs ? (unsigned)a.xs[n] : n;                    // zero-copy compaction: sample n is slot xs[n] of x
         voffA[j] = (unsigned)((((int)nx * a.H + iy0) * a.W + ix0) * CiB);
         if (PLAIN) {
             voffA[j] += cchunk * 16;
@@ -366,7 +366,7 @@ __global__ __launch_bounds__(256 * KSPL) void conv_igemm_kernel(SlotTab, SlotTab
 
 // ---- launch ------------------------------------------------------------------------------------------------
 template <int ES, int BM, int BN, int KS, int KSPL>
-static hipError_t launch_igemm_tile(const ConvArgs& a, bool plain, int ns, hipStream_t s, const SlotTab& xs, const SlotTab& ys)
+static hipError_t launch_igemm_tile(const ConvArgs& a, bool plain, int ns, hipStream_t s)
 {
     const int gm = (a.M + BM - 1) / BM, gn = (a.Co + BN - 1) / BN, per_xcd = (gm + 7) / 8;
     const dim3 grid((unsigned)(8 * per_xcd * gn));
@@ -388,9 +388,9 @@ static hipError_t launch_igemm_tile(const ConvArgs& a, bool plain, int ns, hipSt
     if (granted != hipSuccess) return granted;
     if (lds_bytes > 160 * 1024) return hipErrorInvalidValue;
     if (plain)
-        EE_LAUNCH((conv_igemm_kernel<ES, BM, BN, KS, KSPL, true>), grid, dim3(256 * KSPL), lds_bytes, s, xs, ys, a, gm, gn, magic_gn, per_xcd, ns);
+        EE_LAUNCH((conv_igemm_kernel<ES, BM, BN, KS, KSPL, true>), grid, dim3(256 * KSPL), lds_bytes, s, a, gm, gn, magic_gn, per_xcd, ns);
     else
-        EE_LAUNCH((conv_igemm_kernel<ES, BM, BN, KS, KSPL, false>), grid, dim3(256 * KSPL), lds_bytes, s, xs, ys, a, gm, gn, magic_gn, per_xcd, ns);
+        EE_LAUNCH((conv_igemm_kernel<ES, BM, BN, KS, KSPL, false>), grid, dim3(256 * KSPL), lds_bytes, s, a, gm, gn, magic_gn, per_xcd, ns);
     return hipGetLastError();
 }
 
@@ -399,11 +399,8 @@ static hipError_t launch_igemm_tile(const ConvArgs& a, bool plain, int ns, hipSt
 // wavefront groups splitting the reduction inside a workgroup (0 or 1: none, 2, 4).  Not every combination
 // exists: hipErrorInvalidValue for one that does not (or does not fit LDS).
 template <int ES>
-hipError_t launch_conv_igemm(const ConvArgs& a_in, int cfg, hipStream_t s, const SlotTab* xs_in, const SlotTab* ys_in)
+hipError_t launch_conv_igemm(const ConvArgs& a_in, int cfg, hipStream_t s)
 {
-    static const SlotTab no_slots{};
-    const SlotTab& xs = xs_in ? *xs_in : no_slots;
-    const SlotTab& ys = ys_in ? *ys_in : no_slots;
     if (a_in.M <= 0) return hipSuccess;
     int tile = cfg & 15, ksel = (cfg >> 4) & 15, ns = (cfg >> 8) & 15, kspl = (cfg >> 12) & 15;
     const int kbytes = a_in.kh * a_in.kw * a_in.Ci * ES;
@@ -425,30 +422,30 @@ hipError_t launch_conv_igemm(const ConvArgs& a_in, int cfg, hipStream_t s, const
     }
     if (ns == 0) ns = 2;     // measured: more workgroups per CU beat a deeper ring at these problem sizes
     if (kspl >= 2) {          // measured to pay only for small tiles with the longest step
-        if (kspl == 2 && ks == 256 && tile == 3) return launch_igemm_tile<ES, 64, 64, 256, 2>(a, plain, ns, s, xs, ys);
-        if (kspl == 2 && ks == 256 && tile == 4) return launch_igemm_tile<ES, 64, 128, 256, 2>(a, plain, ns, s, xs, ys);
-        if (kspl == 4 && ks == 256 && tile == 3) return launch_igemm_tile<ES, 64, 64, 256, 4>(a, plain, ns, s, xs, ys);
+        if (kspl == 2 && ks == 256 && tile == 3) return launch_igemm_tile<ES, 64, 64, 256, 2>(a, plain, ns, s);
+        if (kspl == 2 && ks == 256 && tile == 4) return launch_igemm_tile<ES, 64, 128, 256, 2>(a, plain, ns, s);
+        if (kspl == 4 && ks == 256 && tile == 3) return launch_igemm_tile<ES, 64, 64, 256, 4>(a, plain, ns, s);
         return hipErrorInvalidValue;
     }
     if (ks == 256) {
-        if (tile == 1) return launch_igemm_tile<ES, 128, 128, 256, 1>(a, plain, ns, s, xs, ys);
-        if (tile == 2) return launch_igemm_tile<ES, 128, 64, 256, 1>(a, plain, ns, s, xs, ys);
-        if (tile == 4) return launch_igemm_tile<ES, 64, 128, 256, 1>(a, plain, ns, s, xs, ys);
-        return launch_igemm_tile<ES, 64, 64, 256, 1>(a, plain, ns, s, xs, ys);
+        if (tile == 1) return launch_igemm_tile<ES, 128, 128, 256, 1>(a, plain, ns, s);
+        if (tile == 2) return launch_igemm_tile<ES, 128, 64, 256, 1>(a, plain, ns, s);
+        if (tile == 4) return launch_igemm_tile<ES, 64, 128, 256, 1>(a, plain, ns, s);
+        return launch_igemm_tile<ES, 64, 64, 256, 1>(a, plain, ns, s);
     }
     if (ks == 128) {
-        if (tile == 1) return launch_igemm_tile<ES, 128, 128, 128, 1>(a, plain, ns, s, xs, ys);
-        if (tile == 2) return launch_igemm_tile<ES, 128, 64, 128, 1>(a, plain, ns, s, xs, ys);
-        if (tile == 4) return launch_igemm_tile<ES, 64, 128, 128, 1>(a, plain, ns, s, xs, ys);
-        return launch_igemm_tile<ES, 64, 64, 128, 1>(a, plain, ns, s, xs, ys);
+        if (tile == 1) return launch_igemm_tile<ES, 128, 128, 128, 1>(a, plain, ns, s);
+        if (tile == 2) return launch_igemm_tile<ES, 128, 64, 128, 1>(a, plain, ns, s);
+        if (tile == 4) return launch_igemm_tile<ES, 64, 128, 128, 1>(a, plain, ns, s);
+        return launch_igemm_tile<ES, 64, 64, 128, 1>(a, plain, ns, s);
     }
-    if (tile == 1) return launch_igemm_tile<ES, 128, 128, 64, 1>(a, plain, ns, s, xs, ys);
-    if (tile == 2) return launch_igemm_tile<ES, 128, 64, 64, 1>(a, plain, ns, s, xs, ys);
-    if (tile == 4) return launch_igemm_tile<ES, 64, 128, 64, 1>(a, plain, ns, s, xs, ys);
-    return launch_igemm_tile<ES, 64, 64, 64, 1>(a, plain, ns, s, xs, ys);
+    if (tile == 1) return launch_igemm_tile<ES, 128, 128, 64, 1>(a, plain, ns, s);
+    if (tile == 2) return launch_igemm_tile<ES, 128, 64, 64, 1>(a, plain, ns, s);
+    if (tile == 4) return launch_igemm_tile<ES, 64, 128, 64, 1>(a, plain, ns, s);
+    return launch_igemm_tile<ES, 64, 64, 64, 1>(a, plain, ns, s);
 }
 
-template hipError_t launch_conv_igemm<1>(const ConvArgs&, int, hipStream_t, const SlotTab*, const SlotTab*);
-template hipError_t launch_conv_igemm<2>(const ConvArgs&, int, hipStream_t, const SlotTab*, const SlotTab*);
+template hipError_t launch_conv_igemm<1>(const ConvArgs&, int, hipStream_t);
+template hipError_t launch_conv_igemm<2>(const ConvArgs&, int, hipStream_t);
 
 }  // namespace ee

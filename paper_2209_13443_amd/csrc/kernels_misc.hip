@@ -479,7 +479,7 @@ hipError_t launch_avgpool(const PoolArgs& a, int dtype, hipStream_t s)
 // release per workgroup, which on this chip writes back the whole L2 of its XCD.)
 // Needs C * ES / 16 <= 256.
 template <int ES>
-__global__ __launch_bounds__(256) void gap_kernel(SlotTab, HeadArgs a, int pix_per_block)
+__global__ __launch_bounds__(256) void gap_kernel(HeadArgs a, int pix_per_block)
 {
     constexpr int NE = 16 / ES;
     __shared__ int red[256 * NE];
@@ -489,9 +489,7 @@ __global__ __launch_bounds__(256) void gap_kernel(SlotTab, HeadArgs a, int pix_p
     const int q = (int)threadIdx.x % cchunks, pl = (int)threadIdx.x / cchunks;
     const bool active = pl < npl;
     const int p0 = blockIdx.x * pix_per_block, p1 = min(a.HW, p0 + pix_per_block);
-    // zero-copy compaction: sample b of the batch is slot tab[b] of act (the table is the first kernel argument)
-    const __attribute__((address_space(4))) unsigned short* tab = (const __attribute__((address_space(4))) unsigned short*)__builtin_amdgcn_kernarg_segment_ptr();
-    const long long bs = a.gather ? (long long)tab[b] : (long long)b;
+    const long long bs = a.slots ? (long long)a.slots[b] : (long long)b;      // zero-copy compaction: sample b of the batch is slot slots[b] of act
     const unsigned char* x = (const unsigned char*)a.act + bs * a.HW * a.C * ES;
     int acci[NE];
     float accf[NE];
@@ -580,23 +578,18 @@ int head_gap_splits(int B, int HW)
     return (HW + ppb - 1) / ppb;
 }
 
-hipError_t launch_head_gap(const HeadArgs& a_in, int dtype, hipStream_t s, const SlotTab* slots)
+hipError_t launch_head_gap(const HeadArgs& a, int dtype, hipStream_t s)
 {
-    if (a_in.B <= 0) return hipSuccess;
-    static const SlotTab no_slots{};
-    if (slots && a_in.B > EE_ZC_MAX_B) return hipErrorInvalidValue;
-    const SlotTab& tab = slots ? *slots : no_slots;
-    HeadArgs a = a_in;
-    a.gather = slots != nullptr;
+    if (a.B <= 0) return hipSuccess;
     const int ppb = gap_pixels_per_block(a.B, a.HW);
     const int splits = (a.HW + ppb - 1) / ppb;
     if (dtype == EE_I8) {
-        EE_LAUNCH(gap_kernel<1>, dim3(splits, a.B), dim3(256), 0, s, tab, a, ppb);
+        EE_LAUNCH(gap_kernel<1>, dim3(splits, a.B), dim3(256), 0, s, a, ppb);
     } else {
         // two kernels when the pooling is split: a timed launch takes the first one's begin and the second one's end
         const hipEvent_t t0 = g_launch_start, t1 = g_launch_stop;
         if (splits > 1) g_launch_stop = nullptr;
-        EE_LAUNCH(gap_kernel<2>, dim3(splits, a.B), dim3(256), 0, s, tab, a, ppb);
+        EE_LAUNCH(gap_kernel<2>, dim3(splits, a.B), dim3(256), 0, s, a, ppb);
         if (splits > 1) {
             const long long total = (long long)a.B * (a.C / 4);
             g_launch_start = nullptr;
@@ -868,6 +861,19 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(v4i* p, long long n16)
 }
 
 // bytes [0, round-up-to-16(bytes)) of p become zero; a kernel, not a memset node, so that it may be captured
+// ---- slot tables of a step: kernel arguments -> device memory ---------------------------------------------
+__global__ __launch_bounds__(256) void upload_slots_kernel(SlotTab in, SlotTab out, uint16_t* dst)
+{
+    dst[threadIdx.x] = in.s[threadIdx.x];
+    dst[EE_ZC_MAX_B + threadIdx.x] = out.s[threadIdx.x];
+}
+
+hipError_t launch_upload_slots(const SlotTab& in, const SlotTab& out, uint16_t* dst, hipStream_t s)
+{
+    EE_LAUNCH(upload_slots_kernel, dim3(1), dim3(EE_ZC_MAX_B), 0, s, in, out, dst);
+    return hipGetLastError();
+}
+
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s)
 {
     const long long n16 = (long long)((bytes + 15) / 16);

@@ -268,7 +268,7 @@ static int log2_exact(int v)
 bool conv_slab_supported(const ConvArgs& a, int es)
 {
     const int cib = a.Ci * es, k = log2_exact(cib);
-    if (a.slots != 0 || a.mode != 0 || a.stride != 1 || a.Ho != a.H || a.Wo != a.W) return false;
+    if (a.xs || a.ys || a.gap_sums || a.mode != 0 || a.stride != 1 || a.Ho != a.H || a.Wo != a.W) return false;
     if (k < 6 || k > 10 || a.kh * a.kw > 31 || a.kh * a.kw < 2) return false;
     if (a.H + 2 * a.pad - a.kh + 1 != a.Ho || a.W + 2 * a.pad_w - a.kw + 1 != a.Wo) return false;
     return (long long)a.M * cib < (1ll << 31);

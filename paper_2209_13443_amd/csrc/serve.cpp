@@ -119,8 +119,10 @@ struct GpuExec {
             if ((int)fr.size() < b) return EE_ERR_OVERFLOW;            // cannot happen: five blocks cover what can be held
             for (int k = 0; k < b; ++k) { st.out.s[k] = fr.back(); fr.pop_back(); }
         }
-        ctx->zc_in = stage > 0 ? &st.in : nullptr;
-        ctx->zc_out = st.has_out ? &st.out : nullptr;
+        // both tables go to the lane's device buffer in one tiny launch ahead of the step's kernels
+        if (launch_upload_slots(st.in, st.out, ctx->d_slots, ctx->stream) != hipSuccess) return EE_ERR_DEVICE;
+        ctx->zc_in = stage > 0 ? ctx->d_slots : nullptr;
+        ctx->zc_out = st.has_out ? ctx->d_slots + EE_ZC_MAX_B : nullptr;
         return EE_OK;
     }
     // the step has ended (its exit head has reported): the input slots it read are free again
