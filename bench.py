@@ -73,14 +73,20 @@ def layer_table(args, ee, W, blob, dtype):
     if args.load_tables:
         with open(args.load_tables) as f:
             eng.load_tables(json.load(f))
-    else:
+    elif not (args.layer >= 0 and args.cfg):
         eng.autotune(reps=5)
     if args.save_tables:
         with open(args.save_tables, "w") as f:
             json.dump(eng.tables(), f)
     rows = []
     for i, op in enumerate(blob.ops):
-        us, ops, byt = eng.time_layer(i, B, 0, reps=30)
+        if args.layer >= 0 and i != args.layer:
+            continue
+        r = eng.time_layer(i, B, args.cfg if args.layer >= 0 else 0, reps=30)
+        if r is None:
+            print(f"layer {i}: configuration {args.cfg:#x} does not exist for it", file=sys.stderr)
+            continue
+        us, ops, byt = r
         cfgs = eng.config_table(i)
         k = int(op["kh"]) * int(op["kw"]) * int(op["c_in"])
         row = dict(layer=i, kind=int(op["kind"]), h=int(op["h_in"]), w=int(op["w_in"]), ci=int(op["c_in"]), co=int(op["c_out"]), kh=int(op["kh"]),
@@ -421,6 +427,8 @@ def main():
     ap.add_argument("--no-other-configs", action="store_true", help="skip the short runs of the other stream configurations")
     ap.add_argument("--layers", type=int, default=0, metavar="B",
                     help="instead of the stream: every layer of the workload's network alone on B samples, tuned, launches back to back")
+    ap.add_argument("--layer", type=int, default=-1, help="with --layers: only this layer (an index into the network's layer list)")
+    ap.add_argument("--cfg", type=lambda v: int(v, 0), default=0, help="with --layer: a forced kernel configuration word (0 = the tuned one)")
     ap.add_argument("--policies", action="store_true",
                     help="instead of the one stream: the serving policies of the evaluation over arrival rates and SLOs (see policy_sweep)")
     args = ap.parse_args()

@@ -13,9 +13,11 @@
  *     pinned host memory;
  *   - device work is enqueued on the HIP stream given to ee_create and is asynchronous unless
  *     stated otherwise: device outputs are valid once the caller has synchronised that stream;
- *   - nothing is allocated after ee_create: activation workspaces are sized for b_max at
+ *   - no device or pinned memory is allocated after ee_create (ee_lanes excepted, which adds a
+ *     lane's workspace): activation workspaces are sized for b_max at
  *     creation, as the paper pre-allocates its buffers for the largest activation matrix at
- *     B_max (Sec. III-B, "Overhead");
+ *     B_max (Sec. III-B, "Overhead").  ee_serve_stream and ee_schedule_sim keep their queues in
+ *     ordinary host containers that may grow during a call;
  *   - activations are NHWC, dense [slot][H][W][C], slot-major; int8 networks use int8
  *     activations, bf16 networks raw bfloat16 (uint16_t);
  *   - a ctx must not be used from two threads at once.
