@@ -98,13 +98,28 @@ def layer_table(args, ee, W, blob, dtype):
         print("op%3d k%d %3dx%-3d ci%5d co%5d %dx%d s%d res%d M=%7d K=%5d: %8.2f us %8.1f T/s %7.1f GB/s  roof %6.2f us (%4.1f%%) cfg 0x%x" % (
             i, row["kind"], row["h"], row["w"], row["ci"], row["co"], row["kh"], row["kw"], row["stride"], row["res"], row["M"], row["K"],
             row["us"], row["tops"], row["gbps"], row["roof_us"], 100 * row["roof_us"] / row["us"], row["cfg"]), file=sys.stderr, flush=True)
+    blocks = []
+    if args.layer < 0 and eng.ir_count() > 0:                     # inverted-residual blocks: the fused launch beside its three layers
+        for i in range(len(blob.ops) - 2):
+            try:
+                r = eng.time_layer(i, B, 0x20000, reps=30)
+            except ee.EEError:
+                continue                                          # the layer heads no block
+            if r is None:
+                continue
+            sep = sum(x["us"] for x in rows if x["layer"] in (i, i + 1, i + 2))
+            tab = eng.ir_table(i)
+            blocks.append(dict(head=i, fused_us=round(r[0], 2), separate_us=round(sep, 2), gbps=round(r[2] / r[0] / 1e3, 1), tops=round(r[1] / r[0] / 1e6, 1),
+                               table=tab[min(len(tab) - 1, max(0, (B - 1).bit_length()))] if tab else None))
+            print("block at op%3d: fused %8.2f us (%6.1f T/s %7.1f GB/s), three layers %8.2f us, table says %s" % (
+                i, r[0], blocks[-1]["tops"], blocks[-1]["gbps"], sep, blocks[-1]["table"]), file=sys.stderr, flush=True)
     conv = [r for r in rows if r["kind"] == W.OP_CONV]
     tot_us = sum(r["us"] for r in rows)
     conv_us = sum(r["us"] for r in conv)
     conv_ops = sum(r["tops"] * r["us"] for r in conv)             # T/s * us = Mop
     out = dict(mode="layers", workload=args.workload, net=WORKLOADS[args.workload]["net"], batch=B, dtype=dtype, total_us=round(tot_us, 1), conv_us=round(conv_us, 1),
-               conv_tops=round(conv_ops / conv_us, 1), conv_frac_of_peak=round(conv_ops / conv_us / PEAK[dtype], 4),
-               roofline_us=round(sum(r["roof_us"] for r in rows), 1), layers=rows)
+               conv_tops=round(conv_ops / max(conv_us, 1e-9), 1), conv_frac_of_peak=round(conv_ops / max(conv_us, 1e-9) / PEAK[dtype], 4),
+               roofline_us=round(sum(r["roof_us"] for r in rows), 1), layers=rows, ir_blocks=blocks)
     print(json.dumps(out))
     eng.close()
 

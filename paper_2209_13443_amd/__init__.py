@@ -24,7 +24,7 @@ EVENT_DT = np.dtype([("t_ns", "<i8"), ("kind", "<i4"), ("stage", "<i4"), ("b", "
 
 SYMBOLS = ["ee_strerror", "ee_blob_check", "ee_create", "ee_destroy", "ee_query", "ee_stage_forward", "ee_exit_head",
            "ee_compact_refill", "ee_serve_stream", "ee_schedule_sim", "ee_measure_lut", "ee_profile_enable",
-           "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_last_logits", "ee_profile_reserve", "ee_autotune", "ee_config_table",
+           "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_ir_count", "ee_ir_mode", "ee_ir_table", "ee_ir_set", "ee_last_logits", "ee_profile_reserve", "ee_autotune", "ee_config_table",
            "ee_pair_count", "ee_pair_mode", "ee_pair_table", "ee_config_set", "ee_pair_set", "ee_exit_head_static",
            "ee_static_scratch_bytes", "ee_time_layer", "ee_lanes", "ee_zero_copy_supported"]
 
@@ -79,6 +79,10 @@ _lib.ee_pair_mode.argtypes = [_V, C.c_int]
 _lib.ee_pair_table.argtypes = [_V, C.c_int, _V, C.c_int]
 _lib.ee_config_set.argtypes = [_V, C.c_int, _V, C.c_int]
 _lib.ee_pair_set.argtypes = [_V, C.c_int, _V, C.c_int]
+_lib.ee_ir_count.argtypes = [_V]
+_lib.ee_ir_mode.argtypes = [_V, C.c_int]
+_lib.ee_ir_table.argtypes = [_V, C.c_int, _V, C.c_int]
+_lib.ee_ir_set.argtypes = [_V, C.c_int, _V, C.c_int]
 _lib.ee_profile_enable.argtypes = [_V, C.c_int]
 _lib.ee_profile_read.argtypes = [_V, _V, _V]
 _lib.ee_profile_reserve.argtypes = [_V, C.c_int64]
@@ -270,7 +274,7 @@ class Engine:
 
     def tables(self):
         """The tuned tables as plain data: {"config": {layer: [...]}, "pair": {layer: [...]}} (layers that have one)."""
-        out = {"config": {}, "pair": {}}
+        out = {"config": {}, "pair": {}, "ir": {}}
         buf = (C.c_int * 16)()
         layer = 0
         while True:
@@ -282,10 +286,13 @@ class Engine:
             n = _lib.ee_pair_table(self._h, layer, buf, 16)
             if n > 0:
                 out["pair"][str(layer)] = list(buf)[:n]
+            n = _lib.ee_ir_table(self._h, layer, buf, 16)
+            if n > 0:
+                out["ir"][str(layer)] = list(buf)[:n]
             layer += 1
 
     def load_tables(self, tables):
-        for key, fn in (("config", _lib.ee_config_set), ("pair", _lib.ee_pair_set)):
+        for key, fn in (("config", _lib.ee_config_set), ("pair", _lib.ee_pair_set), ("ir", _lib.ee_ir_set)):
             for layer, cfg in tables.get(key, {}).items():
                 buf = (C.c_int * len(cfg))(*cfg)
                 _chk(fn(self._h, int(layer), buf, len(cfg)))
@@ -298,6 +305,20 @@ class Engine:
 
     def pair_mode(self, mode):
         _chk(_lib.ee_pair_mode(self._h, int(mode)))
+
+    def ir_count(self):
+        n = _lib.ee_ir_count(self._h)
+        if n < 0:
+            _chk(n)
+        return n
+
+    def ir_mode(self, mode):
+        _chk(_lib.ee_ir_mode(self._h, int(mode)))
+
+    def ir_table(self, layer):
+        buf = (C.c_int * 16)()
+        n = _lib.ee_ir_table(self._h, int(layer), buf, 16)
+        return list(buf)[:max(n, 0)]
 
     def pair_table(self, layer):
         buf = (C.c_int * 16)()

@@ -155,6 +155,62 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
     return rc;
 }
 
+// Marks layer k of the segment as the head of an inverted-residual block when the fused kernel covers it and packs the
+// block's weights for that kernel (see IrArgs).
+int pack_ir(ee_ctx* ctx, const unsigned char* blob, const StageDesc& st, int k)
+{
+    OpPlan& p = ctx->plans[st.first_op + k];
+    const OpDesc& e = p.d;
+    const OpDesc& dw = ctx->plans[st.first_op + k + 1].d;
+    const OpDesc& pr = ctx->plans[st.first_op + k + 2].d;
+    if (e.kind != OP_CONV || dw.kind != OP_DWCONV || pr.kind != OP_CONV) return EE_OK;
+    if (e.kh != 1 || e.kw != 1 || e.stride != 1 || e.pad != 0 || e.pad_w != 0 || e.res >= 0 || e.c_tot != e.c_out) return EE_OK;
+    if (dw.kh != 3 || dw.kw != 3 || dw.pad != 1 || dw.pad_w != 1 || dw.src != e.dst || dw.c_tot != dw.c_out || dw.c_in != e.c_out) return EE_OK;
+    if (pr.kh != 1 || pr.kw != 1 || pr.stride != 1 || pr.pad != 0 || pr.pad_w != 0 || pr.src != dw.dst || pr.c_tot != pr.c_out) return EE_OK;
+    if (e.dst == st.out_tensor || dw.dst == st.out_tensor || pr.res == e.dst || pr.res == dw.dst) return EE_OK;
+    int readers_e = 0, readers_d = 0;
+    for (int j = 0; j < st.n_ops; ++j) {
+        const OpDesc& o = ctx->plans[st.first_op + j].d;
+        readers_e += (o.src == e.dst) + (o.res == e.dst);
+        readers_d += (o.src == dw.dst) + (o.res == dw.dst);
+    }
+    if (readers_e != 1 || readers_d != 1) return EE_OK;
+    const int Ci = e.c_in, Ce = e.c_out, Co = pr.c_out, Kx = round_up(Ci, 32), Ce32 = round_up(Ce, 32), Co32 = 32 * ir_block_out_blocks(Co);
+    IrArgs probe{};
+    probe.B = 1; probe.H = e.h_in; probe.W = e.w_in; probe.Cin = Ci; probe.Kx = Kx; probe.Ce32 = Ce32; probe.Cout = Co;
+    probe.Ho = dw.h_out; probe.Wo = dw.w_out; probe.stride = dw.stride; probe.pad = dw.pad;
+    probe.B = ctx->b_max;
+    if (!ir_block_supported(probe)) return EE_OK;
+    auto rounded_bias = [&](const OpDesc& d, int n, int n_pad) {
+        std::vector<unsigned char> out(4 * (size_t)n_pad, 0);
+        for (int o = 0; o < n; ++o) {
+            int32_t v;
+            std::memcpy(&v, blob + d.b_off + 4 * (size_t)o, 4);
+            if (d.shift > 0) v += 1 << (d.shift - 1);
+            std::memcpy(&out[4 * (size_t)o], &v, 4);
+        }
+        return out;
+    };
+    std::vector<unsigned char> we((size_t)Ce32 * Kx, 0), wd((size_t)(Ce32 / 32) * 9 * 64 * 16, 0), wp((size_t)Co32 * Ce32, 0);
+    for (int c = 0; c < Ce; ++c) std::memcpy(&we[(size_t)c * Kx], blob + e.w_off + (size_t)c * Ci, (size_t)Ci);
+    for (int c = 0; c < Ce; ++c)                                        // [group][tap][lane][16]: row m = lane % 32 of diag(w) lies in the lane whose 16 reduction bytes hold byte m
+        for (int t = 0; t < 9; ++t) {
+            const int g = c / 32, m = c % 32, lane = m + 32 * (m / 16);
+            wd[(((size_t)g * 9 + t) * 64 + lane) * 16 + m % 16] = blob[dw.w_off + (size_t)c * 9 + t];
+        }
+    for (int o = 0; o < Co; ++o) std::memcpy(&wp[(size_t)o * Ce32], blob + pr.w_off + (size_t)o * Ce, (size_t)Ce);
+    int rc = upload(ctx, &p.ir_we, we);
+    if (!rc) rc = upload(ctx, &p.ir_be, rounded_bias(e, Ce, Ce32));
+    if (!rc) rc = upload(ctx, &p.ir_wd, wd);
+    if (!rc) rc = upload(ctx, &p.ir_bd, rounded_bias(dw, Ce, Ce32));
+    if (!rc) rc = upload(ctx, &p.ir_wp, wp);
+    if (!rc) rc = upload(ctx, &p.ir_bp, rounded_bias(pr, Co, Co32));
+    if (rc) return rc;
+    p.ir_kx = Kx; p.ir_ce32 = Ce32;
+    p.ir = true;
+    return EE_OK;
+}
+
 // Assigns the intermediate tensors of every segment to a small pool of reusable buffers
 // (greedy by liveness); the segment input and output stay with the caller.
 void plan_buffers(ee_ctx* ctx)
@@ -169,6 +225,8 @@ void plan_buffers(ee_ctx* ctx)
             // the head of a fused pair: the one launch reads this layer's input while it writes the next layer's
             // output, so the input's buffer must stay reserved over both
             if (k > 0 && ctx->plans[st.first_op + k - 1].pair) last_use[ctx->plans[st.first_op + k - 1].d.src] = k;
+            // likewise the head of a fused inverted-residual block, over its three layers
+            if (k > 1 && ctx->plans[st.first_op + k - 2].ir) last_use[ctx->plans[st.first_op + k - 2].d.src] = k;
         }
         buf[0] = BUF_EXT_IN;
         buf[st.out_tensor] = BUF_EXT_OUT;
@@ -348,6 +406,14 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
             }
             p.pair = readers == 1 && conv_pair_supported(es, p.d.c_out, p.d.kh, p.d.kw, p.ci_eff, q.d.c_out);
         }
+    // inverted-residual blocks one fused launch can take (int8): a 1x1 stride-1 convolution without residual whose output
+    // is read only by the next layer, a 3x3 depthwise layer with padding 1, whose output is read only by the layer after
+    // it, a 1x1 stride-1 convolution (with or without residual); none of the three writes a channel slice
+    if (es == 1)
+        for (const StageDesc& st : ctx->net.stages)
+            for (int k = 0; k + 2 < st.n_ops; ++k) {
+                if ((rc = pack_ir(ctx, (const unsigned char*)blob, st, k))) return fail(rc);
+            }
     plan_buffers(ctx);
     ctx->pool.resize(ctx->pool_sample_bytes.size(), nullptr);
     for (size_t i = 0; i < ctx->pool.size(); ++i)
@@ -541,6 +607,20 @@ hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const 
     return dt == EE_I8 ? launch_conv_igemm<1>(a, cfg, stream) : launch_conv_igemm<2>(a, cfg, stream);
 }
 
+void ee_ctx::fill_ir_args(int op, int b, IrArgs& a) const
+{
+    const OpPlan& p = plans[(size_t)op];
+    const OpDesc& e = p.d;
+    const OpDesc& dw = plans[(size_t)op + 1].d;
+    const OpDesc& pr = plans[(size_t)op + 2].d;
+    a.we = p.ir_we; a.be = (const int*)p.ir_be; a.wd = p.ir_wd; a.bd = (const int*)p.ir_bd; a.wp = p.ir_wp; a.bp = (const int*)p.ir_bp;
+    a.B = b; a.H = e.h_in; a.W = e.w_in; a.Cin = e.c_in; a.Kx = p.ir_kx; a.Ce32 = p.ir_ce32; a.Cout = pr.c_out;
+    a.Ho = dw.h_out; a.Wo = dw.w_out; a.stride = dw.stride; a.pad = dw.pad;
+    a.sh_e = e.shift; a.lo_e = e.lo; a.hi_e = e.hi;
+    a.sh_d = dw.shift; a.lo_d = dw.lo; a.hi_d = dw.hi;
+    a.sh_p = pr.shift; a.lo_p = pr.lo; a.hi_p = pr.hi; a.res_shift = pr.res_shift;
+}
+
 hipError_t ee_ctx::launch_pair(int op, int b, const void* src, void* dst, const void* res, int cfg)
 {
     const OpPlan& q = plans[op + 1];
@@ -645,6 +725,37 @@ extern "C" int ee_autotune(ee_ctx* ctx, int reps)
             if (!rc) p.pair_cfg = best;
         }
     }
+    // fused inverted-residual blocks: the one launch against the block's three layers with their tuned configurations
+    const int ir_was = ctx->ir_mode;
+    for (size_t s = 0; s < ctx->net.stages.size() && !rc; ++s) {
+        const StageDesc& st = ctx->net.stages[s];
+        for (int k = 0; k + 2 < st.n_ops && !rc; ++k) {
+            OpPlan& p = ctx->plans[st.first_op + k];
+            if (!p.ir) continue;
+            std::vector<int> best(buckets.size(), 0);
+            for (size_t bi = 0; bi < buckets.size() && !rc; ++bi) {
+                float ms[2] = {0.f, 0.f};
+                for (int fused = 0; fused < 2 && !rc; ++fused) {
+                    ctx->ir_mode = fused ? 2 : 0;
+                    p.ir_cfg.clear();
+                    auto block = [&]() -> int {                          // the block alone: its head runs all three layers when fused
+                        int r2 = ctx->run_stage((int)s, buckets[bi], ctx->in_buf[s], ctx->out_buf[s], false, -2 - (st.first_op + k));
+                        return r2;
+                    };
+                    if ((rc = block())) break;
+                    hipEventRecord(e0, ctx->stream);
+                    for (int r = 0; r < reps && !rc; ++r) rc = block();
+                    hipEventRecord(e1, ctx->stream);
+                    if (hipEventSynchronize(e1) != hipSuccess) rc = EE_ERR_DEVICE;
+                    hipEventElapsedTime(&ms[fused], e0, e1);
+                }
+                best[bi] = ms[1] < ms[0] ? 1 : 0;
+            }
+            ctx->ir_mode = ir_was;
+            if (!rc) p.ir_cfg = best;
+        }
+    }
+    ctx->ir_mode = ir_was;
     hipEventDestroy(e0);
     hipEventDestroy(e1);
     ctx->profiling = was;
@@ -711,6 +822,40 @@ extern "C" int ee_pair_set(ee_ctx* ctx, int op, const int* cfg, int n)
     return EE_OK;
 }
 
+extern "C" int ee_ir_count(const ee_ctx* ctx)
+{
+    if (!ctx) return EE_ERR_ARG;
+    int n = 0;
+    for (const OpPlan& p : ctx->plans) n += p.ir;
+    return n;
+}
+
+extern "C" int ee_ir_mode(ee_ctx* ctx, int mode)
+{
+    if (!ctx || mode < 0 || mode > 2) return EE_ERR_ARG;
+    ctx->ir_mode = mode;
+    return EE_OK;
+}
+
+extern "C" int ee_ir_table(const ee_ctx* ctx, int op, int* cfg_out, int n)
+{
+    if (!ctx || op < 0 || op >= (int)ctx->plans.size() || n < 0 || (n > 0 && !cfg_out)) return EE_ERR_ARG;
+    const std::vector<int>& c = ctx->plans[op].ir_cfg;
+    for (int i = 0; i < n && i < (int)c.size(); ++i) cfg_out[i] = c[i];
+    return (int)c.size();
+}
+
+extern "C" int ee_ir_set(ee_ctx* ctx, int op, const int* cfg, int n)
+{
+    if (!ctx || op < 0 || op >= (int)ctx->plans.size() || n < 0 || n > 16 || (n > 0 && !cfg)) return EE_ERR_ARG;
+    OpPlan& p = ctx->plans[op];
+    if (!p.ir) return EE_ERR_ARG;
+    for (int i = 0; i < n; ++i)
+        if (cfg[i] != 0 && cfg[i] != 1) return EE_ERR_ARG;
+    p.ir_cfg.assign(cfg, cfg + n);
+    return EE_OK;
+}
+
 extern "C" int ee_pair_mode(ee_ctx* ctx, int mode)
 {
     if (!ctx || mode < 0 || mode > 2) return EE_ERR_ARG;
@@ -731,11 +876,13 @@ extern "C" int ee_pair_count(const ee_ctx* ctx)
 // ---- one backbone segment ------------------------------------------------------------------------
 int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool first_packed, int only_op, int cfg_force)
 {
+    const int only_block = only_op <= -2 ? -2 - only_op : -1;      // <= -2: just the three layers of the block headed by layer -2 - only_op
     gap_fused = false;
     const StageDesc& st = net.stages[stage];
     const int dt = net.dtype, es = net.elem_bytes();
     for (int k = 0; k < st.n_ops; ++k) {
         if (only_op >= 0 && st.first_op + k != only_op) continue;
+        if (only_block >= 0 && (st.first_op + k < only_block || st.first_op + k > only_block + 2)) continue;
         OpPlan& p = plans[st.first_op + k];
         const OpDesc& d = p.d;
         const void* src = resolve(this, p.src_buf, act_in, act_out);
@@ -748,6 +895,27 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
         const uint16_t* ys = p.dst_buf == BUF_EXT_OUT ? zc_out : nullptr;
         if ((xs || ys) && p.impl != IMPL_MFMA) return EE_ERR_UNSUPPORTED;
         if (zc_in && d.res >= 0 && p.res_buf == BUF_EXT_IN) return EE_ERR_UNSUPPORTED;
+        if (p.ir && ir_mode > 0 && cfg_force == 0 && forced_conv_tile() == 0 && only_op < 0 && !xs && !zc_out &&
+            !(gap_fuse_dst && st.first_op + k + 2 == gap_fuse_op[(size_t)stage])) {
+            // this layer, the depthwise layer and the projection as one launch, where the table says it is faster
+            const int ic = p.ir_cfg.empty() ? 0 : p.ir_cfg[std::min<size_t>(bucket_of(b), p.ir_cfg.size() - 1)];
+            if (ic != 0 || ir_mode == 2) {
+                const OpPlan& q1 = plans[st.first_op + k + 1];
+                const OpPlan& q2 = plans[st.first_op + k + 2];
+                IrArgs ia{};
+                fill_ir_args(st.first_op + k, b, ia);
+                ia.x = src;
+                ia.y = resolve(this, q2.dst_buf, act_in, act_out);
+                ia.res = q2.d.res >= 0 ? resolve(this, q2.res_buf, act_in, act_out) : nullptr;
+                const double mid = 2.0 * b * ((double)d.h_out * d.w_out * d.c_out + (double)q1.d.h_out * q1.d.w_out * q1.d.c_out);   // the tensors that stay on chip
+                e = timed(EE_K_CONV_MFMA, ops + (q1.ops_per_sample + q2.ops_per_sample) * b,
+                          bytes + (q1.bytes_per_sample + q2.bytes_per_sample) * b + q1.weight_bytes + q2.weight_bytes - mid,
+                          [&] { return launch_ir_block(ia, stream); }, st.first_op + k);
+                if (e != hipSuccess) return EE_ERR_DEVICE;
+                k += 2;                                                          // the next two layers are done
+                continue;
+            }
+        }
         if (p.impl == IMPL_MFMA || p.impl == IMPL_MFMA_C4 || p.impl == IMPL_MFMA_CPAD || p.impl == IMPL_MFMA_S2D) {
             if (p.impl == IMPL_MFMA_S2D && !(first_packed && k == 0)) {
                 const double pb = (double)b * ((double)d.h_in * d.w_in * d.c_in + (double)p.Hp * p.Wp * 16) * es;
@@ -1011,6 +1179,10 @@ extern "C" int ee_time_layer(ee_ctx* ctx, int layer, int b, int cfg, int reps, d
     for (size_t s = 0; s < ctx->net.stages.size(); ++s)
         if (layer >= ctx->net.stages[s].first_op && layer < ctx->net.stages[s].first_op + ctx->net.stages[s].n_ops) stage = (int)s;
     if (stage < 0) return EE_ERR_ARG;
+    const bool fused_block = cfg == EE_CFG_IR_BLOCK;               // the inverted-residual block headed by `layer` as one launch
+    if (fused_block && !ctx->plans[layer].ir) return EE_ERR_ARG;
+    const int ir_was = ctx->ir_mode;
+    if (fused_block) ctx->ir_mode = 2;
     const bool was = ctx->profiling;
     ctx->profiling = false;
     hipEvent_t e0, e1;
@@ -1019,7 +1191,9 @@ extern "C" int ee_time_layer(ee_ctx* ctx, int layer, int b, int cfg, int reps, d
     for (int pass = 0; pass < 2 && !rc; ++pass) {                   // pass 0 warms caches and code objects
         const int n = pass == 0 ? 2 : reps;
         hipEventRecord(e0, ctx->stream);
-        for (int r = 0; r < n && !rc; ++r) rc = ctx->run_stage(stage, b, ctx->in_buf[stage], ctx->out_buf[stage], false, layer, cfg);
+        for (int r = 0; r < n && !rc; ++r)
+            rc = fused_block ? ctx->run_stage(stage, b, ctx->in_buf[stage], ctx->out_buf[stage], false, -2 - layer)
+                             : ctx->run_stage(stage, b, ctx->in_buf[stage], ctx->out_buf[stage], false, layer, cfg);
         hipEventRecord(e1, ctx->stream);
         if (hipEventSynchronize(e1) != hipSuccess) rc = EE_ERR_DEVICE;
         float ms = 0.f;
@@ -1027,9 +1201,17 @@ extern "C" int ee_time_layer(ee_ctx* ctx, int layer, int b, int cfg, int reps, d
         *us_out = (double)ms * 1e3 / n;
     }
     (void)hipGetLastError();
+    ctx->ir_mode = ir_was;
     const OpPlan& p = ctx->plans[layer];
     if (ops_out) *ops_out = p.ops_per_sample * b;
     if (bytes_out) *bytes_out = p.bytes_per_sample * b + p.weight_bytes;
+    if (fused_block) {                                               // the three layers' work; the two tensors in between stay on chip
+        const OpPlan& q1 = ctx->plans[layer + 1];
+        const OpPlan& q2 = ctx->plans[layer + 2];
+        const double mid = 2.0 * b * ((double)p.d.h_out * p.d.w_out * p.d.c_out + (double)q1.d.h_out * q1.d.w_out * q1.d.c_out);
+        if (ops_out) *ops_out += (q1.ops_per_sample + q2.ops_per_sample) * b;
+        if (bytes_out) *bytes_out += (q1.bytes_per_sample + q2.bytes_per_sample) * b + q1.weight_bytes + q2.weight_bytes - mid;
+    }
     hipEventDestroy(e0);
     hipEventDestroy(e1);
     ctx->profiling = was;

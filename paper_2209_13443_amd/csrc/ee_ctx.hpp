@@ -25,6 +25,11 @@ struct OpPlan {
     std::vector<int> cfg;       // kernel configuration per batch bucket (see ee_autotune); empty = by shape
     bool pair = false;          // this layer and the next one (a 1x1 layer that alone reads it) can run as one fused launch
     std::vector<int> pair_cfg;  // per batch bucket: configuration of the fused launch, 0 = run the two layers separately; empty = not tuned
+    // this layer (a 1x1 expansion), the 3x3 depthwise layer behind it and the 1x1 projection behind that can run as one fused launch
+    bool ir = false;
+    std::vector<int> ir_cfg;    // per batch bucket: 1 = the fused launch, 0 = the three layers separately; empty = not tuned
+    void* ir_we = nullptr; void* ir_be = nullptr; void* ir_wd = nullptr; void* ir_bd = nullptr; void* ir_wp = nullptr; void* ir_bp = nullptr;
+    int ir_kx = 0, ir_ce32 = 0;
     double ops_per_sample = 0, bytes_per_sample = 0, weight_bytes = 0;
 };
 
@@ -93,6 +98,7 @@ struct ee_ctx {
     bool zero_copy_ok = false;                   // every segment boundary can be served that way (set by ee_create)
     int zc_slots = 0;                            // sample slots in every in_buf behind the first
     int pair_mode = 1;                           // fused layer pairs: 0 never, 1 as the table says, 2 wherever possible
+    int ir_mode = 1;                             // fused inverted-residual blocks: likewise
     // lanes of the stream driver: lanes[lane] is a copy of the per-lane members above while that lane is bound
     std::vector<ee::LaneState> lanes;
     int lane = 0;
@@ -117,7 +123,8 @@ struct ee_ctx {
 
     // internal entry points shared by the C ABI and the stream driver (no argument checks)
     // first_packed: the first layer's folded input copy already holds these samples (admission wrote it)
-    // only_op >= 0: just that layer (an index into plans; fused pairs run as separate layers then);
+    // only_op >= 0: just that layer (an index into plans; fused pairs run as separate layers then); only_op <= -2: just the
+    // inverted-residual block headed by layer -2 - only_op (one launch or three, as ir_mode and the table say);
     // cfg_force > 0: that kernel configuration for every matrix-core layer instead of the table's
     int run_stage(int stage, int b_act, const void* act_in, void* act_out, bool first_packed = false, int only_op = -1, int cfg_force = 0);
     // the plan of segment 0's first layer when that layer reads a folded copy admission can write directly, else null
@@ -134,6 +141,7 @@ struct ee_ctx {
     hipError_t launch_conv(int op, int b, const void* src, void* dst, const void* res, int cfg, const uint16_t* xs = nullptr, const uint16_t* ys = nullptr, int32_t* gap_sums = nullptr);
     // layers op and op + 1 as one fused launch: src feeds layer op, res and dst belong to layer op + 1
     hipError_t launch_pair(int op, int b, const void* src, void* dst, const void* res, int cfg);
+    void fill_ir_args(int op, int b, ee::IrArgs& a) const;      // the block headed by layer `op`; x, res and y are left to the caller
     void fill_conv_args(int op, int b, ee::ConvArgs& a) const;
     static int bucket_of(int b) { int k = 0; while ((1 << k) < b) ++k; return k; }     // smallest k with 2^k >= b
     // to_host: also write the outcomes to h_out and store ++seq to h_seq when they are all there

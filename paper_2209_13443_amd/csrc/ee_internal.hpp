@@ -91,6 +91,20 @@ struct PairArgs {
     float f_lo, f_hi;
 };
 
+// An inverted-residual block in one launch (kernels_ir.hip): 1x1 expansion -> 3x3 depthwise -> 1x1 projection (+ residual).
+// Weights and biases are packed for it when the context is created: expansion rows of Kx bytes (c_in padded with zeros
+// to a multiple of 32) for Ce32 channels (the expanded channels padded to a multiple of 32, padding rows zero), the
+// depthwise weights as ready matrix-instruction operands [Ce32 / 32][tap][lane][16] (diagonal matrices), projection rows
+// of Ce32 bytes for NCO * 32 output channels; be and bd include the rounding constants of their shifts.
+struct IrArgs {
+    const void* x; const void* res; void* y;
+    const void* we; const int* be;
+    const void* wd; const int* bd;
+    const void* wp; const int* bp;
+    int B, H, W, Cin, Kx, Ce32, Cout, Ho, Wo, stride, pad;
+    int sh_e, lo_e, hi_e, sh_d, lo_d, hi_d, sh_p, lo_p, hi_p, res_shift;
+};
+
 struct DirectConvArgs {   // one thread per output element; any shape (correctness fallback)
     const void* x; const void* w; const void* bias; const void* res; void* y;
     int M, H, W, Ci, Ho, Wo, Co, kh, kw, stride, pad, shift, res_shift, lo, hi;
@@ -126,6 +140,7 @@ bool conv_pair_supported(int es, int co2, int kh, int kw, int ci, int co3);
 bool conv_slab_supported(const ConvArgs& a, int es);
 template <int ES> hipError_t launch_conv_slab(const ConvArgs& a, int cfg, hipStream_t s);
 enum { EE_CFG_SLAB = 0x10000 };     // configuration words with this bit name the slab kernel
+enum { EE_CFG_IR_BLOCK = 0x20000 }; // ee_time_layer: the fused inverted-residual block headed by the layer
 // streaming kernel for large, thin int8 layers (es = element bytes); hipErrorInvalidValue for a layer it does not cover
 bool conv_stream_supported(const ConvArgs& a, int es);
 hipError_t launch_conv_stream(const ConvArgs& a, hipStream_t s);
@@ -149,6 +164,10 @@ hipError_t launch_space_to_depth(const void* x, void* y, const int32_t* gather, 
 // [rows][c_bytes] -> [rows][cp_bytes] (both multiples of 4), the tail of every row zero
 hipError_t launch_pad_channels(const void* x, void* y, long long rows, int c_bytes, int cp_bytes, hipStream_t s);
 hipError_t launch_depthwise(const PoolArgs& a, int dtype, hipStream_t s);
+// the fused inverted-residual block (int8); pointers may be null for ir_block_supported
+bool ir_block_supported(const IrArgs& a);
+int ir_block_out_blocks(int c_out);            // blocks of 32 output channels the kernel is instantiated with (weights are padded to it)
+hipError_t launch_ir_block(const IrArgs& a, hipStream_t s);
 hipError_t launch_maxpool(const PoolArgs& a, int dtype, hipStream_t s);
 hipError_t launch_avgpool(const PoolArgs& a, int dtype, hipStream_t s);
 

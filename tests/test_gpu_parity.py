@@ -121,6 +121,60 @@ def test_int8_3x3_window_layers_edge_shapes_and_values(torch, ee, orc, kind):
                 eng.close()
 
 
+IR_CASES = [  # h, w, c_in, expanded, c_out (per block), stride, blocks, samples
+    (9, 11, 16, 48, 16, 1, 2, 7), (8, 8, 24, 144, (24, 32), 1, 2, 7), (13, 8, 24, 144, 32, 2, 1, 7), (14, 14, 64, 208, 64, 1, 1, 5),
+    (7, 7, 160, 320, 160, 1, 1, 3), (16, 16, 16, 96, (24, 16), 2, 2, 7), (5, 6, 8, 48, (40, 16), 1, 2, 7), (7, 7, 96, 160, 128, 1, 1, 3),
+    (20, 18, 32, 64, 96, 1, 1, 3), (1, 1, 16, 32, 16, 1, 1, 2), (3, 2, 32, 96, (8, 16), 2, 2, 2), (28, 28, 32, 192, 32, 1, 1, 40),
+]
+
+
+@pytest.mark.parametrize("case", IR_CASES, ids=lambda c: "x".join(str(v) if isinstance(v, int) else "_".join(map(str, v)) for v in c))
+def test_fused_inverted_residual_blocks_equal_separate_layers_and_oracle(torch, ee, orc, case):
+    """Expansion -> depthwise -> projection (+ residual) as one launch: shapes around the kernel's pixel blocks (8, 14 and 7
+    columns), channel groups (expanded channels that are and are not multiples of 32), output blocks (8 .. 160 channels, partial
+    16-byte stores), strides, one- and two-block segments, extreme inputs; against the oracle and against the three
+    separate layers, bit for bit."""
+    h, w, ci, ce, co, stride, blocks, n = case
+    blob = W.inverted_residual_net(h, w, ci, ce, co, stride, seed=h * 7 + ce, blocks=blocks)
+    say(f"[case] inverted residual {h}x{w} {ci} -> {ce} -> {co} stride {stride}, {blocks} block(s), {n} samples")
+    r = np.random.default_rng(h * 100 + ce)
+    x = np.concatenate([np.full((1, h, w, ci), -128, np.int8), np.full((1, h, w, ci), 127, np.int8),
+                        r.integers(-128, 128, size=(max(n - 2, 1), h, w, ci), dtype=np.int8)])[:n]
+    eng = ee.Engine(blob, max(n, 2))
+    assert eng.ir_count() == blocks
+    for b in sorted({n, 1}, reverse=True):
+        ref = orc.stage_forward(blob, 0, x[:b])
+        for mode in (2, 0, 2):
+            eng.ir_mode(mode)
+            got = host(eng.stage_forward(0, dev(torch, x[:b]), ref.shape[1:]), ref)
+            assert np.array_equal(got, ref), f"mode {mode} b={b}: {np.count_nonzero(got != ref)} of {ref.size} differ, first at {np.argwhere(got != ref)[:3].tolist()}"
+    assert np.unique(ref).size > 8
+    eng.close()
+
+
+def test_fused_inverted_residual_blocks_in_a_network(torch, ee, orc):
+    """The MobileNetV2-style network with every block fused, with none fused and with the table ee_autotune writes: every
+    segment and head against the oracle."""
+    blob = W.load_net("mobilenetv2_small_i8")
+    eng = ee.Engine(blob, 8)
+    assert eng.ir_count() == 15                                            # every block with an expansion but the last (320 output channels)
+    x = W.input_pool(blob, 7)
+    for step, mode in enumerate((2, 0, 1)):
+        if step == 2:
+            eng.autotune(reps=2)
+            tabs = eng.tables()["ir"]
+            assert len(tabs) == 15 and all(set(v) <= {0, 1} for v in tabs.values())
+            eng.load_tables({"ir": tabs})
+        eng.ir_mode(mode)
+        act = x
+        for s in range(blob.n_stages):
+            ref = orc.stage_forward(blob, s, act)
+            got = host(eng.stage_forward(s, dev(torch, act), ref.shape[1:]), ref)
+            assert np.array_equal(got, ref), f"mode {mode} segment {s}: {np.count_nonzero(got != ref)} of {ref.size} differ"
+            act = ref
+    eng.close()
+
+
 def test_int8_thin_1x1_layers_bit_exact(torch, ee, orc):
     """1x1 layers with 4..32 input channels (the kernel that feeds one matrix instruction per 32 x 32 outputs straight
     from global memory): every channel count, output widths that are and are not multiples of 32, pixel counts that
