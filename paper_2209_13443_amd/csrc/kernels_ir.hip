@@ -44,23 +44,51 @@ __device__ __forceinline__ int ir_med3(int v, int lo, int hi)       // lo <= hi:
     return r;
 }
 
-// shift, clamp and pack 16 accumulators (register 4 q + e = channel 8 q + 4 hi + e of the lane's pixel) and exchange
-// between lanes l and l + 32, which hold channels {0-3, 8-11, 16-19, 24-27} and {4-7, 12-15, 20-23, 28-31} of one
-// pixel: afterwards lane l holds channels 0-15 and lane l + 32 channels 16-31, 4 per dword in order.
-__device__ __forceinline__ v4i_r ir_requant_pack(const v16i_r& acc, int shift, int lo, int hi)
+// Requantisation bounds on the unshifted accumulator: clamp(acc >> s, lo, hi) == clamp(acc, lo * 2^s, (hi + 1) * 2^s - 1) >> s
+// (the shift rounds down, so it is monotone); a bound outside int32 clamps nothing, which is then also right.
+struct IrClamp { int shift, lo, hi; };
+__device__ __forceinline__ IrClamp ir_clamp(int shift, int lo, int hi)
 {
-    unsigned d[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        int v[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = ir_med3(acc[4 * q + e] >> shift, lo, hi);
-        const unsigned l2 = __builtin_amdgcn_perm((unsigned)v[1], (unsigned)v[0], 0x0c0c0400u), h2 = __builtin_amdgcn_perm((unsigned)v[3], (unsigned)v[2], 0x0c0c0400u);
-        d[q] = __builtin_amdgcn_perm(h2, l2, 0x05040100u);
-    }
+    const long long l = (long long)lo << shift, h = (((long long)hi + 1) << shift) - 1;
+    return IrClamp{shift, (int)(l < -2147483648LL ? -2147483648LL : l), (int)(h > 2147483647LL ? 2147483647LL : h)};
+}
+
+// clamp, shift and pack 16 accumulators (register 4 q + e = channel 8 q + 4 hi + e of the lane's pixel): the shift writes
+// its low byte straight into byte e of the packed dword (sub-dword addressing), so a value costs two instructions.  Then
+// lanes l and l + 32, which hold channels {0-3, 8-11, 16-19, 24-27} and {4-7, 12-15, 20-23, 28-31} of one pixel, exchange
+// halves: afterwards lane l holds channels 0-15 and lane l + 32 channels 16-31, 4 per dword in order.
+__device__ __forceinline__ v4i_r ir_requant_pack(const v16i_r& acc, const IrClamp& c)
+{
+    unsigned d0, d1, d2, d3;
+    int t0, t1, t2, t3;
+    const int sh = c.shift, lo = c.lo, hi = c.hi;
+    // One block of instructions the compiler does not look into, so it keeps its own distances:
+    //   * the accumulators come straight out of a matrix instruction, whose result may be read 18 wait states after
+    //     it was issued at the earliest (the compiler spaces only instructions it knows): 20 wait states first;
+    //   * an instruction that writes part of a register must not be followed at once by one that reads the same
+    //     register: the four dwords (and the four temporaries that carry a clamped value to its shift) take turns.
+    // %0-%3 packed dwords, %4-%7 temporaries, %8-%23 accumulators, %24 shift, %25 / %26 bounds
+#define EE_IR_MED(t, a) "v_med3_i32 " t ", " a ", %25, %26\n\t"
+#define EE_IR_SHB(dst, src, sel, unused) "v_ashrrev_i32_sdwa " dst ", %24, " src " dst_sel:" sel " dst_unused:" unused " src0_sel:DWORD src1_sel:DWORD\n\t"
+#define EE_IR_ROUND(a0, a1, a2, a3, sel, unused) \
+    EE_IR_MED("%4", a0) EE_IR_MED("%5", a1) EE_IR_MED("%6", a2) EE_IR_MED("%7", a3) \
+    EE_IR_SHB("%0", "%4", sel, unused) EE_IR_SHB("%1", "%5", sel, unused) EE_IR_SHB("%2", "%6", sel, unused) EE_IR_SHB("%3", "%7", sel, unused)
+    asm("s_nop 15\n\ts_nop 3\n\t"
+        EE_IR_ROUND("%8", "%12", "%16", "%20", "BYTE_0", "UNUSED_PAD")
+        EE_IR_ROUND("%9", "%13", "%17", "%21", "BYTE_1", "UNUSED_PRESERVE")
+        EE_IR_ROUND("%10", "%14", "%18", "%22", "BYTE_2", "UNUSED_PRESERVE")
+        EE_IR_ROUND("%11", "%15", "%19", "%23", "BYTE_3", "UNUSED_PRESERVE")
+        "s_nop 1"
+        : "=&v"(d0), "=&v"(d1), "=&v"(d2), "=&v"(d3), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
+        : "v"(acc[0]), "v"(acc[1]), "v"(acc[2]), "v"(acc[3]), "v"(acc[4]), "v"(acc[5]), "v"(acc[6]), "v"(acc[7]),
+          "v"(acc[8]), "v"(acc[9]), "v"(acc[10]), "v"(acc[11]), "v"(acc[12]), "v"(acc[13]), "v"(acc[14]), "v"(acc[15]),
+          "v"(sh), "v"(lo), "v"(hi));
+#undef EE_IR_ROUND
+#undef EE_IR_SHB
+#undef EE_IR_MED
     // v_permlane32_swap(a, b): the upper 32 lanes of a change places with the lower 32 lanes of b
-    const auto s02 = __builtin_amdgcn_permlane32_swap(d[0], d[2], false, false);
-    const auto s13 = __builtin_amdgcn_permlane32_swap(d[1], d[3], false, false);
+    const auto s02 = __builtin_amdgcn_permlane32_swap(d0, d2, false, false);
+    const auto s13 = __builtin_amdgcn_permlane32_swap(d1, d3, false, false);
     return v4i_r{(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
 }
 
@@ -81,7 +109,7 @@ constexpr int IR_MAXCB = 3;                   // blocks of 32 staged pixels per 
 constexpr int IR_MAXK = 5;                    // reduction steps of 32 input channels: c_in <= 160 (template parameter MAXK: 1, 2 or 5)
 
 template <int STRIDE, int NCO, int MAXB, int MAXK>
-__global__ __launch_bounds__(256, (NCO == 1 && MAXK <= 2) ? 4 : 2) void ir_block_i8_kernel(IrArgs a, IrTile t)
+__global__ __launch_bounds__(256, (NCO == 1 && MAXK == 1) ? 4 : 2) void ir_block_i8_kernel(IrArgs a, IrTile t)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char ir_lds[];
     const int tid = threadIdx.x, lane = tid & 63, m = lane & 31, hi = lane >> 5;
@@ -97,6 +125,7 @@ __global__ __launch_bounds__(256, (NCO == 1 && MAXK <= 2) ? 4 : 2) void ir_block
     unsigned char* const l_e = l_x + t.x_bytes;
     const int e_row = t.iw * 32 + 16;                                   // bytes per row of expanded pixels
     const int kx32 = a.Kx >> 5;
+    const IrClamp cl_e = ir_clamp(a.sh_e, a.lo_e, a.hi_e), cl_d = ir_clamp(a.sh_d, a.lo_d, a.hi_d), cl_p = ir_clamp(a.sh_p, a.lo_p, a.hi_p);
 
     // ---- stage the input pixels under the tile; clear the expanded-pixel buffers; biases to LDS ----------------------------
     {
@@ -201,7 +230,7 @@ __global__ __launch_bounds__(256, (NCO == 1 && MAXK <= 2) ? 4 : 2) void ir_block
 #pragma unroll
                 for (int k = 0; k < MAXK; ++k)
                     if (k < kx32) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(we[k], *(const v4i_r*)(l_x + xoff[j] + k * 32), acc, 0, 0, 0);
-                const v4i_r out = ir_requant_pack(acc, a.sh_e, a.lo_e, a.hi_e);
+                const v4i_r out = ir_requant_pack(acc, cl_e);
                 if (eoff[j] >= 0) *(v4i_r*)(ebuf + eoff[j]) = out;
             }
     };
@@ -215,7 +244,7 @@ __global__ __launch_bounds__(256, (NCO == 1 && MAXK <= 2) ? 4 : 2) void ir_block
                 for (int r = 0; r < 3; ++r)
 #pragma unroll
                     for (int c = 0; c < 3; ++c) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wd[3 * r + c], *(const v4i_r*)(win + r * e_row + c * 32), acc, 0, 0, 0);
-                const v4i_r dq = ir_requant_pack(acc, a.sh_d, a.lo_d, a.hi_d);
+                const v4i_r dq = ir_requant_pack(acc, cl_d);
 #pragma unroll
                 for (int c = 0; c < NCO; ++c) accp[s][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wp[c], dq, accp[s][c], 0, 0, 0);
             }
@@ -267,7 +296,7 @@ __global__ __launch_bounds__(256, (NCO == 1 && MAXK <= 2) ? 4 : 2) void ir_block
 #pragma unroll
                         for (int e = 0; e < 4; ++e) acc[4 * q + e] += __builtin_amdgcn_sbfe((int)rq[q], 8 * e, 8) << a.res_shift;
                 }
-                const v4i_r out = ir_requant_pack(acc, a.sh_p, a.lo_p, a.hi_p);
+                const v4i_r out = ir_requant_pack(acc, cl_p);
                 if (px_ok) {
                     unsigned char* yp = (unsigned char*)a.y + pix + ch;
                     if (left >= 16) *(v4i_r*)yp = out;
