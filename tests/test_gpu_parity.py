@@ -617,7 +617,13 @@ def test_full_size_every_segment_element_by_element(torch, ee, orc, name, b_max)
     act, ref = dev(torch, pool), pool[slots]
     for s in range(blob.n_stages):
         say(f"[case] full-size {name} segment {s} at b={b_max}")
+        if eng.ir_count():                                 # every inverted-residual block fused, whatever the tuned table says
+            eng.ir_mode(2)
+            forced = eng.stage_forward(s, act, blob.stage_out_shape(s))
+            eng.ir_mode(1)
         act = eng.stage_forward(s, act, blob.stage_out_shape(s))
+        if eng.ir_count():
+            assert torch.equal(forced, act), f"{name} segment {s}: fused blocks differ from the tuned mix"
         ref = orc.stage_forward(blob, s, ref)
         got = act.cpu().numpy()[slots]
         assert np.array_equal(got, ref), f"{name} segment {s}: {np.count_nonzero(got != ref)} of {ref.size} differ"
