@@ -1181,12 +1181,12 @@ extern "C" int ee_time_layer(ee_ctx* ctx, int layer, int b, int cfg, int reps, d
     if (stage < 0) return EE_ERR_ARG;
     const bool fused_block = cfg == EE_CFG_IR_BLOCK;               // the inverted-residual block headed by `layer` as one launch
     if (fused_block && !ctx->plans[layer].ir) return EE_ERR_ARG;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return EE_ERR_DEVICE;
     const int ir_was = ctx->ir_mode;
     if (fused_block) ctx->ir_mode = 2;
     const bool was = ctx->profiling;
     ctx->profiling = false;
-    hipEvent_t e0, e1;
-    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return EE_ERR_DEVICE;
     int rc = EE_OK;
     for (int pass = 0; pass < 2 && !rc; ++pass) {                   // pass 0 warms caches and code objects
         const int n = pass == 0 ? 2 : reps;

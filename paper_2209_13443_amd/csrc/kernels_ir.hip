@@ -27,6 +27,11 @@
 //     The expansion of group g + 1 runs behind the depthwise + projection of group g without a barrier in between
 //     (other buffer); there is one workgroup barrier per group.
 //   * Epilogue: projection bias, residual, requantisation, 16-byte stores.
+// Small images (a tile is at most MAXB blocks and 96 staged pixels; few workgroups, many channel groups) run the second
+// form, GP: the four or eight wavefronts of a workgroup share the tile's *channel groups* instead of its pixels.  Each wavefront
+// expands, filters and projects every pixel of the tile for the groups g = wavefront, wavefront + 4 (or 8), ... through a buffer
+// of its own, with no barrier inside the loop; the partial projection sums are added in LDS (integer adds,
+// exact in any order) and the epilogue is shared out by (pixel block, output block).
 // Every accumulation is int32 and exact, rounding points are those of the three separate layers: results are equal
 // bit for bit.
 #include "ee_internal.hpp"
@@ -102,15 +107,18 @@ struct IrTile {
     int xp;                // bytes per staged input pixel
     int x_bytes, e_bytes;  // LDS: staged input, one buffer of expanded pixels
     int per_xcd, total;    // workgroups per XCD, workgroups with work
+    int gp;                // 4 or 8: that many wavefronts share the channel groups (small images), 0: four share the pixels
 };
 
 constexpr int IR_BATCH = 8, IR_BATCHES = 2;   // 8-byte loads per lane that stage a tile, in batches: ih * iw * cpp <= 4096
 constexpr int IR_MAXCB = 3;                   // blocks of 32 staged pixels per wavefront in the expansion: ih * iw <= 384
 constexpr int IR_MAXK = 5;                    // reduction steps of 32 input channels: c_in <= 160 (template parameter MAXK: 1, 2 or 5)
 
-template <int STRIDE, int NCO, int MAXB, int MAXK>
-__global__ __launch_bounds__(256, (NCO == 1 && MAXK == 1) ? 4 : 2) void ir_block_i8_kernel(IrArgs a, IrTile t)
+// GP = 0: four wavefronts share the pixels; GP = 4 or 8: that many wavefronts share the channel groups
+template <int STRIDE, int NCO, int MAXB, int MAXK, int GP>
+__global__ __launch_bounds__(GP ? 64 * GP : 256, (NCO == 1 && MAXK == 1 && !GP) ? 4 : 2) void ir_block_i8_kernel(IrArgs a, IrTile t)
 {
+    constexpr int NW = GP ? GP : 4, NT = 64 * NW;                      // wavefronts and lanes per workgroup
     extern __shared__ __attribute__((aligned(16))) unsigned char ir_lds[];
     const int tid = threadIdx.x, lane = tid & 63, m = lane & 31, hi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -135,12 +143,12 @@ __global__ __launch_bounds__(256, (NCO == 1 && MAXK == 1) ? 4 : 2) void ir_block
         unsigned dst[IR_BATCH];                                         // LDS byte offset, ~0u: nothing to write
 #pragma unroll
         for (int batch = 0; batch < IR_BATCHES; ++batch) {
-            if (batch > 0 && 256 * IR_BATCH * batch >= nchunks) break;  // wave-uniform
+            if (batch > 0 && NT * IR_BATCH * batch >= nchunks) break;   // wave-uniform
 #pragma unroll
             for (int i = 0; i < IR_BATCH; ++i) {
                 dst[i] = ~0u;
                 stage[i] = v2i_r{0, 0};
-                const int e0 = 256 * (batch * IR_BATCH + i);
+                const int e0 = NT * (batch * IR_BATCH + i);
                 if (e0 < nchunks) {                                     // wave-uniform
                     const int e = min(e0 + tid, nchunks - 1);
                     const int q = t.cpp == 1 ? e : (int)__umulhi((unsigned)e, t.magic_cpp), ch = e - q * t.cpp;   // 2^32 / 1 + 1 does not fit the magic number
@@ -153,8 +161,9 @@ __global__ __launch_bounds__(256, (NCO == 1 && MAXK == 1) ? 4 : 2) void ir_block
                 }
             }
             if (batch == 0) {
-                for (int o = tid * 16; o < 2 * t.e_bytes; o += 4096) *(v4i_r*)(l_e + o) = v4i_r{0, 0, 0, 0};
-                for (int o = tid * 16; o < 4 * a.Ce32; o += 4096) {
+                // the buffers of expanded pixels (two, or one per wavefront) and, behind them, the projection sums (GP)
+                for (int o = tid * 16; o < (GP ? NW * t.e_bytes + MAXB * NCO * 4096 : 2 * t.e_bytes); o += 16 * NT) *(v4i_r*)(l_e + o) = v4i_r{0, 0, 0, 0};
+                for (int o = tid * 16; o < 4 * a.Ce32; o += 16 * NT) {
                     *(v4i_r*)(l_be + o) = *(const v4i_r*)((const unsigned char*)a.be + o);
                     *(v4i_r*)(l_bd + o) = *(const v4i_r*)((const unsigned char*)a.bd + o);
                 }
@@ -172,7 +181,7 @@ __global__ __launch_bounds__(256, (NCO == 1 && MAXK == 1) ? 4 : 2) void ir_block
     int xoff[IR_MAXCB], eoff[IR_MAXCB];                                 // this lane's pixel in the wavefront's j-th block: byte offsets (eoff < 0: none)
 #pragma unroll
     for (int j = 0; j < IR_MAXCB; ++j) {
-        const int hp = (wave + 4 * j) * 32 + m, hpc = min(hp, max(npix - 1, 0));
+        const int hp = (GP ? j : wave + 4 * j) * 32 + m, hpc = min(hp, max(npix - 1, 0));
         const int ry = hpc / sw, rx = hpc - ry * sw;
         xoff[j] = ((y0 + ry) * t.iw + x0 + rx) * t.xp + 16 * hi;
         eoff[j] = hp < npix ? (y0 + ry) * e_row + (x0 + rx) * 32 + 16 * hi : -1;
@@ -185,7 +194,7 @@ __global__ __launch_bounds__(256, (NCO == 1 && MAXK == 1) ? 4 : 2) void ir_block
     int woff[MAXB];                                                     // window origin of the lane's pixel in the expanded-pixel buffer
 #pragma unroll
     for (int s = 0; s < MAXB; ++s) {
-        const int b = min(wave + 4 * s, nblocks - 1), by = b / t.pbw, bx = b - by * t.pbw;
+        const int b = min(GP ? s : wave + 4 * s, nblocks - 1), by = b / t.pbw, bx = b - by * t.pbw;
         woff[s] = (by * t.nbh + tyc) * STRIDE * e_row + (bx * t.nbw + txc) * STRIDE * 32 + 16 * hi;
     }
 
@@ -225,7 +234,7 @@ __global__ __launch_bounds__(256, (NCO == 1 && MAXK == 1) ? 4 : 2) void ir_block
     auto expand = [&](int g, unsigned char* ebuf) {
 #pragma unroll
         for (int j = 0; j < IR_MAXCB; ++j)
-            if (wave + 4 * j < ncb) {                                   // wave-uniform
+            if ((GP ? j : wave + 4 * j) < ncb) {                        // wave-uniform
                 v16i_r acc = bias16(l_be, g);
 #pragma unroll
                 for (int k = 0; k < MAXK; ++k)
@@ -237,7 +246,7 @@ __global__ __launch_bounds__(256, (NCO == 1 && MAXK == 1) ? 4 : 2) void ir_block
     auto dw_project = [&](int g, const unsigned char* ebuf) {
 #pragma unroll
         for (int s = 0; s < MAXB; ++s)
-            if (wave + 4 * s < nblocks) {                               // wave-uniform
+            if ((GP ? s : wave + 4 * s) < nblocks) {                    // wave-uniform
                 v16i_r acc = bias16(l_bd, g);
                 const unsigned char* win = ebuf + woff[s];
 #pragma unroll
@@ -251,33 +260,58 @@ __global__ __launch_bounds__(256, (NCO == 1 && MAXK == 1) ? 4 : 2) void ir_block
     };
 
     const int ngroups = a.Ce32 >> 5;
-    load_we(0);
-    __syncthreads();                                                    // staged pixels, cleared buffers and biases are in LDS
-    load_wd_wp(0);
-    expand(0, l_e);
-    for (int g = 0; g < ngroups; ++g) {
-        if (g + 1 < ngroups) load_we(g + 1);
-        __syncthreads();                                                // group g is expanded; nobody reads the other buffer any more
-        dw_project(g, l_e + (g & 1) * t.e_bytes);
-        if (g + 1 < ngroups) {
-            load_wd_wp(g + 1);
-            expand(g + 1, l_e + ((g + 1) & 1) * t.e_bytes);
+    int* const l_r = (int*)(l_e + NW * t.e_bytes);                       // GP: projection sums [block][output block][register][lane]
+    if constexpr (GP) {
+        unsigned char* const my_e = l_e + wave * t.e_bytes;
+        __syncthreads();                                                // staged pixels, cleared buffers and biases are in LDS
+        for (int g = wave; g < ngroups; g += NW) {
+            load_we(g);
+            load_wd_wp(g);
+            expand(g, my_e);
+            dw_project(g, my_e);                                        // same wavefront, same buffer: LDS keeps a wavefront's accesses in order
+        }
+#pragma unroll
+        for (int s = 0; s < MAXB; ++s)
+            if (s < nblocks)
+#pragma unroll
+                for (int c = 0; c < NCO; ++c)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) atomicAdd(l_r + ((s * NCO + c) * 16 + i) * 64 + lane, accp[s][c][i]);
+        __syncthreads();                                                // all four partial sums are in
+    } else {
+        load_we(0);
+        __syncthreads();                                                // staged pixels, cleared buffers and biases are in LDS
+        load_wd_wp(0);
+        expand(0, l_e);
+        for (int g = 0; g < ngroups; ++g) {
+            if (g + 1 < ngroups) load_we(g + 1);
+            __syncthreads();                                            // group g is expanded; nobody reads the other buffer any more
+            dw_project(g, l_e + (g & 1) * t.e_bytes);
+            if (g + 1 < ngroups) {
+                load_wd_wp(g + 1);
+                expand(g + 1, l_e + ((g + 1) & 1) * t.e_bytes);
+            }
         }
     }
 
     // ---- epilogue: bias, residual, requantisation, stores ------------------------------------------------------------------
 #pragma unroll
     for (int s = 0; s < MAXB; ++s)
-        if (wave + 4 * s < nblocks) {                                   // wave-uniform
-            const int b = wave + 4 * s, by = b / t.pbw, bx = b - by * t.pbw;
+        if ((GP ? s : wave + 4 * s) < nblocks) {                        // wave-uniform
+            const int b = GP ? s : wave + 4 * s, by = b / t.pbw, bx = b - by * t.pbw;
             const int oy = oy0 + by * t.nbh + tyc, ox = ox0 + bx * t.nbw + txc;
             const bool px_ok = lane_px && oy < a.Ho && ox < a.Wo;
             const unsigned pix = px_ok ? (unsigned)(((n * a.Ho + oy) * a.Wo + ox) * a.Cout) : 0u;      // < 2^31: checked by the launcher
 #pragma unroll
             for (int c = 0; c < NCO; ++c) {
+                if (GP && ((s * NCO + c) & (NW - 1)) != wave) continue; // wave-uniform: the (pixel block, output block) pairs take turns
                 const int ch = 32 * c + 16 * hi;                        // first of the 16 channels this lane stores
                 const int left = a.Cout - ch;                           // channels from there on (a multiple of 8)
                 v16i_r acc = accp[s][c];
+                if constexpr (GP) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[i] = l_r[((s * NCO + c) * 16 + i) * 64 + lane];
+                }
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const v4i_r b4 = *(const v4i_r*)(a.bp + 32 * c + 8 * q + 4 * hi);      // padded to whole blocks of 32, rounding constant included
@@ -358,6 +392,11 @@ bool ir_block_plan(const IrArgs& a, IrTile& t, int& nco, int& maxb)
     if (total > 0x3fffffff) return false;
     t.total = (int)total;
     t.per_xcd = (t.total + 7) / 8;
+    // small images: the wavefronts share the channel groups (instantiated for 2 or more output blocks and 2 or more reduction steps)
+    const int nw = a.Ce32 >= 320 ? 8 : 4;                               // ten or more groups: eight wavefronts
+    t.gp = nco >= 2 && a.Kx >= 64 && a.Ce32 >= 128 && t.pbw * t.pbh <= maxb && t.ih * t.iw <= 32 * IR_MAXCB && total <= 2048 &&
+                   t.ih * t.iw * t.cpp <= 64 * nw * IR_BATCH * IR_BATCHES && 8 * a.Ce32 + t.x_bytes + nw * t.e_bytes + maxb * nco * 4096 <= 64 * 1024
+               ? nw : 0;
     return true;
 }
 
@@ -368,19 +407,31 @@ bool ir_block_supported(const IrArgs& a)
     return ir_block_plan(a, t, nco, maxb);
 }
 
-template <int STRIDE, int NCO, int MAXB, int MAXK>
-static void ir_launch4(const IrArgs& a, const IrTile& t, size_t lds, hipStream_t s)
+template <int STRIDE, int NCO, int MAXB, int MAXK, int GP>
+static void ir_launch5(const IrArgs& a, const IrTile& t, size_t lds, hipStream_t s)
 {
-    EE_LAUNCH((ir_block_i8_kernel<STRIDE, NCO, MAXB, MAXK>), dim3((unsigned)(t.per_xcd * 8)), dim3(256), lds, s, a, t);
+    EE_LAUNCH((ir_block_i8_kernel<STRIDE, NCO, MAXB, MAXK, GP>), dim3((unsigned)(t.per_xcd * 8)), dim3(GP ? 64 * GP : 256), lds, s, a, t);
 }
 
 template <int STRIDE, int NCO, int MAXB>
 static void ir_launch(const IrArgs& a, const IrTile& t, size_t lds, hipStream_t s)
 {
     const int kx32 = a.Kx >> 5;                                         // registers for the expansion weights: 1, 2 or 5 steps
-    if (kx32 <= 1) ir_launch4<STRIDE, NCO, MAXB, 1>(a, t, lds, s);
-    else if (kx32 <= 2) ir_launch4<STRIDE, NCO, MAXB, 2>(a, t, lds, s);
-    else ir_launch4<STRIDE, NCO, MAXB, IR_MAXK>(a, t, lds, s);
+    if constexpr (NCO >= 2) {
+        if (t.gp == 4) {
+            if (kx32 <= 2) ir_launch5<STRIDE, NCO, MAXB, 2, 4>(a, t, lds, s);
+            else ir_launch5<STRIDE, NCO, MAXB, IR_MAXK, 4>(a, t, lds, s);
+            return;
+        }
+        if (t.gp == 8) {
+            if (kx32 <= 2) ir_launch5<STRIDE, NCO, MAXB, 2, 8>(a, t, lds, s);
+            else ir_launch5<STRIDE, NCO, MAXB, IR_MAXK, 8>(a, t, lds, s);
+            return;
+        }
+    }
+    if (kx32 <= 1) ir_launch5<STRIDE, NCO, MAXB, 1, 0>(a, t, lds, s);
+    else if (kx32 <= 2) ir_launch5<STRIDE, NCO, MAXB, 2, 0>(a, t, lds, s);
+    else ir_launch5<STRIDE, NCO, MAXB, IR_MAXK, 0>(a, t, lds, s);
 }
 
 hipError_t launch_ir_block(const IrArgs& a, hipStream_t s)
@@ -388,7 +439,7 @@ hipError_t launch_ir_block(const IrArgs& a, hipStream_t s)
     IrTile t;
     int nco, maxb;
     if (!ir_block_plan(a, t, nco, maxb)) return hipErrorInvalidValue;
-    const size_t lds = (size_t)8 * a.Ce32 + t.x_bytes + 2 * (size_t)t.e_bytes;
+    const size_t lds = (size_t)8 * a.Ce32 + t.x_bytes + (t.gp ? t.gp * (size_t)t.e_bytes + (size_t)maxb * nco * 4096 : 2 * (size_t)t.e_bytes);
     const int v = (a.stride - 1) * 4 + (nco == 1 ? 0 : nco == 2 ? 1 : nco == 3 ? 2 : 3);
     switch (v) {
     case 0: ir_launch<1, 1, 2>(a, t, lds, s); break;
