@@ -107,12 +107,13 @@ def layer_table(args, ee, W, blob, dtype):
                 continue                                          # the layer heads no block
             if r is None:
                 continue
-            sep = sum(x["us"] for x in rows if x["layer"] in (i, i + 1, i + 2))
+            span = 2 if int(blob.ops[i]["kind"]) == W.OP_DWCONV else 3      # a block without expansion is depthwise + projection
+            sep = sum(x["us"] for x in rows if i <= x["layer"] < i + span)
             tab = eng.ir_table(i)
-            blocks.append(dict(head=i, fused_us=round(r[0], 2), separate_us=round(sep, 2), gbps=round(r[2] / r[0] / 1e3, 1), tops=round(r[1] / r[0] / 1e6, 1),
+            blocks.append(dict(head=i, layers=span, fused_us=round(r[0], 2), separate_us=round(sep, 2), gbps=round(r[2] / r[0] / 1e3, 1), tops=round(r[1] / r[0] / 1e6, 1),
                                table=tab[min(len(tab) - 1, max(0, (B - 1).bit_length()))] if tab else None))
-            print("block at op%3d: fused %8.2f us (%6.1f T/s %7.1f GB/s), three layers %8.2f us, table says %s" % (
-                i, r[0], blocks[-1]["tops"], blocks[-1]["gbps"], sep, blocks[-1]["table"]), file=sys.stderr, flush=True)
+            print("block at op%3d: fused %8.2f us (%6.1f T/s %7.1f GB/s), its %d layers %8.2f us, table says %s" % (
+                i, r[0], blocks[-1]["tops"], blocks[-1]["gbps"], span, sep, blocks[-1]["table"]), file=sys.stderr, flush=True)
     conv = [r for r in rows if r["kind"] == W.OP_CONV]
     tot_us = sum(r["us"] for r in rows)
     conv_us = sum(r["us"] for r in conv)

@@ -190,7 +190,7 @@ int ee_measure_lut(ee_ctx* ctx, int reps, int64_t* lut_ns);
  * after two warm-up launches; *us_out = mean microseconds per launch (host), *ops_out = 2 * MACs and *bytes_out = the
  * algorithmic HBM bytes of one launch (may be NULL).  cfg = 0 uses the layer's table entry, else that kernel
  * configuration (as in ee_config_set); cfg = 0x20000 times the fused inverted-residual block headed by `layer` (its
- * three layers' operations and bytes; EE_ERR_ARG when the layer heads none).  Synchronous; overwrites workspace
+ * layers' operations and bytes; EE_ERR_ARG when the layer heads none).  Synchronous; overwrites workspace
  * activations.  EE_ERR_DEVICE when the configuration does not exist for this layer. */
 int ee_time_layer(ee_ctx* ctx, int layer, int b, int cfg, int reps, double* us_out, double* ops_out, double* bytes_out);
 
@@ -259,7 +259,9 @@ int ee_pair_set(ee_ctx* ctx, int layer, const int* cfg, int n);
  * layer with padding 1 that alone reads it and the 1x1 stride-1 convolution (the projection, with or without residual) that
  * alone reads that can run as ONE launch in which the expanded tensor exists only in LDS, 32 channels at a time; results
  * are those of the three separate kernels, bit for bit.  Covered: input channels a multiple of 8 up to 160, output
- * channels a multiple of 8 up to 160, depthwise stride 1 or 2.  ee_ir_count: how many layers of the network head such a
+ * channels a multiple of 8 up to 160, depthwise stride 1 or 2.  A 3x3 depthwise layer that no such block covers and the 1x1
+ * convolution that alone reads it are fused the same way (a block without expansion, headed by the depthwise layer; its
+ * channels a multiple of 16).  ee_ir_count: how many layers of the network head such a
  * block.  ee_ir_mode: 0 = never fuse, 1 = as the table says (default; nothing is fused until ee_autotune has timed the
  * fused launch against the three tuned layers per batch bucket, or a table was loaded), 2 = fuse every block.
  * ee_ir_table / ee_ir_set: the table of the block headed by `layer`, one entry per batch bucket, 1 = fused, 0 = separate

@@ -155,11 +155,73 @@ int pack_op(ee_ctx* ctx, const unsigned char* blob, OpPlan& p)
     return rc;
 }
 
+std::vector<unsigned char> ir_rounded_bias(const unsigned char* blob, const OpDesc& d, int n, int n_pad)
+{
+    std::vector<unsigned char> out(4 * (size_t)n_pad, 0);
+    for (int o = 0; o < n; ++o) {
+        int32_t v;
+        std::memcpy(&v, blob + d.b_off + 4 * (size_t)o, 4);
+        if (d.shift > 0) v += 1 << (d.shift - 1);
+        std::memcpy(&out[4 * (size_t)o], &v, 4);
+    }
+    return out;
+}
+
+// depthwise weights [C][3][3] as ready matrix-instruction operands [group][tap][lane][16]: row m = lane % 32 of diag(w) lies
+// in the lane whose 16 reduction bytes hold byte m
+std::vector<unsigned char> ir_diag_operands(const unsigned char* w, int C, int C32)
+{
+    std::vector<unsigned char> wd((size_t)(C32 / 32) * 9 * 64 * 16, 0);
+    for (int c = 0; c < C; ++c)
+        for (int t = 0; t < 9; ++t) {
+            const int g = c / 32, m = c % 32, lane = m + 32 * (m / 16);
+            wd[(((size_t)g * 9 + t) * 64 + lane) * 16 + m % 16] = w[(size_t)c * 9 + t];
+        }
+    return wd;
+}
+
+// A depthwise 3x3 layer that no fused block in front of it covers, followed by the 1x1 convolution that alone reads it:
+// the fused kernel without its expansion (two layers in one launch).
+int pack_ir_noexp(ee_ctx* ctx, const unsigned char* blob, const StageDesc& st, int k)
+{
+    OpPlan& p = ctx->plans[st.first_op + k];
+    if (k + 1 >= st.n_ops || (k >= 1 && ctx->plans[st.first_op + k - 1].ir && !ctx->plans[st.first_op + k - 1].ir_noexp)) return EE_OK;
+    const OpDesc& dw = p.d;
+    const OpDesc& pr = ctx->plans[st.first_op + k + 1].d;
+    if (pr.kind != OP_CONV || dw.kh != 3 || dw.kw != 3 || dw.pad != 1 || dw.pad_w != 1 || dw.c_tot != dw.c_out) return EE_OK;
+    if (pr.kh != 1 || pr.kw != 1 || pr.stride != 1 || pr.pad != 0 || pr.pad_w != 0 || pr.src != dw.dst || pr.c_tot != pr.c_out) return EE_OK;
+    if (dw.dst == st.out_tensor || pr.res == dw.dst) return EE_OK;
+    int readers = 0;
+    for (int j = 0; j < st.n_ops; ++j) {
+        const OpDesc& o = ctx->plans[st.first_op + j].d;
+        readers += (o.src == dw.dst) + (o.res == dw.dst);
+    }
+    if (readers != 1) return EE_OK;
+    const int C = dw.c_in, C32 = round_up(C, 32), Co = pr.c_out, Co32 = 32 * ir_block_out_blocks(Co);
+    IrArgs probe{};
+    probe.B = ctx->b_max; probe.H = dw.h_in; probe.W = dw.w_in; probe.Cin = C; probe.Kx = 0; probe.Ce32 = C32; probe.Cout = Co;
+    probe.Ho = dw.h_out; probe.Wo = dw.w_out; probe.stride = dw.stride; probe.pad = dw.pad;
+    if (!ir_block_supported(probe)) return EE_OK;
+    std::vector<unsigned char> wp((size_t)Co32 * C32, 0);
+    for (int o = 0; o < Co; ++o) std::memcpy(&wp[(size_t)o * C32], blob + pr.w_off + (size_t)o * C, (size_t)C);
+    int rc = upload(ctx, &p.ir_wd, ir_diag_operands(blob + dw.w_off, C, C32));
+    if (!rc) rc = upload(ctx, &p.ir_bd, ir_rounded_bias(blob, dw, C, C32));
+    if (!rc) rc = upload(ctx, &p.ir_wp, wp);
+    if (!rc) rc = upload(ctx, &p.ir_bp, ir_rounded_bias(blob, pr, Co, Co32));
+    if (rc) return rc;
+    p.ir_kx = 0; p.ir_ce32 = C32;
+    p.ir = true;
+    p.ir_noexp = true;
+    return EE_OK;
+}
+
 // Marks layer k of the segment as the head of an inverted-residual block when the fused kernel covers it and packs the
 // block's weights for that kernel (see IrArgs).
 int pack_ir(ee_ctx* ctx, const unsigned char* blob, const StageDesc& st, int k)
 {
     OpPlan& p = ctx->plans[st.first_op + k];
+    if (p.d.kind == OP_DWCONV) return pack_ir_noexp(ctx, blob, st, k);
+    if (k + 2 >= st.n_ops) return EE_OK;
     const OpDesc& e = p.d;
     const OpDesc& dw = ctx->plans[st.first_op + k + 1].d;
     const OpDesc& pr = ctx->plans[st.first_op + k + 2].d;
@@ -181,30 +243,15 @@ int pack_ir(ee_ctx* ctx, const unsigned char* blob, const StageDesc& st, int k)
     probe.Ho = dw.h_out; probe.Wo = dw.w_out; probe.stride = dw.stride; probe.pad = dw.pad;
     probe.B = ctx->b_max;
     if (!ir_block_supported(probe)) return EE_OK;
-    auto rounded_bias = [&](const OpDesc& d, int n, int n_pad) {
-        std::vector<unsigned char> out(4 * (size_t)n_pad, 0);
-        for (int o = 0; o < n; ++o) {
-            int32_t v;
-            std::memcpy(&v, blob + d.b_off + 4 * (size_t)o, 4);
-            if (d.shift > 0) v += 1 << (d.shift - 1);
-            std::memcpy(&out[4 * (size_t)o], &v, 4);
-        }
-        return out;
-    };
-    std::vector<unsigned char> we((size_t)Ce32 * Kx, 0), wd((size_t)(Ce32 / 32) * 9 * 64 * 16, 0), wp((size_t)Co32 * Ce32, 0);
+    std::vector<unsigned char> we((size_t)Ce32 * Kx, 0), wp((size_t)Co32 * Ce32, 0);
     for (int c = 0; c < Ce; ++c) std::memcpy(&we[(size_t)c * Kx], blob + e.w_off + (size_t)c * Ci, (size_t)Ci);
-    for (int c = 0; c < Ce; ++c)                                        // [group][tap][lane][16]: row m = lane % 32 of diag(w) lies in the lane whose 16 reduction bytes hold byte m
-        for (int t = 0; t < 9; ++t) {
-            const int g = c / 32, m = c % 32, lane = m + 32 * (m / 16);
-            wd[(((size_t)g * 9 + t) * 64 + lane) * 16 + m % 16] = blob[dw.w_off + (size_t)c * 9 + t];
-        }
     for (int o = 0; o < Co; ++o) std::memcpy(&wp[(size_t)o * Ce32], blob + pr.w_off + (size_t)o * Ce, (size_t)Ce);
     int rc = upload(ctx, &p.ir_we, we);
-    if (!rc) rc = upload(ctx, &p.ir_be, rounded_bias(e, Ce, Ce32));
-    if (!rc) rc = upload(ctx, &p.ir_wd, wd);
-    if (!rc) rc = upload(ctx, &p.ir_bd, rounded_bias(dw, Ce, Ce32));
+    if (!rc) rc = upload(ctx, &p.ir_be, ir_rounded_bias(blob, e, Ce, Ce32));
+    if (!rc) rc = upload(ctx, &p.ir_wd, ir_diag_operands(blob + dw.w_off, Ce, Ce32));
+    if (!rc) rc = upload(ctx, &p.ir_bd, ir_rounded_bias(blob, dw, Ce, Ce32));
     if (!rc) rc = upload(ctx, &p.ir_wp, wp);
-    if (!rc) rc = upload(ctx, &p.ir_bp, rounded_bias(pr, Co, Co32));
+    if (!rc) rc = upload(ctx, &p.ir_bp, ir_rounded_bias(blob, pr, Co, Co32));
     if (rc) return rc;
     p.ir_kx = Kx; p.ir_ce32 = Ce32;
     p.ir = true;
@@ -226,7 +273,8 @@ void plan_buffers(ee_ctx* ctx)
             // output, so the input's buffer must stay reserved over both
             if (k > 0 && ctx->plans[st.first_op + k - 1].pair) last_use[ctx->plans[st.first_op + k - 1].d.src] = k;
             // likewise the head of a fused inverted-residual block, over its three layers
-            if (k > 1 && ctx->plans[st.first_op + k - 2].ir) last_use[ctx->plans[st.first_op + k - 2].d.src] = k;
+            if (k > 1 && ctx->plans[st.first_op + k - 2].ir && !ctx->plans[st.first_op + k - 2].ir_noexp) last_use[ctx->plans[st.first_op + k - 2].d.src] = k;
+            if (k > 0 && ctx->plans[st.first_op + k - 1].ir_noexp) last_use[ctx->plans[st.first_op + k - 1].d.src] = k;
         }
         buf[0] = BUF_EXT_IN;
         buf[st.out_tensor] = BUF_EXT_OUT;
@@ -411,7 +459,7 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
     // it, a 1x1 stride-1 convolution (with or without residual); none of the three writes a channel slice
     if (es == 1)
         for (const StageDesc& st : ctx->net.stages)
-            for (int k = 0; k + 2 < st.n_ops; ++k) {
+            for (int k = 0; k + 1 < st.n_ops; ++k) {
                 if ((rc = pack_ir(ctx, (const unsigned char*)blob, st, k))) return fail(rc);
             }
     plan_buffers(ctx);
@@ -610,9 +658,9 @@ hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const 
 void ee_ctx::fill_ir_args(int op, int b, IrArgs& a) const
 {
     const OpPlan& p = plans[(size_t)op];
-    const OpDesc& e = p.d;
-    const OpDesc& dw = plans[(size_t)op + 1].d;
-    const OpDesc& pr = plans[(size_t)op + 2].d;
+    const OpDesc& e = p.d;                                              // without expansion: the depthwise layer itself
+    const OpDesc& dw = plans[(size_t)op + (p.ir_noexp ? 0 : 1)].d;
+    const OpDesc& pr = plans[(size_t)op + (p.ir_noexp ? 1 : 2)].d;
     a.we = p.ir_we; a.be = (const int*)p.ir_be; a.wd = p.ir_wd; a.bd = (const int*)p.ir_bd; a.wp = p.ir_wp; a.bp = (const int*)p.ir_bp;
     a.B = b; a.H = e.h_in; a.W = e.w_in; a.Cin = e.c_in; a.Kx = p.ir_kx; a.Ce32 = p.ir_ce32; a.Cout = pr.c_out;
     a.Ho = dw.h_out; a.Wo = dw.w_out; a.stride = dw.stride; a.pad = dw.pad;
@@ -729,7 +777,7 @@ extern "C" int ee_autotune(ee_ctx* ctx, int reps)
     const int ir_was = ctx->ir_mode;
     for (size_t s = 0; s < ctx->net.stages.size() && !rc; ++s) {
         const StageDesc& st = ctx->net.stages[s];
-        for (int k = 0; k + 2 < st.n_ops && !rc; ++k) {
+        for (int k = 0; k + 1 < st.n_ops && !rc; ++k) {
             OpPlan& p = ctx->plans[st.first_op + k];
             if (!p.ir) continue;
             std::vector<int> best(buckets.size(), 0);
@@ -882,7 +930,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
     const int dt = net.dtype, es = net.elem_bytes();
     for (int k = 0; k < st.n_ops; ++k) {
         if (only_op >= 0 && st.first_op + k != only_op) continue;
-        if (only_block >= 0 && (st.first_op + k < only_block || st.first_op + k > only_block + 2)) continue;
+        if (only_block >= 0 && (st.first_op + k < only_block || st.first_op + k > only_block + (plans[(size_t)only_block].ir_noexp ? 1 : 2))) continue;
         OpPlan& p = plans[st.first_op + k];
         const OpDesc& d = p.d;
         const void* src = resolve(this, p.src_buf, act_in, act_out);
@@ -895,24 +943,28 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
         const uint16_t* ys = p.dst_buf == BUF_EXT_OUT ? zc_out : nullptr;
         if ((xs || ys) && p.impl != IMPL_MFMA) return EE_ERR_UNSUPPORTED;
         if (zc_in && d.res >= 0 && p.res_buf == BUF_EXT_IN) return EE_ERR_UNSUPPORTED;
+        const int ir_last = p.ir_noexp ? 1 : 2;                             // the block's last layer, counted from this one
         if (p.ir && ir_mode > 0 && cfg_force == 0 && forced_conv_tile() == 0 && only_op < 0 && !xs && !zc_out &&
-            !(gap_fuse_dst && st.first_op + k + 2 == gap_fuse_op[(size_t)stage])) {
+            !(gap_fuse_dst && st.first_op + k + ir_last == gap_fuse_op[(size_t)stage])) {
             // this layer, the depthwise layer and the projection as one launch, where the table says it is faster
             const int ic = p.ir_cfg.empty() ? 0 : p.ir_cfg[std::min<size_t>(bucket_of(b), p.ir_cfg.size() - 1)];
             if (ic != 0 || ir_mode == 2) {
-                const OpPlan& q1 = plans[st.first_op + k + 1];
-                const OpPlan& q2 = plans[st.first_op + k + 2];
+                const OpPlan& q2 = plans[st.first_op + k + ir_last];
                 IrArgs ia{};
                 fill_ir_args(st.first_op + k, b, ia);
                 ia.x = src;
                 ia.y = resolve(this, q2.dst_buf, act_in, act_out);
                 ia.res = q2.d.res >= 0 ? resolve(this, q2.res_buf, act_in, act_out) : nullptr;
-                const double mid = 2.0 * b * ((double)d.h_out * d.w_out * d.c_out + (double)q1.d.h_out * q1.d.w_out * q1.d.c_out);   // the tensors that stay on chip
-                e = timed(EE_K_CONV_MFMA, ops + (q1.ops_per_sample + q2.ops_per_sample) * b,
-                          bytes + (q1.bytes_per_sample + q2.bytes_per_sample) * b + q1.weight_bytes + q2.weight_bytes - mid,
-                          [&] { return launch_ir_block(ia, stream); }, st.first_op + k);
+                double f_ops = ops, f_bytes = bytes;                             // the block's layers; the tensors between them stay on chip
+                for (int j = 1; j <= ir_last; ++j) {
+                    const OpPlan& q = plans[st.first_op + k + j];
+                    const OpDesc& prev = plans[st.first_op + k + j - 1].d;
+                    f_ops += q.ops_per_sample * b;
+                    f_bytes += q.bytes_per_sample * b + q.weight_bytes - 2.0 * b * (double)prev.h_out * prev.w_out * prev.c_out;
+                }
+                e = timed(EE_K_CONV_MFMA, f_ops, f_bytes, [&] { return launch_ir_block(ia, stream); }, st.first_op + k);
                 if (e != hipSuccess) return EE_ERR_DEVICE;
-                k += 2;                                                          // the next two layers are done
+                k += ir_last;                                                    // the block's other layers are done
                 continue;
             }
         }
@@ -1205,13 +1257,13 @@ extern "C" int ee_time_layer(ee_ctx* ctx, int layer, int b, int cfg, int reps, d
     const OpPlan& p = ctx->plans[layer];
     if (ops_out) *ops_out = p.ops_per_sample * b;
     if (bytes_out) *bytes_out = p.bytes_per_sample * b + p.weight_bytes;
-    if (fused_block) {                                               // the three layers' work; the two tensors in between stay on chip
-        const OpPlan& q1 = ctx->plans[layer + 1];
-        const OpPlan& q2 = ctx->plans[layer + 2];
-        const double mid = 2.0 * b * ((double)p.d.h_out * p.d.w_out * p.d.c_out + (double)q1.d.h_out * q1.d.w_out * q1.d.c_out);
-        if (ops_out) *ops_out += (q1.ops_per_sample + q2.ops_per_sample) * b;
-        if (bytes_out) *bytes_out += (q1.bytes_per_sample + q2.bytes_per_sample) * b + q1.weight_bytes + q2.weight_bytes - mid;
-    }
+    if (fused_block)                                                 // the block's layers; the tensors between them stay on chip
+        for (int j = 1; j <= (p.ir_noexp ? 1 : 2); ++j) {
+            const OpPlan& q = ctx->plans[layer + j];
+            const OpDesc& prev = ctx->plans[layer + j - 1].d;
+            if (ops_out) *ops_out += q.ops_per_sample * b;
+            if (bytes_out) *bytes_out += q.bytes_per_sample * b + q.weight_bytes - 2.0 * b * (double)prev.h_out * prev.w_out * prev.c_out;
+        }
     hipEventDestroy(e0);
     hipEventDestroy(e1);
     ctx->profiling = was;

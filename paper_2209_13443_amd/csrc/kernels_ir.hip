@@ -112,13 +112,17 @@ struct IrTile {
 
 constexpr int IR_BATCH = 8, IR_BATCHES = 2;   // 8-byte loads per lane that stage a tile, in batches: ih * iw * cpp <= 4096
 constexpr int IR_MAXCB = 3;                   // blocks of 32 staged pixels per wavefront in the expansion: ih * iw <= 384
+constexpr int IR_FILL = 4;                    // 16-byte loads per lane that fill a buffer without expansion: ih * iw * 2 <= 1024
 constexpr int IR_MAXK = 5;                    // reduction steps of 32 input channels: c_in <= 160 (template parameter MAXK: 1, 2 or 5)
 
-// GP = 0: four wavefronts share the pixels; GP = 4 or 8: that many wavefronts share the channel groups
+// GP = 0: four wavefronts share the pixels; GP = 4 or 8: that many wavefronts share the channel groups.
+// MAXK = 0: a block without expansion (depthwise -> projection): the buffers of "expanded" pixels are filled with the
+// block's input itself, 32 channels at a time.
 template <int STRIDE, int NCO, int MAXB, int MAXK, int GP>
-__global__ __launch_bounds__(GP ? 64 * GP : 256, (NCO == 1 && MAXK == 1 && !GP) ? 4 : 2) void ir_block_i8_kernel(IrArgs a, IrTile t)
+__global__ __launch_bounds__(GP ? 64 * GP : 256, (NCO == 1 && !GP && MAXK <= 1) ? (MAXK == 1 ? 4 : 3) : 2) void ir_block_i8_kernel(IrArgs a, IrTile t)
 {
     constexpr int NW = GP ? GP : 4, NT = 64 * NW;                      // wavefronts and lanes per workgroup
+    constexpr bool EXP = MAXK > 0;
     extern __shared__ __attribute__((aligned(16))) unsigned char ir_lds[];
     const int tid = threadIdx.x, lane = tid & 63, m = lane & 31, hi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -138,7 +142,7 @@ __global__ __launch_bounds__(GP ? 64 * GP : 256, (NCO == 1 && MAXK == 1 && !GP) 
     // ---- stage the input pixels under the tile; clear the expanded-pixel buffers; biases to LDS ----------------------------
     {
         const unsigned char* x = (const unsigned char*)a.x + (size_t)n * a.H * a.W * a.Cin;
-        const int nchunks = t.ih * t.iw * t.cpp;
+        const int nchunks = EXP ? t.ih * t.iw * t.cpp : 0;
         v2i_r stage[IR_BATCH];
         unsigned dst[IR_BATCH];                                         // LDS byte offset, ~0u: nothing to write
 #pragma unroll
@@ -164,7 +168,7 @@ __global__ __launch_bounds__(GP ? 64 * GP : 256, (NCO == 1 && MAXK == 1 && !GP) 
                 // the buffers of expanded pixels (two, or one per wavefront) and, behind them, the projection sums (GP)
                 for (int o = tid * 16; o < (GP ? NW * t.e_bytes + MAXB * NCO * 4096 : 2 * t.e_bytes); o += 16 * NT) *(v4i_r*)(l_e + o) = v4i_r{0, 0, 0, 0};
                 for (int o = tid * 16; o < 4 * a.Ce32; o += 16 * NT) {
-                    *(v4i_r*)(l_be + o) = *(const v4i_r*)((const unsigned char*)a.be + o);
+                    if constexpr (EXP) *(v4i_r*)(l_be + o) = *(const v4i_r*)((const unsigned char*)a.be + o);
                     *(v4i_r*)(l_bd + o) = *(const v4i_r*)((const unsigned char*)a.bd + o);
                 }
             }
@@ -201,7 +205,7 @@ __global__ __launch_bounds__(GP ? 64 * GP : 256, (NCO == 1 && MAXK == 1 && !GP) 
     const unsigned char* const we_lane = (const unsigned char*)a.we + (size_t)m * a.Kx + 16 * hi;       // + g * 32 * Kx + k * 32
     const unsigned char* const wd_lane = (const unsigned char*)a.wd + (size_t)lane * 16;               // + (g * 9 + tap) * 1024
     const unsigned char* const wp_lane = (const unsigned char*)a.wp + (size_t)m * a.Ce32 + 16 * hi;     // + cob * 32 * Ce32 + g * 32
-    v4i_r we[MAXK], wd[9], wp[NCO];
+    v4i_r we[EXP ? MAXK : 1], wd[9], wp[NCO];
     v16i_r accp[MAXB][NCO];
 #pragma unroll
     for (int s = 0; s < MAXB; ++s)
@@ -243,6 +247,40 @@ __global__ __launch_bounds__(GP ? 64 * GP : 256, (NCO == 1 && MAXK == 1 && !GP) 
                 if (eoff[j] >= 0) *(v4i_r*)(ebuf + eoff[j]) = out;
             }
     };
+    // without expansion: the group's 32 channels of the tile's input pixels, 16 bytes per lane and load, zeros past the last
+    // channel; pixels outside the image are never written and stay zero.  Loads and stores are separate so that the loads of
+    // the next group can be in flight over the work on this one.
+    constexpr int FT = GP ? 64 : NT;                                    // lanes that fill one buffer: a wavefront's own (GP) or the workgroup's
+    v4i_r fl[EXP ? 1 : IR_FILL];
+    unsigned fdst[EXP ? 1 : IR_FILL];
+    auto fill_load = [&](int g) {
+        if constexpr (!EXP) {
+            const unsigned char* x = (const unsigned char*)a.x + (size_t)n * a.H * a.W * a.Cin;
+            const int nch = t.ih * t.iw * 2, ft = GP ? lane : tid;
+#pragma unroll
+            for (int i = 0; i < IR_FILL; ++i) {
+                fdst[i] = ~0u;
+                fl[i] = v4i_r{0, 0, 0, 0};
+                if (FT * i < nch) {                                     // wave-uniform
+                    const int e = min(FT * i + ft, nch - 1), p = e >> 1, half = e & 1;
+                    const int py = (int)__umulhi((unsigned)p, t.magic_iw), px = p - py * t.iw;
+                    const int iy = iy0 + py, ix = ix0 + px;
+                    const bool in_img = FT * i + ft < nch && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+                    const bool ok = in_img && g * 32 + 16 * half < a.Cin;
+                    fl[i] = *(const v4i_r*)(x + (ok ? (unsigned)((iy * a.W + ix) * a.Cin + g * 32 + 16 * half) : 0u));      // unconditional, in range
+                    if (!ok) fl[i] = v4i_r{0, 0, 0, 0};
+                    if (in_img) fdst[i] = (unsigned)(py * e_row + px * 32 + 16 * half);
+                }
+            }
+        }
+    };
+    auto fill_store = [&](unsigned char* ebuf) {
+        if constexpr (!EXP) {
+#pragma unroll
+            for (int i = 0; i < IR_FILL; ++i)
+                if (fdst[i] != ~0u) *(v4i_r*)(ebuf + fdst[i]) = fl[i];
+        }
+    };
     auto dw_project = [&](int g, const unsigned char* ebuf) {
 #pragma unroll
         for (int s = 0; s < MAXB; ++s)
@@ -265,9 +303,9 @@ __global__ __launch_bounds__(GP ? 64 * GP : 256, (NCO == 1 && MAXK == 1 && !GP) 
         unsigned char* const my_e = l_e + wave * t.e_bytes;
         __syncthreads();                                                // staged pixels, cleared buffers and biases are in LDS
         for (int g = wave; g < ngroups; g += NW) {
-            load_we(g);
+            if constexpr (EXP) load_we(g); else fill_load(g);
             load_wd_wp(g);
-            expand(g, my_e);
+            if constexpr (EXP) expand(g, my_e); else fill_store(my_e);
             dw_project(g, my_e);                                        // same wavefront, same buffer: LDS keeps a wavefront's accesses in order
         }
 #pragma unroll
@@ -279,17 +317,19 @@ __global__ __launch_bounds__(GP ? 64 * GP : 256, (NCO == 1 && MAXK == 1 && !GP) 
                     for (int i = 0; i < 16; ++i) atomicAdd(l_r + ((s * NCO + c) * 16 + i) * 64 + lane, accp[s][c][i]);
         __syncthreads();                                                // all four partial sums are in
     } else {
-        load_we(0);
+        if constexpr (EXP) load_we(0); else fill_load(0);
         __syncthreads();                                                // staged pixels, cleared buffers and biases are in LDS
         load_wd_wp(0);
-        expand(0, l_e);
+        if constexpr (EXP) expand(0, l_e); else fill_store(l_e);
         for (int g = 0; g < ngroups; ++g) {
-            if (g + 1 < ngroups) load_we(g + 1);
-            __syncthreads();                                            // group g is expanded; nobody reads the other buffer any more
+            if (g + 1 < ngroups) {
+                if constexpr (EXP) load_we(g + 1); else fill_load(g + 1);
+            }
+            __syncthreads();                                            // group g is in its buffer; nobody reads the other buffer any more
             dw_project(g, l_e + (g & 1) * t.e_bytes);
             if (g + 1 < ngroups) {
                 load_wd_wp(g + 1);
-                expand(g + 1, l_e + ((g + 1) & 1) * t.e_bytes);
+                if constexpr (EXP) expand(g + 1, l_e + ((g + 1) & 1) * t.e_bytes); else fill_store(l_e + ((g + 1) & 1) * t.e_bytes);
             }
         }
     }
@@ -350,7 +390,9 @@ int ir_block_out_blocks(int c_out)
 bool ir_block_plan(const IrArgs& a, IrTile& t, int& nco, int& maxb)
 {
     if ((a.stride != 1 && a.stride != 2) || a.pad != 1 || a.B < 1) return false;
-    if (a.Cin % 8 != 0 || a.Cin > 32 * IR_MAXK || a.Cout % 8 != 0 || a.Ce32 % 32 != 0 || a.Ce32 < 32 || a.Kx % 32 != 0 || a.Kx < a.Cin) return false;
+    const bool expands = a.Kx > 0;                                      // Kx = 0: depthwise -> projection, no expansion in front
+    if (a.Cout % 8 != 0 || a.Ce32 % 32 != 0 || a.Ce32 < 32) return false;
+    if (expands ? (a.Cin % 8 != 0 || a.Cin > 32 * IR_MAXK || a.Kx % 32 != 0 || a.Kx < a.Cin) : (a.Cin % 16 != 0 || a.Ce32 < a.Cin || a.Ce32 - a.Cin >= 32)) return false;
     if ((double)a.B * a.H * a.W * a.Cin >= 2147483648.0 || (double)a.B * a.Ho * a.Wo * a.Cout >= 2147483648.0) return false;
     nco = ir_block_out_blocks(a.Cout);
     if (nco > 5) return false;
@@ -362,12 +404,13 @@ bool ir_block_plan(const IrArgs& a, IrTile& t, int& nco, int& maxb)
     auto fits = [&] {
         t.iw = (t.pbw * t.nbw - 1) * a.stride + 3;
         t.ih = (t.pbh * t.nbh - 1) * a.stride + 3;
-        t.cpp = a.Cin / 8;
+        t.cpp = expands ? a.Cin / 8 : 1;
         t.xp = a.Kx + 16;
-        t.x_bytes = t.ih * t.iw * t.xp + 128;                           // the last pixel's reduction bytes may be read past its channels
+        t.x_bytes = expands ? t.ih * t.iw * t.xp + 128 : 0;             // the last pixel's reduction bytes may be read past its channels
         t.e_bytes = t.ih * (t.iw * 32 + 16);
-        return t.ih * t.iw <= 128 * IR_MAXCB && t.ih * t.iw * t.cpp <= 256 * IR_BATCH * IR_BATCHES && t.pbw * t.pbh <= 4 * maxb &&
-               8 * a.Ce32 + t.x_bytes + 2 * t.e_bytes <= 64 * 1024;
+        if (t.pbw * t.pbh > 4 * maxb || 8 * a.Ce32 + t.x_bytes + 2 * t.e_bytes > 64 * 1024) return false;
+        return expands ? t.ih * t.iw <= 128 * IR_MAXCB && t.ih * t.iw * t.cpp <= 256 * IR_BATCH * IR_BATCHES
+                       : t.ih * t.iw * 2 <= 256 * IR_FILL;
     };
     if (!fits()) return false;
     for (;;) {                                                          // grow the shorter side in pixels while the tile fits
@@ -394,8 +437,9 @@ bool ir_block_plan(const IrArgs& a, IrTile& t, int& nco, int& maxb)
     t.per_xcd = (t.total + 7) / 8;
     // small images: the wavefronts share the channel groups (instantiated for 2 or more output blocks and 2 or more reduction steps)
     const int nw = a.Ce32 >= 320 ? 8 : 4;                               // ten or more groups: eight wavefronts
-    t.gp = nco >= 2 && a.Kx >= 64 && a.Ce32 >= 128 && t.pbw * t.pbh <= maxb && t.ih * t.iw <= 32 * IR_MAXCB && total <= 2048 &&
-                   t.ih * t.iw * t.cpp <= 64 * nw * IR_BATCH * IR_BATCHES && 8 * a.Ce32 + t.x_bytes + nw * t.e_bytes + maxb * nco * 4096 <= 64 * 1024
+    t.gp = nco >= 2 && a.Ce32 >= 128 && t.pbw * t.pbh <= maxb && total <= 2048 && 8 * a.Ce32 + t.x_bytes + nw * t.e_bytes + maxb * nco * 4096 <= 64 * 1024 &&
+                   (expands ? a.Kx >= 64 && t.ih * t.iw <= 32 * IR_MAXCB && t.ih * t.iw * t.cpp <= 64 * nw * IR_BATCH * IR_BATCHES
+                            : t.ih * t.iw * 2 <= 64 * IR_FILL)
                ? nw : 0;
     return true;
 }
@@ -417,6 +461,14 @@ template <int STRIDE, int NCO, int MAXB>
 static void ir_launch(const IrArgs& a, const IrTile& t, size_t lds, hipStream_t s)
 {
     const int kx32 = a.Kx >> 5;                                         // registers for the expansion weights: 1, 2 or 5 steps
+    if (kx32 == 0) {                                                    // no expansion
+        if constexpr (NCO >= 2) {
+            if (t.gp == 4) { ir_launch5<STRIDE, NCO, MAXB, 0, 4>(a, t, lds, s); return; }
+            if (t.gp == 8) { ir_launch5<STRIDE, NCO, MAXB, 0, 8>(a, t, lds, s); return; }
+        }
+        ir_launch5<STRIDE, NCO, MAXB, 0, 0>(a, t, lds, s);
+        return;
+    }
     if constexpr (NCO >= 2) {
         if (t.gp == 4) {
             if (kx32 <= 2) ir_launch5<STRIDE, NCO, MAXB, 2, 4>(a, t, lds, s);

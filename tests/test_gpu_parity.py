@@ -125,6 +125,9 @@ IR_CASES = [  # h, w, c_in, expanded, c_out (per block), stride, blocks, samples
     (9, 11, 16, 48, 16, 1, 2, 7), (8, 8, 24, 144, (24, 32), 1, 2, 7), (13, 8, 24, 144, 32, 2, 1, 7), (14, 14, 64, 208, 64, 1, 1, 5),
     (7, 7, 160, 320, 160, 1, 1, 3), (16, 16, 16, 96, (24, 16), 2, 2, 7), (5, 6, 8, 48, (40, 16), 1, 2, 7), (7, 7, 96, 160, 128, 1, 1, 3),
     (20, 18, 32, 64, 96, 1, 1, 3), (1, 1, 16, 32, 16, 1, 1, 2), (3, 2, 32, 96, (8, 16), 2, 2, 2), (28, 28, 32, 192, 32, 1, 1, 40),
+    # without expansion (depthwise -> projection): one and several channel groups, both forms of the kernel
+    (9, 11, 32, 0, 16, 1, 1, 7), (8, 8, 48, 0, (32, 16), 2, 2, 7), (14, 14, 144, 0, 64, 1, 1, 5), (7, 7, 208, 0, 96, 1, 1, 3), (12, 20, 16, 0, 16, 1, 2, 7),
+    (28, 28, 32, 0, 16, 1, 1, 40),
 ]
 
 
@@ -136,7 +139,7 @@ def test_fused_inverted_residual_blocks_equal_separate_layers_and_oracle(torch, 
     separate layers, bit for bit."""
     h, w, ci, ce, co, stride, blocks, n = case
     blob = W.inverted_residual_net(h, w, ci, ce, co, stride, seed=h * 7 + ce, blocks=blocks)
-    say(f"[case] inverted residual {h}x{w} {ci} -> {ce} -> {co} stride {stride}, {blocks} block(s), {n} samples")
+    say(f"[case] inverted residual {h}x{w} {ci} -> {ce if ce else 'no expansion'} -> {co} stride {stride}, {blocks} block(s), {n} samples")
     r = np.random.default_rng(h * 100 + ce)
     x = np.concatenate([np.full((1, h, w, ci), -128, np.int8), np.full((1, h, w, ci), 127, np.int8),
                         r.integers(-128, 128, size=(max(n - 2, 1), h, w, ci), dtype=np.int8)])[:n]
@@ -157,13 +160,13 @@ def test_fused_inverted_residual_blocks_in_a_network(torch, ee, orc):
     segment and head against the oracle."""
     blob = W.load_net("mobilenetv2_small_i8")
     eng = ee.Engine(blob, 8)
-    assert eng.ir_count() == 15                                            # every block with an expansion but the last (320 output channels)
+    assert eng.ir_count() == 16                                            # every block but the last (320 output channels)
     x = W.input_pool(blob, 7)
     for step, mode in enumerate((2, 0, 1)):
         if step == 2:
             eng.autotune(reps=2)
             tabs = eng.tables()["ir"]
-            assert len(tabs) == 15 and all(set(v) <= {0, 1} for v in tabs.values())
+            assert len(tabs) == 16 and all(set(v) <= {0, 1} for v in tabs.values())
             eng.load_tables({"ir": tabs})
         eng.ir_mode(mode)
         act = x

@@ -423,7 +423,7 @@ def single_layer_net(kind, h, w, c, k, stride, pad, dtype, seed=0, co=None, act=
 
 
 def inverted_residual_net(h, w, ci, ce, co, stride, seed=0, blocks=1):
-    """One segment of `blocks` inverted-residual blocks (1x1 expansion to `ce` channels, 3x3 depthwise with the given stride
+    """One segment of `blocks` inverted-residual blocks (1x1 expansion to `ce` channels -- none when ce = 0 --, 3x3 depthwise with the given stride
     in the first block, 1x1 projection to `co` channels (an int, or one value per block), with the block's input as residual where shapes allow) on an
     h x w x ci input, int8: the fused-block kernel's shapes alone, for edge cases.  Data only."""
     net = _Net(DT_I8, h, w, ci, 10)
@@ -432,7 +432,7 @@ def inverted_residual_net(h, w, ci, ce, co, stride, seed=0, blocks=1):
     cos = [co] * blocks if isinstance(co, int) else list(co)          # output channels per block
     for i in range(blocks):
         s_i = stride if i == 0 else 1
-        u = net.conv(t, ce, 1, 1, 0, act="relu6")
+        u = net.conv(t, ce, 1, 1, 0, act="relu6") if ce else t         # ce = 0: no expansion, the depthwise layer reads the block's input
         u = net.dwconv(u, 3, s_i, 1, act="relu6")
         t = net.conv(u, cos[i], 1, 1, 0, act="linear", res=t if (s_i == 1 and cin == cos[i]) else -1)
         cin = cos[i]
