@@ -258,6 +258,57 @@ int pack_ir(ee_ctx* ctx, const unsigned char* blob, const StageDesc& st, int k)
     return EE_OK;
 }
 
+// rows [rows][row_bytes] of a weight matrix as ready matrix-instruction operands [row block of 32][step of 32 bytes][lane][16]:
+// lane m + 32 hi holds bytes 16 hi .. 16 hi + 15 of the step of row m
+std::vector<unsigned char> bn_operands(const unsigned char* w, int rows, int row_bytes)
+{
+    std::vector<unsigned char> out((size_t)rows * row_bytes);
+    const int steps = row_bytes / 32;
+    for (int r = 0; r < rows; ++r)
+        for (int k = 0; k < steps; ++k)
+            for (int hi = 0; hi < 2; ++hi)
+                std::memcpy(&out[((((size_t)(r / 32) * steps + k) * 64) + (r % 32) + 32 * hi) * 16], w + (size_t)r * row_bytes + 32 * k + 16 * hi, 16);
+    return out;
+}
+
+// Marks layer k of the segment as the head of a bottleneck block (1x1 -> 3x3 -> 1x1 + residual) when the fused kernel covers
+// it and packs the block's weights for that kernel.
+int pack_bneck(ee_ctx* ctx, const unsigned char* blob, const StageDesc& st, int k)
+{
+    OpPlan& p = ctx->plans[st.first_op + k];
+    if (k + 2 >= st.n_ops) return EE_OK;
+    const OpDesc& c1 = p.d;
+    const OpDesc& c2 = ctx->plans[st.first_op + k + 1].d;
+    const OpDesc& c3 = ctx->plans[st.first_op + k + 2].d;
+    if (c1.kind != OP_CONV || c2.kind != OP_CONV || c3.kind != OP_CONV) return EE_OK;
+    if (c1.kh != 1 || c1.kw != 1 || c1.stride != 1 || c1.pad != 0 || c1.pad_w != 0 || c1.res >= 0 || c1.c_tot != c1.c_out) return EE_OK;
+    if (c2.kh != 3 || c2.kw != 3 || c2.stride != 1 || c2.pad != 1 || c2.pad_w != 1 || c2.res >= 0 || c2.src != c1.dst || c2.c_tot != c2.c_out) return EE_OK;
+    if (c3.kh != 1 || c3.kw != 1 || c3.stride != 1 || c3.pad != 0 || c3.pad_w != 0 || c3.src != c2.dst || c3.c_tot != c3.c_out) return EE_OK;
+    if (c1.dst == st.out_tensor || c2.dst == st.out_tensor || c3.res == c1.dst || c3.res == c2.dst) return EE_OK;
+    int readers_1 = 0, readers_2 = 0;
+    for (int j = 0; j < st.n_ops; ++j) {
+        const OpDesc& o = ctx->plans[st.first_op + j].d;
+        readers_1 += (o.src == c1.dst) + (o.res == c1.dst);
+        readers_2 += (o.src == c2.dst) + (o.res == c2.dst);
+    }
+    if (readers_1 != 1 || readers_2 != 1) return EE_OK;
+    IrArgs probe{};
+    probe.B = ctx->b_max; probe.H = c1.h_in; probe.W = c1.w_in; probe.Cin = c1.c_in; probe.Kx = c1.c_in; probe.Ce32 = c1.c_out; probe.Cout = c3.c_out;
+    probe.Ho = c2.h_out; probe.Wo = c2.w_out; probe.stride = 1; probe.pad = 1;
+    if (c2.c_in != c1.c_out || c2.c_out != c1.c_out || !bneck_block_supported(probe)) return EE_OK;
+    int rc = upload(ctx, &p.ir_we, bn_operands(blob + c1.w_off, c1.c_out, c1.c_in));
+    if (!rc) rc = upload(ctx, &p.ir_be, ir_rounded_bias(blob, c1, c1.c_out, c1.c_out));
+    if (!rc) rc = upload(ctx, &p.ir_wd, bn_operands(blob + c2.w_off, c2.c_out, 9 * c2.c_in));
+    if (!rc) rc = upload(ctx, &p.ir_bd, ir_rounded_bias(blob, c2, c2.c_out, c2.c_out));
+    if (!rc) rc = upload(ctx, &p.ir_wp, bn_operands(blob + c3.w_off, c3.c_out, c3.c_in));
+    if (!rc) rc = upload(ctx, &p.ir_bp, ir_rounded_bias(blob, c3, c3.c_out, c3.c_out));
+    if (rc) return rc;
+    p.ir_kx = c1.c_in; p.ir_ce32 = c1.c_out;
+    p.ir = true;
+    p.ir_bneck = true;
+    return EE_OK;
+}
+
 // Assigns the intermediate tensors of every segment to a small pool of reusable buffers
 // (greedy by liveness); the segment input and output stay with the caller.
 void plan_buffers(ee_ctx* ctx)
@@ -461,6 +512,8 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
         for (const StageDesc& st : ctx->net.stages)
             for (int k = 0; k + 1 < st.n_ops; ++k) {
                 if ((rc = pack_ir(ctx, (const unsigned char*)blob, st, k))) return fail(rc);
+                // likewise bottleneck blocks: 1x1 -> 3x3 (stride 1, padding 1) -> 1x1 (+ residual), each read only by the next
+                if (!ctx->plans[st.first_op + k].ir && (rc = pack_bneck(ctx, (const unsigned char*)blob, st, k))) return fail(rc);
             }
     plan_buffers(ctx);
     ctx->pool.resize(ctx->pool_sample_bytes.size(), nullptr);
@@ -663,6 +716,7 @@ void ee_ctx::fill_ir_args(int op, int b, IrArgs& a) const
     const OpDesc& pr = plans[(size_t)op + (p.ir_noexp ? 1 : 2)].d;
     a.we = p.ir_we; a.be = (const int*)p.ir_be; a.wd = p.ir_wd; a.bd = (const int*)p.ir_bd; a.wp = p.ir_wp; a.bp = (const int*)p.ir_bp;
     a.B = b; a.H = e.h_in; a.W = e.w_in; a.Cin = e.c_in; a.Kx = p.ir_kx; a.Ce32 = p.ir_ce32; a.Cout = pr.c_out;
+    a.ys = nullptr;
     a.Ho = dw.h_out; a.Wo = dw.w_out; a.stride = dw.stride; a.pad = dw.pad;
     a.sh_e = e.shift; a.lo_e = e.lo; a.hi_e = e.hi;
     a.sh_d = dw.shift; a.lo_d = dw.lo; a.hi_d = dw.hi;
@@ -944,7 +998,9 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
         if ((xs || ys) && p.impl != IMPL_MFMA) return EE_ERR_UNSUPPORTED;
         if (zc_in && d.res >= 0 && p.res_buf == BUF_EXT_IN) return EE_ERR_UNSUPPORTED;
         const int ir_last = p.ir_noexp ? 1 : 2;                             // the block's last layer, counted from this one
-        if (p.ir && ir_mode > 0 && cfg_force == 0 && forced_conv_tile() == 0 && only_op < 0 && !xs && !zc_out &&
+        // a bottleneck block may sit in a segment whose last layer writes slots, and may be that layer (its kernel takes the slot table)
+        const bool ir_slots_ok = p.ir_bneck ? !(zc_in && plans[st.first_op + k + ir_last].res_buf == BUF_EXT_IN) : !zc_out;
+        if (p.ir && ir_mode > 0 && cfg_force == 0 && forced_conv_tile() == 0 && only_op < 0 && !xs && ir_slots_ok &&
             !(gap_fuse_dst && st.first_op + k + ir_last == gap_fuse_op[(size_t)stage])) {
             // this layer, the depthwise layer and the projection as one launch, where the table says it is faster
             const int ic = p.ir_cfg.empty() ? 0 : p.ir_cfg[std::min<size_t>(bucket_of(b), p.ir_cfg.size() - 1)];
@@ -955,6 +1011,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                 ia.x = src;
                 ia.y = resolve(this, q2.dst_buf, act_in, act_out);
                 ia.res = q2.d.res >= 0 ? resolve(this, q2.res_buf, act_in, act_out) : nullptr;
+                ia.ys = q2.dst_buf == BUF_EXT_OUT ? zc_out : nullptr;
                 double f_ops = ops, f_bytes = bytes;                             // the block's layers; the tensors between them stay on chip
                 for (int j = 1; j <= ir_last; ++j) {
                     const OpPlan& q = plans[st.first_op + k + j];
@@ -962,7 +1019,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                     f_ops += q.ops_per_sample * b;
                     f_bytes += q.bytes_per_sample * b + q.weight_bytes - 2.0 * b * (double)prev.h_out * prev.w_out * prev.c_out;
                 }
-                e = timed(EE_K_CONV_MFMA, f_ops, f_bytes, [&] { return launch_ir_block(ia, stream); }, st.first_op + k);
+                e = timed(EE_K_CONV_MFMA, f_ops, f_bytes, [&] { return p.ir_bneck ? launch_bneck_block(ia, stream) : launch_ir_block(ia, stream); }, st.first_op + k);
                 if (e != hipSuccess) return EE_ERR_DEVICE;
                 k += ir_last;                                                    // the block's other layers are done
                 continue;

@@ -28,6 +28,7 @@ struct OpPlan {
     // this layer (a 1x1 expansion), the 3x3 depthwise layer behind it and the 1x1 projection behind that can run as one fused launch
     bool ir = false;
     bool ir_noexp = false;      // the block has no expansion: this layer is the depthwise layer, the projection follows it (two layers)
+    bool ir_bneck = false;      // the block is a bottleneck block (1x1 -> 3x3 -> 1x1): its own kernel, the same table and switches
     std::vector<int> ir_cfg;    // per batch bucket: 1 = the fused launch, 0 = the three layers separately; empty = not tuned
     void* ir_we = nullptr; void* ir_be = nullptr; void* ir_wd = nullptr; void* ir_bd = nullptr; void* ir_wp = nullptr; void* ir_bp = nullptr;
     int ir_kx = 0, ir_ce32 = 0;

@@ -103,6 +103,7 @@ struct IrArgs {
     const void* wp; const int* bp;
     int B, H, W, Cin, Kx, Ce32, Cout, Ho, Wo, stride, pad;
     int sh_e, lo_e, hi_e, sh_d, lo_d, hi_d, sh_p, lo_p, hi_p, res_shift;
+    const uint16_t* ys;  // bottleneck block only; not null: sample n of the output goes to slot ys[n] of y (device memory; B <= EE_ZC_MAX_B)
 };
 
 struct DirectConvArgs {   // one thread per output element; any shape (correctness fallback)
@@ -168,6 +169,10 @@ hipError_t launch_depthwise(const PoolArgs& a, int dtype, hipStream_t s);
 bool ir_block_supported(const IrArgs& a);
 int ir_block_out_blocks(int c_out);            // blocks of 32 output channels the kernel is instantiated with (weights are padded to it)
 hipError_t launch_ir_block(const IrArgs& a, hipStream_t s);
+// bottleneck block (1x1 -> 3x3 -> 1x1 + residual) in one launch; the same argument block: we / be, wd / bd, wp / bp are the three
+// layers' operands and biases, Kx = Cin, Ce32 = the middle channels
+bool bneck_block_supported(const IrArgs& a);
+hipError_t launch_bneck_block(const IrArgs& a, hipStream_t s);
 hipError_t launch_maxpool(const PoolArgs& a, int dtype, hipStream_t s);
 hipError_t launch_avgpool(const PoolArgs& a, int dtype, hipStream_t s);
 

@@ -155,6 +155,35 @@ def test_fused_inverted_residual_blocks_equal_separate_layers_and_oracle(torch, 
     eng.close()
 
 
+BN_CASES = [  # h, w, c_in, blocks, samples
+    (8, 8, 64, 1, 3), (9, 11, 64, 2, 7), (5, 17, 256, 1, 7), (16, 8, 256, 2, 5), (1, 1, 64, 1, 2), (28, 28, 256, 1, 40), (56, 56, 64, 2, 6),
+]
+
+
+@pytest.mark.parametrize("case", BN_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_fused_bottleneck_blocks_equal_separate_layers_and_oracle(torch, ee, orc, case):
+    """1x1 -> 3x3 -> 1x1 + residual as one launch (64 middle channels, 256 out): images that are and are not whole tiles of
+    8 x 8 pixels, a single pixel, 64 and 256 input channels (a convolution or the block's input as residual), more tiles than
+    workgroups (a workgroup walks over several), extreme inputs; against the oracle and against the three separate layers,
+    bit for bit."""
+    h, w, ci, blocks, n = case
+    blob = W.bottleneck_net(h, w, ci, seed=h * 7 + w, blocks=blocks)
+    say(f"[case] bottleneck {h}x{w} {ci} -> 64 -> 64 -> 256, {blocks} block(s), {n} samples")
+    r = np.random.default_rng(h * 100 + w)
+    x = np.concatenate([np.full((1, h, w, ci), -128, np.int8), np.full((1, h, w, ci), 127, np.int8),
+                        r.integers(-128, 128, size=(max(n - 2, 1), h, w, ci), dtype=np.int8)])[:n]
+    eng = ee.Engine(blob, max(n, 2))
+    assert eng.ir_count() == blocks
+    for b in sorted({n, 1}, reverse=True):
+        ref = orc.stage_forward(blob, 0, x[:b])
+        for mode in (2, 0, 2):
+            eng.ir_mode(mode)
+            got = host(eng.stage_forward(0, dev(torch, x[:b]), ref.shape[1:]), ref)
+            assert np.array_equal(got, ref), f"mode {mode} b={b}: {np.count_nonzero(got != ref)} of {ref.size} differ, first at {np.argwhere(got != ref)[:3].tolist()}"
+    assert np.unique(ref).size > 8
+    eng.close()
+
+
 def test_fused_inverted_residual_blocks_in_a_network(torch, ee, orc):
     """The MobileNetV2-style network with every block fused, with none fused and with the table ee_autotune writes: every
     segment and head against the oracle."""

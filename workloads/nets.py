@@ -448,6 +448,32 @@ def inverted_residual_net(h, w, ci, ce, co, stride, seed=0, blocks=1):
     return blob
 
 
+def bottleneck_net(h, w, ci, seed=0, blocks=1, mid=64):
+    """One segment of `blocks` bottleneck blocks (1x1 to `mid` channels, 3x3 stride 1, 1x1 to 4 * mid channels with a residual:
+    the block's input where it has 4 * mid channels, else a 1x1 convolution of it) on an h x w x ci input, int8: the fused-block
+    kernel's shapes alone, for edge cases.  Data only."""
+    net = _Net(DT_I8, h, w, ci, 10)
+    t = net.begin_stage()
+    cin = ci
+    for _ in range(blocks):
+        short = t if cin == 4 * mid else net.conv(t, 4 * mid, 1, 1, 0, act="linear")
+        u = net.conv(t, mid, 1, 1, 0)
+        u = net.conv(u, mid, 3, 1, 1)
+        t = net.conv(u, 4 * mid, 1, 1, 0, res=short)
+        cin = 4 * mid
+    net.end_stage(t)
+    blob = _assemble(net, DT_I8, BASE_SEED + 0x7800 + seed)
+    for op in blob.ops:
+        if int(op["kind"]) == OP_CONV:
+            fan_in = int(op["c_in"]) * int(op["kh"]) * int(op["kw"])
+            op["shift"] = max(0, int(math.ceil(math.log2(2.0 * 74 * 40 * math.sqrt(fan_in) / 127))))
+            if int(op["res"]) >= 0:
+                op["res_shift"] = max(0, int(op["shift"]) - 1)
+    for e in blob.exits:
+        e["frac_bits"], e["thr"] = 10, 0.5
+    return blob
+
+
 CONFIGS = {
     # name: (architecture, dtype, seed offset)
     "tiny_i8": (_tiny, DT_I8, 1),
