@@ -41,7 +41,7 @@ template <int K1, bool RES>    // reduction steps of the first layer: c_in / 32;
 __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) void bneck_block_i8_kernel(IrArgs a, BnTile t)
 {
     constexpr int CIN = 32 * K1, CPP = 2 * K1;                         // 16-byte chunks per input pixel
-    constexpr int NCH = 100 * CPP, NL = (NCH + 255) / 256;             // chunks per tile, loads per front lane
+    constexpr int NCH = 100 * CPP, NL = (NCH + 511) / 512;             // chunks per tile, loads per lane (all eight wavefronts stage)
     extern __shared__ __attribute__((aligned(16))) unsigned char bn_lds[];
     const int tid = threadIdx.x, lane = tid & 63, m = lane & 31, hi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -145,38 +145,54 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         }
     };
 
+    // ---- this lane's chunks of a staged tile: offsets from the tile's first pixel, -------------------------------------
+    v4i_r st[NL];                                                   // the loaded chunks
+    int lrel[NL], lpyx[NL];                                         // global byte offset from the tile's pixel (0, 0); staged row | column << 8
+    unsigned ldst[NL];                                              // LDS byte offset of the chunk, ~0u: none
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        const int e0 = 512 * i + tid, e = min(e0, NCH - 1), q = e / CPP, ch = e - q * CPP, py = q / 10, px = q - 10 * py;
+        lrel[i] = ((py - 1) * a.W + (px - 1)) * CIN + 16 * ch;
+        lpyx[i] = py | px << 8;
+        ldst[i] = e0 < NCH ? (unsigned)(q * t.xp + 16 * ch) : ~0u;
+    }
+    auto x_load = [&](const Cursor& cu) {                           // unconditional and in range: a pixel outside the image reads the image's first one
+        const int n = cu.n, oy0 = 8 * cu.ty, ox0 = 8 * cu.tx;
+        const unsigned char* x = (const unsigned char*)a.x + (size_t)n * a.H * a.W * CIN;
+        const int base = (oy0 * a.W + ox0) * CIN;
+        // staged rows y_first .. y_last and columns x_first .. x_last lie inside the image
+        const int y_first = oy0 == 0 ? 1 : 0, y_last = min(9, a.H - oy0), x_first = ox0 == 0 ? 1 : 0, x_last = min(9, a.W - ox0);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int py = lpyx[i] & 255, px = lpyx[i] >> 8;
+            const bool ok = (unsigned)(py - y_first) <= (unsigned)(y_last - y_first) && (unsigned)(px - x_first) <= (unsigned)(x_last - x_first);
+            st[i] = *(const v4i_r*)(x + (ok ? (unsigned)(base + lrel[i]) : 0u));
+        }
+    };
+    auto x_store = [&](unsigned char* xb) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i)
+            if (512 * (i + 1) <= NCH || ldst[i] != ~0u) *(v4i_r*)(xb + ldst[i]) = st[i];     // only the last chunk may be missing
+    };
+    // ---- prologue: the first tile's pixels to LDS, the second tile's requested ---------------------------------------
+    Cursor c_ld = first;                                                // the tile whose pixels are requested next
+    x_load(c_ld);
+    advance(c_ld);
+    x_store(l_x);
+    if (1 < T) x_load(c_ld);                                            // in flight over the first iteration
+    advance(c_ld);
+    // per iteration: tile it + 2, requested one iteration ago, goes into the buffer the first layer read one iteration ago
+    // (tile it's); then the next request, in flight over a whole iteration
+    auto stage_next = [&](int it) {
+        if (it + 2 < T) x_store(l_x + (it & 1) * t.x_bytes);
+        if (it + 3 < T) x_load(c_ld);
+        advance(c_ld);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
     // Each role has its own loop (a wavefront has one role for good, and the registers that live over a loop are the role's
     // own); both loops run the same iterations with the same two barriers, so the workgroup's barriers pair up.
     if (front) {
-        // ---- this lane's chunks of a staged tile: offsets from the tile's first pixel, and its pixel in the first layer -------
-        v4i_r st[NL];                                                   // the loaded chunks
-        int lrel[NL], lpyx[NL];                                         // global byte offset from the tile's pixel (0, 0); staged row | column << 8
-        unsigned ldst[NL];                                              // LDS byte offset of the chunk, ~0u: none
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int e0 = 256 * i + tid, e = min(e0, NCH - 1), q = e / CPP, ch = e - q * CPP, py = q / 10, px = q - 10 * py;
-            lrel[i] = ((py - 1) * a.W + (px - 1)) * CIN + 16 * ch;
-            lpyx[i] = py | px << 8;
-            ldst[i] = e0 < NCH ? (unsigned)(q * t.xp + 16 * ch) : ~0u;
-        }
-        auto x_load = [&](const Cursor& cu) {                           // unconditional and in range: a pixel outside the image reads the image's first one
-            const int n = cu.n, oy0 = 8 * cu.ty, ox0 = 8 * cu.tx;
-            const unsigned char* x = (const unsigned char*)a.x + (size_t)n * a.H * a.W * CIN;
-            const int base = (oy0 * a.W + ox0) * CIN;
-            // staged rows y_first .. y_last and columns x_first .. x_last lie inside the image
-            const int y_first = oy0 == 0 ? 1 : 0, y_last = min(9, a.H - oy0), x_first = ox0 == 0 ? 1 : 0, x_last = min(9, a.W - ox0);
-#pragma unroll
-            for (int i = 0; i < NL; ++i) {
-                const int py = lpyx[i] & 255, px = lpyx[i] >> 8;
-                const bool ok = (unsigned)(py - y_first) <= (unsigned)(y_last - y_first) && (unsigned)(px - x_first) <= (unsigned)(x_last - x_first);
-                st[i] = *(const v4i_r*)(x + (ok ? (unsigned)(base + lrel[i]) : 0u));
-            }
-        };
-        auto x_store = [&](unsigned char* xb) {
-#pragma unroll
-            for (int i = 0; i < NL; ++i)
-                if (256 * (i + 1) <= NCH || ldst[i] != ~0u) *(v4i_r*)(xb + ldst[i]) = st[i];     // only the last chunk may be missing
-        };
         const int hp = 32 * wave + m, hpc = min(hp, 99), hy = hpc / 10, hx = hpc - 10 * hy;
         const int xoff = hpc * t.xp + 16 * hi, m1off = hy * BN_M1_ROW + hx * BN_M1_PX + 16 * hi;
         v4i_r w1[2][K1];                                                // ready operands, 16 bytes per lane each: [block][step]
@@ -184,24 +200,15 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         for (int c = 0; c < 2; ++c)
 #pragma unroll
             for (int k = 0; k < K1; ++k) w1[c][k] = *(const v4i_r*)((const unsigned char*)a.we + ((size_t)(c * K1 + k) * 64 + lane) * 16);
-        Cursor c_out = first, c_l1 = first, c_ld = first;               // the tiles of the last layer, of the first layer, of the loads
-        x_load(c_ld);
-        advance(c_ld);
-        x_store(l_x);
+        Cursor c_out = first, c_l1 = first;                             // the tiles of the last layer, of the first layer
         // every weight has arrived before the loop, so that nothing inside it waits for them by count
 #pragma unroll
         for (int k = 0; k < 2 * K1; ++k) asm volatile("" : "+v"(w1[k / K1][k % K1]));
 #pragma unroll
         for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(w3[k >> 1][k & 1]));
-        if (1 < T) x_load(c_ld);                                        // in flight over the first iteration
-        advance(c_ld);
         __syncthreads();                                                // biases and the first tile's pixels are in LDS
         for (int it = -1; it < T; ++it) {
-            // tile it + 2, requested one iteration ago, goes into the buffer the first layer read one iteration ago (tile it's);
-            // then the next request, in flight over a whole iteration
-            if (it + 2 < T) x_store(l_x + (it & 1) * t.x_bytes);
-            if (it + 3 < T) x_load(c_ld);
-            advance(c_ld);
+            stage_next(it);
             if (it >= 0) { out_pixel(c_out); advance(c_out); }
             if (it + 1 < T) {
                 const int oy0 = 8 * c_l1.ty, ox0 = 8 * c_l1.tx;
@@ -241,29 +248,42 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 #pragma unroll
         for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(w3[k >> 1][k & 1]));
         __syncthreads();                                                // biases and the first tile's pixels are in LDS
-        __syncthreads();                                                // iteration -1 has nothing for this role
-        __syncthreads();
         Cursor c_out = first;
-        for (int it = 0; it < T; ++it) {
+        for (int it = -1; it < T; ++it) {
+            stage_next(it);
+            v4i_r dq = v4i_r{0, 0, 0, 0};
+            if (it >= 0) {
             out_pixel(c_out);
             advance(c_out);
             v16i_r acc = bias16(l_b2, half);
             const unsigned char* win = l_m1 + (it & 1) * BN_M1_BYTES + woff;
-            v4i_r b[18];                                                // every operand requested before the first is used
+            // the eighteen operands in three batches of six through two sets of registers: the third batch is requested when the
+            // first has been used, behind the matrix instructions of the second
+            auto tap = [&](int k) { return *(const v4i_r*)(win + (k / 6) * BN_M1_ROW + ((k / 2) % 3) * BN_M1_PX + (k & 1) * 32); };
+            v4i_r b0[6], b1[6];
 #pragma unroll
-            for (int r = 0; r < 3; ++r)
+            for (int k = 0; k < 6; ++k) b0[k] = tap(k);
 #pragma unroll
-                for (int c = 0; c < 3; ++c)
-#pragma unroll
-                    for (int g = 0; g < 2; ++g) b[(3 * r + c) * 2 + g] = *(const v4i_r*)(win + r * BN_M1_ROW + c * BN_M1_PX + g * 32);
+            for (int k = 0; k < 6; ++k) b1[k] = tap(6 + k);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int k = 0; k < 18; ++k) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w2[k], b[k], acc, 0, 0, 0);
-            const v4i_r dq = ir_requant_pack(acc, cl2);
+            for (int k = 0; k < 6; ++k) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w2[k], b0[k], acc, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < 6; ++k) b0[k] = tap(12 + k);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < 6; ++k) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w2[6 + k], b1[k], acc, 0, 0, 0);
+#pragma unroll
+            for (int k = 0; k < 6; ++k) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w2[12 + k], b0[k], acc, 0, 0, 0);
+            dq = ir_requant_pack(acc, cl2);
             *(v4i_r*)(l_m2 + ((pb * 2 + half) * 64 + lane) * 16) = dq;
+            }
             __syncthreads();                                            // the halves of the second layer's output are in LDS
-            const v4i_r other = *(const v4i_r*)(l_m2 + ((pb * 2 + (half ^ 1)) * 64 + lane) * 16);
-            last_layer(half ? other : dq, half ? dq : other);
+            if (it >= 0) {
+                const v4i_r other = *(const v4i_r*)(l_m2 + ((pb * 2 + (half ^ 1)) * 64 + lane) * 16);
+                last_layer(half ? other : dq, half ? dq : other);
+            }
             __syncthreads();
         }
     }
