@@ -183,8 +183,14 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     advance(c_ld);
     // per iteration: tile it + 2, requested one iteration ago, goes into the buffer the first layer read one iteration ago
     // (tile it's); then the next request, in flight over a whole iteration
-    auto stage_next = [&](int it) {
+    // (the requests go out behind the wavefront's matrix instructions of the first half, whose results take a while anyway:
+    // at the top of the half all eight wavefronts would queue up at the memory pipeline with nothing else to issue)
+    auto stage_write = [&](int it) {
         if (it + 2 < T) x_store(l_x + (it & 1) * t.x_bytes);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto stage_request = [&](int it) {
+        __builtin_amdgcn_sched_barrier(0);
         if (it + 3 < T) x_load(c_ld);
         advance(c_ld);
         __builtin_amdgcn_sched_barrier(0);
@@ -208,7 +214,7 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(w3[k >> 1][k & 1]));
         __syncthreads();                                                // biases and the first tile's pixels are in LDS
         for (int it = -1; it < T; ++it) {
-            stage_next(it);
+            stage_write(it);
             if (it >= 0) { out_pixel(c_out); advance(c_out); }
             if (it + 1 < T) {
                 const int oy0 = 8 * c_l1.ty, ox0 = 8 * c_l1.tx;
@@ -226,6 +232,7 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                     acc0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(w1[0][k], b[k], acc0, 0, 0, 0);
                     acc1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(w1[1][k], b[k], acc1, 0, 0, 0);
                 }
+                stage_request(it);
                 v4i_r o0 = ir_requant_pack(acc0, cl1), o1 = ir_requant_pack(acc1, cl1);
                 if (!in_img) { o0 = v4i_r{0, 0, 0, 0}; o1 = v4i_r{0, 0, 0, 0}; }
                 if (hp < 100) {
@@ -250,8 +257,9 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         __syncthreads();                                                // biases and the first tile's pixels are in LDS
         Cursor c_out = first;
         for (int it = -1; it < T; ++it) {
-            stage_next(it);
+            stage_write(it);
             v4i_r dq = v4i_r{0, 0, 0, 0};
+            if (it < 0) stage_request(it);
             if (it >= 0) {
             out_pixel(c_out);
             advance(c_out);
@@ -276,6 +284,7 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             for (int k = 0; k < 6; ++k) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w2[6 + k], b1[k], acc, 0, 0, 0);
 #pragma unroll
             for (int k = 0; k < 6; ++k) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w2[12 + k], b0[k], acc, 0, 0, 0);
+            stage_request(it);
             dq = ir_requant_pack(acc, cl2);
             *(v4i_r*)(l_m2 + ((pb * 2 + half) * 64 + lane) * 16) = dq;
             }
