@@ -716,7 +716,7 @@ void ee_ctx::fill_ir_args(int op, int b, IrArgs& a) const
     const OpDesc& pr = plans[(size_t)op + (p.ir_noexp ? 1 : 2)].d;
     a.we = p.ir_we; a.be = (const int*)p.ir_be; a.wd = p.ir_wd; a.bd = (const int*)p.ir_bd; a.wp = p.ir_wp; a.bp = (const int*)p.ir_bp;
     a.B = b; a.H = e.h_in; a.W = e.w_in; a.Cin = e.c_in; a.Kx = p.ir_kx; a.Ce32 = p.ir_ce32; a.Cout = pr.c_out;
-    a.ys = nullptr;
+    a.ys = nullptr; a.gap_sums = nullptr;
     a.Ho = dw.h_out; a.Wo = dw.w_out; a.stride = dw.stride; a.pad = dw.pad;
     a.sh_e = e.shift; a.lo_e = e.lo; a.hi_e = e.hi;
     a.sh_d = dw.shift; a.lo_d = dw.lo; a.hi_d = dw.hi;
@@ -1000,8 +1000,10 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
         const int ir_last = p.ir_noexp ? 1 : 2;                             // the block's last layer, counted from this one
         // a bottleneck block may sit in a segment whose last layer writes slots, and may be that layer (its kernel takes the slot table)
         const bool ir_slots_ok = p.ir_bneck ? !(zc_in && plans[st.first_op + k + ir_last].res_buf == BUF_EXT_IN) : !zc_out;
+        // the exit head's pooling rides on the segment's last layer: a bottleneck block's kernel carries it (with a residual), the others do not
+        const bool ir_pools = gap_fuse_dst && only_op < 0 && st.first_op + k + ir_last == gap_fuse_op[(size_t)stage];
         if (p.ir && ir_mode > 0 && cfg_force == 0 && forced_conv_tile() == 0 && only_op < 0 && !xs && ir_slots_ok &&
-            !(gap_fuse_dst && st.first_op + k + ir_last == gap_fuse_op[(size_t)stage])) {
+            !(ir_pools && !(p.ir_bneck && plans[st.first_op + k + ir_last].d.res >= 0))) {
             // this layer, the depthwise layer and the projection as one launch, where the table says it is faster
             const int ic = p.ir_cfg.empty() ? 0 : p.ir_cfg[std::min<size_t>(bucket_of(b), p.ir_cfg.size() - 1)];
             if (ic != 0 || ir_mode == 2) {
@@ -1012,6 +1014,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                 ia.y = resolve(this, q2.dst_buf, act_in, act_out);
                 ia.res = q2.d.res >= 0 ? resolve(this, q2.res_buf, act_in, act_out) : nullptr;
                 ia.ys = q2.dst_buf == BUF_EXT_OUT ? zc_out : nullptr;
+                ia.gap_sums = ir_pools ? gap_fuse_dst : nullptr;
                 double f_ops = ops, f_bytes = bytes;                             // the block's layers; the tensors between them stay on chip
                 for (int j = 1; j <= ir_last; ++j) {
                     const OpPlan& q = plans[st.first_op + k + j];
@@ -1021,6 +1024,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                 }
                 e = timed(EE_K_CONV_MFMA, f_ops, f_bytes, [&] { return p.ir_bneck ? launch_bneck_block(ia, stream) : launch_ir_block(ia, stream); }, st.first_op + k);
                 if (e != hipSuccess) return EE_ERR_DEVICE;
+                if (ir_pools) gap_fused = true;
                 k += ir_last;                                                    // the block's other layers are done
                 continue;
             }

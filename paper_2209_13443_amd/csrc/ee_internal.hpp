@@ -104,6 +104,7 @@ struct IrArgs {
     int B, H, W, Cin, Kx, Ce32, Cout, Ho, Wo, stride, pad;
     int sh_e, lo_e, hi_e, sh_d, lo_d, hi_d, sh_p, lo_p, hi_p, res_shift;
     const uint16_t* ys;  // bottleneck block only; not null: sample n of the output goes to slot ys[n] of y (device memory; B <= EE_ZC_MAX_B)
+    int* gap_sums;       // bottleneck block only; not null: also add the per-sample channel sums of the output into gap_sums[n][Cout]
 };
 
 struct DirectConvArgs {   // one thread per output element; any shape (correctness fallback)

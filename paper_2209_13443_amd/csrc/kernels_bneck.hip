@@ -37,7 +37,9 @@ constexpr int BN_BIAS_BYTES = 4 * (64 + 64 + 256);
 constexpr int BN_M2_BYTES = 4 * 1024;            // requantised second-layer outputs [pixel block][channel half][lane][16]
 constexpr int BN_SLOT_BYTES = 2 * EE_ZC_MAX_B;   // the output slot of every sample
 
-template <int K1, bool RES>    // reduction steps of the first layer: c_in / 32; the last layer adds a residual
+// K1: reduction steps of the first layer, c_in / 32; RES: the last layer adds a residual; GAP: the per-sample channel sums of the
+// output are also added into a.gap_sums (the exit head's pooling)
+template <int K1, bool RES, bool GAP>
 __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) void bneck_block_i8_kernel(IrArgs a, BnTile t)
 {
     constexpr int CIN = 32 * K1, CPP = 2 * K1;                         // 16-byte chunks per input pixel
@@ -99,12 +101,14 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     v4i_r w3[2][2], rr[2];                                              // operands [block][step]; the residual of the lane's pixel, 16 channels per block
     unsigned pix_y = 0;
     bool px_ok = false;
+    int gap_n = 0;                                                      // the sample of the tile in hand
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
         for (int k = 0; k < 2; ++k) w3[c][k] = *(const v4i_r*)((const unsigned char*)a.wp + ((size_t)((cb0 + c) * 2 + k) * 64 + lane) * 16);
     auto out_pixel = [&](const Cursor& cu) {                            // where the lane's pixel of that tile goes; its residual is requested
         const int n = cu.n;
+        gap_n = n;
         const int oy = 8 * cu.ty + 4 * pb + ty, ox = 8 * cu.tx + tx;
         px_ok = oy < a.H && ox < a.W;
         const int sp = px_ok ? (oy * a.W + ox) * 256 + cb0 * 32 + 16 * hi : 0;                  // < 2^31 with the sample: checked by the launcher
@@ -117,6 +121,13 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         }
         __builtin_amdgcn_sched_barrier(0);                              // requested here, not where the compiler finds its first use
     };
+    // pooling: one more matrix instruction with the packed outputs as the A operand (rows = pixels, reduction = channels) and
+    // the identity as B transposes the block: lane (channel, hi) then holds that channel's values of 16 pixels as integers
+    v4i_r ident = v4i_r{0, 0, 0, 0};
+    if constexpr (GAP) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ident[j] = (m >> 2) == 4 * hi + j ? 1 << (8 * (m & 3)) : 0;
+    }
     auto last_layer = [&](const v4i_r& d0, const v4i_r& d1) {           // the two reduction steps: channels 0-31 and 32-63 of the lane's pixel block
         __builtin_amdgcn_sched_barrier(0);                              // nothing of this moves into the first half
         v4i_r out[2];
@@ -142,6 +153,22 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         if (px_ok) {
             *(v4i_r*)((unsigned char*)a.y + pix_y) = out[0];
             *(v4i_r*)((unsigned char*)a.y + pix_y + 32) = out[1];
+        }
+        if constexpr (GAP) {
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const v4i_r o = px_ok ? out[c] : v4i_r{0, 0, 0, 0};     // pixels outside the image count nothing
+                v16i_r tr;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) tr[i] = 0;
+                tr = __builtin_amdgcn_mfma_i32_32x32x32_i8(o, ident, tr, 0, 0, 0);
+                int sum = 0;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sum += tr[i];
+                const auto both = __builtin_amdgcn_permlane32_swap((unsigned)sum, (unsigned)sum, false, false);   // the other 16 pixels
+                sum = (int)(both[0] + both[1]);
+                if (hi == 0) atomicAdd(a.gap_sums + (size_t)gap_n * 256 + (cb0 + c) * 32 + m, sum);       // integer sums: exact in any order
+            }
         }
     };
 
@@ -322,13 +349,13 @@ bool bneck_block_supported(const IrArgs& a)
     return bneck_block_plan(a, t);
 }
 
-template <int K1, bool RES>
+template <int K1, bool RES, bool GAP>
 static hipError_t bneck_launch(const IrArgs& a, const BnTile& t, hipStream_t s)
 {
-    static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&bneck_block_i8_kernel<K1, RES>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&bneck_block_i8_kernel<K1, RES, GAP>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (granted != hipSuccess) return granted;
     const size_t lds = (size_t)BN_BIAS_BYTES + 2 * (size_t)t.x_bytes + 2 * BN_M1_BYTES + BN_M2_BYTES + BN_SLOT_BYTES;
-    EE_LAUNCH((bneck_block_i8_kernel<K1, RES>), dim3((unsigned)(8 * t.nslots)), dim3(512), lds, s, a, t);
+    EE_LAUNCH((bneck_block_i8_kernel<K1, RES, GAP>), dim3((unsigned)(8 * t.nslots)), dim3(512), lds, s, a, t);
     return hipGetLastError();
 }
 
@@ -336,8 +363,12 @@ hipError_t launch_bneck_block(const IrArgs& a, hipStream_t s)
 {
     BnTile t;
     if (!bneck_block_plan(a, t)) return hipErrorInvalidValue;
-    if (a.res) return a.Cin == 64 ? bneck_launch<2, true>(a, t, s) : bneck_launch<8, true>(a, t, s);
-    return a.Cin == 64 ? bneck_launch<2, false>(a, t, s) : bneck_launch<8, false>(a, t, s);
+    if (a.gap_sums) {                                                   // the pooling variant is built with a residual only (the blocks that end a segment have one)
+        if (!a.res) return hipErrorInvalidValue;
+        return a.Cin == 64 ? bneck_launch<2, true, true>(a, t, s) : bneck_launch<8, true, true>(a, t, s);
+    }
+    if (a.res) return a.Cin == 64 ? bneck_launch<2, true, false>(a, t, s) : bneck_launch<8, true, false>(a, t, s);
+    return a.Cin == 64 ? bneck_launch<2, false, false>(a, t, s) : bneck_launch<8, false, false>(a, t, s);
 }
 
 }  // namespace ee

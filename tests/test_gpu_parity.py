@@ -550,6 +550,40 @@ def test_serve_stream_zero_copy_matches_oracle_and_copying(torch, ee, orc, case)
     eng.close()
 
 
+BN_SERVE_CASES = [  # h, w, c_in, seed, frac_bits, thresholds of the first two exits, lanes
+    (12, 10, 64, 3, 11, (0.782, 0.955), 1), (16, 16, 256, 5, 12, (0.8371, 0.8453), 2),
+]
+
+
+@pytest.mark.parametrize("case", BN_SERVE_CASES, ids=lambda c: "x".join(map(str, c[:4])) + f"_lanes{c[6]}")
+def test_serve_stream_with_fused_bottleneck_blocks(torch, ee, orc, case):
+    """Three segments of two bottleneck blocks each, served with every block fused: the block that ends a segment also pools
+    for the exit head and, with zero-copy compaction, writes its samples to their slots.  Results, statistics and events
+    equal the oracle's on the virtual clock with the fused blocks, without them, with and without zero-copy compaction."""
+    h, w, ci, seed, fb, thr, lanes = case
+    blob = W.bottleneck_net(h, w, ci, seed=seed, blocks=2, stages=3)
+    for e, t in zip(blob.exits, thr + (0.0,)):
+        e["thr"], e["frac_bits"] = t, fb
+    n, b_max = 96, 8
+    say(f"[case] serve bottleneck net {case}")
+    pool = W.input_pool(blob, n)
+    arrivals = (np.arange(n) * 150).astype(np.int64)
+    lut = synthetic_lut(blob.n_stages, b_max)
+    ref, rst, rev = orc.serve_stream(blob, arrivals, pool, b_max, lut, refill=2, lanes=lanes, max_events=5000)
+    assert np.all(np.bincount(ref["exit_idx"], minlength=3) > 0)           # every exit is taken
+    eng = ee.Engine(blob, b_max)
+    assert eng.ir_count() == 6 and eng.zero_copy_supported()              # the first block of a later segment reads slots and stays unfused when served zero-copy
+    assert eng.set_lanes(lanes) == lanes
+    dpool = dev(torch, pool)
+    for mode, zc in ((2, 1), (0, 1), (2, 0), (2, 1)):
+        eng.ir_mode(mode)
+        got, gst, gev = eng.serve_stream(arrivals, dpool, lut, clock=1, refill=2, lanes=lanes, max_events=5000, zero_copy=zc)
+        for f in ("exit_idx", "label", "score", "latency_ns"):
+            assert np.array_equal(got[f], ref[f]), (f, mode, zc)
+        assert gst == rst and np.array_equal(gev, rev)
+    eng.close()
+
+
 def test_zero_copy_is_refused_where_it_cannot_run(torch, ee, orc):
     blob = W.load_net("mobilenetv2_small_i8")                               # depthwise / thin layers at the segment boundaries
     eng = ee.Engine(blob, 8)

@@ -448,20 +448,22 @@ def inverted_residual_net(h, w, ci, ce, co, stride, seed=0, blocks=1):
     return blob
 
 
-def bottleneck_net(h, w, ci, seed=0, blocks=1, mid=64):
-    """One segment of `blocks` bottleneck blocks (1x1 to `mid` channels, 3x3 stride 1, 1x1 to 4 * mid channels with a residual:
+def bottleneck_net(h, w, ci, seed=0, blocks=1, mid=64, stages=1):
+    """`stages` segments (each with an exit) of `blocks` bottleneck blocks (1x1 to `mid` channels, 3x3 stride 1, 1x1 to 4 * mid channels with a residual:
     the block's input where it has 4 * mid channels, else a 1x1 convolution of it) on an h x w x ci input, int8: the fused-block
     kernel's shapes alone, for edge cases.  Data only."""
     net = _Net(DT_I8, h, w, ci, 10)
-    t = net.begin_stage()
     cin = ci
-    for _ in range(blocks):
-        short = t if cin == 4 * mid else net.conv(t, 4 * mid, 1, 1, 0, act="linear")
-        u = net.conv(t, mid, 1, 1, 0)
-        u = net.conv(u, mid, 3, 1, 1)
-        t = net.conv(u, 4 * mid, 1, 1, 0, res=short)
-        cin = 4 * mid
-    net.end_stage(t)
+    for _ in range(stages):
+        t = net.begin_stage()
+        for i in range(blocks):
+            # a segment behind the first starts with a convolution on its shortcut, as ResNet-50's groups do (the segment's input is then read by convolutions only)
+            short = t if cin == 4 * mid and not (stages > 1 and i == 0) else net.conv(t, 4 * mid, 1, 1, 0, act="linear")
+            u = net.conv(t, mid, 1, 1, 0)
+            u = net.conv(u, mid, 3, 1, 1)
+            t = net.conv(u, 4 * mid, 1, 1, 0, res=short)
+            cin = 4 * mid
+        net.end_stage(t)
     blob = _assemble(net, DT_I8, BASE_SEED + 0x7800 + seed)
     for op in blob.ops:
         if int(op["kind"]) == OP_CONV:
