@@ -100,14 +100,14 @@ def layer_table(args, ee, W, blob, dtype):
             row["us"], row["tops"], row["gbps"], row["roof_us"], 100 * row["roof_us"] / row["us"], row["cfg"]), file=sys.stderr, flush=True)
     blocks = []
     if args.layer < 0 and eng.ir_count() > 0:                     # inverted-residual blocks: the fused launch beside its three layers
-        for i in range(len(blob.ops) - 2):
+        for i in range(len(blob.ops) - 1):
             try:
                 r = eng.time_layer(i, B, 0x20000, reps=30)
             except ee.EEError:
                 continue                                          # the layer heads no block
             if r is None:
                 continue
-            span = 2 if int(blob.ops[i]["kind"]) == W.OP_DWCONV else 3      # a block without expansion is depthwise + projection
+            span = eng.ir_layers(i)                                # 2: depthwise + projection; 4: with the convolution on the shortcut in front
             sep = sum(x["us"] for x in rows if i <= x["layer"] < i + span)
             tab = eng.ir_table(i)
             blocks.append(dict(head=i, layers=span, fused_us=round(r[0], 2), separate_us=round(sep, 2), gbps=round(r[2] / r[0] / 1e3, 1), tops=round(r[1] / r[0] / 1e6, 1),

@@ -265,8 +265,16 @@ int ee_pair_set(ee_ctx* ctx, int layer, const int* cfg, int n);
  * block.  ee_ir_mode: 0 = never fuse, 1 = as the table says (default; nothing is fused until ee_autotune has timed the
  * fused launch against the three tuned layers per batch bucket, or a table was loaded), 2 = fuse every block.
  * ee_ir_table / ee_ir_set: the table of the block headed by `layer`, one entry per batch bucket, 1 = fused, 0 = separate
- * (ee_ir_set: EE_ERR_ARG when `layer` heads no block). */
+ * (ee_ir_set: EE_ERR_ARG when `layer` heads no block).
+ * Bottleneck blocks of the same three-layer shape (int8) go through the same switches and tables with a kernel of their own: a
+ * 1x1 stride-1 convolution from 64 or 256 to 64 channels, the 3x3 stride-1 convolution with padding 1 (64 -> 64) that alone
+ * reads it, and the 1x1 stride-1 convolution to 256 channels (with or without residual) that alone reads that; as a segment's
+ * last layers the launch also pools for the exit head and writes through the slot table of zero-copy compaction.  Where the
+ * residual is a 1x1 stride-1 convolution of the block's own 64-channel input and that convolution is the layer right in
+ * front of the block, the convolution heads a block of four layers, tuned against that convolution followed by the block of
+ * three.  ee_ir_layers: the number of layers of the block headed by `layer` (2, 3 or 4), 0 when it heads none. */
 int ee_ir_count(const ee_ctx* ctx);
+int ee_ir_layers(const ee_ctx* ctx, int layer);
 int ee_ir_mode(ee_ctx* ctx, int mode);
 int ee_ir_table(const ee_ctx* ctx, int layer, int* cfg_out, int n);
 int ee_ir_set(ee_ctx* ctx, int layer, const int* cfg, int n);

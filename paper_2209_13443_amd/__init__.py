@@ -24,7 +24,7 @@ EVENT_DT = np.dtype([("t_ns", "<i8"), ("kind", "<i4"), ("stage", "<i4"), ("b", "
 
 SYMBOLS = ["ee_strerror", "ee_blob_check", "ee_create", "ee_destroy", "ee_query", "ee_stage_forward", "ee_exit_head",
            "ee_compact_refill", "ee_serve_stream", "ee_schedule_sim", "ee_measure_lut", "ee_profile_enable",
-           "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_ir_count", "ee_ir_mode", "ee_ir_table", "ee_ir_set", "ee_last_logits", "ee_profile_reserve", "ee_autotune", "ee_config_table",
+           "ee_profile_read", "ee_kernel_name", "ee_exp2_table", "ee_tune_conv_tile", "ee_ir_count", "ee_ir_layers", "ee_ir_mode", "ee_ir_table", "ee_ir_set", "ee_last_logits", "ee_profile_reserve", "ee_autotune", "ee_config_table",
            "ee_pair_count", "ee_pair_mode", "ee_pair_table", "ee_config_set", "ee_pair_set", "ee_exit_head_static",
            "ee_static_scratch_bytes", "ee_time_layer", "ee_lanes", "ee_zero_copy_supported"]
 
@@ -80,6 +80,7 @@ _lib.ee_pair_table.argtypes = [_V, C.c_int, _V, C.c_int]
 _lib.ee_config_set.argtypes = [_V, C.c_int, _V, C.c_int]
 _lib.ee_pair_set.argtypes = [_V, C.c_int, _V, C.c_int]
 _lib.ee_ir_count.argtypes = [_V]
+_lib.ee_ir_layers.argtypes = [_V, C.c_int]
 _lib.ee_ir_mode.argtypes = [_V, C.c_int]
 _lib.ee_ir_table.argtypes = [_V, C.c_int, _V, C.c_int]
 _lib.ee_ir_set.argtypes = [_V, C.c_int, _V, C.c_int]
@@ -308,6 +309,13 @@ class Engine:
 
     def ir_count(self):
         n = _lib.ee_ir_count(self._h)
+        if n < 0:
+            _chk(n)
+        return n
+
+    def ir_layers(self, layer):
+        """layers of the fused block headed by `layer`, 0 when it heads none"""
+        n = _lib.ee_ir_layers(self._h, int(layer))
         if n < 0:
             _chk(n)
         return n

@@ -309,6 +309,36 @@ int pack_bneck(ee_ctx* ctx, const unsigned char* blob, const StageDesc& st, int 
     return EE_OK;
 }
 
+// A bottleneck block whose residual is a 1x1 convolution of the block's own input, that convolution being the layer right in front
+// of the block (the first block of a group): the convolution becomes the head of a block of four layers, run by the same kernel.
+int pack_bneck_shortcut(ee_ctx* ctx, const unsigned char* blob, const StageDesc& st, int k)
+{
+    if (k + 3 >= st.n_ops) return EE_OK;
+    OpPlan& p = ctx->plans[st.first_op + k];
+    const OpPlan& h = ctx->plans[st.first_op + k + 1];
+    const OpDesc& sc = p.d;
+    const OpDesc& c1 = h.d;
+    const OpDesc& c3 = ctx->plans[st.first_op + k + 3].d;
+    if (p.ir || !h.ir_bneck || h.ir_sc || sc.kind != OP_CONV) return EE_OK;
+    if (sc.kh != 1 || sc.kw != 1 || sc.stride != 1 || sc.pad != 0 || sc.pad_w != 0 || sc.res >= 0 || sc.c_tot != sc.c_out) return EE_OK;
+    if (sc.src != c1.src || sc.c_in != 64 || sc.c_out != c3.c_out || c3.res != sc.dst || sc.dst == st.out_tensor) return EE_OK;
+    int readers = 0;
+    for (int j = 0; j < st.n_ops; ++j) {
+        const OpDesc& o = ctx->plans[st.first_op + j].d;
+        readers += (o.src == sc.dst) + (o.res == sc.dst);
+    }
+    if (readers != 1) return EE_OK;
+    int rc = upload(ctx, &p.ir_ws, bn_operands(blob + sc.w_off, sc.c_out, sc.c_in));
+    if (!rc) rc = upload(ctx, &p.ir_bs, ir_rounded_bias(blob, sc, sc.c_out, sc.c_out));
+    if (rc) return rc;
+    p.ir_we = h.ir_we; p.ir_be = h.ir_be; p.ir_wd = h.ir_wd; p.ir_bd = h.ir_bd; p.ir_wp = h.ir_wp; p.ir_bp = h.ir_bp;
+    p.ir_kx = h.ir_kx; p.ir_ce32 = h.ir_ce32;
+    p.ir = true;
+    p.ir_bneck = true;
+    p.ir_sc = true;
+    return EE_OK;
+}
+
 // Assigns the intermediate tensors of every segment to a small pool of reusable buffers
 // (greedy by liveness); the segment input and output stay with the caller.
 void plan_buffers(ee_ctx* ctx)
@@ -324,7 +354,8 @@ void plan_buffers(ee_ctx* ctx)
             // output, so the input's buffer must stay reserved over both
             if (k > 0 && ctx->plans[st.first_op + k - 1].pair) last_use[ctx->plans[st.first_op + k - 1].d.src] = k;
             // likewise the head of a fused inverted-residual block, over its three layers
-            if (k > 1 && ctx->plans[st.first_op + k - 2].ir && !ctx->plans[st.first_op + k - 2].ir_noexp) last_use[ctx->plans[st.first_op + k - 2].d.src] = k;
+            if (k > 1 && ctx->plans[st.first_op + k - 2].ir && ctx->plans[st.first_op + k - 2].ir_last() == 2) last_use[ctx->plans[st.first_op + k - 2].d.src] = k;
+            if (k > 2 && ctx->plans[st.first_op + k - 3].ir_sc) last_use[ctx->plans[st.first_op + k - 3].d.src] = k;
             if (k > 0 && ctx->plans[st.first_op + k - 1].ir_noexp) last_use[ctx->plans[st.first_op + k - 1].d.src] = k;
         }
         buf[0] = BUF_EXT_IN;
@@ -515,6 +546,10 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
                 // likewise bottleneck blocks: 1x1 -> 3x3 (stride 1, padding 1) -> 1x1 (+ residual), each read only by the next
                 if (!ctx->plans[st.first_op + k].ir && (rc = pack_bneck(ctx, (const unsigned char*)blob, st, k))) return fail(rc);
             }
+    if (es == 1)
+        for (const StageDesc& st : ctx->net.stages)
+            for (int k = 0; k + 3 < st.n_ops; ++k)
+                if ((rc = pack_bneck_shortcut(ctx, (const unsigned char*)blob, st, k))) return fail(rc);
     plan_buffers(ctx);
     ctx->pool.resize(ctx->pool_sample_bytes.size(), nullptr);
     for (size_t i = 0; i < ctx->pool.size(); ++i)
@@ -711,12 +746,15 @@ hipError_t ee_ctx::launch_conv(int op, int b, const void* src, void* dst, const 
 void ee_ctx::fill_ir_args(int op, int b, IrArgs& a) const
 {
     const OpPlan& p = plans[(size_t)op];
-    const OpDesc& e = p.d;                                              // without expansion: the depthwise layer itself
-    const OpDesc& dw = plans[(size_t)op + (p.ir_noexp ? 0 : 1)].d;
-    const OpDesc& pr = plans[(size_t)op + (p.ir_noexp ? 1 : 2)].d;
+    const int o1 = p.ir_sc ? 1 : 0;                                     // the shortcut convolution in front: the block proper starts one layer on
+    const OpDesc& e = plans[(size_t)op + o1].d;                         // without expansion: the depthwise layer itself
+    const OpDesc& dw = plans[(size_t)op + o1 + (p.ir_noexp ? 0 : 1)].d;
+    const OpDesc& pr = plans[(size_t)op + o1 + (p.ir_noexp ? 1 : 2)].d;
     a.we = p.ir_we; a.be = (const int*)p.ir_be; a.wd = p.ir_wd; a.bd = (const int*)p.ir_bd; a.wp = p.ir_wp; a.bp = (const int*)p.ir_bp;
     a.B = b; a.H = e.h_in; a.W = e.w_in; a.Cin = e.c_in; a.Kx = p.ir_kx; a.Ce32 = p.ir_ce32; a.Cout = pr.c_out;
     a.ys = nullptr; a.gap_sums = nullptr;
+    a.ws = nullptr; a.bs = nullptr;
+    if (p.ir_sc) { a.ws = p.ir_ws; a.bs = (const int*)p.ir_bs; a.sh_s = p.d.shift; a.lo_s = p.d.lo; a.hi_s = p.d.hi; }
     a.Ho = dw.h_out; a.Wo = dw.w_out; a.stride = dw.stride; a.pad = dw.pad;
     a.sh_e = e.shift; a.lo_e = e.lo; a.hi_e = e.hi;
     a.sh_d = dw.shift; a.lo_d = dw.lo; a.hi_d = dw.hi;
@@ -827,36 +865,39 @@ extern "C" int ee_autotune(ee_ctx* ctx, int reps)
             if (!rc) p.pair_cfg = best;
         }
     }
-    // fused inverted-residual blocks: the one launch against the block's three layers with their tuned configurations
+    // fused blocks: the one launch against the block's layers with their tuned configurations.  A block of four layers (a
+    // convolution on the shortcut in front of a bottleneck block) is tuned after the others, against that convolution followed
+    // by whatever the table says for the block of three behind it.
     const int ir_was = ctx->ir_mode;
-    for (size_t s = 0; s < ctx->net.stages.size() && !rc; ++s) {
-        const StageDesc& st = ctx->net.stages[s];
-        for (int k = 0; k + 1 < st.n_ops && !rc; ++k) {
-            OpPlan& p = ctx->plans[st.first_op + k];
-            if (!p.ir) continue;
-            std::vector<int> best(buckets.size(), 0);
-            for (size_t bi = 0; bi < buckets.size() && !rc; ++bi) {
-                float ms[2] = {0.f, 0.f};
-                for (int fused = 0; fused < 2 && !rc; ++fused) {
-                    ctx->ir_mode = fused ? 2 : 0;
-                    p.ir_cfg.clear();
-                    auto block = [&]() -> int {                          // the block alone: its head runs all three layers when fused
-                        int r2 = ctx->run_stage((int)s, buckets[bi], ctx->in_buf[s], ctx->out_buf[s], false, -2 - (st.first_op + k));
-                        return r2;
-                    };
-                    if ((rc = block())) break;
-                    hipEventRecord(e0, ctx->stream);
-                    for (int r = 0; r < reps && !rc; ++r) rc = block();
-                    hipEventRecord(e1, ctx->stream);
-                    if (hipEventSynchronize(e1) != hipSuccess) rc = EE_ERR_DEVICE;
-                    hipEventElapsedTime(&ms[fused], e0, e1);
+    for (int pass = 0; pass < 2 && !rc; ++pass)
+        for (size_t s = 0; s < ctx->net.stages.size() && !rc; ++s) {
+            const StageDesc& st = ctx->net.stages[s];
+            for (int k = 0; k + 1 < st.n_ops && !rc; ++k) {
+                OpPlan& p = ctx->plans[st.first_op + k];
+                if (!p.ir || (pass == 1) != p.ir_sc) continue;
+                std::vector<int> best(buckets.size(), 0);
+                for (size_t bi = 0; bi < buckets.size() && !rc; ++bi) {
+                    float ms[2] = {0.f, 0.f};
+                    for (int fused = 0; fused < 2 && !rc; ++fused) {
+                        ctx->ir_mode = fused ? 2 : (p.ir_sc ? 1 : 0);
+                        p.ir_cfg.assign(buckets.size(), 0);                  // table mode: this head stays separate, the block behind it as tuned
+                        if (fused || !p.ir_sc) p.ir_cfg.clear();
+                        auto block = [&]() -> int {                          // the block alone: its head runs all its layers when fused
+                            return ctx->run_stage((int)s, buckets[bi], ctx->in_buf[s], ctx->out_buf[s], false, -2 - (st.first_op + k));
+                        };
+                        if ((rc = block())) break;
+                        hipEventRecord(e0, ctx->stream);
+                        for (int r = 0; r < reps && !rc; ++r) rc = block();
+                        hipEventRecord(e1, ctx->stream);
+                        if (hipEventSynchronize(e1) != hipSuccess) rc = EE_ERR_DEVICE;
+                        hipEventElapsedTime(&ms[fused], e0, e1);
+                    }
+                    best[bi] = ms[1] < ms[0] ? 1 : 0;
                 }
-                best[bi] = ms[1] < ms[0] ? 1 : 0;
+                ctx->ir_mode = ir_was;
+                if (!rc) p.ir_cfg = best;
             }
-            ctx->ir_mode = ir_was;
-            if (!rc) p.ir_cfg = best;
         }
-    }
     ctx->ir_mode = ir_was;
     hipEventDestroy(e0);
     hipEventDestroy(e1);
@@ -932,6 +973,13 @@ extern "C" int ee_ir_count(const ee_ctx* ctx)
     return n;
 }
 
+extern "C" int ee_ir_layers(const ee_ctx* ctx, int layer)
+{
+    if (!ctx || layer < 0 || layer >= (int)ctx->plans.size()) return EE_ERR_ARG;
+    const OpPlan& p = ctx->plans[(size_t)layer];
+    return p.ir ? p.ir_last() + 1 : 0;
+}
+
 extern "C" int ee_ir_mode(ee_ctx* ctx, int mode)
 {
     if (!ctx || mode < 0 || mode > 2) return EE_ERR_ARG;
@@ -984,7 +1032,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
     const int dt = net.dtype, es = net.elem_bytes();
     for (int k = 0; k < st.n_ops; ++k) {
         if (only_op >= 0 && st.first_op + k != only_op) continue;
-        if (only_block >= 0 && (st.first_op + k < only_block || st.first_op + k > only_block + (plans[(size_t)only_block].ir_noexp ? 1 : 2))) continue;
+        if (only_block >= 0 && (st.first_op + k < only_block || st.first_op + k > only_block + plans[(size_t)only_block].ir_last())) continue;
         OpPlan& p = plans[st.first_op + k];
         const OpDesc& d = p.d;
         const void* src = resolve(this, p.src_buf, act_in, act_out);
@@ -997,7 +1045,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
         const uint16_t* ys = p.dst_buf == BUF_EXT_OUT ? zc_out : nullptr;
         if ((xs || ys) && p.impl != IMPL_MFMA) return EE_ERR_UNSUPPORTED;
         if (zc_in && d.res >= 0 && p.res_buf == BUF_EXT_IN) return EE_ERR_UNSUPPORTED;
-        const int ir_last = p.ir_noexp ? 1 : 2;                             // the block's last layer, counted from this one
+        const int ir_last = p.ir_last();                                    // the block's last layer, counted from this one
         // a bottleneck block may sit in a segment whose last layer writes slots, and may be that layer (its kernel takes the slot table)
         const bool ir_slots_ok = p.ir_bneck ? !(zc_in && plans[st.first_op + k + ir_last].res_buf == BUF_EXT_IN) : !zc_out;
         // the exit head's pooling rides on the segment's last layer: a bottleneck block's kernel carries it (with a residual), the others do not
@@ -1012,7 +1060,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                 fill_ir_args(st.first_op + k, b, ia);
                 ia.x = src;
                 ia.y = resolve(this, q2.dst_buf, act_in, act_out);
-                ia.res = q2.d.res >= 0 ? resolve(this, q2.res_buf, act_in, act_out) : nullptr;
+                ia.res = q2.d.res >= 0 && !p.ir_sc ? resolve(this, q2.res_buf, act_in, act_out) : nullptr;   // the kernel computes the shortcut itself
                 ia.ys = q2.dst_buf == BUF_EXT_OUT ? zc_out : nullptr;
                 ia.gap_sums = ir_pools ? gap_fuse_dst : nullptr;
                 double f_ops = ops, f_bytes = bytes;                             // the block's layers; the tensors between them stay on chip
@@ -1319,7 +1367,7 @@ extern "C" int ee_time_layer(ee_ctx* ctx, int layer, int b, int cfg, int reps, d
     if (ops_out) *ops_out = p.ops_per_sample * b;
     if (bytes_out) *bytes_out = p.bytes_per_sample * b + p.weight_bytes;
     if (fused_block)                                                 // the block's layers; the tensors between them stay on chip
-        for (int j = 1; j <= (p.ir_noexp ? 1 : 2); ++j) {
+        for (int j = 1; j <= p.ir_last(); ++j) {
             const OpPlan& q = ctx->plans[layer + j];
             const OpDesc& prev = ctx->plans[layer + j - 1].d;
             if (ops_out) *ops_out += q.ops_per_sample * b;

@@ -105,6 +105,8 @@ struct IrArgs {
     int sh_e, lo_e, hi_e, sh_d, lo_d, hi_d, sh_p, lo_p, hi_p, res_shift;
     const uint16_t* ys;  // bottleneck block only; not null: sample n of the output goes to slot ys[n] of y (device memory; B <= EE_ZC_MAX_B)
     int* gap_sums;       // bottleneck block only; not null: also add the per-sample channel sums of the output into gap_sums[n][Cout]
+    const void* ws; const int* bs;   // bottleneck block only; not null: the residual is the 1x1 convolution of x with these operands and biases
+    int sh_s, lo_s, hi_s;            // (res is null then), requantised with these
 };
 
 struct DirectConvArgs {   // one thread per output element; any shape (correctness fallback)

@@ -38,12 +38,16 @@ constexpr int BN_M2_BYTES = 4 * 1024;            // requantised second-layer out
 constexpr int BN_SLOT_BYTES = 2 * EE_ZC_MAX_B;   // the output slot of every sample
 
 // K1: reduction steps of the first layer, c_in / 32; RES: the last layer adds a residual; GAP: the per-sample channel sums of the
-// output are also added into a.gap_sums (the exit head's pooling)
-template <int K1, bool RES, bool GAP>
+// output are also added into a.gap_sums (the exit head's pooling); SC: the residual is a 1x1 convolution of the block's input
+// (64 -> 256 channels, the shortcut of a group's first block), computed here from the staged pixels and requantised as that layer
+// would have written it (a third buffer keeps a tile's pixels until its last layer has run)
+template <int K1, bool RES, bool GAP, bool SC>
 __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) void bneck_block_i8_kernel(IrArgs a, BnTile t)
 {
     constexpr int CIN = 32 * K1, CPP = 2 * K1;                         // 16-byte chunks per input pixel
     constexpr int NCH = 100 * CPP, NL = (NCH + 511) / 512;             // chunks per tile, loads per lane (all eight wavefronts stage)
+    constexpr int NXB = SC ? 3 : 2;                                    // buffers of staged pixels
+    static_assert(!SC || (K1 == 2 && RES), "the shortcut convolution reads 64 channels and is the residual");
     extern __shared__ __attribute__((aligned(16))) unsigned char bn_lds[];
     const int tid = threadIdx.x, lane = tid & 63, m = lane & 31, hi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -58,13 +62,16 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     int* const l_b2 = l_b1 + 64;
     int* const l_b3 = l_b1 + 128;
     unsigned char* const l_x = bn_lds + BN_BIAS_BYTES;                  // two buffers of staged input pixels
-    unsigned char* const l_m1 = l_x + 2 * t.x_bytes;                    // two buffers of second-layer input
+    unsigned char* const l_m1 = l_x + NXB * t.x_bytes;                  // two buffers of second-layer input
     unsigned char* const l_m2 = l_m1 + 2 * BN_M1_BYTES;
     const unsigned short* const l_slot = (const unsigned short*)(l_m2 + BN_M2_BYTES);
+    int* const l_bs = (int*)(l_m2 + BN_M2_BYTES + BN_SLOT_BYTES);       // shortcut bias (SC)
+    const IrClamp cl_s = ir_clamp(a.sh_s, a.lo_s, a.hi_s);
     const IrClamp cl1 = ir_clamp(a.sh_e, a.lo_e, a.hi_e), cl2 = ir_clamp(a.sh_d, a.lo_d, a.hi_d), cl3 = ir_clamp(a.sh_p, a.lo_p, a.hi_p);
 
     if (tid < 64) { l_b1[tid] = a.be[tid]; l_b2[tid] = a.bd[tid]; }
     if (tid < 256) l_b3[tid] = a.bp[tid];
+    if constexpr (SC) { if (tid < 256) l_bs[tid] = a.bs[tid]; }
     if (a.ys && tid < a.B) ((unsigned short*)l_slot)[tid] = a.ys[tid];   // B <= EE_ZC_MAX_B <= 512 with a slot table: checked by the launcher
 
     // A workgroup's tiles are nslots apart: a tile's (sample, tile row, tile column) follows from the one before by additions
@@ -99,6 +106,20 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     const int cb0 = 4 * half + (front ? 2 : 0);                         // first of this wavefront's two output blocks
     const int ty = m >> 3, tx = m & 7;
     v4i_r w3[2][2], rr[2];                                              // operands [block][step]; the residual of the lane's pixel, 16 channels per block
+    v4i_r wsc[SC ? 2 : 1][2];                                           // the shortcut's operands [block][step]
+    if constexpr (SC) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int k = 0; k < 2; ++k) wsc[c][k] = *(const v4i_r*)((const unsigned char*)a.ws + ((size_t)((cb0 + c) * 2 + k) * 64 + lane) * 16);
+    }
+    const int xc_off = ((4 * pb + ty + 1) * 10 + tx + 1) * t.xp + 16 * hi;   // the lane's output pixel among the staged ones
+    int xb_out = NXB - 1, xb_l1 = 0, xb_st = 1;                         // buffers of tile it, it + 1, it + 2 (it = -1 at first)
+    auto next_buffers = [&] {
+        xb_out = xb_out + 1 == NXB ? 0 : xb_out + 1;
+        xb_l1 = xb_l1 + 1 == NXB ? 0 : xb_l1 + 1;
+        xb_st = xb_st + 1 == NXB ? 0 : xb_st + 1;
+    };
     unsigned pix_y = 0;
     bool px_ok = false;
     int gap_n = 0;                                                      // the sample of the tile in hand
@@ -114,7 +135,7 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         const int sp = px_ok ? (oy * a.W + ox) * 256 + cb0 * 32 + 16 * hi : 0;                  // < 2^31 with the sample: checked by the launcher
         const int slot_n = a.ys ? (int)l_slot[n] : n;                   // from LDS: a global load here would sit in front of every later wait
         pix_y = (unsigned)(slot_n * a.H * a.W * 256 + sp);
-        if constexpr (RES) {
+        if constexpr (RES && !SC) {
             const unsigned char* rp = (const unsigned char*)a.res + (unsigned)(n * a.H * a.W * 256 + sp);
             rr[0] = *(const v4i_r*)rp;                                  // unconditional and in range
             rr[1] = *(const v4i_r*)(rp + 32);
@@ -130,6 +151,17 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     }
     auto last_layer = [&](const v4i_r& d0, const v4i_r& d1) {           // the two reduction steps: channels 0-31 and 32-63 of the lane's pixel block
         __builtin_amdgcn_sched_barrier(0);                              // nothing of this moves into the first half
+        if constexpr (SC) {
+            const unsigned char* xc = l_x + xb_out * t.x_bytes + xc_off;
+            const v4i_r x0 = *(const v4i_r*)xc, x1 = *(const v4i_r*)(xc + 32);
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                v16i_r acc = bias16(l_bs, cb0 + c);
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wsc[c][0], x0, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wsc[c][1], x1, acc, 0, 0, 0);
+                rr[c] = ir_requant_pack(acc, cl_s);                     // 16 channels per lane in pixel order: what the layer would have stored
+            }
+        }
         v4i_r out[2];
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
@@ -213,7 +245,7 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     // (the requests go out behind the wavefront's matrix instructions of the first half, whose results take a while anyway:
     // at the top of the half all eight wavefronts would queue up at the memory pipeline with nothing else to issue)
     auto stage_write = [&](int it) {
-        if (it + 2 < T) x_store(l_x + (it & 1) * t.x_bytes);
+        if (it + 2 < T) x_store(l_x + xb_st * t.x_bytes);
         __builtin_amdgcn_sched_barrier(0);
     };
     auto stage_request = [&](int it) {
@@ -247,7 +279,7 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                 const int oy0 = 8 * c_l1.ty, ox0 = 8 * c_l1.tx;
                 advance(c_l1);
                 const bool in_img = hp < 100 && (unsigned)(oy0 - 1 + hy) < (unsigned)a.H && (unsigned)(ox0 - 1 + hx) < (unsigned)a.W;
-                const unsigned char* xb = l_x + ((it + 1) & 1) * t.x_bytes + xoff;
+                const unsigned char* xb = l_x + xb_l1 * t.x_bytes + xoff;
                 unsigned char* m1 = l_m1 + ((it + 1) & 1) * BN_M1_BYTES + m1off;
                 v16i_r acc0 = bias16(l_b1, 0), acc1 = bias16(l_b1, 1);
                 v4i_r b[K1];                                            // every operand requested before the first is used
@@ -269,6 +301,7 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             }
             __syncthreads();                                            // the halves of the second layer's output are in LDS
             if (it >= 0) last_layer(*(const v4i_r*)(l_m2 + ((pb * 2 + 0) * 64 + lane) * 16), *(const v4i_r*)(l_m2 + ((pb * 2 + 1) * 64 + lane) * 16));
+            next_buffers();
             __syncthreads();                                            // tile it + 1 is through the first layer, tile it + 2 is staged
         }
     } else {
@@ -320,6 +353,7 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                 const v4i_r other = *(const v4i_r*)(l_m2 + ((pb * 2 + (half ^ 1)) * 64 + lane) * 16);
                 last_layer(half ? other : dq, half ? dq : other);
             }
+            next_buffers();
             __syncthreads();
         }
     }
@@ -349,13 +383,13 @@ bool bneck_block_supported(const IrArgs& a)
     return bneck_block_plan(a, t);
 }
 
-template <int K1, bool RES, bool GAP>
+template <int K1, bool RES, bool GAP, bool SC = false>
 static hipError_t bneck_launch(const IrArgs& a, const BnTile& t, hipStream_t s)
 {
-    static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&bneck_block_i8_kernel<K1, RES, GAP>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&bneck_block_i8_kernel<K1, RES, GAP, SC>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (granted != hipSuccess) return granted;
-    const size_t lds = (size_t)BN_BIAS_BYTES + 2 * (size_t)t.x_bytes + 2 * BN_M1_BYTES + BN_M2_BYTES + BN_SLOT_BYTES;
-    EE_LAUNCH((bneck_block_i8_kernel<K1, RES, GAP>), dim3((unsigned)(8 * t.nslots)), dim3(512), lds, s, a, t);
+    const size_t lds = (size_t)BN_BIAS_BYTES + (SC ? 3 : 2) * (size_t)t.x_bytes + 2 * BN_M1_BYTES + BN_M2_BYTES + BN_SLOT_BYTES + (SC ? 1024 : 0);
+    EE_LAUNCH((bneck_block_i8_kernel<K1, RES, GAP, SC>), dim3((unsigned)(8 * t.nslots)), dim3(512), lds, s, a, t);
     return hipGetLastError();
 }
 
@@ -363,6 +397,10 @@ hipError_t launch_bneck_block(const IrArgs& a, hipStream_t s)
 {
     BnTile t;
     if (!bneck_block_plan(a, t)) return hipErrorInvalidValue;
+    if (a.ws) {                                                         // the residual is the shortcut convolution of the block's input
+        if (a.Cin != 64 || a.res) return hipErrorInvalidValue;
+        return a.gap_sums ? bneck_launch<2, true, true, true>(a, t, s) : bneck_launch<2, true, false, true>(a, t, s);
+    }
     if (a.gap_sums) {                                                   // the pooling variant is built with a residual only (the blocks that end a segment have one)
         if (!a.res) return hipErrorInvalidValue;
         return a.Cin == 64 ? bneck_launch<2, true, true>(a, t, s) : bneck_launch<8, true, true>(a, t, s);
