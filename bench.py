@@ -340,7 +340,7 @@ def run_stream(args, name, steps, warmup, full=True):
     roofline = None
     if conv["launches"]:
         achieved = conv["ops"] / (conv["ms"] * 1e-3) / 1e12
-        roofline = dict(bound="mfma", kernel="conv_igemm_kernel, conv_slab_kernel, conv_pair_kernel", achieved=round(achieved, 2), peak=PEAK[dtype],
+        roofline = dict(bound="mfma", kernel="conv_igemm_kernel, conv_slab_kernel, conv_pair_kernel, bneck_block_i8_kernel, ir_block_i8_kernel", achieved=round(achieved, 2), peak=PEAK[dtype],
                         unit="TOP/s" if dtype == "i8" else "TFLOP/s", frac=round(achieved / PEAK[dtype], 4), traffic=None,
                         launches=conv["launches"], avg_launch_us=round(conv["ms"] * 1e3 / conv["launches"], 2),
                         algorithmic_gops_per_launch=round(conv["ops"] / conv["launches"] / 1e9, 3),

@@ -233,11 +233,31 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         for (int i = 0; i < NL; ++i)
             if (512 * (i + 1) <= NCH || ldst[i] != ~0u) *(v4i_r*)(xb + ldst[i]) = st[i];     // only the last chunk may be missing
     };
-    // ---- prologue: the first tile's pixels to LDS, the second tile's requested ---------------------------------------
+    // ---- prologue: the role's weights (front: the first layer's operands [block][step]; back: [tap][step] of the 3x3 layer for
+    //      this half's 32 middle channels), requested in front of the first tile's pixels so that one wait covers both ---------
+    constexpr int NWR = 2 * K1 > 18 ? 2 * K1 : 18;
+    v4i_r wr[NWR];
+    if (front) {
+#pragma unroll
+        for (int k = 0; k < 2 * K1; ++k) wr[k] = *(const v4i_r*)((const unsigned char*)a.we + ((size_t)k * 64 + lane) * 16);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 18; ++k) wr[k] = *(const v4i_r*)((const unsigned char*)a.wd + ((size_t)(half * 18 + k) * 64 + lane) * 16);
+    }
     Cursor c_ld = first;                                                // the tile whose pixels are requested next
     x_load(c_ld);
     advance(c_ld);
     x_store(l_x);
+    // every weight has arrived before the loops, so that nothing inside them waits for a weight by count
+#pragma unroll
+    for (int k = 0; k < NWR; ++k)
+        if (k < 18 || front) asm volatile("" : "+v"(wr[k]));
+#pragma unroll
+    for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(w3[k >> 1][k & 1]));
+    if constexpr (SC) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(wsc[k >> 1][k & 1]));
+    }
     if (1 < T) x_load(c_ld);                                            // in flight over the first iteration
     advance(c_ld);
     // per iteration: tile it + 2, requested one iteration ago, goes into the buffer the first layer read one iteration ago
@@ -260,17 +280,7 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     if (front) {
         const int hp = 32 * wave + m, hpc = min(hp, 99), hy = hpc / 10, hx = hpc - 10 * hy;
         const int xoff = hpc * t.xp + 16 * hi, m1off = hy * BN_M1_ROW + hx * BN_M1_PX + 16 * hi;
-        v4i_r w1[2][K1];                                                // ready operands, 16 bytes per lane each: [block][step]
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-            for (int k = 0; k < K1; ++k) w1[c][k] = *(const v4i_r*)((const unsigned char*)a.we + ((size_t)(c * K1 + k) * 64 + lane) * 16);
         Cursor c_out = first, c_l1 = first;                             // the tiles of the last layer, of the first layer
-        // every weight has arrived before the loop, so that nothing inside it waits for them by count
-#pragma unroll
-        for (int k = 0; k < 2 * K1; ++k) asm volatile("" : "+v"(w1[k / K1][k % K1]));
-#pragma unroll
-        for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(w3[k >> 1][k & 1]));
         __syncthreads();                                                // biases and the first tile's pixels are in LDS
         for (int it = -1; it < T; ++it) {
             stage_write(it);
@@ -288,8 +298,8 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int k = 0; k < K1; ++k) {
-                    acc0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(w1[0][k], b[k], acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(w1[1][k], b[k], acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(wr[k], b[k], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(wr[K1 + k], b[k], acc1, 0, 0, 0);
                 }
                 stage_request(it);
                 v4i_r o0 = ir_requant_pack(acc0, cl1), o1 = ir_requant_pack(acc1, cl1);
@@ -306,14 +316,6 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         }
     } else {
         const int woff = (pb * 4 + ty) * BN_M1_ROW + tx * BN_M1_PX + 16 * hi;
-        v4i_r w2[18];                                                   // [tap][step] of this half's 32 middle channels
-#pragma unroll
-        for (int k = 0; k < 18; ++k) w2[k] = *(const v4i_r*)((const unsigned char*)a.wd + ((size_t)(half * 18 + k) * 64 + lane) * 16);
-        // every weight has arrived before the loop, so that nothing inside it waits for them by count
-#pragma unroll
-        for (int k = 0; k < 18; ++k) asm volatile("" : "+v"(w2[k]));
-#pragma unroll
-        for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(w3[k >> 1][k & 1]));
         __syncthreads();                                                // biases and the first tile's pixels are in LDS
         Cursor c_out = first;
         for (int it = -1; it < T; ++it) {
@@ -335,15 +337,15 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             for (int k = 0; k < 6; ++k) b1[k] = tap(6 + k);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int k = 0; k < 6; ++k) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w2[k], b0[k], acc, 0, 0, 0);
+            for (int k = 0; k < 6; ++k) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wr[k], b0[k], acc, 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int k = 0; k < 6; ++k) b0[k] = tap(12 + k);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int k = 0; k < 6; ++k) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w2[6 + k], b1[k], acc, 0, 0, 0);
+            for (int k = 0; k < 6; ++k) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wr[6 + k], b1[k], acc, 0, 0, 0);
 #pragma unroll
-            for (int k = 0; k < 6; ++k) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w2[12 + k], b0[k], acc, 0, 0, 0);
+            for (int k = 0; k < 6; ++k) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wr[12 + k], b0[k], acc, 0, 0, 0);
             stage_request(it);
             dq = ir_requant_pack(acc, cl2);
             *(v4i_r*)(l_m2 + ((pb * 2 + half) * 64 + lane) * 16) = dq;
