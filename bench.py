@@ -27,7 +27,7 @@ PEAK = {"i8": 5000.0, "bf16": 2500.0}          # dense MFMA peak of MI355X, TOP/
 HBM_PEAK = 8000.0                               # GB/s
 
 
-CONV_SOURCES = ("kernels_igemm.hip", "kernels_slab.hip", "kernels_pair.hip", "igemm_device.hpp", "igemm_epilogue.hpp")
+CONV_SOURCES = ("kernels_igemm.hip", "kernels_slab.hip", "kernels_pair.hip", "kernels_bneck.hip", "kernels_ir.hip", "igemm_device.hpp", "igemm_epilogue.hpp", "ir_device.hpp")
 
 
 def conv_sources_digest():
