@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libee.so")
-SOURCES = ["kernels_conv.hip", "kernels_igemm.hip", "kernels_pair.hip", "kernels_slab.hip", "kernels_thin.hip", "kernels_stream.hip", "kernels_ir.hip", "kernels_bneck.hip", "kernels_misc.hip", "net.cpp", "ee_api.cpp", "serve.cpp"]
+SOURCES = ["kernels_conv.hip", "kernels_igemm.hip", "kernels_pair.hip", "kernels_slab.hip", "kernels_thin.hip", "kernels_stream.hip", "kernels_ir.hip", "kernels_bneck.hip", "kernels_stem.hip", "kernels_misc.hip", "net.cpp", "ee_api.cpp", "serve.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",     # no packed-FP32 code generation
          "-Wall", "-Wno-unused-value", "-Wno-unused-function", "-Wno-unused-command-line-argument"]

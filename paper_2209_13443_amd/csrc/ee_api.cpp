@@ -356,7 +356,7 @@ void plan_buffers(ee_ctx* ctx)
             // likewise the head of a fused inverted-residual block, over its three layers
             if (k > 1 && ctx->plans[st.first_op + k - 2].ir && ctx->plans[st.first_op + k - 2].ir_last() == 2) last_use[ctx->plans[st.first_op + k - 2].d.src] = k;
             if (k > 2 && ctx->plans[st.first_op + k - 3].ir_sc) last_use[ctx->plans[st.first_op + k - 3].d.src] = k;
-            if (k > 0 && ctx->plans[st.first_op + k - 1].ir_noexp) last_use[ctx->plans[st.first_op + k - 1].d.src] = k;
+            if (k > 0 && (ctx->plans[st.first_op + k - 1].ir_noexp || ctx->plans[st.first_op + k - 1].ir_stem)) last_use[ctx->plans[st.first_op + k - 1].d.src] = k;
         }
         buf[0] = BUF_EXT_IN;
         buf[st.out_tensor] = BUF_EXT_OUT;
@@ -550,6 +550,26 @@ extern "C" int ee_create(const void* blob, size_t bytes, int b_max, int dtype, v
         for (const StageDesc& st : ctx->net.stages)
             for (int k = 0; k + 3 < st.n_ops; ++k)
                 if ((rc = pack_bneck_shortcut(ctx, (const unsigned char*)blob, st, k))) return fail(rc);
+    // the folded first convolution with the max-pool that alone reads it (nothing to pack: the kernel takes the layer's own weights)
+    if (es == 1)
+        for (const StageDesc& st : ctx->net.stages)
+            for (int k = 0; k + 1 < st.n_ops; ++k) {
+                OpPlan& p = ctx->plans[st.first_op + k];
+                const OpDesc& c = p.d;
+                const OpDesc& q = ctx->plans[st.first_op + k + 1].d;
+                if (p.ir || p.impl != IMPL_MFMA_S2D || c.res >= 0 || c.dst == st.out_tensor || q.kind != OP_MAXPOOL || q.src != c.dst) continue;
+                if (q.kh != 3 || q.kw != 3 || q.stride != 2 || q.pad != 1 || q.pad_w != 1 || q.c_tot != q.c_out || q.c_off != 0 || q.dst == st.out_tensor) continue;
+                int readers = 0;
+                for (int j = 0; j < st.n_ops; ++j) {
+                    const OpDesc& o = ctx->plans[st.first_op + j].d;
+                    readers += (o.src == c.dst) + (o.res == c.dst);
+                }
+                ConvArgs probe{};
+                ctx->fill_conv_args(st.first_op + k, b_max, probe);
+                if (readers != 1 || !stem_pool_supported(probe, q.h_out, q.w_out)) continue;
+                p.ir = true;
+                p.ir_stem = true;
+            }
     plan_buffers(ctx);
     ctx->pool.resize(ctx->pool_sample_bytes.size(), nullptr);
     for (size_t i = 0; i < ctx->pool.size(); ++i)
@@ -1047,13 +1067,32 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
         if (zc_in && d.res >= 0 && p.res_buf == BUF_EXT_IN) return EE_ERR_UNSUPPORTED;
         const int ir_last = p.ir_last();                                    // the block's last layer, counted from this one
         // a bottleneck block may sit in a segment whose last layer writes slots, and may be that layer (its kernel takes the slot table)
-        const bool ir_slots_ok = p.ir_bneck ? !(zc_in && plans[st.first_op + k + ir_last].res_buf == BUF_EXT_IN) : !zc_out;
+        // (the fused first convolution + pool writes inside the segment: slots do not concern it)
+        const bool ir_slots_ok = p.ir_bneck ? !(zc_in && plans[st.first_op + k + ir_last].res_buf == BUF_EXT_IN) : p.ir_stem || !zc_out;
         // the exit head's pooling rides on the segment's last layer: a bottleneck block's kernel carries it (with a residual), the others do not
         const bool ir_pools = gap_fuse_dst && only_op < 0 && st.first_op + k + ir_last == gap_fuse_op[(size_t)stage];
         if (p.ir && ir_mode > 0 && cfg_force == 0 && forced_conv_tile() == 0 && only_op < 0 && !xs && ir_slots_ok &&
             !(ir_pools && !(p.ir_bneck && plans[st.first_op + k + ir_last].d.res >= 0))) {
             // this layer, the depthwise layer and the projection as one launch, where the table says it is faster
             const int ic = p.ir_cfg.empty() ? 0 : p.ir_cfg[std::min<size_t>(bucket_of(b), p.ir_cfg.size() - 1)];
+            if ((ic != 0 || ir_mode == 2) && p.ir_stem) {
+                const OpPlan& q2 = plans[st.first_op + k + 1];
+                if (!(first_packed && k == 0)) {                                 // the folded copy of the input, as in front of the layer alone
+                    const double pb = (double)b * ((double)d.h_in * d.w_in * d.c_in + (double)p.Hp * p.Wp * 16) * es;
+                    e = timed(EE_K_PAD_INPUT, 0.0, pb, [&] { return launch_space_to_depth(src, pad_bufs[p.pad_buf], nullptr, b, d.h_in, d.w_in, d.c_in, p.Hp, p.Wp, d.pad, dt, stream); });
+                    if (e != hipSuccess) return EE_ERR_DEVICE;
+                }
+                ConvArgs ca{};
+                fill_conv_args(st.first_op + k, b, ca);
+                ca.x = pad_bufs[p.pad_buf]; ca.mode = 0;
+                void* yq = resolve(this, q2.dst_buf, act_in, act_out);
+                const double mid = 2.0 * b * (double)d.h_out * d.w_out * d.c_out;      // the tensor that stays on chip
+                e = timed(EE_K_CONV_STREAM, ops + q2.ops_per_sample * b, bytes + q2.bytes_per_sample * b + q2.weight_bytes - mid,
+                          [&] { return launch_stem_pool(ca, yq, q2.d.h_out, q2.d.w_out, stream); }, st.first_op + k);
+                if (e != hipSuccess) return EE_ERR_DEVICE;
+                ++k;                                                             // the pool is done
+                continue;
+            }
             if (ic != 0 || ir_mode == 2) {
                 const OpPlan& q2 = plans[st.first_op + k + ir_last];
                 IrArgs ia{};

@@ -31,7 +31,8 @@ struct OpPlan {
     bool ir_bneck = false;      // the block is a bottleneck block (1x1 -> 3x3 -> 1x1): its own kernel, the same table and switches
     bool ir_sc = false;         // a bottleneck block with the 1x1 convolution on its shortcut in front: this layer is that convolution (four layers)
     void* ir_ws = nullptr; void* ir_bs = nullptr;
-    int ir_last() const { return ir_noexp ? 1 : ir_sc ? 3 : 2; }       // the block's last layer, counted from its head
+    bool ir_stem = false;       // this layer is a folded stride-2 first convolution and the 3x3 / 2 max-pool behind it can run in the same launch (two layers)
+    int ir_last() const { return ir_noexp || ir_stem ? 1 : ir_sc ? 3 : 2; }   // the block's last layer, counted from its head
     std::vector<int> ir_cfg;    // per batch bucket: 1 = the fused launch, 0 = the three layers separately; empty = not tuned
     void* ir_we = nullptr; void* ir_be = nullptr; void* ir_wd = nullptr; void* ir_bd = nullptr; void* ir_wp = nullptr; void* ir_bp = nullptr;
     int ir_kx = 0, ir_ce32 = 0;

@@ -174,6 +174,10 @@ int ir_block_out_blocks(int c_out);            // blocks of 32 output channels t
 hipError_t launch_ir_block(const IrArgs& a, hipStream_t s);
 // bottleneck block (1x1 -> 3x3 -> 1x1 + residual) in one launch; the same argument block: we / be, wd / bd, wp / bp are the three
 // layers' operands and biases, Kx = Cin, Ce32 = the middle channels
+// first convolution (folded stride-2 layer, 4 x 4 taps over 16-channel super-pixels, 64 output channels: a as for the streaming
+// kernel, a.y unused) and the 3x3 / 2 max-pool with padding 1 behind it in one launch; yq: the pooled output [B][Hq][Wq][64]
+bool stem_pool_supported(const ConvArgs& a, int Hq, int Wq);
+hipError_t launch_stem_pool(const ConvArgs& a, void* yq, int Hq, int Wq, hipStream_t s);
 bool bneck_block_supported(const IrArgs& a);
 hipError_t launch_bneck_block(const IrArgs& a, hipStream_t s);
 hipError_t launch_maxpool(const PoolArgs& a, int dtype, hipStream_t s);

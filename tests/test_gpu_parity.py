@@ -562,6 +562,32 @@ def test_serve_stream_zero_copy_matches_oracle_and_copying(torch, ee, orc, case)
     eng.close()
 
 
+STEM_CASES = [(224, 224, 5), (57, 80, 7), (32, 32, 7), (17, 16, 3), (7, 16, 2), (114, 56, 9), (9, 48, 4)]      # h, w, samples (h * w a multiple of 16: whole 16-byte chunks per input sample)
+
+
+@pytest.mark.parametrize("case", STEM_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_fused_first_convolution_and_pool_equal_separate_layers_and_oracle(torch, ee, orc, case):
+    """7x7 / 2 convolution and 3x3 / 2 max-pool as one launch: images whose pooled size is and is not whole tiles of 14 x 4, odd
+    sizes (the last pooled row or column sees one convolution row or column only), a pooled image smaller than a tile, extreme
+    inputs; against the oracle and against the two separate layers, bit for bit."""
+    h, w, n = case
+    blob = W.stem_net(h, w, seed=h + w)
+    say(f"[case] first convolution + pool on {h}x{w}, {n} samples")
+    r = np.random.default_rng(h * 100 + w)
+    x = np.concatenate([np.full((1, h, w, 3), -128, np.int8), np.full((1, h, w, 3), 127, np.int8),
+                        r.integers(-128, 128, size=(max(n - 2, 1), h, w, 3), dtype=np.int8)])[:n]
+    eng = ee.Engine(blob, max(n, 2))
+    assert eng.ir_count() == 1 and eng.ir_layers(0) == 2
+    for b in sorted({n, 1}, reverse=True):
+        ref = orc.stage_forward(blob, 0, x[:b])
+        for mode in (2, 0, 2):
+            eng.ir_mode(mode)
+            got = host(eng.stage_forward(0, dev(torch, x[:b]), ref.shape[1:]), ref)
+            assert np.array_equal(got, ref), f"mode {mode} b={b}: {np.count_nonzero(got != ref)} of {ref.size} differ, first at {np.argwhere(got != ref)[:3].tolist()}"
+    assert np.unique(ref).size > 8
+    eng.close()
+
+
 BN_SERVE_CASES = [  # h, w, c_in, seed, frac_bits, thresholds of the first two exits, lanes
     (12, 10, 64, 3, 11, (0.782, 0.955), 1), (16, 16, 256, 5, 12, (0.8371, 0.8453), 2),
 ]

@@ -448,6 +448,24 @@ def inverted_residual_net(h, w, ci, ce, co, stride, seed=0, blocks=1):
     return blob
 
 
+def stem_net(h, w, seed=0):
+    """The first layers of a ResNet-style network alone on an h x w x 3 input, int8: 7x7 stride-2 convolution to 64 channels, 3x3 stride-2
+    max-pool, and a 1x1 convolution to 32 channels as the segment's output: the fused first-layer kernel's shapes, for edge cases.  Data only."""
+    net = _Net(DT_I8, h, w, 3, 10)
+    t = net.begin_stage()
+    t = net.conv(t, 64, 7, 2, 3)
+    t = net.maxpool(t, 3, 2, 1)
+    net.end_stage(net.conv(t, 32, 1, 1, 0))
+    blob = _assemble(net, DT_I8, BASE_SEED + 0x7c00 + seed)
+    for op in blob.ops:
+        if int(op["kind"]) == OP_CONV:
+            fan_in = int(op["c_in"]) * int(op["kh"]) * int(op["kw"])
+            op["shift"] = max(0, int(math.ceil(math.log2(2.0 * 74 * 40 * math.sqrt(fan_in) / 127))))
+    for e in blob.exits:
+        e["frac_bits"], e["thr"] = 10, 0.5
+    return blob
+
+
 def bottleneck_net(h, w, ci, seed=0, blocks=1, mid=64, stages=1):
     """`stages` segments (each with an exit) of `blocks` bottleneck blocks (1x1 to `mid` channels, 3x3 stride 1, 1x1 to 4 * mid channels with a residual:
     the block's input where it has 4 * mid channels, else a 1x1 convolution of it) on an h x w x ci input, int8: the fused-block
