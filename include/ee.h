@@ -272,7 +272,10 @@ int ee_pair_set(ee_ctx* ctx, int layer, const int* cfg, int n);
  * last layers the launch also pools for the exit head and writes through the slot table of zero-copy compaction.  Where the
  * residual is a 1x1 stride-1 convolution of the block's own 64-channel input and that convolution is the layer right in
  * front of the block, the convolution heads a block of four layers, tuned against that convolution followed by the block of
- * three.  ee_ir_layers: the number of layers of the block headed by `layer` (2, 3 or 4), 0 when it heads none. */
+ * three.  The same switches and tables cover the first layers of a ResNet-style network (int8): a 7x7 stride-2 convolution
+ * of a 3-channel image to 64 channels and the 3x3 stride-2 max-pool with padding 1 that alone reads it run as one launch (a block
+ * of two layers headed by the convolution).  ee_ir_layers: the number of layers of the block headed by `layer` (2, 3 or 4), 0
+ * when it heads none. */
 int ee_ir_count(const ee_ctx* ctx);
 int ee_ir_layers(const ee_ctx* ctx, int layer);
 int ee_ir_mode(ee_ctx* ctx, int mode);
