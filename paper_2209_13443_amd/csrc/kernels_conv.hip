@@ -485,6 +485,56 @@ __global__ __launch_bounds__(256) void space_to_depth_rows_kernel(IdTab, const T
     }
 }
 
+// The same for int8 images of 3 channels whose rows are whole 16-byte chunks (the networks' input): the 2 RS image rows under RS folded
+// rows are one contiguous piece of the image, copied with 16-byte loads into LDS rows that have 16 zero bytes in front and 48 behind
+// (rows in the padding are zero), so that pixels left and right of the image read as zeros without a test.  A lane then builds two
+// neighbouring super-pixels: four pixels are 12 contiguous bytes of an image row, read as four dwords around them, shifted into place
+// and spread to 4 bytes per pixel with byte permutes.
+template <int RS>
+__global__ __launch_bounds__(256) void space_to_depth_rows_c3_kernel(IdTab, const signed char* x, signed char* y, const int32_t* gather, int by_value, int H, int W, int Hs, int Ws, int pad)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char s2d3_lds[];
+    typedef int v4i_ __attribute__((ext_vector_type(4)));
+    const int ys0 = blockIdx.x * RS, n = blockIdx.y, tid = threadIdx.x;
+    const __attribute__((address_space(4))) int* tab = (const __attribute__((address_space(4))) int*)__builtin_amdgcn_kernarg_segment_ptr();
+    const long long row = by_value ? tab[n] : (gather ? gather[n] : n);
+    const int row_bytes = 3 * W, pitch = row_bytes + 64, row_chunks = row_bytes >> 4, pitch_chunks = pitch >> 4;
+    const unsigned char* img = (const unsigned char*)x + row * H * row_bytes;
+    // rows r of the 2 RS staged ones that lie inside the image: [ra, rb)
+    const int iy_first = 2 * ys0 - pad;
+    const int ra = min(max(-iy_first, 0), 2 * RS), rb = max(min(H - iy_first, 2 * RS), ra);
+    // margins and padding rows: every chunk that the copy below does not write
+    for (int c = tid; c < 2 * RS * pitch_chunks; c += 256) {
+        const int r = c / pitch_chunks, w = c - r * pitch_chunks;
+        if (r < ra || r >= rb || w == 0 || w > row_chunks) *(v4i_*)(s2d3_lds + c * 16) = v4i_{0, 0, 0, 0};
+    }
+    const unsigned char* first = img + (long long)(iy_first + ra) * row_bytes;
+    for (int c = tid; c < (rb - ra) * row_chunks; c += 256) {
+        const int r = c / row_chunks, w = c - r * row_chunks;
+        *(v4i_*)(s2d3_lds + (ra + r) * pitch + 16 + 16 * w) = *(const v4i_*)(first + (long long)c * 16);
+    }
+    __syncthreads();
+    const int pairs = (Ws + 1) >> 1;
+    if (tid >= RS * pairs) return;
+    const int rr = tid / pairs, xs = 2 * (tid - rr * pairs), ys = ys0 + rr;
+    if (ys >= Hs) return;
+    unsigned px[2][4];                                                  // [image row of the pair][pixel]: 3 channels and a zero byte
+#pragma unroll
+    for (int dy = 0; dy < 2; ++dy) {
+        const int at = (2 * rr + dy) * pitch + 16 + 3 * (2 * xs - pad);   // first byte of the four pixels (>= 0: pad <= 5)
+        const unsigned* wp = (const unsigned*)(s2d3_lds + (at & ~3));
+        const unsigned w0 = wp[0], w1 = wp[1], w2 = wp[2], w3 = wp[3], sh = (unsigned)(at & 3) * 8;
+        const unsigned d0 = __builtin_amdgcn_alignbit(w1, w0, sh), d1 = __builtin_amdgcn_alignbit(w2, w1, sh), d2 = __builtin_amdgcn_alignbit(w3, w2, sh);
+        px[dy][0] = d0 & 0x00ffffffu;
+        px[dy][1] = __builtin_amdgcn_perm(d1, d0, 0x0c050403u);         // bytes 3, 4, 5 of the twelve
+        px[dy][2] = __builtin_amdgcn_perm(d2, d1, 0x0c040302u);         // bytes 6, 7, 8
+        px[dy][3] = d2 >> 8;                                            // bytes 9, 10, 11
+    }
+    signed char* q = y + (((long long)n * Hs + ys) * Ws + xs) * 16;
+    *(v4i_*)q = v4i_{(int)px[0][0], (int)px[0][1], (int)px[1][0], (int)px[1][1]};
+    if (xs + 1 < Ws) *(v4i_*)(q + 16) = v4i_{(int)px[0][2], (int)px[0][3], (int)px[1][2], (int)px[1][3]};
+}
+
 hipError_t launch_space_to_depth(const void* x, void* y, const int32_t* gather, int B, int H, int W, int C, int Hs, int Ws, int pad, int dtype, hipStream_t s, bool gather_on_host)
 {
     const long long total = (long long)B * Hs * Ws;
@@ -497,6 +547,11 @@ hipError_t launch_space_to_depth(const void* x, void* y, const int32_t* gather, 
         IdTab tab{};
         const bool host_ids = gather_on_host && gather && B <= 256;      // ids the host can read: by value
         if (host_ids) std::memcpy(tab.id, gather, sizeof(int32_t) * (size_t)B);
+        if (dtype == EE_I8 && C == 3 && row_bytes % 16 == 0 && ((uintptr_t)x & 15) == 0 && pad >= 0 && pad <= 5 && RS * ((Ws + 1) / 2) <= 256 &&
+            2 * RS * (row_bytes + 64) <= 64 * 1024 && Ws <= (W + 2 * pad + 1) / 2 + 1) {
+            EE_LAUNCH((space_to_depth_rows_c3_kernel<RS>), grid, dim3(256), 2 * RS * (row_bytes + 64), s, tab, (const signed char*)x, (signed char*)y, gather, (int)host_ids, H, W, Hs, Ws, pad);
+            return hipGetLastError();
+        }
         if (dtype == EE_I8)
             EE_LAUNCH((space_to_depth_rows_kernel<signed char, RS>), grid, dim3(256), 2 * RS * row_bytes, s, tab, (const signed char*)x, (signed char*)y, gather, (int)host_ids, H, W, C, Hs, Ws, pad);
         else
