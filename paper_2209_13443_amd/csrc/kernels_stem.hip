@@ -4,8 +4,9 @@
 // once for a quarter of its size to come out of the pool; here it only exists in LDS, a tile at a time.
 //
 // A workgroup (4 wavefronts) walks over tiles of 14 x 8 pooled pixels of one image.  The 29 x 17 convolution outputs under a tile's
-// windows are computed in 16 strips of 32, four per wavefront, as in the streaming kernel: weights and bias in registers for good, the activation
-// operands straight from global memory (a strip ahead), 16 matrix instructions per strip, requantisation, and the strip's pixels
+// windows are computed in 16 strips of 32, four per wavefront, as in the streaming kernel: weights in registers for good, the activation
+// operands straight from global memory, requested two strips ahead through four sets of registers (also across the pooling and into the
+// next tile: a strip's operands come out of L2 in about the time two strips take), 16 matrix instructions per strip, requantisation, and the strip's pixels
 // go to the tile's LDS image -- the smallest int8 value where the convolution has no output (the pool's padding: every window
 // has at least one pixel that exists).  After a barrier the lanes take (pooled pixel, 16 channels) items, 448 per tile: nine 16-byte
 // LDS reads, byte-wise maximum on 16-bit halves, one 16-byte store.  A seventh of the convolution is computed twice (the windows'
@@ -62,18 +63,18 @@ __global__ __launch_bounds__(256, 2) void stem_pool_i8_kernel(ConvArgs a, void* 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const unsigned char* wb = (const unsigned char*)a.w;
     v4i_r wreg[NT][NKB];
-    v16i_r breg[NT];                                                    // bias in the accumulator layout (rounding constant included)
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
+    for (int j = 0; j < NT; ++j)
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb) wreg[j][kb] = *(const v4i_r*)(wb + (size_t)(32 * j + p) * a.Kp + kb * 32 + 16 * hi);
+    int* const l_bias = (int*)(stem_lds + ST_RPIX * ST_PITCH);         // 64 biases behind the tile's image (rounding constant included)
+    if (tid < 64) l_bias[tid] = ((const int*)a.bias)[tid];
+    // every weight has arrived before the loop, so that nothing inside it waits for a weight by count
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const v4i_r b4 = *(const v4i_r*)((const int*)a.bias + 32 * j + 8 * g + 4 * hi);
+    for (int j = 0; j < NT; ++j)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) breg[j][4 * g + e] = b4[e];
-        }
-    }
+        for (int kb = 0; kb < NKB; ++kb) asm volatile("" : "+v"(wreg[j][kb]));
+    __syncthreads();
     const IrClamp cl = ir_clamp(a.shift, a.lo, a.hi);
     const int tpi = t.tiles_x * t.tiles_y;
     // pooling: this lane's items (pooled pixel, channels): tid and tid + 256
@@ -86,49 +87,71 @@ __global__ __launch_bounds__(256, 2) void stem_pool_i8_kernel(ConvArgs a, void* 
         poff[i] = ((2 * pty[i]) * ST_RW + 2 * ptx[i]) * ST_PITCH + 16 * pch;
     }
 
-    for (int u = blockIdx.x; u < t.total; u += gridDim.x) {             // the same trip count for the whole workgroup
-        const int n = u / tpi, r0 = u - n * tpi, tyi = r0 / t.tiles_x, txi = r0 - tyi * t.tiles_x;
-        const int py0 = ST_TH * tyi, px0 = ST_TW * txi;
-        const int cy0 = 2 * py0 - 1, cx0 = 2 * px0 - 1;                 // the first convolution output under the tile
-        const unsigned char* xn = (const unsigned char*)a.x + (size_t)n * a.H * a.W * 16;
-        auto load_strip = [&](int s, v4i_r* xr) {                       // unconditional and in range; the folded input carries its own padding
-            const int r = min(32 * s + p, ST_RPIX - 1), ry = r / ST_RW, rx = r - ry * ST_RW;
-            const int cy = min(max(cy0 + ry, 0), a.Ho - 1), cx = min(max(cx0 + rx, 0), a.Wo - 1);
+    struct Tile { int n, py0, px0; };
+    auto tile_at = [&](int u) {
+        const int n = u / tpi, r0 = u - n * tpi, tyi = r0 / t.tiles_x;
+        return Tile{n, ST_TH * tyi, ST_TW * (r0 - tyi * t.tiles_x)};
+    };
+    auto load_strip = [&](const Tile& tl, int s, v4i_r* xr) {           // unconditional and in range; the folded input carries its own padding
+        const unsigned char* xn = (const unsigned char*)a.x + (size_t)tl.n * a.H * a.W * 16;
+        const int r = min(32 * s + p, ST_RPIX - 1), ry = r / ST_RW, rx = r - ry * ST_RW;
+        const int cy = min(max(2 * tl.py0 - 1 + ry, 0), a.Ho - 1), cx = min(max(2 * tl.px0 - 1 + rx, 0), a.Wo - 1);
+        // the four rows and four columns under the clamped output are inside the folded image (it has three rows and columns more than
+        // the convolution's output: checked by the launcher), so the eight operands lie at fixed offsets from the first
+        const unsigned char* first = xn + (unsigned)((cy * a.W + cx + hi) * 16);
+        const unsigned row = (unsigned)a.W * 16;
 #pragma unroll
-            for (int kb = 0; kb < NKB; ++kb) {
-                const int iy = min(cy + (kb >> 1), a.H - 1), ix = min(cx + 2 * (kb & 1) + hi, a.W - 1);
-                xr[kb] = *(const v4i_r*)(xn + (unsigned)((iy * a.W + ix) * 16));
+        for (int kb = 0; kb < NKB; ++kb) xr[kb] = *(const v4i_r*)(first + (kb >> 1) * row + (kb & 1) * 32);
+    };
+    auto compute_strip = [&](const Tile& tl, int s, const v4i_r* xr) {
+        const int r = 32 * s + p, rc = min(r, ST_RPIX - 1), ry = rc / ST_RW, rx = rc - ry * ST_RW;
+        const bool exists = (unsigned)(2 * tl.py0 - 1 + ry) < (unsigned)a.Ho && (unsigned)(2 * tl.px0 - 1 + rx) < (unsigned)a.Wo;
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            v16i_r acc;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const v4i_r b4 = *(const v4i_r*)(l_bias + 32 * j + 8 * g + 4 * hi);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[4 * g + e] = b4[e];
             }
-        };
-        auto compute_strip = [&](int s, const v4i_r* xr) {
-            const int r = 32 * s + p, rc = min(r, ST_RPIX - 1), ry = rc / ST_RW, rx = rc - ry * ST_RW;
-            const bool exists = (unsigned)(cy0 + ry) < (unsigned)a.Ho && (unsigned)(cx0 + rx) < (unsigned)a.Wo;
 #pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                v16i_r acc = breg[j];
-#pragma unroll
-                for (int kb = 0; kb < NKB; ++kb) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wreg[j][kb], xr[kb], acc, 0, 0, 0);
-                v4i_r o = ir_requant_pack(acc, cl);
-                if (!exists) o = v4i_r{(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
-                if (r < ST_RPIX) *(v4i_r*)(stem_lds + r * ST_PITCH + 32 * j + 16 * hi) = o;
-            }
-        };
-        // strips wave, wave + 4, wave + 8, wave + 12: two operand sets in turn, a strip's operands requested while the one before is computed
-        v4i_r xa[NKB], xb[NKB];
-        load_strip(wave, xa);
-        load_strip(wave + 4, xb);
+            for (int kb = 0; kb < NKB; ++kb) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wreg[j][kb], xr[kb], acc, 0, 0, 0);
+            v4i_r o = ir_requant_pack(acc, cl);
+            if (!exists) o = v4i_r{(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
+            if (r < ST_RPIX) *(v4i_r*)(stem_lds + r * ST_PITCH + 32 * j + 16 * hi) = o;
+        }
+    };
+    // strips wave, wave + 4, wave + 8, wave + 12 of a tile through four operand sets; a strip's operands are requested two strips
+    // before it is computed, the first two of the next tile behind this tile's last two
+    v4i_r xs[4][NKB];
+    int u = (int)blockIdx.x;                                            // the same trip count for the whole workgroup
+    if (u < t.total) {
+        const Tile t0 = tile_at(u);
+        load_strip(t0, wave, xs[0]);
+        load_strip(t0, wave + 4, xs[1]);
+    }
+    for (; u < t.total; u += (int)gridDim.x) {
+        const Tile tl = tile_at(u);
+        const bool more = u + (int)gridDim.x < t.total;
+        const Tile tn = tile_at(more ? u + (int)gridDim.x : u);
+        const int n = tl.n, py0 = tl.py0, px0 = tl.px0;
         __builtin_amdgcn_sched_barrier(0);
-        compute_strip(wave, xa);
+        load_strip(tl, wave + 8, xs[2]);
         __builtin_amdgcn_sched_barrier(0);
-        load_strip(wave + 8, xa);
+        compute_strip(tl, wave, xs[0]);
         __builtin_amdgcn_sched_barrier(0);
-        compute_strip(wave + 4, xb);
+        load_strip(tl, wave + 12, xs[3]);
         __builtin_amdgcn_sched_barrier(0);
-        load_strip(wave + 12, xb);
+        compute_strip(tl, wave + 4, xs[1]);
         __builtin_amdgcn_sched_barrier(0);
-        compute_strip(wave + 8, xa);
+        load_strip(tn, wave, xs[0]);                                    // past the last tile: this tile's once more (a fixed number of loads)
         __builtin_amdgcn_sched_barrier(0);
-        compute_strip(wave + 12, xb);
+        compute_strip(tl, wave + 8, xs[2]);
+        __builtin_amdgcn_sched_barrier(0);
+        load_strip(tn, wave + 4, xs[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_strip(tl, wave + 12, xs[3]);
         __syncthreads();                                                // the tile's convolution outputs are in LDS
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
@@ -172,9 +195,8 @@ hipError_t launch_stem_pool(const ConvArgs& a, void* yq, int Hq, int Wq, hipStre
     const long long total = (long long)(a.M / (a.Ho * a.Wo)) * t.tiles_x * t.tiles_y;
     if (total > 0x3fffffff) return hipErrorInvalidValue;
     t.total = (int)total;
-    const long long rounds = (total + 511) / 512;                       // two workgroups per CU; the loop takes the rest, every workgroup the same share
-    const unsigned blocks = (unsigned)((total + rounds - 1) / rounds);
-    EE_LAUNCH(stem_pool_i8_kernel, dim3(blocks), dim3(256), (size_t)ST_RPIX * ST_PITCH, s, a, yq, t);
+    const unsigned blocks = (unsigned)(total < 512 ? total : 512);      // two workgroups on every CU (what matters is the CU's share, not the workgroup's); the loop takes the rest
+    EE_LAUNCH(stem_pool_i8_kernel, dim3(blocks), dim3(256), (size_t)ST_RPIX * ST_PITCH + 256, s, a, yq, t);
     return hipGetLastError();
 }
 
