@@ -1101,7 +1101,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                 ia.y = resolve(this, q2.dst_buf, act_in, act_out);
                 ia.res = q2.d.res >= 0 && !p.ir_sc ? resolve(this, q2.res_buf, act_in, act_out) : nullptr;   // the kernel computes the shortcut itself
                 ia.ys = q2.dst_buf == BUF_EXT_OUT ? zc_out : nullptr;
-                ia.gap_sums = ir_pools ? gap_fuse_dst : nullptr;
+                ia.gap_sums = ir_pools && bneck_block_pools(ia) ? gap_fuse_dst : nullptr;       // else the head pools the output itself
                 double f_ops = ops, f_bytes = bytes;                             // the block's layers; the tensors between them stay on chip
                 for (int j = 1; j <= ir_last; ++j) {
                     const OpPlan& q = plans[st.first_op + k + j];
@@ -1111,7 +1111,7 @@ int ee_ctx::run_stage(int stage, int b, const void* act_in, void* act_out, bool 
                 }
                 e = timed(EE_K_CONV_MFMA, f_ops, f_bytes, [&] { return p.ir_bneck ? launch_bneck_block(ia, stream) : launch_ir_block(ia, stream); }, st.first_op + k);
                 if (e != hipSuccess) return EE_ERR_DEVICE;
-                if (ir_pools) gap_fused = true;
+                if (ia.gap_sums) gap_fused = true;
                 k += ir_last;                                                    // the block's other layers are done
                 continue;
             }

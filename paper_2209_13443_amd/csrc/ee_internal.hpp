@@ -179,6 +179,7 @@ hipError_t launch_ir_block(const IrArgs& a, hipStream_t s);
 bool stem_pool_supported(const ConvArgs& a, int Hq, int Wq);
 hipError_t launch_stem_pool(const ConvArgs& a, void* yq, int Hq, int Wq, hipStream_t s);
 bool bneck_block_supported(const IrArgs& a);
+bool bneck_block_pools(const IrArgs& a);     // with a.gap_sums the launch also pools: only where its rows of sums fit into LDS
 hipError_t launch_bneck_block(const IrArgs& a, hipStream_t s);
 hipError_t launch_maxpool(const PoolArgs& a, int dtype, hipStream_t s);
 hipError_t launch_avgpool(const PoolArgs& a, int dtype, hipStream_t s);

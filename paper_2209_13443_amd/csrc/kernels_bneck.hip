@@ -28,6 +28,7 @@ struct BnTile {
     int total;                 // tiles in all
     int per_xcd, nslots;       // tiles per XCD (a contiguous run), workgroups per XCD
     int xp, x_bytes;           // bytes per staged input pixel, per buffer of staged pixels
+    int gap_rows;              // pooling: rows of 256 channel sums in LDS, one per tile of a workgroup
 };
 
 constexpr int BN_M1_PX = 80;                     // second layer's input in LDS: 64 bytes per pixel + 16
@@ -73,6 +74,14 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     if (tid < 256) l_b3[tid] = a.bp[tid];
     if constexpr (SC) { if (tid < 256) l_bs[tid] = a.bs[tid]; }
     if (a.ys && tid < a.B) ((unsigned short*)l_slot)[tid] = a.ys[tid];   // B <= EE_ZC_MAX_B <= 512 with a slot table: checked by the launcher
+    // pooling (GAP): a tile's channel sums are gathered in LDS, a row of 256 per tile of this workgroup, and added to a.gap_sums
+    // when the last tile is through: the global atomics then sit behind the loop, where no wait of the loop (for staged pixels
+    // or residuals) has them in front of it
+    int* const l_gap = l_bs + (SC ? 256 : 0);
+    int* const l_gap_n = l_gap + 256 * t.gap_rows;                      // the sample of every row
+    if constexpr (GAP) {
+        for (int i = tid; i < 256 * t.gap_rows; i += 512) l_gap[i] = 0;
+    }
 
     // A workgroup's tiles are nslots apart: a tile's (sample, tile row, tile column) follows from the one before by additions
     // (the divisions are done once).
@@ -122,7 +131,7 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     };
     unsigned pix_y = 0;
     bool px_ok = false;
-    int gap_n = 0;                                                      // the sample of the tile in hand
+    int gap_n = 0, gap_row = -1;                                        // the sample of the tile in hand, its row of sums
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
@@ -130,6 +139,7 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     auto out_pixel = [&](const Cursor& cu) {                            // where the lane's pixel of that tile goes; its residual is requested
         const int n = cu.n;
         gap_n = n;
+        ++gap_row;
         const int oy = 8 * cu.ty + 4 * pb + ty, ox = 8 * cu.tx + tx;
         px_ok = oy < a.H && ox < a.W;
         const int sp = px_ok ? (oy * a.W + ox) * 256 + cb0 * 32 + 16 * hi : 0;                  // < 2^31 with the sample: checked by the launcher
@@ -199,8 +209,10 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                 for (int i = 0; i < 16; ++i) sum += tr[i];
                 const auto both = __builtin_amdgcn_permlane32_swap((unsigned)sum, (unsigned)sum, false, false);   // the other 16 pixels
                 sum = (int)(both[0] + both[1]);
-                if (hi == 0) atomicAdd(a.gap_sums + (size_t)gap_n * 256 + (cb0 + c) * 32 + m, sum);       // integer sums: exact in any order
+                // integer sums: exact in any order
+                if (hi == 0) __hip_atomic_fetch_add((__attribute__((address_space(3))) int*)l_gap + gap_row * 256 + (cb0 + c) * 32 + m, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
+            if (tid == 0) l_gap_n[gap_row] = gap_n;
         }
     };
 
@@ -359,6 +371,9 @@ __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             __syncthreads();
         }
     }
+    if constexpr (GAP) {                                                // every row is complete behind the loop's last barrier
+        for (int i = tid; i < 256 * T; i += 512) atomicAdd(a.gap_sums + (size_t)l_gap_n[i >> 8] * 256 + (i & 255), l_gap[i]);
+    }
 }
 
 // Shapes the kernel covers, and its tiling.
@@ -376,7 +391,16 @@ static bool bneck_block_plan(const IrArgs& a, BnTile& t)
     t.nslots = t.per_xcd < 32 ? t.per_xcd : 32;                         // one workgroup per CU at most: 32 CUs per XCD
     t.xp = a.Cin + 16;
     t.x_bytes = 100 * t.xp + 64;
+    t.gap_rows = (t.per_xcd + t.nslots - 1) / t.nslots;                  // the most tiles a workgroup has
     return true;
+}
+
+// LDS of a launch; 0: the rows of channel sums of a pooling launch do not fit
+static size_t bneck_lds_bytes(const BnTile& t, bool sc, bool gap)
+{
+    size_t lds = (size_t)BN_BIAS_BYTES + (sc ? 3 : 2) * (size_t)t.x_bytes + 2 * BN_M1_BYTES + BN_M2_BYTES + BN_SLOT_BYTES + (sc ? 1024 : 0);
+    if (gap) lds += (size_t)t.gap_rows * (1024 + 4);
+    return lds <= 160 * 1024 ? lds : 0;
 }
 
 bool bneck_block_supported(const IrArgs& a)
@@ -385,12 +409,19 @@ bool bneck_block_supported(const IrArgs& a)
     return bneck_block_plan(a, t);
 }
 
+bool bneck_block_pools(const IrArgs& a)
+{
+    BnTile t;
+    return bneck_block_plan(a, t) && (a.res || a.ws) && bneck_lds_bytes(t, a.ws != nullptr, true) != 0;
+}
+
 template <int K1, bool RES, bool GAP, bool SC = false>
 static hipError_t bneck_launch(const IrArgs& a, const BnTile& t, hipStream_t s)
 {
     static const hipError_t granted = hipFuncSetAttribute(reinterpret_cast<const void*>(&bneck_block_i8_kernel<K1, RES, GAP, SC>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (granted != hipSuccess) return granted;
-    const size_t lds = (size_t)BN_BIAS_BYTES + (SC ? 3 : 2) * (size_t)t.x_bytes + 2 * BN_M1_BYTES + BN_M2_BYTES + BN_SLOT_BYTES + (SC ? 1024 : 0);
+    const size_t lds = bneck_lds_bytes(t, SC, GAP);
+    if (lds == 0) return hipErrorInvalidValue;                          // bneck_block_pools says so beforehand
     EE_LAUNCH((bneck_block_i8_kernel<K1, RES, GAP, SC>), dim3((unsigned)(8 * t.nslots)), dim3(512), lds, s, a, t);
     return hipGetLastError();
 }
