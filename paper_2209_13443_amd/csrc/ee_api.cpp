@@ -1,6 +1,7 @@
 // C ABI entry points: context creation (weight packing, workspace planning), one backbone
 // segment, one exit head, compaction / refill, latency-table measurement and kernel timing.
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstring>
 
@@ -416,16 +417,14 @@ int alloc_lane(ee_ctx* ctx, LaneState& L)
     if ((rc = dev_alloc(ctx, &L.d_conf, sizeof(float) * (size_t)b_max))) return rc;
     if ((rc = dev_alloc(ctx, &L.d_score, sizeof(int64_t) * (size_t)b_max))) return rc;
     if ((rc = dev_alloc(ctx, &L.d_flag, (size_t)b_max + 16))) return rc;
-    if ((rc = dev_alloc(ctx, &L.d_arrive, 64))) return rc;
     if ((rc = dev_alloc(ctx, &L.d_slots, 2 * sizeof(uint16_t) * EE_ZC_MAX_B))) return rc;
     const size_t out_bytes = round_up((int)(sizeof(HostOutcome) * (size_t)b_max), 256), ids_bytes = round_up(4 * b_max, 256);
-    if (hipHostMalloc(&L.h_pinned, out_bytes + 2 * ids_bytes + 256, hipHostMallocCoherent) != hipSuccess) return EE_ERR_DEVICE;
-    std::memset(L.h_pinned, 0, out_bytes + 2 * ids_bytes + 256);
+    if (hipHostMalloc(&L.h_pinned, out_bytes + 2 * ids_bytes, hipHostMallocCoherent) != hipSuccess) return EE_ERR_DEVICE;
+    std::memset(L.h_pinned, 0, out_bytes + 2 * ids_bytes);
     unsigned char* hp = static_cast<unsigned char*>(L.h_pinned);
     L.h_out = reinterpret_cast<HostOutcome*>(hp);
     L.h_ids[0] = reinterpret_cast<int32_t*>(hp + out_bytes);
     L.h_ids[1] = reinterpret_cast<int32_t*>(hp + out_bytes + ids_bytes);
-    L.h_seq = reinterpret_cast<unsigned*>(hp + out_bytes + 2 * ids_bytes);
     for (int s = 0; s < 8; ++s)
         if (hipEventCreateWithFlags(&L.packed[s], hipEventDisableTiming) != hipSuccess) return EE_ERR_DEVICE;
     return EE_OK;
@@ -653,13 +652,14 @@ void ee_ctx::bind_lane(int j)
     if (j == lane) return;
     if (lane >= 0) {                              // the counters of the lane that was bound travel back
         lanes[(size_t)lane].seq = seq;
+        lanes[(size_t)lane].head_b = head_b;
         lanes[(size_t)lane].ids_turn = ids_turn;
     }
     const ee::LaneState& L = lanes[(size_t)j];
     stream = L.stream; pool = L.pool; pad_bufs = L.pad_bufs; out_buf = L.out_buf; in_buf[0] = L.in0;
     sums = L.sums; gap_partial = L.gap_partial; logits = L.logits;
-    d_label = L.d_label; d_conf = L.d_conf; d_score = L.d_score; d_flag = L.d_flag; d_arrive = L.d_arrive; d_slots = L.d_slots;
-    h_out = L.h_out; h_ids[0] = L.h_ids[0]; h_ids[1] = L.h_ids[1]; h_seq = L.h_seq; seq = L.seq; ids_turn = L.ids_turn;
+    d_label = L.d_label; d_conf = L.d_conf; d_score = L.d_score; d_flag = L.d_flag; d_slots = L.d_slots;
+    h_out = L.h_out; h_ids[0] = L.h_ids[0]; h_ids[1] = L.h_ids[1]; seq = L.seq; head_b = L.head_b; ids_turn = L.ids_turn;
     lane = j;
 }
 
@@ -1207,12 +1207,31 @@ int ee_ctx::run_head(int stage, int b, const void* act, float thr, int32_t* labe
     a.last = stage == (int)net.stages.size() - 1;
     a.label = label; a.conf = conf; a.score = score; a.flag = flag;
     a.slots = slots;
-    if (to_host) { a.host_out = h_out; a.host_seq = h_seq; a.seq_value = ++seq; a.arrive_counter = d_arrive; }
+    if (to_host) {
+        // cleared records match no tag: the host takes none of an earlier launch for one of this
+        for (int k = 0; k < b; ++k) {
+            __atomic_store_n(&h_out[k].w0, 0ull, __ATOMIC_RELAXED);
+            __atomic_store_n(&h_out[k].w1, 0ull, __ATOMIC_RELAXED);
+        }
+        a.host_out = h_out; a.tag = ee::outcome_tag(++seq); head_b = b;
+    }
     const double act_bytes = (double)b * a.HW * a.C * es;
     if (!pooled && timed(EE_K_GAP, 0.0, act_bytes + 4.0 * b * a.C, [&] { return launch_head_gap(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;
     if (timed(EE_K_FC, 2.0 * b * a.C * a.n_cls, (double)a.C * a.n_cls * es + 4.0 * b * (a.C + a.n_cls),
               [&] { return launch_head_fc(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;
     if (timed(EE_K_SOFTMAX, 0.0, 4.0 * b * a.n_cls + 17.0 * b, [&] { return launch_head_softmax(a, dt, stream); }) != hipSuccess) return EE_ERR_DEVICE;
+    return EE_OK;
+}
+
+int ee_ctx::wait_head()
+{
+    const auto t0 = std::chrono::steady_clock::now();
+    for (unsigned spins = 0; !head_reported(); ++spins)
+        if ((spins & 0xFFF) == 0xFFF && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2)) {
+            // no records after two seconds: let the runtime say what happened to the stream
+            if (hipStreamSynchronize(stream) != hipSuccess) return EE_ERR_DEVICE;
+            return head_reported() ? EE_OK : EE_ERR_DEVICE;
+        }
     return EE_OK;
 }
 
@@ -1307,7 +1326,7 @@ extern "C" int ee_compact_refill(ee_ctx* ctx, int stage, int b_act, const uint8_
 // The design-time exit-level latency table (Sec. III-B, "Exit-Level Latency Prediction").  An entry is what a step of the
 // stream driver costs on the wall clock, measured the way the driver runs it: the segment (the first one reads its input
 // through the admission copy, as when requests are admitted), the exit head writing its outcomes to host memory, the
-// compaction of all b samples behind it (nobody exits: the upper bound), and the host waiting for the head's word.
+// compaction of all b samples behind it (nobody exits: the upper bound), and the host waiting for the head's records.
 // Eq. 4 relies on the table not under-estimating (a preemption it accepts must not cause a violation).
 extern "C" int ee_measure_lut(ee_ctx* ctx, int reps, int64_t* lut_ns)
 {
@@ -1320,13 +1339,6 @@ extern "C" int ee_measure_lut(ee_ctx* ctx, int reps, int64_t* lut_ns)
     int rc = EE_OK;
     for (int k = 0; k < bm; ++k) ctx->h_ids[0][k] = ctx->h_ids[1][k] = k;      // admission of rows 0..b-1 of segment 0's own input slots
     const OpPlan* fold = ctx->admission_fold();
-    auto wait_word = [&]() {
-        const auto t0 = std::chrono::steady_clock::now();
-        for (unsigned spins = 0; __atomic_load_n(ctx->h_seq, __ATOMIC_ACQUIRE) != ctx->seq; ++spins)
-            if ((spins & 0xFFFF) == 0xFFFF && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2))
-                return hipStreamSynchronize(ctx->stream) == hipSuccess && __atomic_load_n(ctx->h_seq, __ATOMIC_ACQUIRE) == ctx->seq ? EE_OK : EE_ERR_DEVICE;
-        return EE_OK;
-    };
     for (int s = 0; s < n_st && !rc; ++s) {
         std::vector<int> measured;
         for (int b = 1; b <= bm; b += step) measured.push_back(b);
@@ -1349,7 +1361,7 @@ extern "C" int ee_measure_lut(ee_ctx* ctx, int reps, int64_t* lut_ns)
                     ctx->gap_fuse_dst = nullptr;
                     if (!rc) rc = ctx->run_head(s, b, ctx->out_buf[s], 2.0f, ctx->d_label, ctx->d_conf, ctx->d_score, ctx->d_flag, true, nullptr, nullptr, ctx->gap_fused);
                     if (!rc && s + 1 < n_st && launch_compact(ctx->d_flag, ctx->out_buf[s], ctx->in_buf[s + 1], nullptr, nullptr, b, sb_out, 0, 0, nullptr, nullptr, ctx->stream) != hipSuccess) rc = EE_ERR_DEVICE;
-                    if (!rc) rc = wait_word();
+                    if (!rc) rc = ctx->wait_head();
                 }
                 if (hipStreamSynchronize(ctx->stream) != hipSuccess) rc = EE_ERR_DEVICE;
                 t[i] = std::chrono::duration<double, std::nano>(std::chrono::steady_clock::now() - t0).count() / n;

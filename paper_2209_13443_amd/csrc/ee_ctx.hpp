@@ -49,10 +49,10 @@ struct LaneState {
     void* in0 = nullptr;                         // input slots of the first segment
     int32_t* sums = nullptr; int32_t* gap_partial = nullptr; void* logits = nullptr;
     int32_t* d_label = nullptr; float* d_conf = nullptr; int64_t* d_score = nullptr; uint8_t* d_flag = nullptr;
-    unsigned* d_arrive = nullptr;
     uint16_t* d_slots = nullptr;                 // the lane's two slot tables (zero-copy compaction)
-    void* h_pinned = nullptr; HostOutcome* h_out = nullptr; int32_t* h_ids[2] = {nullptr, nullptr}; unsigned* h_seq = nullptr;
+    void* h_pinned = nullptr; HostOutcome* h_out = nullptr; int32_t* h_ids[2] = {nullptr, nullptr};
     unsigned seq = 0;
+    int head_b = 0;
     int ids_turn = 0;
     hipEvent_t packed[8] = {};                   // recorded behind this lane's latest compaction into segment s's input ring
     bool packed_set[8] = {};
@@ -86,9 +86,8 @@ struct ee_ctx {
     void* h_pinned = nullptr;                    // pinned, device-visible host memory: the three blocks below
     ee::HostOutcome* h_out = nullptr;            // [b_max] per-slot outcomes written by the exit-head kernel
     int32_t* h_ids[2] = {nullptr, nullptr};      // admission ids read by the admission kernel, used in turn
-    unsigned* h_seq = nullptr;                   // sequence word stored by the exit head when h_out is complete
-    unsigned seq = 0;                            // last sequence value handed to an exit head
-    unsigned* d_arrive = nullptr;                // device counter of exit-head workgroups that have finished
+    unsigned seq = 0;                            // number of exit heads that have reported to the host: the latest one's tag follows from it
+    int head_b = 0;                              // batch of that exit head: records [0, head_b) of h_out
     uint16_t* d_slots = nullptr;                 // the bound lane's two slot tables (zero-copy compaction)
     int ids_turn = 0;
     // zero-copy compaction (stream serving): slot tables of the step being enqueued, or null.  With zc_in, sample n of a
@@ -150,10 +149,15 @@ struct ee_ctx {
     void fill_ir_args(int op, int b, ee::IrArgs& a) const;      // the block headed by layer `op`; x, res and y are left to the caller
     void fill_conv_args(int op, int b, ee::ConvArgs& a) const;
     static int bucket_of(int b) { int k = 0; while ((1 << k) < b) ++k; return k; }     // smallest k with 2^k >= b
-    // to_host: also write the outcomes to h_out and store ++seq to h_seq when they are all there
+    // to_host: the outcomes also go to h_out, every record with the tag of ++seq (the records are cleared first)
     // own: scratch memory to use instead of the context's (sums, gap_partial, logits)
     int run_head(int stage, int b_act, const void* act, float thr, int32_t* label, float* conf, int64_t* score, uint8_t* flag,
                  bool to_host = false, const ee::HeadScratch* own = nullptr, const uint16_t* slots = nullptr, bool pooled = false);
+    // the bound lane's latest exit head with to_host has written all its records; wait_head spins until it has (EE_ERR_DEVICE
+    // when the stream has failed or nothing has come after two seconds)
+    bool head_reported() const { return ee::outcomes_ready(h_out, head_b, ee::outcome_tag(seq)); }
+    int wait_head();
+    ee::Outcome head_outcome(int k) const { return ee::decode_outcome(h_out[k], net.dtype == EE_I8); }
     // times `launch` with a pair of events attached to its dispatch when profiling
     template <typename F>
     hipError_t timed(int cls, double ops, double bytes, F&& launch, int op = -1);

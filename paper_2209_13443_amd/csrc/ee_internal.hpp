@@ -1,6 +1,7 @@
 // Internal declarations of the early-exit serving library (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <cstring>
 #include <hip/hip_ext.h>
 
 #include <cstdint>
@@ -193,12 +194,43 @@ struct HeadArgs {
     void* logits;        // [B][n_cls] int32 / float scratch
     int64_t s_thr; float thr; int last;
     int32_t* label; float* conf; int64_t* score; uint8_t* flag;
-    // stream serving: per-slot outcomes written straight into pinned host memory, and a sequence word
-    // the last workgroup stores once every record is visible to the host (all three null otherwise)
-    struct HostOutcome* host_out; unsigned* host_seq; unsigned seq_value; unsigned* arrive_counter;
+    // stream serving: per-slot outcomes written straight into pinned host memory, each with the launch's tag (null otherwise)
+    struct HostOutcome* host_out; unsigned tag;
     const uint16_t* slots;   // pooling: not null: sample b of the batch is slot slots[b] of act (device memory)
 };
-struct HostOutcome { int64_t score; int32_t label; float conf; uint32_t flag; uint32_t pad_; };
+// w0: bits 0-43 the score S (int8: S <= n_cls * 2^30 < 2^44; the host derives the confidence 2^30 / S) or the confidence's
+// float bits (bf16); w1: bits 0-31 the label, bit 32 the exit flag; bits 44-63 of both: the launch's tag (never 0: a record the
+// host has cleared matches no launch)
+struct alignas(16) HostOutcome { uint64_t w0, w1; };
+constexpr int EE_OUTCOME_TAG_SHIFT = 44;
+inline unsigned outcome_tag(unsigned seq) { return seq % 0xFFFFFu + 1u; }
+// host side: records [0, b) all carry the tag in both words
+inline bool outcomes_ready(const HostOutcome* h, int b, unsigned tag)
+{
+    for (int k = b - 1; k >= 0; --k)
+        if ((unsigned)(__atomic_load_n(&h[k].w0, __ATOMIC_ACQUIRE) >> EE_OUTCOME_TAG_SHIFT) != tag ||
+            (unsigned)(__atomic_load_n(&h[k].w1, __ATOMIC_ACQUIRE) >> EE_OUTCOME_TAG_SHIFT) != tag) return false;
+    return true;
+}
+struct Outcome { int64_t score; int32_t label; float conf; uint8_t flag; };
+inline bool outcome_exits(const HostOutcome& h) { return (__atomic_load_n(&h.w1, __ATOMIC_RELAXED) >> 32) & 1u; }
+inline Outcome decode_outcome(const HostOutcome& h, bool int8)
+{
+    const uint64_t w0 = __atomic_load_n(&h.w0, __ATOMIC_RELAXED), w1 = __atomic_load_n(&h.w1, __ATOMIC_RELAXED);
+    const uint64_t payload = w0 & ((1ull << EE_OUTCOME_TAG_SHIFT) - 1);
+    Outcome o;
+    o.label = (int32_t)(uint32_t)w1;
+    o.flag = (uint8_t)((w1 >> 32) & 1u);
+    if (int8) {
+        o.score = (int64_t)payload;
+        o.conf = (float)(1073741824.0 / (double)o.score);       // as the kernel computes it for the device-side array
+    } else {
+        o.score = 0;
+        const uint32_t bits = (uint32_t)payload;
+        std::memcpy(&o.conf, &bits, 4);
+    }
+    return o;
+}
 // device address, on the current GPU, of the scratch array that is part of the library image (EE_STATIC_SCRATCH_BYTES bytes)
 hipError_t static_scratch(void** out);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);

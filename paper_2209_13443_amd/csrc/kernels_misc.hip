@@ -716,6 +716,17 @@ __device__ __forceinline__ T block_reduce(T v, T* scratch, bool is_max)
     return r;
 }
 
+// A sample's record for the host: one 16-byte store into pinned host memory.  Both 64-bit words carry the launch's tag, so
+// the host sees by itself when a record is complete (an aligned 64-bit word arrives whole): no fence, no counter of
+// workgroups and no word behind them on the device side, and the host reads a record as soon as it lands.
+__device__ __forceinline__ void host_record(HostOutcome* dst, uint64_t payload, int label, unsigned flag, unsigned tag)
+{
+    const uint64_t w0 = payload | (uint64_t)tag << EE_OUTCOME_TAG_SHIFT;
+    const uint64_t w1 = (uint64_t)(unsigned)label | (uint64_t)(flag & 1u) << 32 | (uint64_t)tag << EE_OUTCOME_TAG_SHIFT;
+    const v4i rec = {(int)(unsigned)w0, (int)(unsigned)(w0 >> 32), (int)(unsigned)w1, (int)(unsigned)(w1 >> 32)};
+    *(v4i*)dst = rec;
+}
+
 // one workgroup per sample.  int8: m = max logit, label = lowest arg-max, S = sum_j T[frac(d_j)] >> (d_j >> f)
 // with d_j = m - a_j (a base-2 softmax denominator in Q30); exits iff S <= s_thr.  bf16: float softmax.
 // The sample's logits are read once into registers (up to 8 per lane: n_cls <= 2048); the arg-max and the
@@ -772,7 +783,7 @@ __global__ __launch_bounds__(256) void softmax_kernel(HeadArgs a)
             a.score[b] = S;
             a.conf[b] = conf;
             a.flag[b] = flag;
-            if (a.host_out) a.host_out[b] = HostOutcome{S, arg, conf, flag, 0u};
+            if (a.host_out) host_record(a.host_out + b, (uint64_t)S, arg, flag, a.tag);
         }
     } else {
         float m = -INFINITY;
@@ -805,16 +816,7 @@ __global__ __launch_bounds__(256) void softmax_kernel(HeadArgs a)
             a.score[b] = 0;
             a.conf[b] = conf;
             a.flag[b] = flag;
-            if (a.host_out) a.host_out[b] = HostOutcome{0, arg, conf, flag, 0u};
-        }
-    }
-    // the workgroup that arrives last tells the host that every record is in place
-    if (a.host_seq && threadIdx.x == 0) {
-        __threadfence_system();
-        if (atomicAdd(a.arrive_counter, 1u) == (unsigned)a.B - 1u) {
-            *a.arrive_counter = 0u;
-            __threadfence_system();
-            __hip_atomic_store(a.host_seq, a.seq_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+            if (a.host_out) host_record(a.host_out + b, (uint64_t)__float_as_uint(conf), arg, flag, a.tag);
         }
     }
 }

@@ -142,7 +142,7 @@ struct GpuExec {
         const int rows = ring_rows > 0 ? ring_rows : (int)map.size();
         int j = 0;
         for (int k = 0; k < st.b; ++k) {
-            if (h[k].flag) free_slots[st.stage + 1].push_back(st.out.s[k]);
+            if (outcome_exits(h[k])) free_slots[st.stage + 1].push_back(st.out.s[k]);
             else map[(size_t)((dst_off + j++) % rows)] = st.out.s[k];
         }
         st.has_out = false;
@@ -191,8 +191,8 @@ struct GpuExec {
     // survivors (flags stay on the device) are packed into the next segment's input slots
     // [dst_off, dst_off + B_rem) right behind the head, dst_off > 0 merging a catch-up batch behind the parked
     // survivors; with ring_rows > 0 those slots form a ring and the destination wraps around its end.
-    // Then the one device-to-host crossing of the boundary: the head kernel has written the per-slot outcomes
-    // into pinned host memory and stores a sequence word when they are complete; the host polls that word.
+    // Then the one device-to-host crossing of the boundary: the head kernel writes the per-slot outcomes into pinned
+    // host memory, every record with the launch's tag; the host polls the records until all of them carry it.
     int segment(int stage, const int32_t*, int b, SlotOutcome* out, int src_off, int dst_off, int ring_rows)
     {
         ctx->bind_lane(0);
@@ -207,11 +207,11 @@ struct GpuExec {
             });
             if (e != hipSuccess) return EE_ERR_DEVICE;
         }
-        if ((rc = wait_outcomes())) return rc;
+        if ((rc = ctx->wait_head())) return rc;
         int kept = 0;
         for (int k = 0; k < b; ++k) {
-            const HostOutcome& h = ctx->h_out[k];
-            out[k] = SlotOutcome{(uint8_t)h.flag, h.label, h.conf, h.score};
+            const Outcome h = ctx->head_outcome(k);
+            out[k] = SlotOutcome{h.flag, h.label, h.conf, h.score};
             kept += h.flag == 0;
         }
         if (zc) { zc_release_inputs(0); zc_pack(0, dst_off, ring_rows); }
@@ -239,18 +239,18 @@ struct GpuExec {
     }
     bool done(int lane)
     {
+        if (lane == ctx->lane) return ctx->head_reported();              // the bound lane's counters are the context's
         const LaneState& L = ctx->lanes[(size_t)lane];
-        const unsigned want = lane == ctx->lane ? ctx->seq : L.seq;
-        return __atomic_load_n(L.h_seq, __ATOMIC_ACQUIRE) == want;
+        return outcomes_ready(L.h_out, L.head_b, outcome_tag(L.seq));
     }
     int collect(int lane, int b, SlotOutcome* out)
     {
         ctx->bind_lane(lane);
-        const int rc = wait_outcomes();
+        const int rc = ctx->wait_head();
         if (rc) return rc;
         for (int k = 0; k < b; ++k) {
-            const HostOutcome& h = ctx->h_out[k];
-            out[k] = SlotOutcome{(uint8_t)h.flag, h.label, h.conf, h.score};
+            const Outcome h = ctx->head_outcome(k);
+            out[k] = SlotOutcome{h.flag, h.label, h.conf, h.score};
         }
         if (zc) zc_release_inputs(lane);
         return EE_OK;
@@ -281,19 +281,6 @@ struct GpuExec {
         if (zc) { zc_pack(lane, step_of[lane].dst, step_of[lane].ring); return; }
         if (pack_rec[lane] >= 0 && ctx->profiling) ctx->prof[(size_t)pack_rec[lane]].bytes = 2.0 * (double)ctx->stage_out_bytes(stage) * kept;
         pack_rec[lane] = -1;
-    }
-    int wait_outcomes()
-    {
-        const unsigned want = ctx->seq;
-        const auto t0 = std::chrono::steady_clock::now();
-        for (unsigned spins = 0; __atomic_load_n(ctx->h_seq, __ATOMIC_ACQUIRE) != want; ++spins) {
-            if ((spins & 0xFFFF) == 0xFFFF && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2)) {
-                // no word after two seconds: let the runtime say what happened to the stream
-                if (hipStreamSynchronize(ctx->stream) != hipSuccess) return EE_ERR_DEVICE;
-                return __atomic_load_n(ctx->h_seq, __ATOMIC_ACQUIRE) == want ? EE_OK : EE_ERR_DEVICE;
-            }
-        }
-        return EE_OK;
     }
 };
 

@@ -1,6 +1,6 @@
 """Builds and runs the gfx950 microbenchmarks behind the kernel design notes (needs a GPU).
 
-    python -m paper_2209_13443_amd.microbench.run [name ...]      # default: all of lds_bw dma_bw mfma_rate clock launch_cost
+    python -m paper_2209_13443_amd.microbench.run [name ...]      # default: all of lds_bw dma_bw mfma_rate clock launch_cost dispatch_floor
 
 Each one is a self-contained HIP program; the binaries go to a temporary directory."""
 import os
@@ -9,7 +9,7 @@ import sys
 import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-ALL = ["clock", "mfma_rate", "lds_bw", "dma_bw", "launch_cost"]
+ALL = ["clock", "mfma_rate", "lds_bw", "dma_bw", "launch_cost", "dispatch_floor"]
 
 
 def main(names):
